@@ -1,0 +1,12 @@
+"""CPU oracle of the RAF HGNN layer.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the product path (`paper_2408_09697_amd`) never does, and this package
+imports nothing from it.  Edge loops live in `heta_oracle.c` (plain C, fp64
+accumulation, explicit edge lists); dense steps are numpy fp64 matmuls.
+"""
+from .layer import (aggregate_bwd, aggregate_fwd, build, csc, cross_rel_sum, in_degree,
+                    layer_backward, layer_forward, project, project_bwd, LayerResult)
+
+__all__ = ["aggregate_bwd", "aggregate_fwd", "build", "csc", "cross_rel_sum", "in_degree",
+           "layer_backward", "layer_forward", "project", "project_bwd", "LayerResult"]

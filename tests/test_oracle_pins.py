@@ -1,0 +1,373 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Each test compares the oracle with what the paper and the mathematics fix: a dense
+count-matrix formulation written with numpy matmul (Eq. 1 with AGG_r = GCN, AGG_all = sum),
+closed forms on regular graphs, linearity, the adjoint identity, finite differences,
+Proposition 1 (any split of the relation set gives the same embedding), and the buffer
+shape implied by the communication example of Section 4.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from gen import rng, workloads
+from gen.graphs import HetGraph, NodeType, Relation, csr_from_edges
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---- a tiny random heterogeneous problem with every awkward feature ---------------------------
+
+def tiny_problem(seed, op, relu=False, with_gid=False):
+    g = np.random.default_rng(seed)
+    n = [int(g.integers(3, 9)), int(g.integers(3, 9)), int(g.integers(2, 6))]
+    d = [5, 3, 4]
+    d_out = 6
+    nts = [NodeType("a", n[0], d[0], False), NodeType("b", n[1], d[1], False), NodeType("c", n[2], d[2], True)]
+    G = HetGraph(nts)
+    for nm, s, t, e in [("aa", 0, 0, 11), ("ba", 1, 0, 7), ("ca", 2, 0, 9), ("ab", 0, 1, 13), ("cb", 2, 1, 0)]:
+        src = g.integers(0, n[s], size=e).astype(np.int32)
+        # leave the last destination row without edges: a zero-degree row in every relation
+        dst = g.integers(0, max(1, n[t] - 1), size=e).astype(np.int32)
+        rowptr, col = csr_from_edges(src, dst, n[t])
+        G.relations.append(Relation(nm, s, t, rowptr, col))
+    src_gid = None
+    tables = []
+    for t in range(3):
+        rows = n[t] + 4 if with_gid else n[t]
+        tables.append(g.standard_normal((rows, d[t])).astype(np.float32))
+    if with_gid:
+        src_gid = [g.permutation(n[t] + 4)[: n[t]].astype(np.int64) for t in range(3)]
+    W = [g.standard_normal((d[r.src_type], d_out)).astype(np.float32) for r in G.relations]
+    Gup = {0: g.standard_normal((n[0], d_out)).astype(np.float32),
+           1: g.standard_normal((n[1], d_out)).astype(np.float32)}
+    return workloads.LayerProblem("tiny", G, op, "f32", tables, W, d_out, Gup, src_gid=src_gid, relu=relu)
+
+
+def dense_layer(p):
+    """Textbook dense formulation: count matrix A_r[v,u], M = D^-1 A X, Z = M W, H = sum Z."""
+    g = p.graph
+    H, M, Acs = {}, {}, {}
+    for i, r in enumerate(g.relations):
+        n_s, n_t = g.ntypes[r.src_type].num_nodes, g.ntypes[r.dst_type].num_nodes
+        A = np.zeros((n_t, n_s))
+        src, dst = r.edge_list()
+        for u, v in zip(src.tolist(), dst.tolist()):
+            A[v, u] += 1.0
+        if p.op == "mean":
+            deg = A.sum(axis=1)
+            A = A / np.where(deg > 0, deg, 1.0)[:, None]
+        X = p.tables[r.src_type].astype(np.float64)
+        if p.src_gid is not None:
+            X = X[p.src_gid[r.src_type]]
+        if p.pre_proj is not None:
+            X = X @ p.pre_proj[r.src_type].astype(np.float64)
+        Acs[i] = A
+        M[i] = A @ X
+        H[r.dst_type] = H.get(r.dst_type, 0.0) + M[i] @ p.W[i].astype(np.float64)
+    pre = {t: h.copy() for t, h in H.items()}
+    if p.relu:
+        H = {t: np.maximum(h, 0.0) for t, h in H.items()}
+    return Acs, M, H, pre
+
+
+def dense_backward(p, Acs, M, pre):
+    g = p.graph
+    dW, dH0 = {}, {}
+    for i, r in enumerate(g.relations):
+        dZ = p.G[r.dst_type].astype(np.float64)
+        if p.relu:
+            dZ = dZ * (pre[r.dst_type] > 0)
+        dW[i] = M[i].T @ dZ
+        dM = dZ @ p.W[i].astype(np.float64).T
+        dH0[r.src_type] = dH0.get(r.src_type, 0.0) + Acs[i].T @ dM
+    return dW, dH0
+
+
+@pytest.mark.parametrize("op", ["mean", "sum"])
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("with_gid", [False, True])
+def test_layer_matches_dense_brute_force(seed, op, relu, with_gid):
+    p = tiny_problem(seed, op, relu, with_gid)
+    Acs, M, H, pre = dense_layer(p)
+    res = oracle.layer_forward(p)
+    for i in M:
+        np.testing.assert_allclose(res.M[i], M[i], rtol=1e-13, atol=1e-13)
+    assert set(res.H) == set(H)
+    for t in H:
+        np.testing.assert_allclose(res.H[t], H[t], rtol=1e-12, atol=1e-12)
+    dW, dH0 = dense_backward(p, Acs, M, pre)
+    odW, odH0, odT = oracle.layer_backward(p, res, p.G)
+    for i in dW:
+        np.testing.assert_allclose(odW[i], dW[i], rtol=1e-12, atol=1e-12)
+    assert set(odH0) == set(dH0)
+    for t in dH0:
+        np.testing.assert_allclose(odH0[t], dH0[t], rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(odT[t], dH0[t], rtol=1e-12, atol=1e-12)
+
+
+def test_config1_matches_dense_brute_force():
+    p = workloads.config1()
+    Acs, M, H, pre = dense_layer(p)
+    res = oracle.layer_forward(p)
+    for t in H:
+        np.testing.assert_allclose(res.H[t], H[t], rtol=1e-11, atol=1e-11)
+    dW, dH0 = dense_backward(p, Acs, M, pre)
+    odW, odH0, odT = oracle.layer_backward(p, res, p.G)
+    for i in dW:
+        np.testing.assert_allclose(odW[i], dW[i], rtol=1e-11, atol=1e-11)
+    for t in dH0:
+        np.testing.assert_allclose(odH0[t], dH0[t], rtol=1e-11, atol=1e-11)
+        np.testing.assert_allclose(odT[t], dH0[t] @ p.pre_proj[t].astype(np.float64).T, rtol=1e-11, atol=1e-11)
+    # type C has no incoming relation: no output for it, only a gradient
+    assert 2 not in res.H and 2 in odH0
+
+
+# ---- closed forms ------------------------------------------------------------------------------
+
+def test_closed_form_ring_and_star():
+    n, d = 12, 3
+    X = np.arange(n * d, dtype=np.float32).reshape(n, d)
+    # ring: v receives from v-1 and v+1 -> mean is the midpoint, sum is twice it
+    src = np.concatenate([(np.arange(n) - 1) % n, (np.arange(n) + 1) % n]).astype(np.int32)
+    dst = np.concatenate([np.arange(n), np.arange(n)]).astype(np.int32)
+    M = oracle.aggregate_fwd(src, dst, n, X, "mean")
+    expect = (X[(np.arange(n) - 1) % n].astype(np.float64) + X[(np.arange(n) + 1) % n]) / 2
+    np.testing.assert_array_equal(M, expect)
+    np.testing.assert_array_equal(oracle.aggregate_fwd(src, dst, n, X, "sum"), 2 * expect)
+    # star: node 0 receives from everybody once, node 1 three times from node 5 (multi-edge)
+    src = np.array(list(range(n)) + [5, 5, 5], dtype=np.int32)
+    dst = np.array([0] * n + [1, 1, 1], dtype=np.int32)
+    S = oracle.aggregate_fwd(src, dst, n, X, "sum")
+    np.testing.assert_array_equal(S[0], X.astype(np.float64).sum(0))
+    np.testing.assert_array_equal(S[1], 3.0 * X[5])
+    np.testing.assert_array_equal(S[2:], 0.0)
+    Mn = oracle.aggregate_fwd(src, dst, n, X, "mean")
+    np.testing.assert_allclose(Mn[0], X.astype(np.float64).mean(0), rtol=1e-15)
+    np.testing.assert_array_equal(Mn[1], X[5])            # mean of three copies of one row
+    np.testing.assert_array_equal(oracle.in_degree(src, dst, n), [n, 3] + [0] * (n - 2))
+
+
+def test_all_ones_gives_degree_and_unit_vectors_count_indices():
+    p = workloads.config1()
+    r = p.graph.relations[1]  # B->A
+    src, dst = r.edge_list()
+    n_s, n_t = 1000, 2000
+    deg = oracle.in_degree(src, dst, n_t)
+    assert deg.sum() == 5000
+    ones = np.ones((n_s, 4), dtype=np.float32)
+    S = oracle.aggregate_fwd(src, dst, n_t, ones, "sum")
+    np.testing.assert_array_equal(S, np.repeat(deg[:, None], 4, axis=1).astype(np.float64))
+    d = 16
+    E = np.zeros((n_s, d), dtype=np.float32)
+    E[np.arange(n_s), np.arange(n_s) % d] = 1.0
+    S = oracle.aggregate_fwd(src, dst, n_t, E, "sum")
+    cnt = np.zeros((n_t, d))
+    np.add.at(cnt, (dst, src % d), 1.0)
+    np.testing.assert_array_equal(S, cnt)
+
+
+def test_zero_degree_and_empty_relation():
+    X = np.random.default_rng(0).standard_normal((5, 3)).astype(np.float32)
+    e = np.zeros(0, dtype=np.int32)
+    for op in ("sum", "mean"):
+        M = oracle.aggregate_fwd(e, e, 4, X, op)
+        assert M.shape == (4, 3) and not M.any() and np.isfinite(M).all()
+        g = oracle.aggregate_bwd(e, e, 5, 4, np.ones((4, 3)), op)
+        assert g.shape == (5, 3) and not g.any()
+    src = np.array([0, 1], dtype=np.int32)
+    dst = np.array([2, 2], dtype=np.int32)
+    M = oracle.aggregate_fwd(src, dst, 4, X, "mean")
+    assert not M[[0, 1, 3]].any()
+    # zero destinations: no output rows
+    assert oracle.aggregate_fwd(e, e, 0, X, "mean").shape == (0, 3)
+
+
+# ---- invariants --------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("op", ["mean", "sum"])
+def test_linearity_aggregate_then_project_equals_project_then_aggregate(op):
+    p = workloads.config1()
+    r = p.graph.relations[3]  # A->B
+    src, dst = r.edge_list()
+    X = p.tables[0]
+    W = np.random.default_rng(1).standard_normal((64, 20))
+    lhs = oracle.project(oracle.aggregate_fwd(src, dst, 1000, X, op), W)
+    XW = X.astype(np.float64) @ W
+    rhs = oracle.aggregate_fwd(src, dst, 1000, XW, op)
+    np.testing.assert_allclose(lhs, rhs, rtol=1e-11, atol=1e-11)
+
+
+@pytest.mark.parametrize("op", ["mean", "sum"])
+def test_adjoint_identity(op):
+    p = workloads.config1()
+    rs = np.random.default_rng(2)
+    for i, r in enumerate(p.graph.relations):
+        src, dst = r.edge_list()
+        n_s, n_t = p.graph.ntypes[r.src_type].num_nodes, p.graph.ntypes[r.dst_type].num_nodes
+        X = rs.standard_normal((n_s, 7)).astype(np.float32)
+        Gm = rs.standard_normal((n_t, 7))
+        lhs = np.vdot(Gm, oracle.aggregate_fwd(src, dst, n_t, X, op))
+        rhs = np.vdot(X.astype(np.float64), oracle.aggregate_bwd(src, dst, n_s, n_t, Gm, op))
+        assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(lhs))
+
+
+def test_backward_of_sum_is_forward_of_transpose():
+    p = workloads.config1()
+    r = p.graph.relations[1]
+    src, dst = r.edge_list()
+    Gm = np.random.default_rng(3).standard_normal((2000, 5)).astype(np.float32)
+    bwd = oracle.aggregate_bwd(src, dst, 1000, 2000, Gm.astype(np.float64), "sum")
+    fwd_T = oracle.aggregate_fwd(dst, src, 1000, Gm, "sum")   # transposed edge list
+    np.testing.assert_allclose(bwd, fwd_T, rtol=1e-13, atol=1e-13)
+
+
+def test_finite_differences_config1():
+    """L = <G, H> is linear in each of tables, embeddings and W_r separately (no ReLU), so a
+    central difference reproduces the gradient up to rounding."""
+    p = workloads.config1()
+    res = oracle.layer_forward(p)
+    dW, dH0, dT = oracle.layer_backward(p, res, p.G)
+
+    def loss(q):
+        out = oracle.layer_forward(q)
+        return sum(np.vdot(q.G[t].astype(np.float64), out.H[t]) for t in out.H)
+
+    rs = np.random.default_rng(4)
+    eps = 2.0 ** -7
+    for t in range(3):
+        for _ in range(3):
+            i, j = int(rs.integers(p.tables[t].shape[0])), int(rs.integers(p.tables[t].shape[1]))
+            old = p.tables[t][i, j]
+            p.tables[t][i, j] = old + np.float32(eps)
+            up = loss(p)
+            p.tables[t][i, j] = old - np.float32(eps)
+            dn = loss(p)
+            p.tables[t][i, j] = old
+            step = float(np.float32(old + np.float32(eps)) - np.float32(old - np.float32(eps)))
+            fd = (up - dn) / step
+            assert abs(fd - dT[t][i, j]) <= 1e-8 * max(1.0, abs(fd)), (t, i, j, fd, dT[t][i, j])
+    for r in range(4):
+        for _ in range(3):
+            i, j = int(rs.integers(32)), int(rs.integers(32))
+            old = p.W[r][i, j]
+            p.W[r][i, j] = old + np.float32(eps)
+            up = loss(p)
+            p.W[r][i, j] = old - np.float32(eps)
+            dn = loss(p)
+            p.W[r][i, j] = old
+            step = float(np.float32(old + np.float32(eps)) - np.float32(old - np.float32(eps)))
+            fd = (up - dn) / step
+            assert abs(fd - dW[r][i, j]) <= 1e-8 * max(1.0, abs(fd)), (r, i, j, fd, dW[r][i, j])
+
+
+def test_finite_differences_with_relu_tiny():
+    p = tiny_problem(5, "mean", relu=True)
+    res = oracle.layer_forward(p)
+    dW, dH0, dT = oracle.layer_backward(p, res, p.G)
+    # stay away from the kink: every pre-activation must be far from zero compared with the step
+    pre = dense_layer(p)[3]
+    # (rows without any incoming edge are exactly 0 and no input can move them)
+    margin = min(np.abs(h[h != 0.0]).min() for h in pre.values())
+    eps = 2.0 ** -20
+    assert margin > 100 * eps * 50
+
+    def loss(q):
+        out = oracle.layer_forward(q)
+        return sum(np.vdot(q.G[t].astype(np.float64), out.H[t]) for t in out.H)
+
+    for t in range(3):
+        for i in range(p.tables[t].shape[0]):
+            for j in range(p.tables[t].shape[1]):
+                old = p.tables[t][i, j]
+                hi, lo = np.float32(old + np.float32(eps)), np.float32(old - np.float32(eps))
+                p.tables[t][i, j] = hi
+                up = loss(p)
+                p.tables[t][i, j] = lo
+                dn = loss(p)
+                p.tables[t][i, j] = old
+                fd = (up - dn) / (float(hi) - float(lo))
+                assert abs(fd - dT[t][i, j]) <= 1e-6 * max(1.0, abs(fd))
+
+
+def test_proposition1_any_split_of_relations():
+    """Partial aggregations over any partition of the relation set, summed, equal the embedding
+    over all relations (Proposition 1); the same holds for the gradients."""
+    p = workloads.config1()
+    full = oracle.layer_forward(p)
+    for split in ([[0], [1], [2], [3]], [[0, 2], [1, 3]], [[3, 1, 0], [2]]):
+        parts = [oracle.layer_forward(p, rels=s) for s in split]
+        for t in full.H:
+            tot = oracle.cross_rel_sum([q.H[t] for q in parts if t in q.H])
+            np.testing.assert_allclose(tot, full.H[t], rtol=1e-12, atol=1e-12)
+    dW, dH0, _ = oracle.layer_backward(p, full, p.G)
+    acc = {}
+    for s in [[0, 2], [1, 3]]:
+        part = oracle.layer_forward(p, rels=s)
+        pdW, pdH0, _ = oracle.layer_backward(p, part, p.G, rels=s)
+        for i in s:
+            np.testing.assert_allclose(pdW[i], dW[i], rtol=1e-12, atol=1e-12)
+        for t, gH in pdH0.items():
+            acc[t] = acc.get(t, 0.0) + gH
+    for t in dH0:
+        np.testing.assert_allclose(acc[t], dH0[t], rtol=1e-12, atol=1e-12)
+
+
+def test_integer_inputs_are_exact():
+    p = workloads.config1(exact=True)
+    p.op = "sum"
+    res = oracle.layer_forward(p)
+    for h in res.H.values():
+        assert np.array_equal(h, np.rint(h)) and np.abs(h).max() < 2 ** 24
+    Acs, M, H, _ = dense_layer(p)
+    for t in H:
+        np.testing.assert_array_equal(res.H[t], H[t])
+
+
+# ---- CSC (stable transpose) -------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_csc_is_the_stable_transpose(seed):
+    g = np.random.default_rng(seed)
+    n_s, n_t, E = 37, 23, 400
+    src = g.integers(0, n_s, size=E).astype(np.int32)
+    dst = np.sort(g.integers(0, n_t, size=E)).astype(np.int32)
+    colptr, row = oracle.csc(src, dst, n_s)
+    order = np.lexsort((np.arange(E), src))      # by source, ties by original position
+    np.testing.assert_array_equal(row, dst[order])
+    np.testing.assert_array_equal(colptr, np.concatenate([[0], np.cumsum(np.bincount(src, minlength=n_s))]))
+    # brute force per column
+    for u in range(n_s):
+        np.testing.assert_array_equal(row[colptr[u]:colptr[u + 1]], dst[src == u])
+
+
+def test_csc_empty():
+    e = np.zeros(0, dtype=np.int32)
+    colptr, row = oracle.csc(e, e, 5)
+    assert colptr.tolist() == [0] * 6 and row.size == 0
+
+
+# ---- the one place the paper prints numbers that touch this path -------------------------------
+
+def test_partial_aggregation_buffer_shape_from_communication_example():
+    """Section 4 prints 8.0 MB (partials and gradients of 14,568 one-hop nodes plus 1,024 seeds)
+    and 0.5 MB (1,024 seeds only) at hidden size 64: both are reproduced by one [n, hidden]
+    4-byte buffer forward and one of the same shape backward."""
+    vals = {}
+    with open(os.path.join(GOLDEN, "comm_example.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                vals[k] = float(v)
+    hidden, seeds, hop1 = int(vals["hidden"]), int(vals["seeds"]), int(vals["one_hop_nodes"])
+    fwd_bwd = 2
+    assert round((hop1 + seeds) * hidden * 4 * fwd_bwd / 1e6, 1) == vals["raf_megabytes"]
+    assert round(seeds * hidden * 4 * fwd_bwd / 2 ** 20, 1) == vals["raf_meta_partitioning_megabytes"]
+    # the oracle's partial aggregation has exactly that shape: one row per destination, hidden wide
+    e = np.zeros(0, dtype=np.int32)
+    Z = oracle.project(oracle.aggregate_fwd(e, e, seeds, np.zeros((1, 8), np.float32), "mean"),
+                       np.zeros((8, hidden)))
+    assert Z.shape == (seeds, hidden)
