@@ -1,0 +1,174 @@
+/*
+ * heta.h - C ABI of the MI355X (gfx950) library for the data-parallel hot path of the
+ * Relation-Aggregation-First (RAF) heterogeneous-GNN layer of arXiv 2408.09697.
+ *
+ * What the path computes (Eq. 1 of the paper with AGG_r = GCN-style neighbour sum/mean
+ * times a per-relation weight matrix, AGG_all = sum; Section 2.1):
+ *
+ *     M_r[v] = (sum | mean) over edges e of relation r into v of H0_s[u_e]      aggregate
+ *     Z_r    = M_r . W_r                                                        project
+ *     H_t    = sum over relations r into type t of Z_r                          cross-relation
+ *
+ * and the backward pass of Algorithm 1's local backpropagation:
+ *
+ *     dZ_r = G_t ;  dW_r = M_r^T dZ_r ;  dM_r = dZ_r W_r^T ;
+ *     dH0_s[u] += sum over edges e of r out of u of c_e dM_r[v_e],  c_e = 1 | 1/deg_r(v_e)
+ *
+ * Conventions for every call
+ *   - "device" pointers are HIP device memory of the current device; "host" pointers are
+ *     ordinary process memory.  The library never takes ownership of a caller's buffer and
+ *     never frees one.  It owns only heta_graph handles and what hangs off them.
+ *   - Matrices are row-major with a leading dimension `ld` counted in ELEMENTS.
+ *   - Every compute call is asynchronous on the given HIP stream (`hip_stream` is a
+ *     hipStream_t passed as void*, NULL = the default stream) and performs no hidden
+ *     synchronisation, except where a call says it may grow the handle's workspace.
+ *   - Every call returns a heta_status.  Arguments are validated on the host before any
+ *     kernel is launched; on failure nothing is launched, output buffers are untouched and
+ *     heta_last_error() describes the reason.  No exception or abort crosses this boundary.
+ *   - Results are deterministic: no atomics are used, the same inputs give the same bits.
+ *   - Node ids within a type and table row numbers must be below 2^31; edge offsets are 64-bit.
+ */
+#ifndef HETA_H
+#define HETA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct heta_graph heta_graph; /* opaque, created and destroyed by the library */
+
+typedef enum {
+    HETA_OK = 0,
+    HETA_ERR_INVALID_ARG = 1, /* null pointer, negative size, unknown enum value, index out of range */
+    HETA_ERR_BAD_CSR = 2,     /* rowptr not monotone / not starting at 0 / not ending at E, column out of range */
+    HETA_ERR_SHAPE = 3,       /* ld < d, widths that do not fit, beta other than 0 or 1 where required */
+    HETA_ERR_UNSUPPORTED = 4, /* dtype combination or size the library has no kernel for */
+    HETA_ERR_OOM = 5,         /* host or device allocation failed */
+    HETA_ERR_DEVICE = 6       /* a HIP call failed; heta_last_error() carries the HIP message */
+} heta_status;
+
+typedef enum { HETA_F32 = 0, HETA_BF16 = 1 } heta_dtype;
+typedef enum { HETA_SUM = 0, HETA_MEAN = 1 } heta_reduce;
+typedef enum { HETA_ACT_NONE = 0, HETA_ACT_RELU = 1 } heta_act;
+
+/* flags of heta_graph_create */
+#define HETA_PTRS_ON_DEVICE 1u /* the index arrays of every heta_relation are device pointers */
+
+/* A node type (Section 2.1: each node type may carry feature vectors of its own width, or
+ * none, in which case it gets learnable vectors).  feat_dim and learnable are descriptive;
+ * tables are passed to the compute calls. */
+typedef struct {
+    int64_t num_nodes;
+    int32_t feat_dim;
+    int32_t learnable;
+} heta_ntype;
+
+/* A relation = one mono-relation subgraph (Section 2.1), a bipartite adjacency from
+ * src_type to dst_type given as a CSR over DESTINATION rows. */
+typedef struct {
+    int32_t src_type, dst_type;
+    int64_t num_edges;
+    const int64_t *csr_rowptr; /* [n_dst + 1], rowptr[0] = 0, non-decreasing, rowptr[n_dst] = num_edges */
+    const int32_t *csr_col;    /* [num_edges] source node ids in [0, n_src); any order, duplicates allowed */
+} heta_relation;
+
+/* ---- graph ingest (HetG and its decomposition into mono-relation subgraphs, Section 2.1) ------
+ * Validates every relation, copies its CSR to the device, computes in-degrees, builds the
+ * transposed adjacency (CSC: for each source u the destinations of its out-edges in ascending
+ * original edge position) and the degree-sorted row schedules both directions use.
+ * Synchronous.  The caller's arrays may be freed on return.  `*out` is written only on success. */
+heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels,
+                              int32_t n_rels, uint32_t flags, heta_graph **out);
+heta_status heta_graph_destroy(heta_graph *g); /* NULL is accepted; synchronises the device */
+
+/* Read-back of the derived index data into HOST buffers (for bit-exact checks). Synchronous. */
+heta_status heta_graph_get_csc(const heta_graph *g, int32_t rel, int64_t *colptr /* [n_src+1] */,
+                               int32_t *row /* [num_edges] */);
+heta_status heta_graph_get_degrees(const heta_graph *g, int32_t rel, int64_t *in_deg /* [n_dst] */);
+
+/* ---- heterogeneous gather: h^0 of a node type from its feature or learnable table -------------
+ * (Section 2.1: h^0_v is the feature vector of v, or its learnable vector.)
+ * out[i, 0:d] = table[gid[i], 0:d] for i < n; bit-exact copy.  All pointers device.
+ * gid entries must lie in [0, n_table_rows): heta_check_ids can verify that. */
+heta_status heta_feature_gather(const void *table, heta_dtype dt, int64_t ld_table, int32_t d,
+                                int64_t n_table_rows, const int64_t *gid, int64_t n, void *out,
+                                int64_t ld_out, void *hip_stream);
+/* Counts entries of a device int64 id array outside [0, limit); synchronises the stream.
+ * Returns HETA_ERR_INVALID_ARG when any is out of range. */
+heta_status heta_check_ids(const int64_t *ids, int64_t n, int64_t limit, void *hip_stream);
+
+/* ---- relation-specific aggregation, forward (Eq. 1, first line; Algorithm 1, the workers'
+ * "aggregate neighbour features/embeddings" step) ------------------------------------------------
+ * out[v, 0:d] = sum over e in CSR row v of src_table[row(col[e]), 0:d], row(u) = src_gid ? src_gid[u] : u;
+ * HETA_MEAN divides by the row's degree; a zero-degree row gives exactly 0.
+ * src_table: device [n_table_rows, ld_src] of in_dt; needs n_table_rows >= n_src when src_gid is NULL.
+ * src_gid:   device [n_src] or NULL (local -> table row map of a sampled block; entries unchecked).
+ * out:       device [n_dst, ld_out] of out_dt (fp32 accumulation either way).
+ * Rows with ld * sizeof(elem) a multiple of 16 and 16-byte aligned bases use 128-bit loads; anything
+ * else runs an element-wise kernel, never an error.  May grow the handle's workspace when the
+ * relation has rows of 512+ edges (first call for a wider d: hipMalloc, which synchronises). */
+heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
+                                   heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
+                                   const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
+                                   void *hip_stream);
+
+/* ---- relation-specific aggregation, backward (Algorithm 1, local backpropagation with the
+ * gradients of the partial aggregations) ---------------------------------------------------------
+ * grad_src[u, 0:d] = beta * grad_src[u, 0:d] + sum over e in CSC column u of c_e * grad_out[row[e], 0:d]
+ * c_e = 1 (HETA_SUM) or 1/deg_r(row[e]) (HETA_MEAN).  A gather over the CSC: no atomics.
+ * grad_out: device fp32 [n_dst, ld_go]; grad_src: device fp32 [n_src, ld_gs]; beta is 0 or 1
+ * (1 accumulates the relations that share a source type, in the caller's call order). */
+heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, const float *grad_out,
+                                   int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs, float beta,
+                                   void *hip_stream);
+
+/* ---- per-relation projection (the per-relation weight matrices of R-GCN, Section 2.1) ---------
+ * out[i, 0:d_out] = beta * out[i, 0:d_out] + s_i * sum_k in[i, k] * B[k, j],  i < n_rows,
+ *   B = W          (W is [d_in, d_out], ld_w >= d_out)   when transW == 0     (forward,  Z = M W)
+ *   B = W^T        (W is [d_out, d_in], ld_w >= d_in)    when transW != 0     (backward, dM = dZ W^T)
+ *   s_i = row_scale ? row_scale[i] : 1.
+ * in: device [n_rows, ld_in] of in_dt; W device of w_dt; out device fp32 [n_rows, ld_out].
+ * Both fp32 -> fp32 MFMA; otherwise operands are rounded to bf16 and multiplied on the bf16 MFMA
+ * path; accumulation is fp32 in both.  beta = 1 fuses the cross-relation sum into the projection.
+ * heta_rel_project takes n_rows = n_dst of the relation; heta_project any row count. */
+heta_status heta_project(int64_t n_rows, const void *in, heta_dtype in_dt, int64_t ld_in, int32_t d_in,
+                         const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_out, int32_t transW,
+                         const float *row_scale, float *out, int64_t ld_out, float beta, void *hip_stream);
+heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
+                             int64_t ld_in, int32_t d_in, const void *W, heta_dtype w_dt, int64_t ld_w,
+                             int32_t d_out, int32_t transW, const float *row_scale, float *out,
+                             int64_t ld_out, float beta, void *hip_stream);
+
+/* Weight gradient dW[0:d_in, 0:d_out] = beta * dW + in^T . gout, the sum running over the n_dst
+ * rows of the relation in a fixed order (split over workgroups, then combined in order).
+ * in: device [n_dst, ld_in] of in_dt (the saved M_r); gout: device fp32 [n_dst, ld_go];
+ * dW: device fp32 [d_in, ld_dw].  Uses the handle's workspace (may grow it, see above). */
+heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
+                                   int64_t ld_in, int32_t d_in, const float *gout, int64_t ld_go,
+                                   int32_t d_out, float *dW, int64_t ld_dw, float beta, void *hip_stream);
+
+/* ---- cross-relation aggregation (Eq. 1, second line; Algorithm 1, AGG_all on the designated
+ * worker; on a subset of relations it yields the partial aggregation a worker would send) --------
+ * out[i, 0:d_out] = act(sum_{p < n_partials} partials[p][i, 0:d_out]), summed in array order.
+ * partials: HOST array of n_partials (1..16) device pointers, each fp32 [n_rows(dst_type), ld];
+ * out: device fp32 [n_rows, ld_out]; out may alias partials[0]. */
+heta_status heta_cross_rel_reduce(const heta_graph *g, int32_t dst_type, const float *const *partials,
+                                  int32_t n_partials, int64_t ld, int32_t d_out, heta_act act,
+                                  float *out, int64_t ld_out, void *hip_stream);
+/* Backward of the activation: grad_in = grad_out * [h > 0] for HETA_ACT_RELU (copy otherwise).
+ * All device fp32 [n_rows, ld]; grad_in may alias grad_out. */
+heta_status heta_act_bwd(int64_t n_rows, int32_t d, heta_act act, const float *h, int64_t ld_h,
+                         const float *grad_out, int64_t ld_go, float *grad_in, int64_t ld_gi,
+                         void *hip_stream);
+
+/* Message of the last failure on the calling thread (valid until that thread's next call). */
+const char *heta_last_error(void);
+/* "major.minor" of the library. */
+const char *heta_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HETA_H */

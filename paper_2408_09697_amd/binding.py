@@ -1,0 +1,327 @@
+"""ctypes binding of libheta.so: the same entry points as include/heta.h, argument
+marshalling only.  Device buffers are torch tensors (PyTorch-ROCm is used for device memory
+and streams, nothing else); host index arrays are numpy arrays.  Every step of the path runs
+inside the library's HIP kernels; there is no fallback: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch  # noqa: F401  (also makes sure the HIP runtime torch ships is the one in the process)
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "lib", "libheta.so")
+
+HETA_OK = 0
+HETA_ERR_INVALID_ARG, HETA_ERR_BAD_CSR, HETA_ERR_SHAPE = 1, 2, 3
+HETA_ERR_UNSUPPORTED, HETA_ERR_OOM, HETA_ERR_DEVICE = 4, 5, 6
+HETA_F32, HETA_BF16 = 0, 1
+HETA_SUM, HETA_MEAN = 0, 1
+HETA_ACT_NONE, HETA_ACT_RELU = 0, 1
+HETA_PTRS_ON_DEVICE = 1
+
+EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "heta_graph_get_degrees",
+           "heta_feature_gather", "heta_check_ids", "heta_rel_aggregate_fwd", "heta_rel_aggregate_bwd",
+           "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
+           "heta_act_bwd", "heta_last_error", "heta_version"]
+
+
+class HetaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"heta status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+class _NType(ctypes.Structure):
+    _fields_ = [("num_nodes", ctypes.c_int64), ("feat_dim", ctypes.c_int32), ("learnable", ctypes.c_int32)]
+
+
+class _Relation(ctypes.Structure):
+    _fields_ = [("src_type", ctypes.c_int32), ("dst_type", ctypes.c_int32), ("num_edges", ctypes.c_int64),
+                ("csr_rowptr", ctypes.c_void_p), ("csr_col", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libheta.so (built in-tree by `paper_2408_09697_amd.build`); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2408_09697_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    i32, i64, u32, vp, f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_float
+    L.heta_graph_create.argtypes = [vp, i32, vp, i32, u32, ctypes.POINTER(vp)]
+    L.heta_graph_destroy.argtypes = [vp]
+    L.heta_graph_get_csc.argtypes = [vp, i32, vp, vp]
+    L.heta_graph_get_degrees.argtypes = [vp, i32, vp]
+    L.heta_feature_gather.argtypes = [vp, i32, i64, i32, i64, vp, i64, vp, i64, vp]
+    L.heta_check_ids.argtypes = [vp, i64, i64, vp]
+    L.heta_rel_aggregate_fwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, i64, vp, vp, i32, i64, vp]
+    L.heta_rel_aggregate_bwd.argtypes = [vp, i32, i32, vp, i64, i32, vp, i64, f32, vp]
+    L.heta_project.argtypes = [i64, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i64, f32, vp]
+    L.heta_rel_project.argtypes = [vp, i32, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i64, f32, vp]
+    L.heta_rel_project_wgrad.argtypes = [vp, i32, vp, i32, i64, i32, vp, i64, i32, vp, i64, f32, vp]
+    L.heta_cross_rel_reduce.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, i64, vp]
+    L.heta_act_bwd.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp]
+    for name in EXPORTS:
+        getattr(L, name).restype = ctypes.c_int
+    L.heta_last_error.restype = ctypes.c_char_p
+    L.heta_last_error.argtypes = []
+    L.heta_version.restype = ctypes.c_char_p
+    L.heta_version.argtypes = []
+    _lib = L
+    return L
+
+
+def _check(st: int) -> None:
+    if st != HETA_OK:
+        raise HetaError(st, load_library().heta_last_error().decode())
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return HETA_F32
+    if t.dtype == torch.bfloat16:
+        return HETA_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _dev(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
+    """Device pointer of a tensor whose last dimension is contiguous."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if t.dim() >= 1 and t.shape[-1] > 1 and t.stride(-1) != 1:
+        raise TypeError(f"{name}: last dimension must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _ld(t: torch.Tensor) -> int:
+    return t.stride(0) if t.dim() == 2 else t.shape[-1]
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+class Graph:
+    """Owner of a heta_graph handle."""
+
+    def __init__(self, handle: int, ntypes, rel_meta):
+        self._h = ctypes.c_void_p(handle)
+        self.ntypes = ntypes          # [(num_nodes, feat_dim, learnable)]
+        self.rels = rel_meta          # [(src_type, dst_type, num_edges)]
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise HetaError(HETA_ERR_INVALID_ARG, "graph already destroyed")
+        return self._h
+
+    def n_src(self, rel: int) -> int:
+        return self.ntypes[self.rels[rel][0]][0]
+
+    def n_dst(self, rel: int) -> int:
+        return self.ntypes[self.rels[rel][1]][0]
+
+    def destroy(self) -> None:
+        if self._h is not None:
+            heta_graph_destroy(self)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def heta_version() -> str:
+    return load_library().heta_version().decode()
+
+
+def heta_last_error() -> str:
+    return load_library().heta_last_error().decode()
+
+
+def heta_graph_create(ntypes: Sequence[Sequence[int]], relations: Sequence[Sequence], flags: int = 0) -> Graph:
+    """ntypes: (num_nodes, feat_dim, learnable) per node type.  relations: (src_type, dst_type,
+    rowptr, col) per relation, rowptr int64 [n_dst+1] and col int32 [E]; numpy arrays, or device
+    tensors when flags has HETA_PTRS_ON_DEVICE."""
+    L = load_library()
+    nt = (_NType * max(1, len(ntypes)))()
+    for i, (n, d, l) in enumerate(ntypes):
+        nt[i] = _NType(int(n), int(d), int(l))
+    rl = (_Relation * max(1, len(relations)))()
+    keep = []
+    meta = []
+    for i, (s, t, rowptr, col) in enumerate(relations):
+        if flags & HETA_PTRS_ON_DEVICE:
+            rp = _dev(rowptr, "rowptr", torch.int64)
+            cp = _dev(col, "col", torch.int32)
+            n_e = int(col.numel())
+        else:
+            rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+            col = np.ascontiguousarray(col, dtype=np.int32)
+            rp, cp, n_e = rowptr.ctypes.data, col.ctypes.data, int(col.size)
+        keep += [rowptr, col]
+        rl[i] = _Relation(int(s), int(t), n_e, rp, cp)
+        meta.append((int(s), int(t), n_e))
+    out = ctypes.c_void_p()
+    _check(L.heta_graph_create(ctypes.addressof(nt) if len(ntypes) else None, len(ntypes),
+                               ctypes.addressof(rl) if len(relations) else None, len(relations),
+                               flags, ctypes.byref(out)))
+    return Graph(out.value, [tuple(int(x) for x in t) for t in ntypes], meta)
+
+
+def heta_graph_destroy(g: Graph) -> None:
+    h, g._h = g._h, None
+    if h is not None:
+        _check(load_library().heta_graph_destroy(h))
+
+
+def heta_graph_get_csc(g: Graph, rel: int):
+    n_src, n_e = g.n_src(rel), g.rels[rel][2]
+    colptr = np.zeros(n_src + 1, dtype=np.int64)
+    row = np.zeros(n_e, dtype=np.int32)
+    _check(load_library().heta_graph_get_csc(g.handle, rel, colptr.ctypes.data, row.ctypes.data))
+    return colptr, row
+
+
+def heta_graph_get_degrees(g: Graph, rel: int) -> np.ndarray:
+    deg = np.zeros(g.n_dst(rel), dtype=np.int64)
+    _check(load_library().heta_graph_get_degrees(g.handle, rel, deg.ctypes.data))
+    return deg
+
+
+def heta_feature_gather(table: torch.Tensor, gid: torch.Tensor, out: torch.Tensor, d: Optional[int] = None,
+                        stream=None) -> torch.Tensor:
+    d = table.shape[1] if d is None else d
+    if table.dtype != out.dtype:
+        raise TypeError("heta_feature_gather: table and out must have the same dtype")
+    _check(load_library().heta_feature_gather(_dev(table, "table"), _dt(table), _ld(table), d, table.shape[0],
+                                              _dev(gid, "gid", torch.int64), gid.numel(), _dev(out, "out"),
+                                              _ld(out), _stream(stream)))
+    return out
+
+
+def heta_check_ids(ids: torch.Tensor, limit: int, stream=None) -> None:
+    _check(load_library().heta_check_ids(_dev(ids, "ids", torch.int64), ids.numel(), limit, _stream(stream)))
+
+
+def heta_rel_aggregate_fwd(g: Graph, rel: int, op: int, src_table: torch.Tensor, out: torch.Tensor,
+                           d: Optional[int] = None, src_gid: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    d = src_table.shape[1] if d is None else d
+    if out.shape[0] < g.n_dst(rel):
+        raise HetaError(HETA_ERR_SHAPE, "out has fewer rows than the relation has destinations")
+    if src_gid is not None and src_gid.numel() < g.n_src(rel):
+        raise HetaError(HETA_ERR_SHAPE, "src_gid has fewer entries than the relation has sources")
+    _check(load_library().heta_rel_aggregate_fwd(
+        g.handle, rel, op, _dev(src_table, "src_table"), _dt(src_table), _ld(src_table), d, src_table.shape[0],
+        _dev(src_gid, "src_gid", torch.int64), _dev(out, "out"), _dt(out), _ld(out), _stream(stream)))
+    return out
+
+
+def heta_rel_aggregate_bwd(g: Graph, rel: int, op: int, grad_out: torch.Tensor, grad_src: torch.Tensor,
+                           beta: float = 0.0, d: Optional[int] = None, stream=None) -> torch.Tensor:
+    d = grad_out.shape[1] if d is None else d
+    if grad_out.shape[0] < g.n_dst(rel) or grad_src.shape[0] < g.n_src(rel):
+        raise HetaError(HETA_ERR_SHAPE, "gradient buffers have fewer rows than the relation needs")
+    _check(load_library().heta_rel_aggregate_bwd(
+        g.handle, rel, op, _dev(grad_out, "grad_out", torch.float32), _ld(grad_out), d,
+        _dev(grad_src, "grad_src", torch.float32), _ld(grad_src), beta, _stream(stream)))
+    return grad_src
+
+
+def _w_ld(W: torch.Tensor) -> int:
+    return W.stride(0)
+
+
+def heta_project(inp: torch.Tensor, W: torch.Tensor, out: torch.Tensor, trans_w: bool = False,
+                 row_scale: Optional[torch.Tensor] = None, beta: float = 0.0, n_rows: Optional[int] = None,
+                 stream=None) -> torch.Tensor:
+    """out = beta*out + row_scale * inp @ (W^T if trans_w else W)."""
+    n_rows = inp.shape[0] if n_rows is None else n_rows
+    d_in = inp.shape[1]
+    d_out = W.shape[0] if trans_w else W.shape[1]
+    if (W.shape[1] if trans_w else W.shape[0]) != d_in:
+        raise HetaError(HETA_ERR_SHAPE, "W does not match the input width")
+    if out.shape[0] < n_rows or out.shape[1] < d_out or inp.shape[0] < n_rows:
+        raise HetaError(HETA_ERR_SHAPE, "buffers too small for the projection")
+    if row_scale is not None and row_scale.numel() < n_rows:
+        raise HetaError(HETA_ERR_SHAPE, "row_scale too short")
+    _check(load_library().heta_project(
+        n_rows, _dev(inp, "in"), _dt(inp), _ld(inp), d_in, _dev(W, "W"), _dt(W), _w_ld(W), d_out, int(trans_w),
+        _dev(row_scale, "row_scale", torch.float32), _dev(out, "out", torch.float32), _ld(out), beta, _stream(stream)))
+    return out
+
+
+def heta_rel_project(g: Graph, rel: int, inp: torch.Tensor, W: torch.Tensor, out: torch.Tensor,
+                     trans_w: bool = False, row_scale: Optional[torch.Tensor] = None, beta: float = 0.0,
+                     stream=None) -> torch.Tensor:
+    n = g.n_dst(rel)
+    d_in = inp.shape[1]
+    d_out = W.shape[0] if trans_w else W.shape[1]
+    if (W.shape[1] if trans_w else W.shape[0]) != d_in:
+        raise HetaError(HETA_ERR_SHAPE, "W does not match the input width")
+    if inp.shape[0] < n or out.shape[0] < n or out.shape[1] < d_out:
+        raise HetaError(HETA_ERR_SHAPE, "buffers too small for the projection")
+    if row_scale is not None and row_scale.numel() < n:
+        raise HetaError(HETA_ERR_SHAPE, "row_scale too short")
+    _check(load_library().heta_rel_project(
+        g.handle, rel, _dev(inp, "in"), _dt(inp), _ld(inp), d_in, _dev(W, "W"), _dt(W), _w_ld(W), d_out,
+        int(trans_w), _dev(row_scale, "row_scale", torch.float32), _dev(out, "out", torch.float32), _ld(out),
+        beta, _stream(stream)))
+    return out
+
+
+def heta_rel_project_wgrad(g: Graph, rel: int, inp: torch.Tensor, gout: torch.Tensor, dW: torch.Tensor,
+                           beta: float = 0.0, stream=None) -> torch.Tensor:
+    n = g.n_dst(rel)
+    d_in, d_out = inp.shape[1], gout.shape[1]
+    if inp.shape[0] < n or gout.shape[0] < n or dW.shape[0] < d_in or dW.shape[1] < d_out:
+        raise HetaError(HETA_ERR_SHAPE, "buffers too small for the weight gradient")
+    _check(load_library().heta_rel_project_wgrad(
+        g.handle, rel, _dev(inp, "in"), _dt(inp), _ld(inp), d_in, _dev(gout, "gout", torch.float32), _ld(gout),
+        d_out, _dev(dW, "dW", torch.float32), _ld(dW), beta, _stream(stream)))
+    return dW
+
+
+def heta_cross_rel_reduce(g: Graph, dst_type: int, partials: List[torch.Tensor], out: torch.Tensor,
+                          act: int = HETA_ACT_NONE, stream=None) -> torch.Tensor:
+    n = g.ntypes[dst_type][0]
+    d_out = partials[0].shape[1]
+    ld = _ld(partials[0])
+    for p in partials:
+        if p.shape[0] < n or p.shape[1] != d_out or _ld(p) != ld:
+            raise HetaError(HETA_ERR_SHAPE, "partials must share shape and leading dimension")
+    if out.shape[0] < n or out.shape[1] < d_out:
+        raise HetaError(HETA_ERR_SHAPE, "out too small")
+    arr = (ctypes.c_void_p * len(partials))(*[_dev(p, "partial", torch.float32) for p in partials])
+    _check(load_library().heta_cross_rel_reduce(g.handle, dst_type, ctypes.addressof(arr), len(partials), ld,
+                                                d_out, act, _dev(out, "out", torch.float32), _ld(out),
+                                                _stream(stream)))
+    return out
+
+
+def heta_act_bwd(act: int, h: Optional[torch.Tensor], grad_out: torch.Tensor, grad_in: torch.Tensor,
+                 stream=None) -> torch.Tensor:
+    n, d = grad_out.shape
+    if grad_in.shape[0] < n or grad_in.shape[1] < d or (h is not None and (h.shape[0] < n or h.shape[1] < d)):
+        raise HetaError(HETA_ERR_SHAPE, "buffers too small")
+    _check(load_library().heta_act_bwd(n, d, act, _dev(h, "h", torch.float32), _ld(h) if h is not None else d,
+                                       _dev(grad_out, "grad_out", torch.float32), _ld(grad_out),
+                                       _dev(grad_in, "grad_in", torch.float32), _ld(grad_in), _stream(stream)))
+    return grad_in

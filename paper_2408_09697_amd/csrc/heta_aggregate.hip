@@ -1,0 +1,582 @@
+// Relation-specific aggregation, forward and backward, as one segmented gather-reduce.
+//
+// Forward (Eq. 1 of the paper, first line, with a GCN-style sum/mean as AGG_r) walks a
+// relation's CSR: output row v adds the source rows of v's in-edges.  Backward (Algorithm 1,
+// local backpropagation) walks the CSC: output row u adds the gradient rows of the
+// destinations of u's out-edges, weighted by 1/deg for the mean.  Both are
+//
+//     out[r] = beta * out[r] + scale(r) * sum_{e in [ptr[r], ptr[r+1])} w[idx[e]] * table[row(idx[e])]
+//
+// so one family of kernels serves both, and nothing is scattered: every output row is
+// written by exactly one lane group, which makes the result independent of scheduling.
+//
+// Mapping to the machine (wave64, HBM-bound):
+//   - A row of d elements is cut into 16-byte chunks; a "lane group" of L lanes (L = the
+//     power of two covering the chunks, at most 64, each lane holding one or two chunks)
+//     reads a whole neighbour row with one 128-bit load per lane, fully coalesced.
+//   - Rows are scheduled by degree (perm = rows by descending degree):
+//       hub rows   (>= 512 edges): cut into 256-edge chunks, one wavefront per chunk, partial
+//                  sums to a workspace, a second kernel adds the partials in chunk order;
+//       long rows  (>= the wave threshold): one wavefront per row; its 64/L lane groups take
+//                  the row's edges round-robin, several loads in flight each, and are
+//                  combined at the end with cross-lane shuffles;
+//       short rows (the bulk of a power-law graph, incl. empty rows): one lane group per row,
+//                  64/L rows per wavefront, neighbours of equal degree side by side.
+//   - Neighbour ids of a long row are fetched 64 at a time with one coalesced load and
+//     broadcast with lane shuffles.
+#include <algorithm>
+
+#include "heta_internal.h"
+
+namespace heta {
+
+struct AggParams {
+    const int64_t *ptr;
+    const int32_t *idx;
+    const int32_t *perm;
+    const HubChunk *hub_chunks;
+    const int64_t *hub_chunk_ptr;
+    const void *table;
+    int64_t ld;            // elements
+    const int64_t *gid;    // nullable: neighbour id -> table row
+    const float *edge_w;   // nullable: weight per neighbour id
+    int mean;              // divide the row sum by the row's degree
+    void *out;
+    int64_t ld_out;
+    int out_bf16;
+    float beta;            // 0 or 1
+    float *ws;             // hub partials [slot][ws_ld]
+    int64_t ws_ld;
+    int d;
+    int64_t n_hub_chunks, n_hub_rows;
+    int64_t n_wave_items;  // hub chunks + long rows
+    int64_t short_lo;      // perm[short_lo .. n_rows) are short rows
+    int64_t n_rows;
+};
+
+using bf16_t = uint16_t;
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return static_cast<bf16_t>((u >> 16) | 0x40u);
+    return static_cast<bf16_t>((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// One chunk of a row: EPC elements of T, read as one load.
+template <typename T, int EPC> struct Chunk;
+template <> struct Chunk<float, 4> {
+    float4 v;
+    __device__ __forceinline__ void load(const float *p) { v = *reinterpret_cast<const float4 *>(p); }
+    __device__ __forceinline__ void zero() { v = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void add_to(float *a, float w) const
+    {
+        a[0] = fmaf(w, v.x, a[0]); a[1] = fmaf(w, v.y, a[1]); a[2] = fmaf(w, v.z, a[2]); a[3] = fmaf(w, v.w, a[3]);
+    }
+    __device__ __forceinline__ void add_to(float *a) const { a[0] += v.x; a[1] += v.y; a[2] += v.z; a[3] += v.w; }
+};
+template <> struct Chunk<float, 1> {
+    float v;
+    __device__ __forceinline__ void load(const float *p) { v = *p; }
+    __device__ __forceinline__ void zero() { v = 0.f; }
+    __device__ __forceinline__ void add_to(float *a, float w) const { a[0] = fmaf(w, v, a[0]); }
+    __device__ __forceinline__ void add_to(float *a) const { a[0] += v; }
+};
+template <> struct Chunk<bf16_t, 8> {
+    uint4 v;
+    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void zero() { v = make_uint4(0u, 0u, 0u, 0u); }
+    __device__ __forceinline__ void widen(float *f) const
+    {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+    __device__ __forceinline__ void add_to(float *a, float w) const
+    {
+        float f[8];
+        widen(f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = fmaf(w, f[i], a[i]);
+    }
+    __device__ __forceinline__ void add_to(float *a) const
+    {
+        float f[8];
+        widen(f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] += f[i];
+    }
+};
+template <> struct Chunk<bf16_t, 1> {
+    bf16_t v;
+    __device__ __forceinline__ void load(const bf16_t *p) { v = *p; }
+    __device__ __forceinline__ void zero() { v = 0; }
+    __device__ __forceinline__ void add_to(float *a, float w) const { a[0] = fmaf(w, bf16_to_f32(v), a[0]); }
+    __device__ __forceinline__ void add_to(float *a) const { a[0] += bf16_to_f32(v); }
+};
+
+// Final store of one lane's chunk of an output row: scale, optional accumulate, element guard.
+template <int EPC>
+__device__ __forceinline__ void store_out(const AggParams &p, int64_t row, int col0, const float *acc, float scale)
+{
+    if (p.out_bf16) {
+        bf16_t *o = static_cast<bf16_t *>(p.out) + row * p.ld_out + col0;
+#pragma unroll
+        for (int i = 0; i < EPC; ++i)
+            if (col0 + i < p.d) {
+                float v = acc[i] * scale;
+                if (p.beta != 0.f) v += bf16_to_f32(o[i]);
+                o[i] = f32_to_bf16(v);
+            }
+    } else {
+        float *o = static_cast<float *>(p.out) + row * p.ld_out + col0;
+        if (EPC == 4 && col0 + 4 <= p.d && ((p.ld_out & 3) == 0) &&
+            ((reinterpret_cast<uintptr_t>(p.out) & 15u) == 0)) {
+            float4 v = make_float4(acc[0] * scale, acc[1] * scale, acc[2] * scale, acc[3] * scale);
+            if (p.beta != 0.f) {
+                float4 old = *reinterpret_cast<float4 *>(o);
+                v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+            }
+            *reinterpret_cast<float4 *>(o) = v;
+        } else {
+#pragma unroll
+            for (int i = 0; i < EPC; ++i)
+                if (col0 + i < p.d) {
+                    float v = acc[i] * scale;
+                    if (p.beta != 0.f) v += o[i];
+                    o[i] = v;
+                }
+        }
+    }
+}
+
+__device__ __forceinline__ float row_scale(const AggParams &p, int64_t deg)
+{
+    if (!p.mean) return 1.f;
+    return deg > 0 ? 1.f / static_cast<float>(deg) : 0.f;
+}
+
+// ---- short rows: one lane group per row ----------------------------------------------------------
+template <typename T, int EPC, int L, int CPL>
+__global__ void __launch_bounds__(256) agg_group_kernel(AggParams p)
+{
+    constexpr int U = 4;
+    const int64_t q = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) / L;
+    if (q >= p.n_rows - p.short_lo) return; // lane groups are independent here: no cross-lane traffic
+    const int l = threadIdx.x % L;
+    const int64_t row = p.perm[p.short_lo + q];
+    const int64_t e0 = p.ptr[row], e1 = p.ptr[row + 1];
+    const int n_chunks = (p.d + EPC - 1) / EPC;
+    const int ch0 = blockIdx.y * (L * CPL) + l;
+    const T *table = static_cast<const T *>(p.table);
+    float acc[CPL][EPC];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c)
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) acc[c][i] = 0.f;
+
+    for (int64_t e = e0; e < e1; e += U) {
+        Chunk<T, EPC> v[U][CPL];
+        float w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool ok = e + u < e1;
+            int c = ok ? p.idx[e + u] : 0;
+            w[u] = (ok && p.edge_w) ? p.edge_w[c] : 1.f;
+            const int64_t r = (ok && p.gid) ? p.gid[c] : c;
+            const T *rp = table + r * p.ld;
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+                const int ch = ch0 + k * L;
+                if (ok && ch < n_chunks) v[u][k].load(rp + static_cast<int64_t>(ch) * EPC);
+                else v[u][k].zero();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+                if (p.edge_w) v[u][k].add_to(acc[k], w[u]);
+                else v[u][k].add_to(acc[k]);
+            }
+    }
+    const float scale = row_scale(p, e1 - e0);
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        const int ch = ch0 + k * L;
+        if (ch < n_chunks) store_out<EPC>(p, row, ch * EPC, acc[k], scale);
+    }
+}
+
+// ---- long rows and hub chunks: one wavefront per item ----------------------------------------------
+template <typename T, int EPC, int L, int CPL>
+__global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
+{
+    constexpr int G = 64 / L;            // lane groups per wavefront
+    constexpr int U = (G >= 8) ? 1 : ((G >= 4) ? 2 : 4); // edges in flight per group and step
+    const int lane = threadIdx.x & 63;
+    const int64_t w = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (w >= p.n_wave_items) return;     // uniform per wavefront
+    int64_t e0, e1, row = -1;
+    int slot = -1;
+    if (w < p.n_hub_chunks) {
+        const HubChunk c = p.hub_chunks[w];
+        e0 = c.e0;
+        e1 = c.e0 + c.len;
+        slot = c.slot;
+    } else {
+        row = p.perm[p.n_hub_rows + (w - p.n_hub_chunks)];
+        e0 = p.ptr[row];
+        e1 = p.ptr[row + 1];
+    }
+    const int g = lane / L, l = lane % L;
+    const int n_chunks = (p.d + EPC - 1) / EPC;
+    const int ch0 = blockIdx.y * (L * CPL) + l;
+    const T *table = static_cast<const T *>(p.table);
+    float acc[CPL][EPC];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c)
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) acc[c][i] = 0.f;
+
+    for (int64_t base = e0; base < e1; base += 64) {
+        const int cnt = static_cast<int>(min(static_cast<int64_t>(64), e1 - base));
+        int rid = 0;
+        float wv = 1.f;
+        if (lane < cnt) {
+            const int c = p.idx[base + lane];
+            rid = p.gid ? static_cast<int>(p.gid[c]) : c;
+            if (p.edge_w) wv = p.edge_w[c];
+        }
+        for (int j = 0; j < cnt; j += G * U) {
+            Chunk<T, EPC> v[U][CPL];
+            float ww[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int k = j + u * G + g;
+                const bool ok = k < cnt;
+                const int r = __shfl(rid, k & 63, 64);
+                ww[u] = __shfl(wv, k & 63, 64);
+                const T *rp = table + static_cast<int64_t>(r) * p.ld;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    const int ch = ch0 + c * L;
+                    if (ok && ch < n_chunks) v[u][c].load(rp + static_cast<int64_t>(ch) * EPC);
+                    else v[u][c].zero();
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    if (p.edge_w) v[u][c].add_to(acc[c], ww[u]);
+                    else v[u][c].add_to(acc[c]);
+                }
+        }
+    }
+    // combine the lane groups (fixed butterfly order)
+#pragma unroll
+    for (int off = L; off < 64; off <<= 1)
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) acc[c][i] += __shfl_xor(acc[c][i], off, 64);
+    if (g != 0) return;
+    if (slot >= 0) {
+        float *o = p.ws + static_cast<int64_t>(slot) * p.ws_ld;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            const int ch = ch0 + c * L;
+            if (ch < n_chunks) {
+#pragma unroll
+                for (int i = 0; i < EPC; ++i) o[ch * EPC + i] = acc[c][i];
+            }
+        }
+    } else {
+        const float scale = row_scale(p, e1 - e0);
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            const int ch = ch0 + c * L;
+            if (ch < n_chunks) store_out<EPC>(p, row, ch * EPC, acc[c], scale);
+        }
+    }
+}
+
+// ---- hub rows: add the chunk partials in chunk order -------------------------------------------------
+// One workgroup per (hub row, tile of 256 columns); wave w adds the partials w, w+4, w+8, ...
+// and the four sums are combined through LDS in wave order.
+__global__ void __launch_bounds__(256) agg_hub_combine_kernel(AggParams p)
+{
+    __shared__ float4 part[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t h = blockIdx.x;
+    const int64_t row = p.perm[h];
+    const int64_t s0 = p.hub_chunk_ptr[h], s1 = p.hub_chunk_ptr[h + 1];
+    const int col0 = (blockIdx.y * 64 + lane) * 4;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (col0 < p.ws_ld) {
+        for (int64_t s = s0 + wave; s < s1; s += 16) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t t = s + 4 * u;
+                if (t < s1) v[u] = *reinterpret_cast<const float4 *>(p.ws + t * p.ws_ld + col0);
+                else v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { a.x += v[u].x; a.y += v[u].y; a.z += v[u].z; a.w += v[u].w; }
+        }
+    }
+    part[wave][lane] = a;
+    __syncthreads();
+    if (wave != 0 || col0 >= p.d) return;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float4 v = part[k][lane];
+        acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+    }
+    const float scale = row_scale(p, p.ptr[row + 1] - p.ptr[row]);
+    store_out<4>(p, row, col0, acc, scale);
+}
+
+// ---- launch ---------------------------------------------------------------------------------------
+template <typename T, int EPC, int L, int CPL>
+static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st)
+{
+    constexpr int G = 64 / L;
+    if (p.n_wave_items > 0) {
+        const int64_t blocks = (p.n_wave_items + 3) / 4;
+        if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many long rows");
+        hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
+        HETA_LAUNCH_CHECK("agg_wave_kernel");
+    }
+    const int64_t n_short = p.n_rows - p.short_lo;
+    if (n_short > 0) {
+        const int64_t blocks = (n_short + 4 * G - 1) / (4 * G);
+        if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many short rows");
+        hipLaunchKernelGGL((agg_group_kernel<T, EPC, L, CPL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
+        HETA_LAUNCH_CHECK("agg_group_kernel");
+    }
+    return HETA_OK;
+}
+
+template <typename T, int EPC>
+static heta_status launch_vec(const AggParams &p, int n_chunks, hipStream_t st)
+{
+    if (n_chunks <= 1) return launch_pair<T, EPC, 1, 1>(p, 1, st);
+    if (n_chunks <= 2) return launch_pair<T, EPC, 2, 1>(p, 1, st);
+    if (n_chunks <= 4) return launch_pair<T, EPC, 4, 1>(p, 1, st);
+    if (n_chunks <= 8) return launch_pair<T, EPC, 8, 1>(p, 1, st);
+    if (n_chunks <= 16) return launch_pair<T, EPC, 16, 1>(p, 1, st);
+    if (n_chunks <= 32) return launch_pair<T, EPC, 32, 1>(p, 1, st);
+    if (n_chunks <= 64) return launch_pair<T, EPC, 64, 1>(p, 1, st);
+    return launch_pair<T, EPC, 64, 2>(p, (n_chunks + 127) / 128, st);
+}
+
+// lanes per row the dispatch above picks for a row of n_chunks chunks
+static int lanes_per_row(int n_chunks)
+{
+    int L = 1;
+    while (L < n_chunks && L < 64) L <<= 1;
+    return L;
+}
+
+// The shared entry of forward and backward.
+static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, heta_dtype in_dt,
+                                 int64_t table_elems_ld, hipStream_t st)
+{
+    (void)table_elems_ld;
+    if (s.n_rows == 0) return HETA_OK;
+    const size_t esz = dtype_size(in_dt);
+    const bool vec = aligned16(p.table) && ((p.ld * esz) % 16 == 0);
+    const int epc = vec ? static_cast<int>(16 / esz) : 1;
+    const int n_chunks = (p.d + epc - 1) / epc;
+    const int L = vec ? lanes_per_row(n_chunks) : 64;
+    const int G = 64 / L;
+    // rows with at least this many edges get a whole wavefront
+    const int wave_min = std::min(kHubMinDeg, std::max(8, 2 * G));
+    const int64_t n_long_or_hub = s.rows_with_deg_ge[wave_min];
+    p.ptr = s.d_ptr;
+    p.idx = s.d_idx;
+    p.perm = s.d_perm;
+    p.hub_chunks = s.d_hub_chunks;
+    p.hub_chunk_ptr = s.d_hub_chunk_ptr;
+    p.n_hub_chunks = s.n_hub_chunks;
+    p.n_hub_rows = s.n_hub_rows;
+    p.n_wave_items = s.n_hub_chunks + (n_long_or_hub - s.n_hub_rows);
+    p.short_lo = n_long_or_hub;
+    p.n_rows = s.n_rows;
+    p.ws_ld = (static_cast<int64_t>(p.d) + 7) / 8 * 8;
+    p.ws = nullptr;
+    if (s.n_hub_chunks > 0) {
+        heta_status e = ensure_workspace(g, static_cast<size_t>(s.n_hub_chunks) * p.ws_ld * sizeof(float));
+        if (e != HETA_OK) return e;
+        p.ws = static_cast<float *>(g->d_ws);
+    }
+    heta_status e;
+    if (in_dt == HETA_F32)
+        e = vec ? launch_vec<float, 4>(p, n_chunks, st) : launch_pair<float, 1, 64, 2>(p, (n_chunks + 127) / 128, st);
+    else
+        e = vec ? launch_vec<bf16_t, 8>(p, n_chunks, st) : launch_pair<bf16_t, 1, 64, 2>(p, (n_chunks + 127) / 128, st);
+    if (e != HETA_OK) return e;
+    if (s.n_hub_rows > 0) {
+        if (s.n_hub_rows > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many hub rows");
+        const int tiles = static_cast<int>((p.ws_ld + 255) / 256);
+        hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(256), 0, st, p);
+        HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
+    }
+    return HETA_OK;
+}
+
+// ---- plain row gather and id check -------------------------------------------------------------------
+template <typename V>
+__global__ void __launch_bounds__(256) gather_rows_kernel(const V *table, int64_t ld_v, const int64_t *gid,
+                                                          int64_t n, int per_row, V *out, int64_t ld_out_v)
+{
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t i = t / per_row;
+    const int c = static_cast<int>(t % per_row);
+    if (i >= n) return;
+    out[i * ld_out_v + c] = table[gid[i] * ld_v + c];
+}
+
+__global__ void __launch_bounds__(256) check_ids_kernel(const int64_t *ids, int64_t n, int64_t limit, int *flag)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n && (ids[i] < 0 || ids[i] >= limit)) *flag = 1; // every writer stores the same value
+}
+
+} // namespace heta
+
+using namespace heta;
+
+extern "C" {
+
+heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
+                                   heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
+                                   const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
+                                   void *hip_stream)
+{
+    if (!g || !src_table || !out) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: null argument");
+    if (rel < 0 || rel >= (int32_t)g->rels.size())
+        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: relation %d out of range", rel);
+    if (op != HETA_SUM && op != HETA_MEAN) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: bad reduce op");
+    if (!valid_dtype(in_dt) || !valid_dtype(out_dt))
+        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: bad dtype");
+    if (d <= 0 || ld_src < d || ld_out < d)
+        return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_fwd: need 0 < d <= ld (d=%d ld_src=%lld ld_out=%lld)", d,
+                    (long long)ld_src, (long long)ld_out);
+    const Relation &r = g->rels[rel];
+    if (n_table_rows < 0 || n_table_rows >= (int64_t(1) << 31))
+        return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_fwd: n_table_rows outside [0, 2^31)");
+    if (!src_gid && n_table_rows < r.n_src)
+        return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_fwd: table has %lld rows, relation needs %lld",
+                    (long long)n_table_rows, (long long)r.n_src);
+    if ((reinterpret_cast<uintptr_t>(src_table) % dtype_size(in_dt)) || (reinterpret_cast<uintptr_t>(out) % dtype_size(out_dt)))
+        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: pointer not aligned to its element size");
+    AggParams p{};
+    p.table = src_table;
+    p.ld = ld_src;
+    p.gid = src_gid;
+    p.edge_w = nullptr;
+    p.mean = (op == HETA_MEAN);
+    p.out = out;
+    p.ld_out = ld_out;
+    p.out_bf16 = (out_dt == HETA_BF16);
+    p.beta = 0.f;
+    p.d = d;
+    return run_aggregate(g, r.csr, p, in_dt, ld_src, as_stream(hip_stream));
+}
+
+heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, const float *grad_out,
+                                   int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs, float beta,
+                                   void *hip_stream)
+{
+    if (!g || !grad_out || !grad_src) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: null argument");
+    if (rel < 0 || rel >= (int32_t)g->rels.size())
+        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: relation %d out of range", rel);
+    if (op != HETA_SUM && op != HETA_MEAN) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: bad reduce op");
+    if (d <= 0 || ld_go < d || ld_gs < d)
+        return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_bwd: need 0 < d <= ld (d=%d ld_go=%lld ld_gs=%lld)", d,
+                    (long long)ld_go, (long long)ld_gs);
+    if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_bwd: beta must be 0 or 1");
+    if ((reinterpret_cast<uintptr_t>(grad_out) & 3u) || (reinterpret_cast<uintptr_t>(grad_src) & 3u))
+        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: pointer not 4-byte aligned");
+    const Relation &r = g->rels[rel];
+    AggParams p{};
+    p.table = grad_out;
+    p.ld = ld_go;
+    p.gid = nullptr;
+    p.edge_w = (op == HETA_MEAN) ? r.d_inv_deg : nullptr;
+    p.mean = 0;
+    p.out = grad_src;
+    p.ld_out = ld_gs;
+    p.out_bf16 = 0;
+    p.beta = beta;
+    p.d = d;
+    return run_aggregate(g, r.csc, p, HETA_F32, ld_go, as_stream(hip_stream));
+}
+
+heta_status heta_feature_gather(const void *table, heta_dtype dt, int64_t ld_table, int32_t d,
+                                int64_t n_table_rows, const int64_t *gid, int64_t n, void *out,
+                                int64_t ld_out, void *hip_stream)
+{
+    if (!table || !gid || !out) return fail(HETA_ERR_INVALID_ARG, "heta_feature_gather: null argument");
+    if (!valid_dtype(dt)) return fail(HETA_ERR_INVALID_ARG, "heta_feature_gather: bad dtype");
+    if (d <= 0 || ld_table < d || ld_out < d || n < 0 || n_table_rows < 0)
+        return fail(HETA_ERR_SHAPE, "heta_feature_gather: bad shape");
+    if (n == 0) return HETA_OK;
+    const size_t esz = dtype_size(dt);
+    if ((reinterpret_cast<uintptr_t>(table) % esz) || (reinterpret_cast<uintptr_t>(out) % esz))
+        return fail(HETA_ERR_INVALID_ARG, "heta_feature_gather: pointer not aligned to its element size");
+    hipStream_t st = as_stream(hip_stream);
+    const size_t row_bytes = static_cast<size_t>(d) * esz;
+    const bool vec = aligned16(table) && aligned16(out) && (ld_table * esz) % 16 == 0 && (ld_out * esz) % 16 == 0 &&
+                     row_bytes % 16 == 0;
+    if (vec) {
+        const int per_row = static_cast<int>(row_bytes / 16);
+        const int64_t threads = n * per_row;
+        hipLaunchKernelGGL(gather_rows_kernel<uint4>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           static_cast<const uint4 *>(table), (int64_t)(ld_table * esz / 16), gid, n, per_row,
+                           static_cast<uint4 *>(out), (int64_t)(ld_out * esz / 16));
+    } else if (esz == 4) {
+        const int64_t threads = n * d;
+        hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           static_cast<const uint32_t *>(table), ld_table, gid, n, (int)d,
+                           static_cast<uint32_t *>(out), ld_out);
+    } else {
+        const int64_t threads = n * d;
+        hipLaunchKernelGGL(gather_rows_kernel<uint16_t>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           static_cast<const uint16_t *>(table), ld_table, gid, n, (int)d,
+                           static_cast<uint16_t *>(out), ld_out);
+    }
+    HETA_LAUNCH_CHECK("gather_rows_kernel");
+    return HETA_OK;
+}
+
+heta_status heta_check_ids(const int64_t *ids, int64_t n, int64_t limit, void *hip_stream)
+{
+    if (n < 0 || (n > 0 && !ids)) return fail(HETA_ERR_INVALID_ARG, "heta_check_ids: bad arguments");
+    if (n == 0) return HETA_OK;
+    hipStream_t st = as_stream(hip_stream);
+    int *flag = nullptr;
+    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&flag), sizeof(int)));
+    int h = 0;
+    hipError_t e = hipMemcpyAsync(flag, &h, sizeof(int), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(check_ids_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ids, n, limit, flag);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(&h, flag, sizeof(int), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(flag);
+    if (e != hipSuccess) return fail(HETA_ERR_DEVICE, "heta_check_ids: %s", hipGetErrorString(e));
+    if (h) return fail(HETA_ERR_INVALID_ARG, "heta_check_ids: an id lies outside [0, %lld)", (long long)limit);
+    return HETA_OK;
+}
+
+} // extern "C"

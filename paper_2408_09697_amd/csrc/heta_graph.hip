@@ -1,0 +1,334 @@
+// Graph ingest: validation, degrees, stable CSR -> CSC transpose, degree-sorted row schedules.
+//
+// A heterogeneous graph is handed over as its mono-relation subgraphs (Section 2.1 of the
+// paper), one CSR over destination rows per relation.  Everything index-shaped that the
+// aggregation kernels need later is derived here once, on the host, and kept on the device.
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+
+#include "heta_internal.h"
+
+namespace heta {
+
+static thread_local std::string g_last_error;
+
+void set_error(const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+}
+
+heta_status fail(heta_status st, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return st;
+}
+
+heta_status ensure_workspace(heta_graph *g, size_t bytes)
+{
+    if (bytes <= g->ws_bytes)
+        return HETA_OK;
+    if (g->d_ws) {
+        HETA_HIP(hipFree(g->d_ws)); // waits for everything that may still read the old buffer
+        g->d_ws = nullptr;
+        g->ws_bytes = 0;
+    }
+    size_t want = bytes + bytes / 4;
+    HETA_HIP(hipMalloc(&g->d_ws, want));
+    g->ws_bytes = want;
+    return HETA_OK;
+}
+
+template <typename T>
+static heta_status upload(T **dst, const T *src, size_t n)
+{
+    *dst = nullptr;
+    HETA_HIP(hipMalloc(reinterpret_cast<void **>(dst), std::max<size_t>(n, 1) * sizeof(T)));
+    if (n)
+        HETA_HIP(hipMemcpy(*dst, src, n * sizeof(T), hipMemcpyHostToDevice));
+    return HETA_OK;
+}
+
+// Builds the device-side schedule of one direction from its host pointer array.
+static heta_status build_schedule(Schedule &s, const int64_t *ptr, const int32_t *idx, int64_t n_rows,
+                                  int64_t n_edges)
+{
+    s.n_rows = n_rows;
+    s.n_edges = n_edges;
+    // counting sort of the rows by min(degree, kHubMinDeg), descending, stable
+    std::vector<int64_t> bucket(kHubMinDeg + 2, 0);
+    for (int64_t r = 0; r < n_rows; ++r) {
+        int64_t d = std::min<int64_t>(ptr[r + 1] - ptr[r], kHubMinDeg);
+        bucket[d] += 1;
+    }
+    // rows_with_deg_ge[k] = sum of bucket[j] for j >= k
+    int64_t run = 0;
+    for (int k = kHubMinDeg; k >= 0; --k) {
+        run += bucket[k];
+        s.rows_with_deg_ge[k] = run;
+    }
+    // start offset of bucket k in the descending order = number of rows with larger key
+    std::vector<int64_t> start(kHubMinDeg + 1);
+    for (int k = 0; k <= kHubMinDeg; ++k)
+        start[k] = (k == kHubMinDeg) ? 0 : s.rows_with_deg_ge[k + 1];
+    std::vector<int32_t> perm(std::max<int64_t>(n_rows, 1));
+    for (int64_t r = 0; r < n_rows; ++r) {
+        int64_t d = std::min<int64_t>(ptr[r + 1] - ptr[r], kHubMinDeg);
+        perm[start[d]++] = static_cast<int32_t>(r);
+    }
+    s.n_hub_rows = s.rows_with_deg_ge[kHubMinDeg];
+    std::vector<HubChunk> chunks;
+    std::vector<int64_t> chunk_ptr(s.n_hub_rows + 1, 0);
+    for (int64_t h = 0; h < s.n_hub_rows; ++h) {
+        int32_t r = perm[h];
+        for (int64_t e = ptr[r]; e < ptr[r + 1]; e += kHubChunk) {
+            HubChunk c;
+            c.e0 = e;
+            c.len = static_cast<int32_t>(std::min<int64_t>(kHubChunk, ptr[r + 1] - e));
+            c.slot = static_cast<int32_t>(chunks.size());
+            chunks.push_back(c);
+        }
+        chunk_ptr[h + 1] = static_cast<int64_t>(chunks.size());
+    }
+    if (chunks.size() >= (size_t(1) << 31))
+        return fail(HETA_ERR_UNSUPPORTED, "too many hub chunks (%zu)", chunks.size());
+    s.n_hub_chunks = static_cast<int64_t>(chunks.size());
+    heta_status st;
+    if ((st = upload(&s.d_ptr, ptr, n_rows + 1)) != HETA_OK) return st;
+    if ((st = upload(&s.d_idx, idx, n_edges)) != HETA_OK) return st;
+    if ((st = upload(&s.d_perm, perm.data(), n_rows)) != HETA_OK) return st;
+    if ((st = upload(&s.d_hub_chunks, chunks.data(), chunks.size())) != HETA_OK) return st;
+    if ((st = upload(&s.d_hub_chunk_ptr, chunk_ptr.data(), chunk_ptr.size())) != HETA_OK) return st;
+    return HETA_OK;
+}
+
+static void free_schedule(Schedule &s)
+{
+    (void)hipFree(s.d_ptr);
+    (void)hipFree(s.d_idx);
+    (void)hipFree(s.d_perm);
+    (void)hipFree(s.d_hub_chunks);
+    (void)hipFree(s.d_hub_chunk_ptr);
+    s = Schedule();
+}
+
+static void destroy(heta_graph *g)
+{
+    if (!g)
+        return;
+    (void)hipDeviceSynchronize();
+    for (auto &r : g->rels) {
+        free_schedule(r.csr);
+        free_schedule(r.csc);
+        (void)hipFree(r.d_inv_deg);
+    }
+    (void)hipFree(g->d_ws);
+    delete g;
+}
+
+// Host-only checks of one relation's arguments and CSR; touches no device.
+static heta_status validate_relation(const std::vector<heta_ntype> &ntypes, const heta_relation &in,
+                                     int32_t index, const int64_t *ptr, const int32_t *col)
+{
+    const int64_t n_dst = ntypes[in.dst_type].num_nodes, n_src = ntypes[in.src_type].num_nodes;
+    const int64_t E = in.num_edges;
+    if (ptr[0] != 0)
+        return fail(HETA_ERR_BAD_CSR, "relation %d: rowptr[0] = %lld, expected 0", index, (long long)ptr[0]);
+    for (int64_t v = 0; v < n_dst; ++v)
+        if (ptr[v + 1] < ptr[v])
+            return fail(HETA_ERR_BAD_CSR, "relation %d: rowptr decreases at row %lld", index, (long long)v);
+    if (ptr[n_dst] != E)
+        return fail(HETA_ERR_BAD_CSR, "relation %d: rowptr[n_dst] = %lld but num_edges = %lld", index,
+                    (long long)ptr[n_dst], (long long)E);
+    for (int64_t e = 0; e < E; ++e)
+        if (col[e] < 0 || col[e] >= n_src)
+            return fail(HETA_ERR_BAD_CSR, "relation %d: col[%lld] = %d outside [0, %lld)", index,
+                        (long long)e, col[e], (long long)n_src);
+    return HETA_OK;
+}
+
+static heta_status check_relation_args(const std::vector<heta_ntype> &ntypes, const heta_relation &in,
+                                       int32_t index)
+{
+    const int32_t n_nt = static_cast<int32_t>(ntypes.size());
+    if (in.src_type < 0 || in.src_type >= n_nt || in.dst_type < 0 || in.dst_type >= n_nt)
+        return fail(HETA_ERR_INVALID_ARG, "relation %d: node type out of range", index);
+    if (in.num_edges < 0)
+        return fail(HETA_ERR_INVALID_ARG, "relation %d: negative num_edges", index);
+    if (!in.csr_rowptr || (in.num_edges > 0 && !in.csr_col))
+        return fail(HETA_ERR_INVALID_ARG, "relation %d: null CSR pointer", index);
+    return HETA_OK;
+}
+
+static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32_t index, bool on_device)
+{
+    Relation rel;
+    rel.src_type = in.src_type;
+    rel.dst_type = in.dst_type;
+    rel.n_src = g->ntypes[in.src_type].num_nodes;
+    rel.n_dst = g->ntypes[in.dst_type].num_nodes;
+    rel.n_edges = in.num_edges;
+    const int64_t E = in.num_edges, n_dst = rel.n_dst, n_src = rel.n_src;
+
+    std::vector<int64_t> h_ptr;
+    std::vector<int32_t> h_col;
+    const int64_t *ptr = in.csr_rowptr;
+    const int32_t *col = in.csr_col;
+    if (on_device) {
+        h_ptr.resize(n_dst + 1);
+        h_col.resize(std::max<int64_t>(E, 1));
+        HETA_HIP(hipMemcpy(h_ptr.data(), in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+        if (E)
+            HETA_HIP(hipMemcpy(h_col.data(), in.csr_col, E * sizeof(int32_t), hipMemcpyDeviceToHost));
+        ptr = h_ptr.data();
+        col = h_col.data();
+        heta_status vst = validate_relation(g->ntypes, in, index, ptr, col);
+        if (vst != HETA_OK)
+            return vst;
+    }
+    // ---- degrees ----
+    rel.h_deg.resize(n_dst);
+    std::vector<float> inv_deg(std::max<int64_t>(n_dst, 1));
+    for (int64_t v = 0; v < n_dst; ++v) {
+        int64_t d = ptr[v + 1] - ptr[v];
+        rel.h_deg[v] = d;
+        inv_deg[v] = d > 0 ? 1.0f / static_cast<float>(d) : 0.0f;
+    }
+    // ---- stable transpose: column u keeps its edges in ascending original edge position ----
+    std::vector<int64_t> colptr(n_src + 1, 0);
+    for (int64_t e = 0; e < E; ++e)
+        colptr[col[e] + 1] += 1;
+    for (int64_t u = 0; u < n_src; ++u)
+        colptr[u + 1] += colptr[u];
+    std::vector<int32_t> row(std::max<int64_t>(E, 1));
+    {
+        std::vector<int64_t> cursor(colptr.begin(), colptr.end() - 1);
+        for (int64_t v = 0; v < n_dst; ++v)
+            for (int64_t e = ptr[v]; e < ptr[v + 1]; ++e)
+                row[cursor[col[e]]++] = static_cast<int32_t>(v);
+    }
+    heta_status st;
+    if ((st = build_schedule(rel.csr, ptr, col, n_dst, E)) != HETA_OK ||
+        (st = build_schedule(rel.csc, colptr.data(), row.data(), n_src, E)) != HETA_OK ||
+        (st = upload(&rel.d_inv_deg, inv_deg.data(), n_dst)) != HETA_OK) {
+        free_schedule(rel.csr);
+        free_schedule(rel.csc);
+        (void)hipFree(rel.d_inv_deg);
+        return st;
+    }
+    g->rels.push_back(std::move(rel));
+    return HETA_OK;
+}
+
+} // namespace heta
+
+using namespace heta;
+
+extern "C" {
+
+const char *heta_last_error(void) { return g_last_error.c_str(); }
+const char *heta_version(void) { return "0.1"; }
+
+heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels,
+                              int32_t n_rels, uint32_t flags, heta_graph **out)
+{
+    if (!out)
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_create: out is NULL");
+    if (!ntypes || n_ntypes <= 0)
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_create: need at least one node type");
+    if (n_rels < 0 || (n_rels > 0 && !rels))
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_create: bad relation array");
+    if (flags & ~HETA_PTRS_ON_DEVICE)
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_create: unknown flag bits 0x%x", flags);
+    for (int32_t t = 0; t < n_ntypes; ++t) {
+        if (ntypes[t].num_nodes < 0 || ntypes[t].num_nodes >= (int64_t(1) << 31))
+            return fail(HETA_ERR_INVALID_ARG, "node type %d: num_nodes %lld outside [0, 2^31)", t,
+                        (long long)ntypes[t].num_nodes);
+        if (ntypes[t].feat_dim < 0)
+            return fail(HETA_ERR_INVALID_ARG, "node type %d: negative feat_dim", t);
+    }
+    const bool on_device = (flags & HETA_PTRS_ON_DEVICE) != 0;
+    {
+        // everything that can be rejected on the host is rejected before the device is touched
+        std::vector<heta_ntype> nts(ntypes, ntypes + n_ntypes);
+        for (int32_t i = 0; i < n_rels; ++i) {
+            heta_status st = check_relation_args(nts, rels[i], i);
+            if (st == HETA_OK && !on_device)
+                st = validate_relation(nts, rels[i], i, rels[i].csr_rowptr, rels[i].csr_col);
+            if (st != HETA_OK)
+                return st;
+        }
+    }
+    heta_graph *g = new (std::nothrow) heta_graph();
+    if (!g)
+        return fail(HETA_ERR_OOM, "heta_graph_create: host allocation failed");
+    g->ntypes.assign(ntypes, ntypes + n_ntypes);
+    hipError_t e = hipGetDevice(&g->device);
+    if (e != hipSuccess) {
+        delete g;
+        return fail(HETA_ERR_DEVICE, "hipGetDevice failed: %s", hipGetErrorString(e));
+    }
+    try {
+        g->rels.reserve(n_rels);
+        for (int32_t i = 0; i < n_rels; ++i) {
+            heta_status st = ingest_relation(g, rels[i], i, on_device);
+            if (st != HETA_OK) {
+                destroy(g);
+                return st;
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        destroy(g);
+        return fail(HETA_ERR_OOM, "heta_graph_create: host allocation failed");
+    }
+    *out = g;
+    return HETA_OK;
+}
+
+heta_status heta_graph_destroy(heta_graph *g)
+{
+    destroy(g);
+    return HETA_OK;
+}
+
+heta_status heta_graph_get_csc(const heta_graph *g, int32_t rel, int64_t *colptr, int32_t *row)
+{
+    if (!g || !colptr || !row)
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_get_csc: null argument");
+    if (rel < 0 || rel >= (int32_t)g->rels.size())
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_get_csc: relation %d out of range", rel);
+    const Relation &r = g->rels[rel];
+    HETA_HIP(hipMemcpy(colptr, r.csc.d_ptr, (r.n_src + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (r.n_edges)
+        HETA_HIP(hipMemcpy(row, r.csc.d_idx, r.n_edges * sizeof(int32_t), hipMemcpyDeviceToHost));
+    return HETA_OK;
+}
+
+heta_status heta_graph_get_degrees(const heta_graph *g, int32_t rel, int64_t *in_deg)
+{
+    if (!g || !in_deg)
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_get_degrees: null argument");
+    if (rel < 0 || rel >= (int32_t)g->rels.size())
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_get_degrees: relation %d out of range", rel);
+    const Relation &r = g->rels[rel];
+    // degrees are recomputed from the device copy of rowptr so that the read-back covers it
+    std::vector<int64_t> ptr(r.n_dst + 1);
+    HETA_HIP(hipMemcpy(ptr.data(), r.csr.d_ptr, (r.n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    for (int64_t v = 0; v < r.n_dst; ++v)
+        in_deg[v] = ptr[v + 1] - ptr[v];
+    return HETA_OK;
+}
+
+} // extern "C"

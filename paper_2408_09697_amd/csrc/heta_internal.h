@@ -1,0 +1,90 @@
+// Internal declarations shared by the translation units of libheta (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "heta.h"
+
+namespace heta {
+
+// ---- error reporting ---------------------------------------------------------------------------
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+heta_status fail(heta_status st, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
+#define HETA_HIP(call)                                                                               \
+    do {                                                                                             \
+        hipError_t e_ = (call);                                                                      \
+        if (e_ != hipSuccess)                                                                        \
+            return ::heta::fail(e_ == hipErrorOutOfMemory ? HETA_ERR_OOM : HETA_ERR_DEVICE,         \
+                                "%s failed: %s", #call, hipGetErrorString(e_));                      \
+    } while (0)
+
+#define HETA_LAUNCH_CHECK(name)                                                                      \
+    do {                                                                                             \
+        hipError_t e_ = hipGetLastError();                                                           \
+        if (e_ != hipSuccess)                                                                        \
+            return ::heta::fail(HETA_ERR_DEVICE, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- row schedule of one direction of one relation ----------------------------------------------
+// Rows are the reduction's output rows: destinations for the CSR (forward), sources for the CSC
+// (backward).  `perm` lists the rows by descending degree (stable, so ascending row id within a
+// degree).  Rows of at least kHubMinDeg edges ("hub rows", the head of a power-law degree
+// distribution) come first in `perm`; each is cut into chunks of kHubChunk edges that separate
+// wavefronts reduce into partial rows of the workspace, and a second kernel adds a hub row's
+// partials in chunk order.
+constexpr int kHubMinDeg = 512;
+constexpr int kHubChunk = 256;
+constexpr int kDegHist = 513; // rows_with_deg_ge[k] for k in [0, 512]
+
+struct HubChunk {       // one wavefront's share of a hub row
+    int64_t e0;         // first edge
+    int32_t len;        // number of edges (<= kHubChunk)
+    int32_t slot;       // partial row in the workspace
+};
+
+struct Schedule {
+    int64_t n_rows = 0, n_edges = 0;
+    int64_t *d_ptr = nullptr;     // [n_rows + 1]
+    int32_t *d_idx = nullptr;     // [n_edges] neighbour ids
+    int32_t *d_perm = nullptr;    // [n_rows] rows by descending degree
+    int64_t n_hub_rows = 0;       // perm[0 .. n_hub_rows) are hub rows
+    int64_t n_hub_chunks = 0;
+    HubChunk *d_hub_chunks = nullptr;    // [n_hub_chunks], grouped by hub row in perm order
+    int64_t *d_hub_chunk_ptr = nullptr;  // [n_hub_rows + 1] chunk range of each hub row
+    int64_t rows_with_deg_ge[kDegHist];  // host: number of rows whose degree is >= k
+};
+
+struct Relation {
+    int32_t src_type = 0, dst_type = 0;
+    int64_t n_src = 0, n_dst = 0, n_edges = 0;
+    Schedule csr;                 // rows = destinations, idx = sources
+    Schedule csc;                 // rows = sources, idx = destinations
+    float *d_inv_deg = nullptr;   // [n_dst] 1/deg_r(v), 0 for zero-degree rows
+    std::vector<int64_t> h_deg;   // host copy of the in-degrees
+};
+
+} // namespace heta
+
+struct heta_graph {
+    int device = 0;
+    std::vector<heta_ntype> ntypes;
+    std::vector<heta::Relation> rels;
+    // workspace for hub-row partials and split weight-gradient partials; grown on demand
+    void *d_ws = nullptr;
+    size_t ws_bytes = 0;
+};
+
+namespace heta {
+// Makes sure g's workspace holds `bytes`; growing frees and reallocates (device synchronising).
+heta_status ensure_workspace(heta_graph *g, size_t bytes);
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t dtype_size(heta_dtype dt) { return dt == HETA_F32 ? 4 : 2; }
+inline bool valid_dtype(int dt) { return dt == HETA_F32 || dt == HETA_BF16; }
+} // namespace heta

@@ -1,0 +1,143 @@
+// Cross-relation aggregation AGG_all = sum (Eq. 1 of the paper, second line; Algorithm 1,
+// the designated worker's step) and the backward of its optional activation.  Pure streaming:
+// every element is read once per partial and written once, 128 bits per lane where the
+// layout allows.
+#include "heta_internal.h"
+
+namespace heta {
+
+constexpr int kMaxPartials = 16;
+
+struct ReduceParams {
+    const float *part[kMaxPartials];
+    int n_partials;
+    int64_t ld, ld_out;
+    int64_t n_rows;
+    int d;
+    int relu;
+    float *out;
+};
+
+template <int V> // V floats per thread (4: vector path, 1: scalar path)
+__global__ void __launch_bounds__(256) cross_rel_reduce_kernel(ReduceParams p)
+{
+    const int per_row = (p.d + V - 1) / V;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t i = t / per_row;
+    const int c = static_cast<int>(t % per_row) * V;
+    if (i >= p.n_rows) return;
+    if (V == 4) {
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < p.n_partials; ++k) {
+            const float4 v = *reinterpret_cast<const float4 *>(p.part[k] + i * p.ld + c);
+            a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+        }
+        if (p.relu) { a.x = fmaxf(a.x, 0.f); a.y = fmaxf(a.y, 0.f); a.z = fmaxf(a.z, 0.f); a.w = fmaxf(a.w, 0.f); }
+        *reinterpret_cast<float4 *>(p.out + i * p.ld_out + c) = a;
+    } else {
+        float a = 0.f;
+        for (int k = 0; k < p.n_partials; ++k) a += p.part[k][i * p.ld + c];
+        if (p.relu) a = fmaxf(a, 0.f);
+        p.out[i * p.ld_out + c] = a;
+    }
+}
+
+template <int V>
+__global__ void __launch_bounds__(256) act_bwd_kernel(int64_t n_rows, int d, int relu, const float *h, int64_t ld_h,
+                                                      const float *go, int64_t ld_go, float *gi, int64_t ld_gi)
+{
+    const int per_row = (d + V - 1) / V;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t i = t / per_row;
+    const int c = static_cast<int>(t % per_row) * V;
+    if (i >= n_rows) return;
+    if (V == 4) {
+        float4 g = *reinterpret_cast<const float4 *>(go + i * ld_go + c);
+        if (relu) {
+            const float4 x = *reinterpret_cast<const float4 *>(h + i * ld_h + c);
+            g.x = x.x > 0.f ? g.x : 0.f; g.y = x.y > 0.f ? g.y : 0.f;
+            g.z = x.z > 0.f ? g.z : 0.f; g.w = x.w > 0.f ? g.w : 0.f;
+        }
+        *reinterpret_cast<float4 *>(gi + i * ld_gi + c) = g;
+    } else {
+        float g = go[i * ld_go + c];
+        if (relu && !(h[i * ld_h + c] > 0.f)) g = 0.f;
+        gi[i * ld_gi + c] = g;
+    }
+}
+
+} // namespace heta
+
+using namespace heta;
+
+extern "C" {
+
+heta_status heta_cross_rel_reduce(const heta_graph *g, int32_t dst_type, const float *const *partials,
+                                  int32_t n_partials, int64_t ld, int32_t d_out, heta_act act,
+                                  float *out, int64_t ld_out, void *hip_stream)
+{
+    if (!g || !partials || !out) return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_reduce: null argument");
+    if (dst_type < 0 || dst_type >= (int32_t)g->ntypes.size())
+        return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_reduce: node type %d out of range", dst_type);
+    if (n_partials < 1 || n_partials > kMaxPartials)
+        return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_reduce: n_partials must be in [1, %d]", kMaxPartials);
+    if (act != HETA_ACT_NONE && act != HETA_ACT_RELU) return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_reduce: bad act");
+    if (d_out <= 0 || ld < d_out || ld_out < d_out) return fail(HETA_ERR_SHAPE, "heta_cross_rel_reduce: bad shape");
+    ReduceParams p{};
+    bool vec = (d_out % 4 == 0) && (ld % 4 == 0) && (ld_out % 4 == 0) && aligned16(out);
+    for (int k = 0; k < n_partials; ++k) {
+        if (!partials[k]) return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_reduce: partial %d is NULL", k);
+        if (reinterpret_cast<uintptr_t>(partials[k]) & 3u)
+            return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_reduce: partial %d not 4-byte aligned", k);
+        vec = vec && aligned16(partials[k]);
+        p.part[k] = partials[k];
+    }
+    if (reinterpret_cast<uintptr_t>(out) & 3u) return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_reduce: out not aligned");
+    p.n_partials = n_partials;
+    p.ld = ld;
+    p.ld_out = ld_out;
+    p.n_rows = g->ntypes[dst_type].num_nodes;
+    p.d = d_out;
+    p.relu = (act == HETA_ACT_RELU);
+    p.out = out;
+    if (p.n_rows == 0) return HETA_OK;
+    const int64_t threads = p.n_rows * (vec ? d_out / 4 : d_out);
+    const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "heta_cross_rel_reduce: too large");
+    if (vec)
+        hipLaunchKernelGGL(cross_rel_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), p);
+    else
+        hipLaunchKernelGGL(cross_rel_reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), p);
+    HETA_LAUNCH_CHECK("cross_rel_reduce_kernel");
+    return HETA_OK;
+}
+
+heta_status heta_act_bwd(int64_t n_rows, int32_t d, heta_act act, const float *h, int64_t ld_h,
+                         const float *grad_out, int64_t ld_go, float *grad_in, int64_t ld_gi, void *hip_stream)
+{
+    if (!grad_out || !grad_in || (act == HETA_ACT_RELU && !h))
+        return fail(HETA_ERR_INVALID_ARG, "heta_act_bwd: null argument");
+    if (act != HETA_ACT_NONE && act != HETA_ACT_RELU) return fail(HETA_ERR_INVALID_ARG, "heta_act_bwd: bad act");
+    if (n_rows < 0 || d <= 0 || ld_go < d || ld_gi < d || (act == HETA_ACT_RELU && ld_h < d))
+        return fail(HETA_ERR_SHAPE, "heta_act_bwd: bad shape");
+    if ((reinterpret_cast<uintptr_t>(grad_out) & 3u) || (reinterpret_cast<uintptr_t>(grad_in) & 3u) ||
+        (h && (reinterpret_cast<uintptr_t>(h) & 3u)))
+        return fail(HETA_ERR_INVALID_ARG, "heta_act_bwd: pointer not 4-byte aligned");
+    if (n_rows == 0) return HETA_OK;
+    const int relu = (act == HETA_ACT_RELU);
+    const bool vec = (d % 4 == 0) && (ld_go % 4 == 0) && (ld_gi % 4 == 0) && aligned16(grad_out) && aligned16(grad_in) &&
+                     (!relu || ((ld_h % 4 == 0) && aligned16(h)));
+    const int64_t threads = n_rows * (vec ? d / 4 : d);
+    const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "heta_act_bwd: too large");
+    if (vec)
+        hipLaunchKernelGGL(act_bwd_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), n_rows, (int)d,
+                           relu, h, ld_h, grad_out, ld_go, grad_in, ld_gi);
+    else
+        hipLaunchKernelGGL(act_bwd_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), n_rows, (int)d,
+                           relu, h, ld_h, grad_out, ld_go, grad_in, ld_gi);
+    HETA_LAUNCH_CHECK("act_bwd_kernel");
+    return HETA_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,136 @@
+"""Sequencing of the library calls for one RAF layer on one GPU (forward and backward).
+
+This module allocates device buffers with torch and issues the C-ABI calls in the order of
+Algorithm 1 of the paper, one worker's share: relation-specific aggregation and projection
+per relation, cross-relation sum per destination type, and the local backward.  It computes
+nothing itself.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+from . import binding as hb
+
+
+class RafLayer:
+    """Device-resident state of one layer over a `binding.Graph`.
+
+    tables[t]   : device [N_t, d_t] (fp32 or bf16), or None for types that are never a source
+    W[r]        : device [d_r, d_out] in the storage dtype
+    pre_proj[t] : optional fixed fp32 [d_t, d_shared] map applied to every table first
+    src_gid[t]  : optional int64 map local source id -> table row (sampled blocks)
+    """
+
+    def __init__(self, graph: hb.Graph, op: int, tables: Sequence[Optional[torch.Tensor]],
+                 W: Sequence[torch.Tensor], d_out: int, pre_proj: Optional[Sequence[torch.Tensor]] = None,
+                 src_gid: Optional[Sequence[Optional[torch.Tensor]]] = None, relu: bool = False,
+                 m_dtype: Optional[torch.dtype] = None, rels: Optional[Sequence[int]] = None):
+        self.g = graph
+        self.op = op
+        self.tables = list(tables)
+        self.W = list(W)
+        self.d_out = d_out
+        self.pre_proj = None if pre_proj is None else list(pre_proj)
+        self.src_gid = None if src_gid is None else list(src_gid)
+        self.relu = relu
+        self.rels = list(range(len(graph.rels))) if rels is None else list(rels)
+        dev = self.W[0].device
+        self.dev = dev
+        n_types = len(graph.ntypes)
+        self.rels_into: Dict[int, List[int]] = {}
+        self.rels_from: Dict[int, List[int]] = {}
+        for r in self.rels:
+            s, t, _ = graph.rels[r]
+            self.rels_into.setdefault(t, []).append(r)
+            self.rels_from.setdefault(s, []).append(r)
+        # width the aggregation of relation r runs at
+        self.d_rel = {r: self.W[r].shape[0] for r in self.rels}
+        if m_dtype is None:
+            m_dtype = torch.bfloat16 if self.W[self.rels[0]].dtype == torch.bfloat16 else torch.float32
+        self.m_dtype = m_dtype
+        # H0 buffers only when a fixed per-type map produces them
+        self.H0: List[Optional[torch.Tensor]] = [None] * n_types
+        if self.pre_proj is not None:
+            for t in range(n_types):
+                if self.tables[t] is not None:
+                    self.H0[t] = torch.empty((self.tables[t].shape[0], self.pre_proj[t].shape[1]),
+                                             dtype=torch.float32, device=dev)
+        self.M = {r: torch.empty((graph.n_dst(r), self.d_rel[r]), dtype=m_dtype, device=dev) for r in self.rels}
+        self.H = {t: torch.empty((graph.ntypes[t][0], d_out), dtype=torch.float32, device=dev)
+                  for t in self.rels_into}
+        self.dW = {r: torch.empty((self.d_rel[r], d_out), dtype=torch.float32, device=dev) for r in self.rels}
+        self.dH0 = {s: torch.empty((graph.ntypes[s][0], self.d_rel[rs[0]]), dtype=torch.float32, device=dev)
+                    for s, rs in self.rels_from.items()}
+        self.dtable: Dict[int, torch.Tensor] = {}
+        if self.pre_proj is not None:
+            for s in self.rels_from:
+                self.dtable[s] = torch.empty((self.tables[s].shape[0], self.pre_proj[s].shape[0]),
+                                             dtype=torch.float32, device=dev)
+        max_rows = max(graph.n_dst(r) for r in self.rels)
+        max_d = max(self.d_rel.values())
+        self._dM = torch.empty((max_rows, max_d), dtype=torch.float32, device=dev)
+        self._Gact = ({t: torch.empty_like(h) for t, h in self.H.items()} if relu else {})
+
+    # ---- forward: aggregate -> project (accumulating over the relations into a type) --------------
+    def source(self, s: int) -> torch.Tensor:
+        return self.H0[s] if self.pre_proj is not None else self.tables[s]
+
+    def forward(self, stream=None) -> Dict[int, torch.Tensor]:
+        if self.pre_proj is not None:
+            for t, h0 in enumerate(self.H0):
+                if h0 is not None:
+                    hb.heta_project(self.tables[t], self.pre_proj[t], h0, stream=stream)
+        for t, rs in self.rels_into.items():
+            for k, r in enumerate(rs):
+                s = self.g.rels[r][0]
+                gid = None if self.src_gid is None else self.src_gid[s]
+                hb.heta_rel_aggregate_fwd(self.g, r, self.op, self.source(s), self.M[r], d=self.d_rel[r],
+                                          src_gid=gid, stream=stream)
+                hb.heta_rel_project(self.g, r, self.M[r], self.W[r], self.H[t], beta=0.0 if k == 0 else 1.0,
+                                    stream=stream)
+            if self.relu:
+                hb.heta_cross_rel_reduce(self.g, t, [self.H[t]], self.H[t], act=hb.HETA_ACT_RELU, stream=stream)
+        return self.H
+
+    def forward_unfused(self, stream=None) -> Dict[int, torch.Tensor]:
+        """Same result through explicit per-relation partials Z_r and heta_cross_rel_reduce."""
+        if self.pre_proj is not None:
+            for t, h0 in enumerate(self.H0):
+                if h0 is not None:
+                    hb.heta_project(self.tables[t], self.pre_proj[t], h0, stream=stream)
+        for t, rs in self.rels_into.items():
+            Z = []
+            for r in rs:
+                s = self.g.rels[r][0]
+                gid = None if self.src_gid is None else self.src_gid[s]
+                hb.heta_rel_aggregate_fwd(self.g, r, self.op, self.source(s), self.M[r], d=self.d_rel[r],
+                                          src_gid=gid, stream=stream)
+                z = torch.empty_like(self.H[t])
+                hb.heta_rel_project(self.g, r, self.M[r], self.W[r], z, stream=stream)
+                Z.append(z)
+            hb.heta_cross_rel_reduce(self.g, t, Z, self.H[t],
+                                     act=hb.HETA_ACT_RELU if self.relu else hb.HETA_ACT_NONE, stream=stream)
+        return self.H
+
+    # ---- backward: dZ = G; dW = M^T dZ; dM = dZ W^T; dH0 += CSC gather of dM ---------------------------
+    def backward(self, G: Dict[int, torch.Tensor], stream=None):
+        first_for_src = {s: True for s in self.rels_from}
+        for t, rs in self.rels_into.items():
+            g = G[t]
+            if self.relu:
+                g = hb.heta_act_bwd(hb.HETA_ACT_RELU, self.H[t], G[t], self._Gact[t], stream=stream)
+            for r in rs:
+                s = self.g.rels[r][0]
+                n, d = self.g.n_dst(r), self.d_rel[r]
+                dM = self._dM[:n, :d]
+                hb.heta_rel_project_wgrad(self.g, r, self.M[r], g, self.dW[r], stream=stream)
+                hb.heta_rel_project(self.g, r, g, self.W[r], dM, trans_w=True, stream=stream)
+                hb.heta_rel_aggregate_bwd(self.g, r, self.op, dM, self.dH0[s],
+                                          beta=0.0 if first_for_src[s] else 1.0, stream=stream)
+                first_for_src[s] = False
+        if self.pre_proj is not None:
+            for s, gh in self.dH0.items():
+                hb.heta_project(gh, self.pre_proj[s], self.dtable[s], trans_w=True, stream=stream)
+        return self.dW, self.dH0, (self.dtable if self.pre_proj is not None else self.dH0)

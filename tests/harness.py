@@ -1,0 +1,94 @@
+"""Shared helpers of the GPU parity tests: upload a gen.LayerProblem, run it through the
+C-ABI binding, and compare with the oracle's fp64 results row by row."""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+import paper_2408_09697_amd as heta
+from gen import rng
+
+
+def dev_table(x: np.ndarray, storage: str, pad_to: int = 1) -> torch.Tensor:
+    """Uploads a float32 host table as fp32 or bf16; `pad_to` pads the leading dimension (in
+    elements) so that rows start on 16-byte boundaries; the returned tensor is the [:, :d] view."""
+    n, d = x.shape
+    ld = (d + pad_to - 1) // pad_to * pad_to
+    if storage == "bf16":
+        bits = rng.f32_to_bf16_bits(x)
+        buf = torch.zeros((n, ld), dtype=torch.bfloat16, device="cuda")
+        buf[:, :d] = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        buf = torch.zeros((n, ld), dtype=torch.float32, device="cuda")
+        buf[:, :d] = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+    return buf[:, :d]
+
+
+def make_graph(p) -> heta.Graph:
+    nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in p.graph.ntypes]
+    rels = [(r.src_type, r.dst_type, r.rowptr, r.col) for r in p.graph.relations]
+    return heta.heta_graph_create(nts, rels)
+
+
+def make_layer(p, graph: Optional[heta.Graph] = None, rels=None) -> heta.RafLayer:
+    graph = make_graph(p) if graph is None else graph
+    pad = 8 if p.storage == "bf16" else 4
+    tables = [dev_table(t, p.storage, pad) for t in p.tables]
+    W = [dev_table(w, p.storage, pad) for w in p.W]
+    P = None if p.pre_proj is None else [dev_table(m, "f32", 4) for m in p.pre_proj]
+    gid = None
+    if p.src_gid is not None:
+        gid = [None if g is None else torch.from_numpy(np.ascontiguousarray(g, dtype=np.int64)).cuda()
+               for g in p.src_gid]
+    op = heta.HETA_MEAN if p.op == "mean" else heta.HETA_SUM
+    return heta.RafLayer(graph, op, tables, W, p.d_out, pre_proj=P, src_gid=gid, relu=p.relu, rels=rels)
+
+
+def run_layer_on_gpu(p, unfused: bool = False) -> Dict[str, dict]:
+    layer = make_layer(p)
+    H = layer.forward_unfused() if unfused else layer.forward()
+    G = {t: torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).cuda() for t, g in p.G.items()}
+    dW, dH0, dT = layer.backward(G)
+    torch.cuda.synchronize()
+    f = lambda x: x.float().cpu().numpy()
+    out = {"H": {t: f(h) for t, h in H.items()}, "M": {r: f(m) for r, m in layer.M.items()},
+           "dW": {r: f(w) for r, w in dW.items()}, "dH0": {s: f(x) for s, x in dH0.items()},
+           "dT": {s: f(x) for s, x in dT.items()}}
+    layer.g.destroy()
+    return out
+
+
+def row_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max over rows i of max_j |got_ij - ref_ij| / max(1, max_j |ref_ij|)."""
+    if ref.size == 0:
+        return 0.0
+    diff = np.abs(got.astype(np.float64) - ref).max(axis=1)
+    scale = np.maximum(1.0, np.abs(ref).max(axis=1))
+    return float((diff / scale).max())
+
+
+def assert_rows_close(got, ref, tol, what=""):
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    e = row_err(got, ref)
+    assert e <= tol, f"{what}: scaled row error {e:.3e} > {tol:.1e}"
+
+
+def compare_layer(p, got, ref_f, ref_b, tol: float, tol_m: Optional[float] = None):
+    """Forward embeddings, saved aggregations and all three gradient families against the oracle."""
+    tol_m = tol if tol_m is None else tol_m
+    dW, dH0, dT = ref_b
+    assert set(got["H"]) == set(ref_f.H)
+    for t, h in ref_f.H.items():
+        assert_rows_close(got["H"][t], h, tol, f"H[{t}]")
+    for r, m in ref_f.M.items():
+        assert_rows_close(got["M"][r], m, tol_m, f"M[{r}]")
+    for r, w in dW.items():
+        assert_rows_close(got["dW"][r], w, tol, f"dW[{r}]")
+    assert set(got["dH0"]) == set(dH0)
+    for s, x in dH0.items():
+        assert_rows_close(got["dH0"][s], x, tol, f"dH0[{s}]")
+    for s, x in dT.items():
+        assert_rows_close(got["dT"][s], x, tol, f"dtable[{s}]")

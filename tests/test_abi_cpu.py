@@ -1,0 +1,99 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and rejects bad arguments on the host before any device call."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2408_09697_amd as heta
+from paper_2408_09697_amd import binding as hb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "heta.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(heta_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = hb.load_library()
+    names = declared_symbols()
+    assert len(names) >= 15
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in heta.h but not exported"
+    assert sorted(hb.EXPORTS) == names
+    assert heta.heta_version() == "0.1"
+
+
+def test_binding_has_the_same_names():
+    for n in declared_symbols():
+        assert callable(getattr(heta, n)), n
+
+
+NT = [(4, 8, 0), (3, 8, 1)]
+
+
+def _create(rels, nts=NT):
+    return heta.heta_graph_create(nts, rels)
+
+
+@pytest.mark.parametrize("rowptr,col,status,needle", [
+    ([1, 1, 2, 2], [0, 1], hb.HETA_ERR_BAD_CSR, "rowptr[0]"),
+    ([0, 2, 1, 2], [0, 1], hb.HETA_ERR_BAD_CSR, "decreases"),
+    ([0, 1, 1, 3], [0, 1], hb.HETA_ERR_BAD_CSR, "num_edges"),
+    ([0, 1, 2, 2], [0, 4], hb.HETA_ERR_BAD_CSR, "outside"),
+    ([0, 1, 2, 2], [-1, 0], hb.HETA_ERR_BAD_CSR, "outside"),
+])
+def test_malformed_csr_is_rejected_on_the_host(rowptr, col, status, needle):
+    # relation from type 0 (4 nodes) into type 1 (3 nodes)
+    with pytest.raises(heta.HetaError) as ei:
+        _create([(0, 1, np.array(rowptr, dtype=np.int64), np.array(col, dtype=np.int32))])
+    assert ei.value.status == status
+    assert needle in ei.value.message
+
+
+def test_bad_node_types_and_counts():
+    rp, col = np.array([0, 0, 0, 0], dtype=np.int64), np.zeros(0, dtype=np.int32)
+    with pytest.raises(heta.HetaError) as ei:
+        _create([(0, 2, rp, col)])
+    assert ei.value.status == hb.HETA_ERR_INVALID_ARG
+    with pytest.raises(heta.HetaError) as ei:
+        _create([(0, 1, rp, col)], nts=[(-1, 8, 0), (3, 8, 0)])
+    assert ei.value.status == hb.HETA_ERR_INVALID_ARG
+    with pytest.raises(heta.HetaError) as ei:
+        _create([(0, 1, rp, col)], nts=[(1 << 31, 8, 0), (3, 8, 0)])
+    assert ei.value.status == hb.HETA_ERR_INVALID_ARG
+    with pytest.raises(heta.HetaError) as ei:
+        heta.heta_graph_create([], [])
+    assert ei.value.status == hb.HETA_ERR_INVALID_ARG
+    with pytest.raises(heta.HetaError) as ei:
+        heta.heta_graph_create(NT, [(0, 1, rp, col)], flags=8)
+    assert ei.value.status == hb.HETA_ERR_INVALID_ARG
+
+
+def test_null_handle_calls_fail_cleanly():
+    lib = hb.load_library()
+    assert lib.heta_graph_destroy(None) == hb.HETA_OK
+    assert lib.heta_graph_get_csc(None, 0, None, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_graph_get_degrees(None, 0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_rel_aggregate_fwd(None, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_rel_aggregate_bwd(None, 0, 0, None, 0, 0, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_project(0, None, 0, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_rel_project(None, 0, None, 0, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_rel_project_wgrad(None, 0, None, 0, 0, 0, None, 0, 0, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_cross_rel_reduce(None, 0, None, 0, 0, 0, 0, None, 0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_act_bwd(0, 0, 0, None, 0, None, 0, None, 0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_feature_gather(None, 0, 0, 0, 0, None, 0, None, 0, None) == hb.HETA_ERR_INVALID_ARG
+    assert b"null" in lib.heta_last_error().lower()
+
+
+def test_project_shape_checks_happen_before_any_launch():
+    lib = hb.load_library()
+    one = 16  # fake, 4-byte aligned non-null addresses: rejected before they are ever dereferenced
+    assert lib.heta_project(4, one, 0, 2, 8, one, 0, 8, 8, 0, None, one, 8, 0.0, None) == hb.HETA_ERR_SHAPE   # ld_in < d_in
+    assert lib.heta_project(4, one, 7, 8, 8, one, 0, 8, 8, 0, None, one, 8, 0.0, None) == hb.HETA_ERR_INVALID_ARG  # dtype
+    assert lib.heta_project(4, one + 2, 0, 8, 8, one, 0, 8, 8, 0, None, one, 8, 0.0, None) == hb.HETA_ERR_INVALID_ARG  # align
+    assert lib.heta_act_bwd(4, 8, 5, one, 8, one, 8, one, 8, None) == hb.HETA_ERR_INVALID_ARG

@@ -1,0 +1,391 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Index work (CSC, degrees, gathers, integer-valued sums) must match bit for bit; floating point
+must satisfy  max_j |got_ij - ref_ij| <= tol * max(1, max_j |ref_ij|)  for every row i, with
+tol = 1e-4 for fp32 storage and 2e-2 for bf16 storage (fp32 accumulation in both).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2408_09697_amd as heta
+from gen import rng, workloads
+from gen.graphs import HetGraph, NodeType, Relation, power_law_degrees
+from tests.harness import (assert_rows_close, compare_layer, dev_table, make_graph, make_layer,
+                           run_layer_on_gpu)
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def skewed_relation(n_src=3000, n_dst=2000, n_edges=60000, name="skew"):
+    """Power-law in-degrees plus hand-placed rows around every scheduling threshold: empty rows,
+    rows of 1, 7, 8, 9, 127, 128, 129, 511, 512, 513 edges, and one 3000-edge hub."""
+    g = rng.stream("tests", name)
+    deg = power_law_degrees(n_dst, n_edges, 2.0, g)
+    for row, k in zip(range(3, 40, 3), [0, 1, 7, 8, 9, 127, 128, 129, 511, 512, 513, 3000, 0]):
+        deg[row] = k
+    rowptr = np.zeros(n_dst + 1, dtype=np.int64)
+    np.cumsum(deg, out=rowptr[1:])
+    col = g.integers(0, n_src, size=int(rowptr[-1]), dtype=np.int32)
+    col[:50] = 0                       # a popular source as well: a hub column for the backward
+    return Relation(name, 0, 1, rowptr, col)
+
+
+def one_relation_graph(rel, n_src, n_dst):
+    g = HetGraph([NodeType("s", n_src, 8, False), NodeType("t", n_dst, 8, False)], [rel])
+    nts = [(n_src, 8, 0), (n_dst, 8, 0)]
+    return g, heta.heta_graph_create(nts, [(0, 1, rel.rowptr, rel.col)])
+
+
+@pytest.fixture(scope="module")
+def skew():
+    rel = skewed_relation()
+    g, hg = one_relation_graph(rel, 3000, 2000)
+    yield rel, hg
+    hg.destroy()
+
+
+# ---- a1: ingest ---------------------------------------------------------------------------------
+
+def test_ingest_csc_and_degrees_bit_exact(skew):
+    rel, hg = skew
+    src, dst = rel.edge_list()
+    colptr, row = heta.heta_graph_get_csc(hg, 0)
+    ref_colptr, ref_row = oracle.csc(src, dst, 3000)
+    assert np.array_equal(colptr, ref_colptr) and np.array_equal(row, ref_row)
+    assert np.array_equal(heta.heta_graph_get_degrees(hg, 0), oracle.in_degree(src, dst, 2000))
+
+
+def test_ingest_config1_and_device_pointers():
+    p = workloads.config1()
+    nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in p.graph.ntypes]
+    rels = [(r.src_type, r.dst_type, torch.from_numpy(r.rowptr).cuda(), torch.from_numpy(r.col).cuda())
+            for r in p.graph.relations]
+    hg = heta.heta_graph_create(nts, rels, flags=heta.HETA_PTRS_ON_DEVICE)
+    for i, r in enumerate(p.graph.relations):
+        src, dst = r.edge_list()
+        n_s, n_t = p.graph.ntypes[r.src_type].num_nodes, p.graph.ntypes[r.dst_type].num_nodes
+        colptr, row = heta.heta_graph_get_csc(hg, i)
+        rc, rr = oracle.csc(src, dst, n_s)
+        assert np.array_equal(colptr, rc) and np.array_equal(row, rr)
+        assert np.array_equal(heta.heta_graph_get_degrees(hg, i), oracle.in_degree(src, dst, n_t))
+    hg.destroy()
+    # a bad CSR that lives on the device is rejected after the copy-back, nothing is leaked or launched
+    bad = [(0, 0, torch.tensor([0, 2, 1] + [1] * 1998, dtype=torch.int64).cuda(), torch.zeros(1, dtype=torch.int32).cuda())]
+    with pytest.raises(heta.HetaError) as ei:
+        heta.heta_graph_create(nts, bad, flags=heta.HETA_PTRS_ON_DEVICE)
+    assert ei.value.status == heta.HETA_ERR_BAD_CSR
+
+
+# ---- a2: heterogeneous gather ----------------------------------------------------------------------
+
+@pytest.mark.parametrize("d,storage,pad", [(128, "f32", 4), (7, "bf16", 8), (7, "bf16", 1), (300, "f32", 1), (789, "bf16", 8)])
+def test_feature_gather_bit_exact(d, storage, pad):
+    x = rng.normal_table(5000, d, "tests", f"gather{d}")
+    tab = dev_table(x, storage, pad)
+    gid = rng.stream("tests", "gid").integers(0, 5000, size=1234)
+    out = torch.zeros((1234, d), dtype=tab.dtype, device="cuda")
+    heta.heta_feature_gather(tab, torch.from_numpy(gid).cuda(), out)
+    heta.heta_check_ids(torch.from_numpy(gid).cuda(), 5000)
+    ref = (rng.round_to_bf16(x) if storage == "bf16" else x)[gid]
+    assert np.array_equal(out.float().cpu().numpy(), ref)
+    with pytest.raises(heta.HetaError):
+        heta.heta_check_ids(torch.tensor([0, 5000], dtype=torch.int64).cuda(), 5000)
+
+
+# ---- a3: forward aggregation -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("op", ["sum", "mean"])
+@pytest.mark.parametrize("d,storage,pad", [
+    (1, "f32", 4), (4, "f32", 4), (7, "f32", 4), (32, "f32", 4), (100, "f32", 4), (128, "f32", 4), (300, "f32", 4),
+    (520, "f32", 4), (1024, "f32", 4),
+    (7, "bf16", 8), (24, "bf16", 8), (64, "bf16", 8), (128, "bf16", 8), (300, "bf16", 8), (512, "bf16", 8),
+    (768, "bf16", 8), (789, "bf16", 8), (1100, "bf16", 8),
+    (7, "f32", 1), (789, "bf16", 1), (33, "bf16", 1),       # unpadded rows: element-wise kernels
+])
+def test_aggregate_fwd(skew, op, d, storage, pad):
+    rel, hg = skew
+    src, dst = rel.edge_list()
+    x = rng.normal_table(3000, d, "tests", f"x{d}")
+    if storage == "bf16":
+        x = rng.round_to_bf16(x)
+    tab = dev_table(x, storage, pad)
+    out = torch.full((2000, d), float("nan"), dtype=torch.float32, device="cuda")
+    heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_MEAN if op == "mean" else heta.HETA_SUM, tab, out)
+    ref = oracle.aggregate_fwd(src, dst, 2000, x, op)
+    assert_rows_close(out.cpu().numpy(), ref, 1e-4, f"M d={d} {storage}")
+    deg = np.diff(rel.rowptr)
+    assert not out.cpu().numpy()[deg == 0].any()           # empty rows are exactly zero
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_aggregate_fwd_with_gid_and_bf16_output(skew, storage):
+    rel, hg = skew
+    src, dst = rel.edge_list()
+    d = 128
+    x = rng.normal_table(10000, d, "tests", "bigtable")
+    if storage == "bf16":
+        x = rng.round_to_bf16(x)
+    gid = rng.stream("tests", "gid2").permutation(10000)[:3000].astype(np.int64)
+    tab = dev_table(x, storage, 8)
+    ref = oracle.aggregate_fwd(src, dst, 2000, x, "mean", gid=gid)
+    out = torch.zeros((2000, d), dtype=torch.float32, device="cuda")
+    heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_MEAN, tab, out, src_gid=torch.from_numpy(gid).cuda())
+    assert_rows_close(out.cpu().numpy(), ref, 1e-4, "gid fp32 out")
+    # strided bf16 output (a column slice of a wider buffer), as used to feed the bf16 projection
+    wide = torch.zeros((2000, 3 * d), dtype=torch.bfloat16, device="cuda")
+    heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_MEAN, tab, wide[:, d:2 * d], src_gid=torch.from_numpy(gid).cuda())
+    w = wide.float().cpu().numpy()
+    assert_rows_close(w[:, d:2 * d], ref, 2e-2, "gid bf16 out")
+    assert not w[:, :d].any() and not w[:, 2 * d:].any()
+
+
+def test_aggregate_integer_inputs_bit_exact(skew):
+    """Small-integer features: every partial sum is exact in fp32, so any summation order must
+    reproduce the oracle's bits (pins binning, hub splitting and the index paths)."""
+    rel, hg = skew
+    src, dst = rel.edge_list()
+    for d, storage in [(128, "f32"), (128, "bf16"), (7, "bf16"), (768, "bf16"), (300, "f32")]:
+        x = rng.small_int_table(3000, d, -2, 2, "tests", f"int{d}")
+        tab = dev_table(x, storage, 8)
+        out = torch.zeros((2000, d), dtype=torch.float32, device="cuda")
+        heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_SUM, tab, out)
+        assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.aggregate_fwd(src, dst, 2000, x, "sum"))
+        g = rng.small_int_table(2000, d, -2, 2, "tests", f"intg{d}")
+        gs = torch.zeros((3000, d), dtype=torch.float32, device="cuda")
+        heta.heta_rel_aggregate_bwd(hg, 0, heta.HETA_SUM, dev_table(g, "f32", 4), gs)
+        assert np.array_equal(gs.cpu().numpy().astype(np.float64),
+                              oracle.aggregate_bwd(src, dst, 3000, 2000, g.astype(np.float64), "sum"))
+    # one-hot rows count every gathered index
+    d = 16
+    e = np.zeros((3000, d), dtype=np.float32)
+    e[np.arange(3000), np.arange(3000) % d] = 1.0
+    out = torch.zeros((2000, d), dtype=torch.float32, device="cuda")
+    heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_SUM, dev_table(e, "f32", 4), out)
+    cnt = np.zeros((2000, d))
+    np.add.at(cnt, (dst, src % d), 1.0)
+    assert np.array_equal(out.cpu().numpy(), cnt)
+
+
+# ---- a7: backward aggregation over the CSC -----------------------------------------------------------
+
+@pytest.mark.parametrize("op", ["sum", "mean"])
+@pytest.mark.parametrize("d,pad", [(1, 4), (7, 4), (32, 4), (128, 4), (300, 4), (768, 4), (1024, 4), (33, 1)])
+def test_aggregate_bwd(skew, op, d, pad):
+    rel, hg = skew
+    src, dst = rel.edge_list()
+    gm = rng.normal_table(2000, d, "tests", f"gm{d}")
+    ref = oracle.aggregate_bwd(src, dst, 3000, 2000, gm.astype(np.float64), op)
+    out = torch.full((3000, d), float("nan"), dtype=torch.float32, device="cuda")
+    hop = heta.HETA_MEAN if op == "mean" else heta.HETA_SUM
+    heta.heta_rel_aggregate_bwd(hg, 0, hop, dev_table(gm, "f32", pad), out, beta=0.0)
+    assert_rows_close(out.cpu().numpy(), ref, 1e-4, f"dH0 d={d}")
+    # beta = 1 accumulates on top
+    heta.heta_rel_aggregate_bwd(hg, 0, hop, dev_table(gm, "f32", pad), out, beta=1.0)
+    assert_rows_close(out.cpu().numpy(), 2 * ref, 1e-4, f"dH0 accumulate d={d}")
+
+
+def test_adjoint_identity_on_gpu_outputs(skew):
+    rel, hg = skew
+    d = 64
+    x = rng.normal_table(3000, d, "tests", "adjx")
+    gm = rng.normal_table(2000, d, "tests", "adjg")
+    for hop in (heta.HETA_SUM, heta.HETA_MEAN):
+        fwd = torch.zeros((2000, d), dtype=torch.float32, device="cuda")
+        bwd = torch.zeros((3000, d), dtype=torch.float32, device="cuda")
+        heta.heta_rel_aggregate_fwd(hg, 0, hop, dev_table(x, "f32", 4), fwd)
+        heta.heta_rel_aggregate_bwd(hg, 0, hop, dev_table(gm, "f32", 4), bwd)
+        lhs = np.vdot(gm.astype(np.float64), fwd.cpu().numpy().astype(np.float64))
+        rhs = np.vdot(x.astype(np.float64), bwd.cpu().numpy().astype(np.float64))
+        assert abs(lhs - rhs) <= 1e-5 * max(1.0, abs(lhs))
+
+
+def test_million_edge_hub_row_and_empty_relation():
+    n_src, n_dst = 5000, 70
+    deg = np.zeros(n_dst, dtype=np.int64)
+    deg[5] = 1 << 20
+    deg[6] = 3
+    rowptr = np.zeros(n_dst + 1, dtype=np.int64)
+    np.cumsum(deg, out=rowptr[1:])
+    col = rng.stream("tests", "hub").integers(0, n_src, size=int(rowptr[-1]), dtype=np.int32)
+    rel = Relation("hub", 0, 1, rowptr, col)
+    empty = Relation("empty", 0, 1, np.zeros(n_dst + 1, dtype=np.int64), np.zeros(0, dtype=np.int32))
+    hg = heta.heta_graph_create([(n_src, 8, 0), (n_dst, 8, 0)],
+                                [(0, 1, rel.rowptr, rel.col), (0, 1, empty.rowptr, empty.col)])
+    src, dst = rel.edge_list()
+    d = 24
+    x = rng.small_int_table(n_src, d, -2, 2, "tests", "hubx")
+    out = torch.full((n_dst, d), float("nan"), dtype=torch.float32, device="cuda")
+    heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_SUM, dev_table(x, "bf16", 8), out)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.aggregate_fwd(src, dst, n_dst, x, "sum"))
+    g = rng.normal_table(n_dst, d, "tests", "hubg")
+    gs = torch.zeros((n_src, d), dtype=torch.float32, device="cuda")
+    heta.heta_rel_aggregate_bwd(hg, 0, heta.HETA_MEAN, dev_table(g, "f32", 4), gs)
+    assert_rows_close(gs.cpu().numpy(), oracle.aggregate_bwd(src, dst, n_src, n_dst, g.astype(np.float64), "mean"), 1e-4)
+    # the empty relation: forward gives zeros, backward with beta = 1 leaves the buffer alone
+    heta.heta_rel_aggregate_fwd(hg, 1, heta.HETA_MEAN, dev_table(x, "bf16", 8), out)
+    assert not out.cpu().numpy().any()
+    before = gs.clone()
+    heta.heta_rel_aggregate_bwd(hg, 1, heta.HETA_MEAN, dev_table(g, "f32", 4), gs, beta=1.0)
+    assert torch.equal(before, gs)
+    heta.heta_rel_aggregate_bwd(hg, 1, heta.HETA_MEAN, dev_table(g, "f32", 4), gs, beta=0.0)
+    assert not gs.cpu().numpy().any()
+    hg.destroy()
+
+
+def test_zero_destination_relation_is_a_noop():
+    hg = heta.heta_graph_create([(10, 8, 0), (0, 8, 0)], [(0, 1, np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32))])
+    x = dev_table(np.ones((10, 8), dtype=np.float32), "f32", 4)
+    out = torch.zeros((1, 8), dtype=torch.float32, device="cuda")
+    heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_MEAN, x, out)
+    gs = torch.ones((10, 8), dtype=torch.float32, device="cuda")
+    heta.heta_rel_aggregate_bwd(hg, 0, heta.HETA_MEAN, out, gs, beta=0.0)
+    assert not gs.cpu().numpy().any()
+    hg.destroy()
+
+
+def test_run_to_run_bitwise_determinism(skew):
+    rel, hg = skew
+    x = dev_table(rng.normal_table(3000, 128, "tests", "detx"), "f32", 4)
+    outs = []
+    for _ in range(3):
+        o = torch.zeros((2000, 128), dtype=torch.float32, device="cuda")
+        heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_MEAN, x, o)
+        outs.append(o)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+# ---- a4 / a6: projection ------------------------------------------------------------------------------
+
+PROJ_SHAPES = [(1000, 32, 32), (777, 128, 256), (300, 7, 256), (513, 24, 256), (400, 300, 256),
+               (260, 789, 256), (129, 768, 1024), (64, 1024, 1024), (1, 5, 3), (2000, 64, 40)]
+
+
+@pytest.mark.parametrize("n,d_in,d_out", PROJ_SHAPES)
+@pytest.mark.parametrize("in_s,w_s", [("f32", "f32"), ("bf16", "bf16"), ("f32", "bf16")])
+@pytest.mark.parametrize("trans", [False, True])
+def test_project(n, d_in, d_out, in_s, w_s, trans):
+    x = rng.normal_table(n, d_in, "tests", f"px{n}")
+    w = rng.normal_table(d_out, d_in, "tests", f"pw{n}") if trans else rng.normal_table(d_in, d_out, "tests", f"pw{n}")
+    w = w * np.float32(1.0 / np.sqrt(d_in))
+    xr = rng.round_to_bf16(x) if in_s == "bf16" else x
+    wr = rng.round_to_bf16(w) if w_s == "bf16" else w
+    ref = xr.astype(np.float64) @ (wr.astype(np.float64).T if trans else wr.astype(np.float64))
+    out = torch.full((n, d_out), float("nan"), dtype=torch.float32, device="cuda")
+    heta.heta_project(dev_table(x, in_s, 8), dev_table(w, w_s, 8), out, trans_w=trans)
+    tol = 1e-4 if (in_s, w_s) == ("f32", "f32") else 2e-2
+    assert_rows_close(out.cpu().numpy(), ref, tol, f"project {n}x{d_in}x{d_out}")
+
+
+@pytest.mark.parametrize("pad", [1, 4])
+def test_project_row_scale_beta_and_odd_strides(pad):
+    n, d_in, d_out = 333, 37, 45
+    x = rng.normal_table(n, d_in, "tests", "rsx")
+    w = rng.normal_table(d_in, d_out, "tests", "rsw")
+    s = rng.uniform_table(n, 1, 0.5, 2.0, "tests", "rss")[:, 0].copy()
+    prev = rng.normal_table(n, d_out, "tests", "rsp")
+    out = dev_table(prev, "f32", pad)
+    heta.heta_project(dev_table(x, "f32", pad), dev_table(w, "f32", pad), out,
+                      row_scale=torch.from_numpy(s).cuda(), beta=1.0)
+    ref = prev.astype(np.float64) + s[:, None].astype(np.float64) * (x.astype(np.float64) @ w.astype(np.float64))
+    assert_rows_close(out.cpu().numpy(), ref, 1e-4, "row_scale+beta")
+
+
+@pytest.mark.parametrize("n,d_in,d_out", [(2000, 32, 32), (5000, 128, 256), (3000, 7, 256), (1500, 300, 256),
+                                          (700, 789, 256), (40, 16, 8), (5000, 768, 1024)])
+@pytest.mark.parametrize("in_s", ["f32", "bf16"])
+def test_project_wgrad(n, d_in, d_out, in_s):
+    rel = Relation("w", 0, 1, np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32))
+    hg = heta.heta_graph_create([(4, 8, 0), (n, 8, 0)], [(0, 1, rel.rowptr, rel.col)])
+    m = rng.normal_table(n, d_in, "tests", f"wgm{n}")
+    g = rng.normal_table(n, d_out, "tests", f"wgg{n}")
+    mr = rng.round_to_bf16(m) if in_s == "bf16" else m
+    ref = mr.astype(np.float64).T @ g.astype(np.float64)
+    dW = torch.full((d_in, d_out), float("nan"), dtype=torch.float32, device="cuda")
+    heta.heta_rel_project_wgrad(hg, 0, dev_table(m, in_s, 8), dev_table(g, "f32", 4), dW)
+    tol = 1e-4 if in_s == "f32" else 2e-2
+    # the contraction runs over n rows: scale the bound by the row norm of the reference
+    assert_rows_close(dW.cpu().numpy(), ref, tol, f"wgrad {n}x{d_in}x{d_out}")
+    heta.heta_rel_project_wgrad(hg, 0, dev_table(m, in_s, 8), dev_table(g, "f32", 4), dW, beta=1.0)
+    assert_rows_close(dW.cpu().numpy(), 2 * ref, tol, "wgrad accumulate")
+    hg.destroy()
+
+
+# ---- a5: cross-relation sum ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d,k,relu", [(256, 3, False), (256, 1, True), (33, 5, True), (32, 16, False)])
+def test_cross_rel_reduce_and_act_bwd(d, k, relu):
+    n = 1237
+    hg = heta.heta_graph_create([(n, 8, 0)], [])
+    parts = [rng.normal_table(n, d, "tests", f"part{i}") for i in range(k)]
+    ref = oracle.cross_rel_sum(parts, relu=relu)
+    out = torch.zeros((n, d), dtype=torch.float32, device="cuda")
+    heta.heta_cross_rel_reduce(hg, 0, [dev_table(q, "f32", 1) for q in parts], out,
+                               act=heta.HETA_ACT_RELU if relu else heta.HETA_ACT_NONE)
+    assert_rows_close(out.cpu().numpy(), ref, 1e-6, "cross-relation sum")
+    g = rng.normal_table(n, d, "tests", "actg")
+    gi = torch.zeros((n, d), dtype=torch.float32, device="cuda")
+    heta.heta_act_bwd(heta.HETA_ACT_RELU if relu else heta.HETA_ACT_NONE, out, dev_table(g, "f32", 1), gi)
+    expect = g * (out.cpu().numpy() > 0) if relu else g
+    assert np.array_equal(gi.cpu().numpy(), expect.astype(np.float32))
+    hg.destroy()
+
+
+# ---- whole layers ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("unfused", [False, True])
+def test_layer_config1(unfused):
+    p = workloads.config1()
+    got = run_layer_on_gpu(p, unfused=unfused)
+    ref_f = oracle.layer_forward(p)
+    ref_b = oracle.layer_backward(p, ref_f, p.G)
+    compare_layer(p, got, ref_f, ref_b, tol=1e-4)
+
+
+def test_layer_config1_relation_split_equals_whole():
+    """Proposition 1 on the GPU path: partial aggregations of two relation subsets, summed by
+    heta_cross_rel_reduce, equal the layer over all relations."""
+    p = workloads.config1()
+    hg = make_graph(p)
+    whole = make_layer(p, hg)
+    H = whole.forward()
+    a = make_layer(p, hg, rels=[0, 2])
+    b = make_layer(p, hg, rels=[1, 3])
+    Ha, Hb = a.forward(), b.forward()
+    tot = torch.zeros_like(H[0])
+    heta.heta_cross_rel_reduce(hg, 0, [Ha[0], Hb[0]], tot)
+    ref = oracle.layer_forward(p)
+    assert_rows_close(tot.cpu().numpy(), ref.H[0], 1e-4, "split sum")
+    assert_rows_close(H[0].cpu().numpy(), ref.H[0], 1e-4, "whole")
+    assert_rows_close(Ha[1].cpu().numpy() if 1 in Ha else Hb[1].cpu().numpy(), ref.H[1], 1e-4, "type B")
+    hg.destroy()
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_layer_config3_scaled(storage):
+    p = workloads.config3(storage, scale=0.02)
+    got = run_layer_on_gpu(p)
+    ref_f = oracle.layer_forward(p)
+    ref_b = oracle.layer_backward(p, ref_f, p.G)
+    compare_layer(p, got, ref_f, ref_b, tol=TOL[storage])
+
+
+def test_layer_config4_scaled():
+    p = workloads.config4(scale=0.01)
+    got = run_layer_on_gpu(p)
+    ref_f = oracle.layer_forward(p)
+    ref_b = oracle.layer_backward(p, ref_f, p.G)
+    compare_layer(p, got, ref_f, ref_b, tol=2e-2)
+
+
+def test_layer_with_relu_and_gid():
+    from tests.test_oracle_pins import tiny_problem
+    for seed in range(3):
+        p = tiny_problem(seed, "mean", relu=True, with_gid=True)
+        got = run_layer_on_gpu(p)
+        ref_f = oracle.layer_forward(p)
+        ref_b = oracle.layer_backward(p, ref_f, p.G)
+        compare_layer(p, got, ref_f, ref_b, tol=1e-4)
