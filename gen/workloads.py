@@ -134,7 +134,7 @@ def academic_graph(scale: float = 1.0, exponent: float = 2.1, workload: str = "a
     return g
 
 
-def config3(storage: str = "f32", scale: float = 1.0, exact: bool = False) -> LayerProblem:
+def config3(storage: str = "f32", scale: float = 1.0, exact: bool = False, upstream: bool = True) -> LayerProblem:
     """Full-graph single layer on the academic-shaped graph (~21 M edges at scale 1):
     128-wide inputs, 256-wide output, mean aggregation."""
     wl = f"config3/{scale:g}" + ("/exact" if exact else "")
@@ -142,7 +142,7 @@ def config3(storage: str = "f32", scale: float = 1.0, exact: bool = False) -> La
     tabs = _tables(g, wl, storage, exact)
     W = _weights(g, lambda i: 128, 256, wl, storage, exact)
     return LayerProblem(f"config3-{storage}", g, "mean", storage, tabs, W, 256,
-                        _upstream(g, 256, wl, exact))
+                        _upstream(g, 256, wl, exact) if upstream else {})
 
 
 # ---- config 4: mixed widths --------------------------------------------------------------------

@@ -163,6 +163,24 @@ heta_status heta_act_bwd(int64_t n_rows, int32_t d, heta_act act, const float *h
                          const float *grad_out, int64_t ld_go, float *grad_in, int64_t ld_gi,
                          void *hip_stream);
 
+/* ---- measurement --------------------------------------------------------------------------------
+ * With profiling on (process-wide), every kernel the library launches is bracketed by two HIP
+ * events on the stream it runs on.  heta_profile_read waits for the outstanding events and
+ * returns one record per kernel name: launches, summed duration, and the algorithmic bytes and
+ * flops of those launches (per relation and direction: E*d*sizeof(in) + 4*E + 8*rows +
+ * rows*d*sizeof(out) for an aggregation; 2*n*d_in*d_out flops for a projection).
+ * `out` is a HOST array of `capacity` records; *n_out receives the number of kernels seen. */
+typedef struct {
+    char name[48];
+    int64_t launches;
+    double total_ms;
+    double algorithmic_bytes;
+    double flops;
+} heta_kernel_stat;
+heta_status heta_profile_enable(int32_t on);
+heta_status heta_profile_reset(void);
+heta_status heta_profile_read(heta_kernel_stat *out, int32_t capacity, int32_t *n_out);
+
 /* Message of the last failure on the calling thread (valid until that thread's next call). */
 const char *heta_last_error(void);
 /* "major.minor" of the library. */

@@ -26,7 +26,8 @@ HETA_PTRS_ON_DEVICE = 1
 EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "heta_graph_get_degrees",
            "heta_feature_gather", "heta_check_ids", "heta_rel_aggregate_fwd", "heta_rel_aggregate_bwd",
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
-           "heta_act_bwd", "heta_last_error", "heta_version"]
+           "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
+           "heta_profile_read"]
 
 
 class HetaError(RuntimeError):
@@ -325,3 +326,34 @@ def heta_act_bwd(act: int, h: Optional[torch.Tensor], grad_out: torch.Tensor, gr
                                        _dev(grad_out, "grad_out", torch.float32), _ld(grad_out),
                                        _dev(grad_in, "grad_in", torch.float32), _ld(grad_in), _stream(stream)))
     return grad_in
+
+
+class _KernelStat(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 48), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double),
+                ("algorithmic_bytes", ctypes.c_double), ("flops", ctypes.c_double)]
+
+
+def heta_profile_enable(on: bool) -> None:
+    L = load_library()
+    L.heta_profile_enable.argtypes = [ctypes.c_int32]
+    _check(L.heta_profile_enable(int(bool(on))))
+
+
+def heta_profile_reset() -> None:
+    _check(load_library().heta_profile_reset())
+
+
+def heta_profile_read():
+    """Per-kernel records: {name: {launches, total_ms, algorithmic_bytes, flops}}."""
+    L = load_library()
+    L.heta_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
+    cap = 64
+    arr = (_KernelStat * cap)()
+    n = ctypes.c_int32(0)
+    _check(L.heta_profile_read(ctypes.addressof(arr), cap, ctypes.byref(n)))
+    out = {}
+    for i in range(min(cap, n.value)):
+        s = arr[i]
+        out[s.name.decode()] = {"launches": int(s.launches), "total_ms": float(s.total_ms),
+                                "algorithmic_bytes": float(s.algorithmic_bytes), "flops": float(s.flops)}
+    return out

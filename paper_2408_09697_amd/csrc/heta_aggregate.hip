@@ -344,13 +344,19 @@ __global__ void __launch_bounds__(256) agg_hub_combine_kernel(AggParams p)
 }
 
 // ---- launch ---------------------------------------------------------------------------------------
+// algorithmic bytes of the two row classes of one call (for the optional profiler)
+struct AggCost {
+    double wave_bytes = 0, group_bytes = 0;
+};
+
 template <typename T, int EPC, int L, int CPL>
-static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st)
+static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st, const AggCost &cost)
 {
     constexpr int G = 64 / L;
     if (p.n_wave_items > 0) {
         const int64_t blocks = (p.n_wave_items + 3) / 4;
         if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many long rows");
+        ProfScope prof("agg_wave_kernel", st, cost.wave_bytes, 0);
         hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
         HETA_LAUNCH_CHECK("agg_wave_kernel");
     }
@@ -358,6 +364,7 @@ static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st)
     if (n_short > 0) {
         const int64_t blocks = (n_short + 4 * G - 1) / (4 * G);
         if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many short rows");
+        ProfScope prof("agg_group_kernel", st, cost.group_bytes, 0);
         hipLaunchKernelGGL((agg_group_kernel<T, EPC, L, CPL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
         HETA_LAUNCH_CHECK("agg_group_kernel");
     }
@@ -365,16 +372,16 @@ static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st)
 }
 
 template <typename T, int EPC>
-static heta_status launch_vec(const AggParams &p, int n_chunks, hipStream_t st)
+static heta_status launch_vec(const AggParams &p, int n_chunks, hipStream_t st, const AggCost &c)
 {
-    if (n_chunks <= 1) return launch_pair<T, EPC, 1, 1>(p, 1, st);
-    if (n_chunks <= 2) return launch_pair<T, EPC, 2, 1>(p, 1, st);
-    if (n_chunks <= 4) return launch_pair<T, EPC, 4, 1>(p, 1, st);
-    if (n_chunks <= 8) return launch_pair<T, EPC, 8, 1>(p, 1, st);
-    if (n_chunks <= 16) return launch_pair<T, EPC, 16, 1>(p, 1, st);
-    if (n_chunks <= 32) return launch_pair<T, EPC, 32, 1>(p, 1, st);
-    if (n_chunks <= 64) return launch_pair<T, EPC, 64, 1>(p, 1, st);
-    return launch_pair<T, EPC, 64, 2>(p, (n_chunks + 127) / 128, st);
+    if (n_chunks <= 1) return launch_pair<T, EPC, 1, 1>(p, 1, st, c);
+    if (n_chunks <= 2) return launch_pair<T, EPC, 2, 1>(p, 1, st, c);
+    if (n_chunks <= 4) return launch_pair<T, EPC, 4, 1>(p, 1, st, c);
+    if (n_chunks <= 8) return launch_pair<T, EPC, 8, 1>(p, 1, st, c);
+    if (n_chunks <= 16) return launch_pair<T, EPC, 16, 1>(p, 1, st, c);
+    if (n_chunks <= 32) return launch_pair<T, EPC, 32, 1>(p, 1, st, c);
+    if (n_chunks <= 64) return launch_pair<T, EPC, 64, 1>(p, 1, st, c);
+    return launch_pair<T, EPC, 64, 2>(p, (n_chunks + 127) / 128, st, c);
 }
 
 // lanes per row the dispatch above picks for a row of n_chunks chunks
@@ -417,15 +424,26 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
         if (e != HETA_OK) return e;
         p.ws = static_cast<float *>(g->d_ws);
     }
+    // Algorithmic bytes per row class: one neighbour row and one 4-byte index per edge, one 8-byte
+    // row pointer and one output row per row.  Hub rows' outputs are written by the combine kernel.
+    AggCost cost;
+    const double osz = p.out_bf16 ? 2.0 : 4.0;
+    const double per_edge = static_cast<double>(p.d) * esz + 4.0, per_row = 8.0 + p.d * osz;
+    const double e_wave = static_cast<double>(s.edges_with_deg_ge[wave_min]);
+    const double r_long = static_cast<double>(n_long_or_hub - s.n_hub_rows);
+    cost.wave_bytes = e_wave * per_edge + r_long * per_row;
+    cost.group_bytes = (static_cast<double>(s.n_edges) - e_wave) * per_edge +
+                       static_cast<double>(s.n_rows - n_long_or_hub) * per_row;
     heta_status e;
     if (in_dt == HETA_F32)
-        e = vec ? launch_vec<float, 4>(p, n_chunks, st) : launch_pair<float, 1, 64, 2>(p, (n_chunks + 127) / 128, st);
+        e = vec ? launch_vec<float, 4>(p, n_chunks, st, cost) : launch_pair<float, 1, 64, 2>(p, (n_chunks + 127) / 128, st, cost);
     else
-        e = vec ? launch_vec<bf16_t, 8>(p, n_chunks, st) : launch_pair<bf16_t, 1, 64, 2>(p, (n_chunks + 127) / 128, st);
+        e = vec ? launch_vec<bf16_t, 8>(p, n_chunks, st, cost) : launch_pair<bf16_t, 1, 64, 2>(p, (n_chunks + 127) / 128, st, cost);
     if (e != HETA_OK) return e;
     if (s.n_hub_rows > 0) {
         if (s.n_hub_rows > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many hub rows");
         const int tiles = static_cast<int>((p.ws_ld + 255) / 256);
+        ProfScope prof("agg_hub_combine_kernel", st, static_cast<double>(s.n_hub_rows) * per_row, 0);
         hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(256), 0, st, p);
         HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
     }

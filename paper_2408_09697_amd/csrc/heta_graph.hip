@@ -68,16 +68,19 @@ static heta_status build_schedule(Schedule &s, const int64_t *ptr, const int32_t
     s.n_rows = n_rows;
     s.n_edges = n_edges;
     // counting sort of the rows by min(degree, kHubMinDeg), descending, stable
-    std::vector<int64_t> bucket(kHubMinDeg + 2, 0);
+    std::vector<int64_t> bucket(kHubMinDeg + 2, 0), bucket_edges(kHubMinDeg + 2, 0);
     for (int64_t r = 0; r < n_rows; ++r) {
         int64_t d = std::min<int64_t>(ptr[r + 1] - ptr[r], kHubMinDeg);
         bucket[d] += 1;
+        bucket_edges[d] += ptr[r + 1] - ptr[r];
     }
     // rows_with_deg_ge[k] = sum of bucket[j] for j >= k
-    int64_t run = 0;
+    int64_t run = 0, run_edges = 0;
     for (int k = kHubMinDeg; k >= 0; --k) {
         run += bucket[k];
+        run_edges += bucket_edges[k];
         s.rows_with_deg_ge[k] = run;
+        s.edges_with_deg_ge[k] = run_edges;
     }
     // start offset of bucket k in the descending order = number of rows with larger key
     std::vector<int64_t> start(kHubMinDeg + 1);

@@ -58,6 +58,7 @@ struct Schedule {
     HubChunk *d_hub_chunks = nullptr;    // [n_hub_chunks], grouped by hub row in perm order
     int64_t *d_hub_chunk_ptr = nullptr;  // [n_hub_rows + 1] chunk range of each hub row
     int64_t rows_with_deg_ge[kDegHist];  // host: number of rows whose degree is >= k
+    int64_t edges_with_deg_ge[kDegHist]; // host: number of edges in those rows
 };
 
 struct Relation {
@@ -81,6 +82,22 @@ struct heta_graph {
 };
 
 namespace heta {
+// Brackets one kernel launch with HIP events when profiling is on (see heta_profile_enable);
+// `bytes` and `flops` are the algorithmic traffic and work of that launch.
+bool profiling_on();
+class ProfScope {
+public:
+    ProfScope(const char *name, hipStream_t st, double bytes, double flops);
+    ~ProfScope();
+    ProfScope(const ProfScope &) = delete;
+    ProfScope &operator=(const ProfScope &) = delete;
+
+private:
+    bool active_;
+    hipStream_t stream_;
+    size_t index_ = 0;
+};
+
 // Makes sure g's workspace holds `bytes`; growing frees and reallocates (device synchronising).
 heta_status ensure_workspace(heta_graph *g, size_t bytes);
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }

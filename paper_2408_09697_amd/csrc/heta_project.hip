@@ -241,6 +241,11 @@ static heta_status launch_gemm(const GemmParams &p, hipStream_t st)
 {
     const int64_t mt = (p.M + BM - 1) / BM, nt = (p.N + BN - 1) / BN;
     if (mt > 0x7fffffff || nt > 65535) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
+    // algorithmic traffic: both operands once, the output once (twice when accumulating)
+    const double bytes = static_cast<double>(p.M) * p.K * sizeof(SA_T) + static_cast<double>(p.K) * p.N * sizeof(SB_T) +
+                         static_cast<double>(p.M) * p.N * 4.0 * (p.beta != 0.f ? 2.0 : 1.0);
+    ProfScope prof(sizeof(CT) == 4 ? (p.partial ? "gemm_wgrad_f32" : "gemm_f32") : (p.partial ? "gemm_wgrad_bf16" : "gemm_bf16"),
+                   st, bytes, 2.0 * p.M * p.N * p.K);
     hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC>), dim3((unsigned)mt, (unsigned)nt, (unsigned)std::max(1, p.n_split)),
                        dim3(256), 0, st, p);
     HETA_LAUNCH_CHECK("gemm_kernel");
@@ -363,6 +368,7 @@ heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, h
     e = dispatch_gemm<true, true>(p, in_dt, HETA_F32, st);
     if (e != HETA_OK) return e;
     const int64_t total = static_cast<int64_t>(d_in) * d_out;
+    ProfScope prof("splitk_reduce_kernel", st, (p.n_split + 1.0) * total * 4.0, 0);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        static_cast<const float *>(g->d_ws), p.n_split, (int64_t)d_in, (int64_t)d_out, dW, ld_dw, beta);
     HETA_LAUNCH_CHECK("splitk_reduce_kernel");

@@ -104,6 +104,8 @@ heta_status heta_cross_rel_reduce(const heta_graph *g, int32_t dst_type, const f
     const int64_t threads = p.n_rows * (vec ? d_out / 4 : d_out);
     const int64_t blocks = (threads + 255) / 256;
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "heta_cross_rel_reduce: too large");
+    ProfScope prof("cross_rel_reduce_kernel", as_stream(hip_stream),
+                   (n_partials + 1.0) * static_cast<double>(p.n_rows) * d_out * 4.0, 0);
     if (vec)
         hipLaunchKernelGGL(cross_rel_reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), p);
     else
@@ -130,6 +132,7 @@ heta_status heta_act_bwd(int64_t n_rows, int32_t d, heta_act act, const float *h
     const int64_t threads = n_rows * (vec ? d / 4 : d);
     const int64_t blocks = (threads + 255) / 256;
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "heta_act_bwd: too large");
+    ProfScope prof("act_bwd_kernel", as_stream(hip_stream), (relu ? 3.0 : 2.0) * static_cast<double>(n_rows) * d * 4.0, 0);
     if (vec)
         hipLaunchKernelGGL(act_bwd_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), n_rows, (int)d,
                            relu, h, ld_h, grad_out, ld_go, grad_in, ld_gi);
