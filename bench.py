@@ -95,6 +95,14 @@ def main() -> int:
     edge_features = p.edge_features()
     n_edges = sum(r.num_edges for r in p.graph.relations)
 
+    # one plain 1 GiB copy: the known-size reference for hardware byte counters in profiler runs
+    calib_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    calib_dst = torch.empty_like(calib_src)
+    for _ in range(3):
+        heta.heta_calibration_copy(calib_dst, calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     def step():
         layer.forward()
         layer.backward(G)

@@ -149,6 +149,31 @@ heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, h
                                    int64_t ld_in, int32_t d_in, const float *gout, int64_t ld_go,
                                    int32_t d_out, float *dW, int64_t ld_dw, float beta, void *hip_stream);
 
+/* ---- projection of all relations into one destination type, fused with the cross-relation sum --
+ * (Eq. 1, both lines in one pass; Algorithm 1, relation-specific aggregation followed by AGG_all.)
+ * out[i, 0:d_out] = act(beta * out[i, 0:d_out] + sum_{p<n} ins[p][i, 0:d_in[p]] . Ws[p]),  i < n_rows(dst_type):
+ * one contraction over the concatenated k ranges, so no per-relation partial ever goes to HBM.
+ * ins, Ws, ld_in, d_in, ld_w: HOST arrays of n (1..8) entries; ins[p] device [n_rows, ld_in[p]] of
+ * in_dt; Ws[p] device [d_in[p], ld_w[p] >= d_out] of w_dt; out device fp32 [n_rows, ld_out].
+ * On a subset of a type's relations with beta = 0 it yields the partial aggregation of that subset. */
+heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
+                                   heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
+                                   const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,
+                                   heta_act act, float *out, int64_t ld_out, float beta, void *hip_stream);
+/* Its backward, one launch each for all n relations into dst_type (Algorithm 1, local
+ * backpropagation): dM[p] = gout . Ws[p]^T and dW[p] = beta * dW[p] + ins[p]^T . gout.
+ * gout device fp32 [n_rows, ld_go]; dM[p] device fp32 [n_rows, ld_dm[p] >= d_in[p]];
+ * dW[p] device fp32 [d_in[p], ld_dw[p] >= d_out]; the pointer arrays are HOST arrays.
+ * The wgrad call uses the handle's workspace (may grow it, see heta_rel_aggregate_fwd). */
+heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, int32_t n, const float *gout,
+                                       int64_t ld_go, int32_t d_out, const void *const *Ws, heta_dtype w_dt,
+                                       const int64_t *ld_w, const int32_t *d_in, float *const *dM,
+                                       const int64_t *ld_dm, void *hip_stream);
+heta_status heta_cross_rel_project_wgrad(heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
+                                         heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
+                                         const float *gout, int64_t ld_go, int32_t d_out, float *const *dW,
+                                         const int64_t *ld_dw, float beta, void *hip_stream);
+
 /* ---- cross-relation aggregation (Eq. 1, second line; Algorithm 1, AGG_all on the designated
  * worker; on a subset of relations it yields the partial aggregation a worker would send) --------
  * out[i, 0:d_out] = act(sum_{p < n_partials} partials[p][i, 0:d_out]), summed in array order.
@@ -180,6 +205,9 @@ typedef struct {
 heta_status heta_profile_enable(int32_t on);
 heta_status heta_profile_reset(void);
 heta_status heta_profile_read(heta_kernel_stat *out, int32_t capacity, int32_t *n_out);
+/* A plain device-to-device streaming copy of n_bytes (multiple of 16, 16-byte aligned buffers):
+ * the kernel of known traffic against which hardware byte counters are scaled. */
+heta_status heta_calibration_copy(void *dst, const void *src, int64_t n_bytes, void *hip_stream);
 
 /* Message of the last failure on the calling thread (valid until that thread's next call). */
 const char *heta_last_error(void);

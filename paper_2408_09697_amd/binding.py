@@ -27,7 +27,8 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_feature_gather", "heta_check_ids", "heta_rel_aggregate_fwd", "heta_rel_aggregate_bwd",
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
-           "heta_profile_read"]
+           "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
+           "heta_cross_rel_project_wgrad"]
 
 
 class HetaError(RuntimeError):
@@ -300,6 +301,88 @@ def heta_rel_project_wgrad(g: Graph, rel: int, inp: torch.Tensor, gout: torch.Te
     return dW
 
 
+def _ptr_array(ts, name, dtype=None):
+    return (ctypes.c_void_p * len(ts))(*[_dev(t, name, dtype) for t in ts])
+
+
+def _i64_array(vals):
+    return (ctypes.c_int64 * len(vals))(*[int(v) for v in vals])
+
+
+def _i32_array(vals):
+    return (ctypes.c_int32 * len(vals))(*[int(v) for v in vals])
+
+
+def heta_cross_rel_project(g: Graph, dst_type: int, ins: List[torch.Tensor], Ws: List[torch.Tensor],
+                           out: torch.Tensor, act: int = HETA_ACT_NONE, beta: float = 0.0, stream=None) -> torch.Tensor:
+    """out = act(beta*out + sum_p ins[p] @ Ws[p]) over the rows of dst_type."""
+    n_rows = g.ntypes[dst_type][0]
+    d_out = Ws[0].shape[1]
+    if len(ins) != len(Ws) or not ins:
+        raise HetaError(HETA_ERR_INVALID_ARG, "need one weight per input")
+    for x, w in zip(ins, Ws):
+        if x.shape[0] < n_rows or w.shape[0] != x.shape[1] or w.shape[1] != d_out or x.dtype != ins[0].dtype \
+                or w.dtype != Ws[0].dtype:
+            raise HetaError(HETA_ERR_SHAPE, "inputs / weights do not match")
+    if out.shape[0] < n_rows or out.shape[1] < d_out:
+        raise HetaError(HETA_ERR_SHAPE, "out too small")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_cross_rel_project.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, i64,
+                                         ctypes.c_float, vp]
+    a_in, a_w = _ptr_array(ins, "in"), _ptr_array(Ws, "W")
+    ld_in, d_in, ld_w = _i64_array([_ld(x) for x in ins]), _i32_array([x.shape[1] for x in ins]), \
+        _i64_array([w.stride(0) for w in Ws])
+    _check(L.heta_cross_rel_project(g.handle, dst_type, len(ins), a_in, _dt(ins[0]), ld_in, d_in, a_w, _dt(Ws[0]),
+                                    ld_w, d_out, act, _dev(out, "out", torch.float32), _ld(out), beta,
+                                    _stream(stream)))
+    return out
+
+
+def heta_cross_rel_project_bwd(g: Graph, dst_type: int, gout: torch.Tensor, Ws: List[torch.Tensor],
+                               dM: List[torch.Tensor], stream=None) -> List[torch.Tensor]:
+    """dM[p] = gout @ Ws[p]^T for every relation p into dst_type, one launch."""
+    n_rows = g.ntypes[dst_type][0]
+    d_out = gout.shape[1]
+    if len(Ws) != len(dM) or not Ws or gout.shape[0] < n_rows:
+        raise HetaError(HETA_ERR_SHAPE, "bad arguments")
+    for w, m in zip(Ws, dM):
+        if w.shape[1] != d_out or m.shape[0] < n_rows or m.shape[1] < w.shape[0] or w.dtype != Ws[0].dtype:
+            raise HetaError(HETA_ERR_SHAPE, "weights / outputs do not match")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_cross_rel_project_bwd.argtypes = [vp, i32, i32, vp, i64, i32, vp, i32, vp, vp, vp, vp, vp]
+    a_w, a_m = _ptr_array(Ws, "W"), _ptr_array(dM, "dM", torch.float32)
+    ld_w, d_in, ld_dm = _i64_array([w.stride(0) for w in Ws]), _i32_array([w.shape[0] for w in Ws]), \
+        _i64_array([_ld(m) for m in dM])
+    _check(L.heta_cross_rel_project_bwd(g.handle, dst_type, len(Ws), _dev(gout, "gout", torch.float32), _ld(gout),
+                                        d_out, a_w, _dt(Ws[0]), ld_w, d_in, a_m, ld_dm, _stream(stream)))
+    return dM
+
+
+def heta_cross_rel_project_wgrad(g: Graph, dst_type: int, ins: List[torch.Tensor], gout: torch.Tensor,
+                                 dW: List[torch.Tensor], beta: float = 0.0, stream=None) -> List[torch.Tensor]:
+    """dW[p] = beta*dW[p] + ins[p]^T @ gout for every relation p into dst_type, one launch."""
+    n_rows = g.ntypes[dst_type][0]
+    d_out = gout.shape[1]
+    if len(ins) != len(dW) or not ins or gout.shape[0] < n_rows:
+        raise HetaError(HETA_ERR_SHAPE, "bad arguments")
+    for x, w in zip(ins, dW):
+        if x.shape[0] < n_rows or w.shape[0] < x.shape[1] or w.shape[1] < d_out or x.dtype != ins[0].dtype:
+            raise HetaError(HETA_ERR_SHAPE, "inputs / gradients do not match")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_cross_rel_project_wgrad.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i64, i32, vp, vp,
+                                               ctypes.c_float, vp]
+    a_in, a_dw = _ptr_array(ins, "in"), _ptr_array(dW, "dW", torch.float32)
+    ld_in, d_in, ld_dw = _i64_array([_ld(x) for x in ins]), _i32_array([x.shape[1] for x in ins]), \
+        _i64_array([_ld(w) for w in dW])
+    _check(L.heta_cross_rel_project_wgrad(g.handle, dst_type, len(ins), a_in, _dt(ins[0]), ld_in, d_in,
+                                          _dev(gout, "gout", torch.float32), _ld(gout), d_out, a_dw, ld_dw, beta,
+                                          _stream(stream)))
+    return dW
+
+
 def heta_cross_rel_reduce(g: Graph, dst_type: int, partials: List[torch.Tensor], out: torch.Tensor,
                           act: int = HETA_ACT_NONE, stream=None) -> torch.Tensor:
     n = g.ntypes[dst_type][0]
@@ -337,6 +420,15 @@ def heta_profile_enable(on: bool) -> None:
     L = load_library()
     L.heta_profile_enable.argtypes = [ctypes.c_int32]
     _check(L.heta_profile_enable(int(bool(on))))
+
+
+def heta_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    n_bytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < n_bytes or not src.is_contiguous() or not dst.is_contiguous():
+        raise HetaError(HETA_ERR_SHAPE, "calibration copy needs contiguous buffers, dst at least as large as src")
+    L = load_library()
+    L.heta_calibration_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    _check(L.heta_calibration_copy(_dev(dst, "dst"), _dev(src, "src"), n_bytes, _stream(stream)))
 
 
 def heta_profile_reset() -> None:

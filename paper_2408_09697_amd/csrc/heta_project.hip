@@ -1,13 +1,18 @@
 // Per-relation projection on the matrix cores: Z_r = M_r W_r (forward), dM_r = dZ_r W_r^T and
 // dW_r = M_r^T dZ_r (backward) - the per-relation weight matrices of an R-GCN-style AGG_r
-// (Section 2.1 of the paper).  This is the only dense contraction on the path and the only
-// place MFMA is used.
+// (Section 2.1 of the paper) - and the same three products for all relations into one
+// destination type at once, where the forward then is Eq. 1 in one pass:
+// H_t = sum_r M_r W_r, a single contraction over the concatenated k ranges of the relations.
+// This is the only dense contraction on the path and the only place MFMA is used.
 //
 // One kernel template computes C[M,N] (+)= A[M,K] . B[K,N] with fp32 accumulation:
-//   - a 256-thread workgroup owns a 128 x 128 tile of C, each of its four wavefronts a 64 x 64
-//     quarter held as 2 x 2 MFMA 32x32 accumulators (64 VGPRs per lane);
+//   - a workgroup of 2 x WN wavefronts owns a 128 x (64*WN) tile of C, each wavefront a 64 x 64
+//     block held as 2 x 2 MFMA 32x32 accumulators (64 VGPRs per lane); WN = 4 (512 threads,
+//     256 output columns) lets a 256-wide projection read its input rows from HBM exactly once;
 //   - A and B tiles of 32 k-values are staged through LDS in a k-contiguous layout, rows padded
-//     by 16 bytes so that the 128-bit fragment reads of 8 consecutive lanes fall on distinct banks;
+//     by 16 bytes so that the 128-bit fragment reads of 8 consecutive lanes fall on distinct
+//     banks; the global loads of tile i+1 are issued before the MFMAs of tile i and only
+//     touched (masked, converted, stored to LDS) after them;
 //   - an operand is described by how it lies in memory: "k-contiguous" (element (r,k) at
 //     base[r*ld + k], copied with 128-bit loads/stores) or "r-contiguous" (element (r,k) at
 //     base[k*ld + r], transposed on the way into LDS);
@@ -15,7 +20,11 @@
 //     bf16 to v_mfma_f32_32x32x16_bf16.  The k index a lane supplies only has to agree between
 //     the A and B fragments, so each lane reads 16 contiguous bytes and spreads them over
 //     consecutive MFMAs;
-//   - the weight gradient contracts over graph rows: the row range is split over grid.z,
+//   - a launch carries up to 8 "segments": either summed into one output (k-concatenation, the
+//     fused forward) or independent products that share an operand (all dM_r or all dW_r of a
+//     destination type), scheduled next to each other so the shared operand is fetched from
+//     HBM once and served from cache to the others;
+//   - the weight gradient contracts over graph rows: the row range is split over workgroups,
 //     partial products go to the workspace and are added in split order (no atomics).
 #include <algorithm>
 
@@ -27,23 +36,31 @@ using bf16_t = uint16_t;
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int BM = 128, BK = 32;
+constexpr int kMaxSeg = 8;
 
-struct GemmParams {
+struct GemmSeg {
     const void *A;
     int64_t lda;
-    int a_vec;          // 128-bit loads allowed for A
     const void *B;
     int64_t ldb;
-    int b_vec;
-    int64_t M, N, K;
-    float *C;           // output, or partial buffer [split][M][ldc] when `partial`
+    float *C;           // output of this segment (batch mode) - segment 0's is used in sum mode
     int64_t ldc;
+    int64_t M, N, K;
+    int a_vec, b_vec;   // 128-bit loads allowed
+};
+
+struct GemmParams {
+    GemmSeg seg[kMaxSeg];
+    int n_seg;
+    int batch;           // 0: C_0 (+)= sum_s A_s B_s ; 1: C_s (+)= A_s B_s for every s
     const float *row_scale;
     float beta;
-    int64_t k_per_split; // multiple of BK; grid.z = n_split ranges of this many k-values
+    int relu;
+    int64_t k_per_split; // multiple of BK
     int n_split;
-    int partial;         // write raw partial products per split instead of the finished output
+    int partial;         // write raw partial products [split][M][ldc] (ldc = N) instead of the output
+    int64_t mt, nt;      // tile counts (maximum over the segments in batch mode)
 };
 
 __device__ __forceinline__ bf16_t to_bf16(float f)
@@ -62,39 +79,43 @@ template <> __device__ __forceinline__ bf16_t convert<bf16_t, bf16_t>(bf16_t v) 
 // LDS row stride in elements of CT: 32 k-values + 16 bytes of padding
 template <typename CT> struct LdsStride { static constexpr int value = BK + 16 / (int)sizeof(CT); };
 
-// Moves a [ROWS x BK] operand tile global -> registers -> LDS.
+// Moves a [ROWS x BK] operand tile global -> registers -> LDS with NT threads.
 //   RC == false: element (r,k) at base[r*ld + k]   (k-contiguous)
 //   RC == true : element (r,k) at base[k*ld + r]   (r-contiguous, transposed into LDS)
-template <typename S, typename CT, bool RC, int ROWS>
+// load() only issues the global loads; masking of ragged edges and conversion happen in store().
+template <typename S, typename CT, bool RC, int ROWS, int NT>
 struct TileLoader {
     static constexpr int E = 16 / (int)sizeof(S);
-    static constexpr int NCH = ROWS * BK / E / 256;
+    static constexpr int NCH = ROWS * BK / E / NT;
     static constexpr int SA = LdsStride<CT>::value;
-    S regs[NCH][E];
+    static_assert(NCH >= 1, "tile too small for the workgroup");
+    uint4 raw[NCH];
+    int left[NCH]; // valid elements of the chunk (0 = nothing loaded)
 
     __device__ __forceinline__ void load(const S *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int64_t K,
                                          bool vec, int tid)
     {
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int q = tid + 256 * i;
+            const int q = tid + NT * i;
             int r, k;
             if (RC) { k = q % BK; r = (q / BK) * E; }
             else { r = q / (BK / E); k = (q % (BK / E)) * E; }
             const int64_t gr = r0 + r, gk = k0 + k;
-#pragma unroll
-            for (int j = 0; j < E; ++j) regs[i][j] = S(0);
-            if (gr >= R || gk >= K) continue;
+            const bool in = gr < R && gk < K;
+            const int64_t rem = RC ? R - gr : K - gk; // valid elements along the contiguous direction
+            left[i] = in ? static_cast<int>(min(rem, static_cast<int64_t>(E))) : 0;
+            raw[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (!in) continue;
             const S *src = RC ? base + gk * ld + gr : base + gr * ld + gk;
-            const int64_t left = RC ? R - gr : K - gk; // valid elements along the contiguous direction
             if (vec) {
-                union { uint4 u; S s[E]; } t;
-                t.u = *reinterpret_cast<const uint4 *>(src);
-#pragma unroll
-                for (int j = 0; j < E; ++j) if (j < left) regs[i][j] = t.s[j];
+                raw[i] = *reinterpret_cast<const uint4 *>(src);
             } else {
+                union { uint4 u; S s[E]; } t;
+                t.u = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-                for (int j = 0; j < E; ++j) if (j < left) regs[i][j] = src[j];
+                for (int j = 0; j < E; ++j) if (j < left[i]) t.s[j] = src[j];
+                raw[i] = t.u;
             }
         }
     }
@@ -103,16 +124,22 @@ struct TileLoader {
     {
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int q = tid + 256 * i;
+            const int q = tid + NT * i;
+            union { uint4 u; S s[E]; } t;
+            t.u = raw[i];
+            if (left[i] < E) {
+#pragma unroll
+                for (int j = 0; j < E; ++j) if (j >= left[i]) t.s[j] = S(0);
+            }
             if (RC) {
                 const int k = q % BK, r = (q / BK) * E;
 #pragma unroll
-                for (int j = 0; j < E; ++j) lds[(r + j) * SA + k] = convert<S, CT>(regs[i][j]);
+                for (int j = 0; j < E; ++j) lds[(r + j) * SA + k] = convert<S, CT>(t.s[j]);
             } else {
                 const int r = q / (BK / E), k = (q % (BK / E)) * E;
                 CT tmp[E];
 #pragma unroll
-                for (int j = 0; j < E; ++j) tmp[j] = convert<S, CT>(regs[i][j]);
+                for (int j = 0; j < E; ++j) tmp[j] = convert<S, CT>(t.s[j]);
                 CT *dst = lds + r * SA + k;
                 if (sizeof(CT) * E == 16) *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(tmp);
                 else *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(tmp);
@@ -121,18 +148,31 @@ struct TileLoader {
     }
 };
 
-template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC>
-__global__ void __launch_bounds__(256) gemm_kernel(GemmParams p)
+template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN>
+__global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
 {
+    constexpr int NT = 128 * WN, BN = 64 * WN;
     constexpr int S = LdsStride<CT>::value;
     __shared__ __attribute__((aligned(16))) CT As[BM * S];
     __shared__ __attribute__((aligned(16))) CT Bs[BN * S];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int wm = (wave / WN) * 64, wn = (wave % WN) * 64;
     const int half = lane >> 5, l32 = lane & 31;
-    const int64_t m0 = static_cast<int64_t>(blockIdx.x) * BM, n0 = static_cast<int64_t>(blockIdx.y) * BN;
-    const int64_t kbeg = static_cast<int64_t>(blockIdx.z) * p.k_per_split;
-    const int64_t kend = min(p.K, kbeg + p.k_per_split);
+
+    // block id -> (segment, n tile, m tile, split): neighbours in launch order share operands
+    int64_t id = blockIdx.x;
+    int s0 = 0;
+    if (p.batch) {
+        s0 = static_cast<int>(id % p.n_seg);
+        id /= p.n_seg;
+    }
+    const int64_t n0 = (id % p.nt) * BN;
+    id /= p.nt;
+    const int64_t m0 = (id % p.mt) * BM;
+    const int64_t split = id / p.mt;
+    const GemmSeg &out_seg = p.seg[s0];
+    if (m0 >= out_seg.M || n0 >= out_seg.N) return; // uniform per workgroup (smaller segment of a batch)
+    const int s_end = p.batch ? s0 + 1 : p.n_seg;
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -142,43 +182,50 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    TileLoader<SA_T, CT, A_RC, BM> la;
-    TileLoader<SB_T, CT, B_RC, BN> lb;
-    const SA_T *A = static_cast<const SA_T *>(p.A);
-    const SB_T *B = static_cast<const SB_T *>(p.B);
+    TileLoader<SA_T, CT, A_RC, BM, NT> la;
+    TileLoader<SB_T, CT, B_RC, BN, NT> lb;
 
-    if (kbeg < kend) {
-        la.load(A, p.lda, m0, p.M, kbeg, kend, p.a_vec, tid);
-        lb.load(B, p.ldb, n0, p.N, kbeg, kend, p.b_vec, tid);
-    }
-    for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
+    // (segment, k0) of the tile whose loads are in flight
+    int ls = s0;
+    int64_t lk = split * p.k_per_split;
+    auto seg_end = [&](int s) { return min(p.seg[s].K, (split + 1) * p.k_per_split); };
+    auto issue = [&]() {
+        const GemmSeg &g = p.seg[ls];
+        const int64_t kend = seg_end(ls);
+        la.load(static_cast<const SA_T *>(g.A), g.lda, m0, g.M, lk, kend, g.a_vec, tid);
+        lb.load(static_cast<const SB_T *>(g.B), g.ldb, n0, g.N, lk, kend, g.b_vec, tid);
+    };
+    // skip leading segments that are empty for this split
+    while (ls < s_end && lk >= seg_end(ls)) { ++ls; lk = split * p.k_per_split; }
+    bool have = ls < s_end;
+    if (have) issue();
+    while (have) {
         __syncthreads(); // previous tile fully consumed
         la.store(As, tid);
         lb.store(Bs, tid);
         __syncthreads();
-        if (k0 + BK < kend) { // next tile's global loads fly during the MFMAs
-            la.load(A, p.lda, m0, p.M, k0 + BK, kend, p.a_vec, tid);
-            lb.load(B, p.ldb, n0, p.N, k0 + BK, kend, p.b_vec, tid);
-        }
+        // advance to the next tile and start its loads; they complete behind the MFMAs below
+        lk += BK;
+        while (ls < s_end && lk >= seg_end(ls)) { ++ls; lk = split * p.k_per_split; }
+        have = ls < s_end;
+        if (have) issue();
         if constexpr (sizeof(CT) == 4) {
 #pragma unroll
             for (int kk = 0; kk < BK; kk += 8) {
-                float4 a[2], b[2];
+                union F4 { float4 v; float f[4]; } a[2], b[2];
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    a[i] = *reinterpret_cast<const float4 *>(&As[(wm + i * 32 + l32) * S + kk + 4 * half]);
+                    a[i].v = *reinterpret_cast<const float4 *>(&As[(wm + i * 32 + l32) * S + kk + 4 * half]);
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    b[j] = *reinterpret_cast<const float4 *>(&Bs[(wn + j * 32 + l32) * S + kk + 4 * half]);
+                    b[j].v = *reinterpret_cast<const float4 *>(&Bs[(wn + j * 32 + l32) * S + kk + 4 * half]);
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
-                    }
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].f[t], b[j].f[t], acc[i][j], 0, 0, 0);
             }
         } else {
 #pragma unroll
@@ -200,105 +247,226 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmParams p)
     }
 
     // epilogue: accumulator register v of lane (half, l32) is C[8*(v/4) + 4*half + v%4][l32] of its 32x32 tile
-    float *C = p.C + (p.partial ? static_cast<int64_t>(blockIdx.z) * p.M * p.ldc : 0);
+    float *C = out_seg.C + (p.partial ? split * out_seg.M * out_seg.ldc : 0);
     const bool direct = !p.partial;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int64_t n = n0 + wn + j * 32 + l32;
-            if (n >= p.N) continue;
+            if (n >= out_seg.N) continue;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t m = m0 + wm + i * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (m >= p.M) continue;
+                if (m >= out_seg.M) continue;
                 float val = acc[i][j][v];
-                float *o = C + m * p.ldc + n;
+                float *o = C + m * out_seg.ldc + n;
                 if (direct) {
                     if (p.row_scale) val *= p.row_scale[m];
                     if (p.beta != 0.f) val += p.beta * *o;
+                    if (p.relu) val = fmaxf(val, 0.f);
                 }
                 *o = val;
             }
         }
 }
 
-// dW[m, n] = beta * dW[m, n] + sum over splits (in split order) of part[s][m][n]
+// out[m, n] = beta * out[m, n] + sum over splits (in split order) of part[s][m][n]
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *part, int n_split, int64_t M, int64_t N,
                                                             float *out, int64_t ldo, float beta)
 {
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (t >= M * N) return;
+    const int64_t total = M * N;
+    if (t >= total) return;
     const int64_t m = t / N, n = t % N;
     float a = 0.f;
-    for (int s = 0; s < n_split; ++s) a += part[(static_cast<int64_t>(s) * M + m) * N + n];
+    int s = 0;
+    for (; s + 8 <= n_split; s += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = part[static_cast<int64_t>(s + u) * total + t];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += v[u];
+    }
+    for (; s < n_split; ++s) a += part[static_cast<int64_t>(s) * total + t];
     float *o = out + m * ldo + n;
     *o = (beta != 0.f) ? beta * *o + a : a;
 }
 
-template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC>
-static heta_status launch_gemm(const GemmParams &p, hipStream_t st)
-{
-    const int64_t mt = (p.M + BM - 1) / BM, nt = (p.N + BN - 1) / BN;
-    if (mt > 0x7fffffff || nt > 65535) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
-    // algorithmic traffic: both operands once, the output once (twice when accumulating)
-    const double bytes = static_cast<double>(p.M) * p.K * sizeof(SA_T) + static_cast<double>(p.K) * p.N * sizeof(SB_T) +
-                         static_cast<double>(p.M) * p.N * 4.0 * (p.beta != 0.f ? 2.0 : 1.0);
-    ProfScope prof(sizeof(CT) == 4 ? (p.partial ? "gemm_wgrad_f32" : "gemm_f32") : (p.partial ? "gemm_wgrad_bf16" : "gemm_bf16"),
-                   st, bytes, 2.0 * p.M * p.N * p.K);
-    hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC>), dim3((unsigned)mt, (unsigned)nt, (unsigned)std::max(1, p.n_split)),
-                       dim3(256), 0, st, p);
-    HETA_LAUNCH_CHECK("gemm_kernel");
-    return HETA_OK;
-}
+// ---- host side -------------------------------------------------------------------------------------
 
 static bool vec_ok(const void *ptr, int64_t ld, heta_dtype dt)
 {
     return aligned16(ptr) && (ld * (int64_t)dtype_size(dt)) % 16 == 0;
 }
 
-template <bool A_RC, bool B_RC>
-static heta_status dispatch_gemm(GemmParams p, heta_dtype a_dt, heta_dtype b_dt, hipStream_t st)
+template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN>
+static heta_status launch_gemm(GemmParams &p, hipStream_t st)
 {
-    p.a_vec = vec_ok(p.A, p.lda, a_dt);
-    p.b_vec = vec_ok(p.B, p.ldb, b_dt);
-    if (a_dt == HETA_F32 && b_dt == HETA_F32) return launch_gemm<float, float, A_RC, float, B_RC>(p, st);
-    if (a_dt == HETA_F32 && b_dt == HETA_BF16) return launch_gemm<bf16_t, float, A_RC, bf16_t, B_RC>(p, st);
-    if (a_dt == HETA_BF16 && b_dt == HETA_F32) return launch_gemm<bf16_t, bf16_t, A_RC, float, B_RC>(p, st);
-    return launch_gemm<bf16_t, bf16_t, A_RC, bf16_t, B_RC>(p, st);
+    constexpr int BN = 64 * WN;
+    int64_t mt = 0, nt = 0;
+    double bytes = 0, flops = 0;
+    const int n_out = p.batch ? p.n_seg : 1;
+    for (int s = 0; s < p.n_seg; ++s) {
+        const GemmSeg &g = p.seg[s];
+        mt = std::max(mt, (g.M + BM - 1) / BM);
+        nt = std::max(nt, (g.N + BN - 1) / BN);
+        flops += 2.0 * g.M * g.N * g.K;
+        // algorithmic traffic: every distinct operand once, every output once (twice when accumulating)
+        bool a_seen = false, b_seen = false;
+        for (int q = 0; q < s; ++q) {
+            a_seen = a_seen || p.seg[q].A == g.A;
+            b_seen = b_seen || p.seg[q].B == g.B;
+        }
+        if (!a_seen) bytes += static_cast<double>(g.M) * g.K * sizeof(SA_T);
+        if (!b_seen) bytes += static_cast<double>(g.K) * g.N * sizeof(SB_T);
+        if (s < n_out) bytes += static_cast<double>(g.M) * g.N * 4.0 * ((p.beta != 0.f && !p.partial) ? 2.0 : 1.0);
+    }
+    p.mt = mt;
+    p.nt = nt;
+    const int64_t blocks = mt * nt * std::max(1, p.n_split) * (p.batch ? p.n_seg : 1);
+    if (blocks <= 0) return HETA_OK;
+    if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
+    ProfScope prof(sizeof(CT) == 4 ? (p.partial ? "gemm_wgrad_f32" : "gemm_f32") : (p.partial ? "gemm_wgrad_bf16" : "gemm_bf16"),
+                   st, bytes, flops);
+    hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN>), dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
+    HETA_LAUNCH_CHECK("gemm_kernel");
+    return HETA_OK;
 }
 
-static heta_status project_impl(int64_t n_rows, const void *in, heta_dtype in_dt, int64_t ld_in, int32_t d_in,
-                                const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_out, int32_t transW,
-                                const float *row_scale, float *out, int64_t ld_out, float beta, hipStream_t st,
-                                const char *who)
+template <bool A_RC, bool B_RC>
+static heta_status dispatch_gemm(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, hipStream_t st)
 {
-    if (!in || !W || !out) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    int64_t n_max = 0;
+    for (int s = 0; s < p.n_seg; ++s) {
+        p.seg[s].a_vec = vec_ok(p.seg[s].A, p.seg[s].lda, a_dt);
+        p.seg[s].b_vec = vec_ok(p.seg[s].B, p.seg[s].ldb, b_dt);
+        n_max = std::max(n_max, p.seg[s].N);
+    }
+    const bool wide = n_max > 128;
+#define HETA_GEMM(CT, SA, SB)                                                            \
+    return wide ? launch_gemm<CT, SA, A_RC, SB, B_RC, 4>(p, st) : launch_gemm<CT, SA, A_RC, SB, B_RC, 2>(p, st)
+    if (a_dt == HETA_F32 && b_dt == HETA_F32) { HETA_GEMM(float, float, float); }
+    if (a_dt == HETA_F32 && b_dt == HETA_BF16) { HETA_GEMM(bf16_t, float, bf16_t); }
+    if (a_dt == HETA_BF16 && b_dt == HETA_F32) { HETA_GEMM(bf16_t, bf16_t, float); }
+    HETA_GEMM(bf16_t, bf16_t, bf16_t);
+#undef HETA_GEMM
+}
+
+static bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+// out = beta*out + row_scale * sum_s in_s . (W_s or W_s^T)
+static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+                                const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
+                                int32_t d_out, int32_t transW, const float *row_scale, int relu, float *out,
+                                int64_t ld_out, float beta, hipStream_t st, const char *who)
+{
+    if (!ins || !Ws || !out || !ld_in || !d_in || !ld_w) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n_seg < 1 || n_seg > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d inputs", who, kMaxSeg);
     if (!valid_dtype(in_dt) || !valid_dtype(w_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
-    if (n_rows < 0 || d_in <= 0 || d_out <= 0) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
-    if (ld_in < d_in || ld_out < d_out || ld_w < (transW ? d_in : d_out))
-        return fail(HETA_ERR_SHAPE, "%s: leading dimension smaller than the row width", who);
-    if ((reinterpret_cast<uintptr_t>(in) % dtype_size(in_dt)) || (reinterpret_cast<uintptr_t>(W) % dtype_size(w_dt)) ||
-        (reinterpret_cast<uintptr_t>(out) & 3u))
-        return fail(HETA_ERR_INVALID_ARG, "%s: pointer not aligned to its element size", who);
-    if (n_rows == 0) return HETA_OK;
+    for (int s = 0; s < n_seg; ++s)
+        if (!ins[s] || !Ws[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n_rows < 0 || d_out <= 0 || ld_out < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
+    if (misaligned(out, 4)) return fail(HETA_ERR_INVALID_ARG, "%s: out not 4-byte aligned", who);
     GemmParams p{};
-    p.A = in;
-    p.lda = ld_in;
-    p.B = W;
-    p.ldb = ld_w;
-    p.M = n_rows;
-    p.N = d_out;
-    p.K = d_in;
-    p.C = out;
-    p.ldc = ld_out;
+    for (int s = 0; s < n_seg; ++s) {
+        if (d_in[s] <= 0 || ld_in[s] < d_in[s] || ld_w[s] < (transW ? d_in[s] : d_out))
+            return fail(HETA_ERR_SHAPE, "%s: leading dimension smaller than the row width", who);
+        if (misaligned(ins[s], dtype_size(in_dt)) || misaligned(Ws[s], dtype_size(w_dt)))
+            return fail(HETA_ERR_INVALID_ARG, "%s: pointer not aligned to its element size", who);
+        GemmSeg &g = p.seg[s];
+        g.A = ins[s];
+        g.lda = ld_in[s];
+        g.B = Ws[s];
+        g.ldb = ld_w[s];
+        g.C = out;
+        g.ldc = ld_out;
+        g.M = n_rows;
+        g.N = d_out;
+        g.K = d_in[s];
+    }
+    if (n_rows == 0) return HETA_OK;
+    p.n_seg = n_seg;
+    p.batch = 0;
     p.row_scale = row_scale;
     p.beta = beta;
-    p.k_per_split = (static_cast<int64_t>(d_in) + BK - 1) / BK * BK;
+    p.relu = relu;
+    p.k_per_split = int64_t(1) << 40;
     p.n_split = 1;
     p.partial = 0;
     // B[k][n] = W[k][n] is n-contiguous (r-contiguous in the loader's terms); W^T is k-contiguous
     return transW ? dispatch_gemm<false, false>(p, in_dt, w_dt, st) : dispatch_gemm<false, true>(p, in_dt, w_dt, st);
+}
+
+// dW_s = beta*dW_s + in_s^T . gout over n_rows graph rows, all s in one launch
+static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const void *const *ins, heta_dtype in_dt,
+                              const int64_t *ld_in, const int32_t *d_in, const float *gout, int64_t ld_go, int32_t d_out,
+                              float *const *dW, const int64_t *ld_dw, float beta, hipStream_t st, const char *who)
+{
+    if (!g || !ins || !gout || !dW || !ld_in || !d_in || !ld_dw) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n_seg < 1 || n_seg > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d inputs", who, kMaxSeg);
+    if (!valid_dtype(in_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
+    if (d_out <= 0 || ld_go < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
+    if (misaligned(gout, 4)) return fail(HETA_ERR_INVALID_ARG, "%s: gout not 4-byte aligned", who);
+    GemmParams p{};
+    int64_t out_elems = 0, tiles = 0;
+    const int BN = d_out > 128 ? 256 : 128;
+    for (int s = 0; s < n_seg; ++s) {
+        if (!ins[s] || !dW[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+        if (d_in[s] <= 0 || ld_in[s] < d_in[s] || ld_dw[s] < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
+        if (misaligned(ins[s], dtype_size(in_dt)) || misaligned(dW[s], 4))
+            return fail(HETA_ERR_INVALID_ARG, "%s: pointer not aligned to its element size", who);
+        GemmSeg &q = p.seg[s];
+        q.A = ins[s];      // A[m = column of `in`][k = graph row] : r-contiguous
+        q.lda = ld_in[s];
+        q.B = gout;        // B[k = graph row][n] : r-contiguous
+        q.ldb = ld_go;
+        q.M = d_in[s];
+        q.N = d_out;
+        q.K = n_rows;
+        q.ldc = d_out;
+        out_elems += static_cast<int64_t>(d_in[s]) * d_out;
+        tiles += ((d_in[s] + BM - 1) / BM) * ((d_out + BN - 1) / BN);
+    }
+    // split the graph rows so that about 512 workgroups run, each with at least 16 k-tiles
+    const int64_t k_tiles = (n_rows + BK - 1) / BK;
+    int64_t n_split = std::max<int64_t>(1, std::min<int64_t>((k_tiles + 15) / 16, (512 + tiles - 1) / tiles));
+    const int64_t tiles_per_split = std::max<int64_t>(1, (k_tiles + n_split - 1) / n_split);
+    n_split = std::max<int64_t>(1, (k_tiles + tiles_per_split - 1) / tiles_per_split);
+    heta_status e = ensure_workspace(g, static_cast<size_t>(n_split) * out_elems * sizeof(float));
+    if (e != HETA_OK) return e;
+    float *ws = static_cast<float *>(g->d_ws);
+    int64_t off = 0;
+    for (int s = 0; s < n_seg; ++s) {
+        p.seg[s].C = ws + off;
+        off += n_split * static_cast<int64_t>(d_in[s]) * d_out;
+    }
+    p.n_seg = n_seg;
+    p.batch = 1;
+    p.row_scale = nullptr;
+    p.beta = 0.f;
+    p.relu = 0;
+    p.k_per_split = tiles_per_split * BK;
+    p.n_split = static_cast<int>(n_split);
+    p.partial = 1;
+    e = dispatch_gemm<true, true>(p, in_dt, HETA_F32, st);
+    if (e != HETA_OK) return e;
+    for (int s = 0; s < n_seg; ++s) {
+        const int64_t total = static_cast<int64_t>(d_in[s]) * d_out;
+        ProfScope prof("splitk_reduce_kernel", st, (n_split + 1.0) * total * 4.0, 0);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           static_cast<const float *>(p.seg[s].C), static_cast<int>(n_split), (int64_t)d_in[s],
+                           (int64_t)d_out, dW[s], ld_dw[s], beta);
+        HETA_LAUNCH_CHECK("splitk_reduce_kernel");
+    }
+    return HETA_OK;
+}
+
+static heta_status check_type(const heta_graph *g, int32_t t, const char *who)
+{
+    if (!g) return fail(HETA_ERR_INVALID_ARG, "%s: graph is NULL", who);
+    if (t < 0 || t >= (int32_t)g->ntypes.size()) return fail(HETA_ERR_INVALID_ARG, "%s: node type %d out of range", who, t);
+    return HETA_OK;
 }
 
 } // namespace heta
@@ -311,8 +479,8 @@ heta_status heta_project(int64_t n_rows, const void *in, heta_dtype in_dt, int64
                          const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_out, int32_t transW,
                          const float *row_scale, float *out, int64_t ld_out, float beta, void *hip_stream)
 {
-    return project_impl(n_rows, in, in_dt, ld_in, d_in, W, w_dt, ld_w, d_out, transW, row_scale, out, ld_out, beta,
-                        as_stream(hip_stream), "heta_project");
+    return project_impl(n_rows, 1, &in, in_dt, &ld_in, &d_in, &W, w_dt, &ld_w, d_out, transW, row_scale, 0, out, ld_out,
+                        beta, as_stream(hip_stream), "heta_project");
 }
 
 heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
@@ -323,56 +491,85 @@ heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, h
     if (!g) return fail(HETA_ERR_INVALID_ARG, "heta_rel_project: graph is NULL");
     if (rel < 0 || rel >= (int32_t)g->rels.size())
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_project: relation %d out of range", rel);
-    return project_impl(g->rels[rel].n_dst, in, in_dt, ld_in, d_in, W, w_dt, ld_w, d_out, transW, row_scale, out,
-                        ld_out, beta, as_stream(hip_stream), "heta_rel_project");
+    return project_impl(g->rels[rel].n_dst, 1, &in, in_dt, &ld_in, &d_in, &W, w_dt, &ld_w, d_out, transW, row_scale, 0,
+                        out, ld_out, beta, as_stream(hip_stream), "heta_rel_project");
 }
 
 heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
                                    int64_t ld_in, int32_t d_in, const float *gout, int64_t ld_go,
                                    int32_t d_out, float *dW, int64_t ld_dw, float beta, void *hip_stream)
 {
-    if (!g || !in || !gout || !dW) return fail(HETA_ERR_INVALID_ARG, "heta_rel_project_wgrad: null argument");
+    if (!g) return fail(HETA_ERR_INVALID_ARG, "heta_rel_project_wgrad: null argument");
     if (rel < 0 || rel >= (int32_t)g->rels.size())
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_project_wgrad: relation %d out of range", rel);
-    if (!valid_dtype(in_dt)) return fail(HETA_ERR_INVALID_ARG, "heta_rel_project_wgrad: bad dtype");
-    if (d_in <= 0 || d_out <= 0 || ld_in < d_in || ld_go < d_out || ld_dw < d_out)
-        return fail(HETA_ERR_SHAPE, "heta_rel_project_wgrad: bad sizes");
-    if ((reinterpret_cast<uintptr_t>(in) % dtype_size(in_dt)) || (reinterpret_cast<uintptr_t>(gout) & 3u) ||
-        (reinterpret_cast<uintptr_t>(dW) & 3u))
-        return fail(HETA_ERR_INVALID_ARG, "heta_rel_project_wgrad: pointer not aligned to its element size");
-    hipStream_t st = as_stream(hip_stream);
-    const int64_t n_rows = g->rels[rel].n_dst;
-    const int64_t mt = (d_in + BM - 1) / BM, nt = (d_out + BN - 1) / BN;
-    const int64_t k_tiles = (n_rows + BK - 1) / BK;
-    int64_t n_split = std::max<int64_t>(1, std::min<int64_t>(k_tiles, (1024 + mt * nt - 1) / (mt * nt)));
-    const int64_t tiles_per_split = std::max<int64_t>(1, (k_tiles + n_split - 1) / n_split);
-    n_split = std::max<int64_t>(1, (k_tiles + tiles_per_split - 1) / tiles_per_split);
-    const size_t part_bytes = static_cast<size_t>(n_split) * d_in * d_out * sizeof(float);
-    heta_status e = ensure_workspace(g, part_bytes);
+    return wgrad_impl(g, g->rels[rel].n_dst, 1, &in, in_dt, &ld_in, &d_in, gout, ld_go, d_out, &dW, &ld_dw, beta,
+                      as_stream(hip_stream), "heta_rel_project_wgrad");
+}
+
+heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
+                                   heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
+                                   const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,
+                                   heta_act act, float *out, int64_t ld_out, float beta, void *hip_stream)
+{
+    heta_status e = check_type(g, dst_type, "heta_cross_rel_project");
     if (e != HETA_OK) return e;
+    if (act != HETA_ACT_NONE && act != HETA_ACT_RELU) return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_project: bad act");
+    return project_impl(g->ntypes[dst_type].num_nodes, n, ins, in_dt, ld_in, d_in, Ws, w_dt, ld_w, d_out, 0, nullptr,
+                        act == HETA_ACT_RELU, out, ld_out, beta, as_stream(hip_stream), "heta_cross_rel_project");
+}
+
+heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, int32_t n, const float *gout,
+                                       int64_t ld_go, int32_t d_out, const void *const *Ws, heta_dtype w_dt,
+                                       const int64_t *ld_w, const int32_t *d_in, float *const *dM,
+                                       const int64_t *ld_dm, void *hip_stream)
+{
+    const char *who = "heta_cross_rel_project_bwd";
+    heta_status e = check_type(g, dst_type, who);
+    if (e != HETA_OK) return e;
+    if (!gout || !Ws || !ld_w || !d_in || !dM || !ld_dm) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n < 1 || n > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d relations", who, kMaxSeg);
+    if (!valid_dtype(w_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
+    if (d_out <= 0 || ld_go < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
+    if (misaligned(gout, 4)) return fail(HETA_ERR_INVALID_ARG, "%s: gout not 4-byte aligned", who);
+    const int64_t n_rows = g->ntypes[dst_type].num_nodes;
     GemmParams p{};
-    p.A = in;          // A[m = column of `in`][k = graph row] : r-contiguous
-    p.lda = ld_in;
-    p.B = gout;        // B[k = graph row][n] : r-contiguous
-    p.ldb = ld_go;
-    p.M = d_in;
-    p.N = d_out;
-    p.K = n_rows;
-    p.C = static_cast<float *>(g->d_ws);
-    p.ldc = d_out;
+    for (int s = 0; s < n; ++s) {
+        if (!Ws[s] || !dM[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+        if (d_in[s] <= 0 || ld_w[s] < d_out || ld_dm[s] < d_in[s]) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
+        if (misaligned(Ws[s], dtype_size(w_dt)) || misaligned(dM[s], 4))
+            return fail(HETA_ERR_INVALID_ARG, "%s: pointer not aligned to its element size", who);
+        GemmSeg &q = p.seg[s];
+        q.A = gout;
+        q.lda = ld_go;
+        q.B = Ws[s];   // B[k][n] = W[n][k]: W is [d_in, d_out] row-major, k-contiguous
+        q.ldb = ld_w[s];
+        q.C = dM[s];
+        q.ldc = ld_dm[s];
+        q.M = n_rows;
+        q.N = d_in[s];
+        q.K = d_out;
+    }
+    if (n_rows == 0) return HETA_OK;
+    p.n_seg = n;
+    p.batch = 1;
     p.row_scale = nullptr;
     p.beta = 0.f;
-    p.k_per_split = tiles_per_split * BK;
-    p.n_split = static_cast<int>(n_split);
-    p.partial = 1;
-    e = dispatch_gemm<true, true>(p, in_dt, HETA_F32, st);
+    p.relu = 0;
+    p.k_per_split = int64_t(1) << 40;
+    p.n_split = 1;
+    p.partial = 0;
+    return dispatch_gemm<false, false>(p, HETA_F32, w_dt, as_stream(hip_stream));
+}
+
+heta_status heta_cross_rel_project_wgrad(heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
+                                         heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
+                                         const float *gout, int64_t ld_go, int32_t d_out, float *const *dW,
+                                         const int64_t *ld_dw, float beta, void *hip_stream)
+{
+    heta_status e = check_type(g, dst_type, "heta_cross_rel_project_wgrad");
     if (e != HETA_OK) return e;
-    const int64_t total = static_cast<int64_t>(d_in) * d_out;
-    ProfScope prof("splitk_reduce_kernel", st, (p.n_split + 1.0) * total * 4.0, 0);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const float *>(g->d_ws), p.n_split, (int64_t)d_in, (int64_t)d_out, dW, ld_dw, beta);
-    HETA_LAUNCH_CHECK("splitk_reduce_kernel");
-    return HETA_OK;
+    return wgrad_impl(g, g->ntypes[dst_type].num_nodes, n, ins, in_dt, ld_in, d_in, gout, ld_go, d_out, dW, ld_dw, beta,
+                      as_stream(hip_stream), "heta_cross_rel_project_wgrad");
 }
 
 } // extern "C"

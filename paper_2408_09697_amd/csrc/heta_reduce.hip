@@ -66,6 +66,14 @@ __global__ void __launch_bounds__(256) act_bwd_kernel(int64_t n_rows, int d, int
     }
 }
 
+// A plain streaming copy of known size: the reference point against which hardware byte
+// counters are scaled when the library's kernels are profiled.
+__global__ void __launch_bounds__(256) calibration_copy_kernel(const uint4 *src, uint4 *dst, int64_t n)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
 } // namespace heta
 
 using namespace heta;
@@ -140,6 +148,21 @@ heta_status heta_act_bwd(int64_t n_rows, int32_t d, heta_act act, const float *h
         hipLaunchKernelGGL(act_bwd_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream), n_rows, (int)d,
                            relu, h, ld_h, grad_out, ld_go, grad_in, ld_gi);
     HETA_LAUNCH_CHECK("act_bwd_kernel");
+    return HETA_OK;
+}
+
+heta_status heta_calibration_copy(void *dst, const void *src, int64_t n_bytes, void *hip_stream)
+{
+    if (!dst || !src || n_bytes < 0 || (n_bytes % 16) || !aligned16(dst) || !aligned16(src))
+        return fail(HETA_ERR_INVALID_ARG, "heta_calibration_copy: need 16-byte aligned buffers and a size that is a multiple of 16");
+    if (n_bytes == 0) return HETA_OK;
+    const int64_t n = n_bytes / 16;
+    const int64_t blocks = (n + 255) / 256;
+    if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "heta_calibration_copy: too large");
+    ProfScope prof("calibration_copy_kernel", as_stream(hip_stream), 2.0 * static_cast<double>(n_bytes), 0);
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream),
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n);
+    HETA_LAUNCH_CHECK("calibration_copy_kernel");
     return HETA_OK;
 }
 

@@ -1,9 +1,9 @@
 """Sequencing of the library calls for one RAF layer on one GPU (forward and backward).
 
 This module allocates device buffers with torch and issues the C-ABI calls in the order of
-Algorithm 1 of the paper, one worker's share: relation-specific aggregation and projection
-per relation, cross-relation sum per destination type, and the local backward.  It computes
-nothing itself.
+Algorithm 1 of the paper, one worker's share: relation-specific aggregation per relation,
+projection of all relations into a destination type fused with the cross-relation sum, and
+the local backward.  It computes nothing itself.
 """
 from __future__ import annotations
 
@@ -35,8 +35,9 @@ class RafLayer:
         self.pre_proj = None if pre_proj is None else list(pre_proj)
         self.src_gid = None if src_gid is None else list(src_gid)
         self.relu = relu
+        self.act = hb.HETA_ACT_RELU if relu else hb.HETA_ACT_NONE
         self.rels = list(range(len(graph.rels))) if rels is None else list(rels)
-        dev = self.W[0].device
+        dev = self.W[self.rels[0]].device
         self.dev = dev
         n_types = len(graph.ntypes)
         self.rels_into: Dict[int, List[int]] = {}
@@ -58,6 +59,7 @@ class RafLayer:
                     self.H0[t] = torch.empty((self.tables[t].shape[0], self.pre_proj[t].shape[1]),
                                              dtype=torch.float32, device=dev)
         self.M = {r: torch.empty((graph.n_dst(r), self.d_rel[r]), dtype=m_dtype, device=dev) for r in self.rels}
+        self.dM = {r: torch.empty((graph.n_dst(r), self.d_rel[r]), dtype=torch.float32, device=dev) for r in self.rels}
         self.H = {t: torch.empty((graph.ntypes[t][0], d_out), dtype=torch.float32, device=dev)
                   for t in self.rels_into}
         self.dW = {r: torch.empty((self.d_rel[r], d_out), dtype=torch.float32, device=dev) for r in self.rels}
@@ -68,26 +70,44 @@ class RafLayer:
             for s in self.rels_from:
                 self.dtable[s] = torch.empty((self.tables[s].shape[0], self.pre_proj[s].shape[0]),
                                              dtype=torch.float32, device=dev)
-        max_rows = max(graph.n_dst(r) for r in self.rels)
-        max_d = max(self.d_rel.values())
-        self._dM = torch.empty((max_rows, max_d), dtype=torch.float32, device=dev)
         self._Gact = ({t: torch.empty_like(h) for t, h in self.H.items()} if relu else {})
 
-    # ---- forward: aggregate -> project (accumulating over the relations into a type) --------------
     def source(self, s: int) -> torch.Tensor:
         return self.H0[s] if self.pre_proj is not None else self.tables[s]
 
-    def forward(self, stream=None) -> Dict[int, torch.Tensor]:
+    def _pre_project(self, stream):
         if self.pre_proj is not None:
             for t, h0 in enumerate(self.H0):
                 if h0 is not None:
                     hb.heta_project(self.tables[t], self.pre_proj[t], h0, stream=stream)
+
+    def _aggregate(self, r: int, stream):
+        s = self.g.rels[r][0]
+        gid = None if self.src_gid is None else self.src_gid[s]
+        hb.heta_rel_aggregate_fwd(self.g, r, self.op, self.source(s), self.M[r], d=self.d_rel[r], src_gid=gid,
+                                  stream=stream)
+
+    # ---- forward ------------------------------------------------------------------------------------
+    def forward(self, stream=None) -> Dict[int, torch.Tensor]:
+        """aggregate every relation, then one fused projection + cross-relation sum per type."""
+        self._pre_project(stream)
+        for t, rs in self.rels_into.items():
+            for r in rs:
+                self._aggregate(r, stream)
+            for c in range(0, len(rs), 8):  # the library takes up to 8 relations per call
+                part = rs[c:c + 8]
+                last = c + 8 >= len(rs)
+                hb.heta_cross_rel_project(self.g, t, [self.M[r] for r in part], [self.W[r] for r in part], self.H[t],
+                                          act=self.act if last else hb.HETA_ACT_NONE, beta=0.0 if c == 0 else 1.0,
+                                          stream=stream)
+        return self.H
+
+    def forward_per_relation(self, stream=None) -> Dict[int, torch.Tensor]:
+        """Same result with one projection per relation accumulating into H (beta = 1)."""
+        self._pre_project(stream)
         for t, rs in self.rels_into.items():
             for k, r in enumerate(rs):
-                s = self.g.rels[r][0]
-                gid = None if self.src_gid is None else self.src_gid[s]
-                hb.heta_rel_aggregate_fwd(self.g, r, self.op, self.source(s), self.M[r], d=self.d_rel[r],
-                                          src_gid=gid, stream=stream)
+                self._aggregate(r, stream)
                 hb.heta_rel_project(self.g, r, self.M[r], self.W[r], self.H[t], beta=0.0 if k == 0 else 1.0,
                                     stream=stream)
             if self.relu:
@@ -96,38 +116,38 @@ class RafLayer:
 
     def forward_unfused(self, stream=None) -> Dict[int, torch.Tensor]:
         """Same result through explicit per-relation partials Z_r and heta_cross_rel_reduce."""
-        if self.pre_proj is not None:
-            for t, h0 in enumerate(self.H0):
-                if h0 is not None:
-                    hb.heta_project(self.tables[t], self.pre_proj[t], h0, stream=stream)
+        self._pre_project(stream)
         for t, rs in self.rels_into.items():
             Z = []
             for r in rs:
-                s = self.g.rels[r][0]
-                gid = None if self.src_gid is None else self.src_gid[s]
-                hb.heta_rel_aggregate_fwd(self.g, r, self.op, self.source(s), self.M[r], d=self.d_rel[r],
-                                          src_gid=gid, stream=stream)
+                self._aggregate(r, stream)
                 z = torch.empty_like(self.H[t])
                 hb.heta_rel_project(self.g, r, self.M[r], self.W[r], z, stream=stream)
                 Z.append(z)
-            hb.heta_cross_rel_reduce(self.g, t, Z, self.H[t],
-                                     act=hb.HETA_ACT_RELU if self.relu else hb.HETA_ACT_NONE, stream=stream)
+            hb.heta_cross_rel_reduce(self.g, t, Z, self.H[t], act=self.act, stream=stream)
         return self.H
 
     # ---- backward: dZ = G; dW = M^T dZ; dM = dZ W^T; dH0 += CSC gather of dM ---------------------------
-    def backward(self, G: Dict[int, torch.Tensor], stream=None):
+    def backward(self, G: Dict[int, torch.Tensor], stream=None, per_relation: bool = False):
         first_for_src = {s: True for s in self.rels_from}
         for t, rs in self.rels_into.items():
             g = G[t]
             if self.relu:
                 g = hb.heta_act_bwd(hb.HETA_ACT_RELU, self.H[t], G[t], self._Gact[t], stream=stream)
+            if per_relation:
+                for r in rs:
+                    hb.heta_rel_project_wgrad(self.g, r, self.M[r], g, self.dW[r], stream=stream)
+                    hb.heta_rel_project(self.g, r, g, self.W[r], self.dM[r], trans_w=True, stream=stream)
+            else:
+                for c in range(0, len(rs), 8):
+                    part = rs[c:c + 8]
+                    hb.heta_cross_rel_project_wgrad(self.g, t, [self.M[r] for r in part], g,
+                                                    [self.dW[r] for r in part], stream=stream)
+                    hb.heta_cross_rel_project_bwd(self.g, t, g, [self.W[r] for r in part],
+                                                  [self.dM[r] for r in part], stream=stream)
             for r in rs:
                 s = self.g.rels[r][0]
-                n, d = self.g.n_dst(r), self.d_rel[r]
-                dM = self._dM[:n, :d]
-                hb.heta_rel_project_wgrad(self.g, r, self.M[r], g, self.dW[r], stream=stream)
-                hb.heta_rel_project(self.g, r, g, self.W[r], dM, trans_w=True, stream=stream)
-                hb.heta_rel_aggregate_bwd(self.g, r, self.op, dM, self.dH0[s],
+                hb.heta_rel_aggregate_bwd(self.g, r, self.op, self.dM[r], self.dH0[s],
                                           beta=0.0 if first_for_src[s] else 1.0, stream=stream)
                 first_for_src[s] = False
         if self.pre_proj is not None:

@@ -46,11 +46,13 @@ def make_layer(p, graph: Optional[heta.Graph] = None, rels=None) -> heta.RafLaye
     return heta.RafLayer(graph, op, tables, W, p.d_out, pre_proj=P, src_gid=gid, relu=p.relu, rels=rels)
 
 
-def run_layer_on_gpu(p, unfused: bool = False) -> Dict[str, dict]:
+def run_layer_on_gpu(p, mode: str = "fused") -> Dict[str, dict]:
+    """mode: "fused" (one projection per destination type), "per_relation" (one projection per
+    relation accumulating with beta = 1) or "unfused" (explicit partials + cross-relation reduce)."""
     layer = make_layer(p)
-    H = layer.forward_unfused() if unfused else layer.forward()
+    H = {"fused": layer.forward, "per_relation": layer.forward_per_relation, "unfused": layer.forward_unfused}[mode]()
     G = {t: torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).cuda() for t, g in p.G.items()}
-    dW, dH0, dT = layer.backward(G)
+    dW, dH0, dT = layer.backward(G, per_relation=(mode != "fused"))
     torch.cuda.synchronize()
     f = lambda x: x.float().cpu().numpy()
     out = {"H": {t: f(h) for t, h in H.items()}, "M": {r: f(m) for r, m in layer.M.items()},

@@ -336,10 +336,10 @@ def test_cross_rel_reduce_and_act_bwd(d, k, relu):
 
 # ---- whole layers ---------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("unfused", [False, True])
-def test_layer_config1(unfused):
+@pytest.mark.parametrize("mode", ["fused", "per_relation", "unfused"])
+def test_layer_config1(mode):
     p = workloads.config1()
-    got = run_layer_on_gpu(p, unfused=unfused)
+    got = run_layer_on_gpu(p, mode=mode)
     ref_f = oracle.layer_forward(p)
     ref_b = oracle.layer_backward(p, ref_f, p.G)
     compare_layer(p, got, ref_f, ref_b, tol=1e-4)
@@ -364,10 +364,11 @@ def test_layer_config1_relation_split_equals_whole():
     hg.destroy()
 
 
+@pytest.mark.parametrize("mode", ["fused", "per_relation"])
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
-def test_layer_config3_scaled(storage):
+def test_layer_config3_scaled(storage, mode):
     p = workloads.config3(storage, scale=0.02)
-    got = run_layer_on_gpu(p)
+    got = run_layer_on_gpu(p, mode=mode)
     ref_f = oracle.layer_forward(p)
     ref_b = oracle.layer_backward(p, ref_f, p.G)
     compare_layer(p, got, ref_f, ref_b, tol=TOL[storage])
@@ -389,3 +390,39 @@ def test_layer_with_relu_and_gid():
         ref_f = oracle.layer_forward(p)
         ref_b = oracle.layer_backward(p, ref_f, p.G)
         compare_layer(p, got, ref_f, ref_b, tol=1e-4)
+
+
+@pytest.mark.parametrize("in_s,w_s", [("f32", "f32"), ("bf16", "bf16")])
+@pytest.mark.parametrize("d_out,relu", [(256, False), (40, True)])
+def test_cross_rel_project_family(in_s, w_s, d_out, relu):
+    """Fused projection + cross-relation sum over relations of different widths, and its backward."""
+    n = 1500
+    widths = [7, 24, 64, 128, 300, 37]
+    hg = heta.heta_graph_create([(n, 8, 0)], [])
+    tol = 1e-4 if in_s == "f32" else 2e-2
+    xs = [rng.normal_table(n, d, "tests", f"crx{d}") for d in widths]
+    ws = [rng.normal_table(d, d_out, "tests", f"crw{d}") * np.float32(1 / np.sqrt(d)) for d in widths]
+    xr = [rng.round_to_bf16(x) if in_s == "bf16" else x for x in xs]
+    wr = [rng.round_to_bf16(w) if w_s == "bf16" else w for w in ws]
+    ref = sum(x.astype(np.float64) @ w.astype(np.float64) for x, w in zip(xr, wr))
+    dx = [dev_table(x, in_s, 8) for x in xs]
+    dw = [dev_table(w, w_s, 8) for w in ws]
+    out = torch.full((n, d_out), float("nan"), dtype=torch.float32, device="cuda")
+    heta.heta_cross_rel_project(hg, 0, dx, dw, out, act=heta.HETA_ACT_RELU if relu else heta.HETA_ACT_NONE)
+    assert_rows_close(out.cpu().numpy(), np.maximum(ref, 0) if relu else ref, tol, "fused forward")
+    # beta = 1 on a split of the relation set (Proposition 1 through the fused call)
+    out2 = torch.zeros((n, d_out), dtype=torch.float32, device="cuda")
+    heta.heta_cross_rel_project(hg, 0, dx[:2], dw[:2], out2)
+    heta.heta_cross_rel_project(hg, 0, dx[2:], dw[2:], out2, beta=1.0)
+    assert_rows_close(out2.cpu().numpy(), ref, tol, "fused forward in two parts")
+    g = rng.normal_table(n, d_out, "tests", "crg")
+    dg = dev_table(g, "f32", 4)
+    dMs = [torch.full((n, d), float("nan"), dtype=torch.float32, device="cuda") for d in widths]
+    heta.heta_cross_rel_project_bwd(hg, 0, dg, dw, dMs)
+    for m, w in zip(dMs, wr):
+        assert_rows_close(m.cpu().numpy(), g.astype(np.float64) @ w.astype(np.float64).T, tol, "fused dM")
+    dWs = [torch.full((d, d_out), float("nan"), dtype=torch.float32, device="cuda") for d in widths]
+    heta.heta_cross_rel_project_wgrad(hg, 0, dx, dg, dWs)
+    for w, x in zip(dWs, xr):
+        assert_rows_close(w.cpu().numpy(), x.astype(np.float64).T @ g.astype(np.float64), tol, "fused dW")
+    hg.destroy()
