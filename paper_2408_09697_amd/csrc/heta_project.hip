@@ -47,7 +47,6 @@ struct GemmSeg {
     float *C;           // output of this segment (batch mode) - segment 0's is used in sum mode
     int64_t ldc;
     int64_t M, N, K;
-    int a_vec, b_vec;   // 128-bit loads allowed
 };
 
 struct GemmParams {
@@ -82,41 +81,57 @@ template <typename CT> struct LdsStride { static constexpr int value = BK + 16 /
 // Moves a [ROWS x BK] operand tile global -> registers -> LDS with NT threads.
 //   RC == false: element (r,k) at base[r*ld + k]   (k-contiguous)
 //   RC == true : element (r,k) at base[k*ld + r]   (r-contiguous, transposed into LDS)
-// load() only issues the global loads; masking of ragged edges and conversion happen in store().
-template <typename S, typename CT, bool RC, int ROWS, int NT>
+// Every thread owns NCH 16-byte chunks at fixed (r,k) positions of the tile; its global
+// addresses are set up once per segment and advanced by one tile per load().  load() only
+// issues the global loads; masking of ragged edges and conversion happen in store().
+// VEC selects 128-bit loads (rows 16-byte aligned) against element-wise loads.
+template <typename S, typename CT, bool RC, int ROWS, int NT, bool VEC>
 struct TileLoader {
     static constexpr int E = 16 / (int)sizeof(S);
     static constexpr int NCH = ROWS * BK / E / NT;
     static constexpr int SA = LdsStride<CT>::value;
     static_assert(NCH >= 1, "tile too small for the workgroup");
+    const S *ptr[NCH];
+    int64_t step;
     uint4 raw[NCH];
     int left[NCH]; // valid elements of the chunk (0 = nothing loaded)
 
-    __device__ __forceinline__ void load(const S *base, int64_t ld, int64_t r0, int64_t R, int64_t k0, int64_t K,
-                                         bool vec, int tid)
+    __device__ __forceinline__ static int row_of(int q) { return RC ? (q / BK) * E : q / (BK / E); }
+    __device__ __forceinline__ static int k_of(int q) { return RC ? q % BK : (q % (BK / E)) * E; }
+
+    __device__ __forceinline__ void init(const S *base, int64_t ld, int64_t r0, int64_t k0, int tid)
+    {
+        step = RC ? BK * ld : BK;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int q = tid + NT * i;
+            const int64_t gr = r0 + row_of(q), gk = k0 + k_of(q);
+            ptr[i] = RC ? base + gk * ld + gr : base + gr * ld + gk;
+        }
+    }
+
+    // rows_left / k_left: valid rows and k-values of this tile (may exceed the tile size)
+    __device__ __forceinline__ void load(int rows_left, int k_left, int tid)
     {
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
             const int q = tid + NT * i;
-            int r, k;
-            if (RC) { k = q % BK; r = (q / BK) * E; }
-            else { r = q / (BK / E); k = (q % (BK / E)) * E; }
-            const int64_t gr = r0 + r, gk = k0 + k;
-            const bool in = gr < R && gk < K;
-            const int64_t rem = RC ? R - gr : K - gk; // valid elements along the contiguous direction
-            left[i] = in ? static_cast<int>(min(rem, static_cast<int64_t>(E))) : 0;
+            const int lr = rows_left - row_of(q), lk = k_left - k_of(q);
+            const bool in = lr > 0 && lk > 0;
+            left[i] = in ? min(E, RC ? lr : lk) : 0;
             raw[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (!in) continue;
-            const S *src = RC ? base + gk * ld + gr : base + gr * ld + gk;
-            if (vec) {
-                raw[i] = *reinterpret_cast<const uint4 *>(src);
-            } else {
-                union { uint4 u; S s[E]; } t;
-                t.u = make_uint4(0u, 0u, 0u, 0u);
+            if (in) {
+                if (VEC) {
+                    raw[i] = *reinterpret_cast<const uint4 *>(ptr[i]);
+                } else {
+                    union { uint4 u; S s[E]; } t;
+                    t.u = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-                for (int j = 0; j < E; ++j) if (j < left[i]) t.s[j] = src[j];
-                raw[i] = t.u;
+                    for (int j = 0; j < E; ++j) if (j < left[i]) t.s[j] = ptr[i][j];
+                    raw[i] = t.u;
+                }
             }
+            ptr[i] += step;
         }
     }
 
@@ -127,16 +142,15 @@ struct TileLoader {
             const int q = tid + NT * i;
             union { uint4 u; S s[E]; } t;
             t.u = raw[i];
-            if (left[i] < E) {
+            if (VEC && left[i] < E) { // a chunk that straddles the edge: the load brought in padding
 #pragma unroll
                 for (int j = 0; j < E; ++j) if (j >= left[i]) t.s[j] = S(0);
             }
+            const int r = row_of(q), k = k_of(q);
             if (RC) {
-                const int k = q % BK, r = (q / BK) * E;
 #pragma unroll
                 for (int j = 0; j < E; ++j) lds[(r + j) * SA + k] = convert<S, CT>(t.s[j]);
             } else {
-                const int r = q / (BK / E), k = (q % (BK / E)) * E;
                 CT tmp[E];
 #pragma unroll
                 for (int j = 0; j < E; ++j) tmp[j] = convert<S, CT>(t.s[j]);
@@ -148,7 +162,7 @@ struct TileLoader {
     }
 };
 
-template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN>
+template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN, bool VEC>
 __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
 {
     constexpr int NT = 128 * WN, BN = 64 * WN;
@@ -173,6 +187,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
     const GemmSeg &out_seg = p.seg[s0];
     if (m0 >= out_seg.M || n0 >= out_seg.N) return; // uniform per workgroup (smaller segment of a batch)
     const int s_end = p.batch ? s0 + 1 : p.n_seg;
+    const int rows_a = static_cast<int>(min(out_seg.M - m0, static_cast<int64_t>(BM)));
+    const int rows_b = static_cast<int>(min(out_seg.N - n0, static_cast<int64_t>(BN)));
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -182,32 +198,42 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    TileLoader<SA_T, CT, A_RC, BM, NT> la;
-    TileLoader<SB_T, CT, B_RC, BN, NT> lb;
+    TileLoader<SA_T, CT, A_RC, BM, NT, VEC> la;
+    TileLoader<SB_T, CT, B_RC, BN, NT, VEC> lb;
 
-    // (segment, k0) of the tile whose loads are in flight
-    int ls = s0;
-    int64_t lk = split * p.k_per_split;
-    auto seg_end = [&](int s) { return min(p.seg[s].K, (split + 1) * p.k_per_split); };
-    auto issue = [&]() {
-        const GemmSeg &g = p.seg[ls];
-        const int64_t kend = seg_end(ls);
-        la.load(static_cast<const SA_T *>(g.A), g.lda, m0, g.M, lk, kend, g.a_vec, tid);
-        lb.load(static_cast<const SB_T *>(g.B), g.ldb, n0, g.N, lk, kend, g.b_vec, tid);
+    // The tile sequence runs over the k range of this split in every segment of the block.
+    // (ls, lk, lend) describe the tile whose loads are issued next.
+    const int64_t kb = split * p.k_per_split;
+    int ls = s0 - 1;
+    int64_t lk = 0, lend = 0;
+    auto next_segment = [&]() -> bool {
+        for (++ls; ls < s_end; ++ls) {
+            const GemmSeg &g = p.seg[ls];
+            lend = min(g.K, kb + p.k_per_split);
+            if (kb < lend) {
+                lk = kb;
+                la.init(static_cast<const SA_T *>(g.A), g.lda, m0, kb, tid);
+                lb.init(static_cast<const SB_T *>(g.B), g.ldb, n0, kb, tid);
+                return true;
+            }
+        }
+        return false;
     };
-    // skip leading segments that are empty for this split
-    while (ls < s_end && lk >= seg_end(ls)) { ++ls; lk = split * p.k_per_split; }
-    bool have = ls < s_end;
+    auto issue = [&]() {
+        const int k_left = static_cast<int>(min(lend - lk, static_cast<int64_t>(BK)));
+        la.load(rows_a, k_left, tid);
+        lb.load(rows_b, k_left, tid);
+        lk += BK;
+    };
+    bool have = next_segment();
     if (have) issue();
     while (have) {
         __syncthreads(); // previous tile fully consumed
         la.store(As, tid);
         lb.store(Bs, tid);
         __syncthreads();
-        // advance to the next tile and start its loads; they complete behind the MFMAs below
-        lk += BK;
-        while (ls < s_end && lk >= seg_end(ls)) { ++ls; lk = split * p.k_per_split; }
-        have = ls < s_end;
+        // start the next tile's loads; they complete behind the MFMAs below
+        have = lk < lend || next_segment();
         if (have) issue();
         if constexpr (sizeof(CT) == 4) {
 #pragma unroll
@@ -249,20 +275,28 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
     // epilogue: accumulator register v of lane (half, l32) is C[8*(v/4) + 4*half + v%4][l32] of its 32x32 tile
     float *C = out_seg.C + (p.partial ? split * out_seg.M * out_seg.ldc : 0);
     const bool direct = !p.partial;
+    const bool plain = !direct || (!p.row_scale && p.beta == 0.f && !p.relu);
+    const bool interior = rows_a == BM && rows_b == BN;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int64_t n = n0 + wn + j * 32 + l32;
-            if (n >= out_seg.N) continue;
+            const int nl = wn + j * 32 + l32;
+            float *col = C + (m0 + wm + i * 32 + 4 * half) * out_seg.ldc + n0 + nl;
+            if (interior && plain) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) col[(8 * (v / 4) + (v % 4)) * out_seg.ldc] = acc[i][j][v];
+                continue;
+            }
+            if (nl >= rows_b) continue;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + wm + i * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (m >= out_seg.M) continue;
+                const int ml = wm + i * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (ml >= rows_a) continue;
                 float val = acc[i][j][v];
-                float *o = C + m * out_seg.ldc + n;
+                float *o = col + (8 * (v / 4) + (v % 4)) * out_seg.ldc;
                 if (direct) {
-                    if (p.row_scale) val *= p.row_scale[m];
+                    if (p.row_scale) val *= p.row_scale[m0 + ml];
                     if (p.beta != 0.f) val += p.beta * *o;
                     if (p.relu) val = fmaxf(val, 0.f);
                 }
@@ -300,7 +334,7 @@ static bool vec_ok(const void *ptr, int64_t ld, heta_dtype dt)
     return aligned16(ptr) && (ld * (int64_t)dtype_size(dt)) % 16 == 0;
 }
 
-template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN>
+template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN, bool VEC>
 static heta_status launch_gemm(GemmParams &p, hipStream_t st)
 {
     constexpr int BN = 64 * WN;
@@ -329,7 +363,7 @@ static heta_status launch_gemm(GemmParams &p, hipStream_t st)
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
     ProfScope prof(sizeof(CT) == 4 ? (p.partial ? "gemm_wgrad_f32" : "gemm_f32") : (p.partial ? "gemm_wgrad_bf16" : "gemm_bf16"),
                    st, bytes, flops);
-    hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN>), dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
+    hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN, VEC>), dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
     HETA_LAUNCH_CHECK("gemm_kernel");
     return HETA_OK;
 }
@@ -338,14 +372,17 @@ template <bool A_RC, bool B_RC>
 static heta_status dispatch_gemm(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, hipStream_t st)
 {
     int64_t n_max = 0;
+    bool vec = true; // 128-bit loads need every operand of the launch to qualify
     for (int s = 0; s < p.n_seg; ++s) {
-        p.seg[s].a_vec = vec_ok(p.seg[s].A, p.seg[s].lda, a_dt);
-        p.seg[s].b_vec = vec_ok(p.seg[s].B, p.seg[s].ldb, b_dt);
+        vec = vec && vec_ok(p.seg[s].A, p.seg[s].lda, a_dt) && vec_ok(p.seg[s].B, p.seg[s].ldb, b_dt);
         n_max = std::max(n_max, p.seg[s].N);
     }
     const bool wide = n_max > 128;
-#define HETA_GEMM(CT, SA, SB)                                                            \
-    return wide ? launch_gemm<CT, SA, A_RC, SB, B_RC, 4>(p, st) : launch_gemm<CT, SA, A_RC, SB, B_RC, 2>(p, st)
+#define HETA_GEMM(CT, SA, SB)                                                                                   \
+    return wide ? (vec ? launch_gemm<CT, SA, A_RC, SB, B_RC, 4, true>(p, st)                                    \
+                       : launch_gemm<CT, SA, A_RC, SB, B_RC, 4, false>(p, st))                                  \
+                : (vec ? launch_gemm<CT, SA, A_RC, SB, B_RC, 2, true>(p, st)                                    \
+                       : launch_gemm<CT, SA, A_RC, SB, B_RC, 2, false>(p, st))
     if (a_dt == HETA_F32 && b_dt == HETA_F32) { HETA_GEMM(float, float, float); }
     if (a_dt == HETA_F32 && b_dt == HETA_BF16) { HETA_GEMM(bf16_t, float, bf16_t); }
     if (a_dt == HETA_BF16 && b_dt == HETA_F32) { HETA_GEMM(bf16_t, bf16_t, float); }
