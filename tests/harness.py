@@ -94,3 +94,50 @@ def compare_layer(p, got, ref_f, ref_b, tol: float, tol_m: Optional[float] = Non
         assert_rows_close(got["dH0"][s], x, tol, f"dH0[{s}]")
     for s, x in dT.items():
         assert_rows_close(got["dT"][s], x, tol, f"dtable[{s}]")
+
+
+# ---- oracle values for sampled rows of a full-size problem ----------------------------------------
+
+def oracle_forward_rows(p, t: int, rows: np.ndarray):
+    """H_t[rows] (fp64) and the per-relation M_r[rows]: the oracle run on the sub-edge-lists whose
+    destination is one of `rows` (degrees of those rows are complete, so means are unchanged)."""
+    import oracle
+    rows = np.asarray(rows, dtype=np.int64)
+    remap = -np.ones(p.graph.ntypes[t].num_nodes, dtype=np.int64)
+    remap[rows] = np.arange(rows.size)
+    Z, Ms = [], {}
+    for i in p.graph.rels_into(t):
+        r = p.graph.relations[i]
+        src, dst = r.edge_list()
+        keep = remap[dst] >= 0
+        gid = None if p.src_gid is None else p.src_gid[r.src_type]
+        M = oracle.aggregate_fwd(src[keep], remap[dst[keep]].astype(np.int32), rows.size, p.tables[r.src_type],
+                                 p.op, gid=gid)
+        Ms[i] = M
+        Z.append(oracle.project(M, p.W[i]))
+    H = oracle.cross_rel_sum(Z, relu=p.relu)
+    return H, Ms
+
+
+def oracle_input_grad_rows(p, s: int, rows: np.ndarray, G):
+    """dH0_s[rows] (fp64): for every relation out of type s, the edges leaving one of `rows`, the
+    gradient rows dM_r = G_t W_r^T of their destinations, scattered with c_e = 1 or 1/deg_r(v_e)."""
+    import oracle
+    rows = np.asarray(rows, dtype=np.int64)
+    remap = -np.ones(p.graph.ntypes[s].num_nodes, dtype=np.int64)
+    remap[rows] = np.arange(rows.size)
+    out = None
+    for i in p.graph.rels_from(s):
+        r = p.graph.relations[i]
+        src, dst = r.edge_list()
+        n_t = p.graph.ntypes[r.dst_type].num_nodes
+        keep = remap[src] >= 0
+        dsts, inv = np.unique(dst[keep], return_inverse=True)
+        dM = np.asarray(G[r.dst_type][dsts], dtype=np.float64) @ np.asarray(p.W[i], dtype=np.float64).T
+        if p.op == "mean":
+            deg = oracle.in_degree(src, dst, n_t)
+            dM = dM / deg[dsts][:, None]
+        part = oracle.aggregate_bwd(remap[src[keep]].astype(np.int32), inv.astype(np.int32), rows.size, dsts.size,
+                                    dM, "sum")
+        out = part if out is None else out + part
+    return out

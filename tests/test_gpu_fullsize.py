@@ -1,0 +1,132 @@
+"""Parity at the benchmark's full size and launch configuration (config 3, 21 M edges).
+
+The oracle cannot run the whole layer at this size in seconds, so: index data and
+integer-valued aggregations are compared in full and bit for bit; floating-point outputs are
+compared on sampled rows the oracle computes one by one (always including the largest hub,
+rows of every scheduling class and empty rows); weight gradients, which contract over every
+row, are compared in full for three relations.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2408_09697_amd as heta
+from gen import rng, workloads
+from tests.harness import (assert_rows_close, dev_table, make_graph, make_layer, oracle_forward_rows,
+                           oracle_input_grad_rows)
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(deg: np.ndarray, n: int, seed: str) -> np.ndarray:
+    """Rows covering the degree spectrum: the largest, some of every class present, random ones."""
+    g = rng.stream("tests/fullsize", seed)
+    picks = [int(np.argmax(deg))]
+    for lo, hi in [(0, 0), (1, 1), (2, 7), (8, 127), (128, 511), (512, 1 << 40)]:
+        idx = np.flatnonzero((deg >= lo) & (deg <= hi))
+        if idx.size:
+            picks += g.choice(idx, size=min(4, idx.size), replace=False).tolist()
+    picks += g.integers(0, deg.size, size=n).tolist()
+    return np.unique(np.asarray(picks, dtype=np.int64))
+
+
+@pytest.fixture(scope="module")
+def full_graph():
+    p = workloads.config3("f32", scale=1.0, upstream=False)
+    hg = make_graph(p)
+    yield p, hg
+    hg.destroy()
+
+
+def test_full_size_ingest_bit_exact(full_graph):
+    p, hg = full_graph
+    for i, r in enumerate(p.graph.relations):
+        src, dst = r.edge_list()
+        n_s, n_t = p.graph.ntypes[r.src_type].num_nodes, p.graph.ntypes[r.dst_type].num_nodes
+        colptr, row = heta.heta_graph_get_csc(hg, i)
+        rc, rr = oracle.csc(src, dst, n_s)
+        assert np.array_equal(colptr, rc) and np.array_equal(row, rr), r.name
+        assert np.array_equal(heta.heta_graph_get_degrees(hg, i), oracle.in_degree(src, dst, n_t)), r.name
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_full_size_integer_aggregation_bit_exact(full_graph, storage):
+    """Small-integer tables: sums are exact in fp32 in any order, so forward (CSR) and backward
+    (CSC) aggregations of all 21 M edges must equal the oracle's bit for bit."""
+    p, hg = full_graph
+    d = 128
+    tabs = {}
+    for i, r in enumerate(p.graph.relations):
+        src, dst = r.edge_list()
+        n_s, n_t = p.graph.ntypes[r.src_type].num_nodes, p.graph.ntypes[r.dst_type].num_nodes
+        if r.src_type not in tabs:
+            x = rng.small_int_table(n_s, d, -2, 2, "tests/fullsize", f"int/{r.src_type}")
+            tabs[r.src_type] = (x, dev_table(x, storage, 8))
+        x, dx = tabs[r.src_type]
+        out = torch.empty((n_t, d), dtype=torch.float32, device="cuda")
+        heta.heta_rel_aggregate_fwd(hg, i, heta.HETA_SUM, dx, out)
+        ref = oracle.aggregate_fwd(src, dst, n_t, x, "sum")
+        assert np.abs(ref).max() < 2 ** 24
+        assert np.array_equal(out.cpu().numpy(), ref.astype(np.float32)), f"forward {r.name}"
+        if storage == "f32":   # the backward reads fp32 gradients whatever the table storage is
+            back = torch.empty((n_s, d), dtype=torch.float32, device="cuda")
+            gx = rng.small_int_table(n_t, d, -2, 2, "tests/fullsize", f"intg/{r.dst_type}")
+            heta.heta_rel_aggregate_bwd(hg, i, heta.HETA_SUM, dev_table(gx, "f32", 4), back)
+            refb = oracle.aggregate_bwd(src, dst, n_s, n_t, gx.astype(np.float64), "sum")
+            assert np.array_equal(back.cpu().numpy(), refb.astype(np.float32)), f"backward {r.name}"
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_full_size_layer_sampled_rows(storage):
+    tol = 1e-4 if storage == "f32" else 2e-2
+    p = workloads.config3(storage, scale=1.0)
+    layer = make_layer(p)
+    H = layer.forward()
+    G = {t: torch.from_numpy(g).cuda() for t, g in p.G.items()}
+    dW, dH0, _ = layer.backward(G)
+    torch.cuda.synchronize()
+    g = p.graph
+    # forward embeddings and saved aggregations
+    for t in H:
+        deg = sum(np.diff(g.relations[i].rowptr) for i in g.rels_into(t))
+        rows = sample_rows(deg, 40, f"fwd/{t}")
+        ref_h, ref_m = oracle_forward_rows(p, t, rows)
+        idx = torch.from_numpy(rows).cuda()
+        assert_rows_close(H[t][idx].cpu().numpy(), ref_h, tol, f"H[{g.ntypes[t].name}]")
+        for i, m in ref_m.items():
+            assert_rows_close(layer.M[i][idx].float().cpu().numpy(), m, tol, f"M[{g.relations[i].name}]")
+    # input / embedding gradients
+    for s in dH0:
+        outdeg = np.zeros(g.ntypes[s].num_nodes, dtype=np.int64)
+        for i in g.rels_from(s):
+            outdeg += np.bincount(g.relations[i].col, minlength=outdeg.size)
+        rows = sample_rows(outdeg, 40, f"bwd/{s}")
+        ref = oracle_input_grad_rows(p, s, rows, p.G)
+        idx = torch.from_numpy(rows).cuda()
+        assert_rows_close(dH0[s][idx].cpu().numpy(), ref, tol, f"dH0[{g.ntypes[s].name}]")
+    # weight gradients contract over every destination row: full comparison for three relations
+    for name in ("cites", "affiliated", "rev_writes"):
+        i = g.rel_index(name)
+        r = g.relations[i]
+        src, dst = r.edge_list()
+        M = oracle.aggregate_fwd(src, dst, g.ntypes[r.dst_type].num_nodes, p.tables[r.src_type], p.op)
+        if storage == "bf16":   # the saved aggregation is stored as bf16 on this path (stated in the design notes)
+            ref = M.T @ p.G[r.dst_type].astype(np.float64)
+            assert_rows_close(dW[i].cpu().numpy(), ref, 2e-2, f"dW[{name}]")
+        else:
+            ref = M.T @ p.G[r.dst_type].astype(np.float64)
+            assert_rows_close(dW[i].cpu().numpy(), ref, tol, f"dW[{name}]")
+    # adjoint identity over the whole graph, on the GPU's own outputs (fp64 on the host)
+    i = g.rel_index("writes")
+    r = g.relations[i]
+    x = p.tables[r.src_type].astype(np.float64)
+    gm = rng.normal_table(g.ntypes[r.dst_type].num_nodes, 128, "tests/fullsize", "adj")
+    fwd = torch.empty((g.ntypes[r.dst_type].num_nodes, 128), dtype=torch.float32, device="cuda")
+    bwd = torch.empty((g.ntypes[r.src_type].num_nodes, 128), dtype=torch.float32, device="cuda")
+    heta.heta_rel_aggregate_fwd(layer.g, i, heta.HETA_MEAN, layer.tables[r.src_type], fwd)
+    heta.heta_rel_aggregate_bwd(layer.g, i, heta.HETA_MEAN, dev_table(gm, "f32", 4), bwd)
+    lhs = np.vdot(gm.astype(np.float64), fwd.cpu().numpy().astype(np.float64))
+    rhs = np.vdot(x, bwd.cpu().numpy().astype(np.float64))
+    assert abs(lhs - rhs) <= 1e-5 * max(1.0, abs(lhs))
+    layer.g.destroy()
