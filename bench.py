@@ -1,18 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the RAF layer hot path on one MI355X.
 
-One step = one forward + one backward pass of a whole layer (heterogeneous gather fused into
-the aggregation, per-relation segmented reduce, per-relation projection with the cross-relation
-sum accumulated in its epilogue; then weight gradients, input-gradient projections and the
-CSC backward aggregation into every source type's gradient) over the full synthetic
+One step = one forward + one backward pass of a whole layer over the full synthetic
 academic-shaped graph of the third benchmark configuration (4 node types, 7 relations,
-21 M edges, 128 -> 256).  Inputs are resident in HBM before the timed region; the graph
-handle (CSC, degree schedules) is built once before it and its build time is reported
-separately.  Prints ONE JSON line.
+21 M edges, 128 -> 256, mean): heterogeneous gather fused into the per-relation segmented
+reduce, one fused projection + cross-relation sum per destination type; then weight gradients,
+input-gradient projections and the CSC backward aggregation into every source type's gradient.
+Inputs are resident in HBM before the timed region; the graph handle (CSC, degree schedules)
+is built once before it and its build time is reported separately.  The headline run uses fp32
+tables; the same layer with bf16 tables (fp32 accumulation) is measured afterwards and reported
+under "bf16_storage".  Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import contextlib
 import json
 import os
 import sys
@@ -26,9 +28,10 @@ PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"gemm_f32": 157.3, "gemm_wgrad_f32": 157.3, "gemm_bf16": 2500.0, "gemm_wgrad_bf16": 2500.0}
 
 
-def cpu_baseline(problem, rel_name: str = "cites"):
-    """Times the oracle, as it stands, on one relation of the same workload (forward aggregation,
-    projection, and the three backward products), single-threaded."""
+def cpu_baseline(problem, budget_s: float = 12.0, rel_names=("cites", "writes", "rev_writes", "has_topic")):
+    """Times the oracle, as it stands, on whole relations of the same workload (forward aggregation
+    and projection, the two backward products and the backward scatter), single-threaded, adding
+    relations until about `budget_s` seconds of CPU work have been spent."""
     import numpy as np
     import oracle
     try:
@@ -36,55 +39,40 @@ def cpu_baseline(problem, rel_name: str = "cites"):
     except ImportError:  # pragma: no cover
         threadpool_limits = None
     g = problem.graph
-    i = g.rel_index(rel_name)
-    r = g.relations[i]
-    src, dst = r.edge_list()
-    n_s, n_t = g.ntypes[r.src_type].num_nodes, g.ntypes[r.dst_type].num_nodes
-    G = np.random.default_rng(0).standard_normal((n_t, problem.d_out)).astype(np.float32)
-    import contextlib
+    total_s, edge_features, used = 0.0, 0, []
     with (threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()):
-        t0 = time.perf_counter()
-        M = oracle.aggregate_fwd(src, dst, n_t, problem.tables[r.src_type], problem.op)
-        Z = oracle.project(M, problem.W[i])
-        dM, dW = oracle.project_bwd(M, G, problem.W[i])
-        oracle.aggregate_bwd(src, dst, n_s, n_t, dM, problem.op)
-        dt = time.perf_counter() - t0
-    d = problem.W[i].shape[0]
-    del Z, dW
-    return {"value": 2.0 * r.num_edges * d / dt, "unit": "edge-features/s", "cores": 1, "kind": "oracle",
-            "sample": f"relation '{rel_name}' of the same graph ({r.num_edges} edges, d={d}): oracle forward "
-                      f"aggregation + projection and backward (dW, dM, scatter), {dt:.1f} s"}
+        for name in rel_names:
+            i = g.rel_index(name)
+            r = g.relations[i]
+            src, dst = r.edge_list()
+            n_s, n_t = g.ntypes[r.src_type].num_nodes, g.ntypes[r.dst_type].num_nodes
+            G = np.random.default_rng(0).standard_normal((n_t, problem.d_out)).astype(np.float32)
+            t0 = time.perf_counter()
+            M = oracle.aggregate_fwd(src, dst, n_t, problem.tables[r.src_type], problem.op)
+            Z = oracle.project(M, problem.W[i])
+            dM, dW = oracle.project_bwd(M, G, problem.W[i])
+            oracle.aggregate_bwd(src, dst, n_s, n_t, dM, problem.op)
+            total_s += time.perf_counter() - t0
+            del M, Z, dM, dW, G
+            edge_features += r.num_edges * problem.W[i].shape[0]
+            used.append(name)
+            if total_s >= budget_s:
+                break
+    return {"value": 2.0 * edge_features / total_s, "unit": "edge-features/s", "cores": 1, "kind": "oracle",
+            "sample": f"relations {used} of the same fp32 graph, forward + backward of each "
+                      f"({edge_features} edge-features per pass, {total_s:.1f} s of oracle time)",
+            "host_cores_visible": os.cpu_count()}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
-    ap.add_argument("--scale", type=float, default=1.0, help="shrinks the graph (testing only)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event pass")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (one GPU's share of the layer); "
-              "--gpus above 1 is not supported", file=sys.stderr)
-        return 2
-
-    import numpy as np
+def measure(storage: str, args, keep_problem: bool = False):
     import torch
     import paper_2408_09697_amd as heta
     from gen import workloads
     from tests.harness import make_graph, make_layer
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    heta.binding.load_library()
-
     t0 = time.perf_counter()
-    p = workloads.config3(args.dtype, scale=args.scale, upstream=False)  # the upstream gradient is drawn on the device below
+    p = workloads.config3(storage, scale=args.scale, upstream=False)  # the upstream gradient is drawn on the device
     gen_s = time.perf_counter() - t0
-
     t0 = time.perf_counter()
     graph = make_graph(p)
     ingest_ms = (time.perf_counter() - t0) * 1e3
@@ -94,14 +82,6 @@ def main() -> int:
     G = {t: torch.randn(h.shape, generator=gen_dev, device="cuda", dtype=torch.float32) for t, h in layer.H.items()}
     edge_features = p.edge_features()
     n_edges = sum(r.num_edges for r in p.graph.relations)
-
-    # one plain 1 GiB copy: the known-size reference for hardware byte counters in profiler runs
-    calib_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-    calib_dst = torch.empty_like(calib_src)
-    for _ in range(3):
-        heta.heta_calibration_copy(calib_dst, calib_src)
-    torch.cuda.synchronize()
-    del calib_src, calib_dst
 
     def step():
         layer.forward()
@@ -126,8 +106,7 @@ def main() -> int:
     torch.cuda.synchronize()
     fwd_ms, bwd_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
 
-    kernels = {}
-    roofline = None
+    kernels, roofline = {}, None
     if not args.no_profile:
         heta.heta_profile_enable(True)
         heta.heta_profile_reset()
@@ -137,9 +116,10 @@ def main() -> int:
         stats = heta.heta_profile_read()
         heta.heta_profile_enable(False)
         for name, s in stats.items():
-            avg_ms = s["total_ms"] / s["launches"]
             k = {"launches_per_step": s["launches"] / args.steps, "ms_per_step": s["total_ms"] / args.steps,
-                 "avg_launch_ms": avg_ms, "GBps": s["algorithmic_bytes"] / s["total_ms"] / 1e6}
+                 "avg_launch_ms": s["total_ms"] / s["launches"],
+                 "algorithmic_MB_per_launch": s["algorithmic_bytes"] / s["launches"] / 1e6,
+                 "GBps": s["algorithmic_bytes"] / s["total_ms"] / 1e6}
             if s["flops"] > 0:
                 k["TFLOPs"] = s["flops"] / s["total_ms"] / 1e9
             kernels[name] = k
@@ -147,40 +127,106 @@ def main() -> int:
         k = kernels[dom]
         if dom in PEAK_TFLOPS and k.get("TFLOPs", 0) / PEAK_TFLOPS[dom] > k["GBps"] / PEAK_HBM_GBS:
             roofline = {"kernel": dom, "bound": "mfma", "achieved": k["TFLOPs"], "peak": PEAK_TFLOPS[dom],
-                        "unit": "TFLOP/s", "frac": k["TFLOPs"] / PEAK_TFLOPS[dom], "traffic": None}
+                        "unit": "TFLOP/s", "frac": k["TFLOPs"] / PEAK_TFLOPS[dom]}
         else:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": k["GBps"] / PEAK_HBM_GBS, "traffic": None}
+                        "frac": k["GBps"] / PEAK_HBM_GBS}
+        roofline["traffic"] = None
+        tf = os.path.join(ROOT, "profiles", f"traffic_config3_{storage}.json")
+        if args.scale == 1.0 and os.path.exists(tf):
+            # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command,
+            # scaled by the 1 GiB calibration copy; written by paper_2408_09697_amd.rocprof_summary
+            with open(tf) as f:
+                rec = json.load(f).get(dom)
+            if rec:
+                roofline["traffic"] = rec["hbm_bytes_per_launch"]
+                roofline["traffic_source"] = os.path.relpath(tf, ROOT)
         roofline["avg_launch_ms"] = k["avg_launch_ms"]
         roofline["timing"] = "HIP events on the launch stream around every launch, over the same K steps"
         # all aggregation kernels together: the HBM-bound part of the step
         agg = [v for n, v in kernels.items() if n.startswith("agg_")]
         agg_ms = sum(v["ms_per_step"] for v in agg)
-        agg_bytes = sum(v["GBps"] * v["ms_per_step"] for v in agg)  # GB/s * ms = MB
-        roofline["aggregation_all_kernels"] = {"ms_per_step": agg_ms, "GBps": agg_bytes / agg_ms if agg_ms else 0.0,
-                                               "frac": (agg_bytes / agg_ms / PEAK_HBM_GBS) if agg_ms else 0.0}
+        agg_mb = sum(v["GBps"] * v["ms_per_step"] for v in agg)  # GB/s * ms = MB
+        roofline["aggregation_all_kernels"] = {"bound": "hbm", "ms_per_step": agg_ms,
+                                               "achieved": agg_mb / agg_ms if agg_ms else 0.0, "peak": PEAK_HBM_GBS,
+                                               "unit": "GB/s",
+                                               "frac": (agg_mb / agg_ms / PEAK_HBM_GBS) if agg_ms else 0.0}
+    res = {"ms_per_step": ms_per_step, "value": 2.0 * edge_features / (ms_per_step * 1e-3),
+           "edges_per_s": 2.0 * n_edges / (ms_per_step * 1e-3), "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+           "ingest_ms": ingest_ms, "input_generation_s": gen_s, "roofline": roofline, "kernels": kernels,
+           "edges": n_edges, "edge_features_per_pass": edge_features}
+    graph.destroy()
+    del layer, G
+    torch.cuda.empty_cache()
+    return res, (p if keep_problem else None)
 
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32", help="table storage of the headline run")
+    ap.add_argument("--single", action="store_true", help="measure only the headline storage type")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrinks the graph (testing only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event pass")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one GPU's share of the layer); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2408_09697_amd as heta
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    heta.binding.load_library()
+
+    # one plain 1 GiB copy: the known-size reference for hardware byte counters in profiler runs
+    calib_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    calib_dst = torch.empty_like(calib_src)
+    for _ in range(3):
+        heta.heta_calibration_copy(calib_dst, calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+    torch.cuda.empty_cache()
+
+    want_cpu = not args.no_cpu_baseline
+    main_res, problem = measure(args.dtype, args, keep_problem=want_cpu and args.dtype == "f32")
+    scale_note = "" if args.scale == 1.0 else f" (scale {args.scale})"
     out = {
         "metric": "aggregated edge-features/sec (fwd+bwd), 1 GPU",
-        "value": 2.0 * edge_features / (ms_per_step * 1e-3),
+        "value": main_res["value"],
         "unit": "edge-features/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if args.dtype == "f32" else "bf16 storage, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"config 3: full-graph single layer, academic-shaped graph, {n_edges} edges, "
-                               f"7 relations, 128->256, mean, {args.dtype}" + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
-                   "edges": n_edges, "edge_features_per_pass": edge_features},
-        "edges_per_s": 2.0 * n_edges / (ms_per_step * 1e-3),
-        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
-        "ingest": {"ms": ingest_ms, "note": "heta_graph_create for all 7 relations (host validation, CSC build, schedules, upload); once per graph, outside the timed steps"},
-        "input_generation_s": gen_s,
-        "roofline": roofline,
-        "kernels": kernels,
+        "config": {"workload": f"config 3: full-graph single layer, academic-shaped graph, {main_res['edges']} edges, "
+                               f"7 relations, 128->256, mean, {args.dtype} tables{scale_note}",
+                   "edges": main_res["edges"], "edge_features_per_pass": main_res["edge_features_per_pass"]},
+        "edges_per_s": main_res["edges_per_s"],
+        "fwd_ms": main_res["fwd_ms"], "bwd_ms": main_res["bwd_ms"],
+        "ingest": {"ms": main_res["ingest_ms"],
+                   "note": "heta_graph_create for all 7 relations (host validation, CSC build, schedules, upload); "
+                           "once per graph, outside the timed steps"},
+        "input_generation_s": main_res["input_generation_s"],
+        "roofline": main_res["roofline"],
+        "kernels": main_res["kernels"],
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(p)
-        out["cpu_baseline"]["host_cores_visible"] = os.cpu_count()
+    if not args.single:
+        other = "bf16" if args.dtype == "f32" else "f32"
+        res, p2 = measure(other, args, keep_problem=want_cpu and other == "f32")
+        problem = problem or p2
+        out["bf16_storage" if other == "bf16" else "f32_storage"] = {
+            k: res[k] for k in ("value", "ms_per_step", "edges_per_s", "fwd_ms", "bwd_ms", "roofline", "kernels")}
+    if want_cpu:
+        if problem is None:
+            from gen import workloads
+            problem = workloads.config3("f32", scale=args.scale, upstream=False)
+        out["cpu_baseline"] = cpu_baseline(problem)
     print(json.dumps(out))
     return 0
 
