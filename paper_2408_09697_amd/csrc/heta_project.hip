@@ -36,7 +36,9 @@ using bf16_t = uint16_t;
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int BM = 128, BK = 32;
+constexpr int BM = 128;
+// BK, the k-values per tile, is a template parameter: 32, or 64 for the bf16 weight gradient,
+// whose long k loop is bound by per-tile overhead rather than by MFMA work.
 constexpr int kMaxSeg = 8;
 
 struct GemmSeg {
@@ -75,35 +77,73 @@ template <> __device__ __forceinline__ float convert<float, float>(float v) { re
 template <> __device__ __forceinline__ bf16_t convert<float, bf16_t>(float v) { return to_bf16(v); }
 template <> __device__ __forceinline__ bf16_t convert<bf16_t, bf16_t>(bf16_t v) { return v; }
 
-// LDS row stride in elements of CT: 32 k-values + 16 bytes of padding
-template <typename CT> struct LdsStride { static constexpr int value = BK + 16 / (int)sizeof(CT); };
+// ---- LDS tile layouts ------------------------------------------------------------------------------
+// A k-contiguous operand (element (r,k) at base[r*ld + k]) is kept r-major in LDS, rows of one
+// tile's k-values (128 bytes) padded by 16 bytes: copied with 128-bit stores, fragments read with one 128-bit load
+// (8 consecutive lanes fall on distinct banks).
+// An r-contiguous operand (element (r,k) at base[k*ld + r]) is kept k-major, exactly as it lies
+// in memory, so that global loads stay coalesced along r and LDS stores stay 128-bit:
+//   fp32 compute: Ls[k][r]; a fragment is four 32-bit reads (lanes along r: conflict-free);
+//   bf16 compute: Ls[k/2][r] of 32-bit words holding the pair (k, k+1); a fragment is four
+//   32-bit reads that deliver eight consecutive k-values.
+// The k index a lane supplies to an MFMA only has to agree between the A and B fragments; all
+// three layouts hand lane (half, l32) the k-values kk + (4|8)*half + 0..(3|7) in order.
+template <typename CT, int BK> struct LdsStride { static constexpr int value = BK + 16 / (int)sizeof(CT); };
+template <typename CT, bool RC, int ROWS, int BK> struct LdsTile {
+    static constexpr int elems = RC ? BK * ROWS : ROWS * LdsStride<CT, BK>::value;
+};
 
-// Moves a [ROWS x BK] operand tile global -> registers -> LDS with NT threads.
-//   RC == false: element (r,k) at base[r*ld + k]   (k-contiguous)
-//   RC == true : element (r,k) at base[k*ld + r]   (r-contiguous, transposed into LDS)
-// Every thread owns NCH 16-byte chunks at fixed (r,k) positions of the tile; its global
-// addresses are set up once per segment and advanced by one tile per load().  load() only
-// issues the global loads; masking of ragged edges and conversion happen in store().
+template <bool RC, int ROWS, int BK>
+__device__ __forceinline__ void frag_f32(const float *tile, int r, int kk, int half, float f[4])
+{
+    if (RC) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) f[t] = tile[(kk + 4 * half + t) * ROWS + r];
+    } else {
+        const float4 v = *reinterpret_cast<const float4 *>(&tile[r * LdsStride<float, BK>::value + kk + 4 * half]);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+}
+
+template <bool RC, int ROWS, int BK>
+__device__ __forceinline__ uint4 frag_bf16(const bf16_t *tile, int r, int kk, int half)
+{
+    if (RC) {
+        const uint32_t *w = reinterpret_cast<const uint32_t *>(tile);
+        const int kp = kk / 2 + 4 * half;
+        return make_uint4(w[(kp + 0) * ROWS + r], w[(kp + 1) * ROWS + r], w[(kp + 2) * ROWS + r], w[(kp + 3) * ROWS + r]);
+    }
+    return *reinterpret_cast<const uint4 *>(&tile[r * LdsStride<bf16_t, BK>::value + kk + 8 * half]);
+}
+
+// Moves a [ROWS x BK] operand tile global -> registers -> LDS with NT threads (layouts above).
+// Every thread owns a fixed set of 16-byte chunks of the tile; its global addresses are set up
+// once per segment and advanced by one tile per load().  load() only issues the global loads;
+// masking of ragged edges, conversion and (for bf16 pairs) interleaving happen in store().
 // VEC selects 128-bit loads (rows 16-byte aligned) against element-wise loads.
-template <typename S, typename CT, bool RC, int ROWS, int NT, bool VEC>
+template <typename S, typename CT, bool RC, int ROWS, int NT, bool VEC, int BK>
 struct TileLoader {
+    static constexpr bool PAIR = RC && sizeof(CT) == 2;
     static constexpr int E = 16 / (int)sizeof(S);
-    static constexpr int NCH = ROWS * BK / E / NT;
-    static constexpr int SA = LdsStride<CT>::value;
-    static_assert(NCH >= 1, "tile too small for the workgroup");
-    const S *ptr[NCH];
-    int64_t step;
-    uint4 raw[NCH];
-    int left[NCH]; // valid elements of the chunk (0 = nothing loaded)
+    static constexpr int CPR = ROWS / E;                                 // chunks along r (r-contiguous operands)
+    static constexpr int ITEMS = PAIR ? (BK / 2) * CPR : ROWS * BK / E;  // work items per tile
+    static constexpr int NI = (ITEMS + NT - 1) / NT;                     // items per thread
+    static constexpr int LPI = PAIR ? 2 : 1;                             // global chunks per item
+    static constexpr int SA = LdsStride<CT, BK>::value;
+    const S *ptr[NI];
+    int64_t step, ld_;
+    uint4 raw[NI][LPI];
+    int left[NI][LPI]; // valid elements of the chunk (0 = nothing loaded)
 
-    __device__ __forceinline__ static int row_of(int q) { return RC ? (q / BK) * E : q / (BK / E); }
-    __device__ __forceinline__ static int k_of(int q) { return RC ? q % BK : (q % (BK / E)) * E; }
+    __device__ __forceinline__ static int row_of(int q) { return RC ? (q % CPR) * E : q / (BK / E); }
+    __device__ __forceinline__ static int k_of(int q) { return RC ? (q / CPR) * LPI : (q % (BK / E)) * E; }
 
     __device__ __forceinline__ void init(const S *base, int64_t ld, int64_t r0, int64_t k0, int tid)
     {
         step = RC ? BK * ld : BK;
+        ld_ = ld;
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int q = tid + NT * i;
             const int64_t gr = r0 + row_of(q), gk = k0 + k_of(q);
             ptr[i] = RC ? base + gk * ld + gr : base + gr * ld + gk;
@@ -114,21 +154,25 @@ struct TileLoader {
     __device__ __forceinline__ void load(int rows_left, int k_left, int tid)
     {
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int q = tid + NT * i;
-            const int lr = rows_left - row_of(q), lk = k_left - k_of(q);
-            const bool in = lr > 0 && lk > 0;
-            left[i] = in ? min(E, RC ? lr : lk) : 0;
-            raw[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (in) {
-                if (VEC) {
-                    raw[i] = *reinterpret_cast<const uint4 *>(ptr[i]);
-                } else {
-                    union { uint4 u; S s[E]; } t;
-                    t.u = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-                    for (int j = 0; j < E; ++j) if (j < left[i]) t.s[j] = ptr[i][j];
-                    raw[i] = t.u;
+            for (int l = 0; l < LPI; ++l) {
+                const int lr = rows_left - row_of(q), lk = k_left - (k_of(q) + l);
+                const bool in = (ITEMS % NT == 0 || q < ITEMS) && lr > 0 && lk > 0;
+                left[i][l] = in ? min(E, RC ? lr : lk) : 0;
+                raw[i][l] = make_uint4(0u, 0u, 0u, 0u);
+                if (in) {
+                    const S *src = ptr[i] + (l ? ld_ : 0);
+                    if (VEC) {
+                        raw[i][l] = *reinterpret_cast<const uint4 *>(src);
+                    } else {
+                        union { uint4 u; S s[E]; } t;
+                        t.u = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+                        for (int j = 0; j < E; ++j) if (j < left[i][l]) t.s[j] = src[j];
+                        raw[i][l] = t.u;
+                    }
                 }
             }
             ptr[i] += step;
@@ -138,22 +182,34 @@ struct TileLoader {
     __device__ __forceinline__ void store(CT *lds, int tid) const
     {
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int q = tid + NT * i;
-            union { uint4 u; S s[E]; } t;
-            t.u = raw[i];
-            if (VEC && left[i] < E) { // a chunk that straddles the edge: the load brought in padding
+            if (ITEMS % NT != 0 && q >= ITEMS) continue;
+            union Chunk { uint4 u; S s[E]; } t[LPI];
 #pragma unroll
-                for (int j = 0; j < E; ++j) if (j >= left[i]) t.s[j] = S(0);
+            for (int l = 0; l < LPI; ++l) {
+                t[l].u = raw[i][l];
+                if (VEC && left[i][l] < E) { // a chunk that straddles the edge: the load brought in padding
+#pragma unroll
+                    for (int j = 0; j < E; ++j) if (j >= left[i][l]) t[l].s[j] = S(0);
+                }
             }
             const int r = row_of(q), k = k_of(q);
-            if (RC) {
+            if (PAIR) {
+                uint32_t w[E];
 #pragma unroll
-                for (int j = 0; j < E; ++j) lds[(r + j) * SA + k] = convert<S, CT>(t.s[j]);
+                for (int j = 0; j < E; ++j)
+                    w[j] = static_cast<uint32_t>(convert<S, bf16_t>(t[0].s[j])) |
+                           (static_cast<uint32_t>(convert<S, bf16_t>(t[LPI - 1].s[j])) << 16);
+                uint32_t *dst = reinterpret_cast<uint32_t *>(lds) + (k / 2) * ROWS + r;
+#pragma unroll
+                for (int j = 0; j < E; j += 4) *reinterpret_cast<uint4 *>(dst + j) = make_uint4(w[j], w[j + 1], w[j + 2], w[j + 3]);
+            } else if (RC) {
+                *reinterpret_cast<uint4 *>(lds + k * ROWS + r) = t[0].u; // fp32 compute: S == CT == float
             } else {
                 CT tmp[E];
 #pragma unroll
-                for (int j = 0; j < E; ++j) tmp[j] = convert<S, CT>(t.s[j]);
+                for (int j = 0; j < E; ++j) tmp[j] = convert<S, CT>(t[0].s[j]);
                 CT *dst = lds + r * SA + k;
                 if (sizeof(CT) * E == 16) *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(tmp);
                 else *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(tmp);
@@ -162,13 +218,12 @@ struct TileLoader {
     }
 };
 
-template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN, bool VEC>
+template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN, bool VEC, int BK>
 __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
 {
     constexpr int NT = 128 * WN, BN = 64 * WN;
-    constexpr int S = LdsStride<CT>::value;
-    __shared__ __attribute__((aligned(16))) CT As[BM * S];
-    __shared__ __attribute__((aligned(16))) CT Bs[BN * S];
+    __shared__ __attribute__((aligned(16))) CT As[LdsTile<CT, A_RC, BM, BK>::elems];
+    __shared__ __attribute__((aligned(16))) CT Bs[LdsTile<CT, B_RC, BN, BK>::elems];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave / WN) * 64, wn = (wave % WN) * 64;
     const int half = lane >> 5, l32 = lane & 31;
@@ -198,8 +253,8 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    TileLoader<SA_T, CT, A_RC, BM, NT, VEC> la;
-    TileLoader<SB_T, CT, B_RC, BN, NT, VEC> lb;
+    TileLoader<SA_T, CT, A_RC, BM, NT, VEC, BK> la;
+    TileLoader<SB_T, CT, B_RC, BN, NT, VEC, BK> lb;
 
     // The tile sequence runs over the k range of this split in every segment of the block.
     // (ls, lk, lend) describe the tile whose loads are issued next.
@@ -238,31 +293,27 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
         if constexpr (sizeof(CT) == 4) {
 #pragma unroll
             for (int kk = 0; kk < BK; kk += 8) {
-                union F4 { float4 v; float f[4]; } a[2], b[2];
+                float a[2][4], b[2][4];
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    a[i].v = *reinterpret_cast<const float4 *>(&As[(wm + i * 32 + l32) * S + kk + 4 * half]);
+                for (int i = 0; i < 2; ++i) frag_f32<A_RC, BM, BK>(As, wm + i * 32 + l32, kk, half, a[i]);
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    b[j].v = *reinterpret_cast<const float4 *>(&Bs[(wn + j * 32 + l32) * S + kk + 4 * half]);
+                for (int j = 0; j < 2; ++j) frag_f32<B_RC, BN, BK>(Bs, wn + j * 32 + l32, kk, half, b[j]);
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
 #pragma unroll
                         for (int j = 0; j < 2; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].f[t], b[j].f[t], acc[i][j], 0, 0, 0);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[j][t], acc[i][j], 0, 0, 0);
             }
         } else {
 #pragma unroll
             for (int kk = 0; kk < BK; kk += 16) {
                 union Frag { uint4 u; bf16x8 v; } a[2], b[2];
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    a[i].u = *reinterpret_cast<const uint4 *>(&As[(wm + i * 32 + l32) * S + kk + 8 * half]);
+                for (int i = 0; i < 2; ++i) a[i].u = frag_bf16<A_RC, BM, BK>(As, wm + i * 32 + l32, kk, half);
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    b[j].u = *reinterpret_cast<const uint4 *>(&Bs[(wn + j * 32 + l32) * S + kk + 8 * half]);
+                for (int j = 0; j < 2; ++j) b[j].u = frag_bf16<B_RC, BN, BK>(Bs, wn + j * 32 + l32, kk, half);
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -335,7 +386,7 @@ static bool vec_ok(const void *ptr, int64_t ld, heta_dtype dt)
 }
 
 template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN, bool VEC>
-static heta_status launch_gemm(GemmParams &p, hipStream_t st)
+static heta_status launch_gemm(GemmParams &p, hipStream_t st, int bk)
 {
     constexpr int BN = 64 * WN;
     int64_t mt = 0, nt = 0;
@@ -363,13 +414,17 @@ static heta_status launch_gemm(GemmParams &p, hipStream_t st)
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
     ProfScope prof(sizeof(CT) == 4 ? (p.partial ? "gemm_wgrad_f32" : "gemm_f32") : (p.partial ? "gemm_wgrad_bf16" : "gemm_bf16"),
                    st, bytes, flops);
-    hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN, VEC>), dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
+    if (sizeof(CT) == 2 && A_RC && B_RC && bk == 64)
+        hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN, VEC, (sizeof(CT) == 2 && A_RC && B_RC) ? 64 : 32>),
+                           dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
+    else
+        hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN, VEC, 32>), dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
     HETA_LAUNCH_CHECK("gemm_kernel");
     return HETA_OK;
 }
 
 template <bool A_RC, bool B_RC>
-static heta_status dispatch_gemm(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, hipStream_t st)
+static heta_status dispatch_gemm(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, hipStream_t st, int bk = 32)
 {
     int64_t n_max = 0;
     bool vec = true; // 128-bit loads need every operand of the launch to qualify
@@ -379,10 +434,10 @@ static heta_status dispatch_gemm(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt
     }
     const bool wide = n_max > 128;
 #define HETA_GEMM(CT, SA, SB)                                                                                   \
-    return wide ? (vec ? launch_gemm<CT, SA, A_RC, SB, B_RC, 4, true>(p, st)                                    \
-                       : launch_gemm<CT, SA, A_RC, SB, B_RC, 4, false>(p, st))                                  \
-                : (vec ? launch_gemm<CT, SA, A_RC, SB, B_RC, 2, true>(p, st)                                    \
-                       : launch_gemm<CT, SA, A_RC, SB, B_RC, 2, false>(p, st))
+    return wide ? (vec ? launch_gemm<CT, SA, A_RC, SB, B_RC, 4, true>(p, st, bk)                                    \
+                       : launch_gemm<CT, SA, A_RC, SB, B_RC, 4, false>(p, st, bk))                                  \
+                : (vec ? launch_gemm<CT, SA, A_RC, SB, B_RC, 2, true>(p, st, bk)                                    \
+                       : launch_gemm<CT, SA, A_RC, SB, B_RC, 2, false>(p, st, bk))
     if (a_dt == HETA_F32 && b_dt == HETA_F32) { HETA_GEMM(float, float, float); }
     if (a_dt == HETA_F32 && b_dt == HETA_BF16) { HETA_GEMM(bf16_t, float, bf16_t); }
     if (a_dt == HETA_BF16 && b_dt == HETA_F32) { HETA_GEMM(bf16_t, bf16_t, float); }
@@ -465,9 +520,13 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
         out_elems += static_cast<int64_t>(d_in[s]) * d_out;
         tiles += ((d_in[s] + BM - 1) / BM) * ((d_out + BN - 1) / BN);
     }
-    // split the graph rows so that about 512 workgroups run, each with at least 16 k-tiles
+    // Split the graph rows so that the workgroups fill the chip exactly once (256 CUs x 2 resident
+    // 512-thread workgroups, or x 4 of 256 threads) and never spill into a second, nearly empty
+    // round; each split keeps at least 16 k-tiles.
+    const int64_t BK = in_dt == HETA_F32 ? 32 : 64;
     const int64_t k_tiles = (n_rows + BK - 1) / BK;
-    int64_t n_split = std::max<int64_t>(1, std::min<int64_t>((k_tiles + 15) / 16, (512 + tiles - 1) / tiles));
+    const int64_t resident = d_out > 128 ? 512 : 1024;
+    int64_t n_split = std::max<int64_t>(1, std::min<int64_t>((k_tiles + 15) / 16, resident / std::max<int64_t>(1, tiles)));
     const int64_t tiles_per_split = std::max<int64_t>(1, (k_tiles + n_split - 1) / n_split);
     n_split = std::max<int64_t>(1, (k_tiles + tiles_per_split - 1) / tiles_per_split);
     heta_status e = ensure_workspace(g, static_cast<size_t>(n_split) * out_elems * sizeof(float));
@@ -486,7 +545,7 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     p.k_per_split = tiles_per_split * BK;
     p.n_split = static_cast<int>(n_split);
     p.partial = 1;
-    e = dispatch_gemm<true, true>(p, in_dt, HETA_F32, st);
+    e = dispatch_gemm<true, true>(p, in_dt, HETA_F32, st, static_cast<int>(BK));
     if (e != HETA_OK) return e;
     for (int s = 0; s < n_seg; ++s) {
         const int64_t total = static_cast<int64_t>(d_in[s]) * d_out;
