@@ -89,3 +89,69 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
     """float32 array whose every value is exactly representable in bfloat16."""
     return bf16_bits_to_f32(f32_to_bf16_bits(x))
+
+
+# ---- counter-based tables: value = f(key, row, column), identical on host and device -----------
+# Tables too large to build on the host (tens of GB) are filled on the GPU with torch integer
+# ops; the host regenerates only the rows a test touches.  Integer mixing (splitmix64), one
+# int -> float conversion and one fp32 multiply: no transcendental function, so both sides
+# produce the same bits.  "normal": sum of four 16-bit uniforms, centred and scaled to unit
+# variance; "embedding": one 16-bit uniform mapped to (-0.1, 0.1).
+
+_SM_A, _SM_B, _SM_C = 0x9E3779B97F4A7C15, 0xBF58476D1CE4E5B9, 0x94D049BB133111EB
+_NORMAL_SCALE = np.float32(1.0 / 37837.0)       # 1 / std of the sum of four uniforms on [0, 65535]
+_EMB_SCALE = np.float32(0.1 / 65535.0)
+
+
+def table_key(workload: str, name: str, seed: int = MASTER_SEED) -> int:
+    return _key(workload, name, 0, seed) & ((1 << 63) - 1)
+
+
+def hashed_rows(key: int, rows: np.ndarray, d: int, kind: str) -> np.ndarray:
+    """float32 [len(rows), d] of the counter-based table `key` (host side)."""
+    rows = np.asarray(rows, dtype=np.uint64)
+    x = rows[:, None] * np.uint64(d) + np.arange(d, dtype=np.uint64)[None, :] + np.uint64(key)
+    with np.errstate(over="ignore"):
+        z = x + np.uint64(_SM_A)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(_SM_B)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(_SM_C)
+        z = z ^ (z >> np.uint64(31))
+    m = np.uint64(0xFFFF)
+    if kind == "normal":
+        s = (z & m) + ((z >> np.uint64(16)) & m) + ((z >> np.uint64(32)) & m) + ((z >> np.uint64(48)) & m)
+        return (s.astype(np.int64) - 131070).astype(np.float32) * _NORMAL_SCALE
+    if kind == "embedding":
+        a = (z & m).astype(np.int64)
+        return (2 * a - 65535).astype(np.float32) * _EMB_SCALE
+    raise ValueError(kind)
+
+
+def hashed_table_device(key: int, n_rows: int, d: int, kind: str, out, chunk_elems: int = 1 << 27) -> None:
+    """Fills the torch device tensor `out[:n_rows, :d]` (fp32 or bf16) with the same table."""
+    import torch
+
+    def s64(v: int) -> int:                      # the same 64 bits as a signed integer
+        return v - (1 << 64) if v >= (1 << 63) else v
+
+    def lsr(z, s: int):                          # logical shift right on int64
+        return (z >> s) & ((1 << (64 - s)) - 1)
+
+    dev = out.device
+    cols = torch.arange(d, dtype=torch.int64, device=dev)[None, :]
+    rows_per = max(1, chunk_elems // d)
+    for r0 in range(0, n_rows, rows_per):
+        r1 = min(n_rows, r0 + rows_per)
+        x = torch.arange(r0, r1, dtype=torch.int64, device=dev)[:, None] * d + cols + s64(key)
+        z = x + s64(_SM_A)
+        z = (z ^ lsr(z, 30)) * s64(_SM_B)
+        z = (z ^ lsr(z, 27)) * s64(_SM_C)
+        z = z ^ lsr(z, 31)
+        if kind == "normal":
+            s = (z & 0xFFFF) + (lsr(z, 16) & 0xFFFF) + (lsr(z, 32) & 0xFFFF) + (lsr(z, 48) & 0xFFFF)
+            v = (s - 131070).to(torch.float32) * float(_NORMAL_SCALE)
+        elif kind == "embedding":
+            v = (2 * (z & 0xFFFF) - 65535).to(torch.float32) * float(_EMB_SCALE)
+        else:
+            raise ValueError(kind)
+        out[r0:r1, :d] = v.to(out.dtype)
+        del x, z, v

@@ -168,3 +168,107 @@ def config4(scale: float = 1.0, exact: bool = False) -> LayerProblem:
     tabs = _tables(g, wl, "bf16", exact)
     W = _weights(g, lambda i: nts[g.relations[i].src_type].feat_dim, 256, wl, "bf16", exact)
     return LayerProblem("config4", g, "sum", "bf16", tabs, W, 256, _upstream(g, 256, wl, exact))
+
+
+# ---- sampled mini-batch problems (configs 2 and 5) ---------------------------------------------
+
+@dataclass
+class MiniBatchProblem:
+    """A k-layer model over sampled blocks: layer l runs on blocks[l]; layer 0 reads the node-type
+    tables through the block's src_gid lists, layer l > 0 reads layer l-1's output embeddings.
+    ReLU follows every layer but the last.  The upstream gradient G is given on the seeds."""
+    name: str
+    base: HetGraph
+    blocks: list                          # gen.sampler.Block, outermost first
+    op: str
+    storage: str
+    W: List[List[np.ndarray]]             # per layer, per relation: [d_in(l), d_hidden]
+    d_hidden: int
+    seed_type: int
+    G: np.ndarray                         # [n_seeds, d_hidden]
+    tables: Optional[List[np.ndarray]] = None          # host tables per base type, or None when counter-based
+    table_keys: Optional[List[int]] = None             # counter-based tables (gen.rng.hashed_rows)
+    table_kinds: Optional[List[str]] = None
+
+    def table_rows(self, t: int, ids: np.ndarray) -> np.ndarray:
+        """float32 rows `ids` of base type t's table, as stored (bf16-exact when storage is bf16)."""
+        if self.tables is not None:
+            return self.tables[t][ids]
+        x = rng.hashed_rows(self.table_keys[t], ids, self.base.ntypes[t].feat_dim, self.table_kinds[t])
+        return _maybe_bf16(x, self.storage)
+
+    def layer_problem(self, l: int, prev_H: Optional[Dict[int, np.ndarray]] = None) -> LayerProblem:
+        """The LayerProblem of layer l with compact host tables (row i = i-th source of the block).
+        prev_H: layer l-1's output per block node type (destination roles), needed for l > 0."""
+        b = self.blocks[l]
+        T = b.n_base_types
+        tabs = []
+        for k in range(2 * T):
+            if k >= T:
+                tabs.append(np.zeros((0, 1), dtype=np.float32))
+            elif l == 0:
+                tabs.append(self.table_rows(k, b.src_gid[k]))
+            else:
+                h = prev_H.get(T + k)
+                n = b.graph.ntypes[k].num_nodes
+                assert h is not None or n == 0, "a source type of an inner layer has no embedding"
+                tabs.append(h if h is not None else np.zeros((0, self.d_hidden)))
+        last = l == len(self.blocks) - 1
+        G = {T + self.seed_type: self.G} if last else {}
+        return LayerProblem(f"{self.name}/L{l + 1}", b.graph, self.op, self.storage, tabs, self.W[l], self.d_hidden,
+                            G, relu=not last)
+
+
+def _minibatch(name: str, base: HetGraph, seed_type: int, n_seeds: int, fanouts: List[int], d_hidden: int,
+               storage: str, wl: str, tables, keys, kinds) -> MiniBatchProblem:
+    from .sampler import sample_blocks
+    g = rng.stream(wl, "seeds")
+    seeds = np.sort(g.choice(base.ntypes[seed_type].num_nodes, size=n_seeds, replace=False)).astype(np.int64)
+    blocks = sample_blocks(base, seed_type, seeds, fanouts, wl)
+    W = []
+    for l in range(len(fanouts)):
+        d_in = lambda i, l=l: base.ntypes[base.relations[i].src_type].feat_dim if l == 0 else d_hidden
+        W.append(_weights(base, d_in, d_hidden, f"{wl}/L{l + 1}", storage, False))
+    G = rng.normal_table(n_seeds, d_hidden, wl, "G/seeds")
+    return MiniBatchProblem(name, base, blocks, "mean", storage, W, d_hidden, seed_type, G,
+                            tables=tables, table_keys=keys, table_kinds=kinds)
+
+
+def config2(scale: float = 1.0) -> MiniBatchProblem:
+    """Sampled 2-layer mini-batch on the academic-shaped graph of config 3: 1,024 seed papers,
+    fanouts [25, 20] (seed hop 20), hidden 256, mean, fp32."""
+    gwl = f"config3/{scale:g}"
+    base = academic_graph(scale, 2.1, gwl)
+    tabs = _tables(base, gwl, "f32", False)
+    n_seeds = min(1024, base.ntypes[0].num_nodes // 2)
+    return _minibatch("config2", base, 0, n_seeds, [25, 20], 256, "f32", f"config2/{scale:g}", tabs, None, None)
+
+
+def mag_graph(scale: float = 1.0, workload: str = "config5") -> HetGraph:
+    """paper / author / institution with 768-wide vectors; cites, writes, affiliated with power-law
+    destination in-degree (exponent 1.9) and uniform sources, plus the exact transposes of the
+    latter two (5 relations, 400 M edges at scale 1)."""
+    n = lambda x: max(4, int(round(x * scale)))
+    nts = [NodeType("paper", n(30_000_000), 768, False), NodeType("author", n(15_000_000), 768, True),
+           NodeType("institution", n(100_000), 768, True)]
+    P, A, I = 0, 1, 2
+    N = [t.num_nodes for t in nts]
+    g = HetGraph(nts)
+    cites = power_law_relation("cites", P, P, N[P], N[P], n(240_000_000), 1.9, workload)
+    writes = power_law_relation("writes", A, P, N[A], N[P], n(70_000_000), 1.9, workload)
+    affiliated = power_law_relation("affiliated", A, I, N[A], N[I], n(10_000_000), 1.9, workload)
+    g.relations += [cites, writes, affiliated, reverse_relation("rev_writes", writes, N[A]),
+                    reverse_relation("rev_affiliated", affiliated, N[A])]
+    return g
+
+
+def config5(scale: float = 1.0) -> MiniBatchProblem:
+    """One GPU's partition of a 240 M-node-shaped graph: sampled 2-layer mini-batch, 4,096 seed
+    papers, fanouts [25, 15], 768 -> 1024 -> 1024, mean, bf16 tables.  The tables are
+    counter-based (filled on the device; the host regenerates the rows it needs)."""
+    wl = f"config5/{scale:g}"
+    base = mag_graph(scale, wl)
+    keys = [rng.table_key(wl, f"table/{t.name}") for t in base.ntypes]
+    kinds = ["embedding" if t.learnable else "normal" for t in base.ntypes]
+    n_seeds = min(4096, base.ntypes[0].num_nodes // 2)
+    return _minibatch("config5", base, 0, n_seeds, [25, 15], 1024, "bf16", wl, None, keys, kinds)

@@ -85,9 +85,14 @@ def aggregate_fwd(src, dst, n_dst: int, H0: np.ndarray, op: str,
     assert op in ("sum", "mean")
     src, dst = _edges(src, dst)
     H0 = np.asarray(H0)
-    assert H0.dtype in (np.float32, np.float64) and H0.ndim == 2 and H0.strides[1] == H0.itemsize
+    assert H0.dtype in (np.float32, np.float64) and H0.ndim == 2
+    if H0.shape[0] == 0:          # an empty table (a source type nobody sampled): strides carry no meaning
+        H0 = np.zeros((0, H0.shape[1]), dtype=H0.dtype)
+        ld = H0.shape[1]
+    else:
+        assert H0.strides[1] == H0.itemsize
+        ld = H0.strides[0] // H0.itemsize
     d = H0.shape[1] if d is None else d
-    ld = H0.strides[0] // H0.itemsize
     if gid is not None:
         gid = np.ascontiguousarray(gid, dtype=np.int64)
         assert src.size == 0 or src.max() < gid.size

@@ -141,3 +141,114 @@ def oracle_input_grad_rows(p, s: int, rows: np.ndarray, G):
                                     dM, "sum")
         out = part if out is None else out + part
     return out
+
+
+# ---- sampled mini-batch models (several layers over blocks) -------------------------------------
+# A ReLU between two layers makes the backward pass discontinuous in the forward values: an
+# embedding whose magnitude is below the forward tolerance may legitimately come out on either
+# side of zero, and a single flipped decision changes whole gradient entries.  As with finite
+# differences, the check stays away from the kink: the upstream gradient handed to an inner
+# layer is zeroed (on both sides, from the ORACLE's embeddings only) wherever the oracle's
+# pre-activation magnitude is within the forward tolerance of zero.
+
+def kink_guard(H_ref: np.ndarray, tol: float) -> np.ndarray:
+    """True where the sign of the embedding is decidable at forward tolerance `tol`."""
+    if H_ref.shape[0] == 0:
+        return np.zeros(H_ref.shape, dtype=bool)
+    scale = np.maximum(1.0, np.abs(H_ref).max(axis=1, keepdims=True))
+    return np.abs(H_ref) > tol * scale
+
+
+def oracle_minibatch(mb, tol: float):
+    """Forward and backward of the whole k-layer model with the oracle.  Returns per layer the
+    LayerResult, (dW, dH0), and the kink guards per layer and destination type."""
+    import oracle
+    fwd, probs = [], []
+    prev = None
+    for l in range(len(mb.blocks)):
+        p = mb.layer_problem(l, prev)
+        r = oracle.layer_forward(p)
+        prev = r.H
+        fwd.append(r)
+        probs.append(p)
+    guards = [{t: kink_guard(h, tol) for t, h in f.H.items()} for f in fwd]
+    out = []
+    T = mb.blocks[0].n_base_types
+    G = None
+    for l in reversed(range(len(mb.blocks))):
+        p = probs[l]
+        if G is None:
+            G = dict(p.G)
+        for t, nt in enumerate(p.graph.ntypes):      # destination roles without an upstream gradient
+            if t >= T and t not in G:
+                G[t] = np.zeros((nt.num_nodes, mb.d_hidden))
+        dW, dH0, _ = oracle.layer_backward(p, fwd[l], G)
+        out.append((dW, dH0))
+        if l > 0:                                    # gradient of layer l-1's outputs, away from the kink
+            G = {T + s: g * guards[l - 1][T + s] for s, g in dH0.items() if (T + s) in guards[l - 1]}
+    out.reverse()
+    return fwd, out, guards
+
+
+def run_minibatch_on_gpu(mb, tables_dev, guards):
+    """tables_dev: device tables per base node type (full size); guards: from oracle_minibatch.
+    Returns the layers (holding H, M), per layer (dW, dH0), and the graph handles."""
+    T = mb.blocks[0].n_base_types
+    op = heta.HETA_MEAN if mb.op == "mean" else heta.HETA_SUM
+    pad = 8 if mb.storage == "bf16" else 4
+    layers, graphs = [], []
+    prev_H = None
+    for l, b in enumerate(mb.blocks):
+        nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in b.graph.ntypes]
+        hg = heta.heta_graph_create(nts, [(r.src_type, r.dst_type, r.rowptr, r.col) for r in b.graph.relations])
+        graphs.append(hg)
+        rels = [i for i, r in enumerate(b.graph.relations) if b.graph.ntypes[r.dst_type].num_nodes > 0]
+        W = [dev_table(w, mb.storage, pad) for w in mb.W[l]]
+        if l == 0:
+            tabs = list(tables_dev) + [None] * T
+            gid = [torch.from_numpy(g).cuda() for g in b.src_gid[:T]] + [None] * T
+        else:
+            tabs = [prev_H.get(T + k) for k in range(T)] + [None] * T
+            gid = None
+        for i in rels:                                # a source type nobody sampled still needs a (dummy) table
+            s = b.graph.relations[i].src_type
+            if tabs[s] is None:
+                assert b.graph.ntypes[s].num_nodes == 0
+                tabs[s] = torch.zeros((1, mb.W[l][i].shape[0]), dtype=torch.float32, device="cuda")
+        layer = heta.RafLayer(hg, op, tabs, W, mb.d_hidden, src_gid=gid, relu=(l < len(mb.blocks) - 1), rels=rels)
+        prev_H = layer.forward()
+        layers.append(layer)
+    G = {T + mb.seed_type: torch.from_numpy(mb.G).cuda()}
+    grads = []
+    for l in reversed(range(len(layers))):
+        layer = layers[l]
+        dW, dH0, _ = layer.backward(G)
+        grads.append((dW, dH0))
+        if l > 0:
+            G = {}
+            for s, g in dH0.items():
+                if (T + s) in layers[l - 1].H:
+                    keep = torch.from_numpy(guards[l - 1][T + s]).cuda()
+                    G[T + s] = g * keep
+            for t, h in layers[l - 1].H.items():      # destination types of the layer below that got no gradient
+                if t not in G:
+                    G[t] = torch.zeros_like(h)
+    grads.reverse()
+    torch.cuda.synchronize()
+    return layers, grads, graphs
+
+
+def compare_minibatch(mb, layers, grads, ref_fwd, ref_bwd, tol):
+    for l, layer in enumerate(layers):
+        for t, h in ref_fwd[l].H.items():
+            if h.shape[0] == 0:
+                continue
+            assert_rows_close(layer.H[t].cpu().numpy(), h, tol, f"layer {l + 1} H[{t}]")
+        dW_ref, dH0_ref = ref_bwd[l]
+        dW, dH0 = grads[l]
+        for r in layer.rels:
+            assert_rows_close(dW[r].cpu().numpy(), dW_ref[r], tol, f"layer {l + 1} dW[{r}]")
+        for s, g in dH0.items():
+            if g.shape[0] == 0:
+                continue
+            assert_rows_close(g.cpu().numpy(), dH0_ref[s], tol, f"layer {l + 1} dH0[{s}]")

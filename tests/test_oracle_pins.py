@@ -371,3 +371,4 @@ def test_partial_aggregation_buffer_shape_from_communication_example():
     Z = oracle.project(oracle.aggregate_fwd(e, e, seeds, np.zeros((1, 8), np.float32), "mean"),
                        np.zeros((8, hidden)))
     assert Z.shape == (seeds, hidden)
+
