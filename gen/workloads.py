@@ -147,7 +147,7 @@ def config3(storage: str = "f32", scale: float = 1.0, exact: bool = False, upstr
 
 # ---- config 4: mixed widths --------------------------------------------------------------------
 
-def config4(scale: float = 1.0, exact: bool = False) -> LayerProblem:
+def config4(scale: float = 1.0, exact: bool = False, upstream: bool = True) -> LayerProblem:
     """Seven node types with widths {7, 24, 64e, 64e, 300, 512, 789} (e = learnable embedding),
     twelve independent power-law relations through the hub type T5, sum aggregation, per-relation
     W_r of shape d_src x 256, bf16 storage."""
@@ -167,7 +167,7 @@ def config4(scale: float = 1.0, exact: bool = False) -> LayerProblem:
         g.relations.append(power_law_relation(f"T5->{nts[t].name}", T5, t, N[T5], N[t], n(e), 2.0, wl))
     tabs = _tables(g, wl, "bf16", exact)
     W = _weights(g, lambda i: nts[g.relations[i].src_type].feat_dim, 256, wl, "bf16", exact)
-    return LayerProblem("config4", g, "sum", "bf16", tabs, W, 256, _upstream(g, 256, wl, exact))
+    return LayerProblem("config4", g, "sum", "bf16", tabs, W, 256, _upstream(g, 256, wl, exact) if upstream else {})
 
 
 # ---- sampled mini-batch problems (configs 2 and 5) ---------------------------------------------

@@ -130,3 +130,61 @@ def test_full_size_layer_sampled_rows(storage):
     rhs = np.vdot(x, bwd.cpu().numpy().astype(np.float64))
     assert abs(lhs - rhs) <= 1e-5 * max(1.0, abs(lhs))
     layer.g.destroy()
+
+
+class HashedRows:
+    """A [n, d] fp32 matrix defined by a counter-based generator: rows are produced on demand on
+    the host, and the whole matrix on the device, from the same key."""
+
+    def __init__(self, key: int, n: int, d: int, kind: str = "normal"):
+        self.key, self.n, self.d, self.kind = key, n, d, kind
+        self.shape = (n, d)
+
+    def __getitem__(self, ids):
+        return rng.hashed_rows(self.key, np.asarray(ids, dtype=np.int64), self.d, self.kind)
+
+    def device(self):
+        out = torch.empty((self.n, self.d), dtype=torch.float32, device="cuda")
+        rng.hashed_table_device(self.key, self.n, self.d, self.kind, out)
+        return out
+
+
+def test_full_size_config4_mixed_widths_sampled_rows():
+    """Config 4 at full size: 7 node types of widths 7 ... 789, 12 power-law relations, 40 M edges,
+    sum aggregation, bf16 tables.  Forward rows, input-gradient rows and two full weight gradients."""
+    tol = 2e-2
+    p = workloads.config4(scale=1.0, upstream=False)
+    g = p.graph
+    G_host = {t: HashedRows(rng.table_key("tests/fullsize", f"c4G/{t}"), g.ntypes[t].num_nodes, 256)
+              for t in range(len(g.ntypes)) if g.rels_into(t)}
+    p.G = G_host
+    layer = make_layer(p)
+    H = layer.forward()
+    G = {t: h.device() for t, h in G_host.items()}
+    dW, dH0, _ = layer.backward(G)
+    torch.cuda.synchronize()
+    for t in H:
+        deg = sum(np.diff(g.relations[i].rowptr) for i in g.rels_into(t))
+        rows = sample_rows(deg, 24, f"c4fwd/{t}")
+        ref_h, ref_m = oracle_forward_rows(p, t, rows)
+        idx = torch.from_numpy(rows).cuda()
+        assert_rows_close(H[t][idx].cpu().numpy(), ref_h, tol, f"H[{g.ntypes[t].name}]")
+        for i, m in ref_m.items():
+            assert_rows_close(layer.M[i][idx].float().cpu().numpy(), m, tol, f"M[{g.relations[i].name}]")
+    for s in dH0:
+        outdeg = np.zeros(g.ntypes[s].num_nodes, dtype=np.int64)
+        for i in g.rels_from(s):
+            outdeg += np.bincount(g.relations[i].col, minlength=outdeg.size)
+        rows = sample_rows(outdeg, 24, f"c4bwd/{s}")
+        ref = oracle_input_grad_rows(p, s, rows, G_host)
+        idx = torch.from_numpy(rows).cuda()
+        assert_rows_close(dH0[s][idx].cpu().numpy(), ref, tol, f"dH0[{g.ntypes[s].name}]")
+    for name in ("T5->T7", "T1->T5"):        # widths 300 -> 256 over 0.1 M rows and 7 -> 256 over 0.5 M rows
+        i = g.rel_index(name)
+        r = g.relations[i]
+        src, dst = r.edge_list()
+        n_t = g.ntypes[r.dst_type].num_nodes
+        M = oracle.aggregate_fwd(src, dst, n_t, p.tables[r.src_type], p.op)
+        ref = M.T @ G_host[r.dst_type][np.arange(n_t)].astype(np.float64)
+        assert_rows_close(dW[i].cpu().numpy(), ref, tol, f"dW[{name}]")
+    layer.g.destroy()
