@@ -71,7 +71,10 @@ def measure(storage: str, args, keep_problem: bool = False):
     from tests.harness import make_graph, make_layer
 
     t0 = time.perf_counter()
-    p = workloads.config3(storage, scale=args.scale, upstream=False)  # the upstream gradient is drawn on the device
+    if args.workload == "config4":   # mixed widths 7..789, 12 relations, 40 M edges, sum, bf16 tables
+        p = workloads.config4(scale=args.scale, upstream=False)
+    else:
+        p = workloads.config3(storage, scale=args.scale, upstream=False)  # the upstream gradient is drawn on the device
     gen_s = time.perf_counter() - t0
     t0 = time.perf_counter()
     graph = make_graph(p)
@@ -132,7 +135,7 @@ def measure(storage: str, args, keep_problem: bool = False):
             roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": k["GBps"] / PEAK_HBM_GBS}
         roofline["traffic"] = None
-        tf = os.path.join(ROOT, "profiles", f"traffic_config3_{storage}.json")
+        tf = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{storage}.json")
         if args.scale == 1.0 and os.path.exists(tf):
             # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command,
             # scaled by the 1 GiB calibration copy; written by paper_2408_09697_amd.rocprof_summary
@@ -161,6 +164,104 @@ def measure(storage: str, args, keep_problem: bool = False):
     return res, (p if keep_problem else None)
 
 
+def measure_minibatch(args):
+    """Config 5: one sampled 2-layer mini-batch (4,096 seeds, fanouts [25, 15], 768 -> 1024 -> 1024, mean,
+    bf16 tables) on one GPU's partition of the 240 M-node-shaped graph.  A step = building the two block
+    handles from the sampled CSRs, forward and backward of both layers."""
+    import numpy as np
+    import torch
+    import paper_2408_09697_amd as heta
+    from gen import rng, workloads
+    from tests.harness import dev_table
+
+    t0 = time.perf_counter()
+    mb = workloads.config5(args.scale)
+    gen_s = time.perf_counter() - t0
+    T = mb.blocks[0].n_base_types
+    tables = []
+    for t, nt in enumerate(mb.base.ntypes):
+        buf = torch.empty((nt.num_nodes, nt.feat_dim), dtype=torch.bfloat16, device="cuda")
+        rng.hashed_table_device(mb.table_keys[t], nt.num_nodes, nt.feat_dim, mb.table_kinds[t], buf)
+        tables.append(buf)
+    W = [[dev_table(w, "bf16", 8) for w in ws] for ws in mb.W]
+    gids = [torch.from_numpy(g).cuda() for g in mb.blocks[0].src_gid[:T]] + [None] * T
+    G_seed = torch.from_numpy(mb.G).cuda()
+    edge_features = sum(r.num_edges * (mb.base.ntypes[mb.base.relations[i].src_type].feat_dim if l == 0 else mb.d_hidden)
+                        for l, b in enumerate(mb.blocks) for i, r in enumerate(b.graph.relations))
+    n_edges = sum(r.num_edges for b in mb.blocks for r in b.graph.relations)
+
+    def build():
+        graphs = []
+        for b in mb.blocks:
+            nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in b.graph.ntypes]
+            graphs.append(heta.heta_graph_create(nts, [(r.src_type, r.dst_type, r.rowptr, r.col) for r in b.graph.relations]))
+        return graphs
+
+    def make_layers(graphs):
+        layers, prev = [], None
+        for l, b in enumerate(mb.blocks):
+            rels = [i for i, r in enumerate(b.graph.relations) if b.graph.ntypes[r.dst_type].num_nodes > 0]
+            tabs = (list(tables) + [None] * T) if l == 0 else ([prev.get(T + k) for k in range(T)] + [None] * T)
+            for i in rels:
+                s = b.graph.relations[i].src_type
+                if tabs[s] is None:
+                    tabs[s] = torch.zeros((1, mb.W[l][i].shape[0]), dtype=torch.float32, device="cuda")
+            layer = heta.RafLayer(graphs[l], heta.HETA_MEAN, tabs, W[l], mb.d_hidden, src_gid=gids if l == 0 else None,
+                                  relu=(l == 0), rels=rels)
+            prev = layer.H
+            layers.append(layer)
+        return layers
+
+    def compute(layers):
+        for layer in layers:
+            layer.forward()
+        G = {T + mb.seed_type: G_seed}
+        for l in reversed(range(len(layers))):
+            _, dH0, _ = layers[l].backward(G)
+            G = {T + s: g for s, g in dH0.items()}
+            if l > 0:
+                for t, h in layers[l - 1].H.items():
+                    if t not in G:
+                        G[t] = layers[l - 1]._Gact[t].zero_()
+
+    graphs = build()
+    layers = make_layers(graphs)
+    for _ in range(args.warmup):
+        compute(layers)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        compute(layers)
+    torch.cuda.synchronize()
+    compute_ms = (time.perf_counter() - t0) * 1e3 / max(1, args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for g in build():
+            g.destroy()
+    ingest_ms = (time.perf_counter() - t0) * 1e3 / max(1, args.steps)
+    heta.heta_profile_enable(True)
+    heta.heta_profile_reset()
+    for _ in range(args.steps):
+        compute(layers)
+    torch.cuda.synchronize()
+    stats = heta.heta_profile_read()
+    heta.heta_profile_enable(False)
+    kernels = {n: {"launches_per_step": s["launches"] / args.steps, "ms_per_step": s["total_ms"] / args.steps,
+                   "GBps": s["algorithmic_bytes"] / s["total_ms"] / 1e6,
+                   **({"TFLOPs": s["flops"] / s["total_ms"] / 1e9} if s["flops"] > 0 else {})} for n, s in stats.items()}
+    ms = compute_ms + ingest_ms
+    return {"metric": "aggregated edge-features/sec (fwd+bwd), 1 GPU", "value": 2.0 * edge_features / (ms * 1e-3),
+            "unit": "edge-features/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage, f32 accumulate",
+            "data": "synthetic",
+            "config": {"workload": f"config 5: sampled 2-layer mini-batch, {mb.G.shape[0]} seeds, fanouts [25, 15], "
+                                   f"768->1024->1024, mean, bf16 tables, {n_edges} sampled edges"
+                                   + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
+                       "edges": n_edges, "edge_features_per_pass": edge_features,
+                       "block_sizes": [[(t.name, t.num_nodes) for t in b.graph.ntypes] for b in mb.blocks]},
+            "compute_ms": compute_ms, "ingest_ms_per_batch": ingest_ms, "input_generation_s": gen_s, "kernels": kernels}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -168,6 +269,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32", help="table storage of the headline run")
     ap.add_argument("--single", action="store_true", help="measure only the headline storage type")
+    ap.add_argument("--workload", choices=["config3", "config4", "config5"], default="config3",
+                    help="config3 is the headline; config4 (mixed widths, bf16) and config5 (sampled 2-layer "
+                         "mini-batch on the 400 M-edge partition, bf16) are additional measurements")
     ap.add_argument("--scale", type=float, default=1.0, help="shrinks the graph (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event pass")
@@ -193,6 +297,11 @@ def main() -> int:
     del calib_src, calib_dst
     torch.cuda.empty_cache()
 
+    if args.workload == "config5":
+        print(json.dumps(measure_minibatch(args)))
+        return 0
+    if args.workload == "config4":
+        args.dtype, args.single, args.no_cpu_baseline = "bf16", True, True
     want_cpu = not args.no_cpu_baseline
     main_res, problem = measure(args.dtype, args, keep_problem=want_cpu and args.dtype == "f32")
     scale_note = "" if args.scale == 1.0 else f" (scale {args.scale})"
@@ -204,8 +313,10 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if args.dtype == "f32" else "bf16 storage, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"config 3: full-graph single layer, academic-shaped graph, {main_res['edges']} edges, "
-                               f"7 relations, 128->256, mean, {args.dtype} tables{scale_note}",
+        "config": {"workload": (f"config 3: full-graph single layer, academic-shaped graph, {main_res['edges']} edges, "
+                                f"7 relations, 128->256, mean, {args.dtype} tables{scale_note}") if args.workload == "config3"
+                   else (f"config 4: full-graph single layer, 7 node types of widths 7..789, {main_res['edges']} edges, "
+                         f"12 relations, d_src->256, sum, bf16 tables{scale_note}"),
                    "edges": main_res["edges"], "edge_features_per_pass": main_res["edge_features_per_pass"]},
         "edges_per_s": main_res["edges_per_s"],
         "fwd_ms": main_res["fwd_ms"], "bwd_ms": main_res["bwd_ms"],

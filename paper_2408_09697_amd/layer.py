@@ -58,12 +58,18 @@ class RafLayer:
                 if self.tables[t] is not None:
                     self.H0[t] = torch.empty((self.tables[t].shape[0], self.pre_proj[t].shape[1]),
                                              dtype=torch.float32, device=dev)
-        self.M = {r: torch.empty((graph.n_dst(r), self.d_rel[r]), dtype=m_dtype, device=dev) for r in self.rels}
-        self.dM = {r: torch.empty((graph.n_dst(r), self.d_rel[r]), dtype=torch.float32, device=dev) for r in self.rels}
+        # rows of every intermediate start on 16-byte boundaries (padded leading dimension), which
+        # keeps awkward widths (7, 300, 789, ...) on the library's 128-bit paths
+        def padded(n, d, dtype):
+            q = 16 // torch.empty((), dtype=dtype).element_size()
+            return torch.empty((n, (d + q - 1) // q * q), dtype=dtype, device=dev)[:, :d]
+
+        self.M = {r: padded(graph.n_dst(r), self.d_rel[r], m_dtype) for r in self.rels}
+        self.dM = {r: padded(graph.n_dst(r), self.d_rel[r], torch.float32) for r in self.rels}
         self.H = {t: torch.empty((graph.ntypes[t][0], d_out), dtype=torch.float32, device=dev)
                   for t in self.rels_into}
         self.dW = {r: torch.empty((self.d_rel[r], d_out), dtype=torch.float32, device=dev) for r in self.rels}
-        self.dH0 = {s: torch.empty((graph.ntypes[s][0], self.d_rel[rs[0]]), dtype=torch.float32, device=dev)
+        self.dH0 = {s: padded(graph.ntypes[s][0], self.d_rel[rs[0]], torch.float32)
                     for s, rs in self.rels_from.items()}
         self.dtable: Dict[int, torch.Tensor] = {}
         if self.pre_proj is not None:
