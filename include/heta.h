@@ -141,6 +141,11 @@ heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, h
                              int32_t d_out, int32_t transW, const float *row_scale, float *out,
                              int64_t ld_out, float beta, void *hip_stream);
 
+/* Testing / measurement switch (process-wide, not thread-safe): when on, every projection runs the
+ * register-staged kernel that otherwise only serves operands whose rows are not 16-byte aligned;
+ * off (the default) prefers the direct-to-LDS pipeline.  Results agree to rounding order. */
+heta_status heta_projection_force_staged(int32_t on);
+
 /* Weight gradient dW[0:d_in, 0:d_out] = beta * dW + in^T . gout, the sum running over the n_dst
  * rows of the relation in a fixed order (split over workgroups, then combined in order).
  * in: device [n_dst, ld_in] of in_dt (the saved M_r); gout: device fp32 [n_dst, ld_go];

@@ -28,7 +28,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
-           "heta_cross_rel_project_wgrad"]
+           "heta_cross_rel_project_wgrad", "heta_projection_force_staged"]
 
 
 class HetaError(RuntimeError):
@@ -420,6 +420,12 @@ def heta_profile_enable(on: bool) -> None:
     L = load_library()
     L.heta_profile_enable.argtypes = [ctypes.c_int32]
     _check(L.heta_profile_enable(int(bool(on))))
+
+
+def heta_projection_force_staged(on: bool) -> None:
+    L = load_library()
+    L.heta_projection_force_staged.argtypes = [ctypes.c_int32]
+    _check(L.heta_projection_force_staged(1 if on else 0))
 
 
 def heta_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -260,6 +260,15 @@ def test_run_to_run_bitwise_determinism(skew):
 
 # ---- a4 / a6: projection ------------------------------------------------------------------------------
 
+@pytest.fixture(params=["direct", "staged"])
+def gemm_path(request):
+    """Both projection kernels: the direct-to-LDS pipeline (default wherever operand rows are 16-byte
+    aligned) and the register-staged kernel (forced here, otherwise the fallback)."""
+    heta.heta_projection_force_staged(request.param == "staged")
+    yield request.param
+    heta.heta_projection_force_staged(False)
+
+
 PROJ_SHAPES = [(1000, 32, 32), (777, 128, 256), (300, 7, 256), (513, 24, 256), (400, 300, 256),
                (260, 789, 256), (129, 768, 1024), (64, 1024, 1024), (1, 5, 3), (2000, 64, 40)]
 
@@ -267,7 +276,7 @@ PROJ_SHAPES = [(1000, 32, 32), (777, 128, 256), (300, 7, 256), (513, 24, 256), (
 @pytest.mark.parametrize("n,d_in,d_out", PROJ_SHAPES)
 @pytest.mark.parametrize("in_s,w_s", [("f32", "f32"), ("bf16", "bf16"), ("f32", "bf16")])
 @pytest.mark.parametrize("trans", [False, True])
-def test_project(n, d_in, d_out, in_s, w_s, trans):
+def test_project(n, d_in, d_out, in_s, w_s, trans, gemm_path):
     x = rng.normal_table(n, d_in, "tests", f"px{n}")
     w = rng.normal_table(d_out, d_in, "tests", f"pw{n}") if trans else rng.normal_table(d_in, d_out, "tests", f"pw{n}")
     w = w * np.float32(1.0 / np.sqrt(d_in))
@@ -281,7 +290,7 @@ def test_project(n, d_in, d_out, in_s, w_s, trans):
 
 
 @pytest.mark.parametrize("pad", [1, 4])
-def test_project_row_scale_beta_and_odd_strides(pad):
+def test_project_row_scale_beta_and_odd_strides(pad, gemm_path):
     n, d_in, d_out = 333, 37, 45
     x = rng.normal_table(n, d_in, "tests", "rsx")
     w = rng.normal_table(d_in, d_out, "tests", "rsw")
@@ -297,7 +306,7 @@ def test_project_row_scale_beta_and_odd_strides(pad):
 @pytest.mark.parametrize("n,d_in,d_out", [(2000, 32, 32), (5000, 128, 256), (3000, 7, 256), (1500, 300, 256),
                                           (700, 789, 256), (40, 16, 8), (5000, 768, 1024)])
 @pytest.mark.parametrize("in_s", ["f32", "bf16"])
-def test_project_wgrad(n, d_in, d_out, in_s):
+def test_project_wgrad(n, d_in, d_out, in_s, gemm_path):
     rel = Relation("w", 0, 1, np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32))
     hg = heta.heta_graph_create([(4, 8, 0), (n, 8, 0)], [(0, 1, rel.rowptr, rel.col)])
     m = rng.normal_table(n, d_in, "tests", f"wgm{n}")
@@ -337,7 +346,7 @@ def test_cross_rel_reduce_and_act_bwd(d, k, relu):
 # ---- whole layers ---------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("mode", ["fused", "per_relation", "unfused"])
-def test_layer_config1(mode):
+def test_layer_config1(mode, gemm_path):
     p = workloads.config1()
     got = run_layer_on_gpu(p, mode=mode)
     ref_f = oracle.layer_forward(p)
@@ -366,7 +375,7 @@ def test_layer_config1_relation_split_equals_whole():
 
 @pytest.mark.parametrize("mode", ["fused", "per_relation"])
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
-def test_layer_config3_scaled(storage, mode):
+def test_layer_config3_scaled(storage, mode, gemm_path):
     p = workloads.config3(storage, scale=0.02)
     got = run_layer_on_gpu(p, mode=mode)
     ref_f = oracle.layer_forward(p)
@@ -374,7 +383,7 @@ def test_layer_config3_scaled(storage, mode):
     compare_layer(p, got, ref_f, ref_b, tol=TOL[storage])
 
 
-def test_layer_config4_scaled():
+def test_layer_config4_scaled(gemm_path):
     p = workloads.config4(scale=0.01)
     got = run_layer_on_gpu(p)
     ref_f = oracle.layer_forward(p)
@@ -394,7 +403,7 @@ def test_layer_with_relu_and_gid():
 
 @pytest.mark.parametrize("in_s,w_s", [("f32", "f32"), ("bf16", "bf16")])
 @pytest.mark.parametrize("d_out,relu", [(256, False), (40, True)])
-def test_cross_rel_project_family(in_s, w_s, d_out, relu):
+def test_cross_rel_project_family(in_s, w_s, d_out, relu, gemm_path):
     """Fused projection + cross-relation sum over relations of different widths, and its backward."""
     n = 1500
     widths = [7, 24, 64, 128, 300, 37]
