@@ -77,11 +77,16 @@ typedef struct {
 /* ---- graph ingest (HetG and its decomposition into mono-relation subgraphs, Section 2.1) ------
  * Validates every relation, copies its CSR to the device, computes in-degrees, builds the
  * transposed adjacency (CSC: for each source u the destinations of its out-edges in ascending
- * original edge position) and the degree-sorted row schedules both directions use.
+ * original edge position) and the degree-sorted row schedules both directions use (device
+ * kernels: a stable radix sort of (source, destination) pairs, scans, binary searches).
  * Synchronous.  The caller's arrays may be freed on return.  `*out` is written only on success. */
 heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels,
                               int32_t n_rels, uint32_t flags, heta_graph **out);
 heta_status heta_graph_destroy(heta_graph *g); /* NULL is accepted; synchronises the device */
+/* Testing switch (process-wide): 0 = relations of at least 2^17 edges + rows are ingested by device
+ * kernels and smaller ones on the host (the default), 1 = always on the host, 2 = always on the
+ * device.  Both paths produce identical index arrays. */
+heta_status heta_ingest_force(int32_t mode);
 
 /* Read-back of the derived index data into HOST buffers (for bit-exact checks). Synchronous. */
 heta_status heta_graph_get_csc(const heta_graph *g, int32_t rel, int64_t *colptr /* [n_src+1] */,
@@ -118,11 +123,12 @@ heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, c
  * gradients of the partial aggregations) ---------------------------------------------------------
  * grad_src[u, 0:d] = beta * grad_src[u, 0:d] + sum over e in CSC column u of c_e * grad_out[row[e], 0:d]
  * c_e = 1 (HETA_SUM) or 1/deg_r(row[e]) (HETA_MEAN).  A gather over the CSC: no atomics.
- * grad_out: device fp32 [n_dst, ld_go]; grad_src: device fp32 [n_src, ld_gs]; beta is 0 or 1
- * (1 accumulates the relations that share a source type, in the caller's call order). */
-heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, const float *grad_out,
-                                   int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs, float beta,
-                                   void *hip_stream);
+ * grad_out: device [n_dst, ld_go] of go_dt (fp32, or bf16 when the caller keeps dM_r in the
+ * storage type; accumulation is fp32 either way); grad_src: device fp32 [n_src, ld_gs]; beta is
+ * 0 or 1 (1 accumulates the relations that share a source type, in the caller's call order). */
+heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, const void *grad_out,
+                                   heta_dtype go_dt, int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs,
+                                   float beta, void *hip_stream);
 
 /* ---- per-relation projection (the per-relation weight matrices of R-GCN, Section 2.1) ---------
  * out[i, 0:d_out] = beta * out[i, 0:d_out] + s_i * sum_k in[i, k] * B[k, j],  i < n_rows,
@@ -167,13 +173,15 @@ heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_
                                    heta_act act, float *out, int64_t ld_out, float beta, void *hip_stream);
 /* Its backward, one launch each for all n relations into dst_type (Algorithm 1, local
  * backpropagation): dM[p] = gout . Ws[p]^T and dW[p] = beta * dW[p] + ins[p]^T . gout.
- * gout device fp32 [n_rows, ld_go]; dM[p] device fp32 [n_rows, ld_dm[p] >= d_in[p]];
- * dW[p] device fp32 [d_in[p], ld_dw[p] >= d_out]; the pointer arrays are HOST arrays.
+ * gout device fp32 [n_rows, ld_go]; dM[p] device [n_rows, ld_dm[p] >= d_in[p]] of dm_dt (fp32, or
+ * bf16: the fp32 accumulator is rounded once on the way out, for callers that store the [n x d]
+ * intermediates of a layer in the storage type); dW[p] device fp32 [d_in[p], ld_dw[p] >= d_out];
+ * the pointer arrays are HOST arrays.
  * The wgrad call uses the handle's workspace (may grow it, see heta_rel_aggregate_fwd). */
 heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, int32_t n, const float *gout,
                                        int64_t ld_go, int32_t d_out, const void *const *Ws, heta_dtype w_dt,
-                                       const int64_t *ld_w, const int32_t *d_in, float *const *dM,
-                                       const int64_t *ld_dm, void *hip_stream);
+                                       const int64_t *ld_w, const int32_t *d_in, void *const *dM,
+                                       heta_dtype dm_dt, const int64_t *ld_dm, void *hip_stream);
 heta_status heta_cross_rel_project_wgrad(heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
                                          heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
                                          const float *gout, int64_t ld_go, int32_t d_out, float *const *dW,

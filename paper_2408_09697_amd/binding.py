@@ -28,7 +28,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
-           "heta_cross_rel_project_wgrad", "heta_projection_force_staged"]
+           "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force"]
 
 
 class HetaError(RuntimeError):
@@ -67,7 +67,7 @@ def load_library() -> ctypes.CDLL:
     L.heta_feature_gather.argtypes = [vp, i32, i64, i32, i64, vp, i64, vp, i64, vp]
     L.heta_check_ids.argtypes = [vp, i64, i64, vp]
     L.heta_rel_aggregate_fwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, i64, vp, vp, i32, i64, vp]
-    L.heta_rel_aggregate_bwd.argtypes = [vp, i32, i32, vp, i64, i32, vp, i64, f32, vp]
+    L.heta_rel_aggregate_bwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, vp, i64, f32, vp]
     L.heta_project.argtypes = [i64, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i64, f32, vp]
     L.heta_rel_project.argtypes = [vp, i32, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i64, f32, vp]
     L.heta_rel_project_wgrad.argtypes = [vp, i32, vp, i32, i64, i32, vp, i64, i32, vp, i64, f32, vp]
@@ -242,7 +242,7 @@ def heta_rel_aggregate_bwd(g: Graph, rel: int, op: int, grad_out: torch.Tensor, 
     if grad_out.shape[0] < g.n_dst(rel) or grad_src.shape[0] < g.n_src(rel):
         raise HetaError(HETA_ERR_SHAPE, "gradient buffers have fewer rows than the relation needs")
     _check(load_library().heta_rel_aggregate_bwd(
-        g.handle, rel, op, _dev(grad_out, "grad_out", torch.float32), _ld(grad_out), d,
+        g.handle, rel, op, _dev(grad_out, "grad_out"), _dt(grad_out), _ld(grad_out), d,
         _dev(grad_src, "grad_src", torch.float32), _ld(grad_src), beta, _stream(stream)))
     return grad_src
 
@@ -351,12 +351,12 @@ def heta_cross_rel_project_bwd(g: Graph, dst_type: int, gout: torch.Tensor, Ws: 
             raise HetaError(HETA_ERR_SHAPE, "weights / outputs do not match")
     L = load_library()
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
-    L.heta_cross_rel_project_bwd.argtypes = [vp, i32, i32, vp, i64, i32, vp, i32, vp, vp, vp, vp, vp]
-    a_w, a_m = _ptr_array(Ws, "W"), _ptr_array(dM, "dM", torch.float32)
+    L.heta_cross_rel_project_bwd.argtypes = [vp, i32, i32, vp, i64, i32, vp, i32, vp, vp, vp, i32, vp, vp]
+    a_w, a_m = _ptr_array(Ws, "W"), _ptr_array(dM, "dM", dM[0].dtype)
     ld_w, d_in, ld_dm = _i64_array([w.stride(0) for w in Ws]), _i32_array([w.shape[0] for w in Ws]), \
         _i64_array([_ld(m) for m in dM])
     _check(L.heta_cross_rel_project_bwd(g.handle, dst_type, len(Ws), _dev(gout, "gout", torch.float32), _ld(gout),
-                                        d_out, a_w, _dt(Ws[0]), ld_w, d_in, a_m, ld_dm, _stream(stream)))
+                                        d_out, a_w, _dt(Ws[0]), ld_w, d_in, a_m, _dt(dM[0]), ld_dm, _stream(stream)))
     return dM
 
 
@@ -420,6 +420,12 @@ def heta_profile_enable(on: bool) -> None:
     L = load_library()
     L.heta_profile_enable.argtypes = [ctypes.c_int32]
     _check(L.heta_profile_enable(int(bool(on))))
+
+
+def heta_ingest_force(mode: int) -> None:
+    L = load_library()
+    L.heta_ingest_force.argtypes = [ctypes.c_int32]
+    _check(L.heta_ingest_force(int(mode)))
 
 
 def heta_projection_force_staged(on: bool) -> None:

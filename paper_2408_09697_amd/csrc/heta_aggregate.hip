@@ -14,14 +14,22 @@
 //   - A row of d elements is cut into 16-byte chunks; a "lane group" of L lanes (L = the
 //     power of two covering the chunks, at most 64, each lane holding one or two chunks)
 //     reads a whole neighbour row with one 128-bit load per lane, fully coalesced.
-//   - Rows are scheduled by degree (perm = rows by descending degree):
+//   - Rows are scheduled by degree (perm = rows by descending degree) and the kernels walk the
+//     schedule-ordered copy of the adjacency (sptr / sidx), so what a wavefront needs before
+//     its first feature load is consecutive in memory:
 //       hub rows   (>= 512 edges): cut into 256-edge chunks, one wavefront per chunk, partial
 //                  sums to a workspace, a second kernel adds the partials in chunk order;
-//       long rows  (>= the wave threshold): one wavefront per row; its 64/L lane groups take
-//                  the row's edges round-robin, several loads in flight each, and are
-//                  combined at the end with cross-lane shuffles;
-//       short rows (the bulk of a power-law graph, incl. empty rows): one lane group per row,
-//                  64/L rows per wavefront, neighbours of equal degree side by side.
+//       long rows  (32 .. 511 edges): one wavefront per row; its 64/L lane groups take the
+//                  row's edges round-robin, several loads in flight each, and are combined at
+//                  the end with cross-lane shuffles;
+//       short rows (< 32 edges: the bulk of a power-law graph, incl. empty rows): one wavefront
+//                  per batch of up to 64 rows of EQUAL degree k.  Where the batch starts, in
+//                  rows and in edges, follows from the degree histogram alone, so the wavefront
+//                  fetches its up to 256 neighbour ids and its row ids with coalesced loads whose
+//                  addresses depend on nothing, parks them in LDS, and then streams feature
+//                  rows: lane group g owns rows g, g + 64/L, ... and keeps 8 row loads in
+//                  flight across row boundaries - two dependent memory round trips per
+//                  wavefront instead of four, and 8 KB in flight per wavefront.
 //   - Neighbour ids of a long row are fetched 64 at a time with one coalesced load and
 //     broadcast with lane shuffles.
 #include <algorithm>
@@ -30,9 +38,12 @@
 
 namespace heta {
 
+constexpr int kShortDeg = 32;      // rows of fewer edges are batched by degree
+constexpr int kBatchIds = 256;     // neighbour ids a batch wavefront parks in LDS
+
 struct AggParams {
-    const int64_t *ptr;
-    const int32_t *idx;
+    const int64_t *sptr;   // schedule-ordered row offsets
+    const int32_t *sidx;   // schedule-ordered neighbour ids
     const int32_t *perm;
     const HubChunk *hub_chunks;
     const int64_t *hub_chunk_ptr;
@@ -50,8 +61,11 @@ struct AggParams {
     int d;
     int64_t n_hub_chunks, n_hub_rows;
     int64_t n_wave_items;  // hub chunks + long rows
-    int64_t short_lo;      // perm[short_lo .. n_rows) are short rows
     int64_t n_rows;
+    // short rows, bucket b holds the rows of degree k = kShortDeg - 1 - b:
+    int32_t batch0[kShortDeg + 1]; // first batch (wavefront) of bucket b; batch0[kShortDeg] = number of batches
+    int32_t row0[kShortDeg + 1];   // schedule position of the bucket's first row; row0[kShortDeg] = n_rows
+    int64_t edge0[kShortDeg];      // position of its first neighbour id in sidx
 };
 
 using bf16_t = uint16_t;
@@ -119,11 +133,32 @@ template <> struct Chunk<bf16_t, 1> {
 };
 
 // Final store of one lane's chunk of an output row: scale, optional accumulate, element guard.
+// Whole chunks on 16-byte aligned rows go out as 128-bit stores (fp32: one per 4 elements; bf16:
+// one per 8 elements, or a 64-bit store for a 4-element chunk).
 template <int EPC>
 __device__ __forceinline__ void store_out(const AggParams &p, int64_t row, int col0, const float *acc, float scale)
 {
+    const bool whole = col0 + EPC <= p.d;
     if (p.out_bf16) {
         bf16_t *o = static_cast<bf16_t *>(p.out) + row * p.ld_out + col0;
+        if constexpr (EPC % 4 == 0) {
+            if (whole && ((p.ld_out & 7) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15u) == 0)) {
+                float v[EPC];
+#pragma unroll
+                for (int i = 0; i < EPC; ++i) v[i] = acc[i] * scale;
+                if (p.beta != 0.f) {
+#pragma unroll
+                    for (int i = 0; i < EPC; ++i) v[i] += bf16_to_f32(o[i]);
+                }
+                uint32_t w[EPC / 2];
+#pragma unroll
+                for (int i = 0; i < EPC / 2; ++i)
+                    w[i] = static_cast<uint32_t>(f32_to_bf16(v[2 * i])) | (static_cast<uint32_t>(f32_to_bf16(v[2 * i + 1])) << 16);
+                if constexpr (EPC == 8) *reinterpret_cast<uint4 *>(o) = make_uint4(w[0], w[1], w[2], w[3]);
+                else *reinterpret_cast<uint2 *>(o) = make_uint2(w[0], w[1]);
+                return;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < EPC; ++i)
             if (col0 + i < p.d) {
@@ -133,23 +168,27 @@ __device__ __forceinline__ void store_out(const AggParams &p, int64_t row, int c
             }
     } else {
         float *o = static_cast<float *>(p.out) + row * p.ld_out + col0;
-        if (EPC == 4 && col0 + 4 <= p.d && ((p.ld_out & 3) == 0) &&
-            ((reinterpret_cast<uintptr_t>(p.out) & 15u) == 0)) {
-            float4 v = make_float4(acc[0] * scale, acc[1] * scale, acc[2] * scale, acc[3] * scale);
-            if (p.beta != 0.f) {
-                float4 old = *reinterpret_cast<float4 *>(o);
-                v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
-            }
-            *reinterpret_cast<float4 *>(o) = v;
-        } else {
+        if constexpr (EPC % 4 == 0) {
+            if (whole && ((p.ld_out & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15u) == 0)) {
 #pragma unroll
-            for (int i = 0; i < EPC; ++i)
-                if (col0 + i < p.d) {
-                    float v = acc[i] * scale;
-                    if (p.beta != 0.f) v += o[i];
-                    o[i] = v;
+                for (int q = 0; q < EPC / 4; ++q) {
+                    float4 v = make_float4(acc[4 * q] * scale, acc[4 * q + 1] * scale, acc[4 * q + 2] * scale, acc[4 * q + 3] * scale);
+                    if (p.beta != 0.f) {
+                        const float4 old = *reinterpret_cast<const float4 *>(o + 4 * q);
+                        v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+                    }
+                    *reinterpret_cast<float4 *>(o + 4 * q) = v;
                 }
+                return;
+            }
         }
+#pragma unroll
+        for (int i = 0; i < EPC; ++i)
+            if (col0 + i < p.d) {
+                float v = acc[i] * scale;
+                if (p.beta != 0.f) v += o[i];
+                o[i] = v;
+            }
     }
 }
 
@@ -159,55 +198,124 @@ __device__ __forceinline__ float row_scale(const AggParams &p, int64_t deg)
     return deg > 0 ? 1.f / static_cast<float>(deg) : 0.f;
 }
 
-// ---- short rows: one lane group per row ----------------------------------------------------------
+// ---- short rows: one wavefront per batch of equal-degree rows ---------------------------------------
+__host__ __device__ inline int batch_rows(int k) { return k == 0 ? 64 : (kBatchIds / k < 64 ? kBatchIds / k : 64); }
+
 template <typename T, int EPC, int L, int CPL>
-__global__ void __launch_bounds__(256) agg_group_kernel(AggParams p)
+__global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
 {
-    constexpr int U = 4;
-    const int64_t q = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) / L;
-    if (q >= p.n_rows - p.short_lo) return; // lane groups are independent here: no cross-lane traffic
-    const int l = threadIdx.x % L;
-    const int64_t row = p.perm[p.short_lo + q];
-    const int64_t e0 = p.ptr[row], e1 = p.ptr[row + 1];
+    constexpr int G = 64 / L;          // lane groups = rows in progress per wavefront
+    constexpr int U = CPL == 1 ? 8 : 4; // row loads in flight per lane group
+    __shared__ int32_t ids_s[4][kBatchIds];
+    __shared__ float w_s[4][kBatchIds];
+    __shared__ int32_t row_s[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int w = blockIdx.x * 4 + wave;
+    const bool active = w < p.batch0[kShortDeg]; // uniform per wavefront; idle wavefronts still reach the barrier
+    int k = 0, nrows = 0;
+    if (active) {
+        int b = 0;
+        while (w >= p.batch0[b + 1]) ++b; // at most kShortDeg scalar steps
+        k = kShortDeg - 1 - b;
+        const int R = batch_rows(k);
+        const int first = (w - p.batch0[b]) * R;
+        const int q0 = p.row0[b] + first;
+        nrows = min(R, p.row0[b + 1] - q0);
+        const int64_t e0 = p.edge0[b] + static_cast<int64_t>(first) * k;
+        const int n_ids = nrows * k;
+        // level 1: everything below has an address that depends on no load
+        if (lane < nrows) row_s[wave][lane] = p.perm[q0 + lane];
+#pragma unroll
+        for (int c = 0; c < kBatchIds / 64; ++c) {
+            const int i = c * 64 + lane;
+            if (i < n_ids) {
+                const int id = p.sidx[e0 + i];
+                ids_s[wave][i] = p.gid ? static_cast<int32_t>(p.gid[id]) : id;
+                if (p.edge_w) w_s[wave][i] = p.edge_w[id];
+            }
+        }
+    }
+    __syncthreads();
+    if (!active) return;
+    const int g = lane / L, l = lane % L;
     const int n_chunks = (p.d + EPC - 1) / EPC;
     const int ch0 = blockIdx.y * (L * CPL) + l;
     const T *table = static_cast<const T *>(p.table);
+    if (k == 0) { // empty rows: exactly 0 (or untouched when accumulating)
+        if (p.beta == 0.f) {
+            float zero[EPC];
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) zero[i] = 0.f;
+            for (int r = g; r < nrows; r += G)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    const int ch = ch0 + c * L;
+                    if (ch < n_chunks) store_out<EPC>(p, row_s[wave][r], ch * EPC, zero, 0.f);
+                }
+        }
+        return;
+    }
+    const float scale = p.mean ? 1.f / static_cast<float>(k) : 1.f;
     float acc[CPL][EPC];
 #pragma unroll
     for (int c = 0; c < CPL; ++c)
 #pragma unroll
         for (int i = 0; i < EPC; ++i) acc[c][i] = 0.f;
-
-    for (int64_t e = e0; e < e1; e += U) {
+    // Lane group g walks the slots (row g + G*rl, edge j) of its rows in order; rl and j are the same
+    // for every group, so the slot bookkeeping is scalar.
+    const int rounds = (nrows + G - 1) / G;
+    int rl = 0, j = 0; // slot at which the next load is issued
+    const int total = rounds * k;
+    for (int s0 = 0; s0 < total; s0 += U) {
         Chunk<T, EPC> v[U][CPL];
-        float w[U];
+        float ww[U];
+        int rl_u = rl, j_u = j;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool ok = e + u < e1;
-            int c = ok ? p.idx[e + u] : 0;
-            w[u] = (ok && p.edge_w) ? p.edge_w[c] : 1.f;
-            const int64_t r = (ok && p.gid) ? p.gid[c] : c;
-            const T *rp = table + r * p.ld;
+            const int r = g + rl_u * G;
+            const bool ok = s0 + u < total && r < nrows;
+            const int i = ok ? r * k + j_u : 0;
+            const int rid = ids_s[wave][i];
+            ww[u] = p.edge_w ? w_s[wave][i] : 1.f;
+            const T *rp = table + static_cast<int64_t>(rid) * p.ld;
 #pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-                const int ch = ch0 + k * L;
-                if (ok && ch < n_chunks) v[u][k].load(rp + static_cast<int64_t>(ch) * EPC);
-                else v[u][k].zero();
+            for (int c = 0; c < CPL; ++c) {
+                const int ch = ch0 + c * L;
+                if (ok && ch < n_chunks) v[u][c].load(rp + static_cast<int64_t>(ch) * EPC);
+                else v[u][c].zero();
+            }
+            if (++j_u == k) {
+                j_u = 0;
+                ++rl_u;
             }
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
+            if (s0 + u < total) {
 #pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-                if (p.edge_w) v[u][k].add_to(acc[k], w[u]);
-                else v[u][k].add_to(acc[k]);
+                for (int c = 0; c < CPL; ++c) {
+                    if (p.edge_w) v[u][c].add_to(acc[c], ww[u]);
+                    else v[u][c].add_to(acc[c]);
+                }
+                if (++j == k) { // last edge of the row: store it, start the next
+                    const int r = g + rl * G;
+                    if (r < nrows) {
+                        const int64_t row = row_s[wave][r];
+#pragma unroll
+                        for (int c = 0; c < CPL; ++c) {
+                            const int ch = ch0 + c * L;
+                            if (ch < n_chunks) store_out<EPC>(p, row, ch * EPC, acc[c], scale);
+                        }
+                    }
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                        for (int i = 0; i < EPC; ++i) acc[c][i] = 0.f;
+                    j = 0;
+                    ++rl;
+                }
             }
-    }
-    const float scale = row_scale(p, e1 - e0);
-#pragma unroll
-    for (int k = 0; k < CPL; ++k) {
-        const int ch = ch0 + k * L;
-        if (ch < n_chunks) store_out<EPC>(p, row, ch * EPC, acc[k], scale);
+        }
     }
 }
 
@@ -228,9 +336,10 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
         e1 = c.e0 + c.len;
         slot = c.slot;
     } else {
-        row = p.perm[p.n_hub_rows + (w - p.n_hub_chunks)];
-        e0 = p.ptr[row];
-        e1 = p.ptr[row + 1];
+        const int64_t q = p.n_hub_rows + (w - p.n_hub_chunks);
+        row = p.perm[q];
+        e0 = p.sptr[q];
+        e1 = p.sptr[q + 1];
     }
     const int g = lane / L, l = lane % L;
     const int n_chunks = (p.d + EPC - 1) / EPC;
@@ -247,7 +356,7 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
         int rid = 0;
         float wv = 1.f;
         if (lane < cnt) {
-            const int c = p.idx[base + lane];
+            const int c = p.sidx[base + lane];
             rid = p.gid ? static_cast<int>(p.gid[c]) : c;
             if (p.edge_w) wv = p.edge_w[c];
         }
@@ -339,7 +448,7 @@ __global__ void __launch_bounds__(256) agg_hub_combine_kernel(AggParams p)
         const float4 v = part[k][lane];
         acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
     }
-    const float scale = row_scale(p, p.ptr[row + 1] - p.ptr[row]);
+    const float scale = row_scale(p, p.sptr[h + 1] - p.sptr[h]);
     store_out<4>(p, row, col0, acc, scale);
 }
 
@@ -352,7 +461,6 @@ struct AggCost {
 template <typename T, int EPC, int L, int CPL>
 static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st, const AggCost &cost)
 {
-    constexpr int G = 64 / L;
     if (p.n_wave_items > 0) {
         const int64_t blocks = (p.n_wave_items + 3) / 4;
         if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many long rows");
@@ -360,13 +468,11 @@ static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st, 
         hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
         HETA_LAUNCH_CHECK("agg_wave_kernel");
     }
-    const int64_t n_short = p.n_rows - p.short_lo;
-    if (n_short > 0) {
-        const int64_t blocks = (n_short + 4 * G - 1) / (4 * G);
-        if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many short rows");
-        ProfScope prof("agg_group_kernel", st, cost.group_bytes, 0);
-        hipLaunchKernelGGL((agg_group_kernel<T, EPC, L, CPL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
-        HETA_LAUNCH_CHECK("agg_group_kernel");
+    const int n_batches = p.batch0[kShortDeg];
+    if (n_batches > 0) {
+        ProfScope prof("agg_batch_kernel", st, cost.group_bytes, 0);
+        hipLaunchKernelGGL((agg_batch_kernel<T, EPC, L, CPL>), dim3((unsigned)((n_batches + 3) / 4), n_super), dim3(256), 0, st, p);
+        HETA_LAUNCH_CHECK("agg_batch_kernel");
     }
     return HETA_OK;
 }
@@ -384,14 +490,6 @@ static heta_status launch_vec(const AggParams &p, int n_chunks, hipStream_t st, 
     return launch_pair<T, EPC, 64, 2>(p, (n_chunks + 127) / 128, st, c);
 }
 
-// lanes per row the dispatch above picks for a row of n_chunks chunks
-static int lanes_per_row(int n_chunks)
-{
-    int L = 1;
-    while (L < n_chunks && L < 64) L <<= 1;
-    return L;
-}
-
 // The shared entry of forward and backward.
 static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, heta_dtype in_dt,
                                  int64_t table_elems_ld, hipStream_t st)
@@ -402,21 +500,31 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     const bool vec = aligned16(p.table) && ((p.ld * esz) % 16 == 0);
     const int epc = vec ? static_cast<int>(16 / esz) : 1;
     const int n_chunks = (p.d + epc - 1) / epc;
-    const int L = vec ? lanes_per_row(n_chunks) : 64;
-    const int G = 64 / L;
     // rows with at least this many edges get a whole wavefront
-    const int wave_min = std::min(kHubMinDeg, std::max(8, 2 * G));
+    const int wave_min = kShortDeg;
     const int64_t n_long_or_hub = s.rows_with_deg_ge[wave_min];
-    p.ptr = s.d_ptr;
-    p.idx = s.d_idx;
+    p.sptr = s.d_sptr;
+    p.sidx = s.d_sidx;
     p.perm = s.d_perm;
     p.hub_chunks = s.d_hub_chunks;
     p.hub_chunk_ptr = s.d_hub_chunk_ptr;
     p.n_hub_chunks = s.n_hub_chunks;
     p.n_hub_rows = s.n_hub_rows;
     p.n_wave_items = s.n_hub_chunks + (n_long_or_hub - s.n_hub_rows);
-    p.short_lo = n_long_or_hub;
     p.n_rows = s.n_rows;
+    // short rows: bucket b = degree kShortDeg - 1 - b, in schedule order (descending degree)
+    int64_t batches = 0;
+    for (int b = 0; b < kShortDeg; ++b) {
+        const int k = kShortDeg - 1 - b;
+        const int64_t first = s.rows_with_deg_ge[k + 1], count = s.rows_with_deg_ge[k] - first;
+        p.batch0[b] = static_cast<int32_t>(batches);
+        p.row0[b] = static_cast<int32_t>(first);
+        p.edge0[b] = s.edges_with_deg_ge[k + 1];
+        batches += (count + batch_rows(k) - 1) / batch_rows(k);
+        if (batches > 0x7ffffff0) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many short rows");
+    }
+    p.batch0[kShortDeg] = static_cast<int32_t>(batches);
+    p.row0[kShortDeg] = static_cast<int32_t>(s.n_rows);
     p.ws_ld = (static_cast<int64_t>(p.d) + 7) / 8 * 8;
     p.ws = nullptr;
     if (s.n_hub_chunks > 0) {
@@ -510,20 +618,21 @@ heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, c
     return run_aggregate(g, r.csr, p, in_dt, ld_src, as_stream(hip_stream));
 }
 
-heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, const float *grad_out,
-                                   int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs, float beta,
-                                   void *hip_stream)
+heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, const void *grad_out,
+                                   heta_dtype go_dt, int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs,
+                                   float beta, void *hip_stream)
 {
     if (!g || !grad_out || !grad_src) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: null argument");
     if (rel < 0 || rel >= (int32_t)g->rels.size())
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: relation %d out of range", rel);
     if (op != HETA_SUM && op != HETA_MEAN) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: bad reduce op");
+    if (!valid_dtype(go_dt)) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: bad dtype");
     if (d <= 0 || ld_go < d || ld_gs < d)
         return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_bwd: need 0 < d <= ld (d=%d ld_go=%lld ld_gs=%lld)", d,
                     (long long)ld_go, (long long)ld_gs);
     if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_bwd: beta must be 0 or 1");
-    if ((reinterpret_cast<uintptr_t>(grad_out) & 3u) || (reinterpret_cast<uintptr_t>(grad_src) & 3u))
-        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: pointer not 4-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(grad_out) % dtype_size(go_dt)) || (reinterpret_cast<uintptr_t>(grad_src) & 3u))
+        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: pointer not aligned to its element size");
     const Relation &r = g->rels[rel];
     AggParams p{};
     p.table = grad_out;
@@ -536,7 +645,7 @@ heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, c
     p.out_bf16 = 0;
     p.beta = beta;
     p.d = d;
-    return run_aggregate(g, r.csc, p, HETA_F32, ld_go, as_stream(hip_stream));
+    return run_aggregate(g, r.csc, p, go_dt, ld_go, as_stream(hip_stream));
 }
 
 heta_status heta_feature_gather(const void *table, heta_dtype dt, int64_t ld_table, int32_t d,

@@ -33,6 +33,7 @@ struct GemmParams {
     const float *row_scale;
     float beta;
     int relu;
+    int out_bf16;        // outputs are bf16 [M][ldc] (plain stores only: no beta, scale, activation, split)
     int64_t k_per_split; // multiple of BK
     int n_split;
     int partial;         // write raw partial products [split][M][ldc] (ldc = N) instead of the output

@@ -430,6 +430,15 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
         for (int jj = 0; jj < 2; ++jj) {
             const int nl = wn + jj * 32 + l32;
             float *col = Cp + (m0 + wm + i * 32 + 4 * half) * out_seg.ldc + n0 + nl;
+            if (p.out_bf16) { // bf16 output: same element mapping, 16-bit stores
+                if (nl >= rows_b) continue;
+                bf16_t *hcol = reinterpret_cast<bf16_t *>(out_seg.C) + (m0 + wm + i * 32 + 4 * half) * out_seg.ldc + n0 + nl;
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (wm + i * 32 + 8 * (v / 4) + 4 * half + (v % 4) < rows_a)
+                        hcol[(8 * (v / 4) + (v % 4)) * out_seg.ldc] = to_bf16(acc[i][jj][v]);
+                continue;
+            }
             if (interior && plain) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) col[(8 * (v / 4) + (v % 4)) * out_seg.ldc] = acc[i][jj][v];

@@ -2,7 +2,9 @@
 //
 // A heterogeneous graph is handed over as its mono-relation subgraphs (Section 2.1 of the
 // paper), one CSR over destination rows per relation.  Everything index-shaped that the
-// aggregation kernels need later is derived here once, on the host, and kept on the device.
+// aggregation kernels need later is derived here once and kept on the device: by the kernels of
+// heta_ingest.hip for relations of real size, by the host code below for the small blocks of a
+// sampled mini-batch, where launch latency would dominate.  Both produce the same arrays.
 #include <algorithm>
 #include <cstring>
 #include <memory>
@@ -61,12 +63,11 @@ static heta_status upload(T **dst, const T *src, size_t n)
     return HETA_OK;
 }
 
-// Builds the device-side schedule of one direction from its host pointer array.
-static heta_status build_schedule(Schedule &s, const int64_t *ptr, const int32_t *idx, int64_t n_rows,
-                                  int64_t n_edges)
+// Host build of one direction's schedule (small relations): the same arrays the device path
+// produces.  s.d_ptr / s.d_idx must already hold the device copies of ptr / idx.
+static heta_status build_schedule_on_host(Schedule &s, const int64_t *ptr, const int32_t *idx)
 {
-    s.n_rows = n_rows;
-    s.n_edges = n_edges;
+    const int64_t n_rows = s.n_rows, n_edges = s.n_edges;
     // counting sort of the rows by min(degree, kHubMinDeg), descending, stable
     std::vector<int64_t> bucket(kHubMinDeg + 2, 0), bucket_edges(kHubMinDeg + 2, 0);
     for (int64_t r = 0; r < n_rows; ++r) {
@@ -74,7 +75,6 @@ static heta_status build_schedule(Schedule &s, const int64_t *ptr, const int32_t
         bucket[d] += 1;
         bucket_edges[d] += ptr[r + 1] - ptr[r];
     }
-    // rows_with_deg_ge[k] = sum of bucket[j] for j >= k
     int64_t run = 0, run_edges = 0;
     for (int k = kHubMinDeg; k >= 0; --k) {
         run += bucket[k];
@@ -82,7 +82,6 @@ static heta_status build_schedule(Schedule &s, const int64_t *ptr, const int32_t
         s.rows_with_deg_ge[k] = run;
         s.edges_with_deg_ge[k] = run_edges;
     }
-    // start offset of bucket k in the descending order = number of rows with larger key
     std::vector<int64_t> start(kHubMinDeg + 1);
     for (int k = 0; k <= kHubMinDeg; ++k)
         start[k] = (k == kHubMinDeg) ? 0 : s.rows_with_deg_ge[k + 1];
@@ -91,15 +90,22 @@ static heta_status build_schedule(Schedule &s, const int64_t *ptr, const int32_t
         int64_t d = std::min<int64_t>(ptr[r + 1] - ptr[r], kHubMinDeg);
         perm[start[d]++] = static_cast<int32_t>(r);
     }
+    // the adjacency in schedule order
+    std::vector<int64_t> sptr(n_rows + 1, 0);
+    std::vector<int32_t> sidx(std::max<int64_t>(n_edges, 1));
+    for (int64_t q = 0; q < n_rows; ++q) {
+        const int64_t r = perm[q], deg = ptr[r + 1] - ptr[r];
+        std::copy(idx + ptr[r], idx + ptr[r] + deg, sidx.begin() + sptr[q]);
+        sptr[q + 1] = sptr[q] + deg;
+    }
     s.n_hub_rows = s.rows_with_deg_ge[kHubMinDeg];
     std::vector<HubChunk> chunks;
     std::vector<int64_t> chunk_ptr(s.n_hub_rows + 1, 0);
     for (int64_t h = 0; h < s.n_hub_rows; ++h) {
-        int32_t r = perm[h];
-        for (int64_t e = ptr[r]; e < ptr[r + 1]; e += kHubChunk) {
+        for (int64_t e = sptr[h]; e < sptr[h + 1]; e += kHubChunk) {
             HubChunk c;
             c.e0 = e;
-            c.len = static_cast<int32_t>(std::min<int64_t>(kHubChunk, ptr[r + 1] - e));
+            c.len = static_cast<int32_t>(std::min<int64_t>(kHubChunk, sptr[h + 1] - e));
             c.slot = static_cast<int32_t>(chunks.size());
             chunks.push_back(c);
         }
@@ -109,9 +115,9 @@ static heta_status build_schedule(Schedule &s, const int64_t *ptr, const int32_t
         return fail(HETA_ERR_UNSUPPORTED, "too many hub chunks (%zu)", chunks.size());
     s.n_hub_chunks = static_cast<int64_t>(chunks.size());
     heta_status st;
-    if ((st = upload(&s.d_ptr, ptr, n_rows + 1)) != HETA_OK) return st;
-    if ((st = upload(&s.d_idx, idx, n_edges)) != HETA_OK) return st;
     if ((st = upload(&s.d_perm, perm.data(), n_rows)) != HETA_OK) return st;
+    if ((st = upload(&s.d_sptr, sptr.data(), sptr.size())) != HETA_OK) return st;
+    if ((st = upload(&s.d_sidx, sidx.data(), n_edges)) != HETA_OK) return st;
     if ((st = upload(&s.d_hub_chunks, chunks.data(), chunks.size())) != HETA_OK) return st;
     if ((st = upload(&s.d_hub_chunk_ptr, chunk_ptr.data(), chunk_ptr.size())) != HETA_OK) return st;
     return HETA_OK;
@@ -122,6 +128,8 @@ static void free_schedule(Schedule &s)
     (void)hipFree(s.d_ptr);
     (void)hipFree(s.d_idx);
     (void)hipFree(s.d_perm);
+    (void)hipFree(s.d_sptr);
+    (void)hipFree(s.d_sidx);
     (void)hipFree(s.d_hub_chunks);
     (void)hipFree(s.d_hub_chunk_ptr);
     s = Schedule();
@@ -175,15 +183,47 @@ static heta_status check_relation_args(const std::vector<heta_ntype> &ntypes, co
     return HETA_OK;
 }
 
+// Relations below this many edges + rows are ingested on the host: a few microseconds of CPU work
+// beat the launch latencies of the device pipeline (sampled mini-batch blocks); everything larger
+// is built by the kernels of heta_ingest.hip.  heta_ingest_force() overrides the choice.
+constexpr int64_t kDeviceIngestMin = 1 << 17;
+static int g_ingest_mode = 0; // 0 = by size, 1 = host, 2 = device
+
 static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32_t index, bool on_device)
 {
-    Relation rel;
+    g->rels.emplace_back();
+    Relation &rel = g->rels.back(); // owned by g from here on: destroy(g) releases whatever was allocated
     rel.src_type = in.src_type;
     rel.dst_type = in.dst_type;
     rel.n_src = g->ntypes[in.src_type].num_nodes;
     rel.n_dst = g->ntypes[in.dst_type].num_nodes;
     rel.n_edges = in.num_edges;
     const int64_t E = in.num_edges, n_dst = rel.n_dst, n_src = rel.n_src;
+    hipStream_t st = nullptr;
+    rel.csr.n_rows = n_dst;
+    rel.csr.n_edges = E;
+    rel.csc.n_rows = n_src;
+    rel.csc.n_edges = E;
+
+    // the CSR itself: a device copy of the caller's arrays
+    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_ptr), (n_dst + 1) * sizeof(int64_t)));
+    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_idx), std::max<int64_t>(E, 1) * sizeof(int32_t)));
+    const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    HETA_HIP(hipMemcpy(rel.csr.d_ptr, in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), kind));
+    if (E) HETA_HIP(hipMemcpy(rel.csr.d_idx, in.csr_col, E * sizeof(int32_t), kind));
+    if (on_device) { // host arrays were validated before the device was touched
+        heta_status vst = validate_csr_on_device(index, rel.csr.d_ptr, rel.csr.d_idx, n_dst, n_src, E, st);
+        if (vst != HETA_OK) return vst;
+    }
+    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.d_inv_deg), std::max<int64_t>(n_dst, 1) * sizeof(float)));
+
+    const bool device_path = g_ingest_mode == 2 || (g_ingest_mode == 0 && E + n_dst + n_src >= kDeviceIngestMin);
+    if (device_path) {
+        heta_status e;
+        if ((e = transpose_on_device(rel.csr, n_src, rel.csc, st)) != HETA_OK) return e;
+        if ((e = build_schedule_on_device(rel.csr, rel.d_inv_deg, st)) != HETA_OK) return e;
+        return build_schedule_on_device(rel.csc, nullptr, st);
+    }
 
     std::vector<int64_t> h_ptr;
     std::vector<int32_t> h_col;
@@ -192,24 +232,18 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
     if (on_device) {
         h_ptr.resize(n_dst + 1);
         h_col.resize(std::max<int64_t>(E, 1));
-        HETA_HIP(hipMemcpy(h_ptr.data(), in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
-        if (E)
-            HETA_HIP(hipMemcpy(h_col.data(), in.csr_col, E * sizeof(int32_t), hipMemcpyDeviceToHost));
+        HETA_HIP(hipMemcpy(h_ptr.data(), rel.csr.d_ptr, (n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+        if (E) HETA_HIP(hipMemcpy(h_col.data(), rel.csr.d_idx, E * sizeof(int32_t), hipMemcpyDeviceToHost));
         ptr = h_ptr.data();
         col = h_col.data();
-        heta_status vst = validate_relation(g->ntypes, in, index, ptr, col);
-        if (vst != HETA_OK)
-            return vst;
     }
-    // ---- degrees ----
-    rel.h_deg.resize(n_dst);
     std::vector<float> inv_deg(std::max<int64_t>(n_dst, 1));
     for (int64_t v = 0; v < n_dst; ++v) {
-        int64_t d = ptr[v + 1] - ptr[v];
-        rel.h_deg[v] = d;
+        const int64_t d = ptr[v + 1] - ptr[v];
         inv_deg[v] = d > 0 ? 1.0f / static_cast<float>(d) : 0.0f;
     }
-    // ---- stable transpose: column u keeps its edges in ascending original edge position ----
+    if (n_dst) HETA_HIP(hipMemcpy(rel.d_inv_deg, inv_deg.data(), n_dst * sizeof(float), hipMemcpyHostToDevice));
+    // stable transpose: column u keeps its edges in ascending original edge position
     std::vector<int64_t> colptr(n_src + 1, 0);
     for (int64_t e = 0; e < E; ++e)
         colptr[col[e] + 1] += 1;
@@ -222,17 +256,11 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
             for (int64_t e = ptr[v]; e < ptr[v + 1]; ++e)
                 row[cursor[col[e]]++] = static_cast<int32_t>(v);
     }
-    heta_status st;
-    if ((st = build_schedule(rel.csr, ptr, col, n_dst, E)) != HETA_OK ||
-        (st = build_schedule(rel.csc, colptr.data(), row.data(), n_src, E)) != HETA_OK ||
-        (st = upload(&rel.d_inv_deg, inv_deg.data(), n_dst)) != HETA_OK) {
-        free_schedule(rel.csr);
-        free_schedule(rel.csc);
-        (void)hipFree(rel.d_inv_deg);
-        return st;
-    }
-    g->rels.push_back(std::move(rel));
-    return HETA_OK;
+    heta_status e;
+    if ((e = upload(&rel.csc.d_ptr, colptr.data(), colptr.size())) != HETA_OK) return e;
+    if ((e = upload(&rel.csc.d_idx, row.data(), E)) != HETA_OK) return e;
+    if ((e = build_schedule_on_host(rel.csr, ptr, col)) != HETA_OK) return e;
+    return build_schedule_on_host(rel.csc, colptr.data(), row.data());
 }
 
 } // namespace heta
@@ -300,6 +328,13 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
     return HETA_OK;
 }
 
+heta_status heta_ingest_force(int32_t mode)
+{
+    if (mode < 0 || mode > 2) return fail(HETA_ERR_INVALID_ARG, "heta_ingest_force: mode must be 0, 1 or 2");
+    g_ingest_mode = mode;
+    return HETA_OK;
+}
+
 heta_status heta_graph_destroy(heta_graph *g)
 {
     destroy(g);
@@ -326,11 +361,18 @@ heta_status heta_graph_get_degrees(const heta_graph *g, int32_t rel, int64_t *in
     if (rel < 0 || rel >= (int32_t)g->rels.size())
         return fail(HETA_ERR_INVALID_ARG, "heta_graph_get_degrees: relation %d out of range", rel);
     const Relation &r = g->rels[rel];
-    // degrees are recomputed from the device copy of rowptr so that the read-back covers it
-    std::vector<int64_t> ptr(r.n_dst + 1);
-    HETA_HIP(hipMemcpy(ptr.data(), r.csr.d_ptr, (r.n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    // taken from the schedule (row ids by descending degree + schedule-ordered offsets), so that
+    // the read-back covers what the aggregation kernels actually walk
+    std::vector<int64_t> sptr(r.n_dst + 1);
+    std::vector<int32_t> perm(std::max<int64_t>(r.n_dst, 1));
+    HETA_HIP(hipMemcpy(sptr.data(), r.csr.d_sptr, (r.n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (r.n_dst)
+        HETA_HIP(hipMemcpy(perm.data(), r.csr.d_perm, r.n_dst * sizeof(int32_t), hipMemcpyDeviceToHost));
     for (int64_t v = 0; v < r.n_dst; ++v)
-        in_deg[v] = ptr[v + 1] - ptr[v];
+        in_deg[v] = -1;
+    for (int64_t q = 0; q < r.n_dst; ++q)
+        if (perm[q] >= 0 && perm[q] < r.n_dst)
+            in_deg[perm[q]] = sptr[q + 1] - sptr[q];
     return HETA_OK;
 }
 

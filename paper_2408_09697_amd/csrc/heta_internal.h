@@ -43,16 +43,22 @@ constexpr int kHubChunk = 256;
 constexpr int kDegHist = 513; // rows_with_deg_ge[k] for k in [0, 512]
 
 struct HubChunk {       // one wavefront's share of a hub row
-    int64_t e0;         // first edge
+    int64_t e0;         // first edge (position in the schedule-ordered neighbour array)
     int32_t len;        // number of edges (<= kHubChunk)
     int32_t slot;       // partial row in the workspace
 };
 
 struct Schedule {
     int64_t n_rows = 0, n_edges = 0;
-    int64_t *d_ptr = nullptr;     // [n_rows + 1]
-    int32_t *d_idx = nullptr;     // [n_edges] neighbour ids
+    int64_t *d_ptr = nullptr;     // [n_rows + 1] offsets by row id (the CSR / CSC itself)
+    int32_t *d_idx = nullptr;     // [n_edges] neighbour ids in that order
     int32_t *d_perm = nullptr;    // [n_rows] rows by descending degree
+    // The same adjacency laid out in schedule order: position q holds row perm[q], its neighbours
+    // are sidx[sptr[q] .. sptr[q+1]).  The kernels walk only this copy, so a wavefront's row
+    // offsets and neighbour ids are consecutive in memory and, for rows of fewer than kHubMinDeg
+    // edges, computable from the degree histogram without a load.
+    int64_t *d_sptr = nullptr;    // [n_rows + 1]
+    int32_t *d_sidx = nullptr;    // [n_edges]
     int64_t n_hub_rows = 0;       // perm[0 .. n_hub_rows) are hub rows
     int64_t n_hub_chunks = 0;
     HubChunk *d_hub_chunks = nullptr;    // [n_hub_chunks], grouped by hub row in perm order
@@ -67,7 +73,6 @@ struct Relation {
     Schedule csr;                 // rows = destinations, idx = sources
     Schedule csc;                 // rows = sources, idx = destinations
     float *d_inv_deg = nullptr;   // [n_dst] 1/deg_r(v), 0 for zero-degree rows
-    std::vector<int64_t> h_deg;   // host copy of the in-degrees
 };
 
 } // namespace heta
@@ -97,6 +102,14 @@ private:
     hipStream_t stream_;
     size_t index_ = 0;
 };
+
+// Device-side ingest (heta_ingest.hip).  All three are synchronous on `st` when they return.
+heta_status validate_csr_on_device(int32_t index, const int64_t *d_ptr, const int32_t *d_col, int64_t n_dst, int64_t n_src,
+                                   int64_t n_edges, hipStream_t st);
+// csc.d_ptr / csc.d_idx (allocated here) = stable transpose of csr.d_ptr / csr.d_idx
+heta_status transpose_on_device(const Schedule &csr, int64_t n_src, Schedule &csc, hipStream_t st);
+// everything of s beyond d_ptr / d_idx (allocated here); inv_deg (optional, [n_rows]) = 1/degree
+heta_status build_schedule_on_device(Schedule &s, float *inv_deg, hipStream_t st);
 
 // Makes sure g's workspace holds `bytes`; growing frees and reallocates (device synchronising).
 heta_status ensure_workspace(heta_graph *g, size_t bytes);

@@ -148,6 +148,15 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
         for (int j = 0; j < 2; ++j) {
             const int nl = wn + j * 32 + l32;
             float *col = C + (m0 + wm + i * 32 + 4 * half) * out_seg.ldc + n0 + nl;
+            if (p.out_bf16) { // bf16 output: same element mapping, 16-bit stores
+                if (nl >= rows_b) continue;
+                bf16_t *hcol = reinterpret_cast<bf16_t *>(out_seg.C) + (m0 + wm + i * 32 + 4 * half) * out_seg.ldc + n0 + nl;
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (wm + i * 32 + 8 * (v / 4) + 4 * half + (v % 4) < rows_a)
+                        hcol[(8 * (v / 4) + (v % 4)) * out_seg.ldc] = to_bf16(acc[i][j][v]);
+                continue;
+            }
             if (interior && plain) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) col[(8 * (v / 4) + (v % 4)) * out_seg.ldc] = acc[i][j][v];
@@ -247,7 +256,7 @@ static void gemm_cost(const GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, dou
         }
         if (!a_seen) *bytes += static_cast<double>(g.M) * g.K * dtype_size(a_dt);
         if (!b_seen) *bytes += static_cast<double>(g.K) * g.N * dtype_size(b_dt);
-        if (s < n_out) *bytes += static_cast<double>(g.M) * g.N * 4.0 * ((p.beta != 0.f && !p.partial) ? 2.0 : 1.0);
+        if (s < n_out) *bytes += static_cast<double>(g.M) * g.N * (p.out_bf16 ? 2.0 : 4.0) * ((p.beta != 0.f && !p.partial) ? 2.0 : 1.0);
     }
 }
 
@@ -463,15 +472,15 @@ heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_
 
 heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, int32_t n, const float *gout,
                                        int64_t ld_go, int32_t d_out, const void *const *Ws, heta_dtype w_dt,
-                                       const int64_t *ld_w, const int32_t *d_in, float *const *dM,
-                                       const int64_t *ld_dm, void *hip_stream)
+                                       const int64_t *ld_w, const int32_t *d_in, void *const *dM,
+                                       heta_dtype dm_dt, const int64_t *ld_dm, void *hip_stream)
 {
     const char *who = "heta_cross_rel_project_bwd";
     heta_status e = check_type(g, dst_type, who);
     if (e != HETA_OK) return e;
     if (!gout || !Ws || !ld_w || !d_in || !dM || !ld_dm) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
     if (n < 1 || n > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d relations", who, kMaxSeg);
-    if (!valid_dtype(w_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
+    if (!valid_dtype(w_dt) || !valid_dtype(dm_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
     if (d_out <= 0 || ld_go < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
     if (misaligned(gout, 4)) return fail(HETA_ERR_INVALID_ARG, "%s: gout not 4-byte aligned", who);
     const int64_t n_rows = g->ntypes[dst_type].num_nodes;
@@ -479,14 +488,14 @@ heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, in
     for (int s = 0; s < n; ++s) {
         if (!Ws[s] || !dM[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
         if (d_in[s] <= 0 || ld_w[s] < d_out || ld_dm[s] < d_in[s]) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
-        if (misaligned(Ws[s], dtype_size(w_dt)) || misaligned(dM[s], 4))
+        if (misaligned(Ws[s], dtype_size(w_dt)) || misaligned(dM[s], dtype_size(dm_dt)))
             return fail(HETA_ERR_INVALID_ARG, "%s: pointer not aligned to its element size", who);
         GemmSeg &q = p.seg[s];
         q.A = gout;
         q.lda = ld_go;
         q.B = Ws[s];   // B[k][n] = W[n][k]: W is [d_in, d_out] row-major, k-contiguous
         q.ldb = ld_w[s];
-        q.C = dM[s];
+        q.C = static_cast<float *>(dM[s]); // typed by p.out_bf16 in the kernels' epilogue
         q.ldc = ld_dm[s];
         q.M = n_rows;
         q.N = d_in[s];
@@ -501,6 +510,7 @@ heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, in
     p.k_per_split = int64_t(1) << 40;
     p.n_split = 1;
     p.partial = 0;
+    p.out_bf16 = dm_dt == HETA_BF16;
     return dispatch_gemm<false, false>(p, HETA_F32, w_dt, as_stream(hip_stream));
 }
 

@@ -65,7 +65,11 @@ class RafLayer:
             return torch.empty((n, (d + q - 1) // q * q), dtype=dtype, device=dev)[:, :d]
 
         self.M = {r: padded(graph.n_dst(r), self.d_rel[r], m_dtype) for r in self.rels}
-        self.dM = {r: padded(graph.n_dst(r), self.d_rel[r], torch.float32) for r in self.rels}
+        # dM_r, like the saved M_r, is an [n x d] intermediate that the backward aggregation re-reads once
+        # per edge: it is kept in the storage type (bf16 tables -> bf16 dM_r, fp32 accumulation around it)
+        self._padded = padded
+        self.dM = {r: padded(graph.n_dst(r), self.d_rel[r], m_dtype) for r in self.rels}
+        self._dM32 = None  # fp32 dM_r for the per-relation call path, whose projection writes fp32
         self.H = {t: torch.empty((graph.ntypes[t][0], d_out), dtype=torch.float32, device=dev)
                   for t in self.rels_into}
         self.dW = {r: torch.empty((self.d_rel[r], d_out), dtype=torch.float32, device=dev) for r in self.rels}
@@ -140,10 +144,15 @@ class RafLayer:
             g = G[t]
             if self.relu:
                 g = hb.heta_act_bwd(hb.HETA_ACT_RELU, self.H[t], G[t], self._Gact[t], stream=stream)
+            dM = self.dM
             if per_relation:
+                if self.m_dtype != torch.float32:
+                    if self._dM32 is None:
+                        self._dM32 = {r: self._padded(self.g.n_dst(r), self.d_rel[r], torch.float32) for r in self.rels}
+                    dM = self._dM32
                 for r in rs:
                     hb.heta_rel_project_wgrad(self.g, r, self.M[r], g, self.dW[r], stream=stream)
-                    hb.heta_rel_project(self.g, r, g, self.W[r], self.dM[r], trans_w=True, stream=stream)
+                    hb.heta_rel_project(self.g, r, g, self.W[r], dM[r], trans_w=True, stream=stream)
             else:
                 for c in range(0, len(rs), 8):
                     part = rs[c:c + 8]
@@ -153,7 +162,7 @@ class RafLayer:
                                                   [self.dM[r] for r in part], stream=stream)
             for r in rs:
                 s = self.g.rels[r][0]
-                hb.heta_rel_aggregate_bwd(self.g, r, self.op, self.dM[r], self.dH0[s],
+                hb.heta_rel_aggregate_bwd(self.g, r, self.op, dM[r], self.dH0[s],
                                           beta=0.0 if first_for_src[s] else 1.0, stream=stream)
                 first_for_src[s] = False
         if self.pre_proj is not None:

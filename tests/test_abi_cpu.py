@@ -80,7 +80,7 @@ def test_null_handle_calls_fail_cleanly():
     assert lib.heta_graph_get_csc(None, 0, None, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_graph_get_degrees(None, 0, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_rel_aggregate_fwd(None, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0, None) == hb.HETA_ERR_INVALID_ARG
-    assert lib.heta_rel_aggregate_bwd(None, 0, 0, None, 0, 0, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_rel_aggregate_bwd(None, 0, 0, None, 0, 0, 0, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_project(0, None, 0, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_rel_project(None, 0, None, 0, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_rel_project_wgrad(None, 0, None, 0, 0, 0, None, 0, 0, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG

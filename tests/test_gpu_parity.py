@@ -40,10 +40,14 @@ def one_relation_graph(rel, n_src, n_dst):
     return g, heta.heta_graph_create(nts, [(0, 1, rel.rowptr, rel.col)])
 
 
-@pytest.fixture(scope="module")
-def skew():
+@pytest.fixture(scope="module", params=["host_ingest", "device_ingest"])
+def skew(request):
+    """The skewed relation, ingested once by the host path (what a relation of this size gets by
+    default) and once by the device kernels (what relations of 2^17+ edges and rows get)."""
     rel = skewed_relation()
+    heta.heta_ingest_force(1 if request.param == "host_ingest" else 2)
     g, hg = one_relation_graph(rel, 3000, 2000)
+    heta.heta_ingest_force(0)
     yield rel, hg
     hg.destroy()
 
@@ -59,12 +63,17 @@ def test_ingest_csc_and_degrees_bit_exact(skew):
     assert np.array_equal(heta.heta_graph_get_degrees(hg, 0), oracle.in_degree(src, dst, 2000))
 
 
-def test_ingest_config1_and_device_pointers():
+@pytest.mark.parametrize("mode", [1, 2])
+def test_ingest_config1_and_device_pointers(mode):
     p = workloads.config1()
     nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in p.graph.ntypes]
     rels = [(r.src_type, r.dst_type, torch.from_numpy(r.rowptr).cuda(), torch.from_numpy(r.col).cuda())
             for r in p.graph.relations]
-    hg = heta.heta_graph_create(nts, rels, flags=heta.HETA_PTRS_ON_DEVICE)
+    heta.heta_ingest_force(mode)
+    try:
+        hg = heta.heta_graph_create(nts, rels, flags=heta.HETA_PTRS_ON_DEVICE)
+    finally:
+        heta.heta_ingest_force(0)
     for i, r in enumerate(p.graph.relations):
         src, dst = r.edge_list()
         n_s, n_t = p.graph.ntypes[r.src_type].num_nodes, p.graph.ntypes[r.dst_type].num_nodes
@@ -73,11 +82,54 @@ def test_ingest_config1_and_device_pointers():
         assert np.array_equal(colptr, rc) and np.array_equal(row, rr)
         assert np.array_equal(heta.heta_graph_get_degrees(hg, i), oracle.in_degree(src, dst, n_t))
     hg.destroy()
-    # a bad CSR that lives on the device is rejected after the copy-back, nothing is leaked or launched
-    bad = [(0, 0, torch.tensor([0, 2, 1] + [1] * 1998, dtype=torch.int64).cuda(), torch.zeros(1, dtype=torch.int32).cuda())]
-    with pytest.raises(heta.HetaError) as ei:
-        heta.heta_graph_create(nts, bad, flags=heta.HETA_PTRS_ON_DEVICE)
-    assert ei.value.status == heta.HETA_ERR_BAD_CSR
+    # a bad CSR that lives on the device is rejected by the validation kernels, with the host validator's wording
+    z = torch.zeros(1, dtype=torch.int32).cuda()
+    for rowptr, col, needle in [([0, 2, 1] + [1] * 1998, z, "decreases at row 1"), ([1] * 2001, z, "rowptr[0]"),
+                                ([0] * 2000 + [2], z, "num_edges"),
+                                ([0] * 2000 + [1], torch.full((1,), 2000, dtype=torch.int32).cuda(), "col[0]"),
+                                ([0] * 2000 + [1], torch.full((1,), -1, dtype=torch.int32).cuda(), "col[0]")]:
+        bad = [(0, 0, torch.tensor(rowptr, dtype=torch.int64).cuda(), col)]
+        with pytest.raises(heta.HetaError) as ei:
+            heta.heta_graph_create(nts, bad, flags=heta.HETA_PTRS_ON_DEVICE)
+        assert ei.value.status == heta.HETA_ERR_BAD_CSR and needle in ei.value.message, ei.value.message
+
+
+def test_device_ingest_edge_cases():
+    """Device-built index arrays on shapes that stress the sort and the scans: no edges, one row, one
+    column holding every edge, a ragged last sort tile, more tiles than one scan tile of tile counts."""
+    heta.heta_ingest_force(2)
+    try:
+        g = rng.stream("tests", "ingest-edge")
+        cases = [(5, 7, 0), (1, 1, 1), (1, 9, 4097), (3, 1, 5000), (40000, 70000, 300001)]
+        for n_src, n_dst, n_e in cases:
+            dst = np.sort(g.integers(0, n_dst, size=n_e)).astype(np.int64)
+            src = g.integers(0, n_src, size=n_e, dtype=np.int32)
+            if n_e > 1000:
+                src[: n_e // 3] = n_src - 1                      # a hub column
+            rowptr = np.zeros(n_dst + 1, dtype=np.int64)
+            np.add.at(rowptr, dst + 1, 1)
+            rowptr = np.cumsum(rowptr)
+            hg = heta.heta_graph_create([(n_src, 8, 0), (n_dst, 8, 0)], [(0, 1, rowptr, src)])
+            colptr, row = heta.heta_graph_get_csc(hg, 0)
+            rc, rr = oracle.csc(src, dst.astype(np.int32), n_src)
+            assert np.array_equal(colptr, rc) and np.array_equal(row, rr), (n_src, n_dst, n_e)
+            assert np.array_equal(heta.heta_graph_get_degrees(hg, 0), np.diff(rowptr)), (n_src, n_dst, n_e)
+            # the schedule-ordered adjacency, through an exact integer aggregation in both directions
+            x = torch.arange(n_src, dtype=torch.float32, device="cuda").remainder(5).sub(2).reshape(-1, 1).repeat(1, 4).contiguous()
+            out = torch.full((n_dst, 4), float("nan"), dtype=torch.float32, device="cuda")
+            heta.heta_rel_aggregate_fwd(hg, 0, heta.HETA_SUM, x, out)
+            ref = np.zeros(n_dst)
+            np.add.at(ref, dst, (src % 5 - 2).astype(np.float64))
+            assert np.array_equal(out[:, 0].cpu().numpy().astype(np.float64), ref), (n_src, n_dst, n_e)
+            y = torch.arange(n_dst, dtype=torch.float32, device="cuda").remainder(3).sub(1).reshape(-1, 1).repeat(1, 4).contiguous()
+            back = torch.full((n_src, 4), float("nan"), dtype=torch.float32, device="cuda")
+            heta.heta_rel_aggregate_bwd(hg, 0, heta.HETA_SUM, y, back)
+            refb = np.zeros(n_src)
+            np.add.at(refb, src, (dst % 3 - 1).astype(np.float64))
+            assert np.array_equal(back[:, 0].cpu().numpy().astype(np.float64), refb), (n_src, n_dst, n_e)
+            hg.destroy()
+    finally:
+        heta.heta_ingest_force(0)
 
 
 # ---- a2: heterogeneous gather ----------------------------------------------------------------------
@@ -173,18 +225,24 @@ def test_aggregate_integer_inputs_bit_exact(skew):
 # ---- a7: backward aggregation over the CSC -----------------------------------------------------------
 
 @pytest.mark.parametrize("op", ["sum", "mean"])
-@pytest.mark.parametrize("d,pad", [(1, 4), (7, 4), (32, 4), (128, 4), (300, 4), (768, 4), (1024, 4), (33, 1)])
-def test_aggregate_bwd(skew, op, d, pad):
+@pytest.mark.parametrize("d,pad,storage", [(1, 4, "f32"), (7, 4, "f32"), (32, 4, "f32"), (128, 4, "f32"), (300, 4, "f32"),
+                                           (768, 4, "f32"), (1024, 4, "f32"), (33, 1, "f32"),
+                                           (7, 8, "bf16"), (64, 8, "bf16"), (128, 8, "bf16"), (300, 8, "bf16"),
+                                           (789, 8, "bf16"), (33, 1, "bf16")])
+def test_aggregate_bwd(skew, op, d, pad, storage):
+    """fp32 gradient rows, and rows kept in bf16 (a dM_r stored in the storage type): the oracle
+    reads the same rounded values, so only the fp32 accumulation order differs."""
     rel, hg = skew
     src, dst = rel.edge_list()
     gm = rng.normal_table(2000, d, "tests", f"gm{d}")
-    ref = oracle.aggregate_bwd(src, dst, 3000, 2000, gm.astype(np.float64), op)
+    seen = rng.round_to_bf16(gm) if storage == "bf16" else gm
+    ref = oracle.aggregate_bwd(src, dst, 3000, 2000, seen.astype(np.float64), op)
     out = torch.full((3000, d), float("nan"), dtype=torch.float32, device="cuda")
     hop = heta.HETA_MEAN if op == "mean" else heta.HETA_SUM
-    heta.heta_rel_aggregate_bwd(hg, 0, hop, dev_table(gm, "f32", pad), out, beta=0.0)
+    heta.heta_rel_aggregate_bwd(hg, 0, hop, dev_table(gm, storage, pad), out, beta=0.0)
     assert_rows_close(out.cpu().numpy(), ref, 1e-4, f"dH0 d={d}")
     # beta = 1 accumulates on top
-    heta.heta_rel_aggregate_bwd(hg, 0, hop, dev_table(gm, "f32", pad), out, beta=1.0)
+    heta.heta_rel_aggregate_bwd(hg, 0, hop, dev_table(gm, storage, pad), out, beta=1.0)
     assert_rows_close(out.cpu().numpy(), 2 * ref, 1e-4, f"dH0 accumulate d={d}")
 
 
@@ -383,6 +441,19 @@ def test_layer_config3_scaled(storage, mode, gemm_path):
     compare_layer(p, got, ref_f, ref_b, tol=TOL[storage])
 
 
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_layer_config3_scaled_device_ingest(storage):
+    heta.heta_ingest_force(2)
+    try:
+        p = workloads.config3(storage, scale=0.02)
+        got = run_layer_on_gpu(p)
+    finally:
+        heta.heta_ingest_force(0)
+    ref_f = oracle.layer_forward(p)
+    ref_b = oracle.layer_backward(p, ref_f, p.G)
+    compare_layer(p, got, ref_f, ref_b, tol=TOL[storage])
+
+
 def test_layer_config4_scaled(gemm_path):
     p = workloads.config4(scale=0.01)
     got = run_layer_on_gpu(p)
@@ -430,6 +501,11 @@ def test_cross_rel_project_family(in_s, w_s, d_out, relu, gemm_path):
     heta.heta_cross_rel_project_bwd(hg, 0, dg, dw, dMs)
     for m, w in zip(dMs, wr):
         assert_rows_close(m.cpu().numpy(), g.astype(np.float64) @ w.astype(np.float64).T, tol, "fused dM")
+    if in_s == "bf16":  # dM_r kept in the storage type: one rounding of the fp32 accumulator on the way out
+        hMs = [dev_table(np.full((n, d), np.nan, dtype=np.float32), "bf16", 8) for d in widths]
+        heta.heta_cross_rel_project_bwd(hg, 0, dg, dw, hMs)
+        for m, w in zip(hMs, wr):
+            assert_rows_close(m.float().cpu().numpy(), g.astype(np.float64) @ w.astype(np.float64).T, tol, "fused dM (bf16)")
     dWs = [torch.full((d, d_out), float("nan"), dtype=torch.float32, device="cuda") for d in widths]
     heta.heta_cross_rel_project_wgrad(hg, 0, dx, dg, dWs)
     for w, x in zip(dWs, xr):
