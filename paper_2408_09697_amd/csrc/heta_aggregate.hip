@@ -199,7 +199,16 @@ __device__ __forceinline__ float row_scale(const AggParams &p, int64_t deg)
 }
 
 // ---- short rows: one wavefront per batch of equal-degree rows ---------------------------------------
-__host__ __device__ inline int batch_rows(int k) { return k == 0 ? 64 : (kBatchIds / k < 64 ? kBatchIds / k : 64); }
+// Rows per batch for degree k and G lane groups: about 16 row loads per lane group (two fills of its
+// load pipeline), at most 64 rows and kBatchIds neighbour ids - small enough that a block of a sampled
+// mini-batch with wide rows (G = 1) still spreads over the whole chip.
+__host__ __device__ inline int batch_rows(int k, int G)
+{
+    if (k == 0) return 64;
+    int r = G * (16 / k > 1 ? 16 / k : 1);
+    r = r < kBatchIds / k ? r : kBatchIds / k;
+    return r < 64 ? r : 64;
+}
 
 template <typename T, int EPC, int L, int CPL>
 __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
@@ -217,7 +226,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
         int b = 0;
         while (w >= p.batch0[b + 1]) ++b; // at most kShortDeg scalar steps
         k = kShortDeg - 1 - b;
-        const int R = batch_rows(k);
+        const int R = batch_rows(k, G);
         const int first = (w - p.batch0[b]) * R;
         const int q0 = p.row0[b] + first;
         nrows = min(R, p.row0[b + 1] - q0);
@@ -500,6 +509,12 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     const bool vec = aligned16(p.table) && ((p.ld * esz) % 16 == 0);
     const int epc = vec ? static_cast<int>(16 / esz) : 1;
     const int n_chunks = (p.d + epc - 1) / epc;
+    int L = 64; // lanes per row, as the dispatch below picks them
+    if (vec) {
+        L = 1;
+        while (L < n_chunks && L < 64) L <<= 1;
+    }
+    const int G = 64 / L;
     // rows with at least this many edges get a whole wavefront
     const int wave_min = kShortDeg;
     const int64_t n_long_or_hub = s.rows_with_deg_ge[wave_min];
@@ -520,7 +535,7 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
         p.batch0[b] = static_cast<int32_t>(batches);
         p.row0[b] = static_cast<int32_t>(first);
         p.edge0[b] = s.edges_with_deg_ge[k + 1];
-        batches += (count + batch_rows(k) - 1) / batch_rows(k);
+        batches += (count + batch_rows(k, G) - 1) / batch_rows(k, G);
         if (batches > 0x7ffffff0) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many short rows");
     }
     p.batch0[kShortDeg] = static_cast<int32_t>(batches);

@@ -54,7 +54,7 @@ heta_status ensure_workspace(heta_graph *g, size_t bytes)
 }
 
 template <typename T>
-static heta_status upload(T **dst, const T *src, size_t n)
+[[maybe_unused]] static heta_status upload(T **dst, const T *src, size_t n)
 {
     *dst = nullptr;
     HETA_HIP(hipMalloc(reinterpret_cast<void **>(dst), std::max<size_t>(n, 1) * sizeof(T)));
@@ -63,9 +63,26 @@ static heta_status upload(T **dst, const T *src, size_t n)
     return HETA_OK;
 }
 
-// Host build of one direction's schedule (small relations): the same arrays the device path
-// produces.  s.d_ptr / s.d_idx must already hold the device copies of ptr / idx.
-static heta_status build_schedule_on_host(Schedule &s, const int64_t *ptr, const int32_t *idx)
+// Host-built relations are assembled in one host buffer and reach the device with one
+// allocation and one copy: byte offsets here, pointers once the device address is known.
+struct HostPack {
+    std::vector<char> buf;
+    template <typename T> size_t add(const T *data, size_t n)
+    {
+        const size_t off = (buf.size() + 255) / 256 * 256;
+        buf.resize(off + std::max<size_t>(n, 1) * sizeof(T));
+        if (n) std::memcpy(buf.data() + off, data, n * sizeof(T));
+        return off;
+    }
+};
+
+struct ScheduleOffsets {
+    size_t ptr, idx, perm, sptr, sidx, hub_chunks, hub_chunk_ptr;
+};
+
+// Host build of one direction's schedule (small relations): the same arrays the device path produces.
+static heta_status build_schedule_on_host(Schedule &s, const int64_t *ptr, const int32_t *idx, HostPack &pack,
+                                          ScheduleOffsets &off)
 {
     const int64_t n_rows = s.n_rows, n_edges = s.n_edges;
     // counting sort of the rows by min(degree, kHubMinDeg), descending, stable
@@ -114,13 +131,25 @@ static heta_status build_schedule_on_host(Schedule &s, const int64_t *ptr, const
     if (chunks.size() >= (size_t(1) << 31))
         return fail(HETA_ERR_UNSUPPORTED, "too many hub chunks (%zu)", chunks.size());
     s.n_hub_chunks = static_cast<int64_t>(chunks.size());
-    heta_status st;
-    if ((st = upload(&s.d_perm, perm.data(), n_rows)) != HETA_OK) return st;
-    if ((st = upload(&s.d_sptr, sptr.data(), sptr.size())) != HETA_OK) return st;
-    if ((st = upload(&s.d_sidx, sidx.data(), n_edges)) != HETA_OK) return st;
-    if ((st = upload(&s.d_hub_chunks, chunks.data(), chunks.size())) != HETA_OK) return st;
-    if ((st = upload(&s.d_hub_chunk_ptr, chunk_ptr.data(), chunk_ptr.size())) != HETA_OK) return st;
+    off.ptr = pack.add(ptr, n_rows + 1);
+    off.idx = pack.add(idx, n_edges);
+    off.perm = pack.add(perm.data(), n_rows);
+    off.sptr = pack.add(sptr.data(), sptr.size());
+    off.sidx = pack.add(sidx.data(), n_edges);
+    off.hub_chunks = pack.add(chunks.data(), chunks.size());
+    off.hub_chunk_ptr = pack.add(chunk_ptr.data(), chunk_ptr.size());
     return HETA_OK;
+}
+
+static void resolve(Schedule &s, const ScheduleOffsets &off, char *base)
+{
+    s.d_ptr = reinterpret_cast<int64_t *>(base + off.ptr);
+    s.d_idx = reinterpret_cast<int32_t *>(base + off.idx);
+    s.d_perm = reinterpret_cast<int32_t *>(base + off.perm);
+    s.d_sptr = reinterpret_cast<int64_t *>(base + off.sptr);
+    s.d_sidx = reinterpret_cast<int32_t *>(base + off.sidx);
+    s.d_hub_chunks = reinterpret_cast<HubChunk *>(base + off.hub_chunks);
+    s.d_hub_chunk_ptr = reinterpret_cast<int64_t *>(base + off.hub_chunk_ptr);
 }
 
 static void free_schedule(Schedule &s)
@@ -141,6 +170,10 @@ static void destroy(heta_graph *g)
         return;
     (void)hipDeviceSynchronize();
     for (auto &r : g->rels) {
+        if (r.d_arena) { // host-built: one allocation
+            (void)hipFree(r.d_arena);
+            continue;
+        }
         free_schedule(r.csr);
         free_schedule(r.csc);
         (void)hipFree(r.d_inv_deg);
@@ -205,20 +238,19 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
     rel.csc.n_rows = n_src;
     rel.csc.n_edges = E;
 
-    // the CSR itself: a device copy of the caller's arrays
-    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_ptr), (n_dst + 1) * sizeof(int64_t)));
-    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_idx), std::max<int64_t>(E, 1) * sizeof(int32_t)));
-    const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
-    HETA_HIP(hipMemcpy(rel.csr.d_ptr, in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), kind));
-    if (E) HETA_HIP(hipMemcpy(rel.csr.d_idx, in.csr_col, E * sizeof(int32_t), kind));
-    if (on_device) { // host arrays were validated before the device was touched
-        heta_status vst = validate_csr_on_device(index, rel.csr.d_ptr, rel.csr.d_idx, n_dst, n_src, E, st);
-        if (vst != HETA_OK) return vst;
-    }
-    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.d_inv_deg), std::max<int64_t>(n_dst, 1) * sizeof(float)));
-
     const bool device_path = g_ingest_mode == 2 || (g_ingest_mode == 0 && E + n_dst + n_src >= kDeviceIngestMin);
     if (device_path) {
+        // the CSR itself: a device copy of the caller's arrays
+        HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_ptr), (n_dst + 1) * sizeof(int64_t)));
+        HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_idx), std::max<int64_t>(E, 1) * sizeof(int32_t)));
+        const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+        HETA_HIP(hipMemcpy(rel.csr.d_ptr, in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), kind));
+        if (E) HETA_HIP(hipMemcpy(rel.csr.d_idx, in.csr_col, E * sizeof(int32_t), kind));
+        if (on_device) { // host arrays were validated before the device was touched
+            heta_status vst = validate_csr_on_device(index, rel.csr.d_ptr, rel.csr.d_idx, n_dst, n_src, E, st);
+            if (vst != HETA_OK) return vst;
+        }
+        HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.d_inv_deg), std::max<int64_t>(n_dst, 1) * sizeof(float)));
         heta_status e;
         if ((e = transpose_on_device(rel.csr, n_src, rel.csc, st)) != HETA_OK) return e;
         if ((e = build_schedule_on_device(rel.csr, rel.d_inv_deg, st)) != HETA_OK) return e;
@@ -232,17 +264,18 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
     if (on_device) {
         h_ptr.resize(n_dst + 1);
         h_col.resize(std::max<int64_t>(E, 1));
-        HETA_HIP(hipMemcpy(h_ptr.data(), rel.csr.d_ptr, (n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
-        if (E) HETA_HIP(hipMemcpy(h_col.data(), rel.csr.d_idx, E * sizeof(int32_t), hipMemcpyDeviceToHost));
+        HETA_HIP(hipMemcpy(h_ptr.data(), in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+        if (E) HETA_HIP(hipMemcpy(h_col.data(), in.csr_col, E * sizeof(int32_t), hipMemcpyDeviceToHost));
         ptr = h_ptr.data();
         col = h_col.data();
+        heta_status vst = validate_relation(g->ntypes, in, index, ptr, col);
+        if (vst != HETA_OK) return vst;
     }
     std::vector<float> inv_deg(std::max<int64_t>(n_dst, 1));
     for (int64_t v = 0; v < n_dst; ++v) {
         const int64_t d = ptr[v + 1] - ptr[v];
         inv_deg[v] = d > 0 ? 1.0f / static_cast<float>(d) : 0.0f;
     }
-    if (n_dst) HETA_HIP(hipMemcpy(rel.d_inv_deg, inv_deg.data(), n_dst * sizeof(float), hipMemcpyHostToDevice));
     // stable transpose: column u keeps its edges in ascending original edge position
     std::vector<int64_t> colptr(n_src + 1, 0);
     for (int64_t e = 0; e < E; ++e)
@@ -256,11 +289,19 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
             for (int64_t e = ptr[v]; e < ptr[v + 1]; ++e)
                 row[cursor[col[e]]++] = static_cast<int32_t>(v);
     }
+    HostPack pack;
+    ScheduleOffsets o_csr, o_csc;
     heta_status e;
-    if ((e = upload(&rel.csc.d_ptr, colptr.data(), colptr.size())) != HETA_OK) return e;
-    if ((e = upload(&rel.csc.d_idx, row.data(), E)) != HETA_OK) return e;
-    if ((e = build_schedule_on_host(rel.csr, ptr, col)) != HETA_OK) return e;
-    return build_schedule_on_host(rel.csc, colptr.data(), row.data());
+    if ((e = build_schedule_on_host(rel.csr, ptr, col, pack, o_csr)) != HETA_OK) return e;
+    if ((e = build_schedule_on_host(rel.csc, colptr.data(), row.data(), pack, o_csc)) != HETA_OK) return e;
+    const size_t o_inv = pack.add(inv_deg.data(), static_cast<size_t>(n_dst));
+    HETA_HIP(hipMalloc(&rel.d_arena, pack.buf.size()));
+    HETA_HIP(hipMemcpy(rel.d_arena, pack.buf.data(), pack.buf.size(), hipMemcpyHostToDevice));
+    char *base = static_cast<char *>(rel.d_arena);
+    resolve(rel.csr, o_csr, base);
+    resolve(rel.csc, o_csc, base);
+    rel.d_inv_deg = reinterpret_cast<float *>(base + o_inv);
+    return HETA_OK;
 }
 
 } // namespace heta

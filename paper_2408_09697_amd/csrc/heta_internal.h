@@ -73,6 +73,7 @@ struct Relation {
     Schedule csr;                 // rows = destinations, idx = sources
     Schedule csc;                 // rows = sources, idx = destinations
     float *d_inv_deg = nullptr;   // [n_dst] 1/deg_r(v), 0 for zero-degree rows
+    void *d_arena = nullptr;      // host-built relations: the one allocation every pointer above points into
 };
 
 } // namespace heta
