@@ -166,7 +166,10 @@ heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, h
  * one contraction over the concatenated k ranges, so no per-relation partial ever goes to HBM.
  * ins, Ws, ld_in, d_in, ld_w: HOST arrays of n (1..8) entries; ins[p] device [n_rows, ld_in[p]] of
  * in_dt; Ws[p] device [d_in[p], ld_w[p] >= d_out] of w_dt; out device fp32 [n_rows, ld_out].
- * On a subset of a type's relations with beta = 0 it yields the partial aggregation of that subset. */
+ * On a subset of a type's relations with beta = 0 it yields the partial aggregation of that subset.
+ * With bf16 inputs and weights the call first rewrites the weights k-contiguous into a buffer of the
+ * handle (grown on demand: the first call for a larger shape synchronises); calls on one handle
+ * that do so must be stream-ordered, like the calls that use its workspace. */
 heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
                                    heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
                                    const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,

@@ -180,6 +180,26 @@ template <int BK> __device__ __forceinline__ uint4 dfrag_bf16(const bf16_t *tile
     return *reinterpret_cast<const uint4 *>(&tile[(r * CPR + c) * 8]);
 }
 
+// bf16 fragment of a k-contiguous operand that is stored (and was loaded) as fp32: the eight
+// k-values of a lane are two 16-byte chunks of its LDS row, rounded to bf16 (nearest even, the
+// hardware's packed convert) on the way to the MFMA
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const floatx2_t f = {lo, hi};
+    const bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+    return *reinterpret_cast<const uint32_t *>(&h);
+}
+template <int BK> __device__ __forceinline__ uint4 dfrag_bf16_from_f32(const float *tile, int r, int kk, int half)
+{
+    constexpr int CPR = BK / 4;
+    const int c0 = kk / 4 + 2 * half, sw = swz<CPR>(r);
+    const float4 lo = *reinterpret_cast<const float4 *>(&tile[(r * CPR + (c0 ^ sw)) * 4]);
+    const float4 hi = *reinterpret_cast<const float4 *>(&tile[(r * CPR + ((c0 + 1) ^ sw)) * 4]);
+    return make_uint4(pack_bf16(lo.x, lo.y), pack_bf16(lo.z, lo.w), pack_bf16(hi.x, hi.y), pack_bf16(hi.z, hi.w));
+}
+
 // zeroes the k-values of a bf16 fragment (8 consecutive k from k_first) that are >= kv
 __device__ __forceinline__ uint4 mask_bf16(uint4 v, int k_first, int kv)
 {
@@ -224,19 +244,22 @@ template <typename CT, typename SA_T, bool A_RC, bool A_DIRECT, typename SB_T, b
 __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p)
 {
     constexpr int NT = 128 * WN, NW = 2 * WN, BN = 64 * WN;
-    using DA = std::conditional_t<A_DIRECT, DirectLoader<CT, A_RC && A_DIRECT, BM, BK, NW>, NoLoader>;
-    using DB = std::conditional_t<B_DIRECT, DirectLoader<CT, B_RC && B_DIRECT, BN, BK, NW>, NoLoader>;
+    // a direct operand lies in LDS in its storage type (fp32 storage under bf16 compute is converted
+    // when fragments are read); a staged operand lies there in the compute type
+    using DA = std::conditional_t<A_DIRECT, DirectLoader<SA_T, A_RC && A_DIRECT, BM, BK, NW>, NoLoader>;
+    using DB = std::conditional_t<B_DIRECT, DirectLoader<SB_T, B_RC && B_DIRECT, BN, BK, NW>, NoLoader>;
     using SA = std::conditional_t<A_DIRECT, NoLoader, TileLoader<SA_T, CT, A_RC, BM, NT, true, BK>>;
     using SB = std::conditional_t<B_DIRECT, NoLoader, TileLoader<SB_T, CT, B_RC, BN, NT, true, BK>>;
     constexpr bool ANY_STAGED = !A_DIRECT || !B_DIRECT;
-    constexpr int A_STRIDE = A_DIRECT ? DA::STAGE_ELEMS : LdsTile<CT, A_RC, BM, BK>::elems;
-    constexpr int B_STRIDE = B_DIRECT ? DB::STAGE_ELEMS : LdsTile<CT, B_RC, BN, BK>::elems;
-    constexpr int A_ELEMS = (A_DIRECT ? ST : 2) * A_STRIDE, B_ELEMS = (B_DIRECT ? ST : 2) * B_STRIDE;
+    // bytes of one LDS stage / buffer of each operand
+    constexpr int A_STRIDE = A_DIRECT ? DA::STAGE_ELEMS * (int)sizeof(SA_T) : LdsTile<CT, A_RC, BM, BK>::elems * (int)sizeof(CT);
+    constexpr int B_STRIDE = B_DIRECT ? DB::STAGE_ELEMS * (int)sizeof(SB_T) : LdsTile<CT, B_RC, BN, BK>::elems * (int)sizeof(CT);
+    constexpr int A_BYTES = (A_DIRECT ? ST : 2) * A_STRIDE, B_BYTES = (B_DIRECT ? ST : 2) * B_STRIDE;
     constexpr int LD_PER_TILE = (A_DIRECT ? DA::NI : 0) + (B_DIRECT ? DB::NI : 0);
     static_assert(A_DIRECT || B_DIRECT, "at least one operand is loaded directly");
     static_assert(ST >= 2 && (ST - 2) * LD_PER_TILE < 64, "vmcnt range");
-    __shared__ __attribute__((aligned(1024))) CT As[A_ELEMS];
-    __shared__ __attribute__((aligned(1024))) CT Bs[B_ELEMS];
+    __shared__ __attribute__((aligned(1024))) char As[A_BYTES];
+    __shared__ __attribute__((aligned(1024))) char Bs[B_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -277,8 +300,8 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
     TileSeq<BK> L = I, C = I;
     auto init_direct = [&]() {
         const GemmSeg &g = p.seg[I.s];
-        if constexpr (A_DIRECT) da.init(static_cast<const CT *>(g.A), g.lda, m0, g.M, I.k, wave, lane);
-        if constexpr (B_DIRECT) db.init(static_cast<const CT *>(g.B), g.ldb, n0, g.N, I.k, wave, lane);
+        if constexpr (A_DIRECT) da.init(static_cast<const SA_T *>(g.A), g.lda, m0, g.M, I.k, wave, lane);
+        if constexpr (B_DIRECT) db.init(static_cast<const SB_T *>(g.B), g.ldb, n0, g.N, I.k, wave, lane);
     };
     auto init_staged = [&]() {
         const GemmSeg &g = p.seg[L.s];
@@ -296,12 +319,12 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
     auto issue_direct = [&](int st) { // st: ring stage the tile goes to
         const int kv = I.valid();
         if (kv == BK) {
-            if constexpr (A_DIRECT) da.issue(a_lds + st * A_STRIDE * (int)sizeof(CT), wave);
-            if constexpr (B_DIRECT) db.issue(b_lds + st * B_STRIDE * (int)sizeof(CT), wave);
+            if constexpr (A_DIRECT) da.issue(a_lds + st * A_STRIDE, wave);
+            if constexpr (B_DIRECT) db.issue(b_lds + st * B_STRIDE, wave);
         } else {
             const GemmSeg &g = p.seg[I.s];
-            if constexpr (A_DIRECT) da.issue_ragged(a_lds + st * A_STRIDE * (int)sizeof(CT), wave, lane, kv, g.lda - I.k);
-            if constexpr (B_DIRECT) db.issue_ragged(b_lds + st * B_STRIDE * (int)sizeof(CT), wave, lane, kv, g.ldb - I.k);
+            if constexpr (A_DIRECT) da.issue_ragged(a_lds + st * A_STRIDE, wave, lane, kv, g.lda - I.k);
+            if constexpr (B_DIRECT) db.issue_ragged(b_lds + st * B_STRIDE, wave, lane, kv, g.ldb - I.k);
         }
         ++ahead;
         if (I.advance()) {
@@ -334,8 +357,8 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
         for (int st = 0; st < ST; ++st) { // st: ring stage of the tile consumed in this step (compile-time)
             if (!c_ok) break;
             // registers of this tile's staged operand -> its LDS buffer (last read two tiles ago)
-            if constexpr (!A_DIRECT) sa.store(As + sbuf * A_STRIDE, tid);
-            if constexpr (!B_DIRECT) sb.store(Bs + sbuf * B_STRIDE, tid);
+            if constexpr (!A_DIRECT) sa.store(reinterpret_cast<CT *>(As + sbuf * A_STRIDE), tid);
+            if constexpr (!B_DIRECT) sb.store(reinterpret_cast<CT *>(Bs + sbuf * B_STRIDE), tid);
             // this tile's direct loads have landed once at most the younger tiles' loads are
             // outstanding (and the staged stores above have reached LDS)
             if (ahead - 1 >= ST - 2) wait_counters<(ST - 2) * LD_PER_TILE, true>();
@@ -346,8 +369,8 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
             }
             if (i_ok) issue_direct((st + ST - 1) % ST);
 
-            const CT *At = As + (A_DIRECT ? st : sbuf) * A_STRIDE;
-            const CT *Bt = Bs + (B_DIRECT ? st : sbuf) * B_STRIDE;
+            const char *At = As + (A_DIRECT ? st : sbuf) * A_STRIDE;
+            const char *Bt = Bs + (B_DIRECT ? st : sbuf) * B_STRIDE;
             const int kv = C.valid();
             const bool ragged = kv < BK;
             if constexpr (sizeof(CT) == 4) {
@@ -356,13 +379,13 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
                     float a[2][4], b[2][4];
 #pragma unroll
                     for (int i = 0; i < 2; ++i) {
-                        if constexpr (A_DIRECT) dfrag_f32<A_RC, BM, BK>(At, wm + i * 32 + l32, kk, half, a[i]);
-                        else frag_f32<A_RC, BM, BK>(At, wm + i * 32 + l32, kk, half, a[i]);
+                        if constexpr (A_DIRECT) dfrag_f32<A_RC, BM, BK>(reinterpret_cast<const float *>(At), wm + i * 32 + l32, kk, half, a[i]);
+                        else frag_f32<A_RC, BM, BK>(reinterpret_cast<const float *>(At), wm + i * 32 + l32, kk, half, a[i]);
                     }
 #pragma unroll
                     for (int jj = 0; jj < 2; ++jj) {
-                        if constexpr (B_DIRECT) dfrag_f32<B_RC, BN, BK>(Bt, wn + jj * 32 + l32, kk, half, b[jj]);
-                        else frag_f32<B_RC, BN, BK>(Bt, wn + jj * 32 + l32, kk, half, b[jj]);
+                        if constexpr (B_DIRECT) dfrag_f32<B_RC, BN, BK>(reinterpret_cast<const float *>(Bt), wn + jj * 32 + l32, kk, half, b[jj]);
+                        else frag_f32<B_RC, BN, BK>(reinterpret_cast<const float *>(Bt), wn + jj * 32 + l32, kk, half, b[jj]);
                     }
                     if (ragged) {
 #pragma unroll
@@ -386,12 +409,16 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
                     union Frag { uint4 u; bf16x8 v; } a[2], b[2];
 #pragma unroll
                     for (int i = 0; i < 2; ++i) {
-                        if constexpr (A_DIRECT) a[i].u = dfrag_bf16<BK>(reinterpret_cast<const bf16_t *>(At), wm + i * 32 + l32, kk, half);
+                        if constexpr (A_DIRECT && sizeof(SA_T) == 4)
+                            a[i].u = dfrag_bf16_from_f32<BK>(reinterpret_cast<const float *>(At), wm + i * 32 + l32, kk, half);
+                        else if constexpr (A_DIRECT) a[i].u = dfrag_bf16<BK>(reinterpret_cast<const bf16_t *>(At), wm + i * 32 + l32, kk, half);
                         else a[i].u = frag_bf16<A_RC, BM, BK>(reinterpret_cast<const bf16_t *>(At), wm + i * 32 + l32, kk, half);
                     }
 #pragma unroll
                     for (int jj = 0; jj < 2; ++jj) {
-                        if constexpr (B_DIRECT) b[jj].u = dfrag_bf16<BK>(reinterpret_cast<const bf16_t *>(Bt), wn + jj * 32 + l32, kk, half);
+                        if constexpr (B_DIRECT && sizeof(SB_T) == 4)
+                            b[jj].u = dfrag_bf16_from_f32<BK>(reinterpret_cast<const float *>(Bt), wn + jj * 32 + l32, kk, half);
+                        else if constexpr (B_DIRECT) b[jj].u = dfrag_bf16<BK>(reinterpret_cast<const bf16_t *>(Bt), wn + jj * 32 + l32, kk, half);
                         else b[jj].u = frag_bf16<B_RC, BN, BK>(reinterpret_cast<const bf16_t *>(Bt), wn + jj * 32 + l32, kk, half);
                     }
                     if (ragged) {
@@ -520,9 +547,13 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         return wide ? launch_direct<bf16_t, bf16_t, false, true, bf16_t, true, false, 4, 32, 3, 4>(p, st, name, bytes, flops)
                     : launch_direct<bf16_t, bf16_t, false, true, bf16_t, true, false, 2, 32, 3, 2>(p, st, name, bytes, flops);
     }
-    if (a_dt == HETA_F32 && b_dt == HETA_BF16 && !a_rc && !b_rc) { // backward: G (fp32 -> bf16) x W_r^T (bf16, k-contiguous)
-        return wide ? launch_direct<bf16_t, float, false, false, bf16_t, false, true, 4, 32, 3, 4>(p, st, name, bytes, flops)
-                    : launch_direct<bf16_t, float, false, false, bf16_t, false, true, 2, 32, 3, 2>(p, st, name, bytes, flops);
+    if (a_dt == HETA_F32 && b_dt == HETA_BF16 && !a_rc && !b_rc) { // backward: G (fp32, rounded at the MFMA) x W_r^T (bf16, k-contiguous)
+        return wide ? launch_direct<bf16_t, float, false, true, bf16_t, false, true, 4, 32, 3, 4>(p, st, name, bytes, flops)
+                    : launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 32, 3, 3>(p, st, name, bytes, flops);
+    }
+    if (a_dt == HETA_BF16 && b_dt == HETA_BF16 && !a_rc && !b_rc) { // both k-contiguous bf16 (forward with a packed W_r^T)
+        return wide ? launch_direct<bf16_t, bf16_t, false, true, bf16_t, false, true, 4, 32, 3, 4>(p, st, name, bytes, flops)
+                    : launch_direct<bf16_t, bf16_t, false, true, bf16_t, false, true, 2, 32, 3, 3>(p, st, name, bytes, flops);
     }
     *handled = false;
     return HETA_OK;

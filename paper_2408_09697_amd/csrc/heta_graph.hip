@@ -179,6 +179,7 @@ static void destroy(heta_graph *g)
         (void)hipFree(r.d_inv_deg);
     }
     (void)hipFree(g->d_ws);
+    (void)hipFree(g->d_pack);
     delete g;
 }
 

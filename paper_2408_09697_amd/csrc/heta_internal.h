@@ -85,6 +85,9 @@ struct heta_graph {
     // workspace for hub-row partials and split weight-gradient partials; grown on demand
     void *d_ws = nullptr;
     size_t ws_bytes = 0;
+    // k-contiguous copies of the bf16 weight matrices of the projection in flight; grown on demand
+    void *d_pack = nullptr;
+    size_t pack_bytes = 0;
 };
 
 namespace heta {

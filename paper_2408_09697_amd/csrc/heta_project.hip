@@ -201,6 +201,20 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *part, i
     *o = (beta != 0.f) ? beta * *o + a : a;
 }
 
+// out[n][k] = W[k][n]: a bf16 weight matrix laid out k-contiguous, the form the direct-to-LDS
+// pipeline can copy into LDS as is (an n-contiguous bf16 operand would need pair interleaving)
+__global__ void __launch_bounds__(256) pack_weight_kernel(const bf16_t *W, int64_t ldw, int K, int N, bf16_t *out, int ld_out)
+{
+    __shared__ bf16_t tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5; // 32 x 8
+    const int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    for (int r = ty; r < 32; r += 8)
+        tile[r][tx] = (k0 + r < K && n0 + tx < N) ? W[static_cast<int64_t>(k0 + r) * ldw + n0 + tx] : bf16_t(0);
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8)
+        if (n0 + r < N && k0 + tx < ld_out) out[static_cast<int64_t>(n0 + r) * ld_out + k0 + tx] = (k0 + tx < K) ? tile[tx][r] : bf16_t(0);
+}
+
 // ---- host side -------------------------------------------------------------------------------------
 
 static void gemm_cost(const GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, double *bytes, double *flops);
@@ -298,7 +312,7 @@ static bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintp
 static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
                                 const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
                                 int32_t d_out, int32_t transW, const float *row_scale, int relu, float *out,
-                                int64_t ld_out, float beta, hipStream_t st, const char *who)
+                                int64_t ld_out, float beta, hipStream_t st, const char *who, heta_graph *pack_owner = nullptr)
 {
     if (!ins || !Ws || !out || !ld_in || !d_in || !ld_w) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
     if (n_seg < 1 || n_seg > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d inputs", who, kMaxSeg);
@@ -334,7 +348,38 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
     p.n_split = 1;
     p.partial = 0;
     // B[k][n] = W[k][n] is n-contiguous (r-contiguous in the loader's terms); W^T is k-contiguous
-    return transW ? dispatch_gemm<false, false>(p, in_dt, w_dt, st) : dispatch_gemm<false, true>(p, in_dt, w_dt, st);
+    if (transW) return dispatch_gemm<false, false>(p, in_dt, w_dt, st);
+    if (pack_owner && !g_force_staged && in_dt == HETA_BF16 && w_dt == HETA_BF16) {
+        // bf16 forward with a graph handle: the small W_r are first rewritten k-contiguous into the
+        // handle's packing buffer, so that both operands can stream into LDS without a register stage
+        bool ok = true;
+        size_t bytes = 0;
+        for (int s = 0; s < n_seg; ++s) {
+            ok = ok && aligned16(ins[s]) && (ld_in[s] * 2) % 16 == 0;
+            bytes += static_cast<size_t>(d_out) * ((d_in[s] + 7) / 8 * 8) * 2 + 256;
+        }
+        if (ok) {
+            if (bytes > pack_owner->pack_bytes) {
+                if (pack_owner->d_pack) HETA_HIP(hipFree(pack_owner->d_pack)); // waits for earlier readers
+                pack_owner->d_pack = nullptr;
+                pack_owner->pack_bytes = 0;
+                HETA_HIP(hipMalloc(&pack_owner->d_pack, bytes * 2));
+                pack_owner->pack_bytes = bytes * 2;
+            }
+            char *dst = static_cast<char *>(pack_owner->d_pack);
+            for (int s = 0; s < n_seg; ++s) {
+                const int ldp = (d_in[s] + 7) / 8 * 8;
+                hipLaunchKernelGGL(pack_weight_kernel, dim3((d_out + 31) / 32, (ldp + 31) / 32), dim3(256), 0, st,
+                                   static_cast<const bf16_t *>(Ws[s]), ld_w[s], d_in[s], d_out, reinterpret_cast<bf16_t *>(dst), ldp);
+                HETA_LAUNCH_CHECK("pack_weight_kernel");
+                p.seg[s].B = dst;
+                p.seg[s].ldb = ldp;
+                dst += (static_cast<size_t>(d_out) * ldp * 2 + 255) / 256 * 256;
+            }
+            return dispatch_gemm<false, false>(p, in_dt, w_dt, st);
+        }
+    }
+    return dispatch_gemm<false, true>(p, in_dt, w_dt, st);
 }
 
 // dW_s = beta*dW_s + in_s^T . gout over n_rows graph rows, all s in one launch
@@ -444,7 +489,7 @@ heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, h
     if (rel < 0 || rel >= (int32_t)g->rels.size())
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_project: relation %d out of range", rel);
     return project_impl(g->rels[rel].n_dst, 1, &in, in_dt, &ld_in, &d_in, &W, w_dt, &ld_w, d_out, transW, row_scale, 0,
-                        out, ld_out, beta, as_stream(hip_stream), "heta_rel_project");
+                        out, ld_out, beta, as_stream(hip_stream), "heta_rel_project", const_cast<heta_graph *>(g));
 }
 
 heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
@@ -467,7 +512,8 @@ heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_
     if (e != HETA_OK) return e;
     if (act != HETA_ACT_NONE && act != HETA_ACT_RELU) return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_project: bad act");
     return project_impl(g->ntypes[dst_type].num_nodes, n, ins, in_dt, ld_in, d_in, Ws, w_dt, ld_w, d_out, 0, nullptr,
-                        act == HETA_ACT_RELU, out, ld_out, beta, as_stream(hip_stream), "heta_cross_rel_project");
+                        act == HETA_ACT_RELU, out, ld_out, beta, as_stream(hip_stream), "heta_cross_rel_project",
+                        const_cast<heta_graph *>(g));
 }
 
 heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, int32_t n, const float *gout,

@@ -34,10 +34,11 @@ def short_name(full: str) -> str:
 def family(name: str) -> str:
     """Kernel family as the library's own profiler names it."""
     base = name.split("<")[0]
-    if base == "gemm_kernel":
+    if base in ("gemm_kernel", "gemm_direct_kernel"):
         args = [a.strip() for a in name[name.index("<") + 1:name.rindex(">")].split(",")]
         ct = "f32" if args[0] == "float" else "bf16"
-        wgrad = args[2] == "true" and args[4] == "true"
+        # both operands r-contiguous = the weight gradient (contraction over graph rows)
+        wgrad = (args[2] == "true" and args[4] == "true") if base == "gemm_kernel" else (args[2] == "true" and args[5] == "true")
         return f"gemm_wgrad_{ct}" if wgrad else f"gemm_{ct}"
     return base
 
