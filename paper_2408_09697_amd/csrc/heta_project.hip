@@ -42,17 +42,19 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
     const int wm = (wave / WN) * 64, wn = (wave % WN) * 64;
     const int half = lane >> 5, l32 = lane & 31;
 
-    // block id -> (segment, n tile, m tile, split): neighbours in launch order share operands
-    int64_t id = blockIdx.x;
-    int s0 = 0;
-    if (p.batch) {
-        s0 = static_cast<int>(id % p.n_seg);
-        id /= p.n_seg;
-    }
-    const int64_t n0 = (id % p.nt) * BN;
-    id /= p.nt;
-    const int64_t m0 = (id % p.mt) * BM;
-    const int64_t split = id / p.mt;
+    // workgroup id -> (XCD, position in that XCD's queue) -> (outer = row block x split, inner =
+    // column tile x segment): workgroups are dealt round-robin to the 8 XCDs, so the tiles that
+    // share an operand (the segments of a batch, the column tiles of a row block) are given
+    // consecutive positions of ONE XCD's queue and meet in its L2
+    const int n_batch = p.batch ? p.n_seg : 1;
+    const int64_t inner = p.nt * n_batch;
+    const int64_t xcd = blockIdx.x % 8, jq = blockIdx.x / 8;
+    const int64_t in_idx = jq % inner, outer = (jq / inner) * 8 + xcd;
+    if (outer >= p.mt * p.n_split) return;
+    const int s0 = p.batch ? static_cast<int>(in_idx % n_batch) : 0;
+    const int64_t n0 = (in_idx / n_batch) * BN;
+    const int64_t m0 = (outer % p.mt) * BM;
+    const int64_t split = outer / p.mt;
     const GemmSeg &out_seg = p.seg[s0];
     if (m0 >= out_seg.M || n0 >= out_seg.N) return; // uniform per workgroup (smaller segment of a batch)
     const int s_end = p.batch ? s0 + 1 : p.n_seg;
@@ -239,7 +241,7 @@ static heta_status launch_gemm(GemmParams &p, hipStream_t st, int bk)
     }
     p.mt = mt;
     p.nt = nt;
-    const int64_t blocks = mt * nt * std::max(1, p.n_split) * (p.batch ? p.n_seg : 1);
+    const int64_t blocks = (mt * std::max(1, p.n_split) + 7) / 8 * 8 * nt * (p.batch ? p.n_seg : 1);
     if (blocks <= 0) return HETA_OK;
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
     ProfScope prof(sizeof(CT) == 4 ? (p.partial ? "gemm_wgrad_f32" : "gemm_f32") : (p.partial ? "gemm_wgrad_bf16" : "gemm_bf16"),

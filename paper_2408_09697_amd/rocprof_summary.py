@@ -27,7 +27,8 @@ CALIB_KIB = float(1 << 20)  # the calibration copy reads 1 GiB and writes 1 GiB
 
 def short_name(full: str) -> str:
     """'void heta::agg_wave_kernel<float, 4, 32, 1>(heta::AggParams)' -> 'agg_wave_kernel<float, 4, 32, 1>'"""
-    n = full.split("(")[0].replace("void ", "").replace("heta::", "").strip()
+    n = full.replace("(anonymous namespace)::", "")
+    n = n.split("(")[0].replace("void ", "").replace("heta::", "").strip()
     return n
 
 
@@ -70,12 +71,12 @@ def main() -> int:
     for f in glob.glob(os.path.join(args.out, "trace", "**", "*kernel_stats.csv"), recursive=True):
         lines.append("")
         lines.append("kernel-trace --stats (durations over the whole run, incl. warm-up):")
-        lines.append(f"{'kernel':66s} {'calls':>6s} {'total_ms':>10s} {'avg_us':>10s} {'pct':>6s}")
+        lines.append(f"{'kernel':100s} {'calls':>6s} {'total_ms':>10s} {'avg_us':>10s} {'pct':>6s}")
         with open(f) as fh:
             for r in list(csv.DictReader(fh))[:16]:
                 n = short_name(r["Name"])
                 durations[n] = float(r["AverageNs"]) / 1e3
-                lines.append(f"{n[:66]:66s} {r['Calls']:>6s} {float(r['TotalDurationNs']) / 1e6:10.3f} "
+                lines.append(f"{n[:100]:100s} {r['Calls']:>6s} {float(r['TotalDurationNs']) / 1e6:10.3f} "
                              f"{float(r['AverageNs']) / 1e3:10.1f} {float(r['Percentage']):6.2f}")
     fetch = read_counter(os.path.join(args.out, "fetch")).get("FETCH_SIZE", {})
     write = read_counter(os.path.join(args.out, "write")).get("WRITE_SIZE", {})
@@ -91,7 +92,7 @@ def main() -> int:
         lines.append("")
         lines.append(f"HBM traffic per launch (KiB counters x calibration factor: FETCH_SIZE x {f_fetch:.3f}, "
                      f"WRITE_SIZE x {f_write:.3f}; factors from the 1 GiB calibration copy):")
-        lines.append(f"{'kernel':66s} {'launches':>8s} {'read_MB':>10s} {'write_MB':>10s} {'GB/s':>8s}")
+        lines.append(f"{'kernel':100s} {'launches':>8s} {'read_MB':>10s} {'write_MB':>10s} {'GB/s':>8s}")
         fam = collections.defaultdict(lambda: [0, 0.0])
         for k in sorted(set(fetch) | set(write), key=lambda k: -(fetch.get(k, [0, 0])[1])):
             if k.startswith("at::") or "rocclr" in k:
@@ -102,7 +103,7 @@ def main() -> int:
             rd = sf / max(nf, 1) * f_fetch * 1024.0
             wr = sw / max(nw, 1) * f_write * 1024.0
             rate = (rd + wr) / (durations[k] * 1e-6) / 1e9 if k in durations else float("nan")
-            lines.append(f"{k[:66]:66s} {n:8d} {rd / 1e6:10.1f} {wr / 1e6:10.1f} {rate:8.0f}")
+            lines.append(f"{k[:100]:100s} {n:8d} {rd / 1e6:10.1f} {wr / 1e6:10.1f} {rate:8.0f}")
             a = fam[family(k)]
             a[0] += n
             a[1] += (rd + wr) * n
@@ -114,7 +115,7 @@ def main() -> int:
             for k, (n, v) in sorted(ks.items(), key=lambda kv: -kv[1][1])[:10]:
                 if k.startswith("at::") or "rocclr" in k:
                     continue
-                lines.append(f"{k[:66]:66s} n={n:6d} avg={v / n:16.1f}")
+                lines.append(f"{k[:100]:100s} n={n:6d} avg={v / n:16.1f}")
     text = "\n".join(lines) + "\n"
     if args.txt:
         with open(args.txt, "w") as fh:
