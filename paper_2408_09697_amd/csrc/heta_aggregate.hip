@@ -333,7 +333,7 @@ template <typename T, int EPC, int L, int CPL>
 __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
 {
     constexpr int G = 64 / L;            // lane groups per wavefront
-    constexpr int U = (G >= 8) ? 1 : ((G >= 4) ? 2 : 4); // edges in flight per group and step
+    constexpr int U = CPL == 2 ? 4 : ((G >= 16) ? 1 : ((G >= 8) ? 2 : ((G >= 4) ? 4 : 8))); // edges in flight per group and step
     const int lane = threadIdx.x & 63;
     const int64_t w = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
     if (w >= p.n_wave_items) return;     // uniform per wavefront
@@ -424,11 +424,13 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
 }
 
 // ---- hub rows: add the chunk partials in chunk order -------------------------------------------------
-// One workgroup per (hub row, tile of 256 columns); wave w adds the partials w, w+4, w+8, ...
-// and the four sums are combined through LDS in wave order.
-__global__ void __launch_bounds__(256) agg_hub_combine_kernel(AggParams p)
+// One workgroup of 16 wavefronts per (hub row, tile of 256 columns); wavefront w adds the partials
+// w, w+16, w+32, ... (four loads in flight) and the sixteen sums are combined through LDS in
+// wavefront order, so the summation order is fixed.
+constexpr int kCombineWaves = 16;
+__global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_kernel(AggParams p)
 {
-    __shared__ float4 part[4][64];
+    __shared__ float4 part[kCombineWaves][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t h = blockIdx.x;
     const int64_t row = p.perm[h];
@@ -436,11 +438,11 @@ __global__ void __launch_bounds__(256) agg_hub_combine_kernel(AggParams p)
     const int col0 = (blockIdx.y * 64 + lane) * 4;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
     if (col0 < p.ws_ld) {
-        for (int64_t s = s0 + wave; s < s1; s += 16) {
+        for (int64_t s = s0 + wave; s < s1; s += 4 * kCombineWaves) {
             float4 v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int64_t t = s + 4 * u;
+                const int64_t t = s + kCombineWaves * u;
                 if (t < s1) v[u] = *reinterpret_cast<const float4 *>(p.ws + t * p.ws_ld + col0);
                 else v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
@@ -453,7 +455,7 @@ __global__ void __launch_bounds__(256) agg_hub_combine_kernel(AggParams p)
     if (wave != 0 || col0 >= p.d) return;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < kCombineWaves; ++k) {
         const float4 v = part[k][lane];
         acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
     }
@@ -567,7 +569,7 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
         if (s.n_hub_rows > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many hub rows");
         const int tiles = static_cast<int>((p.ws_ld + 255) / 256);
         ProfScope prof("agg_hub_combine_kernel", st, static_cast<double>(s.n_hub_rows) * per_row, 0);
-        hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(256), 0, st, p);
+        hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, p);
         HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
     }
     return HETA_OK;

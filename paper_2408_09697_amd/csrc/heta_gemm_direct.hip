@@ -551,7 +551,7 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         // (256 output columns: the fp32 tiles of a direct A would leave LDS room for one workgroup per CU only,
         // so A goes through the register stage there)
         return wide ? launch_direct<bf16_t, float, false, false, bf16_t, false, true, 4, 32, 3, 4>(p, st, name, bytes, flops)
-                    : launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 32, 3, 3>(p, st, name, bytes, flops);
+                    : launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 32, 3, 2>(p, st, name, bytes, flops);
     }
     if (a_dt == HETA_BF16 && b_dt == HETA_BF16 && !a_rc && !b_rc) { // both k-contiguous bf16 (forward with a packed W_r^T)
         return wide ? launch_direct<bf16_t, bf16_t, false, true, bf16_t, false, true, 4, 32, 3, 4>(p, st, name, bytes, flops)
