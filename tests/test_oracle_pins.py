@@ -372,3 +372,80 @@ def test_partial_aggregation_buffer_shape_from_communication_example():
                        np.zeros((8, hidden)))
     assert Z.shape == (seeds, hidden)
 
+
+
+# ---- sparse Adam on learnable tables (Sections 2.2 and 6: learnable vectors and their optimizer states) ----
+
+def _adam_case(seed=0, n_rows=40, d=5, n_ids=17):
+    g = np.random.default_rng(seed)
+    theta = g.standard_normal((n_rows, d))
+    ids = g.permutation(n_rows)[:n_ids]
+    grads = [g.standard_normal((n_ids, d)) for _ in range(4)]
+    return theta, ids, grads
+
+
+def test_adam_first_step_is_a_signed_step_of_size_lr():
+    """From zero states, mhat = g and vhat = g^2 after the first step, so every touched element moves by
+    lr * g / (|g| + eps) (Adam paper, Section 2.1: the effective step is bounded by lr)."""
+    theta, ids, grads = _adam_case()
+    z = np.zeros_like(theta)
+    lr, eps = 0.01, 1e-8
+    t1, m1, v1 = oracle.sparse_adam_step(theta, z, z, ids, grads[0], lr, 0.9, 0.999, eps, 1)
+    g = grads[0]
+    np.testing.assert_allclose(t1[ids], theta[ids] - lr * g / (np.abs(g) + eps), rtol=1e-12, atol=0)
+    np.testing.assert_allclose(m1[ids], 0.1 * g, rtol=1e-12)
+    np.testing.assert_allclose(v1[ids], 0.001 * g * g, rtol=1e-12)
+    untouched = np.setdiff1d(np.arange(theta.shape[0]), ids)
+    assert np.array_equal(t1[untouched], theta[untouched]) and not m1[untouched].any() and not v1[untouched].any()
+
+
+def test_adam_constant_gradient_has_a_closed_form():
+    """A constant gradient keeps mhat = g and vhat = g^2 at every step (the bias corrections cancel the
+    geometric sums exactly), so after T steps theta = theta0 - T lr g / (|g| + eps)."""
+    theta, ids, grads = _adam_case(1)
+    m = np.zeros_like(theta)
+    v = np.zeros_like(theta)
+    lr, eps, T = 0.003, 1e-8, 25
+    x = theta
+    for t in range(1, T + 1):
+        x, m, v = oracle.sparse_adam_step(x, m, v, ids, grads[0], lr, 0.9, 0.999, eps, t)
+    g = grads[0]
+    np.testing.assert_allclose(x[ids], theta[ids] - T * lr * g / (np.abs(g) + eps), rtol=1e-9, atol=1e-12)
+
+
+def test_adam_matches_the_library_optimizer_when_every_row_is_touched():
+    """With all rows touched at every step the sparse step is the dense Adam of torch.optim (fp64)."""
+    import torch
+    g0 = np.random.default_rng(2)
+    n, d, T = 12, 7, 6
+    theta0 = g0.standard_normal((n, d))
+    grads = [g0.standard_normal((n, d)) for _ in range(T)]
+    lr, b1, b2, eps = 0.02, 0.8, 0.95, 1e-6
+    p = torch.nn.Parameter(torch.tensor(theta0, dtype=torch.float64))
+    opt = torch.optim.Adam([p], lr=lr, betas=(b1, b2), eps=eps)
+    x, m, v = theta0, np.zeros_like(theta0), np.zeros_like(theta0)
+    for t in range(1, T + 1):
+        perm = g0.permutation(n)                       # ids in any order: rows are independent
+        p.grad = torch.tensor(grads[t - 1], dtype=torch.float64)
+        opt.step()
+        x, m, v = oracle.sparse_adam_step(x, m, v, perm, grads[t - 1][perm], lr, b1, b2, eps, t)
+        np.testing.assert_allclose(x, p.detach().numpy(), rtol=1e-10, atol=1e-13)
+
+
+def test_adam_rows_skipped_for_a_step_keep_state_and_are_not_decayed():
+    """Lazy semantics: a row absent from `ids` is bit-for-bit unchanged, states included, and on its next
+    visit it sees the global step counter (not a per-row one)."""
+    theta, ids, grads = _adam_case(3)
+    z = np.zeros_like(theta)
+    a, b = ids[:9], ids[5:]
+    x1, m1, v1 = oracle.sparse_adam_step(theta, z, z, a, grads[0][:9], 0.01, 0.9, 0.999, 1e-8, 1)
+    x2, m2, v2 = oracle.sparse_adam_step(x1, m1, v1, b, grads[1][5:], 0.01, 0.9, 0.999, 1e-8, 2)
+    only_a = np.setdiff1d(a, b)
+    assert np.array_equal(x2[only_a], x1[only_a]) and np.array_equal(m2[only_a], m1[only_a]) and np.array_equal(v2[only_a], v1[only_a])
+    only_b = np.setdiff1d(b, a)                        # first visit at t = 2: m = 0.1 g, divided by 1 - 0.9^2
+    g = grads[1][5:][np.isin(b, only_b)]
+    r = b[np.isin(b, only_b)]
+    mhat, vhat = 0.1 * g / (1 - 0.81), 0.001 * g * g / (1 - 0.999 ** 2)
+    np.testing.assert_allclose(x2[r], theta[r] - 0.01 * mhat / (np.sqrt(vhat) + 1e-8), rtol=1e-12)
+    with pytest.raises(AssertionError):
+        oracle.sparse_adam_step(theta, z, z, np.array([1, 1]), grads[0][:2], 0.01, 0.9, 0.999, 1e-8, 1)
