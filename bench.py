@@ -154,7 +154,32 @@ def measure(storage: str, args, keep_problem: bool = False):
                                                "achieved": agg_mb / agg_ms if agg_ms else 0.0, "peak": PEAK_HBM_GBS,
                                                "unit": "GB/s",
                                                "frac": (agg_mb / agg_ms / PEAK_HBM_GBS) if agg_ms else 0.0}
-    res = {"ms_per_step": ms_per_step, "value": 2.0 * edge_features / (ms_per_step * 1e-3),
+    # The update of the learnable tables that follows backpropagation (not part of `value`): one sparse
+    # Adam step over every learnable type, all rows touched (full-graph layer), gradient = this step's dH0.
+    adam = None
+    learn = [t for t, nt in enumerate(p.graph.ntypes) if nt.learnable and t in layer.dH0 and p.pre_proj is None]
+    if learn:
+        states = {t: (torch.zeros(layer.tables[t].shape, dtype=torch.float32, device="cuda"),
+                      torch.zeros(layer.tables[t].shape, dtype=torch.float32, device="cuda")) for t in learn}
+        def adam_step(k):
+            for t in learn:
+                heta.heta_sparse_adam(layer.tables[t], states[t][0], states[t][1], layer.dH0[t], ids=None, lr=1e-3, step=k)
+        adam_step(1)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(2, 2 + args.steps):
+            adam_step(k)
+        e1.record()
+        torch.cuda.synchronize()
+        a_ms = e0.elapsed_time(e1) / max(1, args.steps)
+        esz = 2 if storage == "bf16" else 4
+        a_bytes = sum(layer.tables[t].shape[0] * layer.tables[t].shape[1] * (20 + 2 * esz) for t in learn)
+        adam = {"ms": a_ms, "rows": int(sum(layer.tables[t].shape[0] for t in learn)), "GBps": a_bytes / a_ms / 1e6,
+                "frac_of_hbm_peak": a_bytes / a_ms / 1e6 / PEAK_HBM_GBS,
+                "note": "heta_sparse_adam on every learnable table (all rows), after the timed steps; not part of value"}
+        del states
+    res = {"ms_per_step": ms_per_step, "sparse_adam": adam, "value": 2.0 * edge_features / (ms_per_step * 1e-3),
            "edges_per_s": 2.0 * n_edges / (ms_per_step * 1e-3), "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
            "ingest_ms": ingest_ms, "input_generation_s": gen_s, "roofline": roofline, "kernels": kernels,
            "edges": n_edges, "edge_features_per_pass": edge_features}
@@ -327,13 +352,14 @@ def main() -> int:
         "input_generation_s": main_res["input_generation_s"],
         "roofline": main_res["roofline"],
         "kernels": main_res["kernels"],
+        "sparse_adam": main_res["sparse_adam"],
     }
     if not args.single:
         other = "bf16" if args.dtype == "f32" else "f32"
         res, p2 = measure(other, args, keep_problem=want_cpu and other == "f32")
         problem = problem or p2
         out["bf16_storage" if other == "bf16" else "f32_storage"] = {
-            k: res[k] for k in ("value", "ms_per_step", "edges_per_s", "fwd_ms", "bwd_ms", "roofline", "kernels")}
+            k: res[k] for k in ("value", "ms_per_step", "edges_per_s", "fwd_ms", "bwd_ms", "roofline", "kernels", "sparse_adam")}
     if want_cpu:
         if problem is None:
             from gen import workloads

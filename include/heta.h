@@ -204,6 +204,22 @@ heta_status heta_act_bwd(int64_t n_rows, int32_t d, heta_act act, const float *h
                          const float *grad_out, int64_t ld_go, float *grad_in, int64_t ld_gi,
                          void *hip_stream);
 
+/* ---- sparse update of a learnable feature table (Sections 2.2 and 6: the learnable vectors of
+ * featureless node types and their optimizer states, Adam's moment and variance, are updated after
+ * backpropagation; only the rows a mini-batch touched) ---------------------------------------------
+ * For i < n, with r = ids ? ids[i] : i and g = grad[i, 0:d] (Adam, Kingma & Ba, Algorithm 1, step t):
+ *   m[r] = beta1 m[r] + (1 - beta1) g ;  v[r] = beta2 v[r] + (1 - beta2) g^2 ;
+ *   table[r] -= lr * (m[r] / (1 - beta1^t)) / (sqrt(v[r] / (1 - beta2^t)) + eps).
+ * table: device [n_table_rows, ld_table] of dt (a bf16 table is widened, updated in fp32 and rounded
+ * back); m, v: device fp32 [n_table_rows, ld_state]; grad: device fp32 [n, ld_grad]; ids: device
+ * [n] DISTINCT rows in [0, n_table_rows) (unchecked: heta_check_ids can verify the range; repeated
+ * rows would race) or NULL for the first n rows.  Rows not listed are untouched, states included.
+ * `step` is the global step counter t >= 1.  One pass, asynchronous on the stream. */
+heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_table, int32_t d, int64_t n_table_rows,
+                             float *m, float *v, int64_t ld_state, const int64_t *ids, int64_t n,
+                             const float *grad, int64_t ld_grad, float lr, float beta1, float beta2, float eps,
+                             int64_t step, void *hip_stream);
+
 /* ---- measurement --------------------------------------------------------------------------------
  * With profiling on (process-wide), every kernel the library launches is bracketed by two HIP
  * events on the stream it runs on.  heta_profile_read waits for the outstanding events and

@@ -28,7 +28,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
-           "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force"]
+           "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam"]
 
 
 class HetaError(RuntimeError):
@@ -420,6 +420,26 @@ def heta_profile_enable(on: bool) -> None:
     L = load_library()
     L.heta_profile_enable.argtypes = [ctypes.c_int32]
     _check(L.heta_profile_enable(int(bool(on))))
+
+
+def heta_sparse_adam(table: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grad: torch.Tensor,
+                     ids: Optional[torch.Tensor] = None, lr: float = 1e-3, beta1: float = 0.9, beta2: float = 0.999,
+                     eps: float = 1e-8, step: int = 1, d: Optional[int] = None, stream=None) -> torch.Tensor:
+    """One Adam step on the rows `ids` (distinct) of a learnable table, in place."""
+    d = table.shape[1] if d is None else d
+    n = grad.shape[0]
+    if ids is not None and ids.numel() < n:
+        raise HetaError(HETA_ERR_SHAPE, "fewer ids than gradient rows")
+    if m.shape[0] < table.shape[0] or v.shape[0] < table.shape[0]:
+        raise HetaError(HETA_ERR_SHAPE, "optimizer states have fewer rows than the table")
+    L = load_library()
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.heta_sparse_adam.argtypes = [vp, i32, i64, i32, i64, vp, vp, i64, vp, i64, vp, i64, f32, f32, f32, f32, i64, vp]
+    _check(L.heta_sparse_adam(_dev(table, "table"), _dt(table), _ld(table), d, table.shape[0],
+                              _dev(m, "m", torch.float32), _dev(v, "v", torch.float32), _ld(m),
+                              _dev(ids, "ids", torch.int64), n, _dev(grad, "grad", torch.float32), _ld(grad),
+                              lr, beta1, beta2, eps, int(step), _stream(stream)))
+    return table
 
 
 def heta_ingest_force(mode: int) -> None:
