@@ -110,14 +110,15 @@ heta_status heta_check_ids(const int64_t *ids, int64_t n, int64_t limit, void *h
  * HETA_MEAN divides by the row's degree; a zero-degree row gives exactly 0.
  * src_table: device [n_table_rows, ld_src] of in_dt; needs n_table_rows >= n_src when src_gid is NULL.
  * src_gid:   device [n_src] or NULL (local -> table row map of a sampled block; entries unchecked).
- * out:       device [n_dst, ld_out] of out_dt (fp32 accumulation either way).
+ * out:       device [n_dst, ld_out] of out_dt (fp32 accumulation either way); beta = 1 adds the result
+ *            to what out holds (a relation's aggregate accumulated straight into H_t), beta = 0 overwrites.
  * Rows with ld * sizeof(elem) a multiple of 16 and 16-byte aligned bases use 128-bit loads; anything
  * else runs an element-wise kernel, never an error.  May grow the handle's workspace when the
  * relation has rows of 512+ edges (first call for a wider d: hipMalloc, which synchronises). */
 heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
                                    heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
                                    const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
-                                   void *hip_stream);
+                                   float beta, void *hip_stream);
 
 /* ---- relation-specific aggregation, backward (Algorithm 1, local backpropagation with the
  * gradients of the partial aggregations) ---------------------------------------------------------
@@ -135,17 +136,19 @@ heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, c
  *   B = W          (W is [d_in, d_out], ld_w >= d_out)   when transW == 0     (forward,  Z = M W)
  *   B = W^T        (W is [d_out, d_in], ld_w >= d_in)    when transW != 0     (backward, dM = dZ W^T)
  *   s_i = row_scale ? row_scale[i] : 1.
- * in: device [n_rows, ld_in] of in_dt; W device of w_dt; out device fp32 [n_rows, ld_out].
+ * in: device [n_rows, ld_in] of in_dt; W device of w_dt; out device [n_rows, ld_out] of out_dt
+ * (fp32, or bf16 for an intermediate kept in the storage type: then beta must be 0 and row_scale NULL).
  * Both fp32 -> fp32 MFMA; otherwise operands are rounded to bf16 and multiplied on the bf16 MFMA
  * path; accumulation is fp32 in both.  beta = 1 fuses the cross-relation sum into the projection.
  * heta_rel_project takes n_rows = n_dst of the relation; heta_project any row count. */
 heta_status heta_project(int64_t n_rows, const void *in, heta_dtype in_dt, int64_t ld_in, int32_t d_in,
                          const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_out, int32_t transW,
-                         const float *row_scale, float *out, int64_t ld_out, float beta, void *hip_stream);
+                         const float *row_scale, void *out, heta_dtype out_dt, int64_t ld_out, float beta,
+                         void *hip_stream);
 heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
                              int64_t ld_in, int32_t d_in, const void *W, heta_dtype w_dt, int64_t ld_w,
-                             int32_t d_out, int32_t transW, const float *row_scale, float *out,
-                             int64_t ld_out, float beta, void *hip_stream);
+                             int32_t d_out, int32_t transW, const float *row_scale, void *out,
+                             heta_dtype out_dt, int64_t ld_out, float beta, void *hip_stream);
 
 /* Testing / measurement switch (process-wide, not thread-safe): when on, every projection runs the
  * register-staged kernel that otherwise only serves operands whose rows are not 16-byte aligned;
@@ -180,7 +183,10 @@ heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_
  * bf16: the fp32 accumulator is rounded once on the way out, for callers that store the [n x d]
  * intermediates of a layer in the storage type); dW[p] device fp32 [d_in[p], ld_dw[p] >= d_out];
  * the pointer arrays are HOST arrays.
- * The wgrad call uses the handle's workspace (may grow it, see heta_rel_aggregate_fwd). */
+ * The wgrad call uses the handle's workspace (may grow it, see heta_rel_aggregate_fwd).  With bf16
+ * inputs gout is rounded to bf16 for the MFMA; gout_two_terms != 0 feeds it as two bf16 terms (the
+ * rounded value and what the rounding left: 16 significant bits) - for a gout that was itself
+ * summed over many edges, whose magnitude makes a single rounding visible in dW. */
 heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, int32_t n, const float *gout,
                                        int64_t ld_go, int32_t d_out, const void *const *Ws, heta_dtype w_dt,
                                        const int64_t *ld_w, const int32_t *d_in, void *const *dM,
@@ -188,7 +194,7 @@ heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, in
 heta_status heta_cross_rel_project_wgrad(heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
                                          heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
                                          const float *gout, int64_t ld_go, int32_t d_out, float *const *dW,
-                                         const int64_t *ld_dw, float beta, void *hip_stream);
+                                         const int64_t *ld_dw, float beta, int32_t gout_two_terms, void *hip_stream);
 
 /* ---- cross-relation aggregation (Eq. 1, second line; Algorithm 1, AGG_all on the designated
  * worker; on a subset of relations it yields the partial aggregation a worker would send) --------

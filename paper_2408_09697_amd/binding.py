@@ -66,10 +66,10 @@ def load_library() -> ctypes.CDLL:
     L.heta_graph_get_degrees.argtypes = [vp, i32, vp]
     L.heta_feature_gather.argtypes = [vp, i32, i64, i32, i64, vp, i64, vp, i64, vp]
     L.heta_check_ids.argtypes = [vp, i64, i64, vp]
-    L.heta_rel_aggregate_fwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, i64, vp, vp, i32, i64, vp]
+    L.heta_rel_aggregate_fwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, i64, vp, vp, i32, i64, f32, vp]
     L.heta_rel_aggregate_bwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, vp, i64, f32, vp]
-    L.heta_project.argtypes = [i64, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i64, f32, vp]
-    L.heta_rel_project.argtypes = [vp, i32, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i64, f32, vp]
+    L.heta_project.argtypes = [i64, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i32, i64, f32, vp]
+    L.heta_rel_project.argtypes = [vp, i32, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i32, i64, f32, vp]
     L.heta_rel_project_wgrad.argtypes = [vp, i32, vp, i32, i64, i32, vp, i64, i32, vp, i64, f32, vp]
     L.heta_cross_rel_reduce.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, i64, vp]
     L.heta_act_bwd.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp]
@@ -224,7 +224,8 @@ def heta_check_ids(ids: torch.Tensor, limit: int, stream=None) -> None:
 
 
 def heta_rel_aggregate_fwd(g: Graph, rel: int, op: int, src_table: torch.Tensor, out: torch.Tensor,
-                           d: Optional[int] = None, src_gid: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                           d: Optional[int] = None, src_gid: Optional[torch.Tensor] = None, beta: float = 0.0,
+                           stream=None) -> torch.Tensor:
     d = src_table.shape[1] if d is None else d
     if out.shape[0] < g.n_dst(rel):
         raise HetaError(HETA_ERR_SHAPE, "out has fewer rows than the relation has destinations")
@@ -232,7 +233,7 @@ def heta_rel_aggregate_fwd(g: Graph, rel: int, op: int, src_table: torch.Tensor,
         raise HetaError(HETA_ERR_SHAPE, "src_gid has fewer entries than the relation has sources")
     _check(load_library().heta_rel_aggregate_fwd(
         g.handle, rel, op, _dev(src_table, "src_table"), _dt(src_table), _ld(src_table), d, src_table.shape[0],
-        _dev(src_gid, "src_gid", torch.int64), _dev(out, "out"), _dt(out), _ld(out), _stream(stream)))
+        _dev(src_gid, "src_gid", torch.int64), _dev(out, "out"), _dt(out), _ld(out), beta, _stream(stream)))
     return out
 
 
@@ -266,7 +267,7 @@ def heta_project(inp: torch.Tensor, W: torch.Tensor, out: torch.Tensor, trans_w:
         raise HetaError(HETA_ERR_SHAPE, "row_scale too short")
     _check(load_library().heta_project(
         n_rows, _dev(inp, "in"), _dt(inp), _ld(inp), d_in, _dev(W, "W"), _dt(W), _w_ld(W), d_out, int(trans_w),
-        _dev(row_scale, "row_scale", torch.float32), _dev(out, "out", torch.float32), _ld(out), beta, _stream(stream)))
+        _dev(row_scale, "row_scale", torch.float32), _dev(out, "out"), _dt(out), _ld(out), beta, _stream(stream)))
     return out
 
 
@@ -284,7 +285,7 @@ def heta_rel_project(g: Graph, rel: int, inp: torch.Tensor, W: torch.Tensor, out
         raise HetaError(HETA_ERR_SHAPE, "row_scale too short")
     _check(load_library().heta_rel_project(
         g.handle, rel, _dev(inp, "in"), _dt(inp), _ld(inp), d_in, _dev(W, "W"), _dt(W), _w_ld(W), d_out,
-        int(trans_w), _dev(row_scale, "row_scale", torch.float32), _dev(out, "out", torch.float32), _ld(out),
+        int(trans_w), _dev(row_scale, "row_scale", torch.float32), _dev(out, "out"), _dt(out), _ld(out),
         beta, _stream(stream)))
     return out
 
@@ -361,7 +362,8 @@ def heta_cross_rel_project_bwd(g: Graph, dst_type: int, gout: torch.Tensor, Ws: 
 
 
 def heta_cross_rel_project_wgrad(g: Graph, dst_type: int, ins: List[torch.Tensor], gout: torch.Tensor,
-                                 dW: List[torch.Tensor], beta: float = 0.0, stream=None) -> List[torch.Tensor]:
+                                 dW: List[torch.Tensor], beta: float = 0.0, gout_two_terms: bool = False,
+                                 stream=None) -> List[torch.Tensor]:
     """dW[p] = beta*dW[p] + ins[p]^T @ gout for every relation p into dst_type, one launch."""
     n_rows = g.ntypes[dst_type][0]
     d_out = gout.shape[1]
@@ -373,13 +375,13 @@ def heta_cross_rel_project_wgrad(g: Graph, dst_type: int, ins: List[torch.Tensor
     L = load_library()
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     L.heta_cross_rel_project_wgrad.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i64, i32, vp, vp,
-                                               ctypes.c_float, vp]
+                                               ctypes.c_float, i32, vp]
     a_in, a_dw = _ptr_array(ins, "in"), _ptr_array(dW, "dW", torch.float32)
     ld_in, d_in, ld_dw = _i64_array([_ld(x) for x in ins]), _i32_array([x.shape[1] for x in ins]), \
         _i64_array([_ld(w) for w in dW])
     _check(L.heta_cross_rel_project_wgrad(g.handle, dst_type, len(ins), a_in, _dt(ins[0]), ld_in, d_in,
                                           _dev(gout, "gout", torch.float32), _ld(gout), d_out, a_dw, ld_dw, beta,
-                                          _stream(stream)))
+                                          int(gout_two_terms), _stream(stream)))
     return dW
 
 

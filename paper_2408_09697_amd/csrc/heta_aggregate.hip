@@ -602,12 +602,13 @@ extern "C" {
 heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
                                    heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
                                    const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
-                                   void *hip_stream)
+                                   float beta, void *hip_stream)
 {
     if (!g || !src_table || !out) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: null argument");
     if (rel < 0 || rel >= (int32_t)g->rels.size())
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: relation %d out of range", rel);
     if (op != HETA_SUM && op != HETA_MEAN) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: bad reduce op");
+    if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_fwd: beta must be 0 or 1");
     if (!valid_dtype(in_dt) || !valid_dtype(out_dt))
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: bad dtype");
     if (d <= 0 || ld_src < d || ld_out < d)
@@ -630,7 +631,7 @@ heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, c
     p.out = out;
     p.ld_out = ld_out;
     p.out_bf16 = (out_dt == HETA_BF16);
-    p.beta = 0.f;
+    p.beta = beta;
     p.d = d;
     return run_aggregate(g, r.csr, p, in_dt, ld_src, as_stream(hip_stream));
 }

@@ -33,6 +33,7 @@ struct GemmParams {
     const float *row_scale;
     float beta;
     int relu;
+    int split_b;         // bf16 product with an fp32 B: feed B as two bf16 terms (value = hi + lo, 16 significant bits)
     int out_bf16;        // outputs are bf16 [M][ldc] (plain stores only: no beta, scale, activation, split)
     int64_t k_per_split; // multiple of BK
     int n_split;
@@ -152,6 +153,41 @@ struct TileLoader {
                 }
             }
             ptr[i] += step;
+        }
+    }
+
+    // second term of an fp32 operand fed as two bf16 terms: what rounding to bf16 left over, in the
+    // same LDS layout as store() (pair-interleaved r-contiguous operands only)
+    __device__ __forceinline__ void store_residual(CT *lds, int tid) const
+    {
+        static_assert(sizeof(S) == 4, "only an fp32 operand has a residual");
+        if constexpr (PAIR && sizeof(S) == 4) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int q = tid + NT * i;
+                if (ITEMS % NT != 0 && q >= ITEMS) continue;
+                union Chunk { uint4 u; float s[E]; } t[LPI];
+#pragma unroll
+                for (int l = 0; l < LPI; ++l) {
+                    t[l].u = raw[i][l];
+                    if (VEC && left[i][l] < E) {
+#pragma unroll
+                        for (int j = 0; j < E; ++j) if (j >= left[i][l]) t[l].s[j] = 0.f;
+                    }
+                }
+                const int r = row_of(q), k = k_of(q);
+                uint32_t w[E];
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    const float a = t[0].s[j], b = t[LPI - 1].s[j];
+                    const float ra = a - __uint_as_float(static_cast<uint32_t>(to_bf16(a)) << 16);
+                    const float rb = b - __uint_as_float(static_cast<uint32_t>(to_bf16(b)) << 16);
+                    w[j] = static_cast<uint32_t>(to_bf16(ra)) | (static_cast<uint32_t>(to_bf16(rb)) << 16);
+                }
+                uint32_t *dst = reinterpret_cast<uint32_t *>(lds) + (k / 2) * ROWS + r;
+#pragma unroll
+                for (int j = 0; j < E; j += 4) *reinterpret_cast<uint4 *>(dst + j) = make_uint4(w[j], w[j + 1], w[j + 2], w[j + 3]);
+            }
         }
     }
 

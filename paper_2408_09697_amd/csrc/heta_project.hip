@@ -32,12 +32,14 @@
 
 namespace heta {
 
-template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN, bool VEC, int BK>
+template <typename CT, typename SA_T, bool A_RC, typename SB_T, bool B_RC, int WN, bool VEC, int BK, bool B_SPLIT = false>
 __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
 {
     constexpr int NT = 128 * WN, BN = 64 * WN;
     __shared__ __attribute__((aligned(16))) CT As[LdsTile<CT, A_RC, BM, BK>::elems];
     __shared__ __attribute__((aligned(16))) CT Bs[LdsTile<CT, B_RC, BN, BK>::elems];
+    // B_SPLIT: an fp32 B is fed to the bf16 MFMAs as two terms (rounded value + what the rounding left)
+    __shared__ __attribute__((aligned(16))) CT Bs_lo[B_SPLIT ? LdsTile<CT, B_RC, BN, BK>::elems : 8];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave / WN) * 64, wn = (wave % WN) * 64;
     const int half = lane >> 5, l32 = lane & 31;
@@ -102,6 +104,7 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
         __syncthreads(); // previous tile fully consumed
         la.store(As, tid);
         lb.store(Bs, tid);
+        if constexpr (B_SPLIT) lb.store_residual(Bs_lo, tid);
         __syncthreads();
         // start the next tile's loads; they complete behind the MFMAs below
         have = lk < lend || next_segment();
@@ -135,6 +138,15 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+                if constexpr (B_SPLIT) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) b[j].u = frag_bf16<B_RC, BN, BK>(Bs_lo, wn + j * 32 + l32, kk, half);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+                }
             }
         }
     }
@@ -246,6 +258,13 @@ static heta_status launch_gemm(GemmParams &p, hipStream_t st, int bk)
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
     ProfScope prof(sizeof(CT) == 4 ? (p.partial ? "gemm_wgrad_f32" : "gemm_f32") : (p.partial ? "gemm_wgrad_bf16" : "gemm_bf16"),
                    st, bytes, flops);
+    if constexpr (sizeof(CT) == 2 && A_RC && B_RC && sizeof(SB_T) == 4) {
+        if (p.split_b) {
+            hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN, VEC, 32, true>), dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
+            HETA_LAUNCH_CHECK("gemm_kernel");
+            return HETA_OK;
+        }
+    }
     if (sizeof(CT) == 2 && A_RC && B_RC && bk == 64)
         hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN, VEC, (sizeof(CT) == 2 && A_RC && B_RC) ? 64 : 32>),
                            dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
@@ -313,8 +332,9 @@ static bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintp
 // out = beta*out + row_scale * sum_s in_s . (W_s or W_s^T)
 static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
                                 const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
-                                int32_t d_out, int32_t transW, const float *row_scale, int relu, float *out,
-                                int64_t ld_out, float beta, hipStream_t st, const char *who, heta_graph *pack_owner = nullptr)
+                                int32_t d_out, int32_t transW, const float *row_scale, int relu, void *out,
+                                int64_t ld_out, float beta, hipStream_t st, const char *who, heta_graph *pack_owner = nullptr,
+                                heta_dtype out_dt = HETA_F32)
 {
     if (!ins || !Ws || !out || !ld_in || !d_in || !ld_w) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
     if (n_seg < 1 || n_seg > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d inputs", who, kMaxSeg);
@@ -322,8 +342,12 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
     for (int s = 0; s < n_seg; ++s)
         if (!ins[s] || !Ws[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
     if (n_rows < 0 || d_out <= 0 || ld_out < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
-    if (misaligned(out, 4)) return fail(HETA_ERR_INVALID_ARG, "%s: out not 4-byte aligned", who);
+    if (!valid_dtype(out_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
+    if (misaligned(out, dtype_size(out_dt))) return fail(HETA_ERR_INVALID_ARG, "%s: out not aligned to its element size", who);
+    if (out_dt == HETA_BF16 && (beta != 0.f || row_scale || relu))
+        return fail(HETA_ERR_UNSUPPORTED, "%s: a bf16 output takes no beta, row_scale or activation", who);
     GemmParams p{};
+    p.out_bf16 = out_dt == HETA_BF16;
     for (int s = 0; s < n_seg; ++s) {
         if (d_in[s] <= 0 || ld_in[s] < d_in[s] || ld_w[s] < (transW ? d_in[s] : d_out))
             return fail(HETA_ERR_SHAPE, "%s: leading dimension smaller than the row width", who);
@@ -334,7 +358,7 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
         g.lda = ld_in[s];
         g.B = Ws[s];
         g.ldb = ld_w[s];
-        g.C = out;
+        g.C = static_cast<float *>(out); // typed by p.out_bf16 in the kernels' epilogue
         g.ldc = ld_out;
         g.M = n_rows;
         g.N = d_out;
@@ -387,7 +411,8 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
 // dW_s = beta*dW_s + in_s^T . gout over n_rows graph rows, all s in one launch
 static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const void *const *ins, heta_dtype in_dt,
                               const int64_t *ld_in, const int32_t *d_in, const float *gout, int64_t ld_go, int32_t d_out,
-                              float *const *dW, const int64_t *ld_dw, float beta, hipStream_t st, const char *who)
+                              float *const *dW, const int64_t *ld_dw, float beta, hipStream_t st, const char *who,
+                              int gout_two_terms = 0)
 {
     if (!g || !ins || !gout || !dW || !ld_in || !d_in || !ld_dw) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
     if (n_seg < 1 || n_seg > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d inputs", who, kMaxSeg);
@@ -442,6 +467,7 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     p.k_per_split = tiles_per_split * BK;
     p.n_split = static_cast<int>(n_split);
     p.partial = 1;
+    p.split_b = (gout_two_terms && in_dt == HETA_BF16) ? 1 : 0;
     e = dispatch_gemm<true, true>(p, in_dt, HETA_F32, st, static_cast<int>(BK));
     if (e != HETA_OK) return e;
     for (int s = 0; s < n_seg; ++s) {
@@ -476,22 +502,23 @@ heta_status heta_projection_force_staged(int32_t on)
 
 heta_status heta_project(int64_t n_rows, const void *in, heta_dtype in_dt, int64_t ld_in, int32_t d_in,
                          const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_out, int32_t transW,
-                         const float *row_scale, float *out, int64_t ld_out, float beta, void *hip_stream)
+                         const float *row_scale, void *out, heta_dtype out_dt, int64_t ld_out, float beta,
+                         void *hip_stream)
 {
     return project_impl(n_rows, 1, &in, in_dt, &ld_in, &d_in, &W, w_dt, &ld_w, d_out, transW, row_scale, 0, out, ld_out,
-                        beta, as_stream(hip_stream), "heta_project");
+                        beta, as_stream(hip_stream), "heta_project", nullptr, out_dt);
 }
 
 heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
                              int64_t ld_in, int32_t d_in, const void *W, heta_dtype w_dt, int64_t ld_w,
-                             int32_t d_out, int32_t transW, const float *row_scale, float *out,
-                             int64_t ld_out, float beta, void *hip_stream)
+                             int32_t d_out, int32_t transW, const float *row_scale, void *out,
+                             heta_dtype out_dt, int64_t ld_out, float beta, void *hip_stream)
 {
     if (!g) return fail(HETA_ERR_INVALID_ARG, "heta_rel_project: graph is NULL");
     if (rel < 0 || rel >= (int32_t)g->rels.size())
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_project: relation %d out of range", rel);
     return project_impl(g->rels[rel].n_dst, 1, &in, in_dt, &ld_in, &d_in, &W, w_dt, &ld_w, d_out, transW, row_scale, 0,
-                        out, ld_out, beta, as_stream(hip_stream), "heta_rel_project", const_cast<heta_graph *>(g));
+                        out, ld_out, beta, as_stream(hip_stream), "heta_rel_project", const_cast<heta_graph *>(g), out_dt);
 }
 
 heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
@@ -565,12 +592,12 @@ heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, in
 heta_status heta_cross_rel_project_wgrad(heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
                                          heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
                                          const float *gout, int64_t ld_go, int32_t d_out, float *const *dW,
-                                         const int64_t *ld_dw, float beta, void *hip_stream)
+                                         const int64_t *ld_dw, float beta, int32_t gout_two_terms, void *hip_stream)
 {
     heta_status e = check_type(g, dst_type, "heta_cross_rel_project_wgrad");
     if (e != HETA_OK) return e;
     return wgrad_impl(g, g->ntypes[dst_type].num_nodes, n, ins, in_dt, ld_in, d_in, gout, ld_go, d_out, dW, ld_dw, beta,
-                      as_stream(hip_stream), "heta_cross_rel_project_wgrad");
+                      as_stream(hip_stream), "heta_cross_rel_project_wgrad", gout_two_terms);
 }
 
 } // extern "C"

@@ -26,7 +26,8 @@ class RafLayer:
     def __init__(self, graph: hb.Graph, op: int, tables: Sequence[Optional[torch.Tensor]],
                  W: Sequence[torch.Tensor], d_out: int, pre_proj: Optional[Sequence[torch.Tensor]] = None,
                  src_gid: Optional[Sequence[Optional[torch.Tensor]]] = None, relu: bool = False,
-                 m_dtype: Optional[torch.dtype] = None, rels: Optional[Sequence[int]] = None):
+                 m_dtype: Optional[torch.dtype] = None, rels: Optional[Sequence[int]] = None,
+                 project_first: Optional[bool] = None):
         self.g = graph
         self.op = op
         self.tables = list(tables)
@@ -64,12 +65,22 @@ class RafLayer:
             q = 16 // torch.empty((), dtype=dtype).element_size()
             return torch.empty((n, (d + q - 1) // q * q), dtype=dtype, device=dev)[:, :d]
 
-        self.M = {r: padded(graph.n_dst(r), self.d_rel[r], m_dtype) for r in self.rels}
+        # Aggregation and projection commute (Eq. 1 is linear in H0).  A relation whose input is wider than
+        # the output is projected first: Z'_r = H0_s W_r over the source rows, then aggregated at the
+        # output width straight into H_t - fewer bytes per edge, no M_r, and the contraction runs over
+        # the source rows instead of the destination rows.  Only for whole-table sources (no src_gid).
+        auto = src_gid is None and pre_proj is None
+        self.pf = set(r for r in self.rels if self.d_rel[r] > d_out) if (auto if project_first is None else project_first) else set()
+        self._pf_active = set()  # what the last forward actually used (the other call paths aggregate first)
+        self._padded = padded
+        self._m_shapes = {r: (graph.n_dst(r), self.d_rel[r]) for r in self.rels}
+        self.M = {r: padded(graph.n_dst(r), self.d_rel[r], m_dtype) for r in self.rels if r not in self.pf}
         # dM_r, like the saved M_r, is an [n x d] intermediate that the backward aggregation re-reads once
         # per edge: it is kept in the storage type (bf16 tables -> bf16 dM_r, fp32 accumulation around it)
-        self._padded = padded
-        self.dM = {r: padded(graph.n_dst(r), self.d_rel[r], m_dtype) for r in self.rels}
+        self.dM = {r: padded(graph.n_dst(r), self.d_rel[r], m_dtype) for r in self.rels if r not in self.pf}
         self._dM32 = None  # fp32 dM_r for the per-relation call path, whose projection writes fp32
+        self.Zp = {r: padded(graph.n_src(r), d_out, m_dtype) for r in self.pf}
+        self.Ghat = {r: padded(graph.n_src(r), d_out, torch.float32) for r in self.pf}
         self.H = {t: torch.empty((graph.ntypes[t][0], d_out), dtype=torch.float32, device=dev)
                   for t in self.rels_into}
         self.dW = {r: torch.empty((self.d_rel[r], d_out), dtype=torch.float32, device=dev) for r in self.rels}
@@ -91,6 +102,14 @@ class RafLayer:
                 if h0 is not None:
                     hb.heta_project(self.tables[t], self.pre_proj[t], h0, stream=stream)
 
+    def _aggregate_first_everywhere(self):
+        """The per-relation and unfused call paths aggregate first: give every relation its M_r / dM_r."""
+        self._pf_active = set()
+        for r in self.rels:
+            if r not in self.M:
+                self.M[r] = self._padded(*self._m_shapes[r], self.m_dtype)
+                self.dM[r] = self._padded(*self._m_shapes[r], self.m_dtype)
+
     def _aggregate(self, r: int, stream):
         s = self.g.rels[r][0]
         gid = None if self.src_gid is None else self.src_gid[s]
@@ -101,19 +120,33 @@ class RafLayer:
     def forward(self, stream=None) -> Dict[int, torch.Tensor]:
         """aggregate every relation, then one fused projection + cross-relation sum per type."""
         self._pre_project(stream)
-        for t, rs in self.rels_into.items():
+        self._pf_active = set(self.pf)
+        for t, all_rs in self.rels_into.items():
+            rs = [r for r in all_rs if r not in self.pf]
+            pfs = [r for r in all_rs if r in self.pf]
             for r in rs:
                 self._aggregate(r, stream)
+            wrote = False
             for c in range(0, len(rs), 8):  # the library takes up to 8 relations per call
                 part = rs[c:c + 8]
-                last = c + 8 >= len(rs)
+                last = c + 8 >= len(rs) and not pfs
                 hb.heta_cross_rel_project(self.g, t, [self.M[r] for r in part], [self.W[r] for r in part], self.H[t],
                                           act=self.act if last else hb.HETA_ACT_NONE, beta=0.0 if c == 0 else 1.0,
                                           stream=stream)
+                wrote = True
+            for r in pfs:  # project over the source rows, aggregate at the output width into H_t
+                s = self.g.rels[r][0]
+                hb.heta_project(self.source(s), self.W[r], self.Zp[r], n_rows=self.g.n_src(r), stream=stream)
+                hb.heta_rel_aggregate_fwd(self.g, r, self.op, self.Zp[r], self.H[t], d=self.d_out,
+                                          beta=1.0 if wrote else 0.0, stream=stream)
+                wrote = True
+            if pfs and self.relu:
+                hb.heta_cross_rel_reduce(self.g, t, [self.H[t]], self.H[t], act=hb.HETA_ACT_RELU, stream=stream)
         return self.H
 
     def forward_per_relation(self, stream=None) -> Dict[int, torch.Tensor]:
         """Same result with one projection per relation accumulating into H (beta = 1)."""
+        self._aggregate_first_everywhere()
         self._pre_project(stream)
         for t, rs in self.rels_into.items():
             for k, r in enumerate(rs):
@@ -126,6 +159,7 @@ class RafLayer:
 
     def forward_unfused(self, stream=None) -> Dict[int, torch.Tensor]:
         """Same result through explicit per-relation partials Z_r and heta_cross_rel_reduce."""
+        self._aggregate_first_everywhere()
         self._pre_project(stream)
         for t, rs in self.rels_into.items():
             Z = []
@@ -140,7 +174,9 @@ class RafLayer:
     # ---- backward: dZ = G; dW = M^T dZ; dM = dZ W^T; dH0 += CSC gather of dM ---------------------------
     def backward(self, G: Dict[int, torch.Tensor], stream=None, per_relation: bool = False):
         first_for_src = {s: True for s in self.rels_from}
-        for t, rs in self.rels_into.items():
+        for t, all_rs in self.rels_into.items():
+            rs = [r for r in all_rs if r not in self._pf_active]
+            pfs = [r for r in all_rs if r in self._pf_active]
             g = G[t]
             if self.relu:
                 g = hb.heta_act_bwd(hb.HETA_ACT_RELU, self.H[t], G[t], self._Gact[t], stream=stream)
@@ -164,6 +200,15 @@ class RafLayer:
                 s = self.g.rels[r][0]
                 hb.heta_rel_aggregate_bwd(self.g, r, self.op, dM[r], self.dH0[s],
                                           beta=0.0 if first_for_src[s] else 1.0, stream=stream)
+                first_for_src[s] = False
+            for r in pfs:  # dZ'_r = CSC gather of G_t; dW_r = H0_s^T dZ'_r; dH0_s += dZ'_r W_r^T
+                s = self.g.rels[r][0]
+                hb.heta_rel_aggregate_bwd(self.g, r, self.op, g, self.Ghat[r], d=self.d_out, stream=stream)
+                # dZ'_r sums G over a source's out-edges: fed to the bf16 MFMA as two terms so that its size does not show in dW
+                hb.heta_cross_rel_project_wgrad(self.g, s, [self.source(s)], self.Ghat[r], [self.dW[r]],
+                                                gout_two_terms=True, stream=stream)
+                hb.heta_project(self.Ghat[r], self.W[r], self.dH0[s], trans_w=True, n_rows=self.g.n_src(r),
+                                beta=0.0 if first_for_src[s] else 1.0, stream=stream)
                 first_for_src[s] = False
         if self.pre_proj is not None:
             for s, gh in self.dH0.items():

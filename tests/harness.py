@@ -32,7 +32,7 @@ def make_graph(p) -> heta.Graph:
     return heta.heta_graph_create(nts, rels)
 
 
-def make_layer(p, graph: Optional[heta.Graph] = None, rels=None) -> heta.RafLayer:
+def make_layer(p, graph: Optional[heta.Graph] = None, rels=None, project_first=None) -> heta.RafLayer:
     graph = make_graph(p) if graph is None else graph
     pad = 8 if p.storage == "bf16" else 4
     tables = [dev_table(t, p.storage, pad) for t in p.tables]
@@ -43,19 +43,20 @@ def make_layer(p, graph: Optional[heta.Graph] = None, rels=None) -> heta.RafLaye
         gid = [None if g is None else torch.from_numpy(np.ascontiguousarray(g, dtype=np.int64)).cuda()
                for g in p.src_gid]
     op = heta.HETA_MEAN if p.op == "mean" else heta.HETA_SUM
-    return heta.RafLayer(graph, op, tables, W, p.d_out, pre_proj=P, src_gid=gid, relu=p.relu, rels=rels)
+    return heta.RafLayer(graph, op, tables, W, p.d_out, pre_proj=P, src_gid=gid, relu=p.relu, rels=rels,
+                         project_first=project_first)
 
 
-def run_layer_on_gpu(p, mode: str = "fused") -> Dict[str, dict]:
+def run_layer_on_gpu(p, mode: str = "fused", project_first=None) -> Dict[str, dict]:
     """mode: "fused" (one projection per destination type), "per_relation" (one projection per
     relation accumulating with beta = 1) or "unfused" (explicit partials + cross-relation reduce)."""
-    layer = make_layer(p)
+    layer = make_layer(p, project_first=project_first)
     H = {"fused": layer.forward, "per_relation": layer.forward_per_relation, "unfused": layer.forward_unfused}[mode]()
     G = {t: torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).cuda() for t, g in p.G.items()}
     dW, dH0, dT = layer.backward(G, per_relation=(mode != "fused"))
     torch.cuda.synchronize()
     f = lambda x: x.float().cpu().numpy()
-    out = {"H": {t: f(h) for t, h in H.items()}, "M": {r: f(m) for r, m in layer.M.items()},
+    out = {"H": {t: f(h) for t, h in H.items()}, "M": {r: f(m) for r, m in layer.M.items() if r not in layer._pf_active},
            "dW": {r: f(w) for r, w in dW.items()}, "dH0": {s: f(x) for s, x in dH0.items()},
            "dT": {s: f(x) for s, x in dT.items()}}
     layer.g.destroy()
@@ -86,7 +87,8 @@ def compare_layer(p, got, ref_f, ref_b, tol: float, tol_m: Optional[float] = Non
     for t, h in ref_f.H.items():
         assert_rows_close(got["H"][t], h, tol, f"H[{t}]")
     for r, m in ref_f.M.items():
-        assert_rows_close(got["M"][r], m, tol_m, f"M[{r}]")
+        if r in got["M"]:  # relations that were projected first have no M_r
+            assert_rows_close(got["M"][r], m, tol_m, f"M[{r}]")
     for r, w in dW.items():
         assert_rows_close(got["dW"][r], w, tol, f"dW[{r}]")
     assert set(got["dH0"]) == set(dH0)

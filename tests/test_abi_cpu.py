@@ -79,10 +79,10 @@ def test_null_handle_calls_fail_cleanly():
     assert lib.heta_graph_destroy(None) == hb.HETA_OK
     assert lib.heta_graph_get_csc(None, 0, None, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_graph_get_degrees(None, 0, None) == hb.HETA_ERR_INVALID_ARG
-    assert lib.heta_rel_aggregate_fwd(None, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_rel_aggregate_fwd(None, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_rel_aggregate_bwd(None, 0, 0, None, 0, 0, 0, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
-    assert lib.heta_project(0, None, 0, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
-    assert lib.heta_rel_project(None, 0, None, 0, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_project(0, None, 0, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_rel_project(None, 0, None, 0, 0, 0, None, 0, 0, 0, 0, None, None, 0, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_rel_project_wgrad(None, 0, None, 0, 0, 0, None, 0, 0, None, 0, 0.0, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_cross_rel_reduce(None, 0, None, 0, 0, 0, 0, None, 0, None) == hb.HETA_ERR_INVALID_ARG
     assert lib.heta_act_bwd(0, 0, 0, None, 0, None, 0, None, 0, None) == hb.HETA_ERR_INVALID_ARG
@@ -93,7 +93,7 @@ def test_null_handle_calls_fail_cleanly():
 def test_project_shape_checks_happen_before_any_launch():
     lib = hb.load_library()
     one = 16  # fake, 4-byte aligned non-null addresses: rejected before they are ever dereferenced
-    assert lib.heta_project(4, one, 0, 2, 8, one, 0, 8, 8, 0, None, one, 8, 0.0, None) == hb.HETA_ERR_SHAPE   # ld_in < d_in
-    assert lib.heta_project(4, one, 7, 8, 8, one, 0, 8, 8, 0, None, one, 8, 0.0, None) == hb.HETA_ERR_INVALID_ARG  # dtype
-    assert lib.heta_project(4, one + 2, 0, 8, 8, one, 0, 8, 8, 0, None, one, 8, 0.0, None) == hb.HETA_ERR_INVALID_ARG  # align
+    assert lib.heta_project(4, one, 0, 2, 8, one, 0, 8, 8, 0, None, one, 0, 8, 0.0, None) == hb.HETA_ERR_SHAPE   # ld_in < d_in
+    assert lib.heta_project(4, one, 7, 8, 8, one, 0, 8, 8, 0, None, one, 0, 8, 0.0, None) == hb.HETA_ERR_INVALID_ARG  # dtype
+    assert lib.heta_project(4, one + 2, 0, 8, 8, one, 0, 8, 8, 0, None, one, 0, 8, 0.0, None) == hb.HETA_ERR_INVALID_ARG  # align
     assert lib.heta_act_bwd(4, 8, 5, one, 8, one, 8, one, 8, None) == hb.HETA_ERR_INVALID_ARG

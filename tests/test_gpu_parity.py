@@ -454,9 +454,13 @@ def test_layer_config3_scaled_device_ingest(storage):
     compare_layer(p, got, ref_f, ref_b, tol=TOL[storage])
 
 
-def test_layer_config4_scaled(gemm_path):
+@pytest.mark.parametrize("project_first", [None, False])
+def test_layer_config4_scaled(gemm_path, project_first):
+    """Default: relations wider than the output (300, 512, 789 -> 256) are projected first and aggregated
+    at the output width; False: every relation aggregates first.  Same embeddings and gradients."""
     p = workloads.config4(scale=0.01)
-    got = run_layer_on_gpu(p)
+    got = run_layer_on_gpu(p, project_first=project_first)
+    assert (len(got["M"]) < len(p.graph.relations)) == (project_first is None)
     ref_f = oracle.layer_forward(p)
     ref_b = oracle.layer_backward(p, ref_f, p.G)
     compare_layer(p, got, ref_f, ref_b, tol=2e-2)
