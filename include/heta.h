@@ -163,6 +163,29 @@ heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, h
                                    int64_t ld_in, int32_t d_in, const float *gout, int64_t ld_go,
                                    int32_t d_out, float *dW, int64_t ld_dw, float beta, void *hip_stream);
 
+/* ---- several projections in one launch (the same per-relation weight matrices; used when relations
+ * are projected before they are aggregated, which Eq. 1's linearity allows) --------------------------
+ * heta_project_batch: outs[p] = ins[p] . (Ws[p] or Ws[p]^T) for p < n (1..8), independent products
+ *   scheduled so that operands several of them share (e.g. one source table under the weights of all
+ *   its outgoing relations) are fetched from HBM once.  outs[p] device [n_rows, ld_out[p]] of out_dt.
+ * heta_project_sum:   out = beta * out + sum_p ins[p] . (Ws[p] or Ws[p]^T), one contraction over the
+ *   concatenated k ranges (e.g. a source type's input gradient summed over its outgoing relations).
+ * heta_project_wgrad_batch: dW[p] = beta * dW[p] + ins[p]^T . gouts[p] over n_rows rows, every p with
+ *   its own gradient operand; uses the handle's workspace; gout_two_terms as in
+ *   heta_cross_rel_project_wgrad.
+ * Pointer and size arrays are HOST arrays of n entries; shapes and dtypes as in heta_project. */
+heta_status heta_project_batch(int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+                               const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
+                               int32_t d_out, int32_t transW, void *const *outs, heta_dtype out_dt,
+                               const int64_t *ld_out, void *hip_stream);
+heta_status heta_project_sum(int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+                             const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
+                             int32_t d_out, int32_t transW, float *out, int64_t ld_out, float beta, void *hip_stream);
+heta_status heta_project_wgrad_batch(heta_graph *g, int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt,
+                                     const int64_t *ld_in, const int32_t *d_in, const float *const *gouts,
+                                     const int64_t *ld_go, int32_t d_out, float *const *dW, const int64_t *ld_dw,
+                                     float beta, int32_t gout_two_terms, void *hip_stream);
+
 /* ---- projection of all relations into one destination type, fused with the cross-relation sum --
  * (Eq. 1, both lines in one pass; Algorithm 1, relation-specific aggregation followed by AGG_all.)
  * out[i, 0:d_out] = act(beta * out[i, 0:d_out] + sum_{p<n} ins[p][i, 0:d_in[p]] . Ws[p]),  i < n_rows(dst_type):

@@ -28,7 +28,8 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
-           "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam"]
+           "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam", "heta_project_batch",
+           "heta_project_sum", "heta_project_wgrad_batch"]
 
 
 class HetaError(RuntimeError):
@@ -338,6 +339,72 @@ def heta_cross_rel_project(g: Graph, dst_type: int, ins: List[torch.Tensor], Ws:
                                     ld_w, d_out, act, _dev(out, "out", torch.float32), _ld(out), beta,
                                     _stream(stream)))
     return out
+
+
+def heta_project_batch(ins: List[torch.Tensor], Ws: List[torch.Tensor], outs: List[torch.Tensor], trans_w: bool = False,
+                       n_rows: Optional[int] = None, stream=None) -> List[torch.Tensor]:
+    """outs[p] = ins[p] @ (Ws[p]^T if trans_w else Ws[p]), independent products in one launch."""
+    n_rows = ins[0].shape[0] if n_rows is None else n_rows
+    d_out = Ws[0].shape[0] if trans_w else Ws[0].shape[1]
+    if not ins or len(ins) != len(Ws) or len(ins) != len(outs):
+        raise HetaError(HETA_ERR_SHAPE, "bad arguments")
+    for x, w, o in zip(ins, Ws, outs):
+        if (w.shape[1] if trans_w else w.shape[0]) != x.shape[1] or (w.shape[0] if trans_w else w.shape[1]) != d_out \
+                or x.shape[0] < n_rows or o.shape[0] < n_rows or o.shape[1] < d_out or x.dtype != ins[0].dtype \
+                or w.dtype != Ws[0].dtype or o.dtype != outs[0].dtype:
+            raise HetaError(HETA_ERR_SHAPE, "inputs / weights / outputs do not match")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_project_batch.argtypes = [i64, i32, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, i32, vp, vp]
+    _check(L.heta_project_batch(n_rows, len(ins), _ptr_array(ins, "in"), _dt(ins[0]), _i64_array([_ld(x) for x in ins]),
+                                _i32_array([x.shape[1] for x in ins]), _ptr_array(Ws, "W"), _dt(Ws[0]),
+                                _i64_array([w.stride(0) for w in Ws]), d_out, int(trans_w), _ptr_array(outs, "out"),
+                                _dt(outs[0]), _i64_array([_ld(o) for o in outs]), _stream(stream)))
+    return outs
+
+
+def heta_project_sum(ins: List[torch.Tensor], Ws: List[torch.Tensor], out: torch.Tensor, trans_w: bool = False,
+                     beta: float = 0.0, n_rows: Optional[int] = None, stream=None) -> torch.Tensor:
+    """out = beta*out + sum_p ins[p] @ (Ws[p]^T if trans_w else Ws[p]), one contraction."""
+    n_rows = ins[0].shape[0] if n_rows is None else n_rows
+    d_out = Ws[0].shape[0] if trans_w else Ws[0].shape[1]
+    if not ins or len(ins) != len(Ws) or out.shape[0] < n_rows or out.shape[1] < d_out:
+        raise HetaError(HETA_ERR_SHAPE, "bad arguments")
+    for x, w in zip(ins, Ws):
+        if (w.shape[1] if trans_w else w.shape[0]) != x.shape[1] or (w.shape[0] if trans_w else w.shape[1]) != d_out \
+                or x.shape[0] < n_rows or x.dtype != ins[0].dtype or w.dtype != Ws[0].dtype:
+            raise HetaError(HETA_ERR_SHAPE, "inputs / weights do not match")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_project_sum.argtypes = [i64, i32, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, i64, ctypes.c_float, vp]
+    _check(L.heta_project_sum(n_rows, len(ins), _ptr_array(ins, "in"), _dt(ins[0]), _i64_array([_ld(x) for x in ins]),
+                              _i32_array([x.shape[1] for x in ins]), _ptr_array(Ws, "W"), _dt(Ws[0]),
+                              _i64_array([w.stride(0) for w in Ws]), d_out, int(trans_w), _dev(out, "out", torch.float32),
+                              _ld(out), beta, _stream(stream)))
+    return out
+
+
+def heta_project_wgrad_batch(g: Graph, ins: List[torch.Tensor], gouts: List[torch.Tensor], dW: List[torch.Tensor],
+                             beta: float = 0.0, gout_two_terms: bool = False, n_rows: Optional[int] = None,
+                             stream=None) -> List[torch.Tensor]:
+    """dW[p] = beta*dW[p] + ins[p]^T @ gouts[p] over n_rows rows, one launch."""
+    n_rows = ins[0].shape[0] if n_rows is None else n_rows
+    d_out = gouts[0].shape[1]
+    if not ins or len(ins) != len(gouts) or len(ins) != len(dW):
+        raise HetaError(HETA_ERR_SHAPE, "bad arguments")
+    for x, go, w in zip(ins, gouts, dW):
+        if x.shape[0] < n_rows or go.shape[0] < n_rows or go.shape[1] != d_out or w.shape[0] < x.shape[1] \
+                or w.shape[1] < d_out or x.dtype != ins[0].dtype:
+            raise HetaError(HETA_ERR_SHAPE, "inputs / gradients do not match")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_project_wgrad_batch.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, i32, vp, vp, ctypes.c_float, i32, vp]
+    _check(L.heta_project_wgrad_batch(g.handle, n_rows, len(ins), _ptr_array(ins, "in"), _dt(ins[0]),
+                                      _i64_array([_ld(x) for x in ins]), _i32_array([x.shape[1] for x in ins]),
+                                      _ptr_array(gouts, "gout", torch.float32), _i64_array([_ld(x) for x in gouts]), d_out,
+                                      _ptr_array(dW, "dW", torch.float32), _i64_array([_ld(w) for w in dW]), beta,
+                                      int(gout_two_terms), _stream(stream)))
+    return dW
 
 
 def heta_cross_rel_project_bwd(g: Graph, dst_type: int, gout: torch.Tensor, Ws: List[torch.Tensor],

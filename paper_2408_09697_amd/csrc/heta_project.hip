@@ -334,8 +334,20 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
                                 const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
                                 int32_t d_out, int32_t transW, const float *row_scale, int relu, void *out,
                                 int64_t ld_out, float beta, hipStream_t st, const char *who, heta_graph *pack_owner = nullptr,
-                                heta_dtype out_dt = HETA_F32)
+                                heta_dtype out_dt = HETA_F32, void *const *outs = nullptr, const int64_t *ld_outs = nullptr)
 {
+    // outs != nullptr: n_seg independent products, one output each (out / ld_out unused); else one summed output
+    if (outs && n_seg >= 1) {
+        if (!ld_outs) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+        for (int s = 0; s < n_seg && s < kMaxSeg; ++s) {
+            if (!outs[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+            if (ld_outs[s] < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
+            if (misaligned(outs[s], dtype_size(valid_dtype(out_dt) ? out_dt : HETA_F32)))
+                return fail(HETA_ERR_INVALID_ARG, "%s: out not aligned to its element size", who);
+        }
+        out = outs[0];
+        ld_out = ld_outs[0];
+    }
     if (!ins || !Ws || !out || !ld_in || !d_in || !ld_w) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
     if (n_seg < 1 || n_seg > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d inputs", who, kMaxSeg);
     if (!valid_dtype(in_dt) || !valid_dtype(w_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
@@ -358,15 +370,15 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
         g.lda = ld_in[s];
         g.B = Ws[s];
         g.ldb = ld_w[s];
-        g.C = static_cast<float *>(out); // typed by p.out_bf16 in the kernels' epilogue
-        g.ldc = ld_out;
+        g.C = static_cast<float *>(outs ? outs[s] : out); // typed by p.out_bf16 in the kernels' epilogue
+        g.ldc = outs ? ld_outs[s] : ld_out;
         g.M = n_rows;
         g.N = d_out;
         g.K = d_in[s];
     }
     if (n_rows == 0) return HETA_OK;
     p.n_seg = n_seg;
-    p.batch = 0;
+    p.batch = outs ? 1 : 0;
     p.row_scale = row_scale;
     p.beta = beta;
     p.relu = relu;
@@ -412,8 +424,19 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
 static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const void *const *ins, heta_dtype in_dt,
                               const int64_t *ld_in, const int32_t *d_in, const float *gout, int64_t ld_go, int32_t d_out,
                               float *const *dW, const int64_t *ld_dw, float beta, hipStream_t st, const char *who,
-                              int gout_two_terms = 0)
+                              int gout_two_terms = 0, const float *const *gouts = nullptr, const int64_t *ld_gos = nullptr)
 {
+    // gouts != nullptr: every segment has its own gradient operand (gout / ld_go unused)
+    if (gouts && n_seg >= 1) {
+        if (!ld_gos) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+        for (int s = 0; s < n_seg && s < kMaxSeg; ++s) {
+            if (!gouts[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+            if (ld_gos[s] < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
+            if (misaligned(gouts[s], 4)) return fail(HETA_ERR_INVALID_ARG, "%s: gout not 4-byte aligned", who);
+        }
+        gout = gouts[0];
+        ld_go = ld_gos[0];
+    }
     if (!g || !ins || !gout || !dW || !ld_in || !d_in || !ld_dw) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
     if (n_seg < 1 || n_seg > kMaxSeg) return fail(HETA_ERR_INVALID_ARG, "%s: between 1 and %d inputs", who, kMaxSeg);
     if (!valid_dtype(in_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
@@ -430,8 +453,8 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
         GemmSeg &q = p.seg[s];
         q.A = ins[s];      // A[m = column of `in`][k = graph row] : r-contiguous
         q.lda = ld_in[s];
-        q.B = gout;        // B[k = graph row][n] : r-contiguous
-        q.ldb = ld_go;
+        q.B = gouts ? gouts[s] : gout; // B[k = graph row][n] : r-contiguous
+        q.ldb = gouts ? ld_gos[s] : ld_go;
         q.M = d_in[s];
         q.N = d_out;
         q.K = n_rows;
@@ -530,6 +553,34 @@ heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, h
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_project_wgrad: relation %d out of range", rel);
     return wgrad_impl(g, g->rels[rel].n_dst, 1, &in, in_dt, &ld_in, &d_in, gout, ld_go, d_out, &dW, &ld_dw, beta,
                       as_stream(hip_stream), "heta_rel_project_wgrad");
+}
+
+heta_status heta_project_batch(int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+                               const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,
+                               int32_t transW, void *const *outs, heta_dtype out_dt, const int64_t *ld_out, void *hip_stream)
+{
+    if (!outs || !ld_out) return fail(HETA_ERR_INVALID_ARG, "heta_project_batch: null argument");
+    return project_impl(n_rows, n, ins, in_dt, ld_in, d_in, Ws, w_dt, ld_w, d_out, transW, nullptr, 0, nullptr, 0, 0.f,
+                        as_stream(hip_stream), "heta_project_batch", nullptr, out_dt, outs, ld_out);
+}
+
+heta_status heta_project_sum(int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+                             const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,
+                             int32_t transW, float *out, int64_t ld_out, float beta, void *hip_stream)
+{
+    return project_impl(n_rows, n, ins, in_dt, ld_in, d_in, Ws, w_dt, ld_w, d_out, transW, nullptr, 0, out, ld_out, beta,
+                        as_stream(hip_stream), "heta_project_sum");
+}
+
+heta_status heta_project_wgrad_batch(heta_graph *g, int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt,
+                                     const int64_t *ld_in, const int32_t *d_in, const float *const *gouts,
+                                     const int64_t *ld_go, int32_t d_out, float *const *dW, const int64_t *ld_dw, float beta,
+                                     int32_t gout_two_terms, void *hip_stream)
+{
+    if (!g || !gouts || !ld_go) return fail(HETA_ERR_INVALID_ARG, "heta_project_wgrad_batch: null argument");
+    if (n_rows < 0) return fail(HETA_ERR_SHAPE, "heta_project_wgrad_batch: negative row count");
+    return wgrad_impl(g, n_rows, n, ins, in_dt, ld_in, d_in, nullptr, 0, d_out, dW, ld_dw, beta, as_stream(hip_stream),
+                      "heta_project_wgrad_batch", gout_two_terms, gouts, ld_go);
 }
 
 heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,

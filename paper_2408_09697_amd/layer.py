@@ -121,6 +121,12 @@ class RafLayer:
         """aggregate every relation, then one fused projection + cross-relation sum per type."""
         self._pre_project(stream)
         self._pf_active = set(self.pf)
+        for s, rs in self.rels_from.items():  # Z'_r = H0_s W_r for all project-first relations out of s, one launch
+            pfs = [r for r in rs if r in self.pf]
+            for c in range(0, len(pfs), 8):
+                part = pfs[c:c + 8]
+                hb.heta_project_batch([self.source(s)] * len(part), [self.W[r] for r in part], [self.Zp[r] for r in part],
+                                      n_rows=self.g.ntypes[s][0], stream=stream)
         for t, all_rs in self.rels_into.items():
             rs = [r for r in all_rs if r not in self.pf]
             pfs = [r for r in all_rs if r in self.pf]
@@ -134,9 +140,7 @@ class RafLayer:
                                           act=self.act if last else hb.HETA_ACT_NONE, beta=0.0 if c == 0 else 1.0,
                                           stream=stream)
                 wrote = True
-            for r in pfs:  # project over the source rows, aggregate at the output width into H_t
-                s = self.g.rels[r][0]
-                hb.heta_project(self.source(s), self.W[r], self.Zp[r], n_rows=self.g.n_src(r), stream=stream)
+            for r in pfs:  # projected over the source rows above; aggregate at the output width into H_t
                 hb.heta_rel_aggregate_fwd(self.g, r, self.op, self.Zp[r], self.H[t], d=self.d_out,
                                           beta=1.0 if wrote else 0.0, stream=stream)
                 wrote = True
@@ -201,14 +205,18 @@ class RafLayer:
                 hb.heta_rel_aggregate_bwd(self.g, r, self.op, dM[r], self.dH0[s],
                                           beta=0.0 if first_for_src[s] else 1.0, stream=stream)
                 first_for_src[s] = False
-            for r in pfs:  # dZ'_r = CSC gather of G_t; dW_r = H0_s^T dZ'_r; dH0_s += dZ'_r W_r^T
-                s = self.g.rels[r][0]
+            for r in pfs:  # dZ'_r = CSC gather of G_t over the source rows
                 hb.heta_rel_aggregate_bwd(self.g, r, self.op, g, self.Ghat[r], d=self.d_out, stream=stream)
+        for s, rs in self.rels_from.items():  # per source type: dW_r = H0_s^T dZ'_r ; dH0_s += sum_r dZ'_r W_r^T
+            pfs = [r for r in rs if r in self._pf_active]
+            for c in range(0, len(pfs), 8):
+                part = pfs[c:c + 8]
                 # dZ'_r sums G over a source's out-edges: fed to the bf16 MFMA as two terms so that its size does not show in dW
-                hb.heta_cross_rel_project_wgrad(self.g, s, [self.source(s)], self.Ghat[r], [self.dW[r]],
-                                                gout_two_terms=True, stream=stream)
-                hb.heta_project(self.Ghat[r], self.W[r], self.dH0[s], trans_w=True, n_rows=self.g.n_src(r),
-                                beta=0.0 if first_for_src[s] else 1.0, stream=stream)
+                hb.heta_project_wgrad_batch(self.g, [self.source(s)] * len(part), [self.Ghat[r] for r in part],
+                                            [self.dW[r] for r in part], gout_two_terms=True, n_rows=self.g.ntypes[s][0],
+                                            stream=stream)
+                hb.heta_project_sum([self.Ghat[r] for r in part], [self.W[r] for r in part], self.dH0[s], trans_w=True,
+                                    beta=0.0 if first_for_src[s] else 1.0, n_rows=self.g.ntypes[s][0], stream=stream)
                 first_for_src[s] = False
         if self.pre_proj is not None:
             for s, gh in self.dH0.items():
