@@ -266,16 +266,23 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
     const int wm = (wave / WN) * 64, wn = (wave % WN) * 64;
     const int half = lane >> 5, l32 = lane & 31;
 
-    // workgroup id -> (XCD, position in the XCD's queue) -> (outer = row block x split, inner = column tile x segment)
+    // workgroup id -> (XCD, position in that XCD's queue) -> (outer, inner).  Workgroups are dealt
+    // round-robin to the 8 XCDs; the tiles that share an operand get consecutive positions of ONE
+    // XCD's queue and meet in its L2: for a row-parallel product the column tiles and batch
+    // segments of a row block (inner), one row block per outer step; for a split contraction
+    // (weight gradient) every tile and segment of one split (they share that split's rows of both
+    // operands), one split per outer step.
     const int n_batch = p.batch ? p.n_seg : 1;
-    const int64_t inner = p.nt * n_batch;
+    const int64_t inner = p.nt * n_batch * (p.partial ? p.mt : 1);
+    const int64_t n_outer = p.partial ? p.n_split : p.mt;
     const int64_t xcd = blockIdx.x % 8, j = blockIdx.x / 8;
     const int64_t in_idx = j % inner, outer = (j / inner) * 8 + xcd;
-    if (outer >= p.mt * p.n_split) return;
+    if (outer >= n_outer) return;
     const int s0 = p.batch ? static_cast<int>(in_idx % n_batch) : 0;
-    const int64_t n0 = (in_idx / n_batch) * BN;
-    const int64_t m0 = (outer % p.mt) * BM;
-    const int64_t split = outer / p.mt;
+    const int64_t rest = in_idx / n_batch;
+    const int64_t n0 = (rest % p.nt) * BN;
+    const int64_t m0 = (p.partial ? rest / p.nt : outer) * BM;
+    const int64_t split = p.partial ? outer : 0;
     const GemmSeg &out_seg = p.seg[s0];
     if (m0 >= out_seg.M || n0 >= out_seg.N) return; // uniform per workgroup
     const int rows_a = static_cast<int>(min(out_seg.M - m0, static_cast<int64_t>(BM)));
@@ -502,7 +509,8 @@ static heta_status launch_direct(GemmParams &p, hipStream_t st, const char *name
     }
     p.mt = mt;
     p.nt = nt;
-    const int64_t outer = mt * std::max(1, p.n_split), inner = nt * (p.batch ? p.n_seg : 1);
+    const int64_t inner = nt * (p.batch ? p.n_seg : 1) * (p.partial ? mt : 1);
+    const int64_t outer = p.partial ? std::max(1, p.n_split) : mt;
     const int64_t blocks = (outer + 7) / 8 * 8 * inner;
     if (blocks <= 0) return HETA_OK;
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");

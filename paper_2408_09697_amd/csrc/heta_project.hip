@@ -44,19 +44,23 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
     const int wm = (wave / WN) * 64, wn = (wave % WN) * 64;
     const int half = lane >> 5, l32 = lane & 31;
 
-    // workgroup id -> (XCD, position in that XCD's queue) -> (outer = row block x split, inner =
-    // column tile x segment): workgroups are dealt round-robin to the 8 XCDs, so the tiles that
-    // share an operand (the segments of a batch, the column tiles of a row block) are given
-    // consecutive positions of ONE XCD's queue and meet in its L2
+    // workgroup id -> (XCD, position in that XCD's queue) -> (outer, inner).  Workgroups are dealt
+    // round-robin to the 8 XCDs; the tiles that share an operand get consecutive positions of ONE
+    // XCD's queue and meet in its L2: for a row-parallel product the column tiles and batch
+    // segments of a row block (inner), one row block per outer step; for a split contraction
+    // (weight gradient) every tile and segment of one split (they share that split's rows of both
+    // operands), one split per outer step.
     const int n_batch = p.batch ? p.n_seg : 1;
-    const int64_t inner = p.nt * n_batch;
+    const int64_t inner = p.nt * n_batch * (p.partial ? p.mt : 1);
+    const int64_t n_outer = p.partial ? p.n_split : p.mt;
     const int64_t xcd = blockIdx.x % 8, jq = blockIdx.x / 8;
     const int64_t in_idx = jq % inner, outer = (jq / inner) * 8 + xcd;
-    if (outer >= p.mt * p.n_split) return;
+    if (outer >= n_outer) return;
     const int s0 = p.batch ? static_cast<int>(in_idx % n_batch) : 0;
-    const int64_t n0 = (in_idx / n_batch) * BN;
-    const int64_t m0 = (outer % p.mt) * BM;
-    const int64_t split = outer / p.mt;
+    const int64_t rest = in_idx / n_batch;
+    const int64_t n0 = (rest % p.nt) * BN;
+    const int64_t m0 = (p.partial ? rest / p.nt : outer) * BM;
+    const int64_t split = p.partial ? outer : 0;
     const GemmSeg &out_seg = p.seg[s0];
     if (m0 >= out_seg.M || n0 >= out_seg.N) return; // uniform per workgroup (smaller segment of a batch)
     const int s_end = p.batch ? s0 + 1 : p.n_seg;
@@ -253,7 +257,9 @@ static heta_status launch_gemm(GemmParams &p, hipStream_t st, int bk)
     }
     p.mt = mt;
     p.nt = nt;
-    const int64_t blocks = (mt * std::max(1, p.n_split) + 7) / 8 * 8 * nt * (p.batch ? p.n_seg : 1);
+    const int64_t inner = nt * (p.batch ? p.n_seg : 1) * (p.partial ? mt : 1);
+    const int64_t n_outer = p.partial ? std::max(1, p.n_split) : mt;
+    const int64_t blocks = (n_outer + 7) / 8 * 8 * inner;
     if (blocks <= 0) return HETA_OK;
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
     ProfScope prof(sizeof(CT) == 4 ? (p.partial ? "gemm_wgrad_f32" : "gemm_f32") : (p.partial ? "gemm_wgrad_bf16" : "gemm_bf16"),
@@ -470,7 +476,11 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     const int64_t BK = in_dt == HETA_F32 ? 32 : 64;
     const int64_t k_tiles = (n_rows + BK - 1) / BK;
     const int64_t slots_per_xcd = 32 * (d_out > 128 ? 2 : (in_dt == HETA_F32 ? 3 : 4));
-    const int64_t splits_per_xcd = std::max<int64_t>(1, slots_per_xcd / std::max<int64_t>(1, tiles));
+    // a split's workgroups are (largest segment's row tiles) x (column tiles) x (segments), all on one XCD
+    int64_t mt_max = 1;
+    for (int s = 0; s < n_seg; ++s) mt_max = std::max<int64_t>(mt_max, (d_in[s] + BM - 1) / BM);
+    const int64_t slots_per_split = std::max<int64_t>(tiles, mt_max * ((d_out + BN - 1) / BN) * n_seg);
+    const int64_t splits_per_xcd = std::max<int64_t>(1, slots_per_xcd / std::max<int64_t>(1, slots_per_split));
     int64_t n_split = std::max<int64_t>(1, std::min<int64_t>((k_tiles + 15) / 16, 8 * splits_per_xcd));
     const int64_t tiles_per_split = std::max<int64_t>(1, (k_tiles + n_split - 1) / n_split);
     n_split = std::max<int64_t>(1, (k_tiles + tiles_per_split - 1) / tiles_per_split);
