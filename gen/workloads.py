@@ -108,6 +108,47 @@ def config1(exact: bool = False) -> LayerProblem:
     return LayerProblem("config1", g, "mean", "f32", tabs, W, 32, _upstream(g, 32, wl, exact), pre_proj=P)
 
 
+# ---- R-GAT parameters and a tiny R-GAT problem ----------------------------------------------
+
+@dataclass
+class AttentionParams:
+    """Per relation: `a[i]` [heads, d_out / heads] (source half of the attention vector) and
+    `q[i]` [d_dst_table, heads] (destination half, already multiplied into the table's width)."""
+    heads: int
+    slope: float
+    a: List[np.ndarray]
+    q: List[np.ndarray]
+
+
+def attention_params(problem: LayerProblem, heads: int, slope: float = 0.2, gain: float = 1.0) -> AttentionParams:
+    """Seeded attention parameters for every relation of a layer problem: uniform with the
+    Glorot bound of their shape times `gain` (larger gains give sharper softmaxes)."""
+    assert problem.d_out % heads == 0
+    F = problem.d_out // heads
+    wl = problem.name + f"/attn{heads}"
+    a, q = [], []
+    for r in problem.graph.relations:
+        ba = gain * float(np.sqrt(6.0 / (F + 1)))
+        d_t = problem.tables[r.dst_type].shape[1]
+        bq = gain * float(np.sqrt(6.0 / (d_t + 1)))
+        a.append(rng.uniform_table(heads, F, -ba, ba, wl, f"a/{r.name}"))
+        q.append(rng.uniform_table(d_t, heads, -bq, bq, wl, f"q/{r.name}"))
+    return AttentionParams(heads, slope, a, q)
+
+
+def rgat_tiny(storage: str = "f32", d_out: int = 32) -> LayerProblem:
+    """Config 1's graph as an R-GAT problem: every relation maps its source table's own
+    width (64, 16, 32) to `d_out` with its W_r; ReLU after the cross-relation sum."""
+    wl = "rgat_tiny"
+    nts = [NodeType("A", 2000, 64, False), NodeType("B", 1000, 16, False), NodeType("C", 500, 32, True)]
+    g = HetGraph(nts)
+    for nm, s, t in [("A->A", 0, 0), ("B->A", 1, 0), ("C->A", 2, 0), ("A->B", 0, 1)]:
+        g.relations.append(uniform_relation(nm, s, t, nts[s].num_nodes, nts[t].num_nodes, 5000, wl))
+    tabs = _tables(g, wl, storage, False)
+    W = _weights(g, lambda i: nts[g.relations[i].src_type].feat_dim, d_out, wl, storage, False)
+    return LayerProblem("rgat_tiny", g, "sum", storage, tabs, W, d_out, _upstream(g, d_out, wl, False), relu=True)
+
+
 # ---- the academic-shaped graph of configs 2 and 3 ----------------------------------------------
 
 def academic_graph(scale: float = 1.0, exponent: float = 2.1, workload: str = "academic") -> HetGraph:

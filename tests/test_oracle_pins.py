@@ -449,3 +449,173 @@ def test_adam_rows_skipped_for_a_step_keep_state_and_are_not_decayed():
     np.testing.assert_allclose(x2[r], theta[r] - 0.01 * mhat / (np.sqrt(vhat) + 1e-8), rtol=1e-12)
     with pytest.raises(AssertionError):
         oracle.sparse_adam_step(theta, z, z, np.array([1, 1]), grads[0][:2], 0.01, 0.9, 0.999, 1e-8, 1)
+
+
+# ---- R-GAT (graph attention as AGG_r): pins of oracle/rgat.py --------------------------------------
+
+from oracle import rgat
+
+
+def _tiny_rgat(seed, heads=2, relu=True, gain=2.0):
+    p = tiny_problem(seed, "sum", relu=relu)
+    g = np.random.default_rng(seed + 100)
+    F = p.d_out // heads
+    a = [gain * g.standard_normal((heads, F)) for _ in p.graph.relations]
+    q = [gain * g.standard_normal((p.tables[r.dst_type].shape[1], heads)) for r in p.graph.relations]
+    return p, a, q
+
+
+def _dense_rgat_torch(p, a, q, slope):
+    """GAT written densely for autograd: per relation a count matrix C[v, u] (multi-edges are
+    repeated softmax terms), logits for every (v, u) pair, softmax weights
+    C exp(s) / sum_u C exp(s), output = weights @ Z per head.  Returns H per type and the leaves."""
+    import torch
+    g = p.graph
+    T = [torch.tensor(np.asarray(t, np.float64), requires_grad=True) for t in p.tables]
+    W = [torch.tensor(np.asarray(w, np.float64), requires_grad=True) for w in p.W]
+    A = [torch.tensor(np.asarray(x, np.float64), requires_grad=True) for x in a]
+    Q = [torch.tensor(np.asarray(x, np.float64), requires_grad=True) for x in q]
+    acc = {}
+    for i, r in enumerate(g.relations):
+        n_s, n_t = g.ntypes[r.src_type].num_nodes, g.ntypes[r.dst_type].num_nodes
+        C = np.zeros((n_t, n_s))
+        src, dst = r.edge_list()
+        for u, v in zip(src.tolist(), dst.tolist()):
+            C[v, u] += 1.0
+        C = torch.tensor(C)
+        K, F = A[i].shape
+        Z = (T[r.src_type] @ W[i]).reshape(n_s, K, F)
+        el = (Z * A[i][None]).sum(-1)                 # [n_s, K]
+        er = T[r.dst_type] @ Q[i]                     # [n_t, K]
+        heads = []
+        for k in range(K):
+            s = torch.nn.functional.leaky_relu(er[:, k][:, None] + el[:, k][None, :], slope)   # [n_t, n_s]
+            wgt = C * torch.exp(s)
+            den = wgt.sum(1, keepdim=True)
+            wgt = torch.where(den > 0, wgt / torch.where(den > 0, den, torch.ones_like(den)), torch.zeros_like(wgt))
+            heads.append(wgt @ Z[:, k, :])
+        O = torch.cat(heads, dim=1)
+        acc[r.dst_type] = O if r.dst_type not in acc else acc[r.dst_type] + O
+    H = {t: (torch.relu(h) if p.relu else h) for t, h in acc.items()}
+    return H, T, W, A, Q
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("heads", [1, 2, 3])
+def test_rgat_matches_dense_autograd(seed, heads):
+    import torch
+    p, a, q = _tiny_rgat(seed, heads)
+    slope = 0.2
+    fwd = rgat.rgat_forward(p, a, q, slope)
+    dW, da, dq, dH0 = rgat.rgat_backward(p, a, q, fwd, p.G, slope)
+    H, T, W, A, Q = _dense_rgat_torch(p, a, q, slope)
+    loss = sum((torch.tensor(np.asarray(p.G[t], np.float64)) * H[t]).sum() for t in H)
+    loss.backward()
+    for t in H:
+        np.testing.assert_allclose(fwd.H[t], H[t].detach().numpy(), rtol=1e-11, atol=1e-12)
+    for i in range(len(p.graph.relations)):
+        np.testing.assert_allclose(dW[i], W[i].grad.numpy(), rtol=1e-9, atol=1e-11)
+        np.testing.assert_allclose(da[i], A[i].grad.numpy(), rtol=1e-9, atol=1e-11)
+        np.testing.assert_allclose(dq[i], Q[i].grad.numpy(), rtol=1e-9, atol=1e-11)
+    for t in range(len(p.tables)):
+        ref = T[t].grad.numpy() if T[t].grad is not None else np.zeros_like(p.tables[t])
+        np.testing.assert_allclose(dH0.get(t, np.zeros_like(ref)), ref, rtol=1e-9, atol=1e-11)
+
+
+def test_rgat_with_zero_attention_parameters_is_the_mean_aggregation():
+    """a = 0 and q = 0 give equal logits, so alpha = 1/deg and the module is the R-GCN mean:
+    o_r = mean_agg(H0_s) W_r, which the first oracle computes through its own C edge loop."""
+    p, a, q = _tiny_rgat(3, heads=2, relu=False)
+    a = [np.zeros_like(x) for x in a]
+    q = [np.zeros_like(x) for x in q]
+    fwd = rgat.rgat_forward(p, a, q)
+    p.op = "mean"
+    ref = oracle.layer_forward(p)
+    for t in ref.H:
+        np.testing.assert_allclose(fwd.H[t], ref.H[t], rtol=1e-12, atol=1e-12)
+
+
+def test_edge_softmax_against_the_library_softmax_row_by_row():
+    from scipy.special import softmax
+    g = np.random.default_rng(5)
+    n_src, n_dst, E, K = 9, 7, 40, 3
+    src = g.integers(0, n_src, E)
+    dst = g.integers(0, n_dst - 1, E)           # last row stays empty
+    el = 3.0 * g.standard_normal((n_src, K))
+    er = 3.0 * g.standard_normal((n_dst, K))
+    alpha = rgat.edge_softmax(src, dst, n_dst, el, er, 0.2)
+    for v in range(n_dst):
+        sel = np.nonzero(dst == v)[0]
+        if sel.size == 0:
+            continue
+        x = el[src[sel]] + er[v]
+        s = np.where(x > 0, x, 0.2 * x)
+        np.testing.assert_allclose(alpha[sel], softmax(s, axis=0), rtol=1e-12)
+        np.testing.assert_allclose(alpha[sel].sum(0), 1.0, rtol=1e-12)
+
+
+def test_gat_single_in_edge_copies_the_source_row_and_empty_rows_are_zero():
+    g = np.random.default_rng(6)
+    K, F = 2, 3
+    Z = g.standard_normal((5, K * F))
+    src = np.array([4, 1, 1], dtype=np.int64)
+    dst = np.array([0, 2, 3], dtype=np.int64)
+    el, er = g.standard_normal((5, K)), g.standard_normal((5, K))
+    O, alpha = rgat.gat_aggregate_fwd(src, dst, 5, Z, el, er)
+    assert np.array_equal(alpha, np.ones((3, K)))
+    assert np.array_equal(O[0], Z[4]) and np.array_equal(O[2], Z[1]) and np.array_equal(O[3], Z[1])
+    assert not O[1].any() and not O[4].any()
+    # with a single term the softmax is constant: no gradient reaches the scores
+    dZ, d_el, d_er = rgat.gat_aggregate_bwd(src, dst, 5, 5, Z, el, er, alpha, g.standard_normal((5, K * F)))
+    assert not d_el.any() and not d_er.any()
+
+
+def test_gat_with_slope_one_ignores_the_destination_score():
+    """LeakyReLU with slope 1 is the identity; then er[v] shifts every logit of row v alike,
+    the softmax drops it, and its gradient is exactly the sum of a softmax Jacobian row: 0."""
+    g = np.random.default_rng(7)
+    n_src, n_dst, E, K, F = 8, 6, 30, 2, 4
+    src, dst = g.integers(0, n_src, E), g.integers(0, n_dst, E)
+    Z = g.standard_normal((n_src, K * F))
+    el, er = g.standard_normal((n_src, K)), g.standard_normal((n_dst, K))
+    O1, al1 = rgat.gat_aggregate_fwd(src, dst, n_dst, Z, el, er, slope=1.0)
+    O2, al2 = rgat.gat_aggregate_fwd(src, dst, n_dst, Z, el, 5.0 * er + 1.0, slope=1.0)
+    np.testing.assert_allclose(O1, O2, rtol=1e-12, atol=1e-13)
+    _, _, d_er = rgat.gat_aggregate_bwd(src, dst, n_src, n_dst, Z, el, er, al1, g.standard_normal((n_dst, K * F)), slope=1.0)
+    np.testing.assert_allclose(d_er, 0.0, atol=1e-13)
+
+
+def test_rgat_finite_differences_on_the_tiny_workload():
+    p = workloads.rgat_tiny()
+    ap = workloads.attention_params(p, 4, gain=2.0)
+    a = [np.asarray(x, np.float64) for x in ap.a]
+    q = [np.asarray(x, np.float64) for x in ap.q]
+    p.tables = [np.asarray(t, np.float64) for t in p.tables]
+    p.W = [np.asarray(w, np.float64) for w in p.W]
+    fwd = rgat.rgat_forward(p, a, q, ap.slope)
+    dW, da, dq, dH0 = rgat.rgat_backward(p, a, q, fwd, p.G, ap.slope)
+
+    def loss():
+        f = rgat.rgat_forward(p, a, q, ap.slope)
+        return sum(float((np.asarray(p.G[t], np.float64) * f.H[t]).sum()) for t in f.H)
+
+    g = np.random.default_rng(11)
+    eps = 1e-6
+    checks = []
+    for i in range(len(p.W)):
+        checks.append((p.W[i], dW[i]))
+        checks.append((a[i], da[i]))
+        checks.append((q[i], dq[i]))
+    for t in range(len(p.tables)):
+        checks.append((p.tables[t], dH0[t]))
+    for arr, grad in checks:
+        for _ in range(2):
+            idx = tuple(int(g.integers(0, s)) for s in arr.shape)
+            old = arr[idx]
+            arr[idx] = old + eps
+            up = loss()
+            arr[idx] = old - eps
+            dn = loss()
+            arr[idx] = old
+            fd = (up - dn) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 1e-5 * max(1.0, abs(fd)), (idx, fd, grad[idx])
