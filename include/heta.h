@@ -233,6 +233,46 @@ heta_status heta_act_bwd(int64_t n_rows, int32_t d, heta_act act, const float *h
                          const float *grad_out, int64_t ld_go, float *grad_in, int64_t ld_gi,
                          void *hip_stream);
 
+/* ---- graph attention as the relation-specific aggregation (Section 2.1: R-GAT applies GAT for
+ * AGG_r, sums the relations' outputs and activates the sum with ReLU; the paper prints no formula for
+ * the module, so it is the attention layer of the GAT paper, Velickovic et al. 2018, Eqs. 1-4 with
+ * multi-head concatenation, on a bipartite relation) ------------------------------------------------
+ * With K = heads, F = d / K, z = H0_s W_r (heta_project), for every edge e = (u_e -> v_e) of `rel`:
+ *   s_e[k] = LeakyReLU_slope(el[u_e, k] + er[v_e, k]);  alpha_e[k] = softmax of s_e[k] over the in-edges of v_e;
+ *   out[v, kF + f] = beta out[v, kF + f] + sum_{e into v} alpha_e[k] z[u_e, kF + f].
+ * Multi-edges are separate softmax terms; a destination without in-edges gets 0 (untouched when beta = 1).
+ *
+ * heta_attn_score: score[i, k] = sum_j x[i, j] vec_k[j].  per_head = 1: j runs over head k's columns
+ *   [kF, (k+1)F) and vec is [K][F] (el = <z_u[k,:], a[k,:]>); per_head = 0: j runs over all d columns and
+ *   vec is [K][d] (er = <h_v, q[k,:]>, q[k,:] being the destination-side weight matrix times its half of
+ *   GAT's attention vector).  x: device [n, ld_x] of dt; vec: device fp32; score: device fp32 [n, K]. */
+heta_status heta_attn_score(const void *x, heta_dtype dt, int64_t ld_x, int64_t n, int32_t d, const float *vec,
+                            int32_t heads, int32_t per_head, float *score, void *hip_stream);
+/* Backward of heta_attn_score: dx[i, j] = beta dx[i, j] + sum_k dscore[i, k] vec_k[j] (dx: device fp32
+ * [n, ld_dx] or NULL; beta 0 or 1) and dvec_k[j] = sum_i dscore[i, k] x[i, j] (device fp32, shaped like
+ * vec, overwritten, or NULL), rows added in a fixed order (partial sums in g's attention workspace). */
+heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int64_t ld_x, int64_t n, int32_t d,
+                                const float *vec, int32_t heads, int32_t per_head, const float *dscore, float *dx,
+                                int64_t ld_dx, float beta, float *dvec, void *hip_stream);
+/* z: device [n_src, ld_z] of z_dt; el: device fp32 [n_src, K]; er: device fp32 [n_dst, K]; out: device
+ * [n_dst, ld_out] of out_dt; smax, sinv: device fp32 [n_dst, K], receive the softmax shift and the
+ * reciprocal denominator that heta_rel_attn_bwd needs (both NULL for inference).  1 <= K <= 16, K | d.
+ * The per-edge weights live in g's attention workspace (grown on demand; calls on one handle must be
+ * stream-ordered). */
+heta_status heta_rel_attn_fwd(heta_graph *g, int32_t rel, const void *z, heta_dtype z_dt, int64_t ld_z, int32_t d,
+                              int32_t heads, const float *el, const float *er, float slope, void *out,
+                              heta_dtype out_dt, int64_t ld_out, float beta, float *smax, float *sinv,
+                              void *hip_stream);
+/* Backward of heta_rel_attn_fwd for grad_out = dL/dout (device fp32 [n_dst, ld_go]); `o` is this
+ * relation's own forward output (device [n_dst, ld_o] of o_dt, computed with beta = 0).  Writes
+ *   dz[u, kF+f] = sum_{e out of u} alpha_e[k] grad_out[v_e, kF+f]                (device fp32 [n_src, ld_dz])
+ *   del[u, k], der[v, k]: the gradients of el and er through softmax and LeakyReLU (device fp32).
+ * All three are overwritten.  No atomics: dz and del are gathers over the CSC, der over the CSR. */
+heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dtype z_dt, int64_t ld_z, int32_t d,
+                              int32_t heads, const float *el, const float *er, float slope, const float *smax,
+                              const float *sinv, const void *o, heta_dtype o_dt, int64_t ld_o, const float *grad_out,
+                              int64_t ld_go, float *dz, int64_t ld_dz, float *del, float *der, void *hip_stream);
+
 /* ---- sparse update of a learnable feature table (Sections 2.2 and 6: the learnable vectors of
  * featureless node types and their optimizer states, Adam's moment and variance, are updated after
  * backpropagation; only the rows a mini-batch touched) ---------------------------------------------

@@ -29,7 +29,8 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
            "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam", "heta_project_batch",
-           "heta_project_sum", "heta_project_wgrad_batch"]
+           "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
+           "heta_rel_attn_fwd", "heta_rel_attn_bwd"]
 
 
 class HetaError(RuntimeError):
@@ -103,7 +104,7 @@ def _dev(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
         return None
     if not t.is_cuda:
         raise TypeError(f"{name} must be a device tensor")
-    if t.dim() >= 1 and t.shape[-1] > 1 and t.stride(-1) != 1:
+    if t.numel() and t.dim() >= 1 and t.shape[-1] > 1 and t.stride(-1) != 1:
         raise TypeError(f"{name}: last dimension must be contiguous")
     if dtype is not None and t.dtype != dtype:
         raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
@@ -509,6 +510,87 @@ def heta_sparse_adam(table: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grad
                               _dev(ids, "ids", torch.int64), n, _dev(grad, "grad", torch.float32), _ld(grad),
                               lr, beta1, beta2, eps, int(step), _stream(stream)))
     return table
+
+
+def _scores(t: torch.Tensor, name: str, rows: int, heads: int) -> int:
+    """Device pointer of a contiguous fp32 [rows, heads] score array."""
+    if t.dtype != torch.float32 or not t.is_contiguous() or t.dim() != 2 or t.shape[0] < rows or t.shape[1] != heads:
+        raise HetaError(HETA_ERR_SHAPE, f"{name} must be a contiguous fp32 [>= {rows}, {heads}] tensor")
+    return _dev(t, name, torch.float32)
+
+
+def heta_attn_score(x: torch.Tensor, vec: torch.Tensor, per_head: bool, score: torch.Tensor,
+                    d: Optional[int] = None, stream=None) -> torch.Tensor:
+    """score[i, k] = <x[i, head k's columns], vec[k]> (per_head) or <x[i, :], vec[k]>; vec is [heads, F] or [heads, d]."""
+    d = x.shape[1] if d is None else d
+    heads = vec.shape[0]
+    if not vec.is_contiguous() or vec.shape[1] != (d // heads if per_head else d):
+        raise HetaError(HETA_ERR_SHAPE, "vec must be contiguous [heads, d / heads] (per_head) or [heads, d]")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_attn_score.argtypes = [vp, i32, i64, i64, i32, vp, i32, i32, vp, vp]
+    _check(L.heta_attn_score(_dev(x, "x"), _dt(x), _ld(x), x.shape[0], d, _dev(vec, "vec", torch.float32), heads,
+                             int(bool(per_head)), _scores(score, "score", x.shape[0], heads), _stream(stream)))
+    return score
+
+
+def heta_attn_score_bwd(g: Graph, x: torch.Tensor, vec: torch.Tensor, per_head: bool, dscore: torch.Tensor,
+                        dx: Optional[torch.Tensor] = None, beta: float = 0.0, dvec: Optional[torch.Tensor] = None,
+                        d: Optional[int] = None, stream=None) -> None:
+    d = x.shape[1] if d is None else d
+    heads = vec.shape[0]
+    if not vec.is_contiguous() or vec.shape[1] != (d // heads if per_head else d):
+        raise HetaError(HETA_ERR_SHAPE, "vec must be contiguous [heads, d / heads] (per_head) or [heads, d]")
+    if dvec is not None and (not dvec.is_contiguous() or dvec.shape != vec.shape):
+        raise HetaError(HETA_ERR_SHAPE, "dvec must be contiguous and shaped like vec")
+    if dx is not None and (dx.shape[0] < x.shape[0] or dx.shape[1] < d):
+        raise HetaError(HETA_ERR_SHAPE, "dx is smaller than x")
+    L = load_library()
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.heta_attn_score_bwd.argtypes = [vp, vp, i32, i64, i64, i32, vp, i32, i32, vp, vp, i64, f32, vp, vp]
+    _check(L.heta_attn_score_bwd(g.handle, _dev(x, "x"), _dt(x), _ld(x), x.shape[0], d, _dev(vec, "vec", torch.float32),
+                                 heads, int(bool(per_head)), _scores(dscore, "dscore", x.shape[0], heads),
+                                 _dev(dx, "dx", torch.float32), _ld(dx) if dx is not None else 0, beta,
+                                 _dev(dvec, "dvec", torch.float32), _stream(stream)))
+
+
+def heta_rel_attn_fwd(g: Graph, rel: int, z: torch.Tensor, el: torch.Tensor, er: torch.Tensor, slope: float,
+                      out: torch.Tensor, beta: float = 0.0, smax: Optional[torch.Tensor] = None,
+                      sinv: Optional[torch.Tensor] = None, d: Optional[int] = None, stream=None) -> torch.Tensor:
+    d = z.shape[1] if d is None else d
+    heads = el.shape[1]
+    if z.shape[0] < g.n_src(rel) or out.shape[0] < g.n_dst(rel):
+        raise HetaError(HETA_ERR_SHAPE, "z / out have fewer rows than the relation needs")
+    L = load_library()
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.heta_rel_attn_fwd.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, f32, vp, i32, i64, f32, vp, vp, vp]
+    _check(L.heta_rel_attn_fwd(g.handle, rel, _dev(z, "z"), _dt(z), _ld(z), d, heads,
+                               _scores(el, "el", g.n_src(rel), heads), _scores(er, "er", g.n_dst(rel), heads), slope,
+                               _dev(out, "out"), _dt(out), _ld(out), beta,
+                               None if smax is None else _scores(smax, "smax", g.n_dst(rel), heads),
+                               None if sinv is None else _scores(sinv, "sinv", g.n_dst(rel), heads), _stream(stream)))
+    return out
+
+
+def heta_rel_attn_bwd(g: Graph, rel: int, z: torch.Tensor, el: torch.Tensor, er: torch.Tensor, slope: float,
+                      smax: torch.Tensor, sinv: torch.Tensor, o: torch.Tensor, grad_out: torch.Tensor,
+                      dz: torch.Tensor, d_el: torch.Tensor, d_er: torch.Tensor, d: Optional[int] = None,
+                      stream=None) -> None:
+    d = z.shape[1] if d is None else d
+    heads = el.shape[1]
+    n_src, n_dst = g.n_src(rel), g.n_dst(rel)
+    if z.shape[0] < n_src or dz.shape[0] < n_src or o.shape[0] < n_dst or grad_out.shape[0] < n_dst:
+        raise HetaError(HETA_ERR_SHAPE, "a buffer has fewer rows than the relation needs")
+    L = load_library()
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.heta_rel_attn_bwd.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, f32, vp, vp, vp, i32, i64, vp, i64,
+                                    vp, i64, vp, vp, vp]
+    _check(L.heta_rel_attn_bwd(g.handle, rel, _dev(z, "z"), _dt(z), _ld(z), d, heads,
+                               _scores(el, "el", n_src, heads), _scores(er, "er", n_dst, heads), slope,
+                               _scores(smax, "smax", n_dst, heads), _scores(sinv, "sinv", n_dst, heads),
+                               _dev(o, "o"), _dt(o), _ld(o), _dev(grad_out, "grad_out", torch.float32), _ld(grad_out),
+                               _dev(dz, "dz", torch.float32), _ld(dz), _scores(d_el, "del", n_src, heads),
+                               _scores(d_er, "der", n_dst, heads), _stream(stream)))
 
 
 def heta_ingest_force(mode: int) -> None:

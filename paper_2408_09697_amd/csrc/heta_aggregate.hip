@@ -51,6 +51,9 @@ struct AggParams {
     int64_t ld;            // elements
     const int64_t *gid;    // nullable: neighbour id -> table row
     const float *edge_w;   // nullable: weight per neighbour id
+    const float *slot_w;   // nullable: weight per (edge position in sidx, head): [n_edges][heads]
+    int heads;             // with slot_w: number of heads, columns [h*head_dim, (h+1)*head_dim) use weight h
+    int head_dim;
     int mean;              // divide the row sum by the row's degree
     void *out;
     int64_t ld_out;
@@ -222,6 +225,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
     const int w = blockIdx.x * 4 + wave;
     const bool active = w < p.batch0[kShortDeg]; // uniform per wavefront; idle wavefronts still reach the barrier
     int k = 0, nrows = 0;
+    int64_t e0 = 0;
     if (active) {
         int b = 0;
         while (w >= p.batch0[b + 1]) ++b; // at most kShortDeg scalar steps
@@ -230,7 +234,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
         const int first = (w - p.batch0[b]) * R;
         const int q0 = p.row0[b] + first;
         nrows = min(R, p.row0[b + 1] - q0);
-        const int64_t e0 = p.edge0[b] + static_cast<int64_t>(first) * k;
+        e0 = p.edge0[b] + static_cast<int64_t>(first) * k;
         const int n_ids = nrows * k;
         // level 1: everything below has an address that depends on no load
         if (lane < nrows) row_s[wave][lane] = p.perm[q0 + lane];
@@ -265,6 +269,10 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
         return;
     }
     const float scale = p.mean ? 1.f / static_cast<float>(k) : 1.f;
+    const bool weighted = p.edge_w || p.slot_w;
+    int head[CPL]; // head of each of this lane's chunks (per-head edge weights)
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) head[c] = p.slot_w ? min((ch0 + c * L) * EPC / p.head_dim, p.heads - 1) : 0;
     float acc[CPL][EPC];
 #pragma unroll
     for (int c = 0; c < CPL; ++c)
@@ -277,7 +285,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
     const int total = rounds * k;
     for (int s0 = 0; s0 < total; s0 += U) {
         Chunk<T, EPC> v[U][CPL];
-        float ww[U];
+        float ww[U][CPL];
         int rl_u = rl, j_u = j;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -285,13 +293,17 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
             const bool ok = s0 + u < total && r < nrows;
             const int i = ok ? r * k + j_u : 0;
             const int rid = ids_s[wave][i];
-            ww[u] = p.edge_w ? w_s[wave][i] : 1.f;
             const T *rp = table + static_cast<int64_t>(rid) * p.ld;
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
                 const int ch = ch0 + c * L;
-                if (ok && ch < n_chunks) v[u][c].load(rp + static_cast<int64_t>(ch) * EPC);
-                else v[u][c].zero();
+                ww[u][c] = p.edge_w ? w_s[wave][i] : 1.f;
+                if (ok && ch < n_chunks) {
+                    v[u][c].load(rp + static_cast<int64_t>(ch) * EPC);
+                    if (p.slot_w) ww[u][c] = p.slot_w[(e0 + i) * p.heads + head[c]];
+                } else {
+                    v[u][c].zero();
+                }
             }
             if (++j_u == k) {
                 j_u = 0;
@@ -303,7 +315,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
             if (s0 + u < total) {
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) {
-                    if (p.edge_w) v[u][c].add_to(acc[c], ww[u]);
+                    if (weighted) v[u][c].add_to(acc[c], ww[u][c]);
                     else v[u][c].add_to(acc[c]);
                 }
                 if (++j == k) { // last edge of the row: store it, start the next
@@ -354,6 +366,10 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
     const int n_chunks = (p.d + EPC - 1) / EPC;
     const int ch0 = blockIdx.y * (L * CPL) + l;
     const T *table = static_cast<const T *>(p.table);
+    const bool weighted = p.edge_w || p.slot_w;
+    int head[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) head[c] = p.slot_w ? min((ch0 + c * L) * EPC / p.head_dim, p.heads - 1) : 0;
     float acc[CPL][EPC];
 #pragma unroll
     for (int c = 0; c < CPL; ++c)
@@ -371,26 +387,31 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
         }
         for (int j = 0; j < cnt; j += G * U) {
             Chunk<T, EPC> v[U][CPL];
-            float ww[U];
+            float ww[U][CPL];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int k = j + u * G + g;
                 const bool ok = k < cnt;
                 const int r = __shfl(rid, k & 63, 64);
-                ww[u] = __shfl(wv, k & 63, 64);
+                const float wn = __shfl(wv, k & 63, 64);
                 const T *rp = table + static_cast<int64_t>(r) * p.ld;
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) {
                     const int ch = ch0 + c * L;
-                    if (ok && ch < n_chunks) v[u][c].load(rp + static_cast<int64_t>(ch) * EPC);
-                    else v[u][c].zero();
+                    ww[u][c] = wn;
+                    if (ok && ch < n_chunks) {
+                        v[u][c].load(rp + static_cast<int64_t>(ch) * EPC);
+                        if (p.slot_w) ww[u][c] = p.slot_w[(base + k) * p.heads + head[c]];
+                    } else {
+                        v[u][c].zero();
+                    }
                 }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) {
-                    if (p.edge_w) v[u][c].add_to(acc[c], ww[u]);
+                    if (weighted) v[u][c].add_to(acc[c], ww[u][c]);
                     else v[u][c].add_to(acc[c]);
                 }
         }
@@ -508,7 +529,9 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     (void)table_elems_ld;
     if (s.n_rows == 0) return HETA_OK;
     const size_t esz = dtype_size(in_dt);
-    const bool vec = aligned16(p.table) && ((p.ld * esz) % 16 == 0);
+    // with per-head weights a lane's chunk must not straddle two heads
+    const bool vec = aligned16(p.table) && ((p.ld * esz) % 16 == 0) &&
+                     (!p.slot_w || p.head_dim % static_cast<int>(16 / esz) == 0);
     const int epc = vec ? static_cast<int>(16 / esz) : 1;
     const int n_chunks = (p.d + epc - 1) / epc;
     int L = 64; // lanes per row, as the dispatch below picks them
@@ -553,7 +576,7 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     // row pointer and one output row per row.  Hub rows' outputs are written by the combine kernel.
     AggCost cost;
     const double osz = p.out_bf16 ? 2.0 : 4.0;
-    const double per_edge = static_cast<double>(p.d) * esz + 4.0, per_row = 8.0 + p.d * osz;
+    const double per_edge = static_cast<double>(p.d) * esz + 4.0 + (p.slot_w ? 4.0 * p.heads : 0.0), per_row = 8.0 + p.d * osz;
     const double e_wave = static_cast<double>(s.edges_with_deg_ge[wave_min]);
     const double r_long = static_cast<double>(n_long_or_hub - s.n_hub_rows);
     cost.wave_bytes = e_wave * per_edge + r_long * per_row;
@@ -573,6 +596,26 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
         HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
     }
     return HETA_OK;
+}
+
+// Weighted aggregation with one weight per (edge slot of the schedule, head): the second half of the
+// attention aggregation (heta_attention.hip computes the weights).
+heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld,
+                                    int d, const float *slot_w, int heads, void *out, heta_dtype out_dt,
+                                    int64_t ld_out, float beta, hipStream_t st)
+{
+    AggParams p{};
+    p.table = table;
+    p.ld = ld;
+    p.slot_w = slot_w;
+    p.heads = heads;
+    p.head_dim = d / heads;
+    p.out = out;
+    p.ld_out = ld_out;
+    p.out_bf16 = (out_dt == HETA_BF16);
+    p.beta = beta;
+    p.d = d;
+    return run_aggregate(g, s, p, dt, ld, st);
 }
 
 // ---- plain row gather and id check -------------------------------------------------------------------

@@ -180,6 +180,7 @@ static void destroy(heta_graph *g)
     }
     (void)hipFree(g->d_ws);
     (void)hipFree(g->d_pack);
+    (void)hipFree(g->d_attn);
     delete g;
 }
 

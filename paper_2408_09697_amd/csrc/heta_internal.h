@@ -88,6 +88,10 @@ struct heta_graph {
     // k-contiguous copies of the bf16 weight matrices of the projection in flight; grown on demand
     void *d_pack = nullptr;
     size_t pack_bytes = 0;
+    // per-edge attention weights, per-row score terms and one [rows x d] intermediate of the
+    // attention aggregation; grown on demand
+    void *d_attn = nullptr;
+    size_t attn_bytes = 0;
 };
 
 namespace heta {
@@ -117,6 +121,11 @@ heta_status build_schedule_on_device(Schedule &s, float *inv_deg, hipStream_t st
 
 // Makes sure g's workspace holds `bytes`; growing frees and reallocates (device synchronising).
 heta_status ensure_workspace(heta_graph *g, size_t bytes);
+// out[r] = beta out[r] + sum_e slot_w[e][head of the column] table[idx[e]] over the rows of s; slot_w is
+// indexed by the edge's position in s.d_sidx.  Uses g's workspace for hub rows.
+heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld,
+                                    int d, const float *slot_w, int heads, void *out, heta_dtype out_dt,
+                                    int64_t ld_out, float beta, hipStream_t st);
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t dtype_size(heta_dtype dt) { return dt == HETA_F32 ? 4 : 2; }

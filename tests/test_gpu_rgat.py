@@ -1,0 +1,195 @@
+"""GPU parity of the attention aggregation (R-GAT) against the fp64 oracle of oracle/rgat.py.
+
+Tolerances: `max_j |got_ij - ref_ij| <= tol * max(1, max_j |ref_ij|)` per row, tol = 1e-4 wherever both
+sides read identical inputs (fp32 accumulation of fp32 or bf16-exact values), 2e-2 for the bf16-storage
+layer.  In that mode Z_r = H0_s W_r is stored as bf16 and the attention logits read the stored values; sharp
+softmaxes amplify that rounding (3.5e-2 on a weight gradient of the tiny workload at gain 2), so the
+gradients are compared with the oracle run on Z_r rounded to its storage type (its `z_store` hook), and
+the embeddings additionally with the oracle on exact Z_r.  The ReLU decision is kept away from its kink as in
+the other layer tests: the upstream gradient is zeroed where the oracle's embedding is within the forward
+tolerance of zero.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_09697_amd as heta
+from gen import rng, workloads
+from gen.graphs import HetGraph, NodeType, power_law_relation, reverse_relation, uniform_relation
+from oracle import rgat
+from tests.harness import assert_rows_close, dev_table, kink_guard, make_graph
+
+pytestmark = pytest.mark.gpu
+
+
+def up(x):
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+
+
+def host(x):
+    return x.float().cpu().numpy()
+
+
+# ---- scores -------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,d,heads,pad", [(1000, 256, 4, 4), (333, 64, 1, 4), (50, 30, 3, 1), (100, 1024, 8, 4),
+                                           (77, 7, 1, 1), (0, 64, 2, 4), (4100, 128, 16, 4)])
+@pytest.mark.parametrize("per_head", [True, False])
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_attn_score_and_its_backward(n, d, heads, pad, per_head, storage):
+    g = rng.stream("tests", f"score{n}x{d}x{heads}{per_head}")
+    x = g.standard_normal((n, d)).astype(np.float32)
+    if storage == "bf16":
+        x = rng.round_to_bf16(x)
+    F = d // heads
+    vec = g.standard_normal((heads, F if per_head else d)).astype(np.float32)
+    xd = dev_table(x, storage, (8 if storage == "bf16" else 4) if pad > 1 else 1)
+    score = torch.empty((n, heads), dtype=torch.float32, device="cuda")
+    heta.heta_attn_score(xd, up(vec), per_head, score)
+    x64 = x.astype(np.float64)
+    if per_head:
+        ref = np.einsum("nkf,kf->nk", x64.reshape(n, heads, F), vec.astype(np.float64))
+    else:
+        ref = x64 @ vec.astype(np.float64).T
+    assert_rows_close(host(score), ref, 1e-4, "score")
+    # backward
+    ds = g.standard_normal((n, heads)).astype(np.float32)
+    dx0 = g.standard_normal((n, d)).astype(np.float32)
+    graph = heta.heta_graph_create([(4, 4, 0)], [(0, 0, np.zeros(5, dtype=np.int64), np.zeros(0, dtype=np.int32))])
+    for beta in (0.0, 1.0):
+        dx = dev_table(dx0, "f32", 4 if pad > 1 else 1)
+        dvec = torch.full(vec.shape, 7.0, dtype=torch.float32, device="cuda")
+        heta.heta_attn_score_bwd(graph, xd, up(vec), per_head, up(ds), dx=dx, beta=beta, dvec=dvec)
+        if per_head:
+            rdx = (ds.astype(np.float64)[:, :, None] * vec.astype(np.float64)[None]).reshape(n, d)
+            rdv = np.einsum("nk,nkf->kf", ds.astype(np.float64), x64.reshape(n, heads, F))
+        else:
+            rdx = ds.astype(np.float64) @ vec.astype(np.float64)
+            rdv = ds.astype(np.float64).T @ x64
+        assert_rows_close(host(dx), rdx + beta * dx0, 1e-4, "dx")
+        assert_rows_close(host(dvec), rdv, 1e-4, "dvec")
+    graph.destroy()
+
+
+# ---- one relation ---------------------------------------------------------------------------------------
+
+def _relation_case(kind, n_src, n_dst, n_edges):
+    nts = [NodeType("s", n_src, 4, False), NodeType("t", n_dst, 4, False)]
+    G = HetGraph(nts)
+    wl = f"tests/attn/{kind}/{n_src}/{n_dst}/{n_edges}"
+    if kind == "uniform":
+        G.relations.append(uniform_relation("r", 0, 1, n_src, n_dst, n_edges, wl))
+    elif kind == "skew_dst":   # hubs among the destinations: the forward's long rows
+        G.relations.append(power_law_relation("r", 0, 1, n_src, n_dst, n_edges, 1.5, wl))
+    else:                      # hubs among the sources: the backward's long rows
+        base = power_law_relation("b", 1, 0, n_dst, n_src, n_edges, 1.5, wl)
+        G.relations.append(reverse_relation("r", base, n_dst))
+    return G
+
+
+@pytest.mark.parametrize("kind,n_src,n_dst,n_edges", [("uniform", 700, 900, 6000), ("skew_dst", 2000, 3000, 60000),
+                                                       ("skew_src", 2500, 1800, 50000), ("uniform", 5, 6, 0)])
+@pytest.mark.parametrize("d,heads", [(64, 4), (256, 1), (24, 4), (520, 2), (128, 16)])
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_rel_attn_forward_and_backward(kind, n_src, n_dst, n_edges, d, heads, storage):
+    G = _relation_case(kind, n_src, n_dst, n_edges)
+    r = G.relations[0]
+    src, dst = r.edge_list()
+    if kind != "uniform":
+        deg_d = np.bincount(dst, minlength=n_dst)
+        deg_s = np.bincount(src, minlength=n_src)
+        assert max(deg_d.max(), deg_s.max()) >= 512, "the case is meant to contain a hub row"
+    g = rng.stream("tests", f"attn{kind}{d}x{heads}")
+    z = g.standard_normal((n_src, d)).astype(np.float32)
+    if storage == "bf16":
+        z = rng.round_to_bf16(z)
+    el = (2.0 * g.standard_normal((n_src, heads))).astype(np.float32)
+    er = (2.0 * g.standard_normal((n_dst, heads))).astype(np.float32)
+    go = g.standard_normal((n_dst, d)).astype(np.float32)
+    slope = 0.2
+    graph = heta.heta_graph_create([(n_src, 4, 0), (n_dst, 4, 0)], [(0, 1, r.rowptr, r.col)])
+    pad = 8 if storage == "bf16" else 4
+    zd = dev_table(z, storage, pad if d % 4 == 0 else 1)
+    out = dev_table(np.full((n_dst, d), 3.0, dtype=np.float32), "f32", 4 if d % 4 == 0 else 1)
+    smax = torch.empty((n_dst, heads), dtype=torch.float32, device="cuda")
+    sinv = torch.empty_like(smax)
+    heta.heta_rel_attn_fwd(graph, 0, zd, up(el), up(er), slope, out, beta=0.0, smax=smax, sinv=sinv)
+    ref_o, alpha = rgat.gat_aggregate_fwd(src, dst, n_dst, z, el, er, slope)
+    assert_rows_close(host(out), ref_o, 1e-4, "out")
+    # accumulate on top (beta = 1) without the saved statistics
+    out2 = out.clone()
+    heta.heta_rel_attn_fwd(graph, 0, zd, up(el), up(er), slope, out2, beta=1.0)
+    assert_rows_close(host(out2), 2.0 * ref_o, 1e-4, "out, beta = 1")
+    dz = dev_table(np.full((n_src, d), 5.0, dtype=np.float32), "f32", 4 if d % 4 == 0 else 1)
+    d_el = torch.full((n_src, heads), 5.0, dtype=torch.float32, device="cuda")
+    d_er = torch.full((n_dst, heads), 5.0, dtype=torch.float32, device="cuda")
+    heta.heta_rel_attn_bwd(graph, 0, zd, up(el), up(er), slope, smax, sinv, out, up(go), dz, d_el, d_er)
+    torch.cuda.synchronize()
+    rdz, rdel, rder = rgat.gat_aggregate_bwd(src, dst, n_src, n_dst, z, el, er, alpha, go, slope)
+    assert_rows_close(host(dz), rdz, 1e-4, "dz")
+    assert_rows_close(host(d_el), rdel, 1e-4, "del")
+    assert_rows_close(host(d_er), rder, 1e-4, "der")
+    graph.destroy()
+
+
+def test_attention_argument_checks():
+    graph = heta.heta_graph_create([(4, 4, 0)], [(0, 0, np.array([0, 1, 2, 2, 2], dtype=np.int64), np.array([1, 0], dtype=np.int32))])
+    z = torch.zeros((4, 12), device="cuda")
+    el = torch.zeros((4, 5), device="cuda")
+    with pytest.raises(heta.HetaError, match="heads"):   # 5 heads do not divide 12 columns
+        heta.heta_rel_attn_fwd(graph, 0, z, el, el, 0.2, torch.zeros((4, 12), device="cuda"))
+    el = torch.zeros((4, 3), device="cuda")
+    with pytest.raises(heta.HetaError, match="beta"):
+        heta.heta_rel_attn_fwd(graph, 0, z, el, el, 0.2, torch.zeros((4, 12), device="cuda"), beta=0.5)
+    with pytest.raises(heta.HetaError, match="smax and sinv"):
+        heta.heta_rel_attn_fwd(graph, 0, z, el, el, 0.2, torch.zeros((4, 12), device="cuda"), smax=torch.zeros((4, 3), device="cuda"))
+    graph.destroy()
+
+
+# ---- the whole layer ---------------------------------------------------------------------------------
+
+def _run_layer(p, ap, tol):
+    a64 = [np.asarray(x, np.float64) for x in ap.a]
+    q64 = [np.asarray(x, np.float64) for x in ap.q]
+    # bf16 storage keeps Z_r as bf16: the oracle reads the same stored values (everything after it is fp64)
+    z_store = (lambda z: rng.round_to_bf16(z.astype(np.float32))) if p.storage == "bf16" else None
+    fwd = rgat.rgat_forward(p, a64, q64, ap.slope, z_store=z_store)
+    exact = rgat.rgat_forward(p, a64, q64, ap.slope) if z_store else fwd
+    # keep the ReLU decision away from its kink (both sides get the same, guarded, upstream gradient)
+    G = {t: np.where(kink_guard(fwd.H[t], tol), p.G[t], 0.0).astype(np.float32) for t in p.G}
+    ref = rgat.rgat_backward(p, a64, q64, fwd, G, ap.slope)
+    graph = make_graph(p)
+    pad = 8 if p.storage == "bf16" else 4
+    tables = [dev_table(t, p.storage, pad) for t in p.tables]
+    W = [dev_table(w, p.storage, pad) for w in p.W]
+    layer = heta.RgatLayer(graph, tables, W, [up(x) for x in ap.a], [up(np.ascontiguousarray(x.T)) for x in ap.q],
+                           p.d_out, ap.heads, ap.slope, relu=p.relu)
+    H = layer.forward()
+    dW, da, dq, dH0 = layer.backward({t: up(g) for t, g in G.items()})
+    torch.cuda.synchronize()
+    for t, h in fwd.H.items():
+        assert_rows_close(host(H[t]), h, tol, f"H[{t}]")
+        assert_rows_close(host(H[t]), exact.H[t], tol, f"H[{t}] against exact Z")
+    rdW, rda, rdq, rdH0 = ref
+    for i in range(len(p.W)):
+        assert_rows_close(host(dW[i]), rdW[i], tol, f"dW[{i}]")
+        assert_rows_close(host(da[i]), rda[i], tol, f"da[{i}]")
+        assert_rows_close(host(dq[i]), rdq[i].T, tol, f"dq[{i}]")
+    assert set(dH0) == set(rdH0)
+    for t, x in rdH0.items():
+        assert_rows_close(host(dH0[t]), x, tol, f"dH0[{t}]")
+    graph.destroy()
+
+
+@pytest.mark.parametrize("storage,tol", [("f32", 1e-4), ("bf16", 2e-2)])
+@pytest.mark.parametrize("heads", [1, 4])
+def test_rgat_layer_tiny(storage, tol, heads):
+    p = workloads.rgat_tiny(storage)
+    _run_layer(p, workloads.attention_params(p, heads, gain=2.0), tol)
+
+
+@pytest.mark.parametrize("storage,tol", [("f32", 1e-4), ("bf16", 2e-2)])
+def test_rgat_layer_config3_scaled(storage, tol):
+    p = workloads.config3(storage, scale=0.02)
+    p.relu = True
+    _run_layer(p, workloads.attention_params(p, 4, gain=1.0), tol)
