@@ -189,6 +189,81 @@ def measure(storage: str, args, keep_problem: bool = False):
     return res, (p if keep_problem else None)
 
 
+def measure_rgat(storage: str, args, heads: int = 4):
+    """The same config-3 graph as an R-GAT layer (GAT module per relation, `heads` heads, ReLU after the
+    cross-relation sum): forward + backward per step, per-kernel HIP-event timings."""
+    import torch
+    import paper_2408_09697_amd as heta
+    from gen import workloads
+    import numpy as np
+    from tests.harness import dev_table, make_graph
+
+    p = workloads.config3(storage, scale=args.scale, upstream=False)
+    ap = workloads.attention_params(p, heads)
+    graph = make_graph(p)
+    pad = 8 if storage == "bf16" else 4
+    tables = [dev_table(t, storage, pad) for t in p.tables]
+    W = [dev_table(w, storage, pad) for w in p.W]
+    a = [torch.from_numpy(x).cuda() for x in ap.a]
+    q = [torch.from_numpy(np.ascontiguousarray(x.T)).cuda() for x in ap.q]
+    layer = heta.RgatLayer(graph, tables, W, a, q, p.d_out, heads, ap.slope, relu=True)
+    gen_dev = torch.Generator(device="cuda")
+    gen_dev.manual_seed(20240809)
+    G = {t: torch.randn(h.shape, generator=gen_dev, device="cuda", dtype=torch.float32) for t, h in layer.H.items()}
+    n_edges = sum(r.num_edges for r in p.graph.relations)
+    edge_features = n_edges * p.d_out
+
+    def step():
+        layer.forward()
+        layer.backward(G)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / max(1, args.steps)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record()
+    layer.forward()
+    ev[1].record()
+    layer.backward(G)
+    ev[2].record()
+    torch.cuda.synchronize()
+    kernels = {}
+    if not args.no_profile:
+        heta.heta_profile_enable(True)
+        heta.heta_profile_reset()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        stats = heta.heta_profile_read()
+        heta.heta_profile_enable(False)
+        for name, st in stats.items():
+            k = {"launches_per_step": st["launches"] / args.steps, "ms_per_step": st["total_ms"] / args.steps,
+                 "GBps": st["algorithmic_bytes"] / st["total_ms"] / 1e6}
+            if st["flops"] > 0:
+                k["TFLOPs"] = st["flops"] / st["total_ms"] / 1e9
+            kernels[name] = k
+    agg = [v for n, v in kernels.items() if n.startswith("agg_")]
+    agg_ms = sum(v["ms_per_step"] for v in agg)
+    agg_mb = sum(v["GBps"] * v["ms_per_step"] for v in agg)
+    res = {"model": f"R-GAT layer on the config-3 graph, {heads} heads, 128->256, {storage} tables",
+           "ms_per_step": ms_per_step, "fwd_ms": ev[0].elapsed_time(ev[1]), "bwd_ms": ev[1].elapsed_time(ev[2]),
+           "value": 2.0 * edge_features / (ms_per_step * 1e-3), "unit": "edge-features/s at the output width (fwd+bwd)",
+           "edges": n_edges,
+           "aggregation_all_kernels": {"bound": "hbm", "ms_per_step": agg_ms, "achieved": agg_mb / agg_ms if agg_ms else 0.0,
+                                       "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                       "frac": (agg_mb / agg_ms / PEAK_HBM_GBS) if agg_ms else 0.0},
+           "kernels": kernels}
+    graph.destroy()
+    del layer, G
+    torch.cuda.empty_cache()
+    return res
+
+
 def measure_minibatch(args):
     """Config 5: one sampled 2-layer mini-batch (4,096 seeds, fanouts [25, 15], 768 -> 1024 -> 1024, mean,
     bf16 tables) on one GPU's partition of the 240 M-node-shaped graph.  A step = building the two block
@@ -297,6 +372,8 @@ def main() -> int:
     ap.add_argument("--workload", choices=["config3", "config4", "config5"], default="config3",
                     help="config3 is the headline; config4 (mixed widths, bf16) and config5 (sampled 2-layer "
                          "mini-batch on the 400 M-edge partition, bf16) are additional measurements")
+    ap.add_argument("--model", choices=["rgcn", "rgat"], default="rgcn",
+                    help="rgcn is the headline layer; rgat measures the attention layer on the config-3 graph only")
     ap.add_argument("--scale", type=float, default=1.0, help="shrinks the graph (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event pass")
@@ -322,6 +399,12 @@ def main() -> int:
     del calib_src, calib_dst
     torch.cuda.empty_cache()
 
+    if args.model == "rgat":
+        out = {"f32": measure_rgat("f32", args)}
+        if not args.single:
+            out["bf16"] = measure_rgat("bf16", args)
+        print(json.dumps(out))
+        return 0
     if args.workload == "config5":
         print(json.dumps(measure_minibatch(args)))
         return 0

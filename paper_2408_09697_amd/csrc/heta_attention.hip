@@ -37,170 +37,351 @@ constexpr int kShortDegAttn = 32; // same split as the aggregation: below, one t
 
 __device__ __forceinline__ float lrelu(float x, float slope) { return x > 0.f ? x : slope * x; }
 
-// ---- reductions over the W lanes that share one (row, head) -------------------------------------------
-template <int W> struct Group;
-template <> struct Group<1> {
-    static __device__ __forceinline__ float sum(float v, float *) { return v; }
-    static __device__ __forceinline__ float max(float v, float *) { return v; }
-};
-template <> struct Group<64> {
-    static __device__ __forceinline__ float sum(float v, float *)
-    {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-        return v;
-    }
-    static __device__ __forceinline__ float max(float v, float *)
-    {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-        return v;
-    }
-};
-template <> struct Group<1024> { // one workgroup of 16 wavefronts; lds holds 16 floats
-    static __device__ __forceinline__ float sum(float v, float *lds)
-    {
-        v = Group<64>::sum(v, nullptr);
-        __syncthreads(); // previous use of lds is over
-        if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
-        __syncthreads();
-        float t = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) t += lds[i];
-        return t;
-    }
-    static __device__ __forceinline__ float max(float v, float *lds)
-    {
-        v = Group<64>::max(v, nullptr);
-        __syncthreads();
-        if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
-        __syncthreads();
-        float t = lds[0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) t = fmaxf(t, lds[i]);
-        return t;
-    }
-};
-
 // ---- row sweeps ------------------------------------------------------------------------------------------
+// One sweep visits every edge slot of a schedule once per phase and touches only scalars: the neighbour's
+// id, KT consecutive heads of its score (one vector load), and the per-slot weights it writes.
+//   rows of fewer than 32 edges: one thread per row; 32..511 edges: one wavefront per row;
+//   hub rows (>= 512 edges): one wavefront per 256-edge chunk writes partial statistics, a second kernel
+//   combines a row's chunks in chunk order, and (forward only) a third writes the weights.
 enum SweepOp { SWEEP_FWD = 0, SWEEP_BWD_CSR = 1, SWEEP_BWD_CSC = 2 };
+enum Phase { PH_MAX = 0, PH_SUM = 1, PH_ALPHA = 2, PH_BWD_DST = 3, PH_BWD_SRC = 4 };
 
 struct SweepParams {
     const int64_t *sptr;
     const int32_t *sidx;
     const int32_t *perm;
+    const HubChunk *hub_chunks;
+    const int64_t *hub_chunk_ptr;
+    int64_t n_hub_rows, n_hub_chunks;
     int64_t q0, q1;       // schedule positions of this launch
     int K;
     float slope;
     const float *row_a;   // [rows][K]  score half of the row side (er for the CSR, el for the CSC)
     const float *nbr_a;   // [nbrs][K]  score half of the neighbour side
-    float *smax, *sinv;   // [dst][K]   softmax shift and 1/denominator: written by FWD, read by the others
+    float *smax, *sinv;   // [dst][K]   softmax shift and 1/denominator: written by FWD (nullable), read by the others
     const float *dot;     // [dst][K]   <g, o> per head (backward)
     float *alpha;         // [E][K] by edge slot (FWD, BWD_CSC)
     float *gate;          // [E][K] by edge slot (BWD_*)
     float *corr;          // [rows][K]  the scalar term subtracted from the row's score gradient (BWD_*)
+    float *part;          // hub chunks: [n_hub_chunks][K][2] partial statistics
+    float *hub_stat;      // hub rows (FWD): [n_hub_rows][K][2] = shift, 1/denominator
 };
 
-template <int W, int OP>
-__global__ void __launch_bounds__(W == 1 ? 256 : (W == 64 ? 256 : 1024)) attn_sweep_kernel(SweepParams p)
+template <int KT> __device__ __forceinline__ void loadk(const float *p, float *v);
+template <> __device__ __forceinline__ void loadk<1>(const float *p, float *v) { v[0] = *p; }
+template <> __device__ __forceinline__ void loadk<2>(const float *p, float *v)
 {
-    __shared__ float lds[16];
-    int64_t q;
-    int lane;
-    if (W == 1) {
-        q = p.q0 + static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-        lane = 0;
-    } else if (W == 64) {
-        q = p.q0 + static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-        lane = threadIdx.x & 63;
-    } else {
-        q = p.q0 + blockIdx.x;
-        lane = threadIdx.x;
+    const float2 t = *reinterpret_cast<const float2 *>(p);
+    v[0] = t.x; v[1] = t.y;
+}
+template <> __device__ __forceinline__ void loadk<4>(const float *p, float *v)
+{
+    const float4 t = *reinterpret_cast<const float4 *>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+template <int KT> __device__ __forceinline__ void storek(float *p, const float *v);
+template <> __device__ __forceinline__ void storek<1>(float *p, const float *v) { *p = v[0]; }
+template <> __device__ __forceinline__ void storek<2>(float *p, const float *v) { *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]); }
+template <> __device__ __forceinline__ void storek<4>(float *p, const float *v)
+{
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+// One edge slot e, heads k0 .. k0+KT-1.  ar: the row's score half; m, inv: shift and 1/denominator of the
+// row (unused by PH_MAX and PH_BWD_SRC, which reads the neighbour's); acc: running max or sum.
+template <int KT, int PH>
+__device__ __forceinline__ void visit(const SweepParams &p, int64_t e, int k0, const float *ar, const float *m,
+                                      const float *inv, float *acc)
+{
+    const int64_t id = p.sidx[e];
+    float x[KT];
+    loadk<KT>(p.nbr_a + id * p.K + k0, x);
+    float mv[KT], iv[KT], dv[KT];
+    if (PH == PH_BWD_SRC) {
+        loadk<KT>(p.smax + id * p.K + k0, mv);
+        loadk<KT>(p.sinv + id * p.K + k0, iv);
+        loadk<KT>(p.dot + id * p.K + k0, dv);
     }
-    if (q >= p.q1) return; // uniform over the W lanes of a group (and over the workgroup when W = 1024)
-    const int k = blockIdx.y;
-    const int K = p.K;
+    float a[KT], gt[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        x[k] += ar[k];
+        const float sc = lrelu(x[k], p.slope);
+        if (PH == PH_MAX) {
+            acc[k] = fmaxf(acc[k], sc);
+        } else if (PH == PH_SUM) {
+            acc[k] += expf(sc - m[k]);
+        } else if (PH == PH_ALPHA) {
+            a[k] = expf(sc - m[k]) * inv[k];
+        } else if (PH == PH_BWD_DST) {
+            gt[k] = expf(sc - m[k]) * inv[k] * (x[k] > 0.f ? 1.f : p.slope);
+            acc[k] += gt[k];
+        } else {
+            a[k] = expf(sc - mv[k]) * iv[k];
+            gt[k] = a[k] * (x[k] > 0.f ? 1.f : p.slope);
+            acc[k] = fmaf(gt[k], dv[k], acc[k]);
+        }
+    }
+    if (PH == PH_ALPHA || PH == PH_BWD_SRC) storek<KT>(p.alpha + e * p.K + k0, a);
+    if (PH == PH_BWD_DST || PH == PH_BWD_SRC) storek<KT>(p.gate + e * p.K + k0, gt);
+}
+
+template <int W, int KT, int PH>
+__device__ __forceinline__ void sweep_range(const SweepParams &p, int64_t e0, int64_t e1, int lane, int k0, const float *ar,
+                                            const float *m, const float *inv, float *acc)
+{
+#pragma unroll 4
+    for (int64_t e = e0 + lane; e < e1; e += W) visit<KT, PH>(p, e, k0, ar, m, inv, acc);
+}
+
+template <int KT> __device__ __forceinline__ void wave_sum(float *v)
+{
+#pragma unroll
+    for (int k = 0; k < KT; ++k)
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v[k] += __shfl_xor(v[k], off, 64);
+}
+template <int KT> __device__ __forceinline__ void wave_max(float *v)
+{
+#pragma unroll
+    for (int k = 0; k < KT; ++k)
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v[k] = fmaxf(v[k], __shfl_xor(v[k], off, 64));
+}
+
+// rows below the hub threshold: W = 1 (one thread per row) or W = 64 (one wavefront per row)
+template <int W, int KT, int OP>
+__global__ void __launch_bounds__(256) attn_rows_kernel(SweepParams p)
+{
+    const int lane = W == 1 ? 0 : (threadIdx.x & 63);
+    const int64_t q = p.q0 + (W == 1 ? static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x
+                                     : static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6));
+    if (q >= p.q1) return; // uniform per wavefront when W = 64
+    const int k0 = blockIdx.y * KT;
     const int64_t row = p.perm[q];
     const int64_t e0 = p.sptr[q], e1 = p.sptr[q + 1];
-    const float ar = p.row_a[row * K + k];
+    float ar[KT], acc[KT], m[KT], inv[KT];
+    loadk<KT>(p.row_a + row * p.K + k0, ar);
     if (OP == SWEEP_FWD) {
-        float m = -INFINITY;
-        for (int64_t e = e0 + lane; e < e1; e += W)
-            m = fmaxf(m, lrelu(p.nbr_a[static_cast<int64_t>(p.sidx[e]) * K + k] + ar, p.slope));
-        m = Group<W>::max(m, lds);
-        float den = 0.f;
-        for (int64_t e = e0 + lane; e < e1; e += W)
-            den += expf(lrelu(p.nbr_a[static_cast<int64_t>(p.sidx[e]) * K + k] + ar, p.slope) - m);
-        den = Group<W>::sum(den, lds);
+#pragma unroll
+        for (int k = 0; k < KT; ++k) m[k] = -INFINITY;
+        sweep_range<W, KT, PH_MAX>(p, e0, e1, lane, k0, ar, nullptr, nullptr, m);
+        if (W == 64) wave_max<KT>(m);
+#pragma unroll
+        for (int k = 0; k < KT; ++k) acc[k] = 0.f;
+        sweep_range<W, KT, PH_SUM>(p, e0, e1, lane, k0, ar, m, nullptr, acc);
+        if (W == 64) wave_sum<KT>(acc);
         const bool empty = e1 == e0;
-        const float inv = empty ? 0.f : 1.f / den;
-        if (empty) m = 0.f;
-        for (int64_t e = e0 + lane; e < e1; e += W)
-            p.alpha[e * K + k] = expf(lrelu(p.nbr_a[static_cast<int64_t>(p.sidx[e]) * K + k] + ar, p.slope) - m) * inv;
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            inv[k] = empty ? 0.f : 1.f / acc[k];
+            if (empty) m[k] = 0.f;
+        }
+        sweep_range<W, KT, PH_ALPHA>(p, e0, e1, lane, k0, ar, m, inv, nullptr);
         if (lane == 0 && p.smax) {
-            p.smax[row * K + k] = m;
-            p.sinv[row * K + k] = inv;
+            storek<KT>(p.smax + row * p.K + k0, m);
+            storek<KT>(p.sinv + row * p.K + k0, inv);
         }
-    } else if (OP == SWEEP_BWD_CSR) {
-        const float m = p.smax[row * K + k], inv = p.sinv[row * K + k];
-        float gs = 0.f;
-        for (int64_t e = e0 + lane; e < e1; e += W) {
-            const float x = p.nbr_a[static_cast<int64_t>(p.sidx[e]) * K + k] + ar;
-            const float gt = expf(lrelu(x, p.slope) - m) * inv * (x > 0.f ? 1.f : p.slope);
-            p.gate[e * K + k] = gt;
-            gs += gt;
-        }
-        gs = Group<W>::sum(gs, lds);
-        if (lane == 0) p.corr[row * K + k] = p.dot[row * K + k] * gs;
     } else {
-        float c = 0.f;
-        for (int64_t e = e0 + lane; e < e1; e += W) {
-            const int64_t v = p.sidx[e];
-            const float x = p.nbr_a[v * K + k] + ar;
-            const float a = expf(lrelu(x, p.slope) - p.smax[v * K + k]) * p.sinv[v * K + k];
-            const float gt = a * (x > 0.f ? 1.f : p.slope);
-            p.alpha[e * K + k] = a;
-            p.gate[e * K + k] = gt;
-            c += gt * p.dot[v * K + k];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) acc[k] = 0.f;
+        if (OP == SWEEP_BWD_CSR) {
+            loadk<KT>(p.smax + row * p.K + k0, m);
+            loadk<KT>(p.sinv + row * p.K + k0, inv);
+            sweep_range<W, KT, PH_BWD_DST>(p, e0, e1, lane, k0, ar, m, inv, acc);
+        } else {
+            sweep_range<W, KT, PH_BWD_SRC>(p, e0, e1, lane, k0, ar, nullptr, nullptr, acc);
         }
-        c = Group<W>::sum(c, lds);
-        if (lane == 0) p.corr[row * K + k] = c;
+        if (W == 64) wave_sum<KT>(acc);
+        if (lane == 0) {
+            if (OP == SWEEP_BWD_CSR) {
+                float d[KT];
+                loadk<KT>(p.dot + row * p.K + k0, d);
+#pragma unroll
+                for (int k = 0; k < KT; ++k) acc[k] *= d[k];
+            }
+            storek<KT>(p.corr + row * p.K + k0, acc);
+        }
     }
 }
 
+// hub row of chunk w: the h with hub_chunk_ptr[h] <= w < hub_chunk_ptr[h + 1]
+__device__ __forceinline__ int64_t hub_of_chunk(const SweepParams &p, int64_t w)
+{
+    int64_t lo = 0, hi = p.n_hub_rows; // invariant: ptr[lo] <= w < ptr[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (p.hub_chunk_ptr[mid] <= w) lo = mid;
+        else hi = mid;
+    }
+    return lo;
+}
+
+// hub chunks, first kernel: partial statistics of one chunk (and the backward's weights)
+template <int KT, int OP>
+__global__ void __launch_bounds__(256) attn_hub_partial_kernel(SweepParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t w = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (w >= p.n_hub_chunks) return; // uniform per wavefront
+    const int k0 = blockIdx.y * KT;
+    const HubChunk c = p.hub_chunks[w];
+    const int64_t row = p.perm[hub_of_chunk(p, w)];
+    const int64_t e0 = c.e0, e1 = c.e0 + c.len;
+    float ar[KT], acc[KT], m[KT], inv[KT];
+    loadk<KT>(p.row_a + row * p.K + k0, ar);
+    float *out = p.part + (w * p.K + k0) * 2;
+    if (OP == SWEEP_FWD) {
+#pragma unroll
+        for (int k = 0; k < KT; ++k) m[k] = -INFINITY;
+        sweep_range<64, KT, PH_MAX>(p, e0, e1, lane, k0, ar, nullptr, nullptr, m);
+        wave_max<KT>(m);
+#pragma unroll
+        for (int k = 0; k < KT; ++k) acc[k] = 0.f;
+        sweep_range<64, KT, PH_SUM>(p, e0, e1, lane, k0, ar, m, nullptr, acc);
+        wave_sum<KT>(acc);
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                out[2 * k] = m[k];
+                out[2 * k + 1] = acc[k];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < KT; ++k) acc[k] = 0.f;
+        if (OP == SWEEP_BWD_CSR) {
+            loadk<KT>(p.smax + row * p.K + k0, m);
+            loadk<KT>(p.sinv + row * p.K + k0, inv);
+            sweep_range<64, KT, PH_BWD_DST>(p, e0, e1, lane, k0, ar, m, inv, acc);
+        } else {
+            sweep_range<64, KT, PH_BWD_SRC>(p, e0, e1, lane, k0, ar, nullptr, nullptr, acc);
+        }
+        wave_sum<KT>(acc);
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < KT; ++k) out[2 * k] = acc[k];
+        }
+    }
+}
+
+// hub rows, second kernel: one wavefront per (hub row, head) combines the row's chunks in chunk order
 template <int OP>
-heta_status launch_sweeps(const Schedule &s, SweepParams p, hipStream_t st, const char *name)
+__global__ void __launch_bounds__(256) attn_hub_combine_kernel(SweepParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t h = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (h >= p.n_hub_rows) return;
+    const int k = blockIdx.y;
+    const int64_t row = p.perm[h];
+    const int64_t s0 = p.hub_chunk_ptr[h], s1 = p.hub_chunk_ptr[h + 1];
+    if (OP == SWEEP_FWD) {
+        float m = -INFINITY;
+        for (int64_t s = s0 + lane; s < s1; s += 64) m = fmaxf(m, p.part[(s * p.K + k) * 2]);
+        wave_max<1>(&m);
+        float den = 0.f;
+        for (int64_t s = s0 + lane; s < s1; s += 64) den += p.part[(s * p.K + k) * 2 + 1] * expf(p.part[(s * p.K + k) * 2] - m);
+        wave_sum<1>(&den);
+        if (lane == 0) {
+            const float inv = 1.f / den; // a hub row has edges
+            p.hub_stat[(h * p.K + k) * 2] = m;
+            p.hub_stat[(h * p.K + k) * 2 + 1] = inv;
+            if (p.smax) {
+                p.smax[row * p.K + k] = m;
+                p.sinv[row * p.K + k] = inv;
+            }
+        }
+    } else {
+        float a = 0.f;
+        for (int64_t s = s0 + lane; s < s1; s += 64) a += p.part[(s * p.K + k) * 2];
+        wave_sum<1>(&a);
+        if (lane == 0) p.corr[row * p.K + k] = OP == SWEEP_BWD_CSR ? a * p.dot[row * p.K + k] : a;
+    }
+}
+
+// hub chunks, third kernel (forward): the weights, from the combined statistics
+template <int KT>
+__global__ void __launch_bounds__(256) attn_hub_alpha_kernel(SweepParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t w = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (w >= p.n_hub_chunks) return;
+    const int k0 = blockIdx.y * KT;
+    const HubChunk c = p.hub_chunks[w];
+    const int64_t h = hub_of_chunk(p, w);
+    const int64_t row = p.perm[h];
+    float ar[KT], m[KT], inv[KT];
+    loadk<KT>(p.row_a + row * p.K + k0, ar);
+#pragma unroll
+    for (int k = 0; k < KT; ++k) {
+        m[k] = p.hub_stat[(h * p.K + k0 + k) * 2];
+        inv[k] = p.hub_stat[(h * p.K + k0 + k) * 2 + 1];
+    }
+    sweep_range<64, KT, PH_ALPHA>(p, c.e0, c.e0 + c.len, lane, k0, ar, m, inv, nullptr);
+}
+
+inline size_t hub_scratch_bytes(const Schedule &s, int K)
+{
+    return static_cast<size_t>(s.n_hub_chunks + s.n_hub_rows) * K * 2 * sizeof(float);
+}
+
+template <int KT, int OP>
+heta_status launch_sweeps_kt(const Schedule &s, SweepParams p, hipStream_t st)
+{
+    const int64_t n_long_or_hub = s.rows_with_deg_ge[kShortDegAttn];
+    const unsigned gy = p.K / KT;
+    if (s.n_hub_rows > 0) {
+        const unsigned cb = (unsigned)((s.n_hub_chunks + 3) / 4), rb = (unsigned)((s.n_hub_rows + 3) / 4);
+        hipLaunchKernelGGL((attn_hub_partial_kernel<KT, OP>), dim3(cb, gy), dim3(256), 0, st, p);
+        HETA_LAUNCH_CHECK("attn_hub_partial_kernel");
+        hipLaunchKernelGGL((attn_hub_combine_kernel<OP>), dim3(rb, p.K), dim3(256), 0, st, p);
+        HETA_LAUNCH_CHECK("attn_hub_combine_kernel");
+        if (OP == SWEEP_FWD) {
+            hipLaunchKernelGGL((attn_hub_alpha_kernel<KT>), dim3(cb, gy), dim3(256), 0, st, p);
+            HETA_LAUNCH_CHECK("attn_hub_alpha_kernel");
+        }
+    }
+    if (n_long_or_hub > s.n_hub_rows) {
+        p.q0 = s.n_hub_rows;
+        p.q1 = n_long_or_hub;
+        hipLaunchKernelGGL((attn_rows_kernel<64, KT, OP>), dim3((unsigned)((p.q1 - p.q0 + 3) / 4), gy), dim3(256), 0, st, p);
+        HETA_LAUNCH_CHECK("attn_rows_kernel");
+    }
+    if (s.n_rows > n_long_or_hub) {
+        p.q0 = n_long_or_hub;
+        p.q1 = s.n_rows;
+        hipLaunchKernelGGL((attn_rows_kernel<1, KT, OP>), dim3((unsigned)((p.q1 - p.q0 + 255) / 256), gy), dim3(256), 0, st, p);
+        HETA_LAUNCH_CHECK("attn_rows_kernel");
+    }
+    return HETA_OK;
+}
+
+// `hub_scratch`: hub_scratch_bytes(s, K) bytes of device memory for the hub rows' partial statistics
+template <int OP>
+heta_status launch_sweeps(const Schedule &s, SweepParams p, float *hub_scratch, hipStream_t st, const char *name)
 {
     if (s.n_rows == 0) return HETA_OK;
     p.sptr = s.d_sptr;
     p.sidx = s.d_sidx;
     p.perm = s.d_perm;
-    const int64_t n_long_or_hub = s.rows_with_deg_ge[kShortDegAttn];
-    // Algorithmic bytes: per edge and head one 4-byte score of the neighbour and the weights written;
-    // per edge one 4-byte id; per row its offsets and per-head terms.
-    const double per_edge = 4.0 + p.K * (OP == SWEEP_FWD ? 8.0 : (OP == SWEEP_BWD_CSR ? 8.0 : 24.0));
+    p.hub_chunks = s.d_hub_chunks;
+    p.hub_chunk_ptr = s.d_hub_chunk_ptr;
+    p.n_hub_rows = s.n_hub_rows;
+    p.n_hub_chunks = s.n_hub_chunks;
+    p.part = hub_scratch;
+    p.hub_stat = hub_scratch + s.n_hub_chunks * p.K * 2;
+    // Algorithmic bytes: per edge one 4-byte id, per edge and head the neighbour's 4-byte terms and the
+    // 4-byte weights written; per row its offsets and per-head terms.
+    const double per_edge = 4.0 + p.K * (OP == SWEEP_BWD_CSC ? 24.0 : 8.0);
     ProfScope prof(name, st, per_edge * static_cast<double>(s.n_edges) + static_cast<double>(s.n_rows) * (12.0 + 12.0 * p.K), 0);
-    if (s.n_hub_rows > 0) {
-        p.q0 = 0;
-        p.q1 = s.n_hub_rows;
-        hipLaunchKernelGGL((attn_sweep_kernel<1024, OP>), dim3((unsigned)s.n_hub_rows, p.K), dim3(1024), 0, st, p);
-        HETA_LAUNCH_CHECK("attn_sweep_kernel");
-    }
-    if (n_long_or_hub > s.n_hub_rows) {
-        p.q0 = s.n_hub_rows;
-        p.q1 = n_long_or_hub;
-        const int64_t blocks = (p.q1 - p.q0 + 3) / 4;
-        hipLaunchKernelGGL((attn_sweep_kernel<64, OP>), dim3((unsigned)blocks, p.K), dim3(256), 0, st, p);
-        HETA_LAUNCH_CHECK("attn_sweep_kernel");
-    }
-    if (s.n_rows > n_long_or_hub) {
-        p.q0 = n_long_or_hub;
-        p.q1 = s.n_rows;
-        const int64_t blocks = (p.q1 - p.q0 + 255) / 256;
-        hipLaunchKernelGGL((attn_sweep_kernel<1, OP>), dim3((unsigned)blocks, p.K), dim3(256), 0, st, p);
-        HETA_LAUNCH_CHECK("attn_sweep_kernel");
-    }
-    return HETA_OK;
+    // KT consecutive heads per thread need 4*KT-byte aligned score rows
+    const uintptr_t all = reinterpret_cast<uintptr_t>(p.row_a) | reinterpret_cast<uintptr_t>(p.nbr_a) |
+                          reinterpret_cast<uintptr_t>(p.smax) | reinterpret_cast<uintptr_t>(p.sinv) |
+                          reinterpret_cast<uintptr_t>(p.dot) | reinterpret_cast<uintptr_t>(p.alpha) |
+                          reinterpret_cast<uintptr_t>(p.gate) | reinterpret_cast<uintptr_t>(p.corr);
+    if (p.K % 4 == 0 && all % 16 == 0) return launch_sweeps_kt<4, OP>(s, p, st);
+    if (p.K % 2 == 0 && all % 8 == 0) return launch_sweeps_kt<2, OP>(s, p, st);
+    return launch_sweeps_kt<1, OP>(s, p, st);
 }
 
 // ---- per-row, per-head dot products -------------------------------------------------------------------
@@ -265,6 +446,77 @@ __global__ void __launch_bounds__(256) attn_rowdot_kernel(DotParams p)
     if (lane < p.K) p.out[i * p.K + lane] = res - (p.corr ? p.corr[i * p.K + lane] : 0.f);
 }
 
+// Fast path: a row's 16-byte chunks are spread over a group of L lanes (L a power of two, T chunks per
+// lane), 64 / L rows per wavefront, every chunk loaded once; the per-head sums are segmented cross-lane
+// reductions.  Needs 4-element chunks that do not straddle heads and, per head, a power-of-two number of
+// chunks (cph); a head then lies inside one t (cph <= L) or covers whole t's (cph a multiple of L).
+template <typename TX, typename TY, int T>
+__global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int L, int cph)
+{
+    const int lane = threadIdx.x & 63;
+    const int G = 64 / L, g = lane / L, l = lane % L;
+    const int64_t i = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * G + g;
+    const bool live = i < p.n;
+    const int n_chunks = p.d / 4;
+    const TX *x = static_cast<const TX *>(p.x) + (live ? i : 0) * p.ld_x;
+    const TY *y = static_cast<const TY *>(p.y) + (live ? i : 0) * p.ld_y;
+    float xv[T][4];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int c = l + L * t;
+        if (live && c < n_chunks) ldv<TX, 4>(x + 4 * c, xv[t]);
+        else xv[t][0] = xv[t][1] = xv[t][2] = xv[t][3] = 0.f;
+    }
+    if (p.per_head) {
+        float part[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int c = l + L * t;
+            float yv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (live && c < n_chunks) ldv<TY, 4>(y + 4 * c, yv);
+            part[t] = xv[t][0] * yv[0] + xv[t][1] * yv[1] + xv[t][2] * yv[2] + xv[t][3] * yv[3];
+        }
+        if (cph <= L) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                for (int off = cph >> 1; off > 0; off >>= 1) part[t] += __shfl_xor(part[t], off, 64);
+                const int c = l + L * t;
+                if (live && c < n_chunks && (l & (cph - 1)) == 0) {
+                    const int k = c / cph;
+                    p.out[i * p.K + k] = part[t] - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                }
+            }
+        } else {
+            const int m = cph / L; // t's per head
+            float acc = 0.f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                acc += part[t];
+                if ((t + 1) % m == 0) {
+                    for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+                    const int k = t / m;
+                    if (live && l == 0 && k < p.K) p.out[i * p.K + k] = acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                    acc = 0.f;
+                }
+            }
+        }
+    } else {
+        for (int k = 0; k < p.K; ++k) {
+            const TY *yk = y + static_cast<int64_t>(k) * p.d;
+            float acc = 0.f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int c = l + L * t;
+                float yv[4] = {0.f, 0.f, 0.f, 0.f};
+                if (live && c < n_chunks) ldv<TY, 4>(yk + 4 * c, yv);
+                acc += xv[t][0] * yv[0] + xv[t][1] * yv[1] + xv[t][2] * yv[2] + xv[t][3] * yv[3];
+            }
+            for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+            if (live && l == 0) p.out[i * p.K + k] = acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
+        }
+    }
+}
+
 template <typename TX, typename TY>
 heta_status launch_rowdot_t(const DotParams &p, hipStream_t st)
 {
@@ -277,8 +529,28 @@ heta_status launch_rowdot_t(const DotParams &p, hipStream_t st)
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "attention: too many rows");
     const double bytes = static_cast<double>(p.n) * (p.d * (sx + (p.ld_y ? sy : 0)) + 4.0 * p.K * (p.corr ? 2 : 1));
     ProfScope prof("attn_rowdot_kernel", st, bytes, 0);
-    if (vec) hipLaunchKernelGGL((attn_rowdot_kernel<TX, TY, 4>), dim3((unsigned)blocks), dim3(256), 0, st, p);
-    else hipLaunchKernelGGL((attn_rowdot_kernel<TX, TY, 1>), dim3((unsigned)blocks), dim3(256), 0, st, p);
+    if (vec) {
+        const int n_chunks = p.d / 4;
+        int L = 1;
+        while (L < n_chunks && L < 64) L <<= 1;
+        const int T = (n_chunks + L - 1) / L;
+        const int cph = p.F / 4;
+        const bool pow2 = (cph & (cph - 1)) == 0;
+        if (T <= 4 && (!p.per_head || (pow2 && (cph <= L || T % (cph / L) == 0)))) {
+            const int64_t rows_per_block = 4 * (64 / L);
+            const dim3 grid((unsigned)((p.n + rows_per_block - 1) / rows_per_block));
+            switch (T) {
+            case 1: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 1>), grid, dim3(256), 0, st, p, L, cph); break;
+            case 2: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 2>), grid, dim3(256), 0, st, p, L, cph); break;
+            case 3: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 3>), grid, dim3(256), 0, st, p, L, cph); break;
+            default: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 4>), grid, dim3(256), 0, st, p, L, cph); break;
+            }
+        } else {
+            hipLaunchKernelGGL((attn_rowdot_kernel<TX, TY, 4>), dim3((unsigned)blocks), dim3(256), 0, st, p);
+        }
+    } else {
+        hipLaunchKernelGGL((attn_rowdot_kernel<TX, TY, 1>), dim3((unsigned)blocks), dim3(256), 0, st, p);
+    }
     HETA_LAUNCH_CHECK("attn_rowdot_kernel");
     return HETA_OK;
 }
@@ -309,9 +581,39 @@ __global__ void __launch_bounds__(256) attn_score_bwd_input_kernel(const float *
     *o = beta != 0.f ? *o + v : v;
 }
 
+// the same, four columns per thread (rows 16-byte aligned, heads a multiple of four columns wide)
+__global__ void __launch_bounds__(256) attn_score_bwd_input_vec_kernel(const float *ds, const float *vec, int64_t n, int d,
+                                                                       int K, int F, int per_head, float *dx,
+                                                                       int64_t ld_dx, float beta)
+{
+    const int d4 = d / 4;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t i = t / d4;
+    const int j = static_cast<int>(t - i * d4) * 4;
+    if (i >= n) return;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (per_head) {
+        const float s = ds[i * K + j / F];
+        const float4 w = *reinterpret_cast<const float4 *>(vec + j);
+        v = make_float4(s * w.x, s * w.y, s * w.z, s * w.w);
+    } else {
+        for (int k = 0; k < K; ++k) {
+            const float s = ds[i * K + k];
+            const float4 w = *reinterpret_cast<const float4 *>(vec + static_cast<int64_t>(k) * d + j);
+            v.x = fmaf(s, w.x, v.x); v.y = fmaf(s, w.y, v.y); v.z = fmaf(s, w.z, v.z); v.w = fmaf(s, w.w, v.w);
+        }
+    }
+    float4 *o = reinterpret_cast<float4 *>(dx + i * ld_dx + j);
+    if (beta != 0.f) {
+        const float4 old = *o;
+        v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+    }
+    *o = v;
+}
+
 // dvec_k[j] = sum_i ds[i, k] x[i, j]: stage 1, one workgroup per (slab of rows, 256 columns), partial sums
 // to part[slab][k][j] (per_head: part[slab][j], only k = j / F); stage 2 adds the slabs in order.
-constexpr int kSlabRows = 1024;
+constexpr int kSlabRows = 512;
 template <typename T>
 __global__ void __launch_bounds__(256) attn_score_bwd_param_kernel(const T *x, int64_t ld_x, const float *ds, int64_t n,
                                                                    int d, int K, int F, int per_head, float *part)
@@ -338,6 +640,62 @@ __global__ void __launch_bounds__(256) attn_score_bwd_param_kernel(const T *x, i
 #pragma unroll
     for (int k = 0; k < kMaxHeads; ++k)
         if (k < nk) part[(slab * nk + k) * d + j] = acc[k];
+}
+
+// the same, four columns per lane and four row groups per workgroup (rows 16 / 8-byte aligned, heads a
+// multiple of four columns wide); the row groups are added in order through LDS
+template <typename T>
+__global__ void __launch_bounds__(256) attn_score_bwd_param_vec_kernel(const T *x, int64_t ld_x, const float *ds, int64_t n,
+                                                                       int d, int K, int F, int per_head, float *part)
+{
+    __shared__ float4 red[4][64];
+    const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int j = (blockIdx.y * 64 + lane) * 4;
+    const int64_t slab = blockIdx.x;
+    const int64_t i0 = slab * kSlabRows, i1 = min(n, i0 + kSlabRows);
+    const bool live = j < d;
+    const int nk = per_head ? 1 : K;
+    const int kh = per_head && live ? j / F : 0;
+    float acc[kMaxHeads][4];
+#pragma unroll
+    for (int k = 0; k < kMaxHeads; ++k) acc[k][0] = acc[k][1] = acc[k][2] = acc[k][3] = 0.f;
+    if (live) {
+#pragma unroll 4
+        for (int64_t i = i0 + rg; i < i1; i += 4) {
+            float xv[4];
+            ldv<T, 4>(x + i * ld_x + j, xv);
+            if (per_head) {
+                const float s = ds[i * K + kh];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[0][c] = fmaf(s, xv[c], acc[0][c]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < kMaxHeads; ++k)
+                    if (k < K) {
+                        const float s = ds[i * K + k];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[k][c] = fmaf(s, xv[c], acc[k][c]);
+                    }
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kMaxHeads; ++k) {
+        if (k < nk) { // uniform
+            red[rg][lane] = make_float4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
+            __syncthreads();
+            if (rg == 0 && live) {
+                float4 a = red[0][lane];
+#pragma unroll
+                for (int r = 1; r < 4; ++r) {
+                    const float4 b = red[r][lane];
+                    a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+                }
+                *reinterpret_cast<float4 *>(part + (slab * nk + k) * d + j) = a;
+            }
+            __syncthreads();
+        }
+    }
 }
 
 __global__ void __launch_bounds__(256) attn_slab_sum_kernel(const float *part, int64_t n_slabs, int64_t elems, float *out)
@@ -420,8 +778,13 @@ heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int
         const int64_t blocks = (threads + 255) / 256;
         if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "heta_attn_score_bwd: too many elements");
         ProfScope prof("attn_score_bwd_input_kernel", st, static_cast<double>(n) * (d * (beta != 0.f ? 8.0 : 4.0) + 4.0 * heads), 0);
-        hipLaunchKernelGGL(attn_score_bwd_input_kernel, dim3((unsigned)blocks), dim3(256), 0, st, dscore, vec, n, (int)d,
-                           (int)heads, F, per_head ? 1 : 0, dx, ld_dx, beta);
+        const bool vec4 = d % 4 == 0 && F % 4 == 0 && ld_dx % 4 == 0 && aligned16(dx) && aligned16(vec);
+        if (vec4)
+            hipLaunchKernelGGL(attn_score_bwd_input_vec_kernel, dim3((unsigned)((threads / 4 + 255) / 256)), dim3(256), 0, st,
+                               dscore, vec, n, (int)d, (int)heads, F, per_head ? 1 : 0, dx, ld_dx, beta);
+        else
+            hipLaunchKernelGGL(attn_score_bwd_input_kernel, dim3((unsigned)blocks), dim3(256), 0, st, dscore, vec, n, (int)d,
+                               (int)heads, F, per_head ? 1 : 0, dx, ld_dx, beta);
         HETA_LAUNCH_CHECK("attn_score_bwd_input_kernel");
     }
     if (dvec) {
@@ -438,12 +801,22 @@ heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int
         {
             ProfScope prof("attn_score_bwd_param_kernel", st, static_cast<double>(n) * (d * dtype_size(dt) + 4.0 * heads), 0);
             const dim3 grid((unsigned)n_slabs, (d + 255) / 256);
-            if (dt == HETA_F32)
-                hipLaunchKernelGGL((attn_score_bwd_param_kernel<float>), grid, dim3(256), 0, st, static_cast<const float *>(x),
-                                   ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
-            else
-                hipLaunchKernelGGL((attn_score_bwd_param_kernel<bf16_t>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(x),
-                                   ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
+            const bool vec4 = d % 4 == 0 && F % 4 == 0 && ld_x % 4 == 0 && reinterpret_cast<uintptr_t>(x) % (4 * dtype_size(dt)) == 0;
+            if (dt == HETA_F32) {
+                if (vec4)
+                    hipLaunchKernelGGL((attn_score_bwd_param_vec_kernel<float>), grid, dim3(256), 0, st, static_cast<const float *>(x),
+                                       ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
+                else
+                    hipLaunchKernelGGL((attn_score_bwd_param_kernel<float>), grid, dim3(256), 0, st, static_cast<const float *>(x),
+                                       ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
+            } else {
+                if (vec4)
+                    hipLaunchKernelGGL((attn_score_bwd_param_vec_kernel<bf16_t>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(x),
+                                       ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
+                else
+                    hipLaunchKernelGGL((attn_score_bwd_param_kernel<bf16_t>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(x),
+                                       ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
+            }
             HETA_LAUNCH_CHECK("attn_score_bwd_param_kernel");
         }
         hipLaunchKernelGGL(attn_slab_sum_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, part, n_slabs, elems, dvec);
@@ -467,9 +840,11 @@ heta_status heta_rel_attn_fwd(heta_graph *g, int32_t rel, const void *z, heta_dt
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_attn_fwd: pointer not aligned to its element size");
     const Relation &r = g->rels[rel];
     hipStream_t st = as_stream(hip_stream);
-    e = ensure_attn(g, round256(static_cast<size_t>(r.n_edges) * heads * sizeof(float)));
+    const size_t a_bytes = round256(static_cast<size_t>(r.n_edges) * heads * sizeof(float));
+    e = ensure_attn(g, a_bytes + hub_scratch_bytes(r.csr, heads));
     if (e != HETA_OK) return e;
     float *alpha = static_cast<float *>(g->d_attn);
+    float *hub_scratch = reinterpret_cast<float *>(static_cast<char *>(g->d_attn) + a_bytes);
     SweepParams sp{};
     sp.K = heads;
     sp.slope = slope;
@@ -478,7 +853,7 @@ heta_status heta_rel_attn_fwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     sp.smax = smax;
     sp.sinv = sinv;
     sp.alpha = alpha;
-    e = launch_sweeps<SWEEP_FWD>(r.csr, sp, st, "attn_sweep_fwd");
+    e = launch_sweeps<SWEEP_FWD>(r.csr, sp, hub_scratch, st, "attn_sweep_fwd");
     if (e != HETA_OK) return e;
     return aggregate_slot_weighted(g, r.csr, z, z_dt, ld_z, d, alpha, heads, out, out_dt, ld_out, beta, st);
 }
@@ -506,7 +881,8 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     const size_t src_bytes = round256(static_cast<size_t>(r.n_src) * K * sizeof(float));
     const int64_t ld_r = (static_cast<int64_t>(d) + 3) / 4 * 4;
     const size_t r_bytes = round256(static_cast<size_t>(std::max(r.n_dst, r.n_src)) * ld_r * sizeof(float));
-    e = ensure_attn(g, 2 * w_bytes + 2 * dst_bytes + src_bytes + r_bytes);
+    const size_t hub_bytes = round256(std::max(hub_scratch_bytes(r.csr, K), hub_scratch_bytes(r.csc, K)));
+    e = ensure_attn(g, 2 * w_bytes + 2 * dst_bytes + src_bytes + r_bytes + hub_bytes);
     if (e != HETA_OK) return e;
     char *base = static_cast<char *>(g->d_attn);
     float *w_alpha = reinterpret_cast<float *>(base);
@@ -515,6 +891,7 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     float *corr_d = reinterpret_cast<float *>(base + 2 * w_bytes + dst_bytes);
     float *corr_s = reinterpret_cast<float *>(base + 2 * w_bytes + 2 * dst_bytes);
     float *R = reinterpret_cast<float *>(base + 2 * w_bytes + 2 * dst_bytes + src_bytes);
+    float *hub_scratch = reinterpret_cast<float *>(base + 2 * w_bytes + 2 * dst_bytes + src_bytes + r_bytes);
 
     // dot[v, k] = <g[v, k, :], o[v, k, :]>
     DotParams dp{};
@@ -543,7 +920,7 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     sp.dot = dot;
     sp.gate = w_gate;
     sp.corr = corr_d;
-    e = launch_sweeps<SWEEP_BWD_CSR>(r.csr, sp, st, "attn_sweep_bwd_dst");
+    e = launch_sweeps<SWEEP_BWD_CSR>(r.csr, sp, hub_scratch, st, "attn_sweep_bwd_dst");
     if (e != HETA_OK) return e;
     e = aggregate_slot_weighted(g, r.csr, z, z_dt, ld_z, d, w_gate, K, R, HETA_F32, ld_r, 0.f, st);
     if (e != HETA_OK) return e;
@@ -564,7 +941,7 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     sp.alpha = w_alpha;
     sp.gate = w_gate;
     sp.corr = corr_s;
-    e = launch_sweeps<SWEEP_BWD_CSC>(r.csc, sp, st, "attn_sweep_bwd_src");
+    e = launch_sweeps<SWEEP_BWD_CSC>(r.csc, sp, hub_scratch, st, "attn_sweep_bwd_src");
     if (e != HETA_OK) return e;
     e = aggregate_slot_weighted(g, r.csc, grad_out, HETA_F32, ld_go, d, w_alpha, K, dz, HETA_F32, ld_dz, 0.f, st);
     if (e != HETA_OK) return e;
