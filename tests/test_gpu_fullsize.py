@@ -190,3 +190,60 @@ def test_full_size_config4_mixed_widths_sampled_rows():
         ref = M.T @ G_host[r.dst_type][np.arange(n_t)].astype(np.float64)
         assert_rows_close(dW[i].cpu().numpy(), ref, tol, f"dW[{name}]")
     layer.g.destroy()
+
+
+def test_full_size_rgat_sampled_rows_and_invariants(full_graph):
+    """The attention aggregation of every relation at full size (the launch shapes the R-GAT leg of the
+    benchmark times).  Forward rows and destination-score gradients are local to one destination, so the
+    oracle computes sampled ones from the row's own in-edges; what needs the whole graph is checked by
+    properties that hold at any size: attention weights of a row sum to one (a table of ones aggregates to
+    ones), the aggregation is self-adjoint for fixed weights (<dO, O(z)> = <dz(dO), z>), and both score
+    gradients add up the same per-edge terms (sum_v der = sum_u del per head)."""
+    from oracle import rgat
+    p, hg = full_graph
+    K, d, slope = 4, 256, 0.2
+    F = d // K
+    for i, r in enumerate(p.graph.relations):
+        n_s, n_t = p.graph.ntypes[r.src_type].num_nodes, p.graph.ntypes[r.dst_type].num_nodes
+        g = rng.stream("tests/fullsize", f"rgat/{r.name}")
+        z = rng.normal_table(n_s, d, "tests/fullsize", f"rgat-z/{r.name}")
+        el = (1.5 * g.standard_normal((n_s, K))).astype(np.float32)
+        er = (1.5 * g.standard_normal((n_t, K))).astype(np.float32)
+        go = rng.normal_table(n_t, d, "tests/fullsize", f"rgat-g/{r.name}")
+        zd, eld, erd, god = dev_table(z, "f32", 4), torch.from_numpy(el).cuda(), torch.from_numpy(er).cuda(), dev_table(go, "f32", 4)
+        out = torch.empty((n_t, d), dtype=torch.float32, device="cuda")
+        smax = torch.empty((n_t, K), dtype=torch.float32, device="cuda")
+        sinv = torch.empty_like(smax)
+        heta.heta_rel_attn_fwd(hg, i, zd, eld, erd, slope, out, smax=smax, sinv=sinv)
+        dz = torch.empty((n_s, d), dtype=torch.float32, device="cuda")
+        d_el = torch.empty((n_s, K), dtype=torch.float32, device="cuda")
+        d_er = torch.empty((n_t, K), dtype=torch.float32, device="cuda")
+        heta.heta_rel_attn_bwd(hg, i, zd, eld, erd, slope, smax, sinv, out, god, dz, d_el, d_er)
+        ones = torch.ones((n_s, d), dtype=torch.float32, device="cuda")
+        norm = torch.empty((n_t, d), dtype=torch.float32, device="cuda")
+        heta.heta_rel_attn_fwd(hg, i, ones, eld, erd, slope, norm)
+        torch.cuda.synchronize()
+        deg = np.diff(r.rowptr)
+        # properties over all rows
+        nh = norm.cpu().numpy()
+        assert np.abs(nh[deg > 0] - 1.0).max() <= 1e-5 and not nh[deg == 0].any(), r.name
+        lhs = float((god.double() * out.double()).sum())
+        rhs = float((dz.double() * zd.double()).sum())
+        scale = float((god.double().abs() * out.double().abs()).sum())
+        assert abs(lhs - rhs) <= 1e-6 * scale, (r.name, lhs, rhs)
+        s_er, s_el = d_er.double().sum(0).cpu().numpy(), d_el.double().sum(0).cpu().numpy()
+        mag = d_er.double().abs().sum(0).cpu().numpy()
+        assert np.all(np.abs(s_er - s_el) <= 1e-5 * np.maximum(mag, 1.0)), (r.name, s_er, s_el)
+        # sampled destination rows against the oracle, from the row's own in-edges
+        rows = sample_rows(deg, 12, f"rgat/{r.name}")
+        oh, dh = out.cpu().numpy(), d_er.cpu().numpy()
+        for v in rows.tolist():
+            nb = r.col[r.rowptr[v]:r.rowptr[v + 1]].astype(np.int64)
+            src_l = np.arange(nb.size)
+            ref_o, alpha = rgat.gat_aggregate_fwd(src_l, np.zeros(nb.size, dtype=np.int64), 1, z[nb], el[nb], er[v:v + 1], slope)
+            assert_rows_close(oh[v:v + 1], ref_o, 1e-4, f"{r.name} out[{v}]")
+            _, _, rder = rgat.gat_aggregate_bwd(src_l, np.zeros(nb.size, dtype=np.int64), max(nb.size, 1), 1, z[nb], el[nb],
+                                                er[v:v + 1], alpha, go[v:v + 1], slope)
+            assert_rows_close(dh[v:v + 1], rder, 1e-4, f"{r.name} der[{v}]")
+        del zd, god, out, dz, ones, norm
+    torch.cuda.empty_cache()
