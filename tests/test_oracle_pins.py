@@ -619,3 +619,106 @@ def test_rgat_finite_differences_on_the_tiny_workload():
             arr[idx] = old
             fd = (up - dn) / (2 * eps)
             assert abs(fd - grad[idx]) <= 1e-5 * max(1.0, abs(fd)), (idx, fd, grad[idx])
+
+
+# ---- neighbour sampling: pins of oracle/sampler.py ---------------------------------------------------
+
+from oracle import sampler as osampler
+
+
+def test_splitmix64_matches_the_published_outputs():
+    with open(os.path.join(GOLDEN, "splitmix64.txt")) as f:
+        want = [int(l, 16) for l in f if l.strip() and not l.startswith("#")]
+    state, got = 0, []
+    for _ in want:
+        got.append(osampler.mix(state))
+        state = (state + osampler.GAMMA) & osampler.MASK64
+    assert got == want
+
+
+def test_below_covers_the_range_evenly():
+    assert osampler.below(0, 7) == 0 and osampler.below(osampler.MASK64, 7) == 6
+    counts = np.zeros(7, dtype=np.int64)
+    prev = 0
+    for i in range(1 << 14):
+        b = osampler.below(i << 50, 7)
+        assert b >= prev
+        prev = b
+        counts[b] += 1
+    assert counts.max() - counts.min() <= 1
+
+
+@pytest.mark.parametrize("deg,k", [(5, 2), (6, 3), (4, 3), (7, 1)])
+def test_floyd_subsets_are_uniform_over_all_draws(deg, k):
+    """Feeding every possible sequence of draws (each equally likely) must produce every k-subset of the
+    slots equally often: the defining property of sampling without replacement."""
+    import itertools
+    ranges = [range(j + 1) for j in range(deg - k, deg)]
+    counts = {}
+    for draws in itertools.product(*ranges):
+        s = tuple(osampler.sample_slots(0, deg, k, 0, draw=lambda step, n: draws[step]))
+        assert len(set(s)) == k and list(s) == sorted(s) and 0 <= s[0] and s[-1] < deg
+        counts[s] = counts.get(s, 0) + 1
+    n_subsets = len(list(itertools.combinations(range(deg), k)))
+    assert len(counts) == n_subsets and len(set(counts.values())) == 1
+
+
+def test_sampled_slots_are_uniform_with_the_generator():
+    deg, k, n = 10, 3, 20000
+    hits = np.zeros(deg)
+    for v in range(n):
+        for s in osampler.sample_slots(v, deg, k, 12345):
+            hits[s] += 1
+    p = k / deg
+    sigma = np.sqrt(n * p * (1 - p))
+    assert np.all(np.abs(hits - n * p) < 4.5 * sigma), hits
+    # and a different seed gives a different draw for most destinations
+    same = sum(osampler.sample_slots(v, deg, k, 12345) == osampler.sample_slots(v, deg, k, 54321) for v in range(2000))
+    assert same < 2000 * 0.05
+
+
+def test_sample_neighbors_invariants_and_unique_relabel():
+    g = np.random.default_rng(3)
+    n_src, n_dst, E = 50, 40, 600
+    src = g.integers(0, n_src, E).astype(np.int32)
+    dst = np.sort(g.integers(0, n_dst - 3, E)).astype(np.int32)     # the last rows stay empty
+    rowptr, col = csr_from_edges(src, dst, n_dst)
+    ids = g.permutation(n_dst)[:25]
+    for fanout in (1, 5, 64):
+        ptr, out = osampler.sample_neighbors(rowptr, col, ids, fanout, 7)
+        for i, v in enumerate(ids):
+            nb = col[rowptr[v]:rowptr[v + 1]]
+            got = out[ptr[i]:ptr[i + 1]]
+            assert got.size == min(nb.size, fanout)
+            if nb.size <= fanout:
+                assert np.array_equal(got, nb)
+            else:   # a sub-multiset of the neighbourhood, in edge order: match greedily
+                j = 0
+                for x in got:
+                    while nb[j] != x:
+                        j += 1
+                    j += 1
+                assert j <= nb.size
+    lists = [g.integers(0, 30, 17), g.integers(0, 30, 0), g.integers(0, 30, 40)]
+    uniq, loc = osampler.unique_relabel(lists)
+    ref_u, ref_inv = np.unique(np.concatenate(lists), return_inverse=True)
+    assert np.array_equal(uniq, ref_u)
+    assert np.array_equal(np.concatenate(loc), ref_inv.astype(np.int32))
+
+
+def test_sample_blocks_link_up():
+    p = workloads.academic_graph(scale=0.002, workload="tests/sampler")
+    rels = [(r.src_type, r.dst_type, r.rowptr, r.col) for r in p.relations]
+    seeds = np.arange(0, p.ntypes[0].num_nodes, 7, dtype=np.int64)[:64]
+    blocks = osampler.sample_blocks(len(p.ntypes), rels, 0, seeds, [5, 3], 99)
+    assert len(blocks) == 2 and np.array_equal(blocks[1]["dst_ids"][0], seeds)
+    for t in range(len(p.ntypes)):
+        inner_src = blocks[1]["src_ids"][t]
+        outer_dst = blocks[0]["dst_ids"][t]
+        assert (outer_dst is None and inner_src.size == 0) or np.array_equal(outer_dst, inner_src)
+    for b, fanout in zip(blocks, [5, 3]):
+        for (s, t, rowptr, col), (ptr, loc) in zip(rels, b["rels"]):
+            n_dst = 0 if b["dst_ids"][t] is None else b["dst_ids"][t].size
+            assert ptr.size == n_dst + 1 and ptr[-1] == loc.size and np.all(np.diff(ptr) <= fanout)
+            if loc.size:
+                assert loc.max() < b["src_ids"][s].size
