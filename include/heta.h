@@ -273,6 +273,26 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
                               const float *sinv, const void *o, heta_dtype o_dt, int64_t ld_o, const float *grad_out,
                               int64_t ld_go, float *dz, int64_t ld_dz, float *del, float *der, void *hip_stream);
 
+/* ---- k-hop neighbour sampling into blocks (Section 2.2 and the sampling step of Algorithm 1: a fixed
+ * number of neighbours per relation is sampled, hop by hop, for the nodes of a mini-batch; fan-outs
+ * {25, 20} in Section 8.1).  Rule: all in-edges of a destination if its in-degree is at most `fanout`,
+ * else `fanout` distinct edge slots uniformly without replacement (Floyd's subset algorithm on a
+ * SplitMix64 stream keyed by (seed, destination id): the draw does not depend on the launch or on the
+ * other destinations).
+ * heta_sample_neighbors: dst_ids: device [n_dst] rows of rel's destination type (checked on the device;
+ *   repeated ids are sampled alike); rowptr: device [n_dst + 1], receives the block's row offsets;
+ *   src_ids: device, capacity n_dst * fanout, receives the sampled GLOBAL source ids, per destination in
+ *   ascending edge slot; *n_sampled (host) = rowptr[n_dst].  1 <= fanout <= 64.  Synchronous. */
+heta_status heta_sample_neighbors(const heta_graph *g, int32_t rel, const int64_t *dst_ids, int64_t n_dst, int32_t fanout,
+                                  uint64_t seed, int64_t *rowptr, int64_t *src_ids, int64_t *n_sampled, void *hip_stream);
+/* The source set of a block and the local ids of its edges: unique_ids (device, capacity sum(lens))
+ * receives the ascending distinct values of all lists, *n_unique (host) their number, and local[l]
+ * (device int32 [lens[l]]) the position of lists[l][i] in unique_ids.  lists, lens, local: HOST arrays of
+ * n_lists entries (device pointers / lengths); ids must lie in [0, id_limit), id_limit <= 2^31
+ * (checked on the device).  Synchronous. */
+heta_status heta_unique_relabel(int32_t n_lists, const int64_t *const *lists, const int64_t *lens, int64_t id_limit,
+                                int64_t *unique_ids, int64_t *n_unique, int32_t *const *local, void *hip_stream);
+
 /* ---- sparse update of a learnable feature table (Sections 2.2 and 6: the learnable vectors of
  * featureless node types and their optimizer states, Adam's moment and variance, are updated after
  * backpropagation; only the rows a mini-batch touched) ---------------------------------------------

@@ -30,7 +30,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
            "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam", "heta_project_batch",
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
-           "heta_rel_attn_fwd", "heta_rel_attn_bwd"]
+           "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel"]
 
 
 class HetaError(RuntimeError):
@@ -591,6 +591,42 @@ def heta_rel_attn_bwd(g: Graph, rel: int, z: torch.Tensor, el: torch.Tensor, er:
                                _dev(o, "o"), _dt(o), _ld(o), _dev(grad_out, "grad_out", torch.float32), _ld(grad_out),
                                _dev(dz, "dz", torch.float32), _ld(dz), _scores(d_el, "del", n_src, heads),
                                _scores(d_er, "der", n_dst, heads), _stream(stream)))
+
+
+def heta_sample_neighbors(g: Graph, rel: int, dst_ids: torch.Tensor, fanout: int, seed: int, stream=None):
+    """Samples up to `fanout` in-edges of every destination in dst_ids (device int64).  Returns
+    (rowptr [n + 1] device int64, src_ids [n_sampled] device int64 global source ids)."""
+    n = int(dst_ids.numel())
+    rowptr = torch.empty(n + 1, dtype=torch.int64, device=dst_ids.device)
+    src = torch.empty(max(1, n * fanout), dtype=torch.int64, device=dst_ids.device)
+    n_sampled = ctypes.c_int64(0)
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_sample_neighbors.argtypes = [vp, i32, vp, i64, i32, ctypes.c_uint64, vp, vp, ctypes.POINTER(i64), vp]
+    _check(L.heta_sample_neighbors(g.handle, rel, _dev(dst_ids, "dst_ids", torch.int64), n, fanout,
+                                   ctypes.c_uint64(seed & ((1 << 64) - 1)), _dev(rowptr, "rowptr"), _dev(src, "src_ids"),
+                                   ctypes.byref(n_sampled), _stream(stream)))
+    return rowptr, src[:n_sampled.value]
+
+
+def heta_unique_relabel(lists: List[torch.Tensor], id_limit: int, stream=None):
+    """Ascending unique ids over all lists (device int64) and, per list, the positions of its entries in
+    that array (device int32)."""
+    dev = lists[0].device if lists else torch.device("cuda")
+    total = sum(int(l.numel()) for l in lists)
+    uniq = torch.empty(max(1, total), dtype=torch.int64, device=dev)
+    local = [torch.empty(int(l.numel()), dtype=torch.int32, device=dev) for l in lists]
+    n_unique = ctypes.c_int64(0)
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_unique_relabel.argtypes = [i32, vp, vp, i64, vp, ctypes.POINTER(i64), vp, vp]
+    a_lists = (ctypes.c_void_p * max(1, len(lists)))(*[_dev(l, "list", torch.int64) for l in lists])
+    a_local = (ctypes.c_void_p * max(1, len(lists)))(*[_dev(l, "local") for l in local])
+    a_lens = (ctypes.c_int64 * max(1, len(lists)))(*[int(l.numel()) for l in lists])
+    _check(L.heta_unique_relabel(len(lists), ctypes.addressof(a_lists), ctypes.addressof(a_lens), int(id_limit),
+                                 _dev(uniq, "unique_ids"), ctypes.byref(n_unique), ctypes.addressof(a_local),
+                                 _stream(stream)))
+    return uniq[:n_unique.value], local
 
 
 def heta_ingest_force(mode: int) -> None:

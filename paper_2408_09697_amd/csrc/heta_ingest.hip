@@ -489,4 +489,25 @@ heta_status transpose_on_device(const Schedule &csr, int64_t n_src, Schedule &cs
     return HETA_OK;
 }
 
+// ---- the scan and the sort for other translation units (the neighbour sampler) ---------------------------
+// Both are complete (stream synchronised) when they return, because their scratch is released on return.
+heta_status device_exclusive_scan_i64(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, hipStream_t st)
+{
+    Scratch scr;
+    heta_status e = exclusive_scan<int64_t, int64_t>(in, n_in, out, n_out, scr, st);
+    if (e != HETA_OK) return e;
+    HETA_HIP(hipStreamSynchronize(st));
+    return HETA_OK;
+}
+
+heta_status device_sort_pairs_u32(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n,
+                                  int64_t key_limit, uint32_t **keys_res, uint32_t **vals_res, hipStream_t st)
+{
+    Scratch scr;
+    heta_status e = radix_sort_pairs(keys, vals, keys_tmp, vals_tmp, n, bits_for(key_limit), keys_res, vals_res, scr, st);
+    if (e != HETA_OK) return e;
+    HETA_HIP(hipStreamSynchronize(st));
+    return HETA_OK;
+}
+
 } // namespace heta

@@ -119,6 +119,13 @@ heta_status transpose_on_device(const Schedule &csr, int64_t n_src, Schedule &cs
 // everything of s beyond d_ptr / d_idx (allocated here); inv_deg (optional, [n_rows]) = 1/degree
 heta_status build_schedule_on_device(Schedule &s, float *inv_deg, hipStream_t st);
 
+// out[i] = in[0] + ... + in[i-1] for i < n_out (in[j] = 0 for j >= n_in); synchronous on st.
+heta_status device_exclusive_scan_i64(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, hipStream_t st);
+// Stable sort of n (key, value) pairs by keys in [0, key_limit); (keys, vals) and (keys_tmp, vals_tmp) are
+// ping-pong buffers, *keys_res / *vals_res point at whichever holds the result; synchronous on st.
+heta_status device_sort_pairs_u32(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n,
+                                  int64_t key_limit, uint32_t **keys_res, uint32_t **vals_res, hipStream_t st);
+
 // Makes sure g's workspace holds `bytes`; growing frees and reallocates (device synchronising).
 heta_status ensure_workspace(heta_graph *g, size_t bytes);
 // out[r] = beta out[r] + sum_e slot_w[e][head of the column] table[idx[e]] over the rows of s; slot_w is
