@@ -334,11 +334,16 @@ def measure_minibatch(args):
         compute(layers)
     torch.cuda.synchronize()
     compute_ms = (time.perf_counter() - t0) * 1e3 / max(1, args.steps)
-    t0 = time.perf_counter()
+    its = []
     for _ in range(args.steps):
+        t0 = time.perf_counter()
         for g in build():
             g.destroy()
-    ingest_ms = (time.perf_counter() - t0) * 1e3 / max(1, args.steps)
+        its.append((time.perf_counter() - t0) * 1e3)
+    # median: one iteration in a run of ten or twenty takes tens of ms inside hipFree / hipMalloc (the
+    # runtime returning memory), unrelated to the block's size; mean and maximum are reported beside it
+    ingest_ms = sorted(its)[len(its) // 2] if its else 0.0
+    ingest_mean_ms, ingest_max_ms = (sum(its) / len(its), max(its)) if its else (0.0, 0.0)
     heta.heta_profile_enable(True)
     heta.heta_profile_reset()
     for _ in range(args.steps):
@@ -349,6 +354,39 @@ def measure_minibatch(args):
     kernels = {n: {"launches_per_step": s["launches"] / args.steps, "ms_per_step": s["total_ms"] / args.steps,
                    "GBps": s["algorithmic_bytes"] / s["total_ms"] / 1e6,
                    **({"TFLOPs": s["flops"] / s["total_ms"] / 1e9} if s["flops"] > 0 else {})} for n, s in stats.items()}
+    # The step before the path: sampling the mini-batch's blocks on the device from the resident base graph
+    # (heta_sample_neighbors per relation and hop, heta_unique_relabel per source type, block handles from
+    # the device arrays).  Not part of `value`, whose blocks come from the host generator.
+    sampler = None
+    if not args.no_device_sampler:
+        for g in graphs:
+            g.destroy()
+        del layers
+        t0 = time.perf_counter()
+        base = heta.heta_graph_create([(t.num_nodes, t.feat_dim, int(t.learnable)) for t in mb.base.ntypes],
+                                      [(r.src_type, r.dst_type, r.rowptr, r.col) for r in mb.base.relations])
+        base_ingest_s = time.perf_counter() - t0
+        seeds_all = torch.from_numpy(np.sort(rng.stream("bench", "seeds").choice(
+            mb.base.ntypes[mb.seed_type].num_nodes, size=mb.G.shape[0] * (args.steps + 1), replace=False)).astype(np.int64)).cuda()
+        n_seeds = mb.G.shape[0]
+        sizes = None
+        s_its = []
+        for k in range(args.steps + 1):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            blocks = heta.sampler.sample_blocks(base, mb.seed_type, seeds_all[k * n_seeds:(k + 1) * n_seeds], [25, 15], 20240809 + k)
+            sizes = [int(sum(c.numel() for c in b.col)) for b in blocks]
+            for b in blocks:
+                b.graph.destroy()
+            torch.cuda.synchronize()
+            if k > 0:
+                s_its.append((time.perf_counter() - t0) * 1e3)
+        sampler = {"ms_per_batch": sorted(s_its)[len(s_its) // 2] if s_its else 0.0,
+                   "ms_per_batch_mean": sum(s_its) / max(1, len(s_its)), "base_graph_ingest_s": base_ingest_s,
+                   "sampled_edges_per_block_last_batch": sizes,
+                   "note": "device sampling of both hops + unique/relabel + block handles (their CSC and schedules "
+                           "included), per mini-batch of fresh seeds"}
+        base.destroy()
     ms = compute_ms + ingest_ms
     return {"metric": "aggregated edge-features/sec (fwd+bwd), 1 GPU", "value": 2.0 * edge_features / (ms * 1e-3),
             "unit": "edge-features/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
@@ -359,7 +397,9 @@ def measure_minibatch(args):
                                    + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
                        "edges": n_edges, "edge_features_per_pass": edge_features,
                        "block_sizes": [[(t.name, t.num_nodes) for t in b.graph.ntypes] for b in mb.blocks]},
-            "compute_ms": compute_ms, "ingest_ms_per_batch": ingest_ms, "input_generation_s": gen_s, "kernels": kernels}
+            "compute_ms": compute_ms, "ingest_ms_per_batch": ingest_ms, "ingest_ms_mean": ingest_mean_ms,
+            "ingest_ms_max": ingest_max_ms, "input_generation_s": gen_s, "kernels": kernels,
+            "device_sampler": sampler}
 
 
 def main() -> int:
@@ -377,6 +417,7 @@ def main() -> int:
     ap.add_argument("--scale", type=float, default=1.0, help="shrinks the graph (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event pass")
+    ap.add_argument("--no-device-sampler", action="store_true", help="config5: skip the device-sampler measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one GPU's share of the layer); "
