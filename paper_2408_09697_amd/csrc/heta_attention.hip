@@ -450,69 +450,91 @@ __global__ void __launch_bounds__(256) attn_rowdot_kernel(DotParams p)
 // lane), 64 / L rows per wavefront, every chunk loaded once; the per-head sums are segmented cross-lane
 // reductions.  Needs 4-element chunks that do not straddle heads and, per head, a power-of-two number of
 // chunks (cph); a head then lies inside one t (cph <= L) or covers whole t's (cph a multiple of L).
-template <typename TX, typename TY, int T>
+template <typename TX, typename TY, int T, int R>
 __global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int L, int cph)
 {
     const int lane = threadIdx.x & 63;
     const int G = 64 / L, g = lane / L, l = lane % L;
-    const int64_t i = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * G + g;
-    const bool live = i < p.n;
+    const int64_t first = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * R * G + g; // rows first, first + G, ...
     const int n_chunks = p.d / 4;
-    const TX *x = static_cast<const TX *>(p.x) + (live ? i : 0) * p.ld_x;
-    const TY *y = static_cast<const TY *>(p.y) + (live ? i : 0) * p.ld_y;
-    float xv[T][4];
+    float xv[R][T][4];
+    bool live[R];
+    // every load of the wavefront's R row groups is issued before the first use
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
-        const int c = l + L * t;
-        if (live && c < n_chunks) ldv<TX, 4>(x + 4 * c, xv[t]);
-        else xv[t][0] = xv[t][1] = xv[t][2] = xv[t][3] = 0.f;
-    }
-    if (p.per_head) {
-        float part[T];
+    for (int r = 0; r < R; ++r) {
+        const int64_t i = first + static_cast<int64_t>(r) * G;
+        live[r] = i < p.n;
+        const TX *x = static_cast<const TX *>(p.x) + (live[r] ? i : 0) * p.ld_x;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const int c = l + L * t;
-            float yv[4] = {0.f, 0.f, 0.f, 0.f};
-            if (live && c < n_chunks) ldv<TY, 4>(y + 4 * c, yv);
-            part[t] = xv[t][0] * yv[0] + xv[t][1] * yv[1] + xv[t][2] * yv[2] + xv[t][3] * yv[3];
+            if (live[r] && c < n_chunks) ldv<TX, 4>(x + 4 * c, xv[r][t]);
+            else xv[r][t][0] = xv[r][t][1] = xv[r][t][2] = xv[r][t][3] = 0.f;
         }
-        if (cph <= L) {
+    }
+    if (p.per_head) {
+        float part[R][T];
 #pragma unroll
-            for (int t = 0; t < T; ++t) {
-                for (int off = cph >> 1; off > 0; off >>= 1) part[t] += __shfl_xor(part[t], off, 64);
-                const int c = l + L * t;
-                if (live && c < n_chunks && (l & (cph - 1)) == 0) {
-                    const int k = c / cph;
-                    p.out[i * p.K + k] = part[t] - (p.corr ? p.corr[i * p.K + k] : 0.f);
-                }
-            }
-        } else {
-            const int m = cph / L; // t's per head
-            float acc = 0.f;
-#pragma unroll
-            for (int t = 0; t < T; ++t) {
-                acc += part[t];
-                if ((t + 1) % m == 0) {
-                    for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-                    const int k = t / m;
-                    if (live && l == 0 && k < p.K) p.out[i * p.K + k] = acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
-                    acc = 0.f;
-                }
-            }
-        }
-    } else {
-        for (int k = 0; k < p.K; ++k) {
-            const TY *yk = y + static_cast<int64_t>(k) * p.d;
-            float acc = 0.f;
+        for (int r = 0; r < R; ++r) {
+            const int64_t i = first + static_cast<int64_t>(r) * G;
+            const TY *y = static_cast<const TY *>(p.y) + (live[r] ? i : 0) * p.ld_y;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const int c = l + L * t;
                 float yv[4] = {0.f, 0.f, 0.f, 0.f};
-                if (live && c < n_chunks) ldv<TY, 4>(yk + 4 * c, yv);
-                acc += xv[t][0] * yv[0] + xv[t][1] * yv[1] + xv[t][2] * yv[2] + xv[t][3] * yv[3];
+                if (live[r] && c < n_chunks) ldv<TY, 4>(y + 4 * c, yv);
+                part[r][t] = xv[r][t][0] * yv[0] + xv[r][t][1] * yv[1] + xv[r][t][2] * yv[2] + xv[r][t][3] * yv[3];
             }
-            for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-            if (live && l == 0) p.out[i * p.K + k] = acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t i = first + static_cast<int64_t>(r) * G;
+            if (cph <= L) {
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    for (int off = cph >> 1; off > 0; off >>= 1) part[r][t] += __shfl_xor(part[r][t], off, 64);
+                    const int c = l + L * t;
+                    if (live[r] && c < n_chunks && (l & (cph - 1)) == 0) {
+                        const int k = c / cph;
+                        p.out[i * p.K + k] = part[r][t] - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                    }
+                }
+            } else {
+                const int m = cph / L; // t's per head
+                float acc = 0.f;
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    acc += part[r][t];
+                    if ((t + 1) % m == 0) {
+                        for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+                        const int k = t / m;
+                        if (live[r] && l == 0 && k < p.K) p.out[i * p.K + k] = acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                        acc = 0.f;
+                    }
+                }
+            }
+        }
+    } else {
+        // y_k = p.y + k d is shared by every row (ld_y = 0): one load per k serves the R rows
+        for (int k = 0; k < p.K; ++k) {
+            const TY *yk = static_cast<const TY *>(p.y) + static_cast<int64_t>(k) * p.d;
+            float yv[T][4];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int c = l + L * t;
+                if (c < n_chunks) ldv<TY, 4>(yk + 4 * c, yv[t]);
+                else yv[t][0] = yv[t][1] = yv[t][2] = yv[t][3] = 0.f;
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int64_t i = first + static_cast<int64_t>(r) * G;
+                float acc = 0.f;
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+                    acc += xv[r][t][0] * yv[t][0] + xv[r][t][1] * yv[t][1] + xv[r][t][2] * yv[t][2] + xv[r][t][3] * yv[t][3];
+                for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+                if (live[r] && l == 0) p.out[i * p.K + k] = acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
+            }
         }
     }
 }
@@ -537,13 +559,14 @@ heta_status launch_rowdot_t(const DotParams &p, hipStream_t st)
         const int cph = p.F / 4;
         const bool pow2 = (cph & (cph - 1)) == 0;
         if (T <= 4 && (!p.per_head || (pow2 && (cph <= L || T % (cph / L) == 0)))) {
-            const int64_t rows_per_block = 4 * (64 / L);
+            const int R = T == 1 ? 4 : (T == 2 ? 2 : 1); // row groups per wavefront, all loads in flight together
+            const int64_t rows_per_block = static_cast<int64_t>(4) * R * (64 / L);
             const dim3 grid((unsigned)((p.n + rows_per_block - 1) / rows_per_block));
             switch (T) {
-            case 1: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 1>), grid, dim3(256), 0, st, p, L, cph); break;
-            case 2: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 2>), grid, dim3(256), 0, st, p, L, cph); break;
-            case 3: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 3>), grid, dim3(256), 0, st, p, L, cph); break;
-            default: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 4>), grid, dim3(256), 0, st, p, L, cph); break;
+            case 1: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 1, 4>), grid, dim3(256), 0, st, p, L, cph); break;
+            case 2: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 2, 2>), grid, dim3(256), 0, st, p, L, cph); break;
+            case 3: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 3, 1>), grid, dim3(256), 0, st, p, L, cph); break;
+            default: hipLaunchKernelGGL((attn_rowdot_fast_kernel<TX, TY, 4, 1>), grid, dim3(256), 0, st, p, L, cph); break;
             }
         } else {
             hipLaunchKernelGGL((attn_rowdot_kernel<TX, TY, 4>), dim3((unsigned)blocks), dim3(256), 0, st, p);
@@ -660,22 +683,39 @@ __global__ void __launch_bounds__(256) attn_score_bwd_param_vec_kernel(const T *
 #pragma unroll
     for (int k = 0; k < kMaxHeads; ++k) acc[k][0] = acc[k][1] = acc[k][2] = acc[k][3] = 0.f;
     if (live) {
-#pragma unroll 4
-        for (int64_t i = i0 + rg; i < i1; i += 4) {
-            float xv[4];
-            ldv<T, 4>(x + i * ld_x + j, xv);
-            if (per_head) {
-                const float s = ds[i * K + kh];
+        constexpr int U = 8; // rows in flight per row group
+        for (int64_t ib = i0 + rg; ib < i1; ib += 4 * U) {
+            float xv[U][4], sv[U];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) acc[0][c] = fmaf(s, xv[c], acc[0][c]);
+            for (int u = 0; u < U; ++u) {
+                const int64_t i = ib + 4 * u;
+                if (i < i1) {
+                    ldv<T, 4>(x + i * ld_x + j, xv[u]);
+                    sv[u] = per_head ? ds[i * K + kh] : 0.f;
+                } else {
+                    xv[u][0] = xv[u][1] = xv[u][2] = xv[u][3] = 0.f;
+                    sv[u] = 0.f;
+                }
+            }
+            if (per_head) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[0][c] = fmaf(sv[u], xv[u][c], acc[0][c]);
             } else {
 #pragma unroll
-                for (int k = 0; k < kMaxHeads; ++k)
-                    if (k < K) {
-                        const float s = ds[i * K + k];
+                for (int u = 0; u < U; ++u) {
+                    const int64_t i = ib + 4 * u;
+                    if (i < i1) {
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) acc[k][c] = fmaf(s, xv[c], acc[k][c]);
+                        for (int k = 0; k < kMaxHeads; ++k)
+                            if (k < K) {
+                                const float sk = ds[i * K + k];
+#pragma unroll
+                                for (int c = 0; c < 4; ++c) acc[k][c] = fmaf(sk, xv[u][c], acc[k][c]);
+                            }
                     }
+                }
             }
         }
     }
@@ -698,13 +738,27 @@ __global__ void __launch_bounds__(256) attn_score_bwd_param_vec_kernel(const T *
     }
 }
 
-__global__ void __launch_bounds__(256) attn_slab_sum_kernel(const float *part, int64_t n_slabs, int64_t elems, float *out)
+// stage 2: out[t] = sum over slabs of part[slab][t].  One workgroup of 16 wavefronts per 64 elements:
+// wavefront w adds slabs w, w + 16, ... (coalesced 256-byte reads), the sixteen partial sums are added in
+// wavefront order through LDS.
+__global__ void __launch_bounds__(1024) attn_slab_sum_kernel(const float *part, int64_t n_slabs, int64_t elems, float *out)
 {
-    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (t >= elems) return;
+    __shared__ float red[16][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 64 + lane;
     float a = 0.f;
-    for (int64_t s = 0; s < n_slabs; ++s) a += part[s * elems + t];
-    out[t] = a;
+    if (t < elems) {
+#pragma unroll 4
+        for (int64_t s = w; s < n_slabs; s += 16) a += part[s * elems + t];
+    }
+    red[w][lane] = a;
+    __syncthreads();
+    if (w == 0 && t < elems) {
+        float r = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) r += red[i][lane];
+        out[t] = r;
+    }
 }
 
 heta_status ensure_attn(heta_graph *g, size_t bytes)
@@ -818,9 +872,9 @@ heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int
                                        ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
             }
             HETA_LAUNCH_CHECK("attn_score_bwd_param_kernel");
+            hipLaunchKernelGGL(attn_slab_sum_kernel, dim3((unsigned)((elems + 63) / 64)), dim3(1024), 0, st, part, n_slabs, elems, dvec);
+            HETA_LAUNCH_CHECK("attn_slab_sum_kernel");
         }
-        hipLaunchKernelGGL(attn_slab_sum_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, part, n_slabs, elems, dvec);
-        HETA_LAUNCH_CHECK("attn_slab_sum_kernel");
     }
     return HETA_OK;
 }
