@@ -256,22 +256,27 @@ heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int
                                 int64_t ld_dx, float beta, float *dvec, void *hip_stream);
 /* z: device [n_src, ld_z] of z_dt; el: device fp32 [n_src, K]; er: device fp32 [n_dst, K]; out: device
  * [n_dst, ld_out] of out_dt; smax, sinv: device fp32 [n_dst, K], receive the softmax shift and the
- * reciprocal denominator that heta_rel_attn_bwd needs (both NULL for inference).  1 <= K <= 16, K | d.
- * The per-edge weights live in g's attention workspace (grown on demand; calls on one handle must be
- * stream-ordered). */
+ * reciprocal denominator that heta_rel_attn_bwd needs (both NULL for inference).  out_pos (nullable;
+ * device [n_dst, ld_pos] of out_dt; needs beta = 0) receives the same sum restricted to the edges whose
+ * logit el + er is positive: with it the backward needs no gather on the destination side.
+ * 1 <= K <= 16, K | d.  The per-edge weights live in g's attention workspace (grown on demand; calls on
+ * one handle must be stream-ordered). */
 heta_status heta_rel_attn_fwd(heta_graph *g, int32_t rel, const void *z, heta_dtype z_dt, int64_t ld_z, int32_t d,
                               int32_t heads, const float *el, const float *er, float slope, void *out,
-                              heta_dtype out_dt, int64_t ld_out, float beta, float *smax, float *sinv,
-                              void *hip_stream);
+                              heta_dtype out_dt, int64_t ld_out, float beta, float *smax, float *sinv, void *out_pos,
+                              int64_t ld_pos, void *hip_stream);
 /* Backward of heta_rel_attn_fwd for grad_out = dL/dout (device fp32 [n_dst, ld_go]); `o` is this
- * relation's own forward output (device [n_dst, ld_o] of o_dt, computed with beta = 0).  Writes
+ * relation's own forward output and o_pos its out_pos (device [n_dst, ld_o] of o_dt, computed with
+ * beta = 0; o_pos may be NULL, at the price of one more pass over z).  Writes
  *   dz[u, kF+f] = sum_{e out of u} alpha_e[k] grad_out[v_e, kF+f]                (device fp32 [n_src, ld_dz])
  *   del[u, k], der[v, k]: the gradients of el and er through softmax and LeakyReLU (device fp32).
- * All three are overwritten.  No atomics: dz and del are gathers over the CSC, der over the CSR. */
+ * All three are overwritten.  No atomics: dz and del come from one gather over the CSC, der from row
+ * products (or, without o_pos, from a gather over the CSR). */
 heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dtype z_dt, int64_t ld_z, int32_t d,
                               int32_t heads, const float *el, const float *er, float slope, const float *smax,
-                              const float *sinv, const void *o, heta_dtype o_dt, int64_t ld_o, const float *grad_out,
-                              int64_t ld_go, float *dz, int64_t ld_dz, float *del, float *der, void *hip_stream);
+                              const float *sinv, const void *o, const void *o_pos, heta_dtype o_dt, int64_t ld_o,
+                              const float *grad_out, int64_t ld_go, float *dz, int64_t ld_dz, float *del, float *der,
+                              void *hip_stream);
 
 /* ---- k-hop neighbour sampling into blocks (Section 2.2 and the sampling step of Algorithm 1: a fixed
  * number of neighbours per relation is sampled, hop by hop, for the nodes of a mini-batch; fan-outs

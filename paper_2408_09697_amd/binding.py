@@ -556,39 +556,46 @@ def heta_attn_score_bwd(g: Graph, x: torch.Tensor, vec: torch.Tensor, per_head: 
 
 def heta_rel_attn_fwd(g: Graph, rel: int, z: torch.Tensor, el: torch.Tensor, er: torch.Tensor, slope: float,
                       out: torch.Tensor, beta: float = 0.0, smax: Optional[torch.Tensor] = None,
-                      sinv: Optional[torch.Tensor] = None, d: Optional[int] = None, stream=None) -> torch.Tensor:
+                      sinv: Optional[torch.Tensor] = None, out_pos: Optional[torch.Tensor] = None,
+                      d: Optional[int] = None, stream=None) -> torch.Tensor:
     d = z.shape[1] if d is None else d
     heads = el.shape[1]
     if z.shape[0] < g.n_src(rel) or out.shape[0] < g.n_dst(rel):
         raise HetaError(HETA_ERR_SHAPE, "z / out have fewer rows than the relation needs")
+    if out_pos is not None and (out_pos.shape[0] < g.n_dst(rel) or out_pos.dtype != out.dtype):
+        raise HetaError(HETA_ERR_SHAPE, "out_pos must match out")
     L = load_library()
     vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
-    L.heta_rel_attn_fwd.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, f32, vp, i32, i64, f32, vp, vp, vp]
+    L.heta_rel_attn_fwd.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, f32, vp, i32, i64, f32, vp, vp, vp, i64, vp]
     _check(L.heta_rel_attn_fwd(g.handle, rel, _dev(z, "z"), _dt(z), _ld(z), d, heads,
                                _scores(el, "el", g.n_src(rel), heads), _scores(er, "er", g.n_dst(rel), heads), slope,
                                _dev(out, "out"), _dt(out), _ld(out), beta,
                                None if smax is None else _scores(smax, "smax", g.n_dst(rel), heads),
-                               None if sinv is None else _scores(sinv, "sinv", g.n_dst(rel), heads), _stream(stream)))
+                               None if sinv is None else _scores(sinv, "sinv", g.n_dst(rel), heads),
+                               _dev(out_pos, "out_pos"), _ld(out_pos) if out_pos is not None else 0, _stream(stream)))
     return out
 
 
 def heta_rel_attn_bwd(g: Graph, rel: int, z: torch.Tensor, el: torch.Tensor, er: torch.Tensor, slope: float,
                       smax: torch.Tensor, sinv: torch.Tensor, o: torch.Tensor, grad_out: torch.Tensor,
-                      dz: torch.Tensor, d_el: torch.Tensor, d_er: torch.Tensor, d: Optional[int] = None,
-                      stream=None) -> None:
+                      dz: torch.Tensor, d_el: torch.Tensor, d_er: torch.Tensor, o_pos: Optional[torch.Tensor] = None,
+                      d: Optional[int] = None, stream=None) -> None:
     d = z.shape[1] if d is None else d
     heads = el.shape[1]
     n_src, n_dst = g.n_src(rel), g.n_dst(rel)
     if z.shape[0] < n_src or dz.shape[0] < n_src or o.shape[0] < n_dst or grad_out.shape[0] < n_dst:
         raise HetaError(HETA_ERR_SHAPE, "a buffer has fewer rows than the relation needs")
+    if o_pos is not None and (o_pos.shape[0] < n_dst or o_pos.dtype != o.dtype or _ld(o_pos) != _ld(o)):
+        raise HetaError(HETA_ERR_SHAPE, "o_pos must match o (rows, dtype, leading dimension)")
     L = load_library()
     vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
-    L.heta_rel_attn_bwd.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, f32, vp, vp, vp, i32, i64, vp, i64,
+    L.heta_rel_attn_bwd.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, f32, vp, vp, vp, vp, i32, i64, vp, i64,
                                     vp, i64, vp, vp, vp]
     _check(L.heta_rel_attn_bwd(g.handle, rel, _dev(z, "z"), _dt(z), _ld(z), d, heads,
                                _scores(el, "el", n_src, heads), _scores(er, "er", n_dst, heads), slope,
                                _scores(smax, "smax", n_dst, heads), _scores(sinv, "sinv", n_dst, heads),
-                               _dev(o, "o"), _dt(o), _ld(o), _dev(grad_out, "grad_out", torch.float32), _ld(grad_out),
+                               _dev(o, "o"), _dev(o_pos, "o_pos"), _dt(o), _ld(o),
+                               _dev(grad_out, "grad_out", torch.float32), _ld(grad_out),
                                _dev(dz, "dz", torch.float32), _ld(dz), _scores(d_el, "del", n_src, heads),
                                _scores(d_er, "der", n_dst, heads), _stream(stream)))
 

@@ -54,13 +54,17 @@ struct AggParams {
     const float *slot_w;   // nullable: weight per (edge position in sidx, head): [n_edges][heads]
     int heads;             // with slot_w: number of heads, columns [h*head_dim, (h+1)*head_dim) use weight h
     int head_dim;
+    const float *slot_w2;  // nullable (with slot_w only): a second weight array; the same gathered rows are
+    void *out2;            // reduced a second time with it into out2 (same type and leading dimension rules as out)
+    int64_t ld_out2;
     int mean;              // divide the row sum by the row's degree
     void *out;
     int64_t ld_out;
     int out_bf16;
     float beta;            // 0 or 1
-    float *ws;             // hub partials [slot][ws_ld]
+    float *ws;             // hub partials [slot][ws_stride]; with slot_w2 the second sum follows at +ws_ld
     int64_t ws_ld;
+    int64_t ws_stride;
     int d;
     int64_t n_hub_chunks, n_hub_rows;
     int64_t n_wave_items;  // hub chunks + long rows
@@ -139,13 +143,14 @@ template <> struct Chunk<bf16_t, 1> {
 // Whole chunks on 16-byte aligned rows go out as 128-bit stores (fp32: one per 4 elements; bf16:
 // one per 8 elements, or a 64-bit store for a 4-element chunk).
 template <int EPC>
-__device__ __forceinline__ void store_out(const AggParams &p, int64_t row, int col0, const float *acc, float scale)
+__device__ __forceinline__ void store_out(const AggParams &p, void *out, int64_t ld_out, int64_t row, int col0,
+                                          const float *acc, float scale)
 {
     const bool whole = col0 + EPC <= p.d;
     if (p.out_bf16) {
-        bf16_t *o = static_cast<bf16_t *>(p.out) + row * p.ld_out + col0;
+        bf16_t *o = static_cast<bf16_t *>(out) + row * ld_out + col0;
         if constexpr (EPC % 4 == 0) {
-            if (whole && ((p.ld_out & 7) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15u) == 0)) {
+            if (whole && ((ld_out & 7) == 0) && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
                 float v[EPC];
 #pragma unroll
                 for (int i = 0; i < EPC; ++i) v[i] = acc[i] * scale;
@@ -170,9 +175,9 @@ __device__ __forceinline__ void store_out(const AggParams &p, int64_t row, int c
                 o[i] = f32_to_bf16(v);
             }
     } else {
-        float *o = static_cast<float *>(p.out) + row * p.ld_out + col0;
+        float *o = static_cast<float *>(out) + row * ld_out + col0;
         if constexpr (EPC % 4 == 0) {
-            if (whole && ((p.ld_out & 3) == 0) && ((reinterpret_cast<uintptr_t>(p.out) & 15u) == 0)) {
+            if (whole && ((ld_out & 3) == 0) && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
 #pragma unroll
                 for (int q = 0; q < EPC / 4; ++q) {
                     float4 v = make_float4(acc[4 * q] * scale, acc[4 * q + 1] * scale, acc[4 * q + 2] * scale, acc[4 * q + 3] * scale);
@@ -195,6 +200,12 @@ __device__ __forceinline__ void store_out(const AggParams &p, int64_t row, int c
     }
 }
 
+template <int EPC>
+__device__ __forceinline__ void store_out(const AggParams &p, int64_t row, int col0, const float *acc, float scale)
+{
+    store_out<EPC>(p, p.out, p.ld_out, row, col0, acc, scale);
+}
+
 __device__ __forceinline__ float row_scale(const AggParams &p, int64_t deg)
 {
     if (!p.mean) return 1.f;
@@ -213,7 +224,7 @@ __host__ __device__ inline int batch_rows(int k, int G)
     return r < 64 ? r : 64;
 }
 
-template <typename T, int EPC, int L, int CPL>
+template <typename T, int EPC, int L, int CPL, bool DUAL>
 __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
 {
     constexpr int G = 64 / L;          // lane groups = rows in progress per wavefront
@@ -263,7 +274,10 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) {
                     const int ch = ch0 + c * L;
-                    if (ch < n_chunks) store_out<EPC>(p, row_s[wave][r], ch * EPC, zero, 0.f);
+                    if (ch < n_chunks) {
+                        store_out<EPC>(p, row_s[wave][r], ch * EPC, zero, 0.f);
+                        if (DUAL) store_out<EPC>(p, p.out2, p.ld_out2, row_s[wave][r], ch * EPC, zero, 0.f);
+                    }
                 }
         }
         return;
@@ -273,11 +287,14 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
     int head[CPL]; // head of each of this lane's chunks (per-head edge weights)
 #pragma unroll
     for (int c = 0; c < CPL; ++c) head[c] = p.slot_w ? min((ch0 + c * L) * EPC / p.head_dim, p.heads - 1) : 0;
-    float acc[CPL][EPC];
+    float acc[CPL][EPC], acc2[DUAL ? CPL : 1][EPC];
 #pragma unroll
     for (int c = 0; c < CPL; ++c)
 #pragma unroll
-        for (int i = 0; i < EPC; ++i) acc[c][i] = 0.f;
+        for (int i = 0; i < EPC; ++i) {
+            acc[c][i] = 0.f;
+            if (DUAL) acc2[c][i] = 0.f;
+        }
     // Lane group g walks the slots (row g + G*rl, edge j) of its rows in order; rl and j are the same
     // for every group, so the slot bookkeeping is scalar.
     const int rounds = (nrows + G - 1) / G;
@@ -285,7 +302,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
     const int total = rounds * k;
     for (int s0 = 0; s0 < total; s0 += U) {
         Chunk<T, EPC> v[U][CPL];
-        float ww[U][CPL];
+        float ww[U][CPL], ww2[DUAL ? U : 1][CPL];
         int rl_u = rl, j_u = j;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -301,8 +318,10 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
                 if (ok && ch < n_chunks) {
                     v[u][c].load(rp + static_cast<int64_t>(ch) * EPC);
                     if (p.slot_w) ww[u][c] = p.slot_w[(e0 + i) * p.heads + head[c]];
+                    if (DUAL) ww2[u][c] = p.slot_w2[(e0 + i) * p.heads + head[c]];
                 } else {
                     v[u][c].zero();
+                    if (DUAL) ww2[u][c] = 0.f;
                 }
             }
             if (++j_u == k) {
@@ -317,6 +336,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
                 for (int c = 0; c < CPL; ++c) {
                     if (weighted) v[u][c].add_to(acc[c], ww[u][c]);
                     else v[u][c].add_to(acc[c]);
+                    if (DUAL) v[u][c].add_to(acc2[c], ww2[u][c]);
                 }
                 if (++j == k) { // last edge of the row: store it, start the next
                     const int r = g + rl * G;
@@ -325,13 +345,19 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
 #pragma unroll
                         for (int c = 0; c < CPL; ++c) {
                             const int ch = ch0 + c * L;
-                            if (ch < n_chunks) store_out<EPC>(p, row, ch * EPC, acc[c], scale);
+                            if (ch < n_chunks) {
+                                store_out<EPC>(p, row, ch * EPC, acc[c], scale);
+                                if (DUAL) store_out<EPC>(p, p.out2, p.ld_out2, row, ch * EPC, acc2[c], scale);
+                            }
                         }
                     }
 #pragma unroll
                     for (int c = 0; c < CPL; ++c)
 #pragma unroll
-                        for (int i = 0; i < EPC; ++i) acc[c][i] = 0.f;
+                        for (int i = 0; i < EPC; ++i) {
+                            acc[c][i] = 0.f;
+                            if (DUAL) acc2[c][i] = 0.f;
+                        }
                     j = 0;
                     ++rl;
                 }
@@ -341,7 +367,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
 }
 
 // ---- long rows and hub chunks: one wavefront per item ----------------------------------------------
-template <typename T, int EPC, int L, int CPL>
+template <typename T, int EPC, int L, int CPL, bool DUAL>
 __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
 {
     constexpr int G = 64 / L;            // lane groups per wavefront
@@ -370,11 +396,14 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
     int head[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) head[c] = p.slot_w ? min((ch0 + c * L) * EPC / p.head_dim, p.heads - 1) : 0;
-    float acc[CPL][EPC];
+    float acc[CPL][EPC], acc2[DUAL ? CPL : 1][EPC];
 #pragma unroll
     for (int c = 0; c < CPL; ++c)
 #pragma unroll
-        for (int i = 0; i < EPC; ++i) acc[c][i] = 0.f;
+        for (int i = 0; i < EPC; ++i) {
+            acc[c][i] = 0.f;
+            if (DUAL) acc2[c][i] = 0.f;
+        }
 
     for (int64_t base = e0; base < e1; base += 64) {
         const int cnt = static_cast<int>(min(static_cast<int64_t>(64), e1 - base));
@@ -387,7 +416,7 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
         }
         for (int j = 0; j < cnt; j += G * U) {
             Chunk<T, EPC> v[U][CPL];
-            float ww[U][CPL];
+            float ww[U][CPL], ww2[DUAL ? U : 1][CPL];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int k = j + u * G + g;
@@ -402,8 +431,10 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
                     if (ok && ch < n_chunks) {
                         v[u][c].load(rp + static_cast<int64_t>(ch) * EPC);
                         if (p.slot_w) ww[u][c] = p.slot_w[(base + k) * p.heads + head[c]];
+                        if (DUAL) ww2[u][c] = p.slot_w2[(base + k) * p.heads + head[c]];
                     } else {
                         v[u][c].zero();
+                        if (DUAL) ww2[u][c] = 0.f;
                     }
                 }
             }
@@ -413,6 +444,7 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
                 for (int c = 0; c < CPL; ++c) {
                     if (weighted) v[u][c].add_to(acc[c], ww[u][c]);
                     else v[u][c].add_to(acc[c]);
+                    if (DUAL) v[u][c].add_to(acc2[c], ww2[u][c]);
                 }
         }
     }
@@ -422,16 +454,22 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
 #pragma unroll
         for (int c = 0; c < CPL; ++c)
 #pragma unroll
-            for (int i = 0; i < EPC; ++i) acc[c][i] += __shfl_xor(acc[c][i], off, 64);
+            for (int i = 0; i < EPC; ++i) {
+                acc[c][i] += __shfl_xor(acc[c][i], off, 64);
+                if (DUAL) acc2[c][i] += __shfl_xor(acc2[c][i], off, 64);
+            }
     if (g != 0) return;
     if (slot >= 0) {
-        float *o = p.ws + static_cast<int64_t>(slot) * p.ws_ld;
+        float *o = p.ws + static_cast<int64_t>(slot) * p.ws_stride;
 #pragma unroll
         for (int c = 0; c < CPL; ++c) {
             const int ch = ch0 + c * L;
             if (ch < n_chunks) {
 #pragma unroll
-                for (int i = 0; i < EPC; ++i) o[ch * EPC + i] = acc[c][i];
+                for (int i = 0; i < EPC; ++i) {
+                    o[ch * EPC + i] = acc[c][i];
+                    if (DUAL) o[p.ws_ld + ch * EPC + i] = acc2[c][i];
+                }
             }
         }
     } else {
@@ -439,7 +477,10 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
 #pragma unroll
         for (int c = 0; c < CPL; ++c) {
             const int ch = ch0 + c * L;
-            if (ch < n_chunks) store_out<EPC>(p, row, ch * EPC, acc[c], scale);
+            if (ch < n_chunks) {
+                store_out<EPC>(p, row, ch * EPC, acc[c], scale);
+                if (DUAL) store_out<EPC>(p, p.out2, p.ld_out2, row, ch * EPC, acc2[c], scale);
+            }
         }
     }
 }
@@ -464,7 +505,7 @@ __global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_kernel(Agg
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int64_t t = s + kCombineWaves * u;
-                if (t < s1) v[u] = *reinterpret_cast<const float4 *>(p.ws + t * p.ws_ld + col0);
+                if (t < s1) v[u] = *reinterpret_cast<const float4 *>(p.ws + t * p.ws_stride + col0);
                 else v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
 #pragma unroll
@@ -490,20 +531,23 @@ struct AggCost {
     double wave_bytes = 0, group_bytes = 0;
 };
 
-template <typename T, int EPC, int L, int CPL>
+template <typename T, int EPC, int L, int CPL, bool DUAL = false>
 static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st, const AggCost &cost)
 {
+    if constexpr (!DUAL && EPC > 1) { // the two-weight form exists for the 128-bit paths
+        if (p.slot_w2) return launch_pair<T, EPC, L, CPL, true>(p, n_super, st, cost);
+    }
     if (p.n_wave_items > 0) {
         const int64_t blocks = (p.n_wave_items + 3) / 4;
         if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many long rows");
         ProfScope prof("agg_wave_kernel", st, cost.wave_bytes, 0);
-        hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
         HETA_LAUNCH_CHECK("agg_wave_kernel");
     }
     const int n_batches = p.batch0[kShortDeg];
     if (n_batches > 0) {
         ProfScope prof("agg_batch_kernel", st, cost.group_bytes, 0);
-        hipLaunchKernelGGL((agg_batch_kernel<T, EPC, L, CPL>), dim3((unsigned)((n_batches + 3) / 4), n_super), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((agg_batch_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)((n_batches + 3) / 4), n_super), dim3(256), 0, st, p);
         HETA_LAUNCH_CHECK("agg_batch_kernel");
     }
     return HETA_OK;
@@ -532,6 +576,17 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     // with per-head weights a lane's chunk must not straddle two heads
     const bool vec = aligned16(p.table) && ((p.ld * esz) % 16 == 0) &&
                      (!p.slot_w || p.head_dim % static_cast<int>(16 / esz) == 0);
+    if (p.slot_w2 && !vec) { // the two-weight kernels exist for the 128-bit paths only: two passes otherwise
+        AggParams a = p, b = p;
+        a.slot_w2 = nullptr;
+        b.slot_w = p.slot_w2;
+        b.slot_w2 = nullptr;
+        b.out = p.out2;
+        b.ld_out = p.ld_out2;
+        heta_status e1 = run_aggregate(g, s, a, in_dt, table_elems_ld, st);
+        return e1 != HETA_OK ? e1 : run_aggregate(g, s, b, in_dt, table_elems_ld, st);
+    }
+    const bool dual = p.slot_w2 != nullptr;
     const int epc = vec ? static_cast<int>(16 / esz) : 1;
     const int n_chunks = (p.d + epc - 1) / epc;
     int L = 64; // lanes per row, as the dispatch below picks them
@@ -566,9 +621,10 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     p.batch0[kShortDeg] = static_cast<int32_t>(batches);
     p.row0[kShortDeg] = static_cast<int32_t>(s.n_rows);
     p.ws_ld = (static_cast<int64_t>(p.d) + 7) / 8 * 8;
+    p.ws_stride = dual ? 2 * p.ws_ld : p.ws_ld;
     p.ws = nullptr;
     if (s.n_hub_chunks > 0) {
-        heta_status e = ensure_workspace(g, static_cast<size_t>(s.n_hub_chunks) * p.ws_ld * sizeof(float));
+        heta_status e = ensure_workspace(g, static_cast<size_t>(s.n_hub_chunks) * p.ws_stride * sizeof(float));
         if (e != HETA_OK) return e;
         p.ws = static_cast<float *>(g->d_ws);
     }
@@ -576,7 +632,8 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     // row pointer and one output row per row.  Hub rows' outputs are written by the combine kernel.
     AggCost cost;
     const double osz = p.out_bf16 ? 2.0 : 4.0;
-    const double per_edge = static_cast<double>(p.d) * esz + 4.0 + (p.slot_w ? 4.0 * p.heads : 0.0), per_row = 8.0 + p.d * osz;
+    const double per_edge = static_cast<double>(p.d) * esz + 4.0 + (p.slot_w ? 4.0 * p.heads : 0.0) + (dual ? 4.0 * p.heads : 0.0);
+    const double per_row = 8.0 + p.d * osz * (dual ? 2.0 : 1.0);
     const double e_wave = static_cast<double>(s.edges_with_deg_ge[wave_min]);
     const double r_long = static_cast<double>(n_long_or_hub - s.n_hub_rows);
     cost.wave_bytes = e_wave * per_edge + r_long * per_row;
@@ -594,6 +651,14 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
         ProfScope prof("agg_hub_combine_kernel", st, static_cast<double>(s.n_hub_rows) * per_row, 0);
         hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, p);
         HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
+        if (dual) {
+            AggParams p2 = p;
+            p2.ws = p.ws + p.ws_ld;
+            p2.out = p.out2;
+            p2.ld_out = p.ld_out2;
+            hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, p2);
+            HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
+        }
     }
     return HETA_OK;
 }
@@ -602,12 +667,16 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
 // attention aggregation (heta_attention.hip computes the weights).
 heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld,
                                     int d, const float *slot_w, int heads, void *out, heta_dtype out_dt,
-                                    int64_t ld_out, float beta, hipStream_t st)
+                                    int64_t ld_out, float beta, hipStream_t st, const float *slot_w2, void *out2,
+                                    int64_t ld_out2)
 {
     AggParams p{};
     p.table = table;
     p.ld = ld;
     p.slot_w = slot_w;
+    p.slot_w2 = slot_w2;
+    p.out2 = out2;
+    p.ld_out2 = ld_out2;
     p.heads = heads;
     p.head_dim = d / heads;
     p.out = out;

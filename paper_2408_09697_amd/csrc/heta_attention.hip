@@ -61,7 +61,9 @@ struct SweepParams {
     float *smax, *sinv;   // [dst][K]   softmax shift and 1/denominator: written by FWD (nullable), read by the others
     const float *dot;     // [dst][K]   <g, o> per head (backward)
     float *alpha;         // [E][K] by edge slot (FWD, BWD_CSC)
-    float *gate;          // [E][K] by edge slot (BWD_*)
+    float *gate;          // [E][K] by edge slot: alpha * LeakyReLU' (BWD_SRC; BWD_DST if non-null), or alpha on the
+                          // edges with a positive logit (FWD, if non-null)
+    float dot_shift;      // BWD_CSR: corr = dot * (sum of gates - dot_shift)
     float *corr;          // [rows][K]  the scalar term subtracted from the row's score gradient (BWD_*)
     float *part;          // hub chunks: [n_hub_chunks][K][2] partial statistics
     float *hub_stat;      // hub rows (FWD): [n_hub_rows][K][2] = shift, 1/denominator
@@ -113,6 +115,7 @@ __device__ __forceinline__ void visit(const SweepParams &p, int64_t e, int k0, c
             acc[k] += expf(sc - m[k]);
         } else if (PH == PH_ALPHA) {
             a[k] = expf(sc - m[k]) * inv[k];
+            gt[k] = x[k] > 0.f ? a[k] : 0.f; // the weight restricted to edges with a positive logit
         } else if (PH == PH_BWD_DST) {
             gt[k] = expf(sc - m[k]) * inv[k] * (x[k] > 0.f ? 1.f : p.slope);
             acc[k] += gt[k];
@@ -123,7 +126,7 @@ __device__ __forceinline__ void visit(const SweepParams &p, int64_t e, int k0, c
         }
     }
     if (PH == PH_ALPHA || PH == PH_BWD_SRC) storek<KT>(p.alpha + e * p.K + k0, a);
-    if (PH == PH_BWD_DST || PH == PH_BWD_SRC) storek<KT>(p.gate + e * p.K + k0, gt);
+    if (PH == PH_BWD_SRC || ((PH == PH_ALPHA || PH == PH_BWD_DST) && p.gate)) storek<KT>(p.gate + e * p.K + k0, gt);
 }
 
 template <int W, int KT, int PH>
@@ -198,7 +201,7 @@ __global__ void __launch_bounds__(256) attn_rows_kernel(SweepParams p)
                 float d[KT];
                 loadk<KT>(p.dot + row * p.K + k0, d);
 #pragma unroll
-                for (int k = 0; k < KT; ++k) acc[k] *= d[k];
+                for (int k = 0; k < KT; ++k) acc[k] = (acc[k] - p.dot_shift) * d[k];
             }
             storek<KT>(p.corr + row * p.K + k0, acc);
         }
@@ -295,7 +298,7 @@ __global__ void __launch_bounds__(256) attn_hub_combine_kernel(SweepParams p)
         float a = 0.f;
         for (int64_t s = s0 + lane; s < s1; s += 64) a += p.part[(s * p.K + k) * 2];
         wave_sum<1>(&a);
-        if (lane == 0) p.corr[row * p.K + k] = OP == SWEEP_BWD_CSR ? a * p.dot[row * p.K + k] : a;
+        if (lane == 0) p.corr[row * p.K + k] = OP == SWEEP_BWD_CSR ? (a - p.dot_shift) * p.dot[row * p.K + k] : a;
     }
 }
 
@@ -396,6 +399,7 @@ struct DotParams {
     int64_t ld_y;
     int64_t n;
     int d, K, F, per_head;
+    float scale;          // out = scale * <x, y> - corr
     const float *corr;
     float *out;
 };
@@ -443,7 +447,7 @@ __global__ void __launch_bounds__(256) attn_rowdot_kernel(DotParams p)
         for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
         if (lane == k) res = part;
     }
-    if (lane < p.K) p.out[i * p.K + lane] = res - (p.corr ? p.corr[i * p.K + lane] : 0.f);
+    if (lane < p.K) p.out[i * p.K + lane] = p.scale * res - (p.corr ? p.corr[i * p.K + lane] : 0.f);
 }
 
 // Fast path: a row's 16-byte chunks are spread over a group of L lanes (L a power of two, T chunks per
@@ -496,7 +500,7 @@ __global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int 
                     const int c = l + L * t;
                     if (live[r] && c < n_chunks && (l & (cph - 1)) == 0) {
                         const int k = c / cph;
-                        p.out[i * p.K + k] = part[r][t] - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                        p.out[i * p.K + k] = p.scale * part[r][t] - (p.corr ? p.corr[i * p.K + k] : 0.f);
                     }
                 }
             } else {
@@ -508,7 +512,7 @@ __global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int 
                     if ((t + 1) % m == 0) {
                         for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
                         const int k = t / m;
-                        if (live[r] && l == 0 && k < p.K) p.out[i * p.K + k] = acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                        if (live[r] && l == 0 && k < p.K) p.out[i * p.K + k] = p.scale * acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
                         acc = 0.f;
                     }
                 }
@@ -533,7 +537,7 @@ __global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int 
                 for (int t = 0; t < T; ++t)
                     acc += xv[r][t][0] * yv[t][0] + xv[r][t][1] * yv[t][1] + xv[r][t][2] * yv[t][2] + xv[r][t][3] * yv[t][3];
                 for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-                if (live[r] && l == 0) p.out[i * p.K + k] = acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                if (live[r] && l == 0) p.out[i * p.K + k] = p.scale * acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
             }
         }
     }
@@ -763,6 +767,7 @@ __global__ void __launch_bounds__(1024) attn_slab_sum_kernel(const float *part, 
 
 heta_status ensure_attn(heta_graph *g, size_t bytes)
 {
+    bytes = std::max<size_t>(bytes, 256); // never hand out a null workspace (relations without edges)
     if (bytes <= g->attn_bytes) return HETA_OK;
     if (g->d_attn) HETA_HIP(hipFree(g->d_attn)); // waits for earlier users
     g->d_attn = nullptr;
@@ -811,6 +816,7 @@ heta_status heta_attn_score(const void *x, heta_dtype dt, int64_t ld_x, int64_t 
     p.K = heads;
     p.F = per_head ? d / heads : d;
     p.per_head = per_head ? 1 : 0;
+    p.scale = 1.f;
     p.corr = nullptr;
     p.out = score;
     return launch_rowdot(p, dt, HETA_F32, as_stream(hip_stream));
@@ -881,24 +887,29 @@ heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int
 
 heta_status heta_rel_attn_fwd(heta_graph *g, int32_t rel, const void *z, heta_dtype z_dt, int64_t ld_z, int32_t d,
                               int32_t heads, const float *el, const float *er, float slope, void *out,
-                              heta_dtype out_dt, int64_t ld_out, float beta, float *smax, float *sinv, void *hip_stream)
+                              heta_dtype out_dt, int64_t ld_out, float beta, float *smax, float *sinv, void *out_pos,
+                              int64_t ld_pos, void *hip_stream)
 {
     heta_status e = check_attn_args("heta_rel_attn_fwd", g, rel, d, heads);
     if (e != HETA_OK) return e;
     if (!z || !el || !er || !out || ((smax == nullptr) != (sinv == nullptr)))
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_attn_fwd: null argument (smax and sinv go together)");
     if (!valid_dtype(z_dt) || !valid_dtype(out_dt)) return fail(HETA_ERR_INVALID_ARG, "heta_rel_attn_fwd: bad dtype");
-    if (ld_z < d || ld_out < d) return fail(HETA_ERR_SHAPE, "heta_rel_attn_fwd: need d <= ld");
+    if (ld_z < d || ld_out < d || (out_pos && ld_pos < d)) return fail(HETA_ERR_SHAPE, "heta_rel_attn_fwd: need d <= ld");
     if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "heta_rel_attn_fwd: beta must be 0 or 1");
-    if (reinterpret_cast<uintptr_t>(z) % dtype_size(z_dt) || reinterpret_cast<uintptr_t>(out) % dtype_size(out_dt))
+    if (out_pos && beta != 0.f) return fail(HETA_ERR_SHAPE, "heta_rel_attn_fwd: out_pos needs beta = 0");
+    if (reinterpret_cast<uintptr_t>(z) % dtype_size(z_dt) || reinterpret_cast<uintptr_t>(out) % dtype_size(out_dt) ||
+        reinterpret_cast<uintptr_t>(out_pos) % dtype_size(out_dt))
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_attn_fwd: pointer not aligned to its element size");
     const Relation &r = g->rels[rel];
     hipStream_t st = as_stream(hip_stream);
-    const size_t a_bytes = round256(static_cast<size_t>(r.n_edges) * heads * sizeof(float));
-    e = ensure_attn(g, a_bytes + hub_scratch_bytes(r.csr, heads));
+    const size_t a_bytes = std::max<size_t>(256, round256(static_cast<size_t>(r.n_edges) * heads * sizeof(float)));
+    e = ensure_attn(g, (out_pos ? 2 : 1) * a_bytes + hub_scratch_bytes(r.csr, heads));
     if (e != HETA_OK) return e;
-    float *alpha = static_cast<float *>(g->d_attn);
-    float *hub_scratch = reinterpret_cast<float *>(static_cast<char *>(g->d_attn) + a_bytes);
+    char *base = static_cast<char *>(g->d_attn);
+    float *alpha = reinterpret_cast<float *>(base);
+    float *alpha_pos = out_pos ? reinterpret_cast<float *>(base + a_bytes) : nullptr;
+    float *hub_scratch = reinterpret_cast<float *>(base + (out_pos ? 2 : 1) * a_bytes);
     SweepParams sp{};
     sp.K = heads;
     sp.slope = slope;
@@ -907,15 +918,18 @@ heta_status heta_rel_attn_fwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     sp.smax = smax;
     sp.sinv = sinv;
     sp.alpha = alpha;
+    sp.gate = alpha_pos;
     e = launch_sweeps<SWEEP_FWD>(r.csr, sp, hub_scratch, st, "attn_sweep_fwd");
     if (e != HETA_OK) return e;
-    return aggregate_slot_weighted(g, r.csr, z, z_dt, ld_z, d, alpha, heads, out, out_dt, ld_out, beta, st);
+    return aggregate_slot_weighted(g, r.csr, z, z_dt, ld_z, d, alpha, heads, out, out_dt, ld_out, beta, st, alpha_pos, out_pos,
+                                   ld_pos);
 }
 
 heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dtype z_dt, int64_t ld_z, int32_t d,
                               int32_t heads, const float *el, const float *er, float slope, const float *smax,
-                              const float *sinv, const void *o, heta_dtype o_dt, int64_t ld_o, const float *grad_out,
-                              int64_t ld_go, float *dz, int64_t ld_dz, float *del, float *der, void *hip_stream)
+                              const float *sinv, const void *o, const void *o_pos, heta_dtype o_dt, int64_t ld_o,
+                              const float *grad_out, int64_t ld_go, float *dz, int64_t ld_dz, float *del, float *der,
+                              void *hip_stream)
 {
     heta_status e = check_attn_args("heta_rel_attn_bwd", g, rel, d, heads);
     if (e != HETA_OK) return e;
@@ -924,17 +938,18 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     if (!valid_dtype(z_dt) || !valid_dtype(o_dt)) return fail(HETA_ERR_INVALID_ARG, "heta_rel_attn_bwd: bad dtype");
     if (ld_z < d || ld_o < d || ld_go < d || ld_dz < d) return fail(HETA_ERR_SHAPE, "heta_rel_attn_bwd: need d <= ld");
     if (reinterpret_cast<uintptr_t>(z) % dtype_size(z_dt) || reinterpret_cast<uintptr_t>(o) % dtype_size(o_dt) ||
-        reinterpret_cast<uintptr_t>(grad_out) % 4 || reinterpret_cast<uintptr_t>(dz) % 4)
+        reinterpret_cast<uintptr_t>(o_pos) % dtype_size(o_dt) || reinterpret_cast<uintptr_t>(grad_out) % 4 ||
+        reinterpret_cast<uintptr_t>(dz) % 4)
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_attn_bwd: pointer not aligned to its element size");
     const Relation &r = g->rels[rel];
     hipStream_t st = as_stream(hip_stream);
     const int K = heads;
     // workspace: two per-slot weight arrays, per-row terms, and one [max rows x d] fp32 intermediate
-    const size_t w_bytes = round256(static_cast<size_t>(r.n_edges) * K * sizeof(float));
+    const size_t w_bytes = std::max<size_t>(256, round256(static_cast<size_t>(r.n_edges) * K * sizeof(float)));
     const size_t dst_bytes = round256(static_cast<size_t>(r.n_dst) * K * sizeof(float));
     const size_t src_bytes = round256(static_cast<size_t>(r.n_src) * K * sizeof(float));
     const int64_t ld_r = (static_cast<int64_t>(d) + 3) / 4 * 4;
-    const size_t r_bytes = round256(static_cast<size_t>(std::max(r.n_dst, r.n_src)) * ld_r * sizeof(float));
+    const size_t r_bytes = round256(static_cast<size_t>(o_pos ? r.n_src : std::max(r.n_dst, r.n_src)) * ld_r * sizeof(float));
     const size_t hub_bytes = round256(std::max(hub_scratch_bytes(r.csr, K), hub_scratch_bytes(r.csc, K)));
     e = ensure_attn(g, 2 * w_bytes + 2 * dst_bytes + src_bytes + r_bytes + hub_bytes);
     if (e != HETA_OK) return e;
@@ -958,12 +973,13 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     dp.K = K;
     dp.F = d / K;
     dp.per_head = 1;
+    dp.scale = 1.f;
     dp.corr = nullptr;
     dp.out = dot;
     e = launch_rowdot(dp, HETA_F32, o_dt, st);
     if (e != HETA_OK) return e;
 
-    // destination side: gate per CSR slot, R[v] = sum_e gate_e z[u_e], der = <g, R> - dot * sum_e gate_e
+    // Destination side: der = sum_e gate_e <g, z[u_e]> - dot * sum_e gate_e, gate_e = alpha_e * LeakyReLU'.
     SweepParams sp{};
     sp.K = K;
     sp.slope = slope;
@@ -972,24 +988,40 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     sp.smax = const_cast<float *>(smax);
     sp.sinv = const_cast<float *>(sinv);
     sp.dot = dot;
-    sp.gate = w_gate;
     sp.corr = corr_d;
-    e = launch_sweeps<SWEEP_BWD_CSR>(r.csr, sp, hub_scratch, st, "attn_sweep_bwd_dst");
-    if (e != HETA_OK) return e;
-    e = aggregate_slot_weighted(g, r.csr, z, z_dt, ld_z, d, w_gate, K, R, HETA_F32, ld_r, 0.f, st);
-    if (e != HETA_OK) return e;
-    dp.x = grad_out;
-    dp.ld_x = ld_go;
-    dp.y = R;
-    dp.ld_y = ld_r;
-    dp.n = r.n_dst;
-    dp.corr = corr_d;
-    dp.out = der;
-    e = launch_rowdot(dp, HETA_F32, HETA_F32, st);
-    if (e != HETA_OK) return e;
+    if (o_pos) {
+        // gate_e = alpha_e (slope + (1 - slope) [logit_e > 0]), so with o_pos = sum over positive-logit edges of
+        // alpha_e z[u_e] (saved by the forward): sum_e gate_e <g, z[u_e]> = slope * dot + (1 - slope) <g, o_pos>,
+        // and no feature row is gathered on this side.
+        sp.gate = nullptr;
+        sp.dot_shift = slope;
+        e = launch_sweeps<SWEEP_BWD_CSR>(r.csr, sp, hub_scratch, st, "attn_sweep_bwd_dst");
+        if (e != HETA_OK) return e;
+        dp.y = o_pos;
+        dp.ld_y = ld_o;
+        dp.scale = 1.f - slope;
+        dp.corr = corr_d;
+        dp.out = der;
+        e = launch_rowdot(dp, HETA_F32, o_dt, st);
+        if (e != HETA_OK) return e;
+    } else {
+        // without it: R[v] = sum_e gate_e z[u_e] by one more weighted aggregation over the CSR
+        sp.gate = w_gate;
+        sp.dot_shift = 0.f;
+        e = launch_sweeps<SWEEP_BWD_CSR>(r.csr, sp, hub_scratch, st, "attn_sweep_bwd_dst");
+        if (e != HETA_OK) return e;
+        e = aggregate_slot_weighted(g, r.csr, z, z_dt, ld_z, d, w_gate, K, R, HETA_F32, ld_r, 0.f, st);
+        if (e != HETA_OK) return e;
+        dp.y = R;
+        dp.ld_y = ld_r;
+        dp.corr = corr_d;
+        dp.out = der;
+        e = launch_rowdot(dp, HETA_F32, HETA_F32, st);
+        if (e != HETA_OK) return e;
+    }
 
-    // source side: alpha and gate per CSC slot; dz[u] = sum_e alpha_e g[v_e]; R[u] = sum_e gate_e g[v_e];
-    // del = <z, R> - sum_e gate_e dot[v_e]
+    // Source side: alpha and gate per CSC slot; one pass over the gathered gradient rows gives both
+    // dz[u] = sum_e alpha_e g[v_e] and R[u] = sum_e gate_e g[v_e]; del = <z, R> - sum_e gate_e dot[v_e].
     sp.row_a = el;
     sp.nbr_a = er;
     sp.alpha = w_alpha;
@@ -997,15 +1029,14 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     sp.corr = corr_s;
     e = launch_sweeps<SWEEP_BWD_CSC>(r.csc, sp, hub_scratch, st, "attn_sweep_bwd_src");
     if (e != HETA_OK) return e;
-    e = aggregate_slot_weighted(g, r.csc, grad_out, HETA_F32, ld_go, d, w_alpha, K, dz, HETA_F32, ld_dz, 0.f, st);
-    if (e != HETA_OK) return e;
-    e = aggregate_slot_weighted(g, r.csc, grad_out, HETA_F32, ld_go, d, w_gate, K, R, HETA_F32, ld_r, 0.f, st);
+    e = aggregate_slot_weighted(g, r.csc, grad_out, HETA_F32, ld_go, d, w_alpha, K, dz, HETA_F32, ld_dz, 0.f, st, w_gate, R, ld_r);
     if (e != HETA_OK) return e;
     dp.x = z;
     dp.ld_x = ld_z;
     dp.y = R;
     dp.ld_y = ld_r;
     dp.n = r.n_src;
+    dp.scale = 1.f;
     dp.corr = corr_s;
     dp.out = del;
     return launch_rowdot(dp, z_dt, HETA_F32, st);

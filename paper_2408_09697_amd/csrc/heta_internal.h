@@ -129,10 +129,12 @@ heta_status device_sort_pairs_u32(uint32_t *keys, uint32_t *vals, uint32_t *keys
 // Makes sure g's workspace holds `bytes`; growing frees and reallocates (device synchronising).
 heta_status ensure_workspace(heta_graph *g, size_t bytes);
 // out[r] = beta out[r] + sum_e slot_w[e][head of the column] table[idx[e]] over the rows of s; slot_w is
-// indexed by the edge's position in s.d_sidx.  Uses g's workspace for hub rows.
+// indexed by the edge's position in s.d_sidx.  With slot_w2 the same gathered rows are reduced a second
+// time, with those weights, into out2 (same element type as out).  Uses g's workspace for hub rows.
 heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld,
                                     int d, const float *slot_w, int heads, void *out, heta_dtype out_dt,
-                                    int64_t ld_out, float beta, hipStream_t st);
+                                    int64_t ld_out, float beta, hipStream_t st, const float *slot_w2 = nullptr,
+                                    void *out2 = nullptr, int64_t ld_out2 = 0);
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t dtype_size(heta_dtype dt) { return dt == HETA_F32 ? 4 : 2; }

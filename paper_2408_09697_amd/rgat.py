@@ -66,6 +66,9 @@ class RgatLayer:
         self.smax = {r: torch.empty((n_dst(r), heads), dtype=f32, device=dev) for r in self.rels}
         self.sinv = {r: torch.empty((n_dst(r), heads), dtype=f32, device=dev) for r in self.rels}
         self.O = {r: padded(n_dst(r), d_out, f32) for r in self.rels}
+        # the same sums over the edges with a positive logit: saved so that the backward gathers no
+        # feature row on the destination side
+        self.Opos = {r: padded(n_dst(r), d_out, f32) for r in self.rels}
         self.H = {t: torch.empty((graph.ntypes[t][0], d_out), dtype=f32, device=dev) for t in self.rels_into}
         self._Gact = {t: torch.empty_like(h) for t, h in self.H.items()} if relu else {}
         self.dZ = {r: padded(n_src(r), d_out, f32) for r in self.rels}
@@ -90,7 +93,7 @@ class RgatLayer:
             hb.heta_attn_score(self.Z[r], self.a[r], True, self.el[r], stream=stream)
             hb.heta_attn_score(self.tables[t], self.q[r], False, self.er[r], stream=stream)
             hb.heta_rel_attn_fwd(g, r, self.Z[r], self.el[r], self.er[r], self.slope, self.O[r], beta=0.0,
-                                 smax=self.smax[r], sinv=self.sinv[r], stream=stream)
+                                 smax=self.smax[r], sinv=self.sinv[r], out_pos=self.Opos[r], stream=stream)
         for t, rs in self.rels_into.items():
             hb.heta_cross_rel_reduce(g, t, [self.O[r] for r in rs], self.H[t], act=self.act, stream=stream)
         return self.H
@@ -106,7 +109,8 @@ class RgatLayer:
         for r in self.rels:
             t = g.rels[r][1]
             hb.heta_rel_attn_bwd(g, r, self.Z[r], self.el[r], self.er[r], self.slope, self.smax[r], self.sinv[r],
-                                 self.O[r], grads[t], self.dZ[r], self.d_el[r], self.d_er[r], stream=stream)
+                                 self.O[r], grads[t], self.dZ[r], self.d_el[r], self.d_er[r], o_pos=self.Opos[r],
+                                 stream=stream)
             # el = <Z, a>: its gradient joins dZ and gives da
             hb.heta_attn_score_bwd(g, self.Z[r], self.a[r], True, self.d_el[r], dx=self.dZ[r], beta=1.0,
                                    dvec=self.da[r], stream=stream)

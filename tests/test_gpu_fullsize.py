@@ -214,11 +214,12 @@ def test_full_size_rgat_sampled_rows_and_invariants(full_graph):
         out = torch.empty((n_t, d), dtype=torch.float32, device="cuda")
         smax = torch.empty((n_t, K), dtype=torch.float32, device="cuda")
         sinv = torch.empty_like(smax)
-        heta.heta_rel_attn_fwd(hg, i, zd, eld, erd, slope, out, smax=smax, sinv=sinv)
+        out_pos = torch.empty((n_t, d), dtype=torch.float32, device="cuda")
+        heta.heta_rel_attn_fwd(hg, i, zd, eld, erd, slope, out, smax=smax, sinv=sinv, out_pos=out_pos)
         dz = torch.empty((n_s, d), dtype=torch.float32, device="cuda")
         d_el = torch.empty((n_s, K), dtype=torch.float32, device="cuda")
         d_er = torch.empty((n_t, K), dtype=torch.float32, device="cuda")
-        heta.heta_rel_attn_bwd(hg, i, zd, eld, erd, slope, smax, sinv, out, god, dz, d_el, d_er)
+        heta.heta_rel_attn_bwd(hg, i, zd, eld, erd, slope, smax, sinv, out, god, dz, d_el, d_er, o_pos=out_pos)
         ones = torch.ones((n_s, d), dtype=torch.float32, device="cuda")
         norm = torch.empty((n_t, d), dtype=torch.float32, device="cuda")
         heta.heta_rel_attn_fwd(hg, i, ones, eld, erd, slope, norm)
@@ -245,5 +246,5 @@ def test_full_size_rgat_sampled_rows_and_invariants(full_graph):
             _, _, rder = rgat.gat_aggregate_bwd(src_l, np.zeros(nb.size, dtype=np.int64), max(nb.size, 1), 1, z[nb], el[nb],
                                                 er[v:v + 1], alpha, go[v:v + 1], slope)
             assert_rows_close(dh[v:v + 1], rder, 1e-4, f"{r.name} der[{v}]")
-        del zd, god, out, dz, ones, norm
+        del zd, god, out, out_pos, dz, ones, norm
     torch.cuda.empty_cache()

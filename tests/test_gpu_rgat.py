@@ -91,7 +91,8 @@ def _relation_case(kind, n_src, n_dst, n_edges):
                                                        ("skew_src", 2500, 1800, 50000), ("uniform", 5, 6, 0)])
 @pytest.mark.parametrize("d,heads", [(64, 4), (256, 1), (24, 4), (520, 2), (128, 16)])
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
-def test_rel_attn_forward_and_backward(kind, n_src, n_dst, n_edges, d, heads, storage):
+@pytest.mark.parametrize("saved_pos", [True, False])
+def test_rel_attn_forward_and_backward(kind, n_src, n_dst, n_edges, d, heads, storage, saved_pos):
     G = _relation_case(kind, n_src, n_dst, n_edges)
     r = G.relations[0]
     src, dst = r.edge_list()
@@ -113,9 +114,16 @@ def test_rel_attn_forward_and_backward(kind, n_src, n_dst, n_edges, d, heads, st
     out = dev_table(np.full((n_dst, d), 3.0, dtype=np.float32), "f32", 4 if d % 4 == 0 else 1)
     smax = torch.empty((n_dst, heads), dtype=torch.float32, device="cuda")
     sinv = torch.empty_like(smax)
-    heta.heta_rel_attn_fwd(graph, 0, zd, up(el), up(er), slope, out, beta=0.0, smax=smax, sinv=sinv)
+    # out_pos: the sum over the edges with a positive logit, which lets the backward skip one gather
+    out_pos = dev_table(np.full((n_dst, d), 3.0, dtype=np.float32), "f32", 4 if d % 4 == 0 else 1) if saved_pos else None
+    heta.heta_rel_attn_fwd(graph, 0, zd, up(el), up(er), slope, out, beta=0.0, smax=smax, sinv=sinv, out_pos=out_pos)
     ref_o, alpha = rgat.gat_aggregate_fwd(src, dst, n_dst, z, el, er, slope)
     assert_rows_close(host(out), ref_o, 1e-4, "out")
+    if saved_pos:
+        pos = (el.astype(np.float32)[src] + er.astype(np.float32)[dst]) > 0
+        ref_pos = np.zeros((n_dst, heads, d // heads))
+        np.add.at(ref_pos, dst, (alpha * pos)[:, :, None] * z.astype(np.float64)[src].reshape(-1, heads, d // heads))
+        assert_rows_close(host(out_pos), ref_pos.reshape(n_dst, d), 1e-4, "out_pos")
     # accumulate on top (beta = 1) without the saved statistics
     out2 = out.clone()
     heta.heta_rel_attn_fwd(graph, 0, zd, up(el), up(er), slope, out2, beta=1.0)
@@ -123,7 +131,7 @@ def test_rel_attn_forward_and_backward(kind, n_src, n_dst, n_edges, d, heads, st
     dz = dev_table(np.full((n_src, d), 5.0, dtype=np.float32), "f32", 4 if d % 4 == 0 else 1)
     d_el = torch.full((n_src, heads), 5.0, dtype=torch.float32, device="cuda")
     d_er = torch.full((n_dst, heads), 5.0, dtype=torch.float32, device="cuda")
-    heta.heta_rel_attn_bwd(graph, 0, zd, up(el), up(er), slope, smax, sinv, out, up(go), dz, d_el, d_er)
+    heta.heta_rel_attn_bwd(graph, 0, zd, up(el), up(er), slope, smax, sinv, out, up(go), dz, d_el, d_er, o_pos=out_pos)
     torch.cuda.synchronize()
     rdz, rdel, rder = rgat.gat_aggregate_bwd(src, dst, n_src, n_dst, z, el, er, alpha, go, slope)
     assert_rows_close(host(dz), rdz, 1e-4, "dz")
