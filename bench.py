@@ -109,6 +109,23 @@ def measure(storage: str, args, keep_problem: bool = False):
     torch.cuda.synchronize()
     fwd_ms, bwd_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
 
+    # inference forward: aggregation, projection and cross-relation sum fused in one kernel per destination
+    # type (no M_r in HBM); not part of `value`, which is a training step
+    fused = None
+    try:
+        layer.forward_inference()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            layer.forward_inference()
+        e1.record()
+        torch.cuda.synchronize()
+        fused = {"ms": e0.elapsed_time(e1) / max(1, args.steps), "unfused_forward_ms": fwd_ms,
+                 "note": "heta_cross_rel_aggregate_project per destination type"}
+    except heta.HetaError as err:
+        fused = {"ms": None, "note": f"not taken by the fused kernel: {err.message}"}
+
     kernels, roofline = {}, None
     if not args.no_profile:
         heta.heta_profile_enable(True)
@@ -179,7 +196,7 @@ def measure(storage: str, args, keep_problem: bool = False):
                 "frac_of_hbm_peak": a_bytes / a_ms / 1e6 / PEAK_HBM_GBS,
                 "note": "heta_sparse_adam on every learnable table (all rows), after the timed steps; not part of value"}
         del states
-    res = {"ms_per_step": ms_per_step, "sparse_adam": adam, "value": 2.0 * edge_features / (ms_per_step * 1e-3),
+    res = {"ms_per_step": ms_per_step, "sparse_adam": adam, "fused_inference_forward": fused, "value": 2.0 * edge_features / (ms_per_step * 1e-3),
            "edges_per_s": 2.0 * n_edges / (ms_per_step * 1e-3), "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
            "ingest_ms": ingest_ms, "input_generation_s": gen_s, "roofline": roofline, "kernels": kernels,
            "edges": n_edges, "edge_features_per_pass": edge_features}
@@ -477,13 +494,15 @@ def main() -> int:
         "roofline": main_res["roofline"],
         "kernels": main_res["kernels"],
         "sparse_adam": main_res["sparse_adam"],
+        "fused_inference_forward": main_res["fused_inference_forward"],
     }
     if not args.single:
         other = "bf16" if args.dtype == "f32" else "f32"
         res, p2 = measure(other, args, keep_problem=want_cpu and other == "f32")
         problem = problem or p2
         out["bf16_storage" if other == "bf16" else "f32_storage"] = {
-            k: res[k] for k in ("value", "ms_per_step", "edges_per_s", "fwd_ms", "bwd_ms", "roofline", "kernels", "sparse_adam")}
+            k: res[k] for k in ("value", "ms_per_step", "edges_per_s", "fwd_ms", "bwd_ms", "roofline", "kernels", "sparse_adam",
+                                "fused_inference_forward")}
     if want_cpu:
         if problem is None:
             from gen import workloads

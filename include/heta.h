@@ -219,6 +219,22 @@ heta_status heta_cross_rel_project_wgrad(heta_graph *g, int32_t dst_type, int32_
                                          const float *gout, int64_t ld_go, int32_t d_out, float *const *dW,
                                          const int64_t *ld_dw, float beta, int32_t gout_two_terms, void *hip_stream);
 
+/* ---- fused forward for inference: aggregation, projection and cross-relation sum in one kernel (Eq. 1,
+ * both lines; Algorithm 1, the aggregation and AGG_all steps), the aggregated features never reach HBM:
+ *   out[v, 0:d_out] = act( sum_{p < n} ( (sum|mean)_{e in rels[p], v_e = v} table_p[row(u_e)] ) W_p ).
+ * rels: HOST array of n (1..16) relations, all ending in dst_type; tables, ld_table, d_table (width of
+ * table_p = rows of W_p), n_table_rows, src_gid (nullable array, nullable entries), W, ld_w: HOST arrays of
+ * n entries as in heta_rel_aggregate_fwd / heta_rel_project; tables and W share the element type dt.
+ * out: device fp32 [n_rows(dst_type), ld_out], overwritten.
+ * HETA_ERR_UNSUPPORTED (nothing launched) unless d_out <= 256 and every source row is a 16-byte aligned
+ * multiple of 16 bytes: use the unfused calls then.  Training needs the aggregated features for the
+ * weight gradient and uses the unfused calls as well. */
+heta_status heta_cross_rel_aggregate_project(heta_graph *g, int32_t dst_type, int32_t n, const int32_t *rels,
+                                             heta_reduce op, const void *const *tables, heta_dtype dt,
+                                             const int64_t *ld_table, const int32_t *d_table, const int64_t *n_table_rows,
+                                             const int64_t *const *src_gid, const void *const *W, const int64_t *ld_w,
+                                             int32_t d_out, heta_act act, float *out, int64_t ld_out, void *hip_stream);
+
 /* ---- cross-relation aggregation (Eq. 1, second line; Algorithm 1, AGG_all on the designated
  * worker; on a subset of relations it yields the partial aggregation a worker would send) --------
  * out[i, 0:d_out] = act(sum_{p < n_partials} partials[p][i, 0:d_out]), summed in array order.

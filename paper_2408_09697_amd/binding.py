@@ -30,7 +30,8 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
            "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam", "heta_project_batch",
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
-           "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel"]
+           "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel",
+           "heta_cross_rel_aggregate_project"]
 
 
 class HetaError(RuntimeError):
@@ -598,6 +599,34 @@ def heta_rel_attn_bwd(g: Graph, rel: int, z: torch.Tensor, el: torch.Tensor, er:
                                _dev(grad_out, "grad_out", torch.float32), _ld(grad_out),
                                _dev(dz, "dz", torch.float32), _ld(dz), _scores(d_el, "del", n_src, heads),
                                _scores(d_er, "der", n_dst, heads), _stream(stream)))
+
+
+def heta_cross_rel_aggregate_project(g: Graph, dst_type: int, rels: List[int], op: int, tables: List[torch.Tensor],
+                                     Ws: List[torch.Tensor], out: torch.Tensor, act: int = HETA_ACT_NONE,
+                                     src_gid: Optional[List[Optional[torch.Tensor]]] = None, stream=None) -> torch.Tensor:
+    """out = act(sum_p agg_{rels[p]}(tables[p]) @ Ws[p]) over the rows of dst_type, one fused kernel (inference)."""
+    n = len(rels)
+    if n == 0 or len(tables) != n or len(Ws) != n or (src_gid is not None and len(src_gid) != n):
+        raise HetaError(HETA_ERR_SHAPE, "bad arguments")
+    d_out = Ws[0].shape[1]
+    for t, w in zip(tables, Ws):
+        if w.shape[0] != t.shape[1] or w.shape[1] != d_out or t.dtype != tables[0].dtype or w.dtype != tables[0].dtype:
+            raise HetaError(HETA_ERR_SHAPE, "tables / weights do not match")
+    if out.shape[0] < g.ntypes[dst_type][0] or out.shape[1] < d_out:
+        raise HetaError(HETA_ERR_SHAPE, "out too small")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_cross_rel_aggregate_project.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, i64, vp]
+    gids = None
+    if src_gid is not None:
+        gids = (ctypes.c_void_p * n)(*[_dev(x, "src_gid", torch.int64) for x in src_gid])
+    _check(L.heta_cross_rel_aggregate_project(
+        g.handle, dst_type, n, _i32_array(rels), op, _ptr_array(tables, "table"), _dt(tables[0]),
+        _i64_array([_ld(t) for t in tables]), _i32_array([t.shape[1] for t in tables]),
+        _i64_array([t.shape[0] for t in tables]),
+        None if gids is None else ctypes.addressof(gids), _ptr_array(Ws, "W"), _i64_array([w.stride(0) for w in Ws]),
+        d_out, act, _dev(out, "out", torch.float32), _ld(out), _stream(stream)))
+    return out
 
 
 def heta_sample_neighbors(g: Graph, rel: int, dst_ids: torch.Tensor, fanout: int, seed: int, stream=None):

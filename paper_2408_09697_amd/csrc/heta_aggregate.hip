@@ -58,6 +58,7 @@ struct AggParams {
     void *out2;            // reduced a second time with it into out2 (same type and leading dimension rules as out)
     int64_t ld_out2;
     int mean;              // divide the row sum by the row's degree
+    int hub_only;          // reduce the hub rows only, into out[h] for the h-th hub row of the schedule
     void *out;
     int64_t ld_out;
     int out_bf16;
@@ -495,7 +496,7 @@ __global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_kernel(Agg
     __shared__ float4 part[kCombineWaves][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t h = blockIdx.x;
-    const int64_t row = p.perm[h];
+    const int64_t row = p.hub_only ? h : p.perm[h];
     const int64_t s0 = p.hub_chunk_ptr[h], s1 = p.hub_chunk_ptr[h + 1];
     const int col0 = (blockIdx.y * 64 + lane) * 4;
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -605,7 +606,7 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     p.hub_chunk_ptr = s.d_hub_chunk_ptr;
     p.n_hub_chunks = s.n_hub_chunks;
     p.n_hub_rows = s.n_hub_rows;
-    p.n_wave_items = s.n_hub_chunks + (n_long_or_hub - s.n_hub_rows);
+    p.n_wave_items = s.n_hub_chunks + (p.hub_only ? 0 : n_long_or_hub - s.n_hub_rows);
     p.n_rows = s.n_rows;
     // short rows: bucket b = degree kShortDeg - 1 - b, in schedule order (descending degree)
     int64_t batches = 0;
@@ -615,7 +616,7 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
         p.batch0[b] = static_cast<int32_t>(batches);
         p.row0[b] = static_cast<int32_t>(first);
         p.edge0[b] = s.edges_with_deg_ge[k + 1];
-        batches += (count + batch_rows(k, G) - 1) / batch_rows(k, G);
+        if (!p.hub_only) batches += (count + batch_rows(k, G) - 1) / batch_rows(k, G);
         if (batches > 0x7ffffff0) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many short rows");
     }
     p.batch0[kShortDeg] = static_cast<int32_t>(batches);
@@ -683,6 +684,25 @@ heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void
     p.ld_out = ld_out;
     p.out_bf16 = (out_dt == HETA_BF16);
     p.beta = beta;
+    p.d = d;
+    return run_aggregate(g, s, p, dt, ld, st);
+}
+
+// The hub rows of a schedule only (rows of at least kHubMinDeg edges), reduced into a compact fp32
+// array: out[h] is the sum (or mean) of the h-th row of the schedule order.  For callers that handle
+// all other rows themselves (the fused aggregate-and-project kernel).
+heta_status aggregate_hub_rows(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld, int d,
+                               const int64_t *gid, int mean, float *out, int64_t ld_out, hipStream_t st)
+{
+    if (s.n_hub_rows == 0) return HETA_OK;
+    AggParams p{};
+    p.table = table;
+    p.ld = ld;
+    p.gid = gid;
+    p.mean = mean;
+    p.hub_only = 1;
+    p.out = out;
+    p.ld_out = ld_out;
     p.d = d;
     return run_aggregate(g, s, p, dt, ld, st);
 }

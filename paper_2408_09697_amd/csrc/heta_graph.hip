@@ -170,6 +170,8 @@ static void destroy(heta_graph *g)
         return;
     (void)hipDeviceSynchronize();
     for (auto &r : g->rels) {
+        (void)hipFree(r.d_hub_slot);
+        (void)hipFree(r.d_hub_rows);
         if (r.d_arena) { // host-built: one allocation
             (void)hipFree(r.d_arena);
             continue;

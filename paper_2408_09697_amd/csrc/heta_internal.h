@@ -73,6 +73,9 @@ struct Relation {
     Schedule csr;                 // rows = destinations, idx = sources
     Schedule csc;                 // rows = sources, idx = destinations
     float *d_inv_deg = nullptr;   // [n_dst] 1/deg_r(v), 0 for zero-degree rows
+    int32_t *d_hub_slot = nullptr; // [n_dst] position of a destination among the CSR schedule's hub rows, built on first use
+    float *d_hub_rows = nullptr;   // aggregated hub rows of the fused forward, grown on demand
+    size_t hub_rows_bytes = 0;
     void *d_arena = nullptr;      // host-built relations: the one allocation every pointer above points into
 };
 
@@ -135,6 +138,9 @@ heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void
                                     int d, const float *slot_w, int heads, void *out, heta_dtype out_dt,
                                     int64_t ld_out, float beta, hipStream_t st, const float *slot_w2 = nullptr,
                                     void *out2 = nullptr, int64_t ld_out2 = 0);
+// out[h] (fp32, compact) = sum or mean of the h-th hub row of s (rows of >= kHubMinDeg edges lead the schedule)
+heta_status aggregate_hub_rows(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld, int d,
+                               const int64_t *gid, int mean, float *out, int64_t ld_out, hipStream_t st);
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t dtype_size(heta_dtype dt) { return dt == HETA_F32 ? 4 : 2; }

@@ -161,6 +161,25 @@ class RafLayer:
                 hb.heta_cross_rel_reduce(self.g, t, [self.H[t]], self.H[t], act=hb.HETA_ACT_RELU, stream=stream)
         return self.H
 
+    def forward_inference(self, stream=None) -> Dict[int, torch.Tensor]:
+        """Forward only, one fused kernel per destination type (aggregation, projection, cross-relation sum
+        and activation; no M_r is written, so no backward can follow).  Raises HetaError UNSUPPORTED for
+        shapes the fused kernel does not take (d_out > 256, rows that are not 16-byte aligned)."""
+        self._pre_project(stream)
+        for t, rs in self.rels_into.items():
+            if self.g.ntypes[t][0] == 0:
+                continue
+            for i in range(0, len(rs), 16):
+                part = rs[i:i + 16]
+                if i > 0:
+                    raise hb.HetaError(hb.HETA_ERR_UNSUPPORTED, "more than 16 relations into one node type")
+                srcs = [self.g.rels[r][0] for r in part]
+                gids = None if self.src_gid is None else [self.src_gid[s] for s in srcs]
+                hb.heta_cross_rel_aggregate_project(self.g, t, part, self.op, [self.source(s) for s in srcs],
+                                                    [self.W[r] for r in part], self.H[t], act=self.act, src_gid=gids,
+                                                    stream=stream)
+        return self.H
+
     def forward_unfused(self, stream=None) -> Dict[int, torch.Tensor]:
         """Same result through explicit per-relation partials Z_r and heta_cross_rel_reduce."""
         self._aggregate_first_everywhere()
