@@ -1,0 +1,127 @@
+"""One mini-batch training step with every stage on the device (sampler, block ingest, two layers
+forward and backward, Adam on the weights, sparse Adam on the touched embedding rows) against the same
+step composed from the oracles: sampled blocks bit for bit, embeddings and gradients at 1e-4, and the
+parameter update checked tightly by applying the oracle's Adam to the gradients the GPU produced (Adam's
+first steps move every parameter by about lr whatever the gradient's size, so comparing parameters that
+came from two slightly different gradients would only measure sign flips of near-zero gradients)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2408_09697_amd as heta
+from gen import rng, workloads
+from gen.graphs import HetGraph, NodeType, Relation
+from gen.sampler import Block
+from oracle import sampler as osampler
+from tests.harness import assert_rows_close, dev_table
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_blocks(base, seeds, fanouts, seed):
+    T = len(base.ntypes)
+    rels = [(r.src_type, r.dst_type, r.rowptr, r.col) for r in base.relations]
+    out = []
+    for b in osampler.sample_blocks(T, rels, 0, seeds, fanouts, seed):
+        nts = [NodeType(f"{t.name}/src", int(b["src_ids"][k].size), t.feat_dim, t.learnable) for k, t in enumerate(base.ntypes)]
+        nts += [NodeType(f"{t.name}/dst", 0 if b["dst_ids"][k] is None else int(b["dst_ids"][k].size), t.feat_dim, t.learnable)
+                for k, t in enumerate(base.ntypes)]
+        g = HetGraph(nts)
+        for (s, t, _, _), (ptr, loc), r in zip(rels, b["rels"], base.relations):
+            g.relations.append(Relation(r.name, s, T + t, ptr, loc))
+        out.append(Block(g, list(b["src_ids"]) + [None] * T, [None] * T + list(b["dst_ids"]), T))
+    return out
+
+
+def test_device_training_steps_match_the_composed_oracles():
+    wl = "tests/train"
+    base = workloads.academic_graph(scale=0.01, workload=wl)
+    T = len(base.ntypes)
+    d_hidden, fanouts, lr, seed = 64, [6, 4], 1e-2, 777
+    tables = workloads._tables(base, wl, "f32", False)
+    W = [workloads._weights(base, (lambda i, l=l: base.ntypes[base.relations[i].src_type].feat_dim if l == 0 else d_hidden),
+                            d_hidden, f"{wl}/L{l}", "f32", False) for l in range(2)]
+    hg = heta.heta_graph_create([(t.num_nodes, t.feat_dim, int(t.learnable)) for t in base.ntypes],
+                                [(r.src_type, r.dst_type, r.rowptr, r.col) for r in base.relations])
+    tab_dev = [dev_table(x, "f32", 4) for x in tables]
+    W_dev = [[dev_table(w, "f32", 4) for w in ws] for ws in W]
+    trainer = heta.MiniBatchTrainer(hg, tab_dev, W_dev, fanouts, d_hidden, heta.HETA_MEAN, 0, lr=lr, seed=seed)
+    g = rng.stream("tests", "train/seeds")
+    # oracle-side state
+    tabs = [x.astype(np.float64) for x in tables]
+    Ws = [[w.astype(np.float64) for w in ws] for ws in W]
+    mW = [[np.zeros_like(w) for w in ws] for ws in Ws]
+    vW = [[np.zeros_like(w) for w in ws] for ws in Ws]
+    mT = {t: np.zeros_like(tabs[t]) for t in range(T) if base.ntypes[t].learnable}
+    vT = {t: np.zeros_like(tabs[t]) for t in range(T) if base.ntypes[t].learnable}
+    for step in (1, 2, 3):
+        seeds = np.sort(g.choice(base.ntypes[0].num_nodes, 128, replace=False)).astype(np.int64)
+        Y = g.standard_normal((128, d_hidden)).astype(np.float32)
+        Yd = torch.from_numpy(Y).cuda()
+        H = trainer.step(torch.from_numpy(seeds).cuda(), lambda h: h - Yd, keep_blocks=True)
+        torch.cuda.synchronize()
+        # the same iteration from the oracles, on the parameters as they were before the step
+        blocks = _oracle_blocks(base, seeds, fanouts, seed + step)
+        for b, rb in zip(trainer.last_blocks, blocks):
+            for k in range(T):
+                assert np.array_equal(b.src_ids[k].cpu().numpy(), rb.src_gid[k])
+            for i, r in enumerate(rb.graph.relations):
+                assert np.array_equal(b.rowptr[i].cpu().numpy(), r.rowptr) and np.array_equal(b.col[i].cpu().numpy(), r.col)
+        mb = workloads.MiniBatchProblem("train", base, blocks, "mean", "f32", [[w.astype(np.float32) for w in ws] for ws in Ws],
+                                        d_hidden, 0, Y, tables=[x.astype(np.float32) for x in tabs])
+        fwd, probs, prev = [], [], None
+        for l in range(2):
+            p = mb.layer_problem(l, prev)
+            p.tables = [np.asarray(x, np.float64) for x in p.tables]
+            p.W = Ws[l]
+            if l == 0:   # compact float64 rows of the current tables
+                p.tables = [tabs[k][blocks[0].src_gid[k]] if k < T else p.tables[k] for k in range(2 * T)]
+            r = oracle.layer_forward(p)
+            prev = r.H
+            fwd.append(r)
+            probs.append(p)
+        H_ref = fwd[1].H[T + 0]
+        assert_rows_close(H.cpu().numpy(), H_ref, 1e-4, f"step {step} H")
+        G = {T + 0: H_ref - Y}
+        grads = [None, None]
+        for l in (1, 0):
+            p = probs[l]
+            for t, nt in enumerate(p.graph.ntypes):
+                if t >= T and t not in G:
+                    G[t] = np.zeros((nt.num_nodes, d_hidden))
+            dW, dH0, _ = oracle.layer_backward(p, fwd[l], G)
+            grads[l] = (dW, dH0)
+            G = {T + s: x for s, x in dH0.items()}
+        layers = trainer.last_layers
+        for l in range(2):
+            for r in layers[l].rels:
+                assert_rows_close(layers[l].dW[r].cpu().numpy(), grads[l][0][r], 1e-4, f"step {step} layer {l} dW[{r}]")
+        for s, x in grads[0][1].items():
+            if x.shape[0]:
+                assert_rows_close(layers[0].dH0[s].cpu().numpy(), x, 1e-4, f"step {step} dH0[{s}]")
+        # the update: the oracle's Adam on the GPU's gradients must reproduce the GPU's new parameters
+        for l in range(2):
+            for r in range(len(base.relations)):
+                if r not in layers[l].rels:   # relation without destinations in this block: untouched
+                    assert np.array_equal(W_dev[l][r].cpu().numpy(), Ws[l][r].astype(np.float32))
+                    continue
+                gW = layers[l].dW[r].cpu().numpy()
+                Ws[l][r], mW[l][r], vW[l][r] = oracle.sparse_adam_step(Ws[l][r], mW[l][r], vW[l][r], np.arange(gW.shape[0]),
+                                                                       gW, lr, 0.9, 0.999, 1e-8, step)
+                np.testing.assert_allclose(W_dev[l][r].cpu().numpy(), Ws[l][r], rtol=2e-5, atol=2e-6)
+                Ws[l][r] = W_dev[l][r].cpu().numpy().astype(np.float64)   # continue from the GPU's fp32 state
+        for t in mT:
+            ids = blocks[0].src_gid[t]
+            before = tabs[t].copy()
+            if ids.size and t in layers[0].dH0:
+                gT = layers[0].dH0[t].cpu().numpy()
+                tabs[t], mT[t], vT[t] = oracle.sparse_adam_step(tabs[t], mT[t], vT[t], ids, gT, lr, 0.9, 0.999, 1e-8, step)
+            got = tab_dev[t].cpu().numpy()
+            np.testing.assert_allclose(got, tabs[t], rtol=2e-5, atol=2e-6)
+            untouched = np.setdiff1d(np.arange(before.shape[0]), ids)
+            assert np.array_equal(got[untouched], before[untouched].astype(np.float32))
+            tabs[t] = got.astype(np.float64)
+        for b in trainer.last_blocks:
+            b.graph.destroy()
+    hg.destroy()
