@@ -7,9 +7,13 @@
 // sampled mini-batch, where launch latency would dominate.  Both produce the same arrays.
 #include <algorithm>
 #include <cstring>
+#include <map>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
+#include <unordered_map>
+#include <utility>
 
 #include "heta_internal.h"
 
@@ -36,6 +40,65 @@ heta_status fail(heta_status st, const char *fmt, ...)
     va_end(ap);
     g_last_error = buf;
     return st;
+}
+
+// ---- recycled device blocks for short-lived scratch ---------------------------------------------------
+// Sampling a mini-batch and ingesting its blocks makes dozens of small allocations per iteration; each
+// hipMalloc / hipFree pair costs tens of microseconds and hipFree waits for the device.  Blocks of up to
+// 16 MiB are rounded to a power of two and kept on a free list per (device, size) when released, up to
+// 256 MiB in total; larger ones go straight to hipMalloc / hipFree.  A block must be idle when it is
+// released (the callers synchronise first).
+namespace {
+constexpr size_t kPoolMaxBlock = size_t(16) << 20, kPoolMaxCached = size_t(256) << 20;
+std::mutex g_pool_mu;
+std::unordered_map<void *, std::pair<int, size_t>> g_pool_blocks;     // live pooled block -> (device, size class)
+std::map<std::pair<int, size_t>, std::vector<void *>> g_pool_free;
+size_t g_pool_cached = 0;
+} // namespace
+
+hipError_t scratch_alloc(void **out, size_t bytes)
+{
+    *out = nullptr;
+    size_t cls = 256;
+    while (cls < bytes) cls <<= 1;
+    if (cls > kPoolMaxBlock) return hipMalloc(out, bytes);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    {
+        std::lock_guard<std::mutex> lk(g_pool_mu);
+        auto it = g_pool_free.find({dev, cls});
+        if (it != g_pool_free.end() && !it->second.empty()) {
+            *out = it->second.back();
+            it->second.pop_back();
+            g_pool_cached -= cls;
+            return hipSuccess;
+        }
+    }
+    e = hipMalloc(out, cls);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lk(g_pool_mu);
+    g_pool_blocks[*out] = {dev, cls};
+    return hipSuccess;
+}
+
+void scratch_free(void *p)
+{
+    if (!p) return;
+    {
+        std::lock_guard<std::mutex> lk(g_pool_mu);
+        auto it = g_pool_blocks.find(p);
+        if (it != g_pool_blocks.end()) {
+            const size_t cls = it->second.second;
+            if (g_pool_cached + cls <= kPoolMaxCached) {
+                g_pool_free[it->second].push_back(p);
+                g_pool_cached += cls;
+                return;
+            }
+            g_pool_blocks.erase(it);
+        }
+    }
+    (void)hipFree(p);
 }
 
 heta_status ensure_workspace(heta_graph *g, size_t bytes)
@@ -172,8 +235,8 @@ static void destroy(heta_graph *g)
     for (auto &r : g->rels) {
         (void)hipFree(r.d_hub_slot);
         (void)hipFree(r.d_hub_rows);
-        if (r.d_arena) { // host-built: one allocation
-            (void)hipFree(r.d_arena);
+        if (r.d_arena) { // host-built: one allocation (the device is idle here)
+            scratch_free(r.d_arena);
             continue;
         }
         free_schedule(r.csr);
@@ -299,7 +362,7 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
     if ((e = build_schedule_on_host(rel.csr, ptr, col, pack, o_csr)) != HETA_OK) return e;
     if ((e = build_schedule_on_host(rel.csc, colptr.data(), row.data(), pack, o_csc)) != HETA_OK) return e;
     const size_t o_inv = pack.add(inv_deg.data(), static_cast<size_t>(n_dst));
-    HETA_HIP(hipMalloc(&rel.d_arena, pack.buf.size()));
+    HETA_HIP(scratch_alloc(&rel.d_arena, pack.buf.size()));
     HETA_HIP(hipMemcpy(rel.d_arena, pack.buf.data(), pack.buf.size(), hipMemcpyHostToDevice));
     char *base = static_cast<char *>(rel.d_arena);
     resolve(rel.csr, o_csr, base);

@@ -26,19 +26,22 @@ constexpr int kScanTile = 256 * kScanItems;   // per workgroup
 constexpr int kSortRounds = 16;               // keys per thread
 constexpr int kSortTile = 256 * kSortRounds;  // keys per workgroup
 
-// Frees its device allocations when it goes out of scope (scratch of one ingest).
+// Releases its device blocks when it goes out of scope (scratch of one ingest).  The blocks come from the
+// recycling pool, which needs them idle on release: the destructor waits for the device first.
 struct Scratch {
     std::vector<void *> blocks;
     ~Scratch()
     {
-        for (void *b : blocks) (void)hipFree(b);
+        if (blocks.empty()) return;
+        (void)hipDeviceSynchronize();
+        for (void *b : blocks) scratch_free(b);
     }
     template <typename T> heta_status get(T **out, size_t n)
     {
         void *p = nullptr;
-        hipError_t e = hipMalloc(&p, std::max<size_t>(n, 1) * sizeof(T));
+        hipError_t e = scratch_alloc(&p, std::max<size_t>(n, 1) * sizeof(T));
         if (e != hipSuccess)
-            return fail(e == hipErrorOutOfMemory ? HETA_ERR_OOM : HETA_ERR_DEVICE, "hipMalloc of ingest scratch failed: %s",
+            return fail(e == hipErrorOutOfMemory ? HETA_ERR_OOM : HETA_ERR_DEVICE, "allocation of ingest scratch failed: %s",
                         hipGetErrorString(e));
         blocks.push_back(p);
         *out = static_cast<T *>(p);

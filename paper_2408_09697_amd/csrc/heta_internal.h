@@ -129,6 +129,11 @@ heta_status device_exclusive_scan_i64(const int64_t *in, int64_t n_in, int64_t *
 heta_status device_sort_pairs_u32(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n,
                                   int64_t key_limit, uint32_t **keys_res, uint32_t **vals_res, hipStream_t st);
 
+// Short-lived device scratch from a recycling pool (blocks up to 16 MiB; larger ones are plain hipMalloc).
+// scratch_free requires the block to be idle: synchronise first.
+hipError_t scratch_alloc(void **out, size_t bytes);
+void scratch_free(void *p);
+
 // Makes sure g's workspace holds `bytes`; growing frees and reallocates (device synchronising).
 heta_status ensure_workspace(heta_graph *g, size_t bytes);
 // out[r] = beta out[r] + sum_e slot_w[e][head of the column] table[idx[e]] over the rows of s; slot_w is

@@ -111,14 +111,21 @@ __global__ void __launch_bounds__(256) unique_scatter_kernel(const uint32_t *key
     local_all[vals[i]] = static_cast<int32_t>(u);
 }
 
+// scratch of one call, from the recycling pool (released idle: every entry point below synchronises its
+// stream before it returns, and the destructor waits for the device in case an error path did not)
 template <typename T> struct DevBuf {
     T *p = nullptr;
-    ~DevBuf() { (void)hipFree(p); }
+    ~DevBuf()
+    {
+        if (!p) return;
+        (void)hipDeviceSynchronize();
+        scratch_free(p);
+    }
     heta_status alloc(size_t n)
     {
-        hipError_t e = hipMalloc(reinterpret_cast<void **>(&p), std::max<size_t>(n, 1) * sizeof(T));
+        hipError_t e = scratch_alloc(reinterpret_cast<void **>(&p), std::max<size_t>(n, 1) * sizeof(T));
         if (e != hipSuccess)
-            return fail(e == hipErrorOutOfMemory ? HETA_ERR_OOM : HETA_ERR_DEVICE, "hipMalloc of sampler scratch failed: %s",
+            return fail(e == hipErrorOutOfMemory ? HETA_ERR_OOM : HETA_ERR_DEVICE, "allocation of sampler scratch failed: %s",
                         hipGetErrorString(e));
         return HETA_OK;
     }
