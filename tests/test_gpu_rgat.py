@@ -201,3 +201,50 @@ def test_rgat_layer_config3_scaled(storage, tol):
     p = workloads.config3(storage, scale=0.02)
     p.relu = True
     _run_layer(p, workloads.attention_params(p, 4, gain=1.0), tol)
+
+
+def test_rgat_layer_on_a_sampled_block():
+    """R-GAT over a mini-batch block: the block's node types are the base types twice (source role k,
+    destination role T + k); both roles read compact tables gathered by the block's id lists
+    (heta_feature_gather), and the gradients come back per role."""
+    mb = workloads.config2(scale=0.02)
+    b = mb.blocks[0]
+    T = b.n_base_types
+    g = b.graph
+    tabs_host, tabs_dev = [], []
+    for k in range(2 * T):
+        base_t = k % T
+        ids = b.src_gid[k] if k < T else b.dst_gid[k]
+        ids = np.zeros(0, dtype=np.int64) if ids is None else ids
+        full = dev_table(mb.tables[base_t], "f32", 4)
+        out = dev_table(np.zeros((max(1, ids.size), full.shape[1]), dtype=np.float32), "f32", 4)[:ids.size]
+        if ids.size:
+            heta.heta_feature_gather(full, torch.from_numpy(ids).cuda(), out)
+        tabs_dev.append(out if ids.size else dev_table(np.zeros((1, full.shape[1]), dtype=np.float32), "f32", 4)[:0])
+        tabs_host.append(mb.tables[base_t][ids])
+    rels = [i for i, r in enumerate(g.relations) if g.ntypes[r.dst_type].num_nodes > 0 and g.ntypes[r.src_type].num_nodes > 0]
+    W = [workloads.glorot(g.ntypes[r.src_type].feat_dim, 64, "tests/rgat/block", f"W/{r.name}") for r in g.relations]
+    Gup = {t: rng.normal_table(g.ntypes[t].num_nodes, 64, "tests/rgat/block", f"G/{t}")
+           for t in {g.relations[i].dst_type for i in rels}}
+    p = workloads.LayerProblem("rgat-block", g, "sum", "f32", tabs_host, W, 64, Gup, relu=True)
+    ap = workloads.attention_params(p, 4, gain=1.5)
+    a64, q64 = [np.asarray(x, np.float64) for x in ap.a], [np.asarray(x, np.float64) for x in ap.q]
+    fwd = rgat.rgat_forward(p, a64, q64, ap.slope, rels=rels)
+    G = {t: np.where(kink_guard(fwd.H[t], 1e-4), p.G[t], 0.0).astype(np.float32) for t in fwd.H}
+    rdW, rda, rdq, rdH0 = rgat.rgat_backward(p, a64, q64, fwd, G, ap.slope, rels=rels)
+    hg = make_graph(p)
+    layer = heta.RgatLayer(hg, tabs_dev, [dev_table(w, "f32", 4) for w in W], [up(x) for x in ap.a],
+                           [up(np.ascontiguousarray(x.T)) for x in ap.q], 64, 4, ap.slope, relu=True, rels=rels)
+    H = layer.forward()
+    dW, da, dq, dH0 = layer.backward({t: up(x) for t, x in G.items()})
+    torch.cuda.synchronize()
+    for t, h in fwd.H.items():
+        assert_rows_close(host(H[t]), h, 1e-4, f"H[{t}]")
+    for i in rels:
+        assert_rows_close(host(dW[i]), rdW[i], 1e-4, f"dW[{i}]")
+        assert_rows_close(host(da[i]), rda[i], 1e-4, f"da[{i}]")
+        assert_rows_close(host(dq[i]), rdq[i].T, 1e-4, f"dq[{i}]")
+    for t, x in rdH0.items():
+        if x.shape[0]:
+            assert_rows_close(host(dH0[t]), x, 1e-4, f"dH0[{t}]")
+    hg.destroy()
