@@ -49,6 +49,18 @@ __device__ __forceinline__ bf16_t to_bf16(float f)
     return static_cast<bf16_t>((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
+// two fp32 values -> two bf16 in one 32-bit word (lo in the low half), round to nearest even, with the
+// packed hardware convert (v_cvt_pk_bf16_f32)
+typedef float floatx2_pk __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_pk __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi)
+{
+    const floatx2_pk f = {lo, hi};
+    const bf16x2_pk h = __builtin_convertvector(f, bf16x2_pk);
+    return *reinterpret_cast<const uint32_t *>(&h);
+}
+__device__ __forceinline__ uint32_t pack2_bf16(bf16_t lo, bf16_t hi) { return static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16); }
+
 template <typename S, typename CT> __device__ __forceinline__ CT convert(S v);
 template <> __device__ __forceinline__ float convert<float, float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t convert<float, bf16_t>(float v) { return to_bf16(v); }
@@ -180,9 +192,10 @@ struct TileLoader {
 #pragma unroll
                 for (int j = 0; j < E; ++j) {
                     const float a = t[0].s[j], b = t[LPI - 1].s[j];
-                    const float ra = a - __uint_as_float(static_cast<uint32_t>(to_bf16(a)) << 16);
-                    const float rb = b - __uint_as_float(static_cast<uint32_t>(to_bf16(b)) << 16);
-                    w[j] = static_cast<uint32_t>(to_bf16(ra)) | (static_cast<uint32_t>(to_bf16(rb)) << 16);
+                    const uint32_t hi = pack2_bf16(a, b); // the pair as store() writes it
+                    const float ra = a - __uint_as_float(hi << 16);
+                    const float rb = b - __uint_as_float(hi & 0xffff0000u);
+                    w[j] = pack2_bf16(ra, rb);
                 }
                 uint32_t *dst = reinterpret_cast<uint32_t *>(lds) + (k / 2) * ROWS + r;
 #pragma unroll
@@ -210,14 +223,17 @@ struct TileLoader {
             if (PAIR) {
                 uint32_t w[E];
 #pragma unroll
-                for (int j = 0; j < E; ++j)
-                    w[j] = static_cast<uint32_t>(convert<S, bf16_t>(t[0].s[j])) |
-                           (static_cast<uint32_t>(convert<S, bf16_t>(t[LPI - 1].s[j])) << 16);
+                for (int j = 0; j < E; ++j) w[j] = pack2_bf16(t[0].s[j], t[LPI - 1].s[j]);
                 uint32_t *dst = reinterpret_cast<uint32_t *>(lds) + (k / 2) * ROWS + r;
 #pragma unroll
                 for (int j = 0; j < E; j += 4) *reinterpret_cast<uint4 *>(dst + j) = make_uint4(w[j], w[j + 1], w[j + 2], w[j + 3]);
             } else if (RC) {
                 *reinterpret_cast<uint4 *>(lds + k * ROWS + r) = t[0].u; // fp32 compute: S == CT == float
+            } else if constexpr (sizeof(S) == 4 && sizeof(CT) == 2) { // fp32 -> bf16, k-contiguous: packed converts
+                uint32_t w[E / 2];
+#pragma unroll
+                for (int j = 0; j < E / 2; ++j) w[j] = pack2_bf16(t[0].s[2 * j], t[0].s[2 * j + 1]);
+                *reinterpret_cast<uint2 *>(lds + r * SA + k) = make_uint2(w[0], w[1]);
             } else {
                 CT tmp[E];
 #pragma unroll
