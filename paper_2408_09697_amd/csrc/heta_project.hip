@@ -266,7 +266,7 @@ static heta_status launch_gemm(GemmParams &p, hipStream_t st, int bk)
                    st, bytes, flops);
     if constexpr (sizeof(CT) == 2 && A_RC && B_RC && sizeof(SB_T) == 4) {
         if (p.split_b) {
-            hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN, VEC, 32, true>), dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
+            hipLaunchKernelGGL((gemm_kernel<CT, SA_T, A_RC, SB_T, B_RC, WN, VEC, 64, true>), dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
             HETA_LAUNCH_CHECK("gemm_kernel");
             return HETA_OK;
         }
