@@ -113,14 +113,12 @@ template <typename TO> __global__ void __launch_bounds__(256) scan_add_kernel(TO
     if (i < n) out[i] += tile_sums[i / kScanTile];
 }
 
+// tile_sums: scratch of (n_out + kScanTile - 1) / kScanTile elements; asynchronous on st
 template <typename TI, typename TO>
-heta_status exclusive_scan(const TI *in, int64_t n_in, TO *out, int64_t n_out, Scratch &scr, hipStream_t st)
+heta_status exclusive_scan_with(const TI *in, int64_t n_in, TO *out, int64_t n_out, TO *tile_sums, hipStream_t st)
 {
     if (n_out <= 0) return HETA_OK;
     const int64_t tiles = (n_out + kScanTile - 1) / kScanTile;
-    TO *tile_sums = nullptr;
-    heta_status e = scr.get(&tile_sums, static_cast<size_t>(tiles));
-    if (e != HETA_OK) return e;
     hipLaunchKernelGGL((scan_tile_kernel<TI, TO>), dim3((unsigned)tiles), dim3(256), 0, st, in, n_in, out, n_out, tile_sums);
     HETA_LAUNCH_CHECK("scan_tile_kernel");
     if (tiles > 1) {
@@ -130,6 +128,16 @@ heta_status exclusive_scan(const TI *in, int64_t n_in, TO *out, int64_t n_out, S
         HETA_LAUNCH_CHECK("scan_add_kernel");
     }
     return HETA_OK;
+}
+
+template <typename TI, typename TO>
+heta_status exclusive_scan(const TI *in, int64_t n_in, TO *out, int64_t n_out, Scratch &scr, hipStream_t st)
+{
+    if (n_out <= 0) return HETA_OK;
+    TO *tile_sums = nullptr;
+    heta_status e = scr.get(&tile_sums, static_cast<size_t>((n_out + kScanTile - 1) / kScanTile));
+    if (e != HETA_OK) return e;
+    return exclusive_scan_with<TI, TO>(in, n_in, out, n_out, tile_sums, st);
 }
 
 // ---- stable LSD radix sort of (key, value) pairs ------------------------------------------------------
@@ -200,22 +208,22 @@ __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys,
 
 // Sorts n pairs by the low `bits` bits of the key.  (keys, vals) and (keys_tmp, vals_tmp) are
 // ping-pong buffers; *keys_res / *vals_res point at whichever holds the result.
-heta_status radix_sort_pairs(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n, int bits,
-                             uint32_t **keys_res, uint32_t **vals_res, Scratch &scr, hipStream_t st)
+// hist, offs: scratch of 256 * n_tiles elements each (n_tiles = (n + kSortTile - 1) / kSortTile); tile_sums: scratch
+// for a scan over 256 * n_tiles elements; asynchronous on st
+heta_status radix_sort_pairs_with(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n, int bits,
+                                  uint32_t **keys_res, uint32_t **vals_res, uint32_t *hist, uint32_t *offs, uint32_t *tile_sums,
+                                  hipStream_t st)
 {
     *keys_res = keys;
     *vals_res = vals;
     if (n <= 1 || bits <= 0) return HETA_OK;
     const int64_t n_tiles = (n + kSortTile - 1) / kSortTile;
-    uint32_t *hist = nullptr, *offs = nullptr;
     heta_status e;
-    if ((e = scr.get(&hist, static_cast<size_t>(256 * n_tiles))) != HETA_OK) return e;
-    if ((e = scr.get(&offs, static_cast<size_t>(256 * n_tiles))) != HETA_OK) return e;
     uint32_t *ki = keys, *vi = vals, *ko = keys_tmp, *vo = vals_tmp;
     for (int shift = 0; shift < bits; shift += 8) {
         hipLaunchKernelGGL(sort_hist_kernel, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, n, shift, hist, n_tiles);
         HETA_LAUNCH_CHECK("sort_hist_kernel");
-        if ((e = exclusive_scan<uint32_t, uint32_t>(hist, 256 * n_tiles, offs, 256 * n_tiles, scr, st)) != HETA_OK) return e;
+        if ((e = exclusive_scan_with<uint32_t, uint32_t>(hist, 256 * n_tiles, offs, 256 * n_tiles, tile_sums, st)) != HETA_OK) return e;
         hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo);
         HETA_LAUNCH_CHECK("sort_scatter_kernel");
         std::swap(ki, ko);
@@ -224,6 +232,21 @@ heta_status radix_sort_pairs(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp,
     *keys_res = ki;
     *vals_res = vi;
     return HETA_OK;
+}
+
+heta_status radix_sort_pairs(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n, int bits,
+                             uint32_t **keys_res, uint32_t **vals_res, Scratch &scr, hipStream_t st)
+{
+    *keys_res = keys;
+    *vals_res = vals;
+    if (n <= 1 || bits <= 0) return HETA_OK;
+    const int64_t n_tiles = (n + kSortTile - 1) / kSortTile;
+    uint32_t *hist = nullptr, *offs = nullptr, *tile_sums = nullptr;
+    heta_status e;
+    if ((e = scr.get(&hist, static_cast<size_t>(256 * n_tiles))) != HETA_OK) return e;
+    if ((e = scr.get(&offs, static_cast<size_t>(256 * n_tiles))) != HETA_OK) return e;
+    if ((e = scr.get(&tile_sums, static_cast<size_t>((256 * n_tiles + kScanTile - 1) / kScanTile))) != HETA_OK) return e;
+    return radix_sort_pairs_with(keys, vals, keys_tmp, vals_tmp, n, bits, keys_res, vals_res, hist, offs, tile_sums, st);
 }
 
 // ---- validation of a device CSR ---------------------------------------------------------------------------
@@ -493,7 +516,24 @@ heta_status transpose_on_device(const Schedule &csr, int64_t n_src, Schedule &cs
 }
 
 // ---- the scan and the sort for other translation units (the neighbour sampler) ---------------------------
-// Both are complete (stream synchronised) when they return, because their scratch is released on return.
+// Asynchronous forms with caller-provided scratch (sizes from the two helpers, in elements):
+int64_t scan_scratch_elems(int64_t n_out) { return (n_out + kScanTile - 1) / kScanTile; }
+int64_t sort_hist_elems(int64_t n) { return 256 * ((n + kSortTile - 1) / kSortTile); }
+
+heta_status device_exclusive_scan_i64_async(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, int64_t *tile_sums,
+                                            hipStream_t st)
+{
+    return exclusive_scan_with<int64_t, int64_t>(in, n_in, out, n_out, tile_sums, st);
+}
+
+heta_status device_sort_pairs_u32_async(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n,
+                                        int64_t key_limit, uint32_t **keys_res, uint32_t **vals_res, uint32_t *hist, uint32_t *offs,
+                                        uint32_t *tile_sums, hipStream_t st)
+{
+    return radix_sort_pairs_with(keys, vals, keys_tmp, vals_tmp, n, bits_for(key_limit), keys_res, vals_res, hist, offs, tile_sums, st);
+}
+
+// The synchronous forms are complete (stream synchronised) when they return, because their scratch is released on return.
 heta_status device_exclusive_scan_i64(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, hipStream_t st)
 {
     Scratch scr;

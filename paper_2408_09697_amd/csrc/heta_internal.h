@@ -129,6 +129,16 @@ heta_status device_exclusive_scan_i64(const int64_t *in, int64_t n_in, int64_t *
 heta_status device_sort_pairs_u32(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n,
                                   int64_t key_limit, uint32_t **keys_res, uint32_t **vals_res, hipStream_t st);
 
+// Asynchronous forms with caller-provided scratch: tile_sums of scan_scratch_elems(n_out) elements; hist and offs of
+// sort_hist_elems(n) elements each and tile_sums of scan_scratch_elems(sort_hist_elems(n)) elements.
+int64_t scan_scratch_elems(int64_t n_out);
+int64_t sort_hist_elems(int64_t n);
+heta_status device_exclusive_scan_i64_async(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, int64_t *tile_sums,
+                                            hipStream_t st);
+heta_status device_sort_pairs_u32_async(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n,
+                                        int64_t key_limit, uint32_t **keys_res, uint32_t **vals_res, uint32_t *hist, uint32_t *offs,
+                                        uint32_t *tile_sums, hipStream_t st);
+
 // Short-lived device scratch from a recycling pool (blocks up to 16 MiB; larger ones are plain hipMalloc).
 // scratch_free requires the block to be idle: synchronise first.
 hipError_t scratch_alloc(void **out, size_t bytes);

@@ -118,7 +118,7 @@ template <typename T> struct DevBuf {
     ~DevBuf()
     {
         if (!p) return;
-        (void)hipDeviceSynchronize();
+        (void)hipDeviceSynchronize(); // a no-op wait after the entry point's own synchronisation; covers error paths
         scratch_free(p);
     }
     heta_status alloc(size_t n)
@@ -156,16 +156,21 @@ heta_status heta_sample_neighbors(const heta_graph *g, int32_t rel, const int64_
         HETA_HIP(hipStreamSynchronize(st));
         return HETA_OK;
     }
-    DevBuf<int64_t> cnt;
+    // count -> scan -> fill -> counts to the host, all asynchronous; one synchronisation at the end
+    DevBuf<int64_t> cnt, tsum;
     DevBuf<int> bad;
     heta_status e;
     if ((e = cnt.alloc(static_cast<size_t>(n_dst))) != HETA_OK) return e;
+    if ((e = tsum.alloc(static_cast<size_t>(scan_scratch_elems(n_dst + 1)))) != HETA_OK) return e;
     if ((e = bad.alloc(1)) != HETA_OK) return e;
     HETA_HIP(hipMemsetAsync(bad.p, 0, sizeof(int), st));
     hipLaunchKernelGGL(sample_count_kernel, dim3((unsigned)((n_dst + 255) / 256)), dim3(256), 0, st, r.csr.d_ptr, r.n_dst, dst_ids,
                        n_dst, (int)fanout, cnt.p, bad.p);
     HETA_LAUNCH_CHECK("sample_count_kernel");
-    if ((e = device_exclusive_scan_i64(cnt.p, n_dst, rowptr, n_dst + 1, st)) != HETA_OK) return e;
+    if ((e = device_exclusive_scan_i64_async(cnt.p, n_dst, rowptr, n_dst + 1, tsum.p, st)) != HETA_OK) return e;
+    hipLaunchKernelGGL(sample_fill_kernel, dim3((unsigned)((n_dst + 3) / 4)), dim3(256), 0, st, r.csr.d_ptr, r.csr.d_idx, r.n_dst,
+                       dst_ids, n_dst, (int)fanout, (unsigned long long)seed, rowptr, src_ids);
+    HETA_LAUNCH_CHECK("sample_fill_kernel");
     int h_bad = 0;
     HETA_HIP(hipMemcpyAsync(&h_bad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st));
     HETA_HIP(hipMemcpyAsync(n_sampled, rowptr + n_dst, sizeof(int64_t), hipMemcpyDeviceToHost, st));
@@ -174,12 +179,6 @@ heta_status heta_sample_neighbors(const heta_graph *g, int32_t rel, const int64_
         *n_sampled = 0;
         return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: a destination id lies outside [0, %lld)", (long long)r.n_dst);
     }
-    if (*n_sampled > 0) {
-        hipLaunchKernelGGL(sample_fill_kernel, dim3((unsigned)((n_dst + 3) / 4)), dim3(256), 0, st, r.csr.d_ptr, r.csr.d_idx, r.n_dst,
-                           dst_ids, n_dst, (int)fanout, (unsigned long long)seed, rowptr, src_ids);
-        HETA_LAUNCH_CHECK("sample_fill_kernel");
-    }
-    HETA_HIP(hipStreamSynchronize(st)); // the scratch above is released on return
     return HETA_OK;
 }
 
@@ -201,14 +200,19 @@ heta_status heta_unique_relabel(int32_t n_lists, const int64_t *const *lists, co
     if (total >= (int64_t(1) << 31)) return fail(HETA_ERR_UNSUPPORTED, "heta_unique_relabel: more than 2^31 ids");
     if (!unique_ids) return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: null unique_ids");
     hipStream_t st = as_stream(hip_stream);
-    DevBuf<uint32_t> k0, v0, k1, v1;
-    DevBuf<int64_t> head, before;
+    // gather -> sort -> head flags -> scan -> scatter -> copies, all asynchronous; one synchronisation at the end
+    DevBuf<uint32_t> k0, v0, k1, v1, hist, offs, tsum32;
+    DevBuf<int64_t> head, before, tsum64;
     DevBuf<int32_t> local_all;
     DevBuf<int> bad;
     heta_status e;
     const size_t N = static_cast<size_t>(total);
+    const size_t n_hist = static_cast<size_t>(sort_hist_elems(total));
     if ((e = k0.alloc(N)) != HETA_OK || (e = v0.alloc(N)) != HETA_OK || (e = k1.alloc(N)) != HETA_OK ||
-        (e = v1.alloc(N)) != HETA_OK || (e = head.alloc(N)) != HETA_OK || (e = before.alloc(N + 1)) != HETA_OK ||
+        (e = v1.alloc(N)) != HETA_OK || (e = hist.alloc(n_hist)) != HETA_OK || (e = offs.alloc(n_hist)) != HETA_OK ||
+        (e = tsum32.alloc(static_cast<size_t>(scan_scratch_elems(static_cast<int64_t>(n_hist))))) != HETA_OK ||
+        (e = head.alloc(N)) != HETA_OK || (e = before.alloc(N + 1)) != HETA_OK ||
+        (e = tsum64.alloc(static_cast<size_t>(scan_scratch_elems(total + 1)))) != HETA_OK ||
         (e = local_all.alloc(N)) != HETA_OK || (e = bad.alloc(1)) != HETA_OK)
         return e;
     HETA_HIP(hipMemsetAsync(bad.p, 0, sizeof(int), st));
@@ -220,17 +224,14 @@ heta_status heta_unique_relabel(int32_t n_lists, const int64_t *const *lists, co
         HETA_LAUNCH_CHECK("gather_keys_kernel");
         off += lens[l];
     }
-    int h_bad = 0;
-    HETA_HIP(hipMemcpyAsync(&h_bad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st));
-    HETA_HIP(hipStreamSynchronize(st));
-    if (h_bad) return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: an id lies outside [0, %lld)", (long long)id_limit);
+    // an id outside the range is reported after the synchronisation; until then it is only a key like any other
     uint32_t *ks = nullptr, *vs = nullptr;
-    if ((e = device_sort_pairs_u32(k0.p, v0.p, k1.p, v1.p, total, id_limit, &ks, &vs, st)) != HETA_OK) return e;
+    if ((e = device_sort_pairs_u32_async(k0.p, v0.p, k1.p, v1.p, total, id_limit, &ks, &vs, hist.p, offs.p, tsum32.p, st)) != HETA_OK)
+        return e;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     hipLaunchKernelGGL(head_flag_kernel, dim3(blocks), dim3(256), 0, st, ks, total, head.p);
     HETA_LAUNCH_CHECK("head_flag_kernel");
-    if ((e = device_exclusive_scan_i64(head.p, total, before.p, total + 1, st)) != HETA_OK) return e;
-    HETA_HIP(hipMemcpyAsync(n_unique, before.p + total, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    if ((e = device_exclusive_scan_i64_async(head.p, total, before.p, total + 1, tsum64.p, st)) != HETA_OK) return e;
     hipLaunchKernelGGL(unique_scatter_kernel, dim3(blocks), dim3(256), 0, st, ks, vs, head.p, before.p, total, unique_ids,
                        local_all.p);
     HETA_LAUNCH_CHECK("unique_scatter_kernel");
@@ -240,7 +241,14 @@ heta_status heta_unique_relabel(int32_t n_lists, const int64_t *const *lists, co
         HETA_HIP(hipMemcpyAsync(local[l], local_all.p + off, static_cast<size_t>(lens[l]) * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
         off += lens[l];
     }
+    int h_bad = 0;
+    HETA_HIP(hipMemcpyAsync(&h_bad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st));
+    HETA_HIP(hipMemcpyAsync(n_unique, before.p + total, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     HETA_HIP(hipStreamSynchronize(st));
+    if (h_bad) {
+        *n_unique = 0;
+        return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: an id lies outside [0, %lld)", (long long)id_limit);
+    }
     return HETA_OK;
 }
 
