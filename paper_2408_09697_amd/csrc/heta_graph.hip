@@ -128,13 +128,41 @@ template <typename T>
 
 // Host-built relations are assembled in one host buffer and reach the device with one
 // allocation and one copy: byte offsets here, pointers once the device address is known.
+// The buffer is page-locked (a pageable source would be staged by the runtime at a fraction of the
+// link's rate, which was most of a mini-batch block's ingest time) and kept per thread for the next graph.
+struct PinnedRegion {
+    char *p = nullptr;
+    size_t cap = 0;
+};
+static thread_local PinnedRegion t_pinned; // never freed: it lives as long as the thread builds graphs
+
 struct HostPack {
-    std::vector<char> buf;
-    template <typename T> size_t add(const T *data, size_t n)
+    size_t size = 0;
+    bool failed = false;
+    const char *data() const { return t_pinned.p; }
+    // makes room for `need` bytes, keeping the first `size`
+    bool reserve(size_t need)
     {
-        const size_t off = (buf.size() + 255) / 256 * 256;
-        buf.resize(off + std::max<size_t>(n, 1) * sizeof(T));
-        if (n) std::memcpy(buf.data() + off, data, n * sizeof(T));
+        if (need <= t_pinned.cap) return true;
+        size_t cap = std::max<size_t>(std::max<size_t>(t_pinned.cap * 2, need), size_t(1) << 20);
+        void *q = nullptr;
+        if (hipHostMalloc(&q, cap, hipHostMallocDefault) != hipSuccess) {
+            failed = true;
+            return false;
+        }
+        if (size) std::memcpy(q, t_pinned.p, size);
+        if (t_pinned.p) (void)hipHostFree(t_pinned.p);
+        t_pinned.p = static_cast<char *>(q);
+        t_pinned.cap = cap;
+        return true;
+    }
+    template <typename T> size_t add(const T *data_in, size_t n)
+    {
+        const size_t off = (size + 255) / 256 * 256;
+        const size_t end = off + std::max<size_t>(n, 1) * sizeof(T);
+        if (!reserve(end)) return 0;
+        if (n) std::memcpy(t_pinned.p + off, data_in, n * sizeof(T));
+        size = end;
         return off;
     }
 };
@@ -235,14 +263,12 @@ static void destroy(heta_graph *g)
     for (auto &r : g->rels) {
         (void)hipFree(r.d_hub_slot);
         (void)hipFree(r.d_hub_rows);
-        if (r.d_arena) { // host-built: one allocation (the device is idle here)
-            scratch_free(r.d_arena);
-            continue;
-        }
+        if (r.host_built) continue; // its arrays live in the graph's arena
         free_schedule(r.csr);
         free_schedule(r.csc);
         (void)hipFree(r.d_inv_deg);
     }
+    scratch_free(g->d_arena); // the device is idle here
     (void)hipFree(g->d_ws);
     (void)hipFree(g->d_pack);
     (void)hipFree(g->d_attn);
@@ -289,7 +315,16 @@ static heta_status check_relation_args(const std::vector<heta_ntype> &ntypes, co
 constexpr int64_t kDeviceIngestMin = 1 << 17;
 static int g_ingest_mode = 0; // 0 = by size, 1 = host, 2 = device
 
-static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32_t index, bool on_device)
+// A host-built relation waits in the graph's host buffer until every relation is built; then one
+// allocation and one copy bring all of them to the device and the offsets become pointers.
+struct PendingRelation {
+    size_t rel;
+    ScheduleOffsets csr, csc;
+    size_t inv;
+};
+
+static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32_t index, bool on_device, HostPack &pack,
+                                   std::vector<PendingRelation> &pending)
 {
     g->rels.emplace_back();
     Relation &rel = g->rels.back(); // owned by g from here on: destroy(g) releases whatever was allocated
@@ -356,18 +391,31 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
             for (int64_t e = ptr[v]; e < ptr[v + 1]; ++e)
                 row[cursor[col[e]]++] = static_cast<int32_t>(v);
     }
-    HostPack pack;
-    ScheduleOffsets o_csr, o_csc;
+    PendingRelation pr;
+    pr.rel = g->rels.size() - 1;
     heta_status e;
-    if ((e = build_schedule_on_host(rel.csr, ptr, col, pack, o_csr)) != HETA_OK) return e;
-    if ((e = build_schedule_on_host(rel.csc, colptr.data(), row.data(), pack, o_csc)) != HETA_OK) return e;
-    const size_t o_inv = pack.add(inv_deg.data(), static_cast<size_t>(n_dst));
-    HETA_HIP(scratch_alloc(&rel.d_arena, pack.buf.size()));
-    HETA_HIP(hipMemcpy(rel.d_arena, pack.buf.data(), pack.buf.size(), hipMemcpyHostToDevice));
-    char *base = static_cast<char *>(rel.d_arena);
-    resolve(rel.csr, o_csr, base);
-    resolve(rel.csc, o_csc, base);
-    rel.d_inv_deg = reinterpret_cast<float *>(base + o_inv);
+    if ((e = build_schedule_on_host(rel.csr, ptr, col, pack, pr.csr)) != HETA_OK) return e;
+    if ((e = build_schedule_on_host(rel.csc, colptr.data(), row.data(), pack, pr.csc)) != HETA_OK) return e;
+    pr.inv = pack.add(inv_deg.data(), static_cast<size_t>(n_dst));
+    rel.host_built = true;
+    pending.push_back(pr);
+    return HETA_OK;
+}
+
+// one allocation and one copy for every host-built relation of the graph
+static heta_status upload_host_built(heta_graph *g, const HostPack &pack, const std::vector<PendingRelation> &pending)
+{
+    if (pending.empty()) return HETA_OK;
+    if (pack.failed) return fail(HETA_ERR_OOM, "heta_graph_create: page-locked host allocation failed");
+    HETA_HIP(scratch_alloc(&g->d_arena, pack.size));
+    HETA_HIP(hipMemcpy(g->d_arena, pack.data(), pack.size, hipMemcpyHostToDevice));
+    char *base = static_cast<char *>(g->d_arena);
+    for (const PendingRelation &pr : pending) {
+        Relation &rel = g->rels[pr.rel];
+        resolve(rel.csr, pr.csr, base);
+        resolve(rel.csc, pr.csc, base);
+        rel.d_inv_deg = reinterpret_cast<float *>(base + pr.inv);
+    }
     return HETA_OK;
 }
 
@@ -421,12 +469,19 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
     }
     try {
         g->rels.reserve(n_rels);
+        HostPack pack;
+        std::vector<PendingRelation> pending;
         for (int32_t i = 0; i < n_rels; ++i) {
-            heta_status st = ingest_relation(g, rels[i], i, on_device);
+            heta_status st = ingest_relation(g, rels[i], i, on_device, pack, pending);
             if (st != HETA_OK) {
                 destroy(g);
                 return st;
             }
+        }
+        heta_status st = upload_host_built(g, pack, pending);
+        if (st != HETA_OK) {
+            destroy(g);
+            return st;
         }
     } catch (const std::bad_alloc &) {
         destroy(g);

@@ -76,7 +76,7 @@ struct Relation {
     int32_t *d_hub_slot = nullptr; // [n_dst] position of a destination among the CSR schedule's hub rows, built on first use
     float *d_hub_rows = nullptr;   // aggregated hub rows of the fused forward, grown on demand
     size_t hub_rows_bytes = 0;
-    void *d_arena = nullptr;      // host-built relations: the one allocation every pointer above points into
+    bool host_built = false;      // its device arrays are slices of the graph's arena, not allocations of their own
 };
 
 } // namespace heta
@@ -85,6 +85,7 @@ struct heta_graph {
     int device = 0;
     std::vector<heta_ntype> ntypes;
     std::vector<heta::Relation> rels;
+    void *d_arena = nullptr;      // every host-built relation's arrays: one allocation, one copy
     // workspace for hub-row partials and split weight-gradient partials; grown on demand
     void *d_ws = nullptr;
     size_t ws_bytes = 0;
