@@ -97,3 +97,34 @@ def test_project_shape_checks_happen_before_any_launch():
     assert lib.heta_project(4, one, 7, 8, 8, one, 0, 8, 8, 0, None, one, 0, 8, 0.0, None) == hb.HETA_ERR_INVALID_ARG  # dtype
     assert lib.heta_project(4, one + 2, 0, 8, 8, one, 0, 8, 8, 0, None, one, 0, 8, 0.0, None) == hb.HETA_ERR_INVALID_ARG  # align
     assert lib.heta_act_bwd(4, 8, 5, one, 8, one, 8, one, 8, None) == hb.HETA_ERR_INVALID_ARG
+
+
+def test_null_arguments_of_the_later_entry_points_fail_cleanly():
+    """Attention, sampler, fused forward, optimizer: a null handle or pointer is refused on the host."""
+    import ctypes
+    lib = hb.load_library()
+    vp, i32, i64, f32, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_uint64
+    lib.heta_attn_score.argtypes = [vp, i32, i64, i64, i32, vp, i32, i32, vp, vp]
+    assert lib.heta_attn_score(None, 0, 8, 4, 8, None, 2, 1, None, None) == hb.HETA_ERR_INVALID_ARG
+    lib.heta_attn_score_bwd.argtypes = [vp, vp, i32, i64, i64, i32, vp, i32, i32, vp, vp, i64, f32, vp, vp]
+    assert lib.heta_attn_score_bwd(None, None, 0, 8, 4, 8, None, 2, 1, None, None, 0, 0.0, None, None) == hb.HETA_ERR_INVALID_ARG
+    lib.heta_rel_attn_fwd.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, f32, vp, i32, i64, f32, vp, vp, vp, i64, vp]
+    assert lib.heta_rel_attn_fwd(None, 0, None, 0, 8, 8, 2, None, None, 0.2, None, 0, 8, 0.0, None, None, None, 0, None) \
+        == hb.HETA_ERR_INVALID_ARG
+    lib.heta_rel_attn_bwd.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, f32, vp, vp, vp, vp, i32, i64, vp, i64, vp, i64,
+                                      vp, vp, vp]
+    assert lib.heta_rel_attn_bwd(None, 0, None, 0, 8, 8, 2, None, None, 0.2, None, None, None, None, 0, 8, None, 8, None, 8,
+                                 None, None, None) == hb.HETA_ERR_INVALID_ARG
+    lib.heta_sample_neighbors.argtypes = [vp, i32, vp, i64, i32, u64, vp, vp, vp, vp]
+    assert lib.heta_sample_neighbors(None, 0, None, 4, 5, 1, None, None, None, None) == hb.HETA_ERR_INVALID_ARG
+    lib.heta_unique_relabel.argtypes = [i32, vp, vp, i64, vp, vp, vp, vp]
+    assert lib.heta_unique_relabel(1, None, None, 10, None, None, None, None) == hb.HETA_ERR_INVALID_ARG
+    n_unique = ctypes.c_int64(-1)
+    assert lib.heta_unique_relabel(0, None, None, 10, None, ctypes.byref(n_unique), None, None) == hb.HETA_OK and n_unique.value == 0
+    assert lib.heta_unique_relabel(0, None, None, (1 << 31) + 1, None, ctypes.byref(n_unique), None, None) == hb.HETA_ERR_SHAPE
+    lib.heta_cross_rel_aggregate_project.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, i64, vp]
+    assert lib.heta_cross_rel_aggregate_project(None, 0, 1, None, 0, None, 0, None, None, None, None, None, None, 8, 0, None, 8,
+                                                None) == hb.HETA_ERR_INVALID_ARG
+    lib.heta_sparse_adam.argtypes = [vp, i32, i64, i32, i64, vp, vp, i64, vp, i64, vp, i64, f32, f32, f32, f32, i64, vp]
+    assert lib.heta_sparse_adam(None, 0, 8, 8, 4, None, None, 8, None, 2, None, 8, 1e-3, 0.9, 0.999, 1e-8, 1, None) \
+        == hb.HETA_ERR_INVALID_ARG
