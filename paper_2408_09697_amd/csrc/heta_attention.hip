@@ -65,6 +65,8 @@ struct SweepParams {
                           // edges with a positive logit (FWD, if non-null)
     float dot_shift;      // BWD_CSR: corr = dot * (sum of gates - dot_shift)
     float *corr;          // [rows][K]  the scalar term subtracted from the row's score gradient (BWD_*)
+    const float *nbr_pack; // BWD_CSC: [dst][4][K] = the destination's er, smax, sinv, dot side by side (one cache line
+                          // per neighbour instead of four gathers)
     float *part;          // hub chunks: [n_hub_chunks][K][2] partial statistics
     float *hub_stat;      // hub rows (FWD): [n_hub_rows][K][2] = shift, 1/denominator
 };
@@ -97,12 +99,15 @@ __device__ __forceinline__ void visit(const SweepParams &p, int64_t e, int k0, c
 {
     const int64_t id = p.sidx[e];
     float x[KT];
-    loadk<KT>(p.nbr_a + id * p.K + k0, x);
     float mv[KT], iv[KT], dv[KT];
     if (PH == PH_BWD_SRC) {
-        loadk<KT>(p.smax + id * p.K + k0, mv);
-        loadk<KT>(p.sinv + id * p.K + k0, iv);
-        loadk<KT>(p.dot + id * p.K + k0, dv);
+        const float *pk = p.nbr_pack + id * 4 * p.K + k0;
+        loadk<KT>(pk, x);
+        loadk<KT>(pk + p.K, mv);
+        loadk<KT>(pk + 2 * p.K, iv);
+        loadk<KT>(pk + 3 * p.K, dv);
+    } else {
+        loadk<KT>(p.nbr_a + id * p.K + k0, x);
     }
     float a[KT], gt[KT];
 #pragma unroll
@@ -165,7 +170,47 @@ __global__ void __launch_bounds__(256) attn_rows_kernel(SweepParams p)
     const int64_t e0 = p.sptr[q], e1 = p.sptr[q + 1];
     float ar[KT], acc[KT], m[KT], inv[KT];
     loadk<KT>(p.row_a + row * p.K + k0, ar);
-    if (OP == SWEEP_FWD) {
+    if (OP == SWEEP_FWD && W == 1 && e1 - e0 <= 4 && e1 > e0) {
+        // up to four edges (most rows of a power-law graph): the logits stay in registers, one pass
+        const int n = static_cast<int>(e1 - e0);
+        float sc[4][KT];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j < n) {
+                loadk<KT>(p.nbr_a + static_cast<int64_t>(p.sidx[e0 + j]) * p.K + k0, sc[j]);
+#pragma unroll
+                for (int k = 0; k < KT; ++k) sc[j][k] = lrelu(sc[j][k] + ar[k], p.slope);
+            } else {
+#pragma unroll
+                for (int k = 0; k < KT; ++k) sc[j][k] = -INFINITY;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            m[k] = fmaxf(fmaxf(sc[0][k], sc[1][k]), fmaxf(sc[2][k], sc[3][k]));
+            float den = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) den += j < n ? expf(sc[j][k] - m[k]) : 0.f; // same order as the general path
+            inv[k] = 1.f / den;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j < n) {
+                float a[KT], gt[KT];
+#pragma unroll
+                for (int k = 0; k < KT; ++k) {
+                    a[k] = expf(sc[j][k] - m[k]) * inv[k];
+                    gt[k] = sc[j][k] > 0.f ? a[k] : 0.f; // LeakyReLU keeps the sign of the logit
+                }
+                storek<KT>(p.alpha + (e0 + j) * p.K + k0, a);
+                if (p.gate) storek<KT>(p.gate + (e0 + j) * p.K + k0, gt);
+            }
+        }
+        if (p.smax) {
+            storek<KT>(p.smax + row * p.K + k0, m);
+            storek<KT>(p.sinv + row * p.K + k0, inv);
+        }
+    } else if (OP == SWEEP_FWD) {
 #pragma unroll
         for (int k = 0; k < KT; ++k) m[k] = -INFINITY;
         sweep_range<W, KT, PH_MAX>(p, e0, e1, lane, k0, ar, nullptr, nullptr, m);
@@ -323,6 +368,21 @@ __global__ void __launch_bounds__(256) attn_hub_alpha_kernel(SweepParams p)
     sweep_range<64, KT, PH_ALPHA>(p, c.e0, c.e0 + c.len, lane, k0, ar, m, inv, nullptr);
 }
 
+// pack[v][0..3][K] = er[v], smax[v], sinv[v], dot[v]
+__global__ void __launch_bounds__(256) attn_pack_kernel(const float *er, const float *smax, const float *sinv, const float *dot,
+                                                        int64_t n, int K, float *pack)
+{
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (t >= n * K) return;
+    const int64_t v = t / K;
+    const int k = static_cast<int>(t - v * K);
+    float *o = pack + v * 4 * K + k;
+    o[0] = er[t];
+    o[K] = smax[t];
+    o[2 * K] = sinv[t];
+    o[3 * K] = dot[t];
+}
+
 inline size_t hub_scratch_bytes(const Schedule &s, int K)
 {
     return static_cast<size_t>(s.n_hub_chunks + s.n_hub_rows) * K * 2 * sizeof(float);
@@ -380,7 +440,7 @@ heta_status launch_sweeps(const Schedule &s, SweepParams p, float *hub_scratch, 
     // KT consecutive heads per thread need 4*KT-byte aligned score rows
     const uintptr_t all = reinterpret_cast<uintptr_t>(p.row_a) | reinterpret_cast<uintptr_t>(p.nbr_a) |
                           reinterpret_cast<uintptr_t>(p.smax) | reinterpret_cast<uintptr_t>(p.sinv) |
-                          reinterpret_cast<uintptr_t>(p.dot) | reinterpret_cast<uintptr_t>(p.alpha) |
+                          reinterpret_cast<uintptr_t>(p.dot) | reinterpret_cast<uintptr_t>(p.nbr_pack) | reinterpret_cast<uintptr_t>(p.alpha) |
                           reinterpret_cast<uintptr_t>(p.gate) | reinterpret_cast<uintptr_t>(p.corr);
     if (p.K % 4 == 0 && all % 16 == 0) return launch_sweeps_kt<4, OP>(s, p, st);
     if (p.K % 2 == 0 && all % 8 == 0) return launch_sweeps_kt<2, OP>(s, p, st);
@@ -671,60 +731,54 @@ __global__ void __launch_bounds__(256) attn_score_bwd_param_kernel(const T *x, i
 
 // the same, four columns per lane and four row groups per workgroup (rows 16 / 8-byte aligned, heads a
 // multiple of four columns wide); the row groups are added in order through LDS
-template <typename T>
+// KH = 0: per head (one accumulator per column); KH > 0: every head uses the whole row, K <= KH accumulators per column
+template <typename T, int KH>
 __global__ void __launch_bounds__(256) attn_score_bwd_param_vec_kernel(const T *x, int64_t ld_x, const float *ds, int64_t n,
-                                                                       int d, int K, int F, int per_head, float *part)
+                                                                       int d, int K, int F, float *part)
 {
+    constexpr int NA = KH == 0 ? 1 : KH;
     __shared__ float4 red[4][64];
     const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
     const int j = (blockIdx.y * 64 + lane) * 4;
     const int64_t slab = blockIdx.x;
     const int64_t i0 = slab * kSlabRows, i1 = min(n, i0 + kSlabRows);
     const bool live = j < d;
-    const int nk = per_head ? 1 : K;
-    const int kh = per_head && live ? j / F : 0;
-    float acc[kMaxHeads][4];
+    const int nk = KH == 0 ? 1 : K;
+    const int kh = KH == 0 && live ? j / F : 0;
+    float acc[NA][4];
 #pragma unroll
-    for (int k = 0; k < kMaxHeads; ++k) acc[k][0] = acc[k][1] = acc[k][2] = acc[k][3] = 0.f;
+    for (int k = 0; k < NA; ++k) acc[k][0] = acc[k][1] = acc[k][2] = acc[k][3] = 0.f;
     if (live) {
-        constexpr int U = 8; // rows in flight per row group
+        constexpr int U = KH > 4 ? 4 : 8; // rows in flight per row group
         for (int64_t ib = i0 + rg; ib < i1; ib += 4 * U) {
-            float xv[U][4], sv[U];
+            float xv[U][4], sv[U][NA];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t i = ib + 4 * u;
                 if (i < i1) {
                     ldv<T, 4>(x + i * ld_x + j, xv[u]);
-                    sv[u] = per_head ? ds[i * K + kh] : 0.f;
+                    if (KH == 0) {
+                        sv[u][0] = ds[i * K + kh];
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < NA; ++k) sv[u][k] = k < K ? ds[i * K + k] : 0.f;
+                    }
                 } else {
                     xv[u][0] = xv[u][1] = xv[u][2] = xv[u][3] = 0.f;
-                    sv[u] = 0.f;
+#pragma unroll
+                    for (int k = 0; k < NA; ++k) sv[u][k] = 0.f;
                 }
             }
-            if (per_head) {
 #pragma unroll
-                for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) acc[0][c] = fmaf(sv[u], xv[u][c], acc[0][c]);
-            } else {
+                for (int k = 0; k < NA; ++k)
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t i = ib + 4 * u;
-                    if (i < i1) {
-#pragma unroll
-                        for (int k = 0; k < kMaxHeads; ++k)
-                            if (k < K) {
-                                const float sk = ds[i * K + k];
-#pragma unroll
-                                for (int c = 0; c < 4; ++c) acc[k][c] = fmaf(sk, xv[u][c], acc[k][c]);
-                            }
-                    }
-                }
-            }
+                    for (int c = 0; c < 4; ++c) acc[k][c] = fmaf(sv[u][k], xv[u][c], acc[k][c]);
         }
     }
 #pragma unroll
-    for (int k = 0; k < kMaxHeads; ++k) {
+    for (int k = 0; k < NA; ++k) {
         if (k < nk) { // uniform
             red[rg][lane] = make_float4(acc[k][0], acc[k][1], acc[k][2], acc[k][3]);
             __syncthreads();
@@ -862,20 +916,26 @@ heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int
             ProfScope prof("attn_score_bwd_param_kernel", st, static_cast<double>(n) * (d * dtype_size(dt) + 4.0 * heads), 0);
             const dim3 grid((unsigned)n_slabs, (d + 255) / 256);
             const bool vec4 = d % 4 == 0 && F % 4 == 0 && ld_x % 4 == 0 && reinterpret_cast<uintptr_t>(x) % (4 * dtype_size(dt)) == 0;
-            if (dt == HETA_F32) {
-                if (vec4)
-                    hipLaunchKernelGGL((attn_score_bwd_param_vec_kernel<float>), grid, dim3(256), 0, st, static_cast<const float *>(x),
-                                       ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
-                else
-                    hipLaunchKernelGGL((attn_score_bwd_param_kernel<float>), grid, dim3(256), 0, st, static_cast<const float *>(x),
-                                       ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
+            if (vec4) {
+#define HETA_PARAM_VEC(TT, KH)                                                                                          \
+    hipLaunchKernelGGL((attn_score_bwd_param_vec_kernel<TT, KH>), grid, dim3(256), 0, st, static_cast<const TT *>(x), ld_x, \
+                       dscore, n, (int)d, (int)heads, F, part)
+                if (dt == HETA_F32) {
+                    if (per_head) HETA_PARAM_VEC(float, 0);
+                    else if (heads <= 4) HETA_PARAM_VEC(float, 4);
+                    else HETA_PARAM_VEC(float, 16);
+                } else {
+                    if (per_head) HETA_PARAM_VEC(bf16_t, 0);
+                    else if (heads <= 4) HETA_PARAM_VEC(bf16_t, 4);
+                    else HETA_PARAM_VEC(bf16_t, 16);
+                }
+#undef HETA_PARAM_VEC
+            } else if (dt == HETA_F32) {
+                hipLaunchKernelGGL((attn_score_bwd_param_kernel<float>), grid, dim3(256), 0, st, static_cast<const float *>(x), ld_x,
+                                   dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
             } else {
-                if (vec4)
-                    hipLaunchKernelGGL((attn_score_bwd_param_vec_kernel<bf16_t>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(x),
-                                       ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
-                else
-                    hipLaunchKernelGGL((attn_score_bwd_param_kernel<bf16_t>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(x),
-                                       ld_x, dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
+                hipLaunchKernelGGL((attn_score_bwd_param_kernel<bf16_t>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(x), ld_x,
+                                   dscore, n, (int)d, (int)heads, F, per_head ? 1 : 0, part);
             }
             HETA_LAUNCH_CHECK("attn_score_bwd_param_kernel");
             hipLaunchKernelGGL(attn_slab_sum_kernel, dim3((unsigned)((elems + 63) / 64)), dim3(1024), 0, st, part, n_slabs, elems, dvec);
@@ -951,7 +1011,8 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     const int64_t ld_r = (static_cast<int64_t>(d) + 3) / 4 * 4;
     const size_t r_bytes = round256(static_cast<size_t>(o_pos ? r.n_src : std::max(r.n_dst, r.n_src)) * ld_r * sizeof(float));
     const size_t hub_bytes = round256(std::max(hub_scratch_bytes(r.csr, K), hub_scratch_bytes(r.csc, K)));
-    e = ensure_attn(g, 2 * w_bytes + 2 * dst_bytes + src_bytes + r_bytes + hub_bytes);
+    const size_t pack_bytes = 4 * dst_bytes;
+    e = ensure_attn(g, 2 * w_bytes + 2 * dst_bytes + src_bytes + r_bytes + hub_bytes + pack_bytes);
     if (e != HETA_OK) return e;
     char *base = static_cast<char *>(g->d_attn);
     float *w_alpha = reinterpret_cast<float *>(base);
@@ -961,6 +1022,7 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     float *corr_s = reinterpret_cast<float *>(base + 2 * w_bytes + 2 * dst_bytes);
     float *R = reinterpret_cast<float *>(base + 2 * w_bytes + 2 * dst_bytes + src_bytes);
     float *hub_scratch = reinterpret_cast<float *>(base + 2 * w_bytes + 2 * dst_bytes + src_bytes + r_bytes);
+    float *nbr_pack = reinterpret_cast<float *>(base + 2 * w_bytes + 2 * dst_bytes + src_bytes + r_bytes + hub_bytes);
 
     // dot[v, k] = <g[v, k, :], o[v, k, :]>
     DotParams dp{};
@@ -1022,8 +1084,15 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
 
     // Source side: alpha and gate per CSC slot; one pass over the gathered gradient rows gives both
     // dz[u] = sum_e alpha_e g[v_e] and R[u] = sum_e gate_e g[v_e]; del = <z, R> - sum_e gate_e dot[v_e].
+    if (r.n_dst > 0) {
+        const int64_t total = r.n_dst * K;
+        hipLaunchKernelGGL(attn_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, er, smax, sinv, dot, r.n_dst, K,
+                           nbr_pack);
+        HETA_LAUNCH_CHECK("attn_pack_kernel");
+    }
     sp.row_a = el;
     sp.nbr_a = er;
+    sp.nbr_pack = nbr_pack;
     sp.alpha = w_alpha;
     sp.gate = w_gate;
     sp.corr = corr_s;
