@@ -248,3 +248,27 @@ def test_rgat_layer_on_a_sampled_block():
         if x.shape[0]:
             assert_rows_close(host(dH0[t]), x, 1e-4, f"dH0[{t}]")
     hg.destroy()
+
+
+def test_attention_is_bitwise_reproducible_run_to_run():
+    """No atomics anywhere: two runs on a relation with hub rows give identical bits, forward and backward."""
+    G = _relation_case("skew_dst", 2000, 3000, 60000)
+    r = G.relations[0]
+    g = rng.stream("tests", "attn/repro")
+    d, heads = 128, 4
+    z = up(g.standard_normal((2000, d)))
+    el, er = up(2.0 * g.standard_normal((2000, heads))), up(2.0 * g.standard_normal((3000, heads)))
+    go = up(g.standard_normal((3000, d)))
+    graph = heta.heta_graph_create([(2000, 4, 0), (3000, 4, 0)], [(0, 1, r.rowptr, r.col)])
+    runs = []
+    for _ in range(2):
+        out, pos = torch.empty((3000, d), device="cuda"), torch.empty((3000, d), device="cuda")
+        smax, sinv = torch.empty((3000, heads), device="cuda"), torch.empty((3000, heads), device="cuda")
+        dz, d_el, d_er = torch.empty((2000, d), device="cuda"), torch.empty((2000, heads), device="cuda"), torch.empty((3000, heads), device="cuda")
+        heta.heta_rel_attn_fwd(graph, 0, z, el, er, 0.2, out, smax=smax, sinv=sinv, out_pos=pos)
+        heta.heta_rel_attn_bwd(graph, 0, z, el, er, 0.2, smax, sinv, out, go, dz, d_el, d_er, o_pos=pos)
+        torch.cuda.synchronize()
+        runs.append((out, pos, smax, sinv, dz, d_el, d_er))
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
+    graph.destroy()
