@@ -89,7 +89,7 @@ def _relation_case(kind, n_src, n_dst, n_edges):
 
 @pytest.mark.parametrize("kind,n_src,n_dst,n_edges", [("uniform", 700, 900, 6000), ("skew_dst", 2000, 3000, 60000),
                                                        ("skew_src", 2500, 1800, 50000), ("uniform", 5, 6, 0)])
-@pytest.mark.parametrize("d,heads", [(64, 4), (256, 1), (24, 4), (520, 2), (128, 16)])
+@pytest.mark.parametrize("d,heads", [(64, 4), (256, 1), (24, 4), (520, 2), (128, 16), (48, 3)])
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
 @pytest.mark.parametrize("saved_pos", [True, False])
 def test_rel_attn_forward_and_backward(kind, n_src, n_dst, n_edges, d, heads, storage, saved_pos):
