@@ -722,3 +722,164 @@ def test_sample_blocks_link_up():
             assert ptr.size == n_dst + 1 and ptr[-1] == loc.size and np.all(np.diff(ptr) <= fanout)
             if loc.size:
                 assert loc.max() < b["src_ids"][s].size
+
+
+# ---- meta-partitioning (Section 5, Algorithm 2) ---------------------------------------------------
+
+import itertools
+
+from oracle import metapartition as omp
+
+
+def _read_metapartition_example():
+    types, rels, out = {}, [], {}
+    for line in open(os.path.join(GOLDEN, "metapartition_example.txt")):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "type":
+            types[f[1]] = (len(types), int(f[2]))
+        elif f[0] == "rel":
+            rels.append((f[1], types[f[2]][0], types[f[3]][0], int(f[4])))
+        else:
+            out[f[0]] = [float(x) for x in f[1:]]
+    return types, rels, out
+
+
+def test_metapartition_reproduces_the_papers_worked_example():
+    types, rels, want = _read_metapartition_example()
+    tw = [w for _, w in sorted(types.values())]
+    pairs = [(s, t) for _, s, t, _ in rels]
+    rw = [w for *_, w in rels]
+    mp = omp.meta_partition(tw, pairs, rw, root=types["paper"][0], k=2, p=2)
+    names = [rels[i][0] for i in mp.sub_rel]
+    assert sorted(names) == ["cites", "rev_has_topic", "writes"]          # the root has three children
+    assert sorted(round(w / 1e6) for w in mp.sub_weight) == want["sub_weights_millions"]
+    heavy = int(np.argmax(mp.sub_weight))
+    assert names[heavy] == "cites"
+    light = [c for c in range(3) if c != heavy]
+    assert mp.sub_part[light[0]] == mp.sub_part[light[1]] != mp.sub_part[heavy]
+    for key, q, subs in (("partition_light_pair", mp.sub_part[light[0]], light), ("partition_heavy", mp.sub_part[heavy], [heavy])):
+        n_rel, nodes_m, edges_m = want[key]
+        assert sum(mp.rel_mask[q]) == n_rel
+        nodes = sum(tw[t] for t in range(len(tw)) if mp.type_mask[q][t])
+        assert round(nodes / 1e6, 1) == nodes_m
+        # the printed edge counts are those of the sub-metatrees' links before a repeated relation
+        # is dropped (the heavy partition holds "cites" twice: 25 million with it, 20 without)
+        assert round(sum(mp.sub_links[c] for c in subs) / 1e6) == edges_m
+    q = mp.sub_part[heavy]
+    assert round(sum(rw[i] for i in range(len(rw)) if mp.rel_mask[q][i]) / 1e6) == 20
+    assert sorted(rels[i][0] for i in range(len(rels)) if mp.rel_mask[q][i]) == ["cites", "rev_has_topic", "writes"]
+
+
+def _random_metagraph(seed, n_types, n_rels):
+    r = np.random.default_rng(seed)
+    pairs = [(int(r.integers(n_types)), int(r.integers(n_types))) for _ in range(n_rels)]
+    return pairs, [int(x) for x in r.integers(1, 1000, n_types)], [int(x) for x in r.integers(1, 5000, n_rels)]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_metatree_levels_count_the_walks(seed):
+    """Level l of the tree holds one vertex per walk of l relations from the root: e_root^T B^l 1,
+    B[t, s] = number of relations from s into t."""
+    pairs, _, _ = _random_metagraph(seed, 5, 9)
+    B = np.zeros((5, 5), dtype=np.int64)
+    for s, t in pairs:
+        B[t, s] += 1
+    for root in range(5):
+        tree = omp.build_metatree(pairs, root, 4)
+        for l in range(5):
+            walks = int(np.linalg.matrix_power(B, l)[root].sum())
+            assert sum(1 for v in tree if v.depth == l) == walks
+        for j, v in enumerate(tree[1:], 1):
+            s, t = pairs[v.via]
+            assert (v.ntype, tree[v.parent].ntype, v.depth) == (s, t, tree[v.parent].depth + 1) and v.parent < j
+
+
+def test_lpt_on_grahams_tight_instance_and_against_the_optimum():
+    # Graham 1969: 2m+1 jobs {2m-1, 2m-1, ..., m+1, m+1, m, m, m}; LPT ends at 4m-1, the optimum is 3m
+    part, sums = omp.lpt([5, 5, 4, 4, 3, 3, 3], 3)
+    assert sums == [11, 8, 8] and part == [0, 1, 2, 2, 0, 1, 0]
+    assert part[:2] == [0, 1] and part[2] == 2                  # heaviest first, lowest free index first
+    r = np.random.default_rng(3)
+    for _ in range(60):
+        n, p = int(r.integers(1, 8)), int(r.integers(1, 4))
+        w = [int(x) for x in r.integers(1, 30, n)]
+        part, sums = omp.lpt(w, p)
+        assert sorted(part + list(range(p)))[-1] < p and sum(sums) == sum(w)
+        assert all(sums[q] == sum(w[i] for i in range(n) if part[i] == q) for q in range(p))
+        best = min(max(sum(w[i] for i in range(n) if a[i] == q) for q in range(p)) for a in itertools.product(range(p), repeat=n))
+        assert best <= max(sums) <= (4.0 / 3.0 - 1.0 / (3 * p)) * best + 1e-9
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_metapartition_invariants_on_random_metagraphs(seed):
+    n_types, n_rels = 5, 8
+    pairs, tw, rw = _random_metagraph(100 + seed, n_types, n_rels)
+    for root, k, p in itertools.product(range(n_types), (1, 2, 3), (1, 2, 3)):
+        mp = omp.meta_partition(tw, pairs, rw, root, k, p)
+        into_root = [i for i, (s, t) in enumerate(pairs) if t == root]
+        assert mp.sub_rel == into_root
+        n_real = min(p, len(into_root))
+        assert sum(mp.part_weight) == sum(mp.sub_weight) and all(0 <= q < max(n_real, 1) for q in mp.sub_part)
+        # relations within k steps of the root (a plain frontier sweep): held by some partition; no others
+        reach, frontier = set(), {root}
+        for _ in range(k):
+            step = {i for i, (s, t) in enumerate(pairs) if t in frontier}
+            reach |= step
+            frontier = {pairs[i][0] for i in step}
+        held = {i for q in range(p) for i in range(n_rels) if mp.rel_mask[q][i]}
+        assert held == reach
+        for q in range(p):
+            rels_q = [i for i in range(n_rels) if mp.rel_mask[q][i]]
+            if q >= n_real:
+                assert (mp.replica_of[q] >= 0) == (n_real > 0)
+                continue
+            assert mp.replica_of[q] == -1 and mp.type_mask[q][root] == 1
+            # closed: both end types of every relation are in the partition, and no type is idle
+            ends = {root} | {x for i in rels_q for x in pairs[i]}
+            assert ends == {t for t in range(n_types) if mp.type_mask[q][t]}
+            # the aggregation path stays inside: every relation is reached from the root through the
+            # partition's own relations
+            got, frontier = set(), {root}
+            for _ in range(k):
+                step = {i for i in rels_q if pairs[i][1] in frontier}
+                got |= step
+                frontier = {pairs[i][0] for i in step}
+            assert got == set(rels_q)
+
+
+def test_metapartition_one_hop_closed_form_and_metapaths():
+    pairs = [(1, 0), (2, 0), (0, 0), (0, 1), (1, 0)]
+    tw, rw = [10, 20, 30], [1, 2, 3, 4, 5]
+    mp = omp.meta_partition(tw, pairs, rw, root=0, k=1, p=2)
+    assert mp.sub_rel == [0, 1, 2, 4]
+    assert mp.sub_weight == [10 + 20 + 1, 10 + 30 + 2, 10 + 3, 10 + 20 + 5]      # a self-loop counts its type once
+    # 42 -> 0, 35 -> 1, 31 -> 1 (35 < 42), 13 -> 0 (42 < 66)
+    assert mp.sub_part == [1, 0, 0, 1] and mp.part_weight == [42 + 13, 35 + 31]
+    # every walk of at most k relations given as a metapath = the breadth-first tree
+    k = 3
+    tree = omp.build_metatree(pairs, 0, k)
+    paths = []
+    for j in range(1, len(tree)):
+        path, at = [], j
+        while at > 0:
+            path.append(tree[at].via)
+            at = tree[at].parent
+        paths.append(path[::-1])
+    a = omp.meta_partition(tw, pairs, rw, 0, k, 2)
+    b = omp.meta_partition(tw, pairs, rw, 0, k, 2, metapaths=paths)
+    assert (a.sub_weight, a.sub_part, a.rel_mask, a.type_mask) == (b.sub_weight, b.sub_part, b.rel_mask, b.type_mask)
+    # two metapaths sharing their first relation make one sub-metatree
+    c = omp.meta_partition(tw, pairs, rw, 0, k, 2, metapaths=[[0, 3], [0, 3, 2], [2]])
+    assert c.sub_rel == [0, 2] and c.sub_weight == [10 + 20 + 1 + 4 + 3, 10 + 3]
+    with pytest.raises(ValueError):
+        omp.meta_partition(tw, pairs, rw, 0, k, 2, metapaths=[[3]])
+
+
+def test_metapartition_replicates_the_heaviest_partition_per_replica():
+    pairs = [(1, 0), (2, 0)]
+    mp = omp.meta_partition([0, 0, 0], pairs, [90, 40], root=0, k=1, p=5)
+    assert mp.part_weight == [90, 40, 0, 0, 0]
+    assert mp.replica_of == [-1, -1, 0, 0, 1]        # 90 vs 40; 45 vs 40; 30 vs 40
+    assert mp.rel_mask[2] == mp.rel_mask[0] == [1, 0] and mp.rel_mask[4] == [0, 1]
