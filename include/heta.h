@@ -330,6 +330,36 @@ heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_table, int32
                              const float *grad, int64_t ld_grad, float lr, float beta1, float beta2, float eps,
                              int64_t step, void *hip_stream);
 
+/* ---- meta-partitioning (Section 5, Algorithm 2): which relations a GPU (or machine) holds ---------
+ * Host-only: works on the weighted metagraph, touches no device.  All pointers are HOST arrays.
+ *   type_weight [n_types]: nodes per node type; rel_src, rel_dst, rel_weight [n_rels]: the relations
+ *   (messages flow src -> dst) and their edge counts; root: the target node type; k: number of layers
+ *   (depth of the metatree); p: number of partitions.
+ *   metapath_ptr [n_metapaths + 1] / metapath_rels: optional user-given metapaths as relation indices
+ *   listed from the root outwards (the first relation ends in `root`, each next one ends in the source
+ *   type of the one before); n_metapaths = 0 (pointers may be NULL): the metatree is the tree of all
+ *   walks of at most k relations from the root.
+ * Steps: metatree; one sub-metatree per child of the root (root + child + descendants), weighted by
+ * its node types (each once) plus its links (each per occurrence); longest-processing-time-first
+ * assignment (heaviest first, equal weights by lower relation index, to the partition with the smallest
+ * sum, equal sums to the lowest index); per partition the union of its sub-metatrees' relations and
+ * types.  With more partitions than sub-metatrees each further partition replicates the one with the
+ * largest weight per replica (replicas split the target nodes between them).
+ * Outputs (caller-allocated, overwritten):
+ *   *n_sub; sub_rel, sub_weight, sub_links, sub_part [capacity n_rels]: per sub-metatree the relation
+ *   from the root to its child, its weight, the link part of the weight, and its partition;
+ *   part_weight [p]: the assignment's sums (0 for replicas); replica_of [p]: -1 or the partition copied;
+ *   rel_mask [p * n_rels], type_mask [p * n_types]: 1 where partition q holds relation i / type t.
+ * HETA_ERR_INVALID_ARG for a null pointer, an index out of range, a negative weight, k < 1, p < 1 or a
+ * metapath that does not follow the metagraph; HETA_ERR_UNSUPPORTED if the metatree would exceed 2^22
+ * vertices. */
+heta_status heta_meta_partition(int32_t n_types, const int64_t *type_weight, int32_t n_rels, const int32_t *rel_src,
+                                const int32_t *rel_dst, const int64_t *rel_weight, int32_t root, int32_t k, int32_t p,
+                                int32_t n_metapaths, const int32_t *metapath_ptr, const int32_t *metapath_rels,
+                                int32_t *n_sub, int32_t *sub_rel, int64_t *sub_weight, int64_t *sub_links,
+                                int32_t *sub_part, int64_t *part_weight, int32_t *replica_of, uint8_t *rel_mask,
+                                uint8_t *type_mask);
+
 /* ---- measurement --------------------------------------------------------------------------------
  * With profiling on (process-wide), every kernel the library launches is bracketed by two HIP
  * events on the stream it runs on.  heta_profile_read waits for the outstanding events and

@@ -31,7 +31,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam", "heta_project_batch",
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
            "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel",
-           "heta_cross_rel_aggregate_project"]
+           "heta_cross_rel_aggregate_project", "heta_meta_partition"]
 
 
 class HetaError(RuntimeError):
@@ -141,6 +141,11 @@ class Graph:
 
     def n_dst(self, rel: int) -> int:
         return self.ntypes[self.rels[rel][1]][0]
+
+    def meta_partition(self, root: int, k: int, p: int, metapaths=None) -> dict:
+        """heta_meta_partition on this graph's own metagraph (nodes per type, edges per relation)."""
+        return heta_meta_partition([n for n, _, _ in self.ntypes], [s for s, _, _ in self.rels],
+                                   [t for _, t, _ in self.rels], [e for _, _, e in self.rels], root, k, p, metapaths)
 
     def destroy(self) -> None:
         if self._h is not None:
@@ -663,6 +668,50 @@ def heta_unique_relabel(lists: List[torch.Tensor], id_limit: int, stream=None):
                                  _dev(uniq, "unique_ids"), ctypes.byref(n_unique), ctypes.addressof(a_local),
                                  _stream(stream)))
     return uniq[:n_unique.value], local
+
+
+def heta_meta_partition(type_weight: Sequence[int], rel_src: Sequence[int], rel_dst: Sequence[int],
+                        rel_weight: Sequence[int], root: int, k: int, p: int,
+                        metapaths: Optional[Sequence[Sequence[int]]] = None) -> dict:
+    """Meta-partitioning of the weighted metagraph (host only, no device needed).  Returns a dict of
+    plain lists: sub_rel, sub_weight, sub_links, sub_part (per sub-metatree), part_weight, replica_of
+    (per partition), rel_mask [p][n_rels], type_mask [p][n_types]."""
+    n_types, n_rels = len(type_weight), len(rel_src)
+    if len(rel_dst) != n_rels or len(rel_weight) != n_rels:
+        raise HetaError(HETA_ERR_SHAPE, "rel_src, rel_dst and rel_weight must have one entry per relation")
+    i32, i64, u8 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint8
+    a_tw = (i64 * max(1, n_types))(*[int(x) for x in type_weight])
+    a_rs = (i32 * max(1, n_rels))(*[int(x) for x in rel_src])
+    a_rd = (i32 * max(1, n_rels))(*[int(x) for x in rel_dst])
+    a_rw = (i64 * max(1, n_rels))(*[int(x) for x in rel_weight])
+    paths = [list(m) for m in metapaths] if metapaths else []
+    ptr = [0]
+    for m in paths:
+        ptr.append(ptr[-1] + len(m))
+    flat = [int(i) for m in paths for i in m]
+    a_mp = (i32 * len(ptr))(*ptr)
+    a_mr = (i32 * max(1, len(flat)))(*flat)
+    n_sub = i32(0)
+    sub_rel, sub_part = (i32 * max(1, n_rels))(), (i32 * max(1, n_rels))()
+    sub_weight, sub_links = (i64 * max(1, n_rels))(), (i64 * max(1, n_rels))()
+    np_ = max(1, int(p))
+    part_weight, replica_of = (i64 * np_)(), (i32 * np_)()
+    rel_mask, type_mask = (u8 * max(1, np_ * n_rels))(), (u8 * max(1, np_ * n_types))()
+    L = load_library()
+    vp = ctypes.c_void_p
+    L.heta_meta_partition.argtypes = [i32, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, ctypes.POINTER(i32),
+                                      vp, vp, vp, vp, vp, vp, vp, vp]
+    _check(L.heta_meta_partition(n_types, ctypes.addressof(a_tw), n_rels, ctypes.addressof(a_rs), ctypes.addressof(a_rd),
+                                 ctypes.addressof(a_rw), int(root), int(k), int(p), len(paths), ctypes.addressof(a_mp),
+                                 ctypes.addressof(a_mr), ctypes.byref(n_sub), ctypes.addressof(sub_rel),
+                                 ctypes.addressof(sub_weight), ctypes.addressof(sub_links), ctypes.addressof(sub_part),
+                                 ctypes.addressof(part_weight), ctypes.addressof(replica_of), ctypes.addressof(rel_mask),
+                                 ctypes.addressof(type_mask)))
+    n = n_sub.value
+    return {"sub_rel": list(sub_rel[:n]), "sub_weight": list(sub_weight[:n]), "sub_links": list(sub_links[:n]),
+            "sub_part": list(sub_part[:n]), "part_weight": list(part_weight[:p]), "replica_of": list(replica_of[:p]),
+            "rel_mask": [list(rel_mask[q * n_rels:(q + 1) * n_rels]) for q in range(p)],
+            "type_mask": [list(type_mask[q * n_types:(q + 1) * n_types]) for q in range(p)]}
 
 
 def heta_ingest_force(mode: int) -> None:

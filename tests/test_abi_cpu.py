@@ -128,3 +128,7 @@ def test_null_arguments_of_the_later_entry_points_fail_cleanly():
     lib.heta_sparse_adam.argtypes = [vp, i32, i64, i32, i64, vp, vp, i64, vp, i64, vp, i64, f32, f32, f32, f32, i64, vp]
     assert lib.heta_sparse_adam(None, 0, 8, 8, 4, None, None, 8, None, 2, None, 8, 1e-3, 0.9, 0.999, 1e-8, 1, None) \
         == hb.HETA_ERR_INVALID_ARG
+    lib.heta_meta_partition.argtypes = [i32, vp, i32, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    assert lib.heta_meta_partition(2, None, 1, None, None, None, 0, 1, 1, 0, None, None, None, None, None, None, None, None,
+                                   None, None, None) == hb.HETA_ERR_INVALID_ARG
+    assert "null argument" in hb.heta_last_error()

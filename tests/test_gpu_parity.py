@@ -431,6 +431,37 @@ def test_layer_config1_relation_split_equals_whole():
     hg.destroy()
 
 
+def test_layer_config1_meta_partitions_sum_to_the_whole():
+    """The relation sets that the library's meta-partitioning deals to two partitions (Section 5), each run
+    as its own layer: the partial aggregations of the target type add up to the whole layer's
+    embeddings, each weight gradient is computed by exactly one partition, the table gradients add up."""
+    p = workloads.config1()
+    hg = make_graph(p)
+    mp = hg.meta_partition(root=0, k=1, p=2)
+    sets = [[i for i, m in enumerate(mask) if m] for mask in mp["rel_mask"]]
+    into_root = [i for i, (s, t, _) in enumerate(hg.rels) if t == 0]
+    assert sorted(sets[0] + sets[1]) == into_root and sets[0] and sets[1]
+    ref_f = oracle.layer_forward(p, rels=into_root)
+    ref_dW, ref_dH0, _ = oracle.layer_backward(p, ref_f, p.G, rels=into_root)
+    layers = [make_layer(p, hg, rels=s) for s in sets]
+    parts = [l.forward()[0] for l in layers]
+    tot = torch.zeros_like(parts[0])
+    heta.heta_cross_rel_reduce(hg, 0, parts, tot)
+    assert_rows_close(tot.cpu().numpy(), ref_f.H[0], 1e-4, "sum of the partitions' partial aggregations")
+    G = {0: torch.from_numpy(np.ascontiguousarray(p.G[0], dtype=np.float32)).cuda()}
+    dH0 = {}
+    for l, s in zip(layers, sets):
+        dW, dh, _ = l.backward(G)
+        for r in s:
+            assert_rows_close(dW[r].cpu().numpy(), ref_dW[r], 1e-4, f"dW[{r}]")
+        for t, g in dh.items():
+            dH0[t] = g.cpu().numpy().astype(np.float64) + dH0.get(t, 0.0)
+    assert sorted(dH0) == sorted(ref_dH0)
+    for t in dH0:
+        assert_rows_close(dH0[t], ref_dH0[t], 1e-4, f"dH0[{t}]")
+    hg.destroy()
+
+
 @pytest.mark.parametrize("mode", ["fused", "per_relation"])
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
 def test_layer_config3_scaled(storage, mode, gemm_path):
