@@ -472,7 +472,8 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     // second, nearly empty round.  Workgroups are dealt round-robin to the 8 XCDs (32 CUs each) and
     // the kernel keeps the `tiles` output tiles of one split on one XCD, so a split costs `tiles`
     // workgroup slots of its XCD: 2 resident 512-thread workgroups per CU (3 or 4 of 256 threads).
-    // Each split keeps at least 16 k-tiles.
+    // Each split keeps at least 4 k-tiles (a few thousand graph rows still spread over the chip: a
+    // workgroup's k-tiles are latency-bound when few workgroups run).
     const int64_t BK = in_dt == HETA_F32 ? 32 : 64;
     const int64_t k_tiles = (n_rows + BK - 1) / BK;
     const int64_t slots_per_xcd = 32 * (d_out > 128 ? 2 : (in_dt == HETA_F32 ? 3 : 4));
@@ -481,7 +482,7 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     for (int s = 0; s < n_seg; ++s) mt_max = std::max<int64_t>(mt_max, (d_in[s] + BM - 1) / BM);
     const int64_t slots_per_split = std::max<int64_t>(tiles, mt_max * ((d_out + BN - 1) / BN) * n_seg);
     const int64_t splits_per_xcd = std::max<int64_t>(1, slots_per_xcd / std::max<int64_t>(1, slots_per_split));
-    int64_t n_split = std::max<int64_t>(1, std::min<int64_t>((k_tiles + 15) / 16, 8 * splits_per_xcd));
+    int64_t n_split = std::max<int64_t>(1, std::min<int64_t>((k_tiles + 3) / 4, 8 * splits_per_xcd));
     const int64_t tiles_per_split = std::max<int64_t>(1, (k_tiles + n_split - 1) / n_split);
     n_split = std::max<int64_t>(1, (k_tiles + tiles_per_split - 1) / tiles_per_split);
     heta_status e = ensure_workspace(g, static_cast<size_t>(n_split) * out_elems * sizeof(float));

@@ -14,6 +14,43 @@ import torch
 from . import binding as hb
 
 
+def project_first_pays(n_src: int, n_dst: int, n_edges: int, d_r: int, d_out: int, elt_bytes: int) -> bool:
+    """Whether relation r is cheaper projected first (Z'_r = H0_s W_r over the n_src source rows, aggregated
+    at width d_out straight into H_t) than aggregated first (M_r over the n_dst destination rows, then
+    projected).  Both orders give the same result (Eq. 1 is linear in H0); this is an estimate of the time
+    of forward + backward from flops and bytes alone:
+
+      aggregate first: 3 contractions over n_dst rows; gathers of d_r-wide rows per edge, forward and backward
+      project first  : 3 contractions over n_src rows; gathers of d_out-wide rows per edge, the forward one
+                       accumulating into H_t (rows with in-edges only), the backward one reading fp32 G_t
+
+    priced at 5 TB/s (what the gather kernels reach), a gather from a table of at most 64 MB at twice
+    that (it stays in the last-level cache), fp32 contractions at 120 TFLOP/s and bf16 ones at 500.
+    Wider-than-output relations are always projected first (measured on the mixed-width workload, where
+    the contraction over d_r > d_out is the slower one at any row count).  The typical case it finds:
+    few source rows feeding many destination rows through few edges, where aggregating first spends
+    three contractions on mostly empty rows of M_r."""
+    if d_r > d_out:
+        return True
+    bw, flops = 5e12, (120e12 if elt_bytes == 4 else 500e12)
+    b = float(elt_bytes)
+
+    def contraction(rows, byt):
+        return max(2.0 * rows * d_r * d_out / flops, byt / bw)
+
+    def gather(table_rows, width, elt):
+        return n_edges * width * elt / (bw * (2.0 if table_rows * width * elt <= 64e6 else 1.0))
+
+    agg_first = (3.0 * contraction(n_dst, n_dst * d_r * b)
+                 + gather(n_src, d_r, b) + n_dst * d_r * b / bw
+                 + gather(n_dst, d_r, b) + n_src * d_r * 4.0 / bw)
+    proj_first = (contraction(n_src, n_src * (d_r * b + d_out * b)) + contraction(n_src, n_src * (d_r * b + d_out * 4.0))
+                  + contraction(n_src, n_src * (d_out * 4.0 + 2.0 * d_r * 4.0))
+                  + gather(n_src, d_out, b) + 2.0 * min(n_edges, n_dst) * d_out * 4.0 / bw
+                  + gather(n_dst, d_out, 4.0) + n_src * d_out * 4.0 / bw)
+    return proj_first < agg_first
+
+
 class RafLayer:
     """Device-resident state of one layer over a `binding.Graph`.
 
@@ -27,7 +64,7 @@ class RafLayer:
                  W: Sequence[torch.Tensor], d_out: int, pre_proj: Optional[Sequence[torch.Tensor]] = None,
                  src_gid: Optional[Sequence[Optional[torch.Tensor]]] = None, relu: bool = False,
                  m_dtype: Optional[torch.dtype] = None, rels: Optional[Sequence[int]] = None,
-                 project_first: Optional[bool] = None):
+                 project_first=None):
         self.g = graph
         self.op = op
         self.tables = list(tables)
@@ -65,12 +102,21 @@ class RafLayer:
             q = 16 // torch.empty((), dtype=dtype).element_size()
             return torch.empty((n, (d + q - 1) // q * q), dtype=dtype, device=dev)[:, :d]
 
-        # Aggregation and projection commute (Eq. 1 is linear in H0).  A relation whose input is wider than
-        # the output is projected first: Z'_r = H0_s W_r over the source rows, then aggregated at the
-        # output width straight into H_t - fewer bytes per edge, no M_r, and the contraction runs over
-        # the source rows instead of the destination rows.  Only for whole-table sources (no src_gid).
+        # Aggregation and projection commute (Eq. 1 is linear in H0).  A relation can be projected
+        # first: Z'_r = H0_s W_r over the source rows, then aggregated at the output width straight
+        # into H_t - no M_r, and the contraction runs over the source rows instead of the destination
+        # rows.  project_first: None = per relation by project_first_pays (whole-table sources only: no
+        # src_gid, no pre_proj); True = the relations wider than the output; False = none; or an
+        # explicit collection of relations.
         auto = src_gid is None and pre_proj is None
-        self.pf = set(r for r in self.rels if self.d_rel[r] > d_out) if (auto if project_first is None else project_first) else set()
+        elt = self.W[self.rels[0]].element_size()
+        if project_first is None:
+            self.pf = set(r for r in self.rels if project_first_pays(graph.n_src(r), graph.n_dst(r), graph.rels[r][2],
+                                                                    self.d_rel[r], d_out, elt)) if auto else set()
+        elif isinstance(project_first, bool):
+            self.pf = set(r for r in self.rels if self.d_rel[r] > d_out) if project_first else set()
+        else:
+            self.pf = set(int(r) for r in project_first) & set(self.rels)
         self._pf_active = set()  # what the last forward actually used (the other call paths aggregate first)
         self._padded = padded
         self._m_shapes = {r: (graph.n_dst(r), self.d_rel[r]) for r in self.rels}

@@ -132,3 +132,17 @@ def test_null_arguments_of_the_later_entry_points_fail_cleanly():
     assert lib.heta_meta_partition(2, None, 1, None, None, None, 0, 1, 1, 0, None, None, None, None, None, None, None, None,
                                    None, None, None) == hb.HETA_ERR_INVALID_ARG
     assert "null argument" in hb.heta_last_error()
+
+
+def test_relation_order_rule_on_the_shapes_it_was_measured_on():
+    """Host logic: which relations the layer projects before aggregating.  On the academic-shaped graph
+    (128 -> 256) only the relations from few sources into many, mostly empty, destination rows; every
+    relation wider than the output; never a narrow relation into fewer rows."""
+    from paper_2408_09697_amd.layer import project_first_pays as pays
+    A, P, F, I = 1_100_000, 700_000, 60_000, 9_000
+    c3 = [(A, P, 4_000_000), (P, P, 4_000_000), (P, F, 4_000_000), (A, I, 500_000), (P, A, 4_000_000), (F, P, 4_000_000),
+          (I, A, 500_000)]
+    assert [i for i, (s, t, e) in enumerate(c3) if pays(s, t, e, 128, 256, 4)] == [5, 6]
+    assert [i for i, (s, t, e) in enumerate(c3) if pays(s, t, e, 128, 256, 2)] == [6]
+    assert pays(500_000, 1_500_000, 5_000_000, 300, 256, 2) and pays(100_000, 500_000, 2_000_000, 789, 256, 2)
+    assert not pays(1_500_000, 500_000, 5_000_000, 7, 256, 2) and not pays(800_000, 500_000, 4_000_000, 64, 256, 2)

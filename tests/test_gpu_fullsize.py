@@ -81,7 +81,8 @@ def test_full_size_integer_aggregation_bit_exact(full_graph, storage):
 def test_full_size_layer_sampled_rows(storage):
     tol = 1e-4 if storage == "f32" else 2e-2
     p = workloads.config3(storage, scale=1.0)
-    layer = make_layer(p)
+    layer = make_layer(p)   # the relation order the benchmark runs: chosen per relation
+    assert {p.graph.relations[i].name for i in layer.pf} == ({"rev_has_topic", "rev_affiliated"} if storage == "f32" else {"rev_affiliated"})
     H = layer.forward()
     G = {t: torch.from_numpy(g).cuda() for t, g in p.G.items()}
     dW, dH0, _ = layer.backward(G)
@@ -95,7 +96,8 @@ def test_full_size_layer_sampled_rows(storage):
         idx = torch.from_numpy(rows).cuda()
         assert_rows_close(H[t][idx].cpu().numpy(), ref_h, tol, f"H[{g.ntypes[t].name}]")
         for i, m in ref_m.items():
-            assert_rows_close(layer.M[i][idx].float().cpu().numpy(), m, tol, f"M[{g.relations[i].name}]")
+            if i in layer.M:   # relations projected first have no saved aggregation
+                assert_rows_close(layer.M[i][idx].float().cpu().numpy(), m, tol, f"M[{g.relations[i].name}]")
     # input / embedding gradients
     for s in dH0:
         outdeg = np.zeros(g.ntypes[s].num_nodes, dtype=np.int64)
@@ -105,8 +107,9 @@ def test_full_size_layer_sampled_rows(storage):
         ref = oracle_input_grad_rows(p, s, rows, p.G)
         idx = torch.from_numpy(rows).cuda()
         assert_rows_close(dH0[s][idx].cpu().numpy(), ref, tol, f"dH0[{g.ntypes[s].name}]")
-    # weight gradients contract over every destination row: full comparison for three relations
-    for name in ("cites", "affiliated", "rev_writes"):
+    # weight gradients contract over every destination row: full comparison for five relations, those
+    # projected first among them
+    for name in ("cites", "affiliated", "rev_writes", "rev_has_topic", "rev_affiliated"):
         i = g.rel_index(name)
         r = g.relations[i]
         src, dst = r.edge_list()
