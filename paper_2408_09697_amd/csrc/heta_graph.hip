@@ -135,6 +135,54 @@ struct PinnedRegion {
     size_t cap = 0;
 };
 static thread_local PinnedRegion t_pinned; // never freed: it lives as long as the thread builds graphs
+// Small relations handed over as DEVICE arrays are built on the host: their arrays come back through
+// this second page-locked buffer, all copies of a graph queued at once and awaited together.
+static thread_local PinnedRegion t_download;
+
+struct StagedCsr {
+    const int64_t *ptr = nullptr;
+    const int32_t *col = nullptr;
+};
+
+static bool takes_device_path(int64_t E, int64_t n_dst, int64_t n_src);
+
+static heta_status download_small_relations(const std::vector<heta_ntype> &nts, const heta_relation *rels, int32_t n_rels,
+                                            std::vector<StagedCsr> &staged)
+{
+    staged.assign(n_rels, StagedCsr());
+    std::vector<size_t> off_ptr(n_rels, 0), off_col(n_rels, 0);
+    size_t total = 0;
+    for (int32_t i = 0; i < n_rels; ++i) {
+        const int64_t n_dst = nts[rels[i].dst_type].num_nodes, n_src = nts[rels[i].src_type].num_nodes, E = rels[i].num_edges;
+        if (takes_device_path(E, n_dst, n_src)) continue;
+        off_ptr[i] = total;
+        total += (static_cast<size_t>(n_dst) + 1) * sizeof(int64_t);
+        off_col[i] = total;
+        total += (static_cast<size_t>(std::max<int64_t>(E, 1)) * sizeof(int32_t) + 7) / 8 * 8;
+    }
+    if (total == 0) return HETA_OK;
+    if (total > t_download.cap) {
+        const size_t cap = std::max<size_t>(std::max<size_t>(t_download.cap * 2, total), size_t(1) << 20);
+        void *q = nullptr;
+        if (hipHostMalloc(&q, cap, hipHostMallocDefault) != hipSuccess)
+            return fail(HETA_ERR_OOM, "heta_graph_create: page-locked host allocation of %zu bytes failed", cap);
+        if (t_download.p) (void)hipHostFree(t_download.p);
+        t_download.p = static_cast<char *>(q);
+        t_download.cap = cap;
+    }
+    for (int32_t i = 0; i < n_rels; ++i) {
+        const int64_t n_dst = nts[rels[i].dst_type].num_nodes, n_src = nts[rels[i].src_type].num_nodes, E = rels[i].num_edges;
+        if (takes_device_path(E, n_dst, n_src)) continue;
+        int64_t *hp = reinterpret_cast<int64_t *>(t_download.p + off_ptr[i]);
+        int32_t *hc = reinterpret_cast<int32_t *>(t_download.p + off_col[i]);
+        HETA_HIP(hipMemcpyAsync(hp, rels[i].csr_rowptr, (n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, nullptr));
+        if (E) HETA_HIP(hipMemcpyAsync(hc, rels[i].csr_col, E * sizeof(int32_t), hipMemcpyDeviceToHost, nullptr));
+        staged[i].ptr = hp;
+        staged[i].col = hc;
+    }
+    HETA_HIP(hipStreamSynchronize(nullptr));
+    return HETA_OK;
+}
 
 struct HostPack {
     size_t size = 0;
@@ -323,8 +371,13 @@ struct PendingRelation {
     size_t inv;
 };
 
+static bool takes_device_path(int64_t E, int64_t n_dst, int64_t n_src)
+{
+    return g_ingest_mode == 2 || (g_ingest_mode == 0 && E + n_dst + n_src >= kDeviceIngestMin);
+}
+
 static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32_t index, bool on_device, HostPack &pack,
-                                   std::vector<PendingRelation> &pending)
+                                   std::vector<PendingRelation> &pending, const StagedCsr &staged)
 {
     g->rels.emplace_back();
     Relation &rel = g->rels.back(); // owned by g from here on: destroy(g) releases whatever was allocated
@@ -340,7 +393,7 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
     rel.csc.n_rows = n_src;
     rel.csc.n_edges = E;
 
-    const bool device_path = g_ingest_mode == 2 || (g_ingest_mode == 0 && E + n_dst + n_src >= kDeviceIngestMin);
+    const bool device_path = takes_device_path(E, n_dst, n_src);
     if (device_path) {
         // the CSR itself: a device copy of the caller's arrays
         HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_ptr), (n_dst + 1) * sizeof(int64_t)));
@@ -359,17 +412,12 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
         return build_schedule_on_device(rel.csc, nullptr, st);
     }
 
-    std::vector<int64_t> h_ptr;
-    std::vector<int32_t> h_col;
     const int64_t *ptr = in.csr_rowptr;
     const int32_t *col = in.csr_col;
-    if (on_device) {
-        h_ptr.resize(n_dst + 1);
-        h_col.resize(std::max<int64_t>(E, 1));
-        HETA_HIP(hipMemcpy(h_ptr.data(), in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
-        if (E) HETA_HIP(hipMemcpy(h_col.data(), in.csr_col, E * sizeof(int32_t), hipMemcpyDeviceToHost));
-        ptr = h_ptr.data();
-        col = h_col.data();
+    if (on_device) { // the caller's device arrays, already copied to the host with the graph's other small relations
+        if (!staged.ptr) return fail(HETA_ERR_DEVICE, "heta_graph_create: relation %d was not staged", index);
+        ptr = staged.ptr;
+        col = staged.col;
         heta_status vst = validate_relation(g->ntypes, in, index, ptr, col);
         if (vst != HETA_OK) return vst;
     }
@@ -471,8 +519,16 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
         g->rels.reserve(n_rels);
         HostPack pack;
         std::vector<PendingRelation> pending;
+        std::vector<StagedCsr> staged(n_rels);
+        if (on_device) {
+            heta_status st = download_small_relations(g->ntypes, rels, n_rels, staged);
+            if (st != HETA_OK) {
+                destroy(g);
+                return st;
+            }
+        }
         for (int32_t i = 0; i < n_rels; ++i) {
-            heta_status st = ingest_relation(g, rels[i], i, on_device, pack, pending);
+            heta_status st = ingest_relation(g, rels[i], i, on_device, pack, pending, staged[i]);
             if (st != HETA_OK) {
                 destroy(g);
                 return st;
