@@ -93,12 +93,17 @@ def measure(storage: str, args, keep_problem: bool = False):
 
     for _ in range(args.warmup):
         step()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()   # per-step device times for the median / minimum; `value` uses the wall clock
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / max(1, args.steps)
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    step_stats = {"median_ms": per_step[len(per_step) // 2], "min_ms": per_step[0], "max_ms": per_step[-1]} if per_step else None
 
     # forward / backward split (same stream, device events)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -174,6 +179,40 @@ def measure(storage: str, args, keep_problem: bool = False):
                                                "achieved": agg_mb / agg_ms if agg_ms else 0.0, "peak": PEAK_HBM_GBS,
                                                "unit": "GB/s",
                                                "frac": (agg_mb / agg_ms / PEAK_HBM_GBS) if agg_ms else 0.0}
+    # Each relation's aggregation on its own (standalone calls at the relation's input width, storage
+    # type in, fp32 gradients in the backward): algorithmic bytes E*d*b_in + 4E + 8(rows+1) + rows*d*b_out.
+    per_relation = []
+    if not args.no_profile:
+        esz_t = 2 if storage == "bf16" else 4
+        for r, rel in enumerate(p.graph.relations):
+            s_t, d_t = rel.src_type, rel.dst_type
+            n_s, n_t, E = p.graph.ntypes[s_t].num_nodes, p.graph.ntypes[d_t].num_nodes, rel.num_edges
+            d = layer.d_rel[r]
+            out = layer._padded(n_t, d, layer.m_dtype)
+            gin = layer._padded(n_t, d, torch.float32).zero_()
+            back = layer._padded(n_s, d, torch.float32)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            reps = 5
+            heta.heta_rel_aggregate_fwd(graph, r, layer.op, layer.source(s_t), out, d=d)
+            heta.heta_rel_aggregate_bwd(graph, r, layer.op, gin, back)
+            ev[0].record()
+            for _ in range(reps):
+                heta.heta_rel_aggregate_fwd(graph, r, layer.op, layer.source(s_t), out, d=d)
+            ev[1].record()
+            for _ in range(reps):
+                heta.heta_rel_aggregate_bwd(graph, r, layer.op, gin, back)
+            ev[2].record()
+            torch.cuda.synchronize()
+            f_ms, b_ms = ev[0].elapsed_time(ev[1]) / reps, ev[1].elapsed_time(ev[2]) / reps
+            f_bytes = E * d * esz_t + 4 * E + 8 * (n_t + 1) + n_t * d * esz_t
+            b_bytes = E * d * 4 + 4 * E + 8 * (n_s + 1) + n_s * d * 4
+            per_relation.append({"relation": rel.name, "edges": E, "d": d,
+                                 "aggregate_fwd_ms": f_ms, "aggregate_fwd_GBps": f_bytes / f_ms / 1e6,
+                                 "aggregate_fwd_frac_of_hbm_peak": f_bytes / f_ms / 1e6 / PEAK_HBM_GBS,
+                                 "aggregate_bwd_ms": b_ms, "aggregate_bwd_GBps": b_bytes / b_ms / 1e6,
+                                 "aggregate_bwd_frac_of_hbm_peak": b_bytes / b_ms / 1e6 / PEAK_HBM_GBS,
+                                 "edge_features_per_s": 2.0 * E * d / ((f_ms + b_ms) * 1e-3)})
+            del out, gin, back
     # The update of the learnable tables that follows backpropagation (not part of `value`): one sparse
     # Adam step over every learnable type, all rows touched (full-graph layer), gradient = this step's dH0.
     adam = None
@@ -203,7 +242,8 @@ def measure(storage: str, args, keep_problem: bool = False):
            "edges_per_s": 2.0 * n_edges / (ms_per_step * 1e-3), "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
            "ingest_ms": ingest_ms, "input_generation_s": gen_s, "roofline": roofline, "kernels": kernels,
            "edges": n_edges, "edge_features_per_pass": edge_features,
-           "projected_first": sorted(p.graph.relations[r].name for r in layer.pf)}
+           "projected_first": sorted(p.graph.relations[r].name for r in layer.pf),
+           "step_time": step_stats, "per_relation_aggregation": per_relation}
     graph.destroy()
     del layer, G
     torch.cuda.empty_cache()
@@ -518,6 +558,11 @@ def main() -> int:
                                               "cheaper order is used, same result"}},
         "edges_per_s": main_res["edges_per_s"],
         "fwd_ms": main_res["fwd_ms"], "bwd_ms": main_res["bwd_ms"],
+        "step_time": main_res["step_time"],
+        "per_relation_aggregation": main_res["per_relation_aggregation"],
+        "per_relation_aggregation_note": "standalone heta_rel_aggregate_fwd / _bwd per relation; GB/s and fractions use the "
+                                         "algorithmic byte count, which charges one source row per edge: a fraction above 1 "
+                                         "means rows re-read from cache, not more than 8 TB/s from HBM",
         "ingest": {"ms": main_res["ingest_ms"],
                    "note": "heta_graph_create for every relation (host validation of the caller's arrays, upload, then "
                            "device kernels: radix-sort transpose, scans, degree-sorted schedules); once per graph, "
@@ -534,7 +579,7 @@ def main() -> int:
         problem = problem or p2
         out["bf16_storage" if other == "bf16" else "f32_storage"] = {
             k: res[k] for k in ("value", "ms_per_step", "edges_per_s", "fwd_ms", "bwd_ms", "roofline", "kernels", "sparse_adam",
-                                "fused_inference_forward", "projected_first")}
+                                "fused_inference_forward", "projected_first", "step_time", "per_relation_aggregation")}
     if not args.single and args.workload == "config3":
         # the paper's second model on the same graph: R-GAT layer, forward + backward (not part of `value`)
         out["rgat"] = {}
