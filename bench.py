@@ -325,10 +325,11 @@ def measure_rgat(storage: str, args, heads: int = 4):
     return res
 
 
-def measure_minibatch(args):
-    """Config 5: one sampled 2-layer mini-batch (4,096 seeds, fanouts [25, 15], 768 -> 1024 -> 1024, mean,
-    bf16 tables) on one GPU's partition of the 240 M-node-shaped graph.  A step = building the two block
-    handles from the sampled CSRs, forward and backward of both layers."""
+def measure_minibatch(args, which: str = "config5"):
+    """One sampled 2-layer mini-batch.  config5: 4,096 seeds, fanouts [25, 15], 768 -> 1024 -> 1024, mean, bf16
+    tables, on one GPU's partition of the 240 M-node-shaped graph.  config2: 1,024 seeds, fanouts [25, 20],
+    128 -> 256 -> 256, mean, fp32, on the academic-shaped graph of config 3.  A step = building the two
+    block handles from the sampled CSRs, forward and backward of both layers."""
     import numpy as np
     import torch
     import paper_2408_09697_amd as heta
@@ -336,15 +337,20 @@ def measure_minibatch(args):
     from tests.harness import dev_table
 
     t0 = time.perf_counter()
-    mb = workloads.config5(args.scale)
+    mb = workloads.config5(args.scale) if which == "config5" else workloads.config2(args.scale)
     gen_s = time.perf_counter() - t0
     T = mb.blocks[0].n_base_types
+    storage = mb.storage
+    fanouts = [25, 15] if which == "config5" else [25, 20]
     tables = []
     for t, nt in enumerate(mb.base.ntypes):
-        buf = torch.empty((nt.num_nodes, nt.feat_dim), dtype=torch.bfloat16, device="cuda")
-        rng.hashed_table_device(mb.table_keys[t], nt.num_nodes, nt.feat_dim, mb.table_kinds[t], buf)
-        tables.append(buf)
-    W = [[dev_table(w, "bf16", 8) for w in ws] for ws in mb.W]
+        if mb.tables is not None:   # host tables
+            tables.append(dev_table(mb.tables[t], storage, 8 if storage == "bf16" else 4))
+        else:                       # counter-based tables, filled on the device
+            buf = torch.empty((nt.num_nodes, nt.feat_dim), dtype=torch.bfloat16, device="cuda")
+            rng.hashed_table_device(mb.table_keys[t], nt.num_nodes, nt.feat_dim, mb.table_kinds[t], buf)
+            tables.append(buf)
+    W = [[dev_table(w, storage, 8 if storage == "bf16" else 4) for w in ws] for ws in mb.W]
     gids = [torch.from_numpy(g).cuda() for g in mb.blocks[0].src_gid[:T]] + [None] * T
     G_seed = torch.from_numpy(mb.G).cuda()
     edge_features = sum(r.num_edges * (mb.base.ntypes[mb.base.relations[i].src_type].feat_dim if l == 0 else mb.d_hidden)
@@ -435,7 +441,7 @@ def measure_minibatch(args):
         for k in range(args.steps + 1):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            blocks = heta.sampler.sample_blocks(base, mb.seed_type, seeds_all[k * n_seeds:(k + 1) * n_seeds], [25, 15], 20240809 + k)
+            blocks = heta.sampler.sample_blocks(base, mb.seed_type, seeds_all[k * n_seeds:(k + 1) * n_seeds], fanouts, 20240809 + k)
             sizes = [int(sum(c.numel() for c in b.col)) for b in blocks]
             for b in blocks:
                 b.graph.destroy()
@@ -450,7 +456,7 @@ def measure_minibatch(args):
         # one whole training iteration on the device: sample, ingest, forward, backward, Adam on the weights,
         # sparse Adam on the touched embedding rows (moments for every learnable row are resident)
         try:
-            trainer = heta.MiniBatchTrainer(base, tables, W, [25, 15], mb.d_hidden, heta.HETA_MEAN, mb.seed_type, lr=1e-3,
+            trainer = heta.MiniBatchTrainer(base, tables, W, fanouts, mb.d_hidden, heta.HETA_MEAN, mb.seed_type, lr=1e-3,
                                             seed=20240809)
             Y = torch.zeros((n_seeds, mb.d_hidden), dtype=torch.float32, device="cuda")
             t_its = []
@@ -473,10 +479,13 @@ def measure_minibatch(args):
     ms = compute_ms + ingest_ms
     return {"metric": "aggregated edge-features/sec (fwd+bwd), 1 GPU", "value": 2.0 * edge_features / (ms * 1e-3),
             "unit": "edge-features/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage, f32 accumulate",
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16 storage, f32 accumulate" if storage == "bf16" else "f32",
             "data": "synthetic",
-            "config": {"workload": f"config 5: sampled 2-layer mini-batch, {mb.G.shape[0]} seeds, fanouts [25, 15], "
-                                   f"768->1024->1024, mean, bf16 tables, {n_edges} sampled edges"
+            "config": {"workload": (f"config 5: sampled 2-layer mini-batch, {mb.G.shape[0]} seeds, fanouts [25, 15], "
+                                    f"768->1024->1024, mean, bf16 tables, {n_edges} sampled edges" if which == "config5" else
+                                    f"config 2: sampled 2-layer mini-batch on the config-3 graph, {mb.G.shape[0]} seeds, "
+                                    f"fanouts [25, 20], 128->256->256, mean, fp32, {n_edges} sampled edges")
                                    + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
                        "edges": n_edges, "edge_features_per_pass": edge_features,
                        "block_sizes": [[(t.name, t.num_nodes) for t in b.graph.ntypes] for b in mb.blocks]},
@@ -492,9 +501,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32", help="table storage of the headline run")
     ap.add_argument("--single", action="store_true", help="measure only the headline storage type")
-    ap.add_argument("--workload", choices=["config3", "config4", "config5"], default="config3",
-                    help="config3 is the headline; config4 (mixed widths, bf16) and config5 (sampled 2-layer "
-                         "mini-batch on the 400 M-edge partition, bf16) are additional measurements")
+    ap.add_argument("--workload", choices=["config2", "config3", "config4", "config5"], default="config3",
+                    help="config3 is the headline; config4 (mixed widths, bf16), config2 (sampled 2-layer mini-batch on "
+                         "the config-3 graph, fp32) and config5 (sampled 2-layer mini-batch on the 400 M-edge partition, "
+                         "bf16) are additional measurements")
     ap.add_argument("--model", choices=["rgcn", "rgat"], default="rgcn",
                     help="rgcn is the headline layer; rgat measures the attention layer on the config-3 graph only")
     ap.add_argument("--project-first", default="auto",
@@ -532,8 +542,8 @@ def main() -> int:
             out["bf16"] = measure_rgat("bf16", args)
         print(json.dumps(out))
         return 0
-    if args.workload == "config5":
-        print(json.dumps(measure_minibatch(args)))
+    if args.workload in ("config2", "config5"):
+        print(json.dumps(measure_minibatch(args, args.workload)))
         return 0
     if args.workload == "config4":
         args.dtype, args.single, args.no_cpu_baseline = "bf16", True, True
@@ -587,6 +597,12 @@ def main() -> int:
             r = measure_rgat(st_, args)
             out["rgat"][st_] = {k: r[k] for k in ("model", "ms_per_step", "fwd_ms", "bwd_ms", "value", "unit",
                                                    "aggregation_all_kernels")}
+    if not args.single and args.workload == "config3":
+        # the sampled 2-layer mini-batch on the same graph (1,024 seeds, fan-outs [25, 20], fp32): launch-bound
+        # blocks of ~10^4-10^5 edges; with the device sampler and the whole device training iteration
+        mbr = measure_minibatch(args, "config2")
+        out["minibatch_config2"] = {k: mbr[k] for k in ("value", "unit", "ms_per_step", "compute_ms", "ingest_ms_per_batch",
+                                                        "dtype", "config", "device_sampler")}
     # The paper reports no per-layer or per-kernel figure; its end-to-end results are quoted as context only
     # (evaluation section: 2 machines x 8 NVIDIA T4 16 GB, 2-layer models, hidden 64, batch 1,024, fan-out {25, 20}).
     out["paper_context"] = {

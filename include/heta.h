@@ -83,7 +83,7 @@ typedef struct {
 heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels,
                               int32_t n_rels, uint32_t flags, heta_graph **out);
 heta_status heta_graph_destroy(heta_graph *g); /* NULL is accepted; synchronises the device */
-/* Testing switch (process-wide): 0 = relations of at least 2^17 edges + rows are ingested by device
+/* Testing switch (process-wide): 0 = relations of at least 2^18 edges + rows are ingested by device
  * kernels and smaller ones on the host (the default), 1 = always on the host, 2 = always on the
  * device.  Both paths produce identical index arrays. */
 heta_status heta_ingest_force(int32_t mode);

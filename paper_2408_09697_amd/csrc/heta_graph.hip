@@ -6,12 +6,15 @@
 // heta_ingest.hip for relations of real size, by the host code below for the small blocks of a
 // sampled mini-batch, where launch latency would dominate.  Both produce the same arrays.
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <map>
 #include <memory>
 #include <mutex>
 #include <new>
 #include <string>
+#include <system_error>
+#include <thread>
 #include <unordered_map>
 #include <utility>
 
@@ -219,17 +222,52 @@ struct ScheduleOffsets {
     size_t ptr, idx, perm, sptr, sidx, hub_chunks, hub_chunk_ptr;
 };
 
-// Host build of one direction's schedule (small relations): the same arrays the device path produces.
-static heta_status build_schedule_on_host(Schedule &s, const int64_t *ptr, const int32_t *idx, HostPack &pack,
-                                          ScheduleOffsets &off)
+// Every array of a host-built relation has a size known from (rows, edges) alone, hub chunks up to a
+// bound, so the whole graph is laid out in the page-locked buffer first and the builders write their
+// results in place: no allocation and no copy per relation (fresh std::vectors of this size are
+// mapped and page-faulted anew on every call, which was most of a block's ingest time).
+static size_t take(size_t &cursor, size_t bytes)
 {
-    const int64_t n_rows = s.n_rows, n_edges = s.n_edges;
+    const size_t off = (cursor + 255) / 256 * 256;
+    cursor = off + std::max<size_t>(bytes, 1);
+    return off;
+}
+
+static size_t hub_chunk_bound(int64_t n_edges) // sum over hub rows of ceil(deg / chunk) <= E / chunk + E / min hub degree
+{
+    return static_cast<size_t>(n_edges / kHubChunk + n_edges / kHubMinDeg + 1);
+}
+
+static void lay_out(const Schedule &s, size_t &cursor, ScheduleOffsets &off)
+{
+    const size_t rows = static_cast<size_t>(s.n_rows), edges = static_cast<size_t>(s.n_edges);
+    off.ptr = take(cursor, (rows + 1) * sizeof(int64_t));
+    off.idx = take(cursor, edges * sizeof(int32_t));
+    off.perm = take(cursor, rows * sizeof(int32_t));
+    off.sptr = take(cursor, (rows + 1) * sizeof(int64_t));
+    off.sidx = take(cursor, edges * sizeof(int32_t));
+    off.hub_chunks = take(cursor, hub_chunk_bound(s.n_edges) * sizeof(HubChunk));
+    off.hub_chunk_ptr = take(cursor, (static_cast<size_t>(s.n_edges / kHubMinDeg) + 2) * sizeof(int64_t));
+}
+
+// Host build of one direction's schedule (small relations): the same arrays the device path produces.
+// `base + off.ptr` and `base + off.idx` already hold the adjacency by row id.
+static heta_status build_schedule_on_host(Schedule &s, char *base, const ScheduleOffsets &off)
+{
+    const int64_t n_rows = s.n_rows;
+    const int64_t *ptr = reinterpret_cast<const int64_t *>(base + off.ptr);
+    const int32_t *idx = reinterpret_cast<const int32_t *>(base + off.idx);
+    int32_t *perm = reinterpret_cast<int32_t *>(base + off.perm);
+    int64_t *sptr = reinterpret_cast<int64_t *>(base + off.sptr);
+    int32_t *sidx = reinterpret_cast<int32_t *>(base + off.sidx);
+    HubChunk *chunks = reinterpret_cast<HubChunk *>(base + off.hub_chunks);
+    int64_t *chunk_ptr = reinterpret_cast<int64_t *>(base + off.hub_chunk_ptr);
     // counting sort of the rows by min(degree, kHubMinDeg), descending, stable
-    std::vector<int64_t> bucket(kHubMinDeg + 2, 0), bucket_edges(kHubMinDeg + 2, 0);
+    int64_t bucket[kHubMinDeg + 2] = {0}, bucket_edges[kHubMinDeg + 2] = {0};
     for (int64_t r = 0; r < n_rows; ++r) {
-        int64_t d = std::min<int64_t>(ptr[r + 1] - ptr[r], kHubMinDeg);
+        const int64_t deg = ptr[r + 1] - ptr[r], d = std::min<int64_t>(deg, kHubMinDeg);
         bucket[d] += 1;
-        bucket_edges[d] += ptr[r + 1] - ptr[r];
+        bucket_edges[d] += deg;
     }
     int64_t run = 0, run_edges = 0;
     for (int k = kHubMinDeg; k >= 0; --k) {
@@ -238,45 +276,38 @@ static heta_status build_schedule_on_host(Schedule &s, const int64_t *ptr, const
         s.rows_with_deg_ge[k] = run;
         s.edges_with_deg_ge[k] = run_edges;
     }
-    std::vector<int64_t> start(kHubMinDeg + 1);
+    int64_t start[kHubMinDeg + 1];
     for (int k = 0; k <= kHubMinDeg; ++k)
         start[k] = (k == kHubMinDeg) ? 0 : s.rows_with_deg_ge[k + 1];
-    std::vector<int32_t> perm(std::max<int64_t>(n_rows, 1));
     for (int64_t r = 0; r < n_rows; ++r) {
-        int64_t d = std::min<int64_t>(ptr[r + 1] - ptr[r], kHubMinDeg);
+        const int64_t d = std::min<int64_t>(ptr[r + 1] - ptr[r], kHubMinDeg);
         perm[start[d]++] = static_cast<int32_t>(r);
     }
     // the adjacency in schedule order
-    std::vector<int64_t> sptr(n_rows + 1, 0);
-    std::vector<int32_t> sidx(std::max<int64_t>(n_edges, 1));
+    sptr[0] = 0;
     for (int64_t q = 0; q < n_rows; ++q) {
         const int64_t r = perm[q], deg = ptr[r + 1] - ptr[r];
-        std::copy(idx + ptr[r], idx + ptr[r] + deg, sidx.begin() + sptr[q]);
+        std::copy(idx + ptr[r], idx + ptr[r] + deg, sidx + sptr[q]);
         sptr[q + 1] = sptr[q] + deg;
     }
     s.n_hub_rows = s.rows_with_deg_ge[kHubMinDeg];
-    std::vector<HubChunk> chunks;
-    std::vector<int64_t> chunk_ptr(s.n_hub_rows + 1, 0);
+    const size_t bound = hub_chunk_bound(s.n_edges);
+    size_t n_chunks = 0;
+    chunk_ptr[0] = 0;
     for (int64_t h = 0; h < s.n_hub_rows; ++h) {
         for (int64_t e = sptr[h]; e < sptr[h + 1]; e += kHubChunk) {
+            if (n_chunks >= bound) return fail(HETA_ERR_UNSUPPORTED, "hub chunk bound %zu exceeded", bound);
             HubChunk c;
             c.e0 = e;
             c.len = static_cast<int32_t>(std::min<int64_t>(kHubChunk, sptr[h + 1] - e));
-            c.slot = static_cast<int32_t>(chunks.size());
-            chunks.push_back(c);
+            c.slot = static_cast<int32_t>(n_chunks);
+            chunks[n_chunks++] = c;
         }
-        chunk_ptr[h + 1] = static_cast<int64_t>(chunks.size());
+        chunk_ptr[h + 1] = static_cast<int64_t>(n_chunks);
     }
-    if (chunks.size() >= (size_t(1) << 31))
-        return fail(HETA_ERR_UNSUPPORTED, "too many hub chunks (%zu)", chunks.size());
-    s.n_hub_chunks = static_cast<int64_t>(chunks.size());
-    off.ptr = pack.add(ptr, n_rows + 1);
-    off.idx = pack.add(idx, n_edges);
-    off.perm = pack.add(perm.data(), n_rows);
-    off.sptr = pack.add(sptr.data(), sptr.size());
-    off.sidx = pack.add(sidx.data(), n_edges);
-    off.hub_chunks = pack.add(chunks.data(), chunks.size());
-    off.hub_chunk_ptr = pack.add(chunk_ptr.data(), chunk_ptr.size());
+    if (n_chunks >= (size_t(1) << 31))
+        return fail(HETA_ERR_UNSUPPORTED, "too many hub chunks (%zu)", n_chunks);
+    s.n_hub_chunks = static_cast<int64_t>(n_chunks);
     return HETA_OK;
 }
 
@@ -360,7 +391,7 @@ static heta_status check_relation_args(const std::vector<heta_ntype> &ntypes, co
 // Relations below this many edges + rows are ingested on the host: a few microseconds of CPU work
 // beat the launch latencies of the device pipeline (sampled mini-batch blocks); everything larger
 // is built by the kernels of heta_ingest.hip.  heta_ingest_force() overrides the choice.
-constexpr int64_t kDeviceIngestMin = 1 << 17;
+constexpr int64_t kDeviceIngestMin = 1 << 18;
 static int g_ingest_mode = 0; // 0 = by size, 1 = host, 2 = device
 
 // A host-built relation waits in the graph's host buffer until every relation is built; then one
@@ -376,8 +407,9 @@ static bool takes_device_path(int64_t E, int64_t n_dst, int64_t n_src)
     return g_ingest_mode == 2 || (g_ingest_mode == 0 && E + n_dst + n_src >= kDeviceIngestMin);
 }
 
-static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32_t index, bool on_device, HostPack &pack,
-                                   std::vector<PendingRelation> &pending, const StagedCsr &staged)
+// Registers relation `index` in g; a large relation is built on the device right away, a small one
+// is left for build_on_host (device_path tells which).
+static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32_t index, bool on_device, bool &device_path)
 {
     g->rels.emplace_back();
     Relation &rel = g->rels.back(); // owned by g from here on: destroy(g) releases whatever was allocated
@@ -393,60 +425,138 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
     rel.csc.n_rows = n_src;
     rel.csc.n_edges = E;
 
-    const bool device_path = takes_device_path(E, n_dst, n_src);
-    if (device_path) {
-        // the CSR itself: a device copy of the caller's arrays
-        HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_ptr), (n_dst + 1) * sizeof(int64_t)));
-        HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_idx), std::max<int64_t>(E, 1) * sizeof(int32_t)));
-        const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
-        HETA_HIP(hipMemcpy(rel.csr.d_ptr, in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), kind));
-        if (E) HETA_HIP(hipMemcpy(rel.csr.d_idx, in.csr_col, E * sizeof(int32_t), kind));
-        if (on_device) { // host arrays were validated before the device was touched
-            heta_status vst = validate_csr_on_device(index, rel.csr.d_ptr, rel.csr.d_idx, n_dst, n_src, E, st);
-            if (vst != HETA_OK) return vst;
-        }
-        HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.d_inv_deg), std::max<int64_t>(n_dst, 1) * sizeof(float)));
-        heta_status e;
-        if ((e = transpose_on_device(rel.csr, n_src, rel.csc, st)) != HETA_OK) return e;
-        if ((e = build_schedule_on_device(rel.csr, rel.d_inv_deg, st)) != HETA_OK) return e;
-        return build_schedule_on_device(rel.csc, nullptr, st);
-    }
-
-    const int64_t *ptr = in.csr_rowptr;
-    const int32_t *col = in.csr_col;
-    if (on_device) { // the caller's device arrays, already copied to the host with the graph's other small relations
-        if (!staged.ptr) return fail(HETA_ERR_DEVICE, "heta_graph_create: relation %d was not staged", index);
-        ptr = staged.ptr;
-        col = staged.col;
-        heta_status vst = validate_relation(g->ntypes, in, index, ptr, col);
+    device_path = takes_device_path(E, n_dst, n_src);
+    if (!device_path) return HETA_OK;
+    // the CSR itself: a device copy of the caller's arrays
+    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_ptr), (n_dst + 1) * sizeof(int64_t)));
+    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_idx), std::max<int64_t>(E, 1) * sizeof(int32_t)));
+    const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    HETA_HIP(hipMemcpy(rel.csr.d_ptr, in.csr_rowptr, (n_dst + 1) * sizeof(int64_t), kind));
+    if (E) HETA_HIP(hipMemcpy(rel.csr.d_idx, in.csr_col, E * sizeof(int32_t), kind));
+    if (on_device) { // host arrays were validated before the device was touched
+        heta_status vst = validate_csr_on_device(index, rel.csr.d_ptr, rel.csr.d_idx, n_dst, n_src, E, st);
         if (vst != HETA_OK) return vst;
     }
-    std::vector<float> inv_deg(std::max<int64_t>(n_dst, 1));
+    HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.d_inv_deg), std::max<int64_t>(n_dst, 1) * sizeof(float)));
+    heta_status e;
+    if ((e = transpose_on_device(rel.csr, n_src, rel.csc, st)) != HETA_OK) return e;
+    if ((e = build_schedule_on_device(rel.csr, rel.d_inv_deg, st)) != HETA_OK) return e;
+    return build_schedule_on_device(rel.csc, nullptr, st);
+}
+
+// Host build of one small relation: 1/deg, the stable transpose, both schedules, written in place into
+// the relation's slices of the page-locked buffer.  Touches no device and no state shared with other
+// relations, so the relations of a graph are built by several threads; a failure is returned with its
+// message (the thread-local error slot belongs to the worker).
+struct SmallLayout {
+    ScheduleOffsets csr, csc; // in the page-locked buffer
+    size_t inv;               // 1/deg, in the page-locked buffer
+    size_t cursor;            // fill positions of the transpose, in the scratch arena
+};
+
+struct HostBuilt {
+    heta_status status = HETA_OK;
+    std::string message;
+};
+
+static void build_on_host(const std::vector<heta_ntype> &ntypes, const heta_relation &in, int32_t index, Relation &rel,
+                          const int64_t *ptr, const int32_t *col, bool validate, char *base, const SmallLayout &lay,
+                          char *scratch, HostBuilt &out)
+{
+    const int64_t E = rel.n_edges, n_dst = rel.n_dst, n_src = rel.n_src;
+    if (validate) { // arrays that came from the device: checked now that they are on the host
+        out.status = validate_relation(ntypes, in, index, ptr, col);
+        if (out.status != HETA_OK) {
+            out.message = g_last_error;
+            return;
+        }
+    }
+    std::memcpy(base + lay.csr.ptr, ptr, (n_dst + 1) * sizeof(int64_t));
+    if (E) std::memcpy(base + lay.csr.idx, col, E * sizeof(int32_t));
+    float *inv_deg = reinterpret_cast<float *>(base + lay.inv);
     for (int64_t v = 0; v < n_dst; ++v) {
         const int64_t d = ptr[v + 1] - ptr[v];
         inv_deg[v] = d > 0 ? 1.0f / static_cast<float>(d) : 0.0f;
     }
     // stable transpose: column u keeps its edges in ascending original edge position
-    std::vector<int64_t> colptr(n_src + 1, 0);
+    int64_t *colptr = reinterpret_cast<int64_t *>(base + lay.csc.ptr);
+    int32_t *row = reinterpret_cast<int32_t *>(base + lay.csc.idx);
+    int64_t *cursor = reinterpret_cast<int64_t *>(scratch + lay.cursor);
+    std::fill(colptr, colptr + n_src + 1, int64_t(0));
     for (int64_t e = 0; e < E; ++e)
         colptr[col[e] + 1] += 1;
     for (int64_t u = 0; u < n_src; ++u)
         colptr[u + 1] += colptr[u];
-    std::vector<int32_t> row(std::max<int64_t>(E, 1));
-    {
-        std::vector<int64_t> cursor(colptr.begin(), colptr.end() - 1);
-        for (int64_t v = 0; v < n_dst; ++v)
-            for (int64_t e = ptr[v]; e < ptr[v + 1]; ++e)
-                row[cursor[col[e]]++] = static_cast<int32_t>(v);
+    std::copy(colptr, colptr + n_src, cursor);
+    for (int64_t v = 0; v < n_dst; ++v)
+        for (int64_t e = ptr[v]; e < ptr[v + 1]; ++e)
+            row[cursor[col[e]]++] = static_cast<int32_t>(v);
+    if ((out.status = build_schedule_on_host(rel.csr, base, lay.csr)) == HETA_OK)
+        out.status = build_schedule_on_host(rel.csc, base, lay.csc);
+    if (out.status != HETA_OK) out.message = g_last_error;
+}
+
+static thread_local std::vector<char> t_scratch; // the transposes' fill positions; grows, never shrinks
+
+// Builds every small relation of the graph on the host, several at a time.  The box gives a process
+// 16 cores; 8 workers cover the relation counts of the paper's graphs (5 to 14 per block) and leave
+// room for the caller's other threads.  Largest relations first, dealt by an atomic counter.
+static heta_status build_small_relations(heta_graph *g, const heta_relation *rels, const std::vector<int32_t> &small,
+                                         bool on_device, const std::vector<StagedCsr> &staged, HostPack &pack,
+                                         std::vector<PendingRelation> &pending)
+{
+    if (small.empty()) return HETA_OK;
+    // the layout of the whole graph, in relation order
+    std::vector<SmallLayout> lay(small.size());
+    size_t total = pack.size, scratch_total = 0;
+    for (size_t k = 0; k < small.size(); ++k) {
+        const Relation &rel = g->rels[small[k]];
+        lay_out(rel.csr, total, lay[k].csr);
+        lay_out(rel.csc, total, lay[k].csc);
+        lay[k].inv = take(total, static_cast<size_t>(rel.n_dst) * sizeof(float));
+        lay[k].cursor = take(scratch_total, static_cast<size_t>(rel.n_src) * sizeof(int64_t));
     }
-    PendingRelation pr;
-    pr.rel = g->rels.size() - 1;
-    heta_status e;
-    if ((e = build_schedule_on_host(rel.csr, ptr, col, pack, pr.csr)) != HETA_OK) return e;
-    if ((e = build_schedule_on_host(rel.csc, colptr.data(), row.data(), pack, pr.csc)) != HETA_OK) return e;
-    pr.inv = pack.add(inv_deg.data(), static_cast<size_t>(n_dst));
-    rel.host_built = true;
-    pending.push_back(pr);
+    if (!pack.reserve(total)) return fail(HETA_ERR_OOM, "heta_graph_create: page-locked host allocation of %zu bytes failed", total);
+    pack.size = total;
+    if (t_scratch.size() < scratch_total) t_scratch.resize(scratch_total);
+    char *base = t_pinned.p, *scratch = t_scratch.data();
+
+    std::vector<size_t> order(small.size());
+    for (size_t k = 0; k < order.size(); ++k) order[k] = k;
+    auto work = [&](size_t k) { const Relation &r = g->rels[small[k]]; return r.n_edges + r.n_dst + r.n_src; };
+    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return work(a) > work(b); });
+    std::vector<HostBuilt> built(small.size());
+    std::atomic<size_t> next{0};
+    auto run = [&]() {
+        for (size_t j = next.fetch_add(1); j < order.size(); j = next.fetch_add(1)) {
+            const size_t k = order[j];
+            const int32_t i = small[k];
+            const int64_t *ptr = on_device ? staged[i].ptr : rels[i].csr_rowptr;
+            const int32_t *col = on_device ? staged[i].col : rels[i].csr_col;
+            build_on_host(g->ntypes, rels[i], i, g->rels[i], ptr, col, on_device, base, lay[k], scratch, built[k]);
+        }
+    };
+    int64_t total_work = 0;
+    for (size_t k = 0; k < small.size(); ++k) total_work += work(k);
+    // below ~64 k elements of work a thread's start costs more than it saves
+    const size_t n_threads = total_work < (int64_t(1) << 16) ? 1 : std::min<size_t>(order.size(), 8);
+    std::vector<std::thread> workers;
+    try {
+        for (size_t t = 1; t < n_threads; ++t) workers.emplace_back(run);
+    } catch (const std::system_error &) { // no more threads to be had: the caller's thread does what is left
+    }
+    run();
+    for (std::thread &w : workers) w.join();
+    for (size_t k = 0; k < small.size(); ++k) {
+        if (built[k].status != HETA_OK) return fail(built[k].status, "%s", built[k].message.c_str());
+        PendingRelation pr;
+        pr.rel = static_cast<size_t>(small[k]);
+        pr.csr = lay[k].csr;
+        pr.csc = lay[k].csc;
+        pr.inv = lay[k].inv;
+        g->rels[small[k]].host_built = true;
+        pending.push_back(pr);
+    }
     return HETA_OK;
 }
 
@@ -527,14 +637,18 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
                 return st;
             }
         }
+        std::vector<int32_t> small;
         for (int32_t i = 0; i < n_rels; ++i) {
-            heta_status st = ingest_relation(g, rels[i], i, on_device, pack, pending, staged[i]);
+            bool device_path = false;
+            heta_status st = ingest_relation(g, rels[i], i, on_device, device_path);
             if (st != HETA_OK) {
                 destroy(g);
                 return st;
             }
+            if (!device_path) small.push_back(i);
         }
-        heta_status st = upload_host_built(g, pack, pending);
+        heta_status st = build_small_relations(g, rels, small, on_device, staged, pack, pending);
+        if (st == HETA_OK) st = upload_host_built(g, pack, pending);
         if (st != HETA_OK) {
             destroy(g);
             return st;

@@ -43,7 +43,7 @@ def one_relation_graph(rel, n_src, n_dst):
 @pytest.fixture(scope="module", params=["host_ingest", "device_ingest"])
 def skew(request):
     """The skewed relation, ingested once by the host path (what a relation of this size gets by
-    default) and once by the device kernels (what relations of 2^17+ edges and rows get)."""
+    default) and once by the device kernels (what relations of 2^18+ edges and rows get)."""
     rel = skewed_relation()
     heta.heta_ingest_force(1 if request.param == "host_ingest" else 2)
     g, hg = one_relation_graph(rel, 3000, 2000)
