@@ -313,6 +313,20 @@ heta_status heta_sample_neighbors(const heta_graph *g, int32_t rel, const int64_
  * (checked on the device).  Synchronous. */
 heta_status heta_unique_relabel(int32_t n_lists, const int64_t *const *lists, const int64_t *lens, int64_t id_limit,
                                 int64_t *unique_ids, int64_t *n_unique, int32_t *const *local, void *hip_stream);
+/* The same two operations for several relations / several id sets in one call: every stage of every item
+ * is queued on the stream and the call synchronises once (a mini-batch hop is one call of each).
+ * heta_sample_neighbors_batch: item i samples relation rels[i] for dst_ids[i] (device [n_dst[i]]) with
+ *   seeds[i] into rowptr[i] / src_ids[i] (device, sized as above); n_sampled[i] (host) receives its count.
+ *   The arrays rels, dst_ids, n_dst, seeds, rowptr, src_ids, n_sampled are HOST arrays of n entries.
+ * heta_unique_relabel_batch: group j owns the lists group_ptr[j] .. group_ptr[j+1]-1 of `lists` / `lens` /
+ *   `local` (host arrays of device pointers / lengths) and writes unique_ids[j] (device), n_unique[j]
+ *   (host) with its own id_limit[j].  Results and errors are those of the single calls. */
+heta_status heta_sample_neighbors_batch(const heta_graph *g, int32_t n, const int32_t *rels, const int64_t *const *dst_ids,
+                                        const int64_t *n_dst, int32_t fanout, const uint64_t *seeds, int64_t *const *rowptr,
+                                        int64_t *const *src_ids, int64_t *n_sampled, void *hip_stream);
+heta_status heta_unique_relabel_batch(int32_t n_groups, const int32_t *group_ptr, const int64_t *const *lists,
+                                      const int64_t *lens, const int64_t *id_limit, int64_t *const *unique_ids,
+                                      int64_t *n_unique, int32_t *const *local, void *hip_stream);
 
 /* ---- sparse update of a learnable feature table (Sections 2.2 and 6: the learnable vectors of
  * featureless node types and their optimizer states, Adam's moment and variance, are updated after

@@ -31,7 +31,8 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam", "heta_project_batch",
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
            "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel",
-           "heta_cross_rel_aggregate_project", "heta_meta_partition"]
+           "heta_cross_rel_aggregate_project", "heta_meta_partition", "heta_sample_neighbors_batch",
+           "heta_unique_relabel_batch"]
 
 
 class HetaError(RuntimeError):
@@ -648,6 +649,79 @@ def heta_sample_neighbors(g: Graph, rel: int, dst_ids: torch.Tensor, fanout: int
                                    ctypes.c_uint64(seed & ((1 << 64) - 1)), _dev(rowptr, "rowptr"), _dev(src, "src_ids"),
                                    ctypes.byref(n_sampled), _stream(stream)))
     return rowptr, src[:n_sampled.value]
+
+
+def heta_sample_neighbors_batch(g: Graph, rels: Sequence[int], dst_ids: Sequence[torch.Tensor], fanout: int,
+                                seeds: Sequence[int], stream=None):
+    """heta_sample_neighbors for several relations in one call (one synchronisation).  Returns a list of
+    (rowptr, src_ids) pairs, one per item."""
+    n = len(rels)
+    if n == 0:
+        return []
+    dev = dst_ids[0].device
+    sizes = [int(d.numel()) for d in dst_ids]
+    # one allocation for all row offsets and one for all source ids, cut into per-item views
+    rp_all = torch.empty(sum(sizes) + n, dtype=torch.int64, device=dev)
+    src_all = torch.empty(max(1, sum(sizes) * fanout), dtype=torch.int64, device=dev)
+    rowptr, src, o_r, o_s = [], [], 0, 0
+    for k in sizes:
+        rowptr.append(rp_all[o_r:o_r + k + 1])
+        src.append(src_all[o_s:o_s + k * fanout])
+        o_r += k + 1
+        o_s += k * fanout
+    vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
+    a_rels = (i32 * n)(*[int(r) for r in rels])
+    a_dst = (vp * n)(*[_dev(d, "dst_ids", torch.int64) if d.numel() else None for d in dst_ids])
+    a_n = (i64 * n)(*sizes)
+    a_seed = (u64 * n)(*[int(x) & ((1 << 64) - 1) for x in seeds])
+    a_rp = (vp * n)(*[r.data_ptr() for r in rowptr])
+    a_src = (vp * n)(*[x.data_ptr() if x.numel() else None for x in src])
+    a_cnt = (i64 * n)()
+    L = load_library()
+    L.heta_sample_neighbors_batch.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    _check(L.heta_sample_neighbors_batch(g.handle, n, ctypes.addressof(a_rels), ctypes.addressof(a_dst), ctypes.addressof(a_n),
+                                         int(fanout), ctypes.addressof(a_seed), ctypes.addressof(a_rp), ctypes.addressof(a_src),
+                                         ctypes.addressof(a_cnt), _stream(stream)))
+    return [(rowptr[i], src[i][:a_cnt[i]]) for i in range(n)]
+
+
+def heta_unique_relabel_batch(groups: Sequence[Sequence[torch.Tensor]], id_limits: Sequence[int], stream=None):
+    """heta_unique_relabel for several id sets in one call (one synchronisation).  groups[j] is the list of
+    device int64 tensors of set j.  Returns a list of (unique_ids, [local per list]) pairs."""
+    n = len(groups)
+    if n == 0:
+        return []
+    dev = next((l.device for grp in groups for l in grp), torch.device("cuda"))
+    totals = [sum(int(l.numel()) for l in grp) for grp in groups]
+    uniq_all = torch.empty(max(1, sum(totals)), dtype=torch.int64, device=dev)
+    local_all = torch.empty(max(1, sum(totals)), dtype=torch.int32, device=dev)
+    uniq, local, lists, ptr, o_u, o_l = [], [], [], [0], 0, 0
+    for grp, tot in zip(groups, totals):
+        uniq.append(uniq_all[o_u:o_u + tot])
+        o_u += tot
+        loc = []
+        for l in grp:
+            k = int(l.numel())
+            loc.append(local_all[o_l:o_l + k])
+            o_l += k
+            lists.append(l)
+        local.append(loc)
+        ptr.append(len(lists))
+    m = max(1, len(lists))
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    a_ptr = (i32 * (n + 1))(*ptr)
+    a_lists = (vp * m)(*[_dev(l, "list", torch.int64) if l.numel() else None for l in lists])
+    a_lens = (i64 * m)(*[int(l.numel()) for l in lists])
+    a_local = (vp * m)(*[x.data_ptr() if x.numel() else None for loc in local for x in loc])
+    a_lim = (i64 * n)(*[int(x) for x in id_limits])
+    a_uniq = (vp * n)(*[u.data_ptr() if u.numel() else None for u in uniq])
+    a_cnt = (i64 * n)()
+    L = load_library()
+    L.heta_unique_relabel_batch.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    _check(L.heta_unique_relabel_batch(n, ctypes.addressof(a_ptr), ctypes.addressof(a_lists), ctypes.addressof(a_lens),
+                                       ctypes.addressof(a_lim), ctypes.addressof(a_uniq), ctypes.addressof(a_cnt),
+                                       ctypes.addressof(a_local), _stream(stream)))
+    return [(uniq[j][:a_cnt[j]], local[j]) for j in range(n)]
 
 
 def heta_unique_relabel(lists: List[torch.Tensor], id_limit: int, stream=None):

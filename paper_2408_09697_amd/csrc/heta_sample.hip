@@ -13,6 +13,7 @@
 // ascending order of the output is each lane's rank among the chosen slots.  The unique source ids of a
 // node type and the local ids of the sampled edges come from one radix sort of all sampled ids.
 #include <algorithm>
+#include <vector>
 
 #include "heta_internal.h"
 
@@ -113,23 +114,57 @@ __global__ void __launch_bounds__(256) unique_scatter_kernel(const uint32_t *key
 
 // scratch of one call, from the recycling pool (released idle: every entry point below synchronises its
 // stream before it returns, and the destructor waits for the device in case an error path did not)
-template <typename T> struct DevBuf {
-    T *p = nullptr;
-    ~DevBuf()
+struct Scratch {
+    char *p = nullptr;
+    size_t cursor = 0;
+    ~Scratch()
     {
         if (!p) return;
         (void)hipDeviceSynchronize(); // a no-op wait after the entry point's own synchronisation; covers error paths
         scratch_free(p);
     }
-    heta_status alloc(size_t n)
+    static size_t padded(size_t bytes) { return (std::max<size_t>(bytes, 1) + 255) / 256 * 256; }
+    heta_status alloc(size_t bytes)
     {
-        hipError_t e = scratch_alloc(reinterpret_cast<void **>(&p), std::max<size_t>(n, 1) * sizeof(T));
+        hipError_t e = scratch_alloc(reinterpret_cast<void **>(&p), std::max<size_t>(bytes, 256));
         if (e != hipSuccess)
             return fail(e == hipErrorOutOfMemory ? HETA_ERR_OOM : HETA_ERR_DEVICE, "allocation of sampler scratch failed: %s",
                         hipGetErrorString(e));
         return HETA_OK;
     }
+    template <typename T> T *take(size_t n) // slices were sized with padded() before alloc()
+    {
+        T *q = reinterpret_cast<T *>(p + cursor);
+        cursor += padded(n * sizeof(T));
+        return q;
+    }
 };
+
+// Counts and error flags come back through page-locked slots, so that the copies are asynchronous and a
+// whole batch is awaited once (a copy into pageable memory blocks the host until it has landed).
+struct Slot {
+    int64_t count;
+    int32_t bad;
+    int32_t pad;
+};
+struct PinnedSlots {
+    Slot *p = nullptr;
+    size_t cap = 0;
+};
+static thread_local PinnedSlots t_slots; // never freed: it lives as long as the thread samples
+
+static heta_status slots_reserve(size_t n)
+{
+    if (n <= t_slots.cap) return HETA_OK;
+    const size_t cap = std::max<size_t>(n, 64);
+    void *q = nullptr;
+    if (hipHostMalloc(&q, cap * sizeof(Slot), hipHostMallocDefault) != hipSuccess)
+        return fail(HETA_ERR_OOM, "page-locked host allocation of %zu result slots failed", cap);
+    if (t_slots.p) (void)hipHostFree(t_slots.p);
+    t_slots.p = static_cast<Slot *>(q);
+    t_slots.cap = cap;
+    return HETA_OK;
+}
 
 } // namespace
 
@@ -139,117 +174,167 @@ using namespace heta;
 
 extern "C" {
 
+heta_status heta_sample_neighbors_batch(const heta_graph *g, int32_t n, const int32_t *rels, const int64_t *const *dst_ids,
+                                        const int64_t *n_dst, int32_t fanout, const uint64_t *seeds, int64_t *const *rowptr,
+                                        int64_t *const *src_ids, int64_t *n_sampled, void *hip_stream)
+{
+    if (!g || n < 0 || (n > 0 && (!rels || !dst_ids || !n_dst || !seeds || !rowptr || !src_ids || !n_sampled)))
+        return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: null argument");
+    if (fanout < 1 || fanout > kMaxFanout)
+        return fail(HETA_ERR_SHAPE, "heta_sample_neighbors: need 1 <= fanout <= %d", kMaxFanout);
+    size_t bytes = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (rels[i] < 0 || rels[i] >= (int32_t)g->rels.size())
+            return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: relation %d out of range", rels[i]);
+        if (n_dst[i] < 0) return fail(HETA_ERR_SHAPE, "heta_sample_neighbors: need n_dst >= 0");
+        if (!rowptr[i] || (n_dst[i] > 0 && (!dst_ids[i] || !src_ids[i])))
+            return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: null argument");
+        n_sampled[i] = 0;
+        if (n_dst[i] == 0) continue;
+        bytes += Scratch::padded(static_cast<size_t>(n_dst[i]) * sizeof(int64_t)) +
+                 Scratch::padded(static_cast<size_t>(scan_scratch_elems(n_dst[i] + 1)) * sizeof(int64_t));
+    }
+    if (n == 0) return HETA_OK;
+    bytes += Scratch::padded(static_cast<size_t>(n) * sizeof(int));
+    hipStream_t st = as_stream(hip_stream);
+    Scratch scratch;
+    heta_status e;
+    if ((e = scratch.alloc(bytes)) != HETA_OK || (e = slots_reserve(static_cast<size_t>(n))) != HETA_OK) return e;
+    int *bad = scratch.take<int>(static_cast<size_t>(n));
+    HETA_HIP(hipMemsetAsync(bad, 0, static_cast<size_t>(n) * sizeof(int), st));
+    // per relation count -> scan -> fill -> count and flag to the host, all asynchronous; one synchronisation for the batch
+    for (int32_t i = 0; i < n; ++i) {
+        const Relation &r = g->rels[rels[i]];
+        t_slots.p[i].count = 0;
+        t_slots.p[i].bad = 0;
+        if (n_dst[i] == 0) {
+            HETA_HIP(hipMemsetAsync(rowptr[i], 0, sizeof(int64_t), st));
+            continue;
+        }
+        int64_t *cnt = scratch.take<int64_t>(static_cast<size_t>(n_dst[i]));
+        int64_t *tsum = scratch.take<int64_t>(static_cast<size_t>(scan_scratch_elems(n_dst[i] + 1)));
+        hipLaunchKernelGGL(sample_count_kernel, dim3((unsigned)((n_dst[i] + 255) / 256)), dim3(256), 0, st, r.csr.d_ptr, r.n_dst,
+                           dst_ids[i], n_dst[i], (int)fanout, cnt, bad + i);
+        HETA_LAUNCH_CHECK("sample_count_kernel");
+        if ((e = device_exclusive_scan_i64_async(cnt, n_dst[i], rowptr[i], n_dst[i] + 1, tsum, st)) != HETA_OK) return e;
+        hipLaunchKernelGGL(sample_fill_kernel, dim3((unsigned)((n_dst[i] + 3) / 4)), dim3(256), 0, st, r.csr.d_ptr, r.csr.d_idx,
+                           r.n_dst, dst_ids[i], n_dst[i], (int)fanout, (unsigned long long)seeds[i], rowptr[i], src_ids[i]);
+        HETA_LAUNCH_CHECK("sample_fill_kernel");
+        HETA_HIP(hipMemcpyAsync(&t_slots.p[i].bad, bad + i, sizeof(int), hipMemcpyDeviceToHost, st));
+        HETA_HIP(hipMemcpyAsync(&t_slots.p[i].count, rowptr[i] + n_dst[i], sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    }
+    HETA_HIP(hipStreamSynchronize(st));
+    for (int32_t i = 0; i < n; ++i)
+        if (t_slots.p[i].bad)
+            return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: a destination id of relation %d lies outside [0, %lld)",
+                        rels[i], (long long)g->rels[rels[i]].n_dst);
+    for (int32_t i = 0; i < n; ++i) n_sampled[i] = t_slots.p[i].count;
+    return HETA_OK;
+}
+
 heta_status heta_sample_neighbors(const heta_graph *g, int32_t rel, const int64_t *dst_ids, int64_t n_dst, int32_t fanout,
                                   uint64_t seed, int64_t *rowptr, int64_t *src_ids, int64_t *n_sampled, void *hip_stream)
 {
-    if (!g || !rowptr || !n_sampled || (n_dst > 0 && (!dst_ids || !src_ids)))
-        return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: null argument");
-    if (rel < 0 || rel >= (int32_t)g->rels.size())
-        return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: relation %d out of range", rel);
-    if (n_dst < 0 || fanout < 1 || fanout > kMaxFanout)
-        return fail(HETA_ERR_SHAPE, "heta_sample_neighbors: need n_dst >= 0 and 1 <= fanout <= %d", kMaxFanout);
-    const Relation &r = g->rels[rel];
+    if (!n_sampled) return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: null argument");
+    return heta_sample_neighbors_batch(g, 1, &rel, &dst_ids, &n_dst, fanout, &seed, &rowptr, &src_ids, n_sampled, hip_stream);
+}
+
+heta_status heta_unique_relabel_batch(int32_t n_groups, const int32_t *group_ptr, const int64_t *const *lists,
+                                      const int64_t *lens, const int64_t *id_limit, int64_t *const *unique_ids,
+                                      int64_t *n_unique, int32_t *const *local, void *hip_stream)
+{
+    if (n_groups < 0 || (n_groups > 0 && (!group_ptr || !id_limit || !unique_ids || !n_unique)))
+        return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: null argument");
+    if (n_groups == 0) return HETA_OK;
+    if (group_ptr[0] != 0) return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: group_ptr[0] must be 0");
+    std::vector<int64_t> totals(n_groups, 0);
+    size_t bytes = Scratch::padded(static_cast<size_t>(n_groups) * sizeof(int));
+    for (int32_t gidx = 0; gidx < n_groups; ++gidx) {
+        if (group_ptr[gidx + 1] < group_ptr[gidx]) return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: group_ptr decreases");
+        if (group_ptr[gidx + 1] > group_ptr[gidx] && (!lists || !lens || !local))
+            return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: null argument");
+        if (id_limit[gidx] < 0 || id_limit[gidx] > (int64_t(1) << 31))
+            return fail(HETA_ERR_SHAPE, "heta_unique_relabel: id_limit outside [0, 2^31]");
+        for (int32_t l = group_ptr[gidx]; l < group_ptr[gidx + 1]; ++l) {
+            if (lens[l] < 0 || (lens[l] > 0 && (!lists[l] || !local[l])))
+                return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: list %d is null or has a negative length", l);
+            totals[gidx] += lens[l];
+        }
+        n_unique[gidx] = 0;
+        const int64_t total = totals[gidx];
+        if (total == 0) continue;
+        if (total >= (int64_t(1) << 31)) return fail(HETA_ERR_UNSUPPORTED, "heta_unique_relabel: more than 2^31 ids");
+        if (!unique_ids[gidx]) return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: null unique_ids");
+        const size_t N = static_cast<size_t>(total), n_hist = static_cast<size_t>(sort_hist_elems(total));
+        bytes += 4 * Scratch::padded(N * sizeof(uint32_t)) + 2 * Scratch::padded(n_hist * sizeof(uint32_t)) +
+                 Scratch::padded(static_cast<size_t>(scan_scratch_elems(static_cast<int64_t>(n_hist))) * sizeof(uint32_t)) +
+                 Scratch::padded(N * sizeof(int64_t)) + Scratch::padded((N + 1) * sizeof(int64_t)) +
+                 Scratch::padded(static_cast<size_t>(scan_scratch_elems(total + 1)) * sizeof(int64_t)) +
+                 Scratch::padded(N * sizeof(int32_t));
+    }
+    if (std::all_of(totals.begin(), totals.end(), [](int64_t t) { return t == 0; })) return HETA_OK; // nothing for the device
     hipStream_t st = as_stream(hip_stream);
-    *n_sampled = 0;
-    if (n_dst == 0) {
-        HETA_HIP(hipMemsetAsync(rowptr, 0, sizeof(int64_t), st));
-        HETA_HIP(hipStreamSynchronize(st));
-        return HETA_OK;
-    }
-    // count -> scan -> fill -> counts to the host, all asynchronous; one synchronisation at the end
-    DevBuf<int64_t> cnt, tsum;
-    DevBuf<int> bad;
+    Scratch scratch;
     heta_status e;
-    if ((e = cnt.alloc(static_cast<size_t>(n_dst))) != HETA_OK) return e;
-    if ((e = tsum.alloc(static_cast<size_t>(scan_scratch_elems(n_dst + 1)))) != HETA_OK) return e;
-    if ((e = bad.alloc(1)) != HETA_OK) return e;
-    HETA_HIP(hipMemsetAsync(bad.p, 0, sizeof(int), st));
-    hipLaunchKernelGGL(sample_count_kernel, dim3((unsigned)((n_dst + 255) / 256)), dim3(256), 0, st, r.csr.d_ptr, r.n_dst, dst_ids,
-                       n_dst, (int)fanout, cnt.p, bad.p);
-    HETA_LAUNCH_CHECK("sample_count_kernel");
-    if ((e = device_exclusive_scan_i64_async(cnt.p, n_dst, rowptr, n_dst + 1, tsum.p, st)) != HETA_OK) return e;
-    hipLaunchKernelGGL(sample_fill_kernel, dim3((unsigned)((n_dst + 3) / 4)), dim3(256), 0, st, r.csr.d_ptr, r.csr.d_idx, r.n_dst,
-                       dst_ids, n_dst, (int)fanout, (unsigned long long)seed, rowptr, src_ids);
-    HETA_LAUNCH_CHECK("sample_fill_kernel");
-    int h_bad = 0;
-    HETA_HIP(hipMemcpyAsync(&h_bad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st));
-    HETA_HIP(hipMemcpyAsync(n_sampled, rowptr + n_dst, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    HETA_HIP(hipStreamSynchronize(st));
-    if (h_bad) {
-        *n_sampled = 0;
-        return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: a destination id lies outside [0, %lld)", (long long)r.n_dst);
+    if ((e = scratch.alloc(bytes)) != HETA_OK || (e = slots_reserve(static_cast<size_t>(n_groups))) != HETA_OK) return e;
+    int *bad = scratch.take<int>(static_cast<size_t>(n_groups));
+    HETA_HIP(hipMemsetAsync(bad, 0, static_cast<size_t>(n_groups) * sizeof(int), st));
+    // per group gather -> sort -> head flags -> scan -> scatter -> copies, all asynchronous; one synchronisation for the batch
+    for (int32_t gidx = 0; gidx < n_groups; ++gidx) {
+        t_slots.p[gidx].count = 0;
+        t_slots.p[gidx].bad = 0;
+        const int64_t total = totals[gidx];
+        if (total == 0) continue;
+        const size_t N = static_cast<size_t>(total), n_hist = static_cast<size_t>(sort_hist_elems(total));
+        uint32_t *k0 = scratch.take<uint32_t>(N), *v0 = scratch.take<uint32_t>(N), *k1 = scratch.take<uint32_t>(N),
+                 *v1 = scratch.take<uint32_t>(N), *hist = scratch.take<uint32_t>(n_hist), *offs = scratch.take<uint32_t>(n_hist);
+        uint32_t *tsum32 = scratch.take<uint32_t>(static_cast<size_t>(scan_scratch_elems(static_cast<int64_t>(n_hist))));
+        int64_t *head = scratch.take<int64_t>(N), *before = scratch.take<int64_t>(N + 1);
+        int64_t *tsum64 = scratch.take<int64_t>(static_cast<size_t>(scan_scratch_elems(total + 1)));
+        int32_t *local_all = scratch.take<int32_t>(N);
+        int64_t off = 0;
+        for (int32_t l = group_ptr[gidx]; l < group_ptr[gidx + 1]; ++l) {
+            if (lens[l] == 0) continue;
+            hipLaunchKernelGGL(gather_keys_kernel, dim3((unsigned)((lens[l] + 255) / 256)), dim3(256), 0, st, lists[l], lens[l], off,
+                               id_limit[gidx], k0, v0, bad + gidx);
+            HETA_LAUNCH_CHECK("gather_keys_kernel");
+            off += lens[l];
+        }
+        // an id outside the range is reported after the synchronisation; until then it is only a key like any other
+        uint32_t *ks = nullptr, *vs = nullptr;
+        if ((e = device_sort_pairs_u32_async(k0, v0, k1, v1, total, id_limit[gidx], &ks, &vs, hist, offs, tsum32, st)) != HETA_OK)
+            return e;
+        const unsigned blocks = (unsigned)((total + 255) / 256);
+        hipLaunchKernelGGL(head_flag_kernel, dim3(blocks), dim3(256), 0, st, ks, total, head);
+        HETA_LAUNCH_CHECK("head_flag_kernel");
+        if ((e = device_exclusive_scan_i64_async(head, total, before, total + 1, tsum64, st)) != HETA_OK) return e;
+        hipLaunchKernelGGL(unique_scatter_kernel, dim3(blocks), dim3(256), 0, st, ks, vs, head, before, total, unique_ids[gidx],
+                           local_all);
+        HETA_LAUNCH_CHECK("unique_scatter_kernel");
+        off = 0;
+        for (int32_t l = group_ptr[gidx]; l < group_ptr[gidx + 1]; ++l) {
+            if (lens[l] == 0) continue;
+            HETA_HIP(hipMemcpyAsync(local[l], local_all + off, static_cast<size_t>(lens[l]) * sizeof(int32_t),
+                                    hipMemcpyDeviceToDevice, st));
+            off += lens[l];
+        }
+        HETA_HIP(hipMemcpyAsync(&t_slots.p[gidx].bad, bad + gidx, sizeof(int), hipMemcpyDeviceToHost, st));
+        HETA_HIP(hipMemcpyAsync(&t_slots.p[gidx].count, before + total, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     }
+    HETA_HIP(hipStreamSynchronize(st));
+    for (int32_t gidx = 0; gidx < n_groups; ++gidx)
+        if (t_slots.p[gidx].bad)
+            return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: an id lies outside [0, %lld)", (long long)id_limit[gidx]);
+    for (int32_t gidx = 0; gidx < n_groups; ++gidx) n_unique[gidx] = t_slots.p[gidx].count;
     return HETA_OK;
 }
 
 heta_status heta_unique_relabel(int32_t n_lists, const int64_t *const *lists, const int64_t *lens, int64_t id_limit,
                                 int64_t *unique_ids, int64_t *n_unique, int32_t *const *local, void *hip_stream)
 {
-    if (n_lists < 0 || (n_lists > 0 && (!lists || !lens || !local)) || !n_unique)
-        return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: null argument");
-    if (id_limit < 0 || id_limit > (int64_t(1) << 31))
-        return fail(HETA_ERR_SHAPE, "heta_unique_relabel: id_limit outside [0, 2^31]");
-    int64_t total = 0;
-    for (int32_t l = 0; l < n_lists; ++l) {
-        if (lens[l] < 0 || (lens[l] > 0 && (!lists[l] || !local[l])))
-            return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: list %d is null or has a negative length", l);
-        total += lens[l];
-    }
-    *n_unique = 0;
-    if (total == 0) return HETA_OK;
-    if (total >= (int64_t(1) << 31)) return fail(HETA_ERR_UNSUPPORTED, "heta_unique_relabel: more than 2^31 ids");
-    if (!unique_ids) return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: null unique_ids");
-    hipStream_t st = as_stream(hip_stream);
-    // gather -> sort -> head flags -> scan -> scatter -> copies, all asynchronous; one synchronisation at the end
-    DevBuf<uint32_t> k0, v0, k1, v1, hist, offs, tsum32;
-    DevBuf<int64_t> head, before, tsum64;
-    DevBuf<int32_t> local_all;
-    DevBuf<int> bad;
-    heta_status e;
-    const size_t N = static_cast<size_t>(total);
-    const size_t n_hist = static_cast<size_t>(sort_hist_elems(total));
-    if ((e = k0.alloc(N)) != HETA_OK || (e = v0.alloc(N)) != HETA_OK || (e = k1.alloc(N)) != HETA_OK ||
-        (e = v1.alloc(N)) != HETA_OK || (e = hist.alloc(n_hist)) != HETA_OK || (e = offs.alloc(n_hist)) != HETA_OK ||
-        (e = tsum32.alloc(static_cast<size_t>(scan_scratch_elems(static_cast<int64_t>(n_hist))))) != HETA_OK ||
-        (e = head.alloc(N)) != HETA_OK || (e = before.alloc(N + 1)) != HETA_OK ||
-        (e = tsum64.alloc(static_cast<size_t>(scan_scratch_elems(total + 1)))) != HETA_OK ||
-        (e = local_all.alloc(N)) != HETA_OK || (e = bad.alloc(1)) != HETA_OK)
-        return e;
-    HETA_HIP(hipMemsetAsync(bad.p, 0, sizeof(int), st));
-    int64_t off = 0;
-    for (int32_t l = 0; l < n_lists; ++l) {
-        if (lens[l] == 0) continue;
-        hipLaunchKernelGGL(gather_keys_kernel, dim3((unsigned)((lens[l] + 255) / 256)), dim3(256), 0, st, lists[l], lens[l], off,
-                           id_limit, k0.p, v0.p, bad.p);
-        HETA_LAUNCH_CHECK("gather_keys_kernel");
-        off += lens[l];
-    }
-    // an id outside the range is reported after the synchronisation; until then it is only a key like any other
-    uint32_t *ks = nullptr, *vs = nullptr;
-    if ((e = device_sort_pairs_u32_async(k0.p, v0.p, k1.p, v1.p, total, id_limit, &ks, &vs, hist.p, offs.p, tsum32.p, st)) != HETA_OK)
-        return e;
-    const unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(head_flag_kernel, dim3(blocks), dim3(256), 0, st, ks, total, head.p);
-    HETA_LAUNCH_CHECK("head_flag_kernel");
-    if ((e = device_exclusive_scan_i64_async(head.p, total, before.p, total + 1, tsum64.p, st)) != HETA_OK) return e;
-    hipLaunchKernelGGL(unique_scatter_kernel, dim3(blocks), dim3(256), 0, st, ks, vs, head.p, before.p, total, unique_ids,
-                       local_all.p);
-    HETA_LAUNCH_CHECK("unique_scatter_kernel");
-    off = 0;
-    for (int32_t l = 0; l < n_lists; ++l) {
-        if (lens[l] == 0) continue;
-        HETA_HIP(hipMemcpyAsync(local[l], local_all.p + off, static_cast<size_t>(lens[l]) * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
-        off += lens[l];
-    }
-    int h_bad = 0;
-    HETA_HIP(hipMemcpyAsync(&h_bad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st));
-    HETA_HIP(hipMemcpyAsync(n_unique, before.p + total, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    HETA_HIP(hipStreamSynchronize(st));
-    if (h_bad) {
-        *n_unique = 0;
-        return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: an id lies outside [0, %lld)", (long long)id_limit);
-    }
-    return HETA_OK;
+    if (n_lists < 0 || !n_unique) return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: null argument");
+    const int32_t group_ptr[2] = {0, n_lists};
+    return heta_unique_relabel_batch(1, group_ptr, lists, lens, &id_limit, &unique_ids, n_unique, local, hip_stream);
 }
 
 } // extern "C"

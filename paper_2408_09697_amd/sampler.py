@@ -1,8 +1,8 @@
 """Sequencing of the device sampler for a k-hop mini-batch (Section 2.2 and the sampling step of
 Algorithm 1 of the paper): hop by hop from the seeds outwards, per relation a call of
 `heta_sample_neighbors` on the current frontier of its destination type, then per source type one
-`heta_unique_relabel` over the relations leaving it, and one `heta_graph_create` on the device
-arrays of the hop.  No arithmetic here beyond the seed given to each (hop, relation) pair.
+`heta_unique_relabel` over the relations leaving it (each hop issues them as one batched call of each
+kind, synchronising twice), and one `heta_graph_create` on the device arrays of the hop.  No arithmetic here beyond the seed given to each (hop, relation) pair.
 """
 from __future__ import annotations
 
@@ -41,17 +41,18 @@ def sample_blocks(base: hb.Graph, seed_type: int, seeds: torch.Tensor, fanouts: 
     empty = torch.zeros(0, dtype=torch.int64, device=seeds.device)
     blocks: List[DeviceBlock] = []
     for hop, fanout in enumerate(reversed(list(fanouts))):
-        rowptrs, srcs = [], []
-        for i, (s, t, _) in enumerate(base.rels):
-            dst = frontier[t] if frontier[t] is not None else empty
-            rp, src = hb.heta_sample_neighbors(base, i, dst, fanout, relation_seed(seed, hop, i), stream=stream)
-            rowptrs.append(rp)
-            srcs.append(src)
+        n_rels = len(base.rels)
+        sampled = hb.heta_sample_neighbors_batch(
+            base, list(range(n_rels)), [frontier[t] if frontier[t] is not None else empty for _, t, _ in base.rels], fanout,
+            [relation_seed(seed, hop, i) for i in range(n_rels)], stream=stream)
+        rowptrs = [rp for rp, _ in sampled]
+        srcs = [src for _, src in sampled]
+        by_type = [[i for i, r in enumerate(base.rels) if r[0] == s] for s in range(T)]
+        relabelled = hb.heta_unique_relabel_batch([[srcs[i] for i in rs] for rs in by_type],
+                                                  [base.ntypes[s][0] for s in range(T)], stream=stream)
         src_ids: List[torch.Tensor] = []
-        cols: List[Optional[torch.Tensor]] = [None] * len(base.rels)
-        for s in range(T):
-            rs = [i for i, r in enumerate(base.rels) if r[0] == s]
-            uniq, local = hb.heta_unique_relabel([srcs[i] for i in rs], base.ntypes[s][0], stream=stream)
+        cols: List[Optional[torch.Tensor]] = [None] * n_rels
+        for rs, (uniq, local) in zip(by_type, relabelled):
             src_ids.append(uniq)
             for i, l in zip(rs, local):
                 cols[i] = l

@@ -132,6 +132,11 @@ def test_null_arguments_of_the_later_entry_points_fail_cleanly():
     assert lib.heta_meta_partition(2, None, 1, None, None, None, 0, 1, 1, 0, None, None, None, None, None, None, None, None,
                                    None, None, None) == hb.HETA_ERR_INVALID_ARG
     assert "null argument" in hb.heta_last_error()
+    lib.heta_sample_neighbors_batch.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    assert lib.heta_sample_neighbors_batch(None, 2, None, None, None, 5, None, None, None, None, None) == hb.HETA_ERR_INVALID_ARG
+    lib.heta_unique_relabel_batch.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    assert lib.heta_unique_relabel_batch(2, None, None, None, None, None, None, None, None) == hb.HETA_ERR_INVALID_ARG
+    assert lib.heta_unique_relabel_batch(0, None, None, None, None, None, None, None, None) == hb.HETA_OK
 
 
 def test_relation_order_rule_on_the_shapes_it_was_measured_on():

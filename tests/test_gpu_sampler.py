@@ -99,3 +99,44 @@ def test_sampled_blocks_match_the_oracle_and_run_a_layer():
     for b in blocks:
         b.graph.destroy()
     hg.destroy()
+
+
+def test_batched_sampling_and_relabelling_match_the_oracle():
+    """Several relations (and several id sets) in one call: item by item the results of the oracle, with an
+    empty frontier, a repeated relation and different seeds in the batch; an id out of range in any item
+    fails the call and names the relation."""
+    wl = "tests/sampler/batch"
+    nts = [NodeType("a", 3000, 4, False), NodeType("b", 2500, 4, False), NodeType("c", 40, 4, False)]
+    G = HetGraph(nts)
+    G.relations.append(uniform_relation("ab", 0, 1, 3000, 2500, 20000, wl))
+    G.relations.append(power_law_relation("ba", 1, 0, 2500, 3000, 60000, 1.7, wl))
+    G.relations.append(power_law_relation("ca", 2, 0, 40, 3000, 9000, 1.5, wl))
+    hg = make_graph(type("P", (), {"graph": G})())
+    g = rng.stream("tests", "sampler/batch")
+    fr = [g.permutation(nts[t].num_nodes)[:k].astype(np.int64) for t, k in ((1, 600), (0, 900), (0, 0), (1, 37))]
+    rels, seeds = [0, 1, 2, 0], [11, 0xFEEDFACE12345678, 13, 14]
+    for fanout in (3, 20):
+        got = heta.heta_sample_neighbors_batch(hg, rels, [torch.from_numpy(f).cuda() for f in fr], fanout, seeds)
+        srcs = []
+        for (rp, src), i, f, sd in zip(got, rels, fr, seeds):
+            r = G.relations[i]
+            ref_ptr, ref_src = osampler.sample_neighbors(r.rowptr, r.col, f, fanout, sd)
+            assert np.array_equal(rp.cpu().numpy(), ref_ptr) and np.array_equal(src.cpu().numpy(), ref_src)
+            srcs.append(src)
+        # source sets per source type: relations 0 and 3 leave type a, 1 leaves b, 2 leaves c; plus an empty group
+        groups = [[srcs[0], srcs[3]], [srcs[1]], [srcs[2]], []]
+        out = heta.heta_unique_relabel_batch(groups, [3000, 2500, 40, 10])
+        for grp, (uniq, local) in zip(groups, out):
+            ref_u, ref_l = osampler.unique_relabel([x.cpu().numpy() for x in grp])
+            assert np.array_equal(uniq.cpu().numpy(), ref_u)
+            assert len(local) == len(ref_l)
+            for a, b in zip(local, ref_l):
+                assert np.array_equal(a.cpu().numpy(), b)
+    bad = [torch.from_numpy(f).cuda() for f in fr]
+    bad[1] = torch.tensor([5, 3000], dtype=torch.int64, device="cuda")      # relation 1's destinations are type a: 3000 is out
+    with pytest.raises(heta.HetaError, match="relation 1"):
+        heta.heta_sample_neighbors_batch(hg, rels, bad, 3, seeds)
+    with pytest.raises(heta.HetaError, match="outside"):
+        heta.heta_unique_relabel_batch([[srcs[0]], [srcs[1]]], [3000, 5])
+    assert heta.heta_sample_neighbors_batch(hg, [], [], 3, []) == [] and heta.heta_unique_relabel_batch([], []) == []
+    hg.destroy()
