@@ -498,9 +498,9 @@ static void build_on_host(const std::vector<heta_ntype> &ntypes, const heta_rela
 
 static thread_local std::vector<char> t_scratch; // the transposes' fill positions; grows, never shrinks
 
-// Builds every small relation of the graph on the host, several at a time.  The box gives a process
-// 16 cores; 8 workers cover the relation counts of the paper's graphs (5 to 14 per block) and leave
-// room for the caller's other threads.  Largest relations first, dealt by an atomic counter.
+// Builds every small relation of the graph on the host, several at a time: at most 8 workers, which
+// covers the relation counts of the paper's graphs (5 to 14 per block) and leaves cores to the caller's
+// other threads.  Largest relations first, dealt by an atomic counter.
 static heta_status build_small_relations(heta_graph *g, const heta_relation *rels, const std::vector<int32_t> &small,
                                          bool on_device, const std::vector<StagedCsr> &staged, HostPack &pack,
                                          std::vector<PendingRelation> &pending)
