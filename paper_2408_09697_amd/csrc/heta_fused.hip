@@ -408,10 +408,13 @@ heta_status heta_cross_rel_aggregate_project(heta_graph *g, int32_t dst_type, in
         pack_elems += static_cast<size_t>(d_out) * ((d_in[s] + 15) / 16 * 16);
     }
     if (pack_elems * esz > g->pack_bytes) {
-        if (g->d_pack) HETA_HIP(hipFree(g->d_pack)); // waits for earlier readers
+        if (g->d_pack) {
+            HETA_HIP(hipDeviceSynchronize()); // earlier readers
+            scratch_free(g->d_pack);
+        }
         g->d_pack = nullptr;
         g->pack_bytes = 0;
-        HETA_HIP(hipMalloc(&g->d_pack, pack_elems * esz));
+        HETA_HIP(scratch_alloc(&g->d_pack, pack_elems * esz));
         g->pack_bytes = pack_elems * esz;
     }
     size_t pack_off = 0;

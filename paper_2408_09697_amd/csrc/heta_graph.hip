@@ -108,13 +108,16 @@ heta_status ensure_workspace(heta_graph *g, size_t bytes)
 {
     if (bytes <= g->ws_bytes)
         return HETA_OK;
+    // From the recycling pool: a sampled block's graph lives for one iteration, and a fresh hipMalloc for
+    // its workspace cost more than the block's whole weight gradient.
     if (g->d_ws) {
-        HETA_HIP(hipFree(g->d_ws)); // waits for everything that may still read the old buffer
+        HETA_HIP(hipDeviceSynchronize()); // everything that may still read the old buffer
+        scratch_free(g->d_ws);
         g->d_ws = nullptr;
         g->ws_bytes = 0;
     }
     size_t want = bytes + bytes / 4;
-    HETA_HIP(hipMalloc(&g->d_ws, want));
+    HETA_HIP(scratch_alloc(&g->d_ws, want));
     g->ws_bytes = want;
     return HETA_OK;
 }
@@ -348,8 +351,8 @@ static void destroy(heta_graph *g)
         (void)hipFree(r.d_inv_deg);
     }
     scratch_free(g->d_arena); // the device is idle here
-    (void)hipFree(g->d_ws);
-    (void)hipFree(g->d_pack);
+    scratch_free(g->d_ws);
+    scratch_free(g->d_pack);
     (void)hipFree(g->d_attn);
     delete g;
 }

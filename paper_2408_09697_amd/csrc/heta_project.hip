@@ -404,10 +404,13 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
         }
         if (ok) {
             if (bytes > pack_owner->pack_bytes) {
-                if (pack_owner->d_pack) HETA_HIP(hipFree(pack_owner->d_pack)); // waits for earlier readers
+                if (pack_owner->d_pack) {
+                    HETA_HIP(hipDeviceSynchronize()); // earlier readers
+                    scratch_free(pack_owner->d_pack);
+                }
                 pack_owner->d_pack = nullptr;
                 pack_owner->pack_bytes = 0;
-                HETA_HIP(hipMalloc(&pack_owner->d_pack, bytes * 2));
+                HETA_HIP(scratch_alloc(&pack_owner->d_pack, bytes * 2));
                 pack_owner->pack_bytes = bytes * 2;
             }
             char *dst = static_cast<char *>(pack_owner->d_pack);
