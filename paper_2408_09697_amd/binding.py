@@ -118,8 +118,8 @@ def _ld(t: torch.Tensor) -> int:
 
 
 def _stream(stream) -> Optional[int]:
-    if stream is None:
-        stream = torch.cuda.current_stream()
+    if stream is None:  # torch's current stream on the current device, without building a Stream object (3 us a call)
+        return torch._C._cuda_getCurrentRawStream(torch.cuda.current_device())
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 

@@ -540,7 +540,20 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         n_max = std::max(n_max, g.N);
     }
     if (p.n_split > 1 && p.k_per_split * p.n_split >= (int64_t(1) << 31) - 256) return HETA_OK;
-    const bool wide = n_max > 128;
+    bool wide = n_max > 128;
+    if (wide) {
+        // A launch that gives a workgroup to half the CUs at most (the projections of a sampled mini-batch
+        // block) is bound by the matrix pipe of the few CUs it runs on: a 128 x 256 tile keeps two wavefronts
+        // per SIMD busy for 32 MFMAs each per k-step.  128 x 128 tiles put the same work on twice the CUs.
+        int64_t mt = 0, nt = 0;
+        for (int s = 0; s < p.n_seg; ++s) {
+            mt = std::max(mt, (p.seg[s].M + BM - 1) / BM);
+            nt = std::max(nt, (p.seg[s].N + 255) / 256);
+        }
+        const int64_t inner = nt * (p.batch ? p.n_seg : 1) * (p.partial ? mt : 1);
+        const int64_t outer = p.partial ? std::max(1, p.n_split) : mt;
+        if (outer * inner <= 128) wide = false;
+    }
     *handled = true;
     if (a_dt == HETA_F32 && b_dt == HETA_F32) {
 #define HETA_D32(ARC, BRC)                                                                                          \
