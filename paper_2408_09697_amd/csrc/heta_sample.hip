@@ -34,11 +34,9 @@ __host__ __device__ inline unsigned long long mix(unsigned long long x)
 
 __device__ __forceinline__ bool id_ok(int64_t v, int64_t n_rows) { return v >= 0 && v < n_rows; }
 
-__global__ void __launch_bounds__(256) sample_count_kernel(const int64_t *ptr, int64_t n_rows, const int64_t *dst_ids,
-                                                           int64_t n, int fanout, int64_t *cnt, int *bad)
+__device__ __forceinline__ void count_one(const int64_t *ptr, int64_t n_rows, const int64_t *dst_ids, int64_t i, int fanout,
+                                          int64_t *cnt, int *bad)
 {
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (i >= n) return;
     const int64_t v = dst_ids[i];
     if (!id_ok(v, n_rows)) {
         *bad = 1; // every writer stores the same value
@@ -49,13 +47,10 @@ __global__ void __launch_bounds__(256) sample_count_kernel(const int64_t *ptr, i
     cnt[i] = deg < fanout ? deg : fanout;
 }
 
-__global__ void __launch_bounds__(256) sample_fill_kernel(const int64_t *ptr, const int32_t *idx, int64_t n_rows,
-                                                          const int64_t *dst_ids, int64_t n, int fanout,
-                                                          unsigned long long seed, const int64_t *rowptr, int64_t *out)
+// one wavefront: the sampled in-edges of destination i, ascending edge slot, at out[rowptr[i] ...]
+__device__ __forceinline__ void fill_one(const int64_t *ptr, const int32_t *idx, int64_t n_rows, const int64_t *dst_ids, int64_t i,
+                                         int fanout, unsigned long long seed, const int64_t *rowptr, int64_t *out, int lane)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (i >= n) return; // uniform per wavefront
     const int64_t v = dst_ids[i];
     if (!id_ok(v, n_rows)) return;
     const int64_t start = ptr[v], deg = ptr[v + 1] - start;
@@ -79,6 +74,67 @@ __global__ void __launch_bounds__(256) sample_fill_kernel(const int64_t *ptr, co
         rank += other < mine ? 1 : 0;
     }
     if (lane < fanout) out[base + rank] = idx[start + mine];
+}
+
+__global__ void __launch_bounds__(256) sample_count_kernel(const int64_t *ptr, int64_t n_rows, const int64_t *dst_ids,
+                                                           int64_t n, int fanout, int64_t *cnt, int *bad)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n) return;
+    count_one(ptr, n_rows, dst_ids, i, fanout, cnt, bad);
+}
+
+__global__ void __launch_bounds__(256) sample_fill_kernel(const int64_t *ptr, const int32_t *idx, int64_t n_rows,
+                                                          const int64_t *dst_ids, int64_t n, int fanout,
+                                                          unsigned long long seed, const int64_t *rowptr, int64_t *out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (i >= n) return; // uniform per wavefront
+    fill_one(ptr, idx, n_rows, dst_ids, i, fanout, seed, rowptr, out, lane);
+}
+
+// ---- several relations per launch (a hop of a mini-batch): blockIdx.y = item ------------------------------------
+constexpr int kFusedItems = 32;
+struct FusedSample { // passed by value
+    int n, fanout;
+    const int64_t *ptr[kFusedItems];
+    const int32_t *idx[kFusedItems];
+    int64_t n_rows[kFusedItems];
+    const int64_t *dst[kFusedItems];
+    int64_t n_dst[kFusedItems];
+    int64_t off[kFusedItems + 1]; // item r's counts sit at cnt_all[off[r] ...]; off[n] = total
+    unsigned long long seed[kFusedItems];
+    int64_t *rowptr[kFusedItems];
+    int64_t *out[kFusedItems];
+};
+
+__global__ void __launch_bounds__(256) sample_count_multi_kernel(FusedSample f, int64_t *cnt_all, int *bad)
+{
+    const int r = blockIdx.y;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= f.n_dst[r]) return;
+    count_one(f.ptr[r], f.n_rows[r], f.dst[r], i, f.fanout, cnt_all + f.off[r], bad + r);
+}
+
+// scan_all = exclusive scan of all items' counts laid end to end; an item's row offsets restart at 0
+__global__ void __launch_bounds__(256) sample_rowptr_multi_kernel(FusedSample f, const int64_t *scan_all, int64_t *counts)
+{
+    const int r = blockIdx.y;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i > f.n_dst[r]) return;
+    const int64_t first = scan_all[f.off[r]];
+    f.rowptr[r][i] = scan_all[f.off[r] + i] - first;
+    if (i == f.n_dst[r]) counts[r] = scan_all[f.off[r] + i] - first;
+}
+
+__global__ void __launch_bounds__(256) sample_fill_multi_kernel(FusedSample f)
+{
+    const int r = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (i >= f.n_dst[r]) return; // uniform per wavefront
+    fill_one(f.ptr[r], f.idx[r], f.n_rows[r], f.dst[r], i, f.fanout, f.seed[r], f.rowptr[r], f.out[r], lane);
 }
 
 // ---- unique + relabel ----------------------------------------------------------------------------------------
@@ -110,6 +166,54 @@ __global__ void __launch_bounds__(256) unique_scatter_kernel(const uint32_t *key
     const int64_t u = before[i] + head[i] - 1;
     if (head[i]) unique_ids[u] = keys[i];
     local_all[vals[i]] = static_cast<int32_t>(u);
+}
+
+// ---- several id sets per launch: the set's index rides in the key's high bits ---------------------------------
+constexpr int kFusedLists = 64;
+struct FusedLists { // passed by value
+    int n_lists, shift; // shift: bits of the id part of a key
+    const int64_t *ids[kFusedLists];
+    int64_t len[kFusedLists];
+    int64_t off[kFusedLists]; // position of the list's first id in the concatenation of all sets
+    int64_t limit[kFusedLists];
+    uint32_t group[kFusedLists];
+};
+struct FusedGroups { // passed by value
+    int n, shift;
+    int64_t base[kFusedItems + 1]; // set g occupies [base[g], base[g+1]) of the sorted array
+    int64_t *uniq[kFusedItems];
+};
+
+__global__ void __launch_bounds__(256) gather_keys_multi_kernel(FusedLists f, uint32_t *keys, uint32_t *vals, int *bad)
+{
+    const int l = blockIdx.y;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= f.len[l]) return;
+    const int64_t v = f.ids[l][i];
+    const bool ok = v >= 0 && v < f.limit[l];
+    if (!ok) bad[f.group[l]] = 1;
+    // an id out of range must not reach another set's key range (the sets' sizes in the sorted array are relied on)
+    keys[f.off[l] + i] = (f.group[l] << f.shift) | (ok ? static_cast<uint32_t>(v) : 0u);
+    vals[f.off[l] + i] = static_cast<uint32_t>(f.off[l] + i);
+}
+
+__global__ void __launch_bounds__(256) unique_scatter_multi_kernel(FusedGroups f, const uint32_t *keys, const uint32_t *vals,
+                                                                   const int64_t *head, const int64_t *before, int64_t n,
+                                                                   int32_t *local_all)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t key = keys[i];
+    const int g = static_cast<int>(key >> f.shift);
+    const int64_t u = before[i] + head[i] - 1 - before[f.base[g]];
+    if (head[i]) f.uniq[g][u] = static_cast<int64_t>(key & ((1u << f.shift) - 1u));
+    local_all[vals[i]] = static_cast<int32_t>(u);
+}
+
+__global__ void __launch_bounds__(64) group_counts_kernel(FusedGroups f, const int64_t *before, int64_t *counts)
+{
+    const int g = threadIdx.x;
+    if (g < f.n) counts[g] = before[f.base[g + 1]] - before[f.base[g]];
 }
 
 // scratch of one call, from the recycling pool (released idle: every entry point below synchronises its
@@ -195,10 +299,67 @@ heta_status heta_sample_neighbors_batch(const heta_graph *g, int32_t n, const in
                  Scratch::padded(static_cast<size_t>(scan_scratch_elems(n_dst[i] + 1)) * sizeof(int64_t));
     }
     if (n == 0) return HETA_OK;
-    bytes += Scratch::padded(static_cast<size_t>(n) * sizeof(int));
     hipStream_t st = as_stream(hip_stream);
     Scratch scratch;
     heta_status e;
+    int64_t all_dst = 0;
+    for (int32_t i = 0; i < n; ++i) all_dst += n_dst[i];
+    if (n <= kFusedItems && all_dst > 0) {
+        // every item in the same launches: counts of all items end to end, one scan, row offsets per item
+        FusedSample f{};
+        f.n = n;
+        f.fanout = fanout;
+        int64_t total = 0, n_max = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            const Relation &r = g->rels[rels[i]];
+            f.ptr[i] = r.csr.d_ptr;
+            f.idx[i] = r.csr.d_idx;
+            f.n_rows[i] = r.n_dst;
+            f.dst[i] = dst_ids[i];
+            f.n_dst[i] = n_dst[i];
+            f.off[i] = total;
+            f.seed[i] = seeds[i];
+            f.rowptr[i] = rowptr[i];
+            f.out[i] = src_ids[i];
+            total += n_dst[i];
+            n_max = std::max(n_max, n_dst[i]);
+        }
+        f.off[n] = total;
+        if (total >= (int64_t(1) << 31)) return fail(HETA_ERR_UNSUPPORTED, "heta_sample_neighbors: more than 2^31 destinations");
+        const size_t T = static_cast<size_t>(total);
+        const size_t fused_bytes = Scratch::padded(static_cast<size_t>(n) * sizeof(int)) + Scratch::padded(T * sizeof(int64_t)) +
+                                   Scratch::padded((T + 1) * sizeof(int64_t)) +
+                                   Scratch::padded(static_cast<size_t>(scan_scratch_elems(total + 1)) * sizeof(int64_t)) +
+                                   Scratch::padded(static_cast<size_t>(n) * sizeof(int64_t));
+        if ((e = scratch.alloc(fused_bytes)) != HETA_OK || (e = slots_reserve(2 * static_cast<size_t>(n))) != HETA_OK) return e;
+        int *bad = scratch.take<int>(static_cast<size_t>(n));
+        int64_t *cnt_all = scratch.take<int64_t>(T), *scan_all = scratch.take<int64_t>(T + 1);
+        int64_t *tsum = scratch.take<int64_t>(static_cast<size_t>(scan_scratch_elems(total + 1)));
+        int64_t *counts = scratch.take<int64_t>(static_cast<size_t>(n));
+        HETA_HIP(hipMemsetAsync(bad, 0, static_cast<size_t>(n) * sizeof(int), st));
+        hipLaunchKernelGGL(sample_count_multi_kernel, dim3((unsigned)((n_max + 255) / 256), (unsigned)n), dim3(256), 0, st, f,
+                           cnt_all, bad);
+        HETA_LAUNCH_CHECK("sample_count_multi_kernel");
+        if ((e = device_exclusive_scan_i64_async(cnt_all, total, scan_all, total + 1, tsum, st)) != HETA_OK) return e;
+        hipLaunchKernelGGL(sample_rowptr_multi_kernel, dim3((unsigned)((n_max + 1 + 255) / 256), (unsigned)n), dim3(256), 0, st, f,
+                           scan_all, counts);
+        HETA_LAUNCH_CHECK("sample_rowptr_multi_kernel");
+        hipLaunchKernelGGL(sample_fill_multi_kernel, dim3((unsigned)((n_max + 3) / 4), (unsigned)n), dim3(256), 0, st, f);
+        HETA_LAUNCH_CHECK("sample_fill_multi_kernel");
+        // counts in slots [0, n), flags in slots [n, 2n) (their .bad fields), one copy each
+        int64_t *h_counts = reinterpret_cast<int64_t *>(t_slots.p);
+        int *h_bad = reinterpret_cast<int *>(t_slots.p + n);
+        HETA_HIP(hipMemcpyAsync(h_counts, counts, static_cast<size_t>(n) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        HETA_HIP(hipMemcpyAsync(h_bad, bad, static_cast<size_t>(n) * sizeof(int), hipMemcpyDeviceToHost, st));
+        HETA_HIP(hipStreamSynchronize(st));
+        for (int32_t i = 0; i < n; ++i)
+            if (h_bad[i])
+                return fail(HETA_ERR_INVALID_ARG, "heta_sample_neighbors: a destination id of relation %d lies outside [0, %lld)",
+                            rels[i], (long long)g->rels[rels[i]].n_dst);
+        for (int32_t i = 0; i < n; ++i) n_sampled[i] = h_counts[i];
+        return HETA_OK;
+    }
+    bytes += Scratch::padded(static_cast<size_t>(n) * sizeof(int));
     if ((e = scratch.alloc(bytes)) != HETA_OK || (e = slots_reserve(static_cast<size_t>(n))) != HETA_OK) return e;
     int *bad = scratch.take<int>(static_cast<size_t>(n));
     HETA_HIP(hipMemsetAsync(bad, 0, static_cast<size_t>(n) * sizeof(int), st));
@@ -276,6 +437,94 @@ heta_status heta_unique_relabel_batch(int32_t n_groups, const int32_t *group_ptr
     hipStream_t st = as_stream(hip_stream);
     Scratch scratch;
     heta_status e;
+    {
+        // All sets in one sort when the set index fits above the ids in a 32-bit key: set g's ids then occupy
+        // exactly [base[g], base[g+1]) of the sorted array, and one pass of every stage serves all sets.
+        int id_bits = 1, set_bits = 0;
+        int64_t N = 0;
+        for (int32_t gidx = 0; gidx < n_groups; ++gidx) {
+            while ((int64_t(1) << id_bits) < id_limit[gidx]) ++id_bits;
+            N += totals[gidx];
+        }
+        while ((1 << set_bits) < n_groups) ++set_bits;
+        const int32_t n_lists = group_ptr[n_groups];
+        if (n_groups <= kFusedItems && n_lists <= kFusedLists && id_bits + set_bits <= 32 && id_bits <= 31 && N < (int64_t(1) << 31)) {
+            FusedLists fl{};
+            FusedGroups fg{};
+            fl.n_lists = n_lists;
+            fl.shift = fg.shift = id_bits;
+            fg.n = n_groups;
+            int64_t off = 0, len_max = 0;
+            int32_t *local_first = nullptr;
+            bool contiguous = true; // the lists' local arrays laid end to end in the same order: written in place
+            for (int32_t gidx = 0; gidx < n_groups; ++gidx) {
+                fg.base[gidx] = off;
+                fg.uniq[gidx] = unique_ids[gidx];
+                for (int32_t l = group_ptr[gidx]; l < group_ptr[gidx + 1]; ++l) {
+                    fl.ids[l] = lists[l];
+                    fl.len[l] = lens[l];
+                    fl.off[l] = off;
+                    fl.limit[l] = id_limit[gidx];
+                    fl.group[l] = static_cast<uint32_t>(gidx);
+                    if (lens[l] > 0) {
+                        if (!local_first) local_first = local[l];
+                        contiguous = contiguous && local[l] == local_first + off;
+                    }
+                    off += lens[l];
+                    len_max = std::max(len_max, lens[l]);
+                }
+            }
+            fg.base[n_groups] = off;
+            const size_t Ns = static_cast<size_t>(N), n_hist = static_cast<size_t>(sort_hist_elems(N));
+            const size_t fused_bytes =
+                Scratch::padded(static_cast<size_t>(n_groups) * sizeof(int)) + 4 * Scratch::padded(Ns * sizeof(uint32_t)) +
+                2 * Scratch::padded(n_hist * sizeof(uint32_t)) +
+                Scratch::padded(static_cast<size_t>(scan_scratch_elems(static_cast<int64_t>(n_hist))) * sizeof(uint32_t)) +
+                Scratch::padded(Ns * sizeof(int64_t)) + Scratch::padded((Ns + 1) * sizeof(int64_t)) +
+                Scratch::padded(static_cast<size_t>(scan_scratch_elems(N + 1)) * sizeof(int64_t)) + Scratch::padded(Ns * sizeof(int32_t)) +
+                Scratch::padded(static_cast<size_t>(n_groups) * sizeof(int64_t));
+            if ((e = scratch.alloc(fused_bytes)) != HETA_OK || (e = slots_reserve(2 * static_cast<size_t>(n_groups))) != HETA_OK) return e;
+            int *bad = scratch.take<int>(static_cast<size_t>(n_groups));
+            uint32_t *k0 = scratch.take<uint32_t>(Ns), *v0 = scratch.take<uint32_t>(Ns), *k1 = scratch.take<uint32_t>(Ns),
+                     *v1 = scratch.take<uint32_t>(Ns), *hist = scratch.take<uint32_t>(n_hist), *offs = scratch.take<uint32_t>(n_hist);
+            uint32_t *tsum32 = scratch.take<uint32_t>(static_cast<size_t>(scan_scratch_elems(static_cast<int64_t>(n_hist))));
+            int64_t *head = scratch.take<int64_t>(Ns), *before = scratch.take<int64_t>(Ns + 1);
+            int64_t *tsum64 = scratch.take<int64_t>(static_cast<size_t>(scan_scratch_elems(N + 1)));
+            int32_t *local_scratch = scratch.take<int32_t>(Ns);
+            int64_t *counts = scratch.take<int64_t>(static_cast<size_t>(n_groups));
+            int32_t *local_all = contiguous ? local_first : local_scratch;
+            HETA_HIP(hipMemsetAsync(bad, 0, static_cast<size_t>(n_groups) * sizeof(int), st));
+            hipLaunchKernelGGL(gather_keys_multi_kernel, dim3((unsigned)((len_max + 255) / 256), (unsigned)n_lists), dim3(256), 0, st, fl,
+                               k0, v0, bad);
+            HETA_LAUNCH_CHECK("gather_keys_multi_kernel");
+            uint32_t *ks = nullptr, *vs = nullptr;
+            const int64_t key_limit = static_cast<int64_t>(n_groups) << id_bits;
+            if ((e = device_sort_pairs_u32_async(k0, v0, k1, v1, N, key_limit, &ks, &vs, hist, offs, tsum32, st)) != HETA_OK) return e;
+            const unsigned blocks = (unsigned)((N + 255) / 256);
+            hipLaunchKernelGGL(head_flag_kernel, dim3(blocks), dim3(256), 0, st, ks, N, head);
+            HETA_LAUNCH_CHECK("head_flag_kernel");
+            if ((e = device_exclusive_scan_i64_async(head, N, before, N + 1, tsum64, st)) != HETA_OK) return e;
+            hipLaunchKernelGGL(unique_scatter_multi_kernel, dim3(blocks), dim3(256), 0, st, fg, ks, vs, head, before, N, local_all);
+            HETA_LAUNCH_CHECK("unique_scatter_multi_kernel");
+            hipLaunchKernelGGL(group_counts_kernel, dim3(1), dim3(64), 0, st, fg, before, counts);
+            HETA_LAUNCH_CHECK("group_counts_kernel");
+            if (!contiguous)
+                for (int32_t l = 0; l < n_lists; ++l)
+                    if (lens[l] > 0)
+                        HETA_HIP(hipMemcpyAsync(local[l], local_all + fl.off[l], static_cast<size_t>(lens[l]) * sizeof(int32_t),
+                                                hipMemcpyDeviceToDevice, st));
+            int64_t *h_counts = reinterpret_cast<int64_t *>(t_slots.p);
+            int *h_bad = reinterpret_cast<int *>(t_slots.p + n_groups);
+            HETA_HIP(hipMemcpyAsync(h_counts, counts, static_cast<size_t>(n_groups) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+            HETA_HIP(hipMemcpyAsync(h_bad, bad, static_cast<size_t>(n_groups) * sizeof(int), hipMemcpyDeviceToHost, st));
+            HETA_HIP(hipStreamSynchronize(st));
+            for (int32_t gidx = 0; gidx < n_groups; ++gidx)
+                if (h_bad[gidx])
+                    return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: an id lies outside [0, %lld)", (long long)id_limit[gidx]);
+            for (int32_t gidx = 0; gidx < n_groups; ++gidx) n_unique[gidx] = h_counts[gidx];
+            return HETA_OK;
+        }
+    }
     if ((e = scratch.alloc(bytes)) != HETA_OK || (e = slots_reserve(static_cast<size_t>(n_groups))) != HETA_OK) return e;
     int *bad = scratch.take<int>(static_cast<size_t>(n_groups));
     HETA_HIP(hipMemsetAsync(bad, 0, static_cast<size_t>(n_groups) * sizeof(int), st));

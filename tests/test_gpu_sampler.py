@@ -140,3 +140,28 @@ def test_batched_sampling_and_relabelling_match_the_oracle():
         heta.heta_unique_relabel_batch([[srcs[0]], [srcs[1]]], [3000, 5])
     assert heta.heta_sample_neighbors_batch(hg, [], [], 3, []) == [] and heta.heta_unique_relabel_batch([], []) == []
     hg.destroy()
+
+
+def test_batches_beyond_the_fused_limits_take_the_per_item_path():
+    """More than 32 items in one sampling call, and id sets whose set index does not fit above the ids in a
+    32-bit key (three sets with 2^31 possible ids each): same results, item by item."""
+    wl = "tests/sampler/batch"
+    nts = [NodeType("a", 3000, 4, False), NodeType("b", 2500, 4, False)]
+    G = HetGraph(nts)
+    G.relations.append(uniform_relation("ab", 0, 1, 3000, 2500, 20000, wl))
+    G.relations.append(power_law_relation("ba", 1, 0, 2500, 3000, 60000, 1.7, wl))
+    hg = make_graph(type("P", (), {"graph": G})())
+    g = rng.stream("tests", "sampler/fallback")
+    rels = [i % 2 for i in range(35)]
+    fr = [g.permutation(nts[1 - r].num_nodes)[:(0 if i == 7 else 40 + 3 * i)].astype(np.int64) for i, r in enumerate(rels)]
+    seeds = [1000 + i for i in range(35)]
+    got = heta.heta_sample_neighbors_batch(hg, rels, [torch.from_numpy(f).cuda() for f in fr], 6, seeds)
+    for (rp, src), i, f, sd in zip(got, rels, fr, seeds):
+        ref_ptr, ref_src = osampler.sample_neighbors(G.relations[i].rowptr, G.relations[i].col, f, 6, sd)
+        assert np.array_equal(rp.cpu().numpy(), ref_ptr) and np.array_equal(src.cpu().numpy(), ref_src)
+    big = [np.array([2**31 - 1, 5, 5, 2**30, 0], dtype=np.int64), np.array([7, 7, 7], dtype=np.int64), np.array([2**31 - 2], dtype=np.int64)]
+    out = heta.heta_unique_relabel_batch([[torch.from_numpy(x).cuda()] for x in big], [2**31] * 3)
+    for x, (uniq, local) in zip(big, out):
+        ref_u, ref_l = osampler.unique_relabel([x])
+        assert np.array_equal(uniq.cpu().numpy(), ref_u) and np.array_equal(local[0].cpu().numpy(), ref_l[0])
+    hg.destroy()
