@@ -68,7 +68,7 @@ def measure(storage: str, args, keep_problem: bool = False):
     import torch
     import paper_2408_09697_amd as heta
     from gen import workloads
-    from tests.harness import make_graph, make_layer
+    from paper_2408_09697_amd.problems import make_graph, make_layer
 
     t0 = time.perf_counter()
     if args.workload == "config4":   # mixed widths 7..789, 12 relations, 40 M edges, sum, bf16 tables
@@ -257,7 +257,7 @@ def measure_rgat(storage: str, args, heads: int = 4):
     import paper_2408_09697_amd as heta
     from gen import workloads
     import numpy as np
-    from tests.harness import dev_table, make_graph
+    from paper_2408_09697_amd.problems import dev_table, make_graph
 
     p = workloads.config3(storage, scale=args.scale, upstream=False)
     ap = workloads.attention_params(p, heads)
@@ -334,7 +334,7 @@ def measure_minibatch(args, which: str = "config5"):
     import torch
     import paper_2408_09697_amd as heta
     from gen import rng, workloads
-    from tests.harness import dev_table
+    from paper_2408_09697_amd.problems import dev_table
 
     t0 = time.perf_counter()
     mb = workloads.config5(args.scale) if which == "config5" else workloads.config2(args.scale)

@@ -8,43 +8,8 @@ import numpy as np
 import torch
 
 import paper_2408_09697_amd as heta
-from gen import rng
-
-
-def dev_table(x: np.ndarray, storage: str, pad_to: int = 1) -> torch.Tensor:
-    """Uploads a float32 host table as fp32 or bf16; `pad_to` pads the leading dimension (in
-    elements) so that rows start on 16-byte boundaries; the returned tensor is the [:, :d] view."""
-    n, d = x.shape
-    ld = (d + pad_to - 1) // pad_to * pad_to
-    if storage == "bf16":
-        bits = rng.f32_to_bf16_bits(x)
-        buf = torch.zeros((n, ld), dtype=torch.bfloat16, device="cuda")
-        buf[:, :d] = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-    else:
-        buf = torch.zeros((n, ld), dtype=torch.float32, device="cuda")
-        buf[:, :d] = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
-    return buf[:, :d]
-
-
-def make_graph(p) -> heta.Graph:
-    nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in p.graph.ntypes]
-    rels = [(r.src_type, r.dst_type, r.rowptr, r.col) for r in p.graph.relations]
-    return heta.heta_graph_create(nts, rels)
-
-
-def make_layer(p, graph: Optional[heta.Graph] = None, rels=None, project_first=None) -> heta.RafLayer:
-    graph = make_graph(p) if graph is None else graph
-    pad = 8 if p.storage == "bf16" else 4
-    tables = [dev_table(t, p.storage, pad) for t in p.tables]
-    W = [dev_table(w, p.storage, pad) for w in p.W]
-    P = None if p.pre_proj is None else [dev_table(m, "f32", 4) for m in p.pre_proj]
-    gid = None
-    if p.src_gid is not None:
-        gid = [None if g is None else torch.from_numpy(np.ascontiguousarray(g, dtype=np.int64)).cuda()
-               for g in p.src_gid]
-    op = heta.HETA_MEAN if p.op == "mean" else heta.HETA_SUM
-    return heta.RafLayer(graph, op, tables, W, p.d_out, pre_proj=P, src_gid=gid, relu=p.relu, rels=rels,
-                         project_first=project_first)
+from gen import rng  # noqa: F401
+from paper_2408_09697_amd.problems import dev_table, make_graph, make_layer  # noqa: F401  (re-exported to the tests)
 
 
 def run_layer_on_gpu(p, mode: str = "fused", project_first=None) -> Dict[str, dict]:
