@@ -197,13 +197,20 @@ __global__ void __launch_bounds__(128 * WN) gemm_kernel(GemmParams p)
         }
 }
 
-// out[m, n] = beta * out[m, n] + sum over splits (in split order) of part[s][m][n]
-__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *part, int n_split, int64_t M, int64_t N,
-                                                            float *out, int64_t ldo, float beta)
+// out[m, n] = beta * out[m, n] + sum over splits (in split order) of part[s][m][n], for every segment of
+// a batched weight gradient in one launch (blockIdx.y = segment)
+struct SplitSegs { // passed by value
+    const float *part[kMaxSeg];
+    float *out[kMaxSeg];
+    int64_t M[kMaxSeg], ldo[kMaxSeg];
+};
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(SplitSegs g, int n_split, int64_t N, float beta)
 {
+    const int seg = blockIdx.y;
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    const int64_t total = M * N;
+    const int64_t total = g.M[seg] * N;
     if (t >= total) return;
+    const float *part = g.part[seg];
     const int64_t m = t / N, n = t % N;
     float a = 0.f;
     int s = 0;
@@ -215,7 +222,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float *part, i
         for (int u = 0; u < 8; ++u) a += v[u];
     }
     for (; s < n_split; ++s) a += part[static_cast<int64_t>(s) * total + t];
-    float *o = out + m * ldo + n;
+    float *o = g.out[seg] + m * g.ldo[seg] + n;
     *o = (beta != 0.f) ? beta * *o + a : a;
 }
 
@@ -507,12 +514,22 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     p.split_b = (gout_two_terms && in_dt == HETA_BF16) ? 1 : 0;
     e = dispatch_gemm<true, true>(p, in_dt, HETA_F32, st, static_cast<int>(BK));
     if (e != HETA_OK) return e;
-    for (int s = 0; s < n_seg; ++s) {
-        const int64_t total = static_cast<int64_t>(d_in[s]) * d_out;
-        ProfScope prof("splitk_reduce_kernel", st, (n_split + 1.0) * total * 4.0, 0);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                           static_cast<const float *>(p.seg[s].C), static_cast<int>(n_split), (int64_t)d_in[s],
-                           (int64_t)d_out, dW[s], ld_dw[s], beta);
+    {
+        SplitSegs segs{};
+        int64_t total_max = 0;
+        double bytes = 0;
+        for (int s = 0; s < n_seg; ++s) {
+            const int64_t total = static_cast<int64_t>(d_in[s]) * d_out;
+            segs.part[s] = static_cast<const float *>(p.seg[s].C);
+            segs.out[s] = dW[s];
+            segs.M[s] = d_in[s];
+            segs.ldo[s] = ld_dw[s];
+            total_max = std::max(total_max, total);
+            bytes += (n_split + 1.0) * total * 4.0;
+        }
+        ProfScope prof("splitk_reduce_kernel", st, bytes, 0);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total_max + 255) / 256), (unsigned)n_seg), dim3(256), 0, st, segs,
+                           static_cast<int>(n_split), (int64_t)d_out, beta);
         HETA_LAUNCH_CHECK("splitk_reduce_kernel");
     }
     return HETA_OK;
