@@ -12,9 +12,9 @@ from .optim import sparse_adam_step
 from . import rgat
 from . import sampler
 from . import metapartition
-from .layer import (aggregate_bwd, aggregate_fwd, build, csc, cross_rel_sum, in_degree,
+from .layer import (aggregate_bwd, aggregate_fwd, aggregate_fwd_f32_sequential, build, csc, cross_rel_sum, in_degree,
                     layer_backward, layer_forward, project, project_bwd, LayerResult)
 
-__all__ = ["aggregate_bwd", "aggregate_fwd", "build", "csc", "cross_rel_sum", "in_degree",
+__all__ = ["aggregate_bwd", "aggregate_fwd", "aggregate_fwd_f32_sequential", "build", "csc", "cross_rel_sum", "in_degree",
            "layer_backward", "layer_forward", "project", "project_bwd", "LayerResult", "sparse_adam_step", "rgat", "sampler",
            "metapartition"]

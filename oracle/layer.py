@@ -106,6 +106,21 @@ def aggregate_fwd(src, dst, n_dst: int, H0: np.ndarray, op: str,
     return M
 
 
+def aggregate_fwd_f32_sequential(src, dst, n_dst: int, H0: np.ndarray, op: str) -> np.ndarray:
+    """The same neighbour sum accumulated in float32, edge after edge in list order: NOT the oracle, only a
+    yardstick for the error a plain single-precision loop makes on long rows (the tolerances of the parity
+    tests are judged against it)."""
+    src, dst = _edges(src, dst)
+    H0 = np.asarray(H0, dtype=np.float32)
+    M = np.zeros((n_dst, H0.shape[1]), dtype=np.float32)
+    for u, v in zip(src.tolist(), dst.tolist()):
+        M[v] += H0[u]
+    if op == "mean":
+        deg = np.bincount(dst, minlength=n_dst).astype(np.float32)
+        M = np.where(deg[:, None] > 0, M / np.maximum(deg, 1)[:, None], np.float32(0))
+    return M
+
+
 def aggregate_bwd(src, dst, n_src: int, n_dst: int, dM: np.ndarray, op: str,
                   out: Optional[np.ndarray] = None) -> np.ndarray:
     """dH0 [n_src, d] fp64 (+)= per-edge scatter of c_e * dM[v_e]; accumulates into `out` if given."""

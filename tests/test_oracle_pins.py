@@ -6,6 +6,7 @@ closed forms on regular graphs, linearity, the adjoint identity, finite differen
 Proposition 1 (any split of the relation set gives the same embedding), and the buffer
 shape implied by the communication example of Section 4.
 """
+import math
 import os
 
 import numpy as np
@@ -883,3 +884,21 @@ def test_metapartition_replicates_the_heaviest_partition_per_replica():
     assert mp.part_weight == [90, 40, 0, 0, 0]
     assert mp.replica_of == [-1, -1, 0, 0, 1]        # 90 vs 40; 45 vs 40; 30 vs 40
     assert mp.rel_mask[2] == mp.rel_mask[0] == [1, 0] and mp.rel_mask[4] == [0, 1]
+
+
+def test_error_scale_of_a_plain_float32_loop_on_a_long_row():
+    """Why the oracle accumulates in fp64 and what the 1e-4 bound of the fp32 parity tests means: a hub row of
+    2^17 N(0,1) neighbours summed edge after edge in float32 is off by a few 1e-6 of the row's largest
+    entry, the fp64 loop by less than 1e-12: a tree-ordered float32 sum (the GPU's) has room to spare under
+    1e-4, and the oracle's own rounding is invisible at that scale."""
+    g = rng.stream("tests", "pins/f32scale")
+    n, d = 1 << 17, 8
+    X = g.standard_normal((n, d)).astype(np.float32)
+    src = np.arange(n, dtype=np.int64)
+    dst = np.zeros(n, dtype=np.int64)
+    ref = oracle.aggregate_fwd(src, dst, 1, X, "sum")
+    exact = np.array([math.fsum(X[:, j].astype(np.float64)) for j in range(d)])
+    assert np.abs(ref[0] - exact).max() <= 1e-12 * np.abs(exact).max() + 1e-9
+    plain = oracle.aggregate_fwd_f32_sequential(src, dst, 1, X, "sum")
+    err = np.abs(plain[0].astype(np.float64) - exact).max() / max(1.0, np.abs(exact).max())
+    assert 1e-9 < err < 1e-4
