@@ -103,7 +103,9 @@ def measure(storage: str, args, keep_problem: bool = False):
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / max(1, args.steps)
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
-    step_stats = {"median_ms": per_step[len(per_step) // 2], "min_ms": per_step[0], "max_ms": per_step[-1]} if per_step else None
+    step_stats = {"median_ms": per_step[len(per_step) // 2], "min_ms": per_step[0], "max_ms": per_step[-1],
+                  "caches": "steps run back to back over the same buffers (warm); a step touches several GB, far more than "
+                            "the 256 MB last-level cache holds"} if per_step else None
 
     # forward / backward split (same stream, device events)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
