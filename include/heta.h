@@ -120,6 +120,22 @@ heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, c
                                    const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
                                    float beta, void *hip_stream);
 
+/* The same operation for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): identical arguments, kernels and results, but
+ * the partial sums of rows with 512+ edges go to a fixed array of HETA_NOALLOC_SCRATCH_BYTES that the
+ * library's code object holds on every device (until the process ends) instead of the handle's
+ * grow-on-demand workspace.  The call performs no hipMalloc / hipFree and creates no events (its
+ * launches are not seen by heta_profile_*).  The array's address is looked up once per device, by
+ * heta_graph_create or else by the first call.  A relation whose partials do not fit
+ * (ceil(E_hub / 256 + hub rows) * round8(d) * 4 bytes, E_hub = edges in rows of 512+ edges) returns
+ * HETA_ERR_UNSUPPORTED with nothing launched.  All calls on one device share the array: calls that
+ * overlap in time on one GPU (different streams or threads) race; keep them stream-ordered. */
+#define HETA_NOALLOC_SCRATCH_BYTES (32u << 20)
+heta_status heta_rel_aggregate_fwd_noalloc(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
+                                           heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
+                                           const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
+                                           float beta, void *hip_stream);
+
 /* ---- relation-specific aggregation, backward (Algorithm 1, local backpropagation with the
  * gradients of the partial aggregations) ---------------------------------------------------------
  * grad_src[u, 0:d] = beta * grad_src[u, 0:d] + sum over e in CSC column u of c_e * grad_out[row[e], 0:d]

@@ -32,7 +32,8 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
            "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel",
            "heta_cross_rel_aggregate_project", "heta_meta_partition", "heta_sample_neighbors_batch",
-           "heta_unique_relabel_batch"]
+           "heta_unique_relabel_batch", "heta_rel_aggregate_fwd_noalloc"]
+HETA_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
 class HetaError(RuntimeError):
@@ -71,6 +72,7 @@ def load_library() -> ctypes.CDLL:
     L.heta_feature_gather.argtypes = [vp, i32, i64, i32, i64, vp, i64, vp, i64, vp]
     L.heta_check_ids.argtypes = [vp, i64, i64, vp]
     L.heta_rel_aggregate_fwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, i64, vp, vp, i32, i64, f32, vp]
+    L.heta_rel_aggregate_fwd_noalloc.argtypes = L.heta_rel_aggregate_fwd.argtypes
     L.heta_rel_aggregate_bwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, vp, i64, f32, vp]
     L.heta_project.argtypes = [i64, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i32, i64, f32, vp]
     L.heta_rel_project.argtypes = [vp, i32, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i32, i64, f32, vp]
@@ -241,6 +243,21 @@ def heta_rel_aggregate_fwd(g: Graph, rel: int, op: int, src_table: torch.Tensor,
     if src_gid is not None and src_gid.numel() < g.n_src(rel):
         raise HetaError(HETA_ERR_SHAPE, "src_gid has fewer entries than the relation has sources")
     _check(load_library().heta_rel_aggregate_fwd(
+        g.handle, rel, op, _dev(src_table, "src_table"), _dt(src_table), _ld(src_table), d, src_table.shape[0],
+        _dev(src_gid, "src_gid", torch.int64), _dev(out, "out"), _dt(out), _ld(out), beta, _stream(stream)))
+    return out
+
+
+def heta_rel_aggregate_fwd_noalloc(g: Graph, rel: int, op: int, src_table: torch.Tensor, out: torch.Tensor,
+                                   d: Optional[int] = None, src_gid: Optional[torch.Tensor] = None,
+                                   beta: float = 0.0, stream=None) -> torch.Tensor:
+    """heta_rel_aggregate_fwd for callers that cannot allocate: fixed scratch, errors when it does not fit."""
+    d = src_table.shape[1] if d is None else d
+    if out.shape[0] < g.n_dst(rel):
+        raise HetaError(HETA_ERR_SHAPE, "out has fewer rows than the relation has destinations")
+    if src_gid is not None and src_gid.numel() < g.n_src(rel):
+        raise HetaError(HETA_ERR_SHAPE, "src_gid has fewer entries than the relation has sources")
+    _check(load_library().heta_rel_aggregate_fwd_noalloc(
         g.handle, rel, op, _dev(src_table, "src_table"), _dt(src_table), _ld(src_table), d, src_table.shape[0],
         _dev(src_gid, "src_gid", torch.int64), _dev(out, "out"), _dt(out), _ld(out), beta, _stream(stream)))
     return out

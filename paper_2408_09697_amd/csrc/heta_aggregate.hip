@@ -33,6 +33,7 @@
 //   - Neighbour ids of a long row are fetched 64 at a time with one coalesced load and
 //     broadcast with lane shuffles.
 #include <algorithm>
+#include <mutex>
 
 #include "heta_internal.h"
 
@@ -530,6 +531,7 @@ __global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_kernel(Agg
 // algorithmic bytes of the two row classes of one call (for the optional profiler)
 struct AggCost {
     double wave_bytes = 0, group_bytes = 0;
+    bool timed = true; // false: no event brackets (the entry point that must not allocate)
 };
 
 template <typename T, int EPC, int L, int CPL, bool DUAL = false>
@@ -541,13 +543,13 @@ static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st, 
     if (p.n_wave_items > 0) {
         const int64_t blocks = (p.n_wave_items + 3) / 4;
         if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many long rows");
-        ProfScope prof("agg_wave_kernel", st, cost.wave_bytes, 0);
+        ProfScope prof(cost.timed ? "agg_wave_kernel" : nullptr, st, cost.wave_bytes, 0);
         hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
         HETA_LAUNCH_CHECK("agg_wave_kernel");
     }
     const int n_batches = p.batch0[kShortDeg];
     if (n_batches > 0) {
-        ProfScope prof("agg_batch_kernel", st, cost.group_bytes, 0);
+        ProfScope prof(cost.timed ? "agg_batch_kernel" : nullptr, st, cost.group_bytes, 0);
         hipLaunchKernelGGL((agg_batch_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)((n_batches + 3) / 4), n_super), dim3(256), 0, st, p);
         HETA_LAUNCH_CHECK("agg_batch_kernel");
     }
@@ -567,9 +569,12 @@ static heta_status launch_vec(const AggParams &p, int n_chunks, hipStream_t st, 
     return launch_pair<T, EPC, 64, 2>(p, (n_chunks + 127) / 128, st, c);
 }
 
-// The shared entry of forward and backward.
+// The shared entry of forward and backward.  With fixed_ws the hub partials go to that buffer of
+// fixed_ws_bytes instead of the handle's grow-on-demand workspace, and nothing is allocated: a shape
+// that does not fit is an error, and the launches are not bracketed by profiling events.
 static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, heta_dtype in_dt,
-                                 int64_t table_elems_ld, hipStream_t st)
+                                 int64_t table_elems_ld, hipStream_t st, float *fixed_ws = nullptr,
+                                 size_t fixed_ws_bytes = 0)
 {
     (void)table_elems_ld;
     if (s.n_rows == 0) return HETA_OK;
@@ -625,13 +630,24 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     p.ws_stride = dual ? 2 * p.ws_ld : p.ws_ld;
     p.ws = nullptr;
     if (s.n_hub_chunks > 0) {
-        heta_status e = ensure_workspace(g, static_cast<size_t>(s.n_hub_chunks) * p.ws_stride * sizeof(float));
-        if (e != HETA_OK) return e;
-        p.ws = static_cast<float *>(g->d_ws);
+        const size_t need = static_cast<size_t>(s.n_hub_chunks) * p.ws_stride * sizeof(float);
+        if (fixed_ws) {
+            if (need > fixed_ws_bytes)
+                return fail(HETA_ERR_UNSUPPORTED,
+                            "aggregate: %lld hub chunks of %d columns need %zu bytes of partial sums, the fixed scratch "
+                            "holds %zu; use the allocating entry point",
+                            (long long)s.n_hub_chunks, p.d, need, fixed_ws_bytes);
+            p.ws = fixed_ws;
+        } else {
+            heta_status e = ensure_workspace(g, need);
+            if (e != HETA_OK) return e;
+            p.ws = static_cast<float *>(g->d_ws);
+        }
     }
     // Algorithmic bytes per row class: one neighbour row and one 4-byte index per edge, one 8-byte
     // row pointer and one output row per row.  Hub rows' outputs are written by the combine kernel.
     AggCost cost;
+    cost.timed = fixed_ws == nullptr;
     const double osz = p.out_bf16 ? 2.0 : 4.0;
     const double per_edge = static_cast<double>(p.d) * esz + 4.0 + (p.slot_w ? 4.0 * p.heads : 0.0) + (dual ? 4.0 * p.heads : 0.0);
     const double per_row = 8.0 + p.d * osz * (dual ? 2.0 : 1.0);
@@ -649,7 +665,7 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     if (s.n_hub_rows > 0) {
         if (s.n_hub_rows > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many hub rows");
         const int tiles = static_cast<int>((p.ws_ld + 255) / 256);
-        ProfScope prof("agg_hub_combine_kernel", st, static_cast<double>(s.n_hub_rows) * per_row, 0);
+        ProfScope prof(cost.timed ? "agg_hub_combine_kernel" : nullptr, st, static_cast<double>(s.n_hub_rows) * per_row, 0);
         hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, p);
         HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
         if (dual) {
@@ -725,35 +741,72 @@ __global__ void __launch_bounds__(256) check_ids_kernel(const int64_t *ids, int6
     if (i < n && (ids[i] < 0 || ids[i] >= limit)) *flag = 1; // every writer stores the same value
 }
 
+// ---- fixed scratch of the entry point that allocates nothing ------------------------------------------
+// Hub-row partial sums of heta_rel_aggregate_fwd_noalloc.  The array lives in the code object, so every
+// device the library runs on holds a copy of its own until the process ends.  In host code its name is
+// only a handle for hipGetSymbolAddress: kernels get the per-device address looked up below.
+constexpr size_t kNoallocScratchBytes = static_cast<size_t>(HETA_NOALLOC_SCRATCH_BYTES);
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static float *g_scratch_ptr[kMaxDevices];          // per device, filled once with that device current
+static std::once_flag g_scratch_once[kMaxDevices];
+
+// Address of the current device's copy of `scratch` (looked up on the first call per device).
+static heta_status noalloc_scratch(float **out)
+{
+    int dev = 0;
+    HETA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(HETA_ERR_UNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices);
+    hipError_t err = hipSuccess;
+    std::call_once(g_scratch_once[dev], [&] {
+        void *ptr = nullptr;
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        g_scratch_ptr[dev] = err == hipSuccess ? static_cast<float *>(ptr) : nullptr;
+    });
+    if (err != hipSuccess || !g_scratch_ptr[dev])
+        return fail(HETA_ERR_DEVICE, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev,
+                    err != hipSuccess ? hipGetErrorString(err) : "no address");
+    *out = g_scratch_ptr[dev];
+    return HETA_OK;
+}
+
+heta_status noalloc_scratch_init()
+{
+    float *p = nullptr;
+    return noalloc_scratch(&p);
+}
+
 } // namespace heta
 
 using namespace heta;
 
-extern "C" {
-
-heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
-                                   heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
-                                   const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
-                                   float beta, void *hip_stream)
+// argument checks shared by the two forward entry points
+static heta_status check_fwd_args(const char *fn, heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
+                                  heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
+                                  const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out, float beta)
 {
-    if (!g || !src_table || !out) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: null argument");
-    if (rel < 0 || rel >= (int32_t)g->rels.size())
-        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: relation %d out of range", rel);
-    if (op != HETA_SUM && op != HETA_MEAN) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: bad reduce op");
-    if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_fwd: beta must be 0 or 1");
-    if (!valid_dtype(in_dt) || !valid_dtype(out_dt))
-        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: bad dtype");
+    if (!g || !src_table || !out) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", fn);
+    if (rel < 0 || rel >= (int32_t)g->rels.size()) return fail(HETA_ERR_INVALID_ARG, "%s: relation %d out of range", fn, rel);
+    if (op != HETA_SUM && op != HETA_MEAN) return fail(HETA_ERR_INVALID_ARG, "%s: bad reduce op", fn);
+    if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "%s: beta must be 0 or 1", fn);
+    if (!valid_dtype(in_dt) || !valid_dtype(out_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", fn);
     if (d <= 0 || ld_src < d || ld_out < d)
-        return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_fwd: need 0 < d <= ld (d=%d ld_src=%lld ld_out=%lld)", d,
-                    (long long)ld_src, (long long)ld_out);
+        return fail(HETA_ERR_SHAPE, "%s: need 0 < d <= ld (d=%d ld_src=%lld ld_out=%lld)", fn, d, (long long)ld_src,
+                    (long long)ld_out);
     const Relation &r = g->rels[rel];
-    if (n_table_rows < 0 || n_table_rows >= (int64_t(1) << 31))
-        return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_fwd: n_table_rows outside [0, 2^31)");
+    if (n_table_rows < 0 || n_table_rows >= (int64_t(1) << 31)) return fail(HETA_ERR_SHAPE, "%s: n_table_rows outside [0, 2^31)", fn);
     if (!src_gid && n_table_rows < r.n_src)
-        return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_fwd: table has %lld rows, relation needs %lld",
-                    (long long)n_table_rows, (long long)r.n_src);
+        return fail(HETA_ERR_SHAPE, "%s: table has %lld rows, relation needs %lld", fn, (long long)n_table_rows,
+                    (long long)r.n_src);
     if ((reinterpret_cast<uintptr_t>(src_table) % dtype_size(in_dt)) || (reinterpret_cast<uintptr_t>(out) % dtype_size(out_dt)))
-        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_fwd: pointer not aligned to its element size");
+        return fail(HETA_ERR_INVALID_ARG, "%s: pointer not aligned to its element size", fn);
+    return HETA_OK;
+}
+
+static AggParams fwd_params(heta_reduce op, const void *src_table, int64_t ld_src, int32_t d, const int64_t *src_gid,
+                            void *out, heta_dtype out_dt, int64_t ld_out, float beta)
+{
     AggParams p{};
     p.table = src_table;
     p.ld = ld_src;
@@ -765,7 +818,38 @@ heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, c
     p.out_bf16 = (out_dt == HETA_BF16);
     p.beta = beta;
     p.d = d;
-    return run_aggregate(g, r.csr, p, in_dt, ld_src, as_stream(hip_stream));
+    return p;
+}
+
+extern "C" {
+
+heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
+                                   heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
+                                   const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
+                                   float beta, void *hip_stream)
+{
+    heta_status e = check_fwd_args("heta_rel_aggregate_fwd", g, rel, op, src_table, in_dt, ld_src, d, n_table_rows, src_gid,
+                                   out, out_dt, ld_out, beta);
+    if (e != HETA_OK) return e;
+    const AggParams p = fwd_params(op, src_table, ld_src, d, src_gid, out, out_dt, ld_out, beta);
+    return run_aggregate(g, g->rels[rel].csr, p, in_dt, ld_src, as_stream(hip_stream));
+}
+
+heta_status heta_rel_aggregate_fwd_noalloc(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
+                                           heta_dtype in_dt, int64_t ld_src, int32_t d, int64_t n_table_rows,
+                                           const int64_t *src_gid, void *out, heta_dtype out_dt, int64_t ld_out,
+                                           float beta, void *hip_stream)
+{
+    heta_status e = check_fwd_args("heta_rel_aggregate_fwd_noalloc", g, rel, op, src_table, in_dt, ld_src, d, n_table_rows,
+                                   src_gid, out, out_dt, ld_out, beta);
+    if (e != HETA_OK) return e;
+    float *ws = nullptr;
+    e = noalloc_scratch(&ws);
+    if (e != HETA_OK) return e;
+    const AggParams p = fwd_params(op, src_table, ld_src, d, src_gid, out, out_dt, ld_out, beta);
+    // Every partial row the combine kernel reads is written by this call's own chunk kernel first, so
+    // what an earlier call left in the array is never read and nothing needs clearing.
+    return run_aggregate(g, g->rels[rel].csr, p, in_dt, ld_src, as_stream(hip_stream), ws, kNoallocScratchBytes);
 }
 
 heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, const void *grad_out,

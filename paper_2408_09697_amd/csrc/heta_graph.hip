@@ -628,6 +628,14 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
         delete g;
         return fail(HETA_ERR_DEVICE, "hipGetDevice failed: %s", hipGetErrorString(e));
     }
+    {
+        // set-up time: this device's address of the fixed scratch of heta_rel_aggregate_fwd_noalloc
+        heta_status st = noalloc_scratch_init();
+        if (st != HETA_OK) {
+            delete g;
+            return st;
+        }
+    }
     try {
         g->rels.reserve(n_rels);
         HostPack pack;

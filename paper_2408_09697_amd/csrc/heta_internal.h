@@ -157,6 +157,9 @@ heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void
 // out[h] (fp32, compact) = sum or mean of the h-th hub row of s (rows of >= kHubMinDeg edges lead the schedule)
 heta_status aggregate_hub_rows(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld, int d,
                                const int64_t *gid, int mean, float *out, int64_t ld_out, hipStream_t st);
+// Looks up the current device's address of the fixed scratch array of heta_rel_aggregate_fwd_noalloc
+// (heta_aggregate.hip); heta_graph_create calls it so that the look-up happens at set-up time.
+heta_status noalloc_scratch_init();
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t dtype_size(heta_dtype dt) { return dt == HETA_F32 ? 4 : 2; }

@@ -73,7 +73,7 @@ bool profiling_on() { return g_on; }
 
 ProfScope::ProfScope(const char *name, hipStream_t st, double bytes, double flops) : active_(false), stream_(st)
 {
-    if (!g_on) return;
+    if (!g_on || !name) return; // a null name = a launch site that must not create events
     std::lock_guard<std::mutex> lk(g_mu);
     Pending p;
     p.kernel = kernel_id(name);
