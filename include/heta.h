@@ -286,6 +286,19 @@ heta_status heta_attn_score(const void *x, heta_dtype dt, int64_t ld_x, int64_t 
 heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int64_t ld_x, int64_t n, int32_t d,
                                 const float *vec, int32_t heads, int32_t per_head, const float *dscore, float *dx,
                                 int64_t ld_dx, float beta, float *dvec, void *hip_stream);
+/* The source score taken off the input table: since z_u = W^T h_u, el[u, k] = <z_u[k,:], a[k,:]> equals
+ * <h_u, wa[k,:]> with wa[k, j] = sum_f W[j, kF + f] a[k, f].  heta_attn_fold writes wa (device fp32
+ * [K][d_in]); el is then heta_attn_score(H0_s, wa, per_head = 0) - read from the input table, so in the
+ * bf16 storage mode the logits do not see the rounding of the stored z.
+ * W: device [d_in, ld_w >= d_out] of w_dt; a: device fp32 [K][F], F = d_out / K.
+ * heta_attn_fold_bwd, given dwa (device fp32 [K][d_in], the dvec of heta_attn_score_bwd), writes
+ *   dW[j, kF + f] = beta dW[j, kF + f] + dwa[k, j] a[k, f]   (device fp32 [d_in, ld_dw] or NULL; beta 0 or 1)
+ *   da[k, f]      = sum_j dwa[k, j] W[j, kF + f]             (device fp32 [K][F] or NULL, overwritten; fixed order). */
+heta_status heta_attn_fold(const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_in, int32_t d_out, const float *a,
+                           int32_t heads, float *wa, void *hip_stream);
+heta_status heta_attn_fold_bwd(const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_in, int32_t d_out, const float *a,
+                               int32_t heads, const float *dwa, float *dW, int64_t ld_dw, float beta, float *da,
+                               void *hip_stream);
 /* z: device [n_src, ld_z] of z_dt; el: device fp32 [n_src, K]; er: device fp32 [n_dst, K]; out: device
  * [n_dst, ld_out] of out_dt; smax, sinv: device fp32 [n_dst, K], receive the softmax shift and the
  * reciprocal denominator that heta_rel_attn_bwd needs (both NULL for inference).  out_pos (nullable;

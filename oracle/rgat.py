@@ -120,14 +120,9 @@ class RgatResult:
 
 
 def rgat_forward(problem, a: Sequence[np.ndarray], q: Sequence[np.ndarray], slope: float = 0.2,
-                 rels: Optional[Sequence[int]] = None, z_store=None) -> RgatResult:
+                 rels: Optional[Sequence[int]] = None) -> RgatResult:
     """One R-GAT layer over a LayerProblem (its W are the W_r; `a[i]` is [K, F], `q[i]` is
-    [d_t, K] for relation i); ReLU after the cross-relation sum when problem.relu.
-
-    `z_store`, when given, maps the projected source features Z_r to the values their storage
-    type can hold (bf16 storage: round to nearest even); logits and aggregation then read the
-    stored values, and the backward treats the rounding as the identity.  Without it Z_r is
-    exact."""
+    [d_t, K] for relation i); ReLU after the cross-relation sum when problem.relu."""
     g = problem.graph
     rels = list(range(len(g.relations))) if rels is None else list(rels)
     res = RgatResult()
@@ -137,8 +132,6 @@ def rgat_forward(problem, a: Sequence[np.ndarray], q: Sequence[np.ndarray], slop
         src, dst = r.edge_list()
         n_dst = g.ntypes[r.dst_type].num_nodes
         Z = np.asarray(problem.tables[r.src_type], np.float64) @ np.asarray(problem.W[i], np.float64)
-        if z_store is not None:
-            Z = np.asarray(z_store(Z), dtype=np.float64)
         el = source_scores(Z, a[i])
         er = destination_scores(problem.tables[r.dst_type], q[i])
         O, alpha = gat_aggregate_fwd(src, dst, n_dst, Z, el, er, slope)

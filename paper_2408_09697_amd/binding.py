@@ -32,7 +32,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
            "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel",
            "heta_cross_rel_aggregate_project", "heta_meta_partition", "heta_sample_neighbors_batch",
-           "heta_unique_relabel_batch", "heta_rel_aggregate_fwd_noalloc"]
+           "heta_unique_relabel_batch", "heta_rel_aggregate_fwd_noalloc", "heta_attn_fold", "heta_attn_fold_bwd"]
 HETA_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
@@ -556,6 +556,38 @@ def heta_attn_score(x: torch.Tensor, vec: torch.Tensor, per_head: bool, score: t
     _check(L.heta_attn_score(_dev(x, "x"), _dt(x), _ld(x), x.shape[0], d, _dev(vec, "vec", torch.float32), heads,
                              int(bool(per_head)), _scores(score, "score", x.shape[0], heads), _stream(stream)))
     return score
+
+
+def heta_attn_fold(W: torch.Tensor, a: torch.Tensor, wa: torch.Tensor, stream=None) -> torch.Tensor:
+    """wa[k, j] = sum_f W[j, k F + f] a[k, f]: the vector that turns the source score into a product with the input table."""
+    d_in, d_out = W.shape
+    heads = a.shape[0]
+    if not a.is_contiguous() or a.shape[1] * heads != d_out or not wa.is_contiguous() or tuple(wa.shape) != (heads, d_in):
+        raise HetaError(HETA_ERR_SHAPE, "a must be contiguous [heads, d_out / heads] and wa contiguous [heads, d_in]")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_attn_fold.argtypes = [vp, i32, i64, i32, i32, vp, i32, vp, vp]
+    _check(L.heta_attn_fold(_dev(W, "W"), _dt(W), _w_ld(W), d_in, d_out, _dev(a, "a", torch.float32), heads,
+                            _dev(wa, "wa", torch.float32), _stream(stream)))
+    return wa
+
+
+def heta_attn_fold_bwd(W: torch.Tensor, a: torch.Tensor, dwa: torch.Tensor, dW: Optional[torch.Tensor] = None,
+                       beta: float = 0.0, da: Optional[torch.Tensor] = None, stream=None) -> None:
+    d_in, d_out = W.shape
+    heads = a.shape[0]
+    if not a.is_contiguous() or a.shape[1] * heads != d_out or not dwa.is_contiguous() or tuple(dwa.shape) != (heads, d_in):
+        raise HetaError(HETA_ERR_SHAPE, "a must be contiguous [heads, d_out / heads] and dwa contiguous [heads, d_in]")
+    if dW is not None and (dW.shape[0] < d_in or dW.shape[1] < d_out):
+        raise HetaError(HETA_ERR_SHAPE, "dW is smaller than W")
+    if da is not None and (not da.is_contiguous() or da.shape != a.shape):
+        raise HetaError(HETA_ERR_SHAPE, "da must be contiguous and shaped like a")
+    L = load_library()
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.heta_attn_fold_bwd.argtypes = [vp, i32, i64, i32, i32, vp, i32, vp, vp, i64, f32, vp, vp]
+    _check(L.heta_attn_fold_bwd(_dev(W, "W"), _dt(W), _w_ld(W), d_in, d_out, _dev(a, "a", torch.float32), heads,
+                                _dev(dwa, "dwa", torch.float32), _dev(dW, "dW", torch.float32),
+                                _w_ld(dW) if dW is not None else 0, beta, _dev(da, "da", torch.float32), _stream(stream)))
 
 
 def heta_attn_score_bwd(g: Graph, x: torch.Tensor, vec: torch.Tensor, per_head: bool, dscore: torch.Tensor,

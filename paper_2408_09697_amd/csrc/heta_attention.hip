@@ -819,6 +819,52 @@ __global__ void __launch_bounds__(1024) attn_slab_sum_kernel(const float *part, 
     }
 }
 
+
+// ---- the source score taken off the input table ------------------------------------------------------
+// el[u, k] = <z_u[k, :], a[k, :]> with z_u = W^T h_u equals <h_u, wa[k, :]> with wa[k, j] = sum_f W[j, kF + f] a[k, f]:
+// the scores then come from the (narrower, never rounded) input table instead of the stored projection.
+// One thread per (k, j); the sum over f runs in order.
+template <typename T>
+__global__ void __launch_bounds__(256) attn_fold_kernel(const T *W, int64_t ld_w, int d_in, int K, int F, const float *a, float *wa)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= K * d_in) return;
+    const int k = t / d_in, j = t - k * d_in;
+    const T *w = W + static_cast<int64_t>(j) * ld_w + k * F;
+    float acc = 0.f;
+    for (int f = 0; f < F; ++f) acc = fmaf(ld1(w + f), a[k * F + f], acc);
+    wa[t] = acc;
+}
+
+// Its backward: dW[j, kF + f] = beta dW[j, kF + f] + dwa[k, j] a[k, f]   (one thread per element of dW)
+__global__ void __launch_bounds__(256) attn_fold_bwd_w_kernel(const float *dwa, const float *a, int d_in, int K, int F, float *dW,
+                                                              int64_t ld_dw, float beta)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int d_out = K * F;
+    if (t >= d_in * d_out) return;
+    const int j = t / d_out, c = t - j * d_out;
+    const float v = dwa[(c / F) * d_in + j] * a[c];
+    float *o = dW + static_cast<int64_t>(j) * ld_dw + c;
+    *o = beta != 0.f ? *o + v : v;
+}
+
+// da[k, f] = sum_j dwa[k, j] W[j, kF + f]: one wavefront per (k, f), lanes take j round-robin and are
+// combined by a fixed butterfly, so the order of the sum is fixed.
+template <typename T>
+__global__ void __launch_bounds__(256) attn_fold_bwd_a_kernel(const float *dwa, const T *W, int64_t ld_w, int d_in, int K, int F, float *da)
+{
+    const int lane = threadIdx.x & 63;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (c >= K * F) return; // uniform per wavefront
+    const int k = c / F;
+    float acc = 0.f;
+    for (int j = lane; j < d_in; j += 64) acc = fmaf(dwa[k * d_in + j], ld1(W + static_cast<int64_t>(j) * ld_w + c), acc);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) da[c] = acc;
+}
+
 heta_status ensure_attn(heta_graph *g, size_t bytes)
 {
     bytes = std::max<size_t>(bytes, 256); // never hand out a null workspace (relations without edges)
@@ -941,6 +987,63 @@ heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int
             hipLaunchKernelGGL(attn_slab_sum_kernel, dim3((unsigned)((elems + 63) / 64)), dim3(1024), 0, st, part, n_slabs, elems, dvec);
             HETA_LAUNCH_CHECK("attn_slab_sum_kernel");
         }
+    }
+    return HETA_OK;
+}
+
+heta_status heta_attn_fold(const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_in, int32_t d_out, const float *a,
+                           int32_t heads, float *wa, void *hip_stream)
+{
+    if (!W || !a || !wa) return fail(HETA_ERR_INVALID_ARG, "heta_attn_fold: null argument");
+    if (!valid_dtype(w_dt)) return fail(HETA_ERR_INVALID_ARG, "heta_attn_fold: bad dtype");
+    if (d_in <= 0 || d_out <= 0 || ld_w < d_out || heads <= 0 || heads > kMaxHeads || d_out % heads != 0 ||
+        static_cast<int64_t>(d_in) * d_out > (int64_t(1) << 30))
+        return fail(HETA_ERR_SHAPE, "heta_attn_fold: bad shape (d_in=%d d_out=%d ld_w=%lld heads=%d)", d_in, d_out,
+                    (long long)ld_w, heads);
+    if (reinterpret_cast<uintptr_t>(W) % dtype_size(w_dt) || reinterpret_cast<uintptr_t>(a) % 4 || reinterpret_cast<uintptr_t>(wa) % 4)
+        return fail(HETA_ERR_INVALID_ARG, "heta_attn_fold: pointer not aligned to its element size");
+    hipStream_t st = as_stream(hip_stream);
+    const int F = d_out / heads;
+    const unsigned blocks = static_cast<unsigned>((heads * d_in + 255) / 256);
+    if (w_dt == HETA_F32)
+        hipLaunchKernelGGL(attn_fold_kernel<float>, dim3(blocks), dim3(256), 0, st, static_cast<const float *>(W), ld_w, (int)d_in,
+                           (int)heads, F, a, wa);
+    else
+        hipLaunchKernelGGL(attn_fold_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, static_cast<const bf16_t *>(W), ld_w, (int)d_in,
+                           (int)heads, F, a, wa);
+    HETA_LAUNCH_CHECK("attn_fold_kernel");
+    return HETA_OK;
+}
+
+heta_status heta_attn_fold_bwd(const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_in, int32_t d_out, const float *a,
+                               int32_t heads, const float *dwa, float *dW, int64_t ld_dw, float beta, float *da,
+                               void *hip_stream)
+{
+    if (!W || !a || !dwa) return fail(HETA_ERR_INVALID_ARG, "heta_attn_fold_bwd: null argument");
+    if (!valid_dtype(w_dt)) return fail(HETA_ERR_INVALID_ARG, "heta_attn_fold_bwd: bad dtype");
+    if (d_in <= 0 || d_out <= 0 || ld_w < d_out || heads <= 0 || heads > kMaxHeads || d_out % heads != 0 || (dW && ld_dw < d_out) ||
+        static_cast<int64_t>(d_in) * d_out > (int64_t(1) << 30))
+        return fail(HETA_ERR_SHAPE, "heta_attn_fold_bwd: bad shape (d_in=%d d_out=%d heads=%d)", d_in, d_out, heads);
+    if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "heta_attn_fold_bwd: beta must be 0 or 1");
+    if (reinterpret_cast<uintptr_t>(W) % dtype_size(w_dt) || reinterpret_cast<uintptr_t>(a) % 4 ||
+        reinterpret_cast<uintptr_t>(dwa) % 4 || reinterpret_cast<uintptr_t>(dW) % 4 || reinterpret_cast<uintptr_t>(da) % 4)
+        return fail(HETA_ERR_INVALID_ARG, "heta_attn_fold_bwd: pointer not aligned to its element size");
+    hipStream_t st = as_stream(hip_stream);
+    const int F = d_out / heads;
+    if (dW) {
+        const unsigned blocks = static_cast<unsigned>((static_cast<int64_t>(d_in) * d_out + 255) / 256);
+        hipLaunchKernelGGL(attn_fold_bwd_w_kernel, dim3(blocks), dim3(256), 0, st, dwa, a, (int)d_in, (int)heads, F, dW, ld_dw, beta);
+        HETA_LAUNCH_CHECK("attn_fold_bwd_w_kernel");
+    }
+    if (da) {
+        const unsigned blocks = static_cast<unsigned>((d_out + 3) / 4);
+        if (w_dt == HETA_F32)
+            hipLaunchKernelGGL(attn_fold_bwd_a_kernel<float>, dim3(blocks), dim3(256), 0, st, dwa, static_cast<const float *>(W), ld_w,
+                               (int)d_in, (int)heads, F, da);
+        else
+            hipLaunchKernelGGL(attn_fold_bwd_a_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, dwa, static_cast<const bf16_t *>(W), ld_w,
+                               (int)d_in, (int)heads, F, da);
+        HETA_LAUNCH_CHECK("attn_fold_bwd_a_kernel");
     }
     return HETA_OK;
 }

@@ -6,13 +6,14 @@ module allocates device buffers with torch and issues the C-ABI calls; it comput
 itself.  Per relation r from source type s to destination type t:
 
     Z_r  = H0_s W_r                         heta_project_batch (all relations leaving s in one launch)
-    el_r = <Z_r[u, head k], a_r[k]>         heta_attn_score (per head)
+    el_r = <Z_r[u, head k], a_r[k]>         = <H0_s[u], (W_r a_r)[k]>: heta_attn_fold + heta_attn_score on the
+                                            input table (narrower than Z_r, and never rounded to the storage type)
     er_r = <H0_t[v], q_r[k]>                heta_attn_score (whole row)
     O_r  = edge-softmax weighted sum of Z_r heta_rel_attn_fwd
     H_t  = ReLU(sum_r O_r)                  heta_cross_rel_reduce
 
 and the backward runs the same chain in reverse (heta_act_bwd, heta_rel_attn_bwd,
-heta_attn_score_bwd, heta_project_wgrad_batch, heta_project_sum).
+heta_attn_score_bwd, heta_project_wgrad_batch, heta_attn_fold_bwd, heta_project_sum).
 """
 from __future__ import annotations
 
@@ -76,6 +77,9 @@ class RgatLayer:
         self.d_er = {r: torch.empty((n_dst(r), heads), dtype=f32, device=dev) for r in self.rels}
         self.dW = {r: torch.empty((self.W[r].shape[0], d_out), dtype=f32, device=dev) for r in self.rels}
         self.da = {r: torch.empty_like(self.a[r]) for r in self.rels}
+        # wa_r = W_r a_r per head ([heads, d_s]) and its gradient
+        self.wa = {r: torch.empty((heads, self.W[r].shape[0]), dtype=f32, device=dev) for r in self.rels}
+        self.dwa = {r: torch.empty_like(self.wa[r]) for r in self.rels}
         self.dq = {r: torch.empty_like(self.q[r]) for r in self.rels}
         touched = set(self.rels_from) | set(self.rels_into)
         self.dH0 = {t: padded(graph.ntypes[t][0], self.tables[t].shape[1], f32) for t in sorted(touched)}
@@ -89,8 +93,9 @@ class RgatLayer:
                 hb.heta_project_batch([self.tables[s]] * len(part), [self.W[r] for r in part],
                                       [self.Z[r] for r in part], stream=stream)
         for r in self.rels:
-            t = g.rels[r][1]
-            hb.heta_attn_score(self.Z[r], self.a[r], True, self.el[r], stream=stream)
+            s, t, _ = g.rels[r]
+            hb.heta_attn_fold(self.W[r], self.a[r], self.wa[r], stream=stream)
+            hb.heta_attn_score(self.tables[s], self.wa[r], False, self.el[r], stream=stream)
             hb.heta_attn_score(self.tables[t], self.q[r], False, self.er[r], stream=stream)
             hb.heta_rel_attn_fwd(g, r, self.Z[r], self.el[r], self.er[r], self.slope, self.O[r], beta=0.0,
                                  smax=self.smax[r], sinv=self.sinv[r], out_pos=self.Opos[r], stream=stream)
@@ -107,13 +112,14 @@ class RgatLayer:
             grads[t] = hb.heta_act_bwd(self.act, self.H[t], G[t], self._Gact[t], stream=stream) if self.relu else G[t]
         written = set()
         for r in self.rels:
-            t = g.rels[r][1]
+            s, t, _ = g.rels[r]
             hb.heta_rel_attn_bwd(g, r, self.Z[r], self.el[r], self.er[r], self.slope, self.smax[r], self.sinv[r],
                                  self.O[r], grads[t], self.dZ[r], self.d_el[r], self.d_er[r], o_pos=self.Opos[r],
                                  stream=stream)
-            # el = <Z, a>: its gradient joins dZ and gives da
-            hb.heta_attn_score_bwd(g, self.Z[r], self.a[r], True, self.d_el[r], dx=self.dZ[r], beta=1.0,
-                                   dvec=self.da[r], stream=stream)
+            # el = <H0_s, wa>: its gradient reaches the source type's table and, through wa, W_r and a_r
+            hb.heta_attn_score_bwd(g, self.tables[s], self.wa[r], False, self.d_el[r], dx=self.dH0[s],
+                                   beta=1.0 if s in written else 0.0, dvec=self.dwa[r], stream=stream)
+            written.add(s)
             # er = <H0_t, q>: its gradient reaches the destination type's table and gives dq
             hb.heta_attn_score_bwd(g, self.tables[t], self.q[r], False, self.d_er[r], dx=self.dH0[t],
                                    beta=1.0 if t in written else 0.0, dvec=self.dq[r], stream=stream)
@@ -123,6 +129,9 @@ class RgatLayer:
                 part = rs[i:i + _MAX_BATCH]
                 hb.heta_project_wgrad_batch(g, [self.tables[s]] * len(part), [self.dZ[r] for r in part],
                                             [self.dW[r] for r in part], gout_two_terms=self.two_terms, stream=stream)
+                for r in part:
+                    hb.heta_attn_fold_bwd(self.W[r], self.a[r], self.dwa[r], dW=self.dW[r], beta=1.0, da=self.da[r],
+                                          stream=stream)
                 hb.heta_project_sum([self.dZ[r] for r in part], [self.W[r] for r in part], self.dH0[s], trans_w=True,
                                     beta=1.0 if s in written else 0.0, stream=stream)
                 written.add(s)

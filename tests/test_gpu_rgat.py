@@ -2,10 +2,10 @@
 
 Tolerances: `max_j |got_ij - ref_ij| <= tol * max(1, max_j |ref_ij|)` per row, tol = 1e-4 wherever both
 sides read identical inputs (fp32 accumulation of fp32 or bf16-exact values), 2e-2 for the bf16-storage
-layer.  In that mode Z_r = H0_s W_r is stored as bf16 and the attention logits read the stored values; sharp
-softmaxes amplify that rounding (3.5e-2 on a weight gradient of the tiny workload at gain 2), so the
-gradients are compared with the oracle run on Z_r rounded to its storage type (its `z_store` hook), and
-the embeddings additionally with the oracle on exact Z_r.  The ReLU decision is kept away from its kink as in
+layer.  In that mode Z_r = H0_s W_r is stored as bf16 for the weighted sums, but the attention logits are
+taken from the input tables (el = <H0_s, W_r a_r> in fp32), so a sharp softmax does not amplify the storage
+rounding; embeddings and every gradient are compared with the plain fp64 oracle.  The largest observed scaled
+error is printed per family.  The ReLU decision is kept away from its kink as in
 the other layer tests: the upstream gradient is zeroed where the oracle's embedding is within the forward
 tolerance of zero.
 """
@@ -17,7 +17,7 @@ import paper_2408_09697_amd as heta
 from gen import rng, workloads
 from gen.graphs import HetGraph, NodeType, power_law_relation, reverse_relation, uniform_relation
 from oracle import rgat
-from tests.harness import assert_rows_close, dev_table, kink_guard, make_graph
+from tests.harness import assert_rows_close, dev_table, kink_guard, make_graph, row_err
 
 pytestmark = pytest.mark.gpu
 
@@ -159,10 +159,7 @@ def test_attention_argument_checks():
 def _run_layer(p, ap, tol):
     a64 = [np.asarray(x, np.float64) for x in ap.a]
     q64 = [np.asarray(x, np.float64) for x in ap.q]
-    # bf16 storage keeps Z_r as bf16: the oracle reads the same stored values (everything after it is fp64)
-    z_store = (lambda z: rng.round_to_bf16(z.astype(np.float32))) if p.storage == "bf16" else None
-    fwd = rgat.rgat_forward(p, a64, q64, ap.slope, z_store=z_store)
-    exact = rgat.rgat_forward(p, a64, q64, ap.slope) if z_store else fwd
+    fwd = rgat.rgat_forward(p, a64, q64, ap.slope)
     # keep the ReLU decision away from its kink (both sides get the same, guarded, upstream gradient)
     G = {t: np.where(kink_guard(fwd.H[t], tol), p.G[t], 0.0).astype(np.float32) for t in p.G}
     ref = rgat.rgat_backward(p, a64, q64, fwd, G, ap.slope)
@@ -175,32 +172,42 @@ def _run_layer(p, ap, tol):
     H = layer.forward()
     dW, da, dq, dH0 = layer.backward({t: up(g) for t, g in G.items()})
     torch.cuda.synchronize()
+    worst = {}
+
+    def check(got, want, what, family):
+        assert_rows_close(got, want, tol, what)
+        worst[family] = max(worst.get(family, 0.0), row_err(got, want))
+
     for t, h in fwd.H.items():
-        assert_rows_close(host(H[t]), h, tol, f"H[{t}]")
-        assert_rows_close(host(H[t]), exact.H[t], tol, f"H[{t}] against exact Z")
+        check(host(H[t]), h, f"H[{t}]", "H")
     rdW, rda, rdq, rdH0 = ref
     for i in range(len(p.W)):
-        assert_rows_close(host(dW[i]), rdW[i], tol, f"dW[{i}]")
-        assert_rows_close(host(da[i]), rda[i], tol, f"da[{i}]")
-        assert_rows_close(host(dq[i]), rdq[i].T, tol, f"dq[{i}]")
+        check(host(dW[i]), rdW[i], f"dW[{i}]", "dW")
+        check(host(da[i]), rda[i], f"da[{i}]", "da")
+        check(host(dq[i]), rdq[i].T, f"dq[{i}]", "dq")
     assert set(dH0) == set(rdH0)
     for t, x in rdH0.items():
-        assert_rows_close(host(dH0[t]), x, tol, f"dH0[{t}]")
+        check(host(dH0[t]), x, f"dH0[{t}]", "dH0")
     graph.destroy()
+    print(f"\n[observed] rgat {p.name} {p.storage}: " + " ".join(f"{k}={v:.2e}" for k, v in worst.items()))
+    return worst
 
 
 @pytest.mark.parametrize("storage,tol", [("f32", 1e-4), ("bf16", 2e-2)])
 @pytest.mark.parametrize("heads", [1, 4])
 def test_rgat_layer_tiny(storage, tol, heads):
     p = workloads.rgat_tiny(storage)
-    _run_layer(p, workloads.attention_params(p, heads, gain=2.0), tol)
+    worst = _run_layer(p, workloads.attention_params(p, heads, gain=2.0), tol)
+    # the observed error stays well inside the contractual tolerance (a regression guard, not the contract)
+    assert max(worst.values()) <= (1.2e-2 if storage == "bf16" else 1e-5)
 
 
 @pytest.mark.parametrize("storage,tol", [("f32", 1e-4), ("bf16", 2e-2)])
 def test_rgat_layer_config3_scaled(storage, tol):
     p = workloads.config3(storage, scale=0.02)
     p.relu = True
-    _run_layer(p, workloads.attention_params(p, 4, gain=1.0), tol)
+    worst = _run_layer(p, workloads.attention_params(p, 4, gain=1.0), tol)
+    assert max(worst.values()) <= (1.2e-2 if storage == "bf16" else 1e-5)
 
 
 def test_rgat_layer_on_a_sampled_block():
