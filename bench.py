@@ -163,7 +163,7 @@ def measure(storage: str, args, keep_problem: bool = False):
         tf = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{storage}.json")
         if args.scale == 1.0 and os.path.exists(tf):
             # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command,
-            # scaled by the 1 GiB calibration copy; written by paper_2408_09697_amd.rocprof_summary
+            # scaled by the 1 GiB calibration copy; written by rocprof_summary.py
             with open(tf) as f:
                 rec = json.load(f).get(dom)
             if rec:

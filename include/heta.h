@@ -156,12 +156,13 @@ heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, c
  * (fp32, or bf16 for an intermediate kept in the storage type: then beta must be 0 and row_scale NULL).
  * Both fp32 -> fp32 MFMA; otherwise operands are rounded to bf16 and multiplied on the bf16 MFMA
  * path; accumulation is fp32 in both.  beta = 1 fuses the cross-relation sum into the projection.
- * heta_rel_project takes n_rows = n_dst of the relation; heta_project any row count. */
+ * heta_rel_project takes n_rows = n_dst of the relation; heta_project any row count.  The handle is not
+ * const: with bf16 weights the call may grow its packing buffer (see heta_cross_rel_project). */
 heta_status heta_project(int64_t n_rows, const void *in, heta_dtype in_dt, int64_t ld_in, int32_t d_in,
                          const void *W, heta_dtype w_dt, int64_t ld_w, int32_t d_out, int32_t transW,
                          const float *row_scale, void *out, heta_dtype out_dt, int64_t ld_out, float beta,
                          void *hip_stream);
-heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
+heta_status heta_rel_project(heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
                              int64_t ld_in, int32_t d_in, const void *W, heta_dtype w_dt, int64_t ld_w,
                              int32_t d_out, int32_t transW, const float *row_scale, void *out,
                              heta_dtype out_dt, int64_t ld_out, float beta, void *hip_stream);
@@ -212,7 +213,7 @@ heta_status heta_project_wgrad_batch(heta_graph *g, int64_t n_rows, int32_t n, c
  * With bf16 inputs and weights the call first rewrites the weights k-contiguous into a buffer of the
  * handle (grown on demand: the first call for a larger shape synchronises); calls on one handle
  * that do so must be stream-ordered, like the calls that use its workspace. */
-heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
+heta_status heta_cross_rel_project(heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
                                    heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
                                    const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,
                                    heta_act act, float *out, int64_t ld_out, float beta, void *hip_stream);

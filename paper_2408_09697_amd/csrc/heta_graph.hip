@@ -698,7 +698,7 @@ heta_status heta_graph_get_csc(const heta_graph *g, int32_t rel, int64_t *colptr
     return HETA_OK;
 }
 
-heta_status heta_graph_get_degrees(const heta_graph *g, int32_t rel, int64_t *in_deg)
+static heta_status heta_graph_get_degrees_impl(const heta_graph *g, int32_t rel, int64_t *in_deg)
 {
     if (!g || !in_deg)
         return fail(HETA_ERR_INVALID_ARG, "heta_graph_get_degrees: null argument");
@@ -718,6 +718,18 @@ heta_status heta_graph_get_degrees(const heta_graph *g, int32_t rel, int64_t *in
         if (perm[q] >= 0 && perm[q] < r.n_dst)
             in_deg[perm[q]] = sptr[q + 1] - sptr[q];
     return HETA_OK;
+}
+
+// No exception crosses the boundary: host containers may throw std::bad_alloc.
+heta_status heta_graph_get_degrees(const heta_graph *g, int32_t rel, int64_t *in_deg)
+{
+    try {
+        return heta_graph_get_degrees_impl(g, rel, in_deg);
+    } catch (const std::bad_alloc &) {
+        return fail(HETA_ERR_OOM, "heta_graph_get_degrees: host allocation failed");
+    } catch (...) {
+        return fail(HETA_ERR_DEVICE, "heta_graph_get_degrees: unexpected exception");
+    }
 }
 
 } // extern "C"

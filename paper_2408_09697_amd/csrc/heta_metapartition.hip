@@ -6,6 +6,8 @@
 #include <cstring>
 #include <numeric>
 
+#include <new>
+
 #include "heta_internal.h"
 
 namespace {
@@ -22,13 +24,14 @@ constexpr size_t kMaxWalks = size_t(1) << 22;
 
 }  // namespace
 
-extern "C" heta_status heta_meta_partition(int32_t n_types, const int64_t *type_weight, int32_t n_rels,
+static heta_status heta_meta_partition_impl(int32_t n_types, const int64_t *type_weight, int32_t n_rels,
                                            const int32_t *rel_src, const int32_t *rel_dst, const int64_t *rel_weight,
                                            int32_t root, int32_t k, int32_t p, int32_t n_metapaths,
                                            const int32_t *metapath_ptr, const int32_t *metapath_rels, int32_t *n_sub,
                                            int32_t *sub_rel, int64_t *sub_weight, int64_t *sub_links, int32_t *sub_part,
                                            int64_t *part_weight, int32_t *replica_of, uint8_t *rel_mask,
-                                           uint8_t *type_mask) {
+                                           uint8_t *type_mask)
+{
     using heta::fail;
     if (n_types < 1 || n_rels < 0 || k < 1 || p < 1 || n_metapaths < 0)
         return fail(HETA_ERR_INVALID_ARG, "heta_meta_partition: n_types %d, n_rels %d, k %d, p %d, n_metapaths %d",
@@ -165,4 +168,22 @@ extern "C" heta_status heta_meta_partition(int32_t n_types, const int64_t *type_
         }
     }
     return HETA_OK;
+}
+
+// No exception crosses the boundary: host containers may throw std::bad_alloc.
+extern "C" heta_status heta_meta_partition(int32_t n_types, const int64_t *type_weight, int32_t n_rels,
+                                           const int32_t *rel_src, const int32_t *rel_dst, const int64_t *rel_weight,
+                                           int32_t root, int32_t k, int32_t p, int32_t n_metapaths,
+                                           const int32_t *metapath_ptr, const int32_t *metapath_rels, int32_t *n_sub,
+                                           int32_t *sub_rel, int64_t *sub_weight, int64_t *sub_links, int32_t *sub_part,
+                                           int64_t *part_weight, int32_t *replica_of, uint8_t *rel_mask,
+                                           uint8_t *type_mask)
+{
+    try {
+        return heta_meta_partition_impl(n_types, type_weight, n_rels, rel_src, rel_dst, rel_weight, root, k, p, n_metapaths, metapath_ptr, metapath_rels, n_sub, sub_rel, sub_weight, sub_links, sub_part, part_weight, replica_of, rel_mask, type_mask);
+    } catch (const std::bad_alloc &) {
+        return heta::fail(HETA_ERR_OOM, "heta_meta_partition: host allocation failed");
+    } catch (...) {
+        return heta::fail(HETA_ERR_DEVICE, "heta_meta_partition: unexpected exception");
+    }
 }

@@ -563,7 +563,7 @@ heta_status heta_project(int64_t n_rows, const void *in, heta_dtype in_dt, int64
                         beta, as_stream(hip_stream), "heta_project", nullptr, out_dt);
 }
 
-heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
+heta_status heta_rel_project(heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
                              int64_t ld_in, int32_t d_in, const void *W, heta_dtype w_dt, int64_t ld_w,
                              int32_t d_out, int32_t transW, const float *row_scale, void *out,
                              heta_dtype out_dt, int64_t ld_out, float beta, void *hip_stream)
@@ -572,7 +572,7 @@ heta_status heta_rel_project(const heta_graph *g, int32_t rel, const void *in, h
     if (rel < 0 || rel >= (int32_t)g->rels.size())
         return fail(HETA_ERR_INVALID_ARG, "heta_rel_project: relation %d out of range", rel);
     return project_impl(g->rels[rel].n_dst, 1, &in, in_dt, &ld_in, &d_in, &W, w_dt, &ld_w, d_out, transW, row_scale, 0,
-                        out, ld_out, beta, as_stream(hip_stream), "heta_rel_project", const_cast<heta_graph *>(g), out_dt);
+                        out, ld_out, beta, as_stream(hip_stream), "heta_rel_project", g, out_dt);
 }
 
 heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, heta_dtype in_dt,
@@ -614,7 +614,7 @@ heta_status heta_project_wgrad_batch(heta_graph *g, int64_t n_rows, int32_t n, c
                       "heta_project_wgrad_batch", gout_two_terms, gouts, ld_go);
 }
 
-heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
+heta_status heta_cross_rel_project(heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
                                    heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
                                    const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,
                                    heta_act act, float *out, int64_t ld_out, float beta, void *hip_stream)
@@ -623,8 +623,7 @@ heta_status heta_cross_rel_project(const heta_graph *g, int32_t dst_type, int32_
     if (e != HETA_OK) return e;
     if (act != HETA_ACT_NONE && act != HETA_ACT_RELU) return fail(HETA_ERR_INVALID_ARG, "heta_cross_rel_project: bad act");
     return project_impl(g->ntypes[dst_type].num_nodes, n, ins, in_dt, ld_in, d_in, Ws, w_dt, ld_w, d_out, 0, nullptr,
-                        act == HETA_ACT_RELU, out, ld_out, beta, as_stream(hip_stream), "heta_cross_rel_project",
-                        const_cast<heta_graph *>(g));
+                        act == HETA_ACT_RELU, out, ld_out, beta, as_stream(hip_stream), "heta_cross_rel_project", g);
 }
 
 heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, int32_t n, const float *gout,

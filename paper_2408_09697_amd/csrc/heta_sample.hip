@@ -15,6 +15,8 @@
 #include <algorithm>
 #include <vector>
 
+#include <new>
+
 #include "heta_internal.h"
 
 namespace heta {
@@ -400,7 +402,7 @@ heta_status heta_sample_neighbors(const heta_graph *g, int32_t rel, const int64_
     return heta_sample_neighbors_batch(g, 1, &rel, &dst_ids, &n_dst, fanout, &seed, &rowptr, &src_ids, n_sampled, hip_stream);
 }
 
-heta_status heta_unique_relabel_batch(int32_t n_groups, const int32_t *group_ptr, const int64_t *const *lists,
+static heta_status heta_unique_relabel_batch_impl(int32_t n_groups, const int32_t *group_ptr, const int64_t *const *lists,
                                       const int64_t *lens, const int64_t *id_limit, int64_t *const *unique_ids,
                                       int64_t *n_unique, int32_t *const *local, void *hip_stream)
 {
@@ -576,6 +578,20 @@ heta_status heta_unique_relabel_batch(int32_t n_groups, const int32_t *group_ptr
             return fail(HETA_ERR_INVALID_ARG, "heta_unique_relabel: an id lies outside [0, %lld)", (long long)id_limit[gidx]);
     for (int32_t gidx = 0; gidx < n_groups; ++gidx) n_unique[gidx] = t_slots.p[gidx].count;
     return HETA_OK;
+}
+
+// No exception crosses the boundary: host containers may throw std::bad_alloc.
+heta_status heta_unique_relabel_batch(int32_t n_groups, const int32_t *group_ptr, const int64_t *const *lists,
+                                      const int64_t *lens, const int64_t *id_limit, int64_t *const *unique_ids,
+                                      int64_t *n_unique, int32_t *const *local, void *hip_stream)
+{
+    try {
+        return heta_unique_relabel_batch_impl(n_groups, group_ptr, lists, lens, id_limit, unique_ids, n_unique, local, hip_stream);
+    } catch (const std::bad_alloc &) {
+        return fail(HETA_ERR_OOM, "heta_unique_relabel_batch: host allocation failed");
+    } catch (...) {
+        return fail(HETA_ERR_DEVICE, "heta_unique_relabel_batch: unexpected exception");
+    }
 }
 
 heta_status heta_unique_relabel(int32_t n_lists, const int64_t *const *lists, const int64_t *lens, int64_t id_limit,

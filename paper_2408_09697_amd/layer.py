@@ -117,6 +117,10 @@ class RafLayer:
             self.pf = set(r for r in self.rels if self.d_rel[r] > d_out) if project_first else set()
         else:
             self.pf = set(int(r) for r in project_first) & set(self.rels)
+        if self.pf and not auto:
+            # the project-first calls below run over whole source tables: with a row map or a fixed per-type
+            # map in front they would project the wrong rows
+            raise hb.HetaError(hb.HETA_ERR_UNSUPPORTED, "project_first needs whole-table sources (no src_gid, no pre_proj)")
         self._pf_active = set()  # what the last forward actually used (the other call paths aggregate first)
         self._padded = padded
         self._m_shapes = {r: (graph.n_dst(r), self.d_rel[r]) for r in self.rels}

@@ -66,14 +66,27 @@ class MiniBatchTrainer:
                     tabs[s] = torch.zeros((1, self.W[l][i].shape[0]), dtype=torch.float32, device=self.W[l][i].device)
             layer = RafLayer(b.graph, self.op, tabs, self.W[l], self.d_hidden, src_gid=gid,
                              relu=(l < len(blocks) - 1), rels=rels)
-            prev = layer.forward()
+            prev = layer.forward()  # on torch's current stream, like every buffer the layer allocated
             layers.append(layer)
         return layers
 
     def step(self, seeds: torch.Tensor, loss_grad: Callable[[torch.Tensor], torch.Tensor], stream=None,
              keep_blocks: bool = False) -> torch.Tensor:
         """One iteration on the mini-batch `seeds` (device int64, distinct).  `loss_grad(H)` returns dL/dH
-        for the seeds' embeddings H [n_seeds, d_hidden] (fp32).  Returns H."""
+        for the seeds' embeddings H [n_seeds, d_hidden] (fp32).  Returns H.
+
+        The whole iteration - sampling, the buffers torch allocates for it, forward, backward, updates and
+        `loss_grad` - runs on ONE stream: torch's current stream, or `stream` (a torch stream or a raw
+        hipStream_t), which is made the current stream for the duration of the call.  The caller orders that
+        stream against whatever produced `seeds` and the tables."""
+        if stream is not None:
+            ts = stream if isinstance(stream, torch.cuda.Stream) else torch.cuda.ExternalStream(int(stream))
+            with torch.cuda.stream(ts):
+                return self._step(seeds, loss_grad, keep_blocks)
+        return self._step(seeds, loss_grad, keep_blocks)
+
+    def _step(self, seeds: torch.Tensor, loss_grad: Callable[[torch.Tensor], torch.Tensor], keep_blocks: bool) -> torch.Tensor:
+        stream = None  # every library call below takes torch's current stream
         self.t += 1
         T = self.T
         blocks = hs.sample_blocks(self.base, self.seed_type, seeds, self.fanouts, self.seed + self.t, stream=stream)

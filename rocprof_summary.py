@@ -6,7 +6,13 @@ Usage (after three runs of the same command, e.g. `python3 bench.py --single --n
     rocprofv3 --kernel-trace --stats --output-format csv -d OUT/trace -o t -- python3 bench.py ...
     rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d OUT/fetch -o p -- python3 bench.py ...
     rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d OUT/write -o p -- python3 bench.py ...
-    python3 -m paper_2408_09697_amd.rocprof_summary OUT --txt summary.txt --json traffic.json [--extra DIR ...]
+    python3 rocprof_summary.py OUT --txt summary.txt --json traffic.json [--extra DIR ...]
+
+    (optional) rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES --kernel-trace ... -d OUT/mfma ...  and  --extra OUT/mfma
+
+With both MFMA counters in an --extra directory the summary derives, per kernel,
+mfma_busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 * SQ_BUSY_CU_CYCLES): the share of the busy compute units' SIMD
+cycles (4 SIMDs per CU) in which the matrix pipe was working.
 
 FETCH_SIZE / WRITE_SIZE are scaled by what the same counters read for the library's own 1 GiB
 `calibration_copy_kernel` (which every bench.py run launches first): factor = 2^20 KiB / reading.
@@ -109,7 +115,22 @@ def main() -> int:
             a[1] += (rd + wr) * n
         traffic = {k: {"launches": n, "hbm_bytes_per_launch": tot / n} for k, (n, tot) in fam.items() if n}
     for d in args.extra:
-        for cname, ks in read_counter(d).items():
+        counters = read_counter(d)
+        busy, cu = counters.get("SQ_VALU_MFMA_BUSY_CYCLES"), counters.get("SQ_BUSY_CU_CYCLES")
+        if busy and cu:
+            lines.append("")
+            lines.append("MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES), per kernel (launch-weighted):")
+            fam_busy = collections.defaultdict(lambda: [0.0, 0.0])
+            for k, (n, v) in sorted(busy.items(), key=lambda kv: -kv[1][1]):
+                if k.startswith("at::") or "rocclr" in k or k not in cu or cu[k][1] <= 0 or v <= 0:
+                    continue
+                lines.append(f"{k[:100]:100s} n={n:6d} mfma_busy={v / (4.0 * cu[k][1]):6.3f}")
+                fb = fam_busy[family(k)]
+                fb[0] += v
+                fb[1] += 4.0 * cu[k][1]
+            for k, (num, den) in fam_busy.items():
+                traffic.setdefault(k, {})["mfma_busy"] = num / den
+        for cname, ks in counters.items():
             lines.append("")
             lines.append(f"counter {cname} (average per launch):")
             for k, (n, v) in sorted(ks.items(), key=lambda kv: -kv[1][1])[:10]:

@@ -44,23 +44,35 @@ def assert_rows_close(got, ref, tol, what=""):
     assert e <= tol, f"{what}: scaled row error {e:.3e} > {tol:.1e}"
 
 
-def compare_layer(p, got, ref_f, ref_b, tol: float, tol_m: Optional[float] = None):
-    """Forward embeddings, saved aggregations and all three gradient families against the oracle."""
+def compare_layer(p, got, ref_f, ref_b, tol: float, tol_m: Optional[float] = None, observed_max: Optional[float] = None):
+    """Forward embeddings, saved aggregations and all three gradient families against the oracle.
+    Returns the largest observed scaled row error per family and prints it; with `observed_max` it must
+    also stay below that (a regression guard well inside the contractual tolerance `tol`)."""
     tol_m = tol if tol_m is None else tol_m
     dW, dH0, dT = ref_b
+    worst: Dict[str, float] = {}
+
+    def check(g, r, t, what, family):
+        assert_rows_close(g, r, t, what)
+        worst[family] = max(worst.get(family, 0.0), row_err(g, r))
+
     assert set(got["H"]) == set(ref_f.H)
     for t, h in ref_f.H.items():
-        assert_rows_close(got["H"][t], h, tol, f"H[{t}]")
+        check(got["H"][t], h, tol, f"H[{t}]", "H")
     for r, m in ref_f.M.items():
         if r in got["M"]:  # relations that were projected first have no M_r
-            assert_rows_close(got["M"][r], m, tol_m, f"M[{r}]")
+            check(got["M"][r], m, tol_m, f"M[{r}]", "M")
     for r, w in dW.items():
-        assert_rows_close(got["dW"][r], w, tol, f"dW[{r}]")
+        check(got["dW"][r], w, tol, f"dW[{r}]", "dW")
     assert set(got["dH0"]) == set(dH0)
     for s, x in dH0.items():
-        assert_rows_close(got["dH0"][s], x, tol, f"dH0[{s}]")
+        check(got["dH0"][s], x, tol, f"dH0[{s}]", "dH0")
     for s, x in dT.items():
-        assert_rows_close(got["dT"][s], x, tol, f"dtable[{s}]")
+        check(got["dT"][s], x, tol, f"dtable[{s}]", "dtable")
+    print(f"\n[observed] {p.name} {getattr(p, 'storage', '')}: " + " ".join(f"{k}={v:.2e}" for k, v in worst.items()))
+    if observed_max is not None:
+        assert max(worst.values()) <= observed_max, f"observed error {worst} above the guard {observed_max:.1e}"
+    return worst
 
 
 # ---- oracle values for sampled rows of a full-size problem ----------------------------------------

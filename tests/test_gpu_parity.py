@@ -516,7 +516,10 @@ def test_layer_config3_scaled(storage, mode, gemm_path):
     got = run_layer_on_gpu(p, mode=mode)
     ref_f = oracle.layer_forward(p)
     ref_b = oracle.layer_backward(p, ref_f, p.G)
-    compare_layer(p, got, ref_f, ref_b, tol=TOL[storage])
+    # contract: 1e-4 / 2e-2.  Observed on this data: ~1e-6 for fp32; for bf16 storage 3.9e-3 on M_r (one
+    # rounding of a stored value in [1, 2): 2^-8 absolute) and 6.1e-3 on dH0 (a few such terms per row).
+    # Guarded at 1e-5 / 1e-2.
+    compare_layer(p, got, ref_f, ref_b, tol=TOL[storage], observed_max=1e-2 if storage == "bf16" else 1e-5)
 
 
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
@@ -541,7 +544,18 @@ def test_layer_config4_scaled(gemm_path, project_first):
     assert (len(got["M"]) < len(p.graph.relations)) == (project_first is None)
     ref_f = oracle.layer_forward(p)
     ref_b = oracle.layer_backward(p, ref_f, p.G)
-    compare_layer(p, got, ref_f, ref_b, tol=2e-2)
+    compare_layer(p, got, ref_f, ref_b, tol=2e-2, observed_max=1e-2)
+
+
+def test_explicit_project_first_is_rejected_with_a_row_map_or_a_fixed_map():
+    """Project-first runs over whole source tables; with src_gid or a fixed per-type map in front it would
+    project the wrong rows, so an explicit request is an error (the automatic choice never makes it)."""
+    from tests.test_oracle_pins import tiny_problem
+    p = tiny_problem(0, "mean", relu=False, with_gid=True)
+    with pytest.raises(heta.HetaError, match="whole-table"):
+        make_layer(p, project_first=[0])
+    with pytest.raises(heta.HetaError, match="whole-table"):
+        make_layer(workloads.config1(), project_first=[0])
 
 
 def test_layer_with_relu_and_gid():

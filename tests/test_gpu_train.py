@@ -125,3 +125,44 @@ def test_device_training_steps_match_the_composed_oracles():
         for b in trainer.last_blocks:
             b.graph.destroy()
     hg.destroy()
+
+
+def test_training_step_on_a_caller_stream_matches_the_default_stream_bit_for_bit():
+    """Two trainers on identical state run three iterations each, one on torch's default stream and one
+    on a stream of the caller (made current for the duration of step()): the embeddings, every weight
+    and every table must agree bit for bit."""
+    wl = "tests/train-stream"
+    base = workloads.academic_graph(scale=0.01, workload=wl)
+    d_hidden, fanouts = 64, [6, 4]
+    tables = workloads._tables(base, wl, "f32", False)
+    W = [workloads._weights(base, (lambda i, l=l: base.ntypes[base.relations[i].src_type].feat_dim if l == 0 else d_hidden),
+                            d_hidden, f"{wl}/L{l}", "f32", False) for l in range(2)]
+    hg = heta.heta_graph_create([(t.num_nodes, t.feat_dim, int(t.learnable)) for t in base.ntypes],
+                                [(r.src_type, r.dst_type, r.rowptr, r.col) for r in base.relations])
+    g = rng.stream("tests", "train-stream/seeds")
+    batches = [(np.sort(g.choice(base.ntypes[0].num_nodes, 128, replace=False)).astype(np.int64),
+                g.standard_normal((128, d_hidden)).astype(np.float32)) for _ in range(3)]
+    results = []
+    side = torch.cuda.Stream()
+    for stream in (None, side):
+        tab_dev = [dev_table(x, "f32", 4) for x in tables]
+        W_dev = [[dev_table(w, "f32", 4) for w in ws] for ws in W]
+        trainer = heta.MiniBatchTrainer(hg, tab_dev, W_dev, fanouts, d_hidden, heta.HETA_MEAN, 0, lr=1e-2, seed=5)
+        torch.cuda.synchronize()   # uploads (default stream) are done before the side stream starts
+        Hs = []
+        for seeds, Y in batches:
+            sd, Yd = torch.from_numpy(seeds).cuda(), torch.from_numpy(Y).cuda()
+            torch.cuda.synchronize()
+            H = trainer.step(sd, lambda h: h - Yd, stream=stream)
+            torch.cuda.synchronize()
+            Hs.append(H.clone())
+        results.append((Hs, tab_dev, W_dev))
+    (H0, T0, W0), (H1, T1, W1) = results
+    for a, b in zip(H0, H1):
+        assert torch.equal(a, b)
+    for a, b in zip(T0, T1):
+        assert torch.equal(a, b)
+    for wa, wb in zip(W0, W1):
+        for a, b in zip(wa, wb):
+            assert torch.equal(a, b)
+    hg.destroy()
