@@ -26,52 +26,202 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"gemm_f32": 157.3, "gemm_wgrad_f32": 157.3, "gemm_bf16": 2500.0, "gemm_wgrad_bf16": 2500.0}
+# flop per byte above which a contraction is bound by the matrix pipe rather than by HBM
+RIDGE = {k: v * 1e12 / (PEAK_HBM_GBS * 1e9) for k, v in PEAK_TFLOPS.items()}
 
 
-def cpu_baseline(problem, budget_s: float = 12.0, rel_names=("cites", "writes", "rev_writes", "has_topic")):
-    """Times the oracle, as it stands, on whole relations of the same workload (forward aggregation
-    and projection, the two backward products and the backward scatter), single-threaded, adding
-    relations until about `budget_s` seconds of CPU work have been spent."""
+def kernel_table(stats, steps: int):
+    """Per kernel name: launches and time per step, algorithmic bytes and flops per launch, rates."""
+    kernels = {}
+    for name, s in stats.items():
+        k = {"launches_per_step": s["launches"] / steps, "ms_per_step": s["total_ms"] / steps,
+             "avg_launch_ms": s["total_ms"] / s["launches"],
+             "algorithmic_MB_per_launch": s["algorithmic_bytes"] / s["launches"] / 1e6,
+             "GBps": s["algorithmic_bytes"] / s["total_ms"] / 1e6}
+        if s["flops"] > 0:
+            k["TFLOPs"] = s["flops"] / s["total_ms"] / 1e9
+            k["flop_per_byte"] = s["flops"] / max(s["algorithmic_bytes"], 1.0)
+        kernels[name] = k
+    return kernels
+
+
+def load_traffic(workload: str, storage: str, scale: float):
+    """HBM bytes per launch and MFMA busy per kernel family from the rocprofv3 counter runs of this same
+    command (profiles/traffic_<workload>_<storage>.json, written by rocprof_summary.py), or {}."""
+    tf = os.path.join(ROOT, "profiles", f"traffic_{workload}_{storage}.json")
+    if scale != 1.0 or not os.path.exists(tf):
+        return {}, None
+    with open(tf) as f:
+        return json.load(f), os.path.relpath(tf, ROOT)
+
+
+def roofline_of(kernels, traffic, traffic_source):
+    """The roofline record of the kernel with the largest share of the step.  The bound follows from the
+    kernel's arithmetic intensity (algorithmic flop per algorithmic byte) against the ridge point of its
+    MFMA type: at or above the ridge the matrix pipe bounds it, below it HBM does."""
+    if not kernels:
+        return None
+    dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+    k = kernels[dom]
+    intensity = k.get("flop_per_byte", 0.0)
+    if dom in PEAK_TFLOPS and intensity >= RIDGE[dom]:
+        r = {"kernel": dom, "bound": "mfma", "achieved": k["TFLOPs"], "peak": PEAK_TFLOPS[dom], "unit": "TFLOP/s",
+             "frac": k["TFLOPs"] / PEAK_TFLOPS[dom]}
+    else:
+        r = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": k["GBps"] / PEAK_HBM_GBS}
+    if dom in PEAK_TFLOPS:
+        r["flop_per_byte"] = intensity
+        r["ridge_flop_per_byte"] = RIDGE[dom]
+        r["TFLOPs"] = k.get("TFLOPs")
+        r["algorithmic_GBps"] = k["GBps"]
+    r["traffic"] = None
+    rec = traffic.get(dom) if traffic else None
+    if rec and "hbm_bytes_per_launch" in rec:
+        r["traffic"] = rec["hbm_bytes_per_launch"]
+        r["traffic_source"] = traffic_source
+        r["traffic_note"] = ("FETCH_SIZE x 2 + WRITE_SIZE (calibrated by a 1 GiB copy), counted between L2 and the fabric: "
+                             "reads served by the 256 MB Infinity Cache are included")
+        # > 1: sector waste or operand re-reads; < 1: rows re-read from L2 (the algorithmic count charges one row per edge)
+        r["moved_over_algorithmic"] = rec["hbm_bytes_per_launch"] / (k["algorithmic_MB_per_launch"] * 1e6)
+    if rec and "mfma_busy" in rec:
+        r["mfma_busy"] = rec["mfma_busy"]
+    r["avg_launch_ms"] = k["avg_launch_ms"]
+    r["timing"] = "HIP events on the launch stream around every launch, over the same K steps"
+    return r
+
+
+def aggregation_summary(kernels, traffic, bytes_by_input_width=None):
+    """All aggregation kernels of a step together (the HBM-bound part).  Three byte counts, none replacing
+    another: `as_run` = algorithmic bytes of the launches as issued (a relation projected first is gathered
+    at the output width); `by_input_width` = the same formula at every relation's input width d_r, whatever
+    order ran (E d_r b + 4 E + 8 (rows + 1) + rows d_r b, forward and backward); `counter` = bytes the
+    hardware counters saw.  `frac` is the by_input_width rate when known, else the as-run rate."""
+    agg = {n: v for n, v in kernels.items() if n.startswith("agg_")}
+    ms = sum(v["ms_per_step"] for v in agg.values())
+    if not agg or ms <= 0:
+        return None
+    as_run_mb = sum(v["GBps"] * v["ms_per_step"] for v in agg.values())  # GB/s * ms = MB
+    out = {"bound": "hbm", "ms_per_step": ms, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+           "as_run": {"MB_per_step": as_run_mb, "GBps": as_run_mb / ms, "over_hbm_peak": as_run_mb / ms / PEAK_HBM_GBS}}
+    if bytes_by_input_width is not None:
+        mb = bytes_by_input_width / 1e6
+        out["by_input_width"] = {"MB_per_step": mb, "GBps": mb / ms, "over_hbm_peak": mb / ms / PEAK_HBM_GBS}
+    if traffic and all(n in traffic and "hbm_bytes_per_launch" in traffic[n] for n in agg):
+        mb = sum(traffic[n]["hbm_bytes_per_launch"] * v["launches_per_step"] for n, v in agg.items()) / 1e6
+        out["counter"] = {"MB_per_step": mb, "GBps": mb / ms, "over_hbm_peak": mb / ms / PEAK_HBM_GBS,
+                          "note": "bytes between L2 and the fabric (Infinity Cache hits included)"}
+    best = out.get("by_input_width", out["as_run"])
+    out["achieved"], out["frac"] = best["GBps"], best["over_hbm_peak"]
+    out["frac_basis"] = "by_input_width" if "by_input_width" in out else "as_run"
+    return out
+
+
+# ---- the oracle on the host cores ---------------------------------------------------------------------
+def _oracle_relation(oracle, np, src, dst, n_s, n_t, table, W, G, op, threads: int):
+    """Forward aggregation + projection, the two backward products and the backward scatter of one relation
+    through the unchanged oracle.  threads > 1: the edge loops run on disjoint destination ranges of the
+    destination-ordered edge list (destination rows are independent; the backward scatters into one private
+    buffer per thread, added up afterwards), the matrix products use the BLAS library's own threads."""
+    if threads <= 1:
+        M = oracle.aggregate_fwd(src, dst, n_t, table, op)
+        oracle.project(M, W)
+        dM, _ = oracle.project_bwd(M, G, W)
+        return M, oracle.aggregate_bwd(src, dst, n_s, n_t, dM, op)
+    from concurrent.futures import ThreadPoolExecutor
+    rowptr = np.searchsorted(dst, np.arange(n_t + 1))            # dst is ascending in a CSR-ordered edge list
+    cuts = [int(np.searchsorted(rowptr, (len(dst) * i) // threads)) for i in range(threads + 1)]
+    cuts[0], cuts[-1] = 0, n_t
+    cuts = sorted(set(min(max(c, 0), n_t) for c in cuts))
+    spans = [(a, b) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+    M = np.empty((n_t, table.shape[1]), dtype=np.float64)
+
+    def fwd(span):
+        a, b = span
+        e0, e1 = int(rowptr[a]), int(rowptr[b])
+        M[a:b] = oracle.aggregate_fwd(src[e0:e1], dst[e0:e1] - a, b - a, table, op)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(fwd, spans))
+        oracle.project(M, W)
+        dM, _ = oracle.project_bwd(M, G, W)
+
+        def bwd(span):
+            a, b = span
+            e0, e1 = int(rowptr[a]), int(rowptr[b])
+            return oracle.aggregate_bwd(src[e0:e1], dst[e0:e1] - a, n_s, b - a, dM[a:b], op)
+
+        parts = list(ex.map(bwd, spans))
+    out = parts[0]
+    for q in parts[1:]:
+        out += q
+    return M, out
+
+
+def cpu_baseline(relations, op: str, budget_s: float, threads: int):
+    """Times the oracle, as it stands, on whole relations of a workload until about `budget_s` seconds are
+    spent.  relations: [(name, src, dst, n_src, n_dst, table float32 [n_src, d], W [d, d_out])]."""
     import numpy as np
     import oracle
     try:
         from threadpoolctl import threadpool_limits
     except ImportError:  # pragma: no cover
         threadpool_limits = None
-    g = problem.graph
     total_s, edge_features, used = 0.0, 0, []
-    with (threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()):
-        for name in rel_names:
-            i = g.rel_index(name)
-            r = g.relations[i]
-            src, dst = r.edge_list()
-            n_s, n_t = g.ntypes[r.src_type].num_nodes, g.ntypes[r.dst_type].num_nodes
-            G = np.random.default_rng(0).standard_normal((n_t, problem.d_out)).astype(np.float32)
+    with (threadpool_limits(limits=threads) if threadpool_limits else contextlib.nullcontext()):
+        for name, src, dst, n_s, n_t, table, W in relations:
+            G = np.random.default_rng(0).standard_normal((n_t, W.shape[1])).astype(np.float32)
             t0 = time.perf_counter()
-            M = oracle.aggregate_fwd(src, dst, n_t, problem.tables[r.src_type], problem.op)
-            Z = oracle.project(M, problem.W[i])
-            dM, dW = oracle.project_bwd(M, G, problem.W[i])
-            oracle.aggregate_bwd(src, dst, n_s, n_t, dM, problem.op)
+            _oracle_relation(oracle, np, src, dst, n_s, n_t, table, W, G, op, threads)
             total_s += time.perf_counter() - t0
-            del M, Z, dM, dW, G
-            edge_features += r.num_edges * problem.W[i].shape[0]
+            edge_features += len(src) * W.shape[0]
             used.append(name)
             if total_s >= budget_s:
                 break
-    return {"value": 2.0 * edge_features / total_s, "unit": "edge-features/s", "cores": 1, "kind": "oracle",
-            "sample": f"relations {used} of the same fp32 graph, forward + backward of each "
-                      f"({edge_features} edge-features per pass, {total_s:.1f} s of oracle time)",
-            "host_cores_visible": os.cpu_count()}
+    return {"value": 2.0 * edge_features / max(total_s, 1e-9), "unit": "edge-features/s", "cores": threads, "kind": "oracle",
+            "sample": f"relations {used}, forward + backward of each ({edge_features} edge-features per pass, "
+                      f"{total_s:.1f} s of oracle time)"}
 
 
-def measure(storage: str, args, keep_problem: bool = False):
+def cpu_baseline_both(relations, op: str, budget_s: float = 6.0):
+    """The oracle with one thread and with all cores of this process (nproc printed): `value` is the
+    all-cores figure."""
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
+    one = cpu_baseline(relations, op, budget_s, 1)
+    allc = cpu_baseline(relations, op, budget_s, cores) if cores > 1 else one
+    out = dict(allc)
+    out["single_thread"] = {k: one[k] for k in ("value", "unit", "cores", "sample")}
+    out["nproc"] = os.cpu_count()
+    out["threads_note"] = ("all-cores leg: Python threads over disjoint destination ranges calling the unchanged C edge loops "
+                           "(ctypes releases the interpreter lock), BLAS threads for the fp64 matrix products")
+    return out
+
+
+def layer_problem_relations(problem, names=None, max_rels=None):
+    """cpu_baseline's relation tuples for a gen.workloads.LayerProblem (whole-table sources)."""
+    g = problem.graph
+    idx = [g.rel_index(n) for n in names] if names else list(range(len(g.relations)))
+    out = []
+    for i in idx[:max_rels]:
+        r = g.relations[i]
+        src, dst = r.edge_list()
+        gid = None if problem.src_gid is None else problem.src_gid[r.src_type]
+        table = problem.tables[r.src_type]
+        if gid is not None:
+            table = table[gid] if table.shape[0] != gid.size else table
+        out.append((r.name, src, dst, g.ntypes[r.src_type].num_nodes, g.ntypes[r.dst_type].num_nodes, table, problem.W[i]))
+    return out
+
+
+def measure(storage: str, workload: str, args, keep_problem: bool = False):
     import torch
     import paper_2408_09697_amd as heta
     from gen import workloads
     from paper_2408_09697_amd.problems import make_graph, make_layer
 
     t0 = time.perf_counter()
-    if args.workload == "config4":   # mixed widths 7..789, 12 relations, 40 M edges, sum, bf16 tables
+    if workload == "config4":   # mixed widths 7..789, 12 relations, 40 M edges, sum, bf16 tables
         p = workloads.config4(scale=args.scale, upstream=False)
     else:
         p = workloads.config3(storage, scale=args.scale, upstream=False)  # the upstream gradient is drawn on the device
@@ -143,44 +293,19 @@ def measure(storage: str, args, keep_problem: bool = False):
         torch.cuda.synchronize()
         stats = heta.heta_profile_read()
         heta.heta_profile_enable(False)
-        for name, s in stats.items():
-            k = {"launches_per_step": s["launches"] / args.steps, "ms_per_step": s["total_ms"] / args.steps,
-                 "avg_launch_ms": s["total_ms"] / s["launches"],
-                 "algorithmic_MB_per_launch": s["algorithmic_bytes"] / s["launches"] / 1e6,
-                 "GBps": s["algorithmic_bytes"] / s["total_ms"] / 1e6}
-            if s["flops"] > 0:
-                k["TFLOPs"] = s["flops"] / s["total_ms"] / 1e9
-            kernels[name] = k
-        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-        k = kernels[dom]
-        if dom in PEAK_TFLOPS and k.get("TFLOPs", 0) / PEAK_TFLOPS[dom] > k["GBps"] / PEAK_HBM_GBS:
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["TFLOPs"], "peak": PEAK_TFLOPS[dom],
-                        "unit": "TFLOP/s", "frac": k["TFLOPs"] / PEAK_TFLOPS[dom]}
-        else:
-            roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": k["GBps"] / PEAK_HBM_GBS}
-        roofline["traffic"] = None
-        tf = os.path.join(ROOT, "profiles", f"traffic_{args.workload}_{storage}.json")
-        if args.scale == 1.0 and os.path.exists(tf):
-            # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command,
-            # scaled by the 1 GiB calibration copy; written by rocprof_summary.py
-            with open(tf) as f:
-                rec = json.load(f).get(dom)
-            if rec:
-                roofline["traffic"] = rec["hbm_bytes_per_launch"]
-                roofline["traffic_source"] = os.path.relpath(tf, ROOT)
-                # > 1: sector waste; < 1: sources re-read from cache (the algorithmic count charges one row per edge)
-                roofline["moved_over_algorithmic"] = rec["hbm_bytes_per_launch"] / (k["algorithmic_MB_per_launch"] * 1e6)
-        roofline["avg_launch_ms"] = k["avg_launch_ms"]
-        roofline["timing"] = "HIP events on the launch stream around every launch, over the same K steps"
-        # all aggregation kernels together: the HBM-bound part of the step
-        agg = [v for n, v in kernels.items() if n.startswith("agg_")]
-        agg_ms = sum(v["ms_per_step"] for v in agg)
-        agg_mb = sum(v["GBps"] * v["ms_per_step"] for v in agg)  # GB/s * ms = MB
-        roofline["aggregation_all_kernels"] = {"bound": "hbm", "ms_per_step": agg_ms,
-                                               "achieved": agg_mb / agg_ms if agg_ms else 0.0, "peak": PEAK_HBM_GBS,
-                                               "unit": "GB/s",
-                                               "frac": (agg_mb / agg_ms / PEAK_HBM_GBS) if agg_ms else 0.0}
+        kernels = kernel_table(stats, args.steps)
+        traffic, traffic_source = load_traffic(workload, storage, args.scale)
+        roofline = roofline_of(kernels, traffic, traffic_source)
+        # the aggregation's bytes at every relation's INPUT width d_r, forward (storage type in and out) and
+        # backward (dM_r in the storage type, fp32 gradient rows out), whichever order the relation ran in
+        esz = 2 if storage == "bf16" else 4
+        by_width = 0.0
+        for r, rel in enumerate(p.graph.relations):
+            n_s, n_t, E = p.graph.ntypes[rel.src_type].num_nodes, p.graph.ntypes[rel.dst_type].num_nodes, rel.num_edges
+            d = p.W[r].shape[0]
+            by_width += E * d * esz + 4 * E + 8 * (n_t + 1) + n_t * d * esz
+            by_width += E * d * esz + 4 * E + 8 * (n_s + 1) + n_s * d * 4
+        roofline["aggregation_all_kernels"] = aggregation_summary(kernels, traffic, by_width)
     # Each relation's aggregation on its own (standalone calls at the relation's input width, storage
     # type in, fp32 gradients in the backward): algorithmic bytes E*d*b_in + 4E + 8(rows+1) + rows*d*b_out.
     per_relation = []
@@ -209,10 +334,10 @@ def measure(storage: str, args, keep_problem: bool = False):
             f_bytes = E * d * esz_t + 4 * E + 8 * (n_t + 1) + n_t * d * esz_t
             b_bytes = E * d * 4 + 4 * E + 8 * (n_s + 1) + n_s * d * 4
             per_relation.append({"relation": rel.name, "edges": E, "d": d,
-                                 "aggregate_fwd_ms": f_ms, "aggregate_fwd_GBps": f_bytes / f_ms / 1e6,
-                                 "aggregate_fwd_frac_of_hbm_peak": f_bytes / f_ms / 1e6 / PEAK_HBM_GBS,
-                                 "aggregate_bwd_ms": b_ms, "aggregate_bwd_GBps": b_bytes / b_ms / 1e6,
-                                 "aggregate_bwd_frac_of_hbm_peak": b_bytes / b_ms / 1e6 / PEAK_HBM_GBS,
+                                 "aggregate_fwd_ms": f_ms, "aggregate_fwd_algorithmic_GBps": f_bytes / f_ms / 1e6,
+                                 "aggregate_fwd_algorithmic_rate_over_hbm_peak": f_bytes / f_ms / 1e6 / PEAK_HBM_GBS,
+                                 "aggregate_bwd_ms": b_ms, "aggregate_bwd_algorithmic_GBps": b_bytes / b_ms / 1e6,
+                                 "aggregate_bwd_algorithmic_rate_over_hbm_peak": b_bytes / b_ms / 1e6 / PEAK_HBM_GBS,
                                  "edge_features_per_s": 2.0 * E * d / ((f_ms + b_ms) * 1e-3)})
             del out, gin, back
     # The update of the learnable tables that follows backpropagation (not part of `value`): one sparse
@@ -237,7 +362,7 @@ def measure(storage: str, args, keep_problem: bool = False):
         esz = 2 if storage == "bf16" else 4
         a_bytes = sum(layer.tables[t].shape[0] * layer.tables[t].shape[1] * (20 + 2 * esz) for t in learn)
         adam = {"ms": a_ms, "rows": int(sum(layer.tables[t].shape[0] for t in learn)), "GBps": a_bytes / a_ms / 1e6,
-                "frac_of_hbm_peak": a_bytes / a_ms / 1e6 / PEAK_HBM_GBS,
+                "frac_of_hbm_peak": a_bytes / a_ms / 1e6 / PEAK_HBM_GBS,  # streaming, every byte once: no reuse to inflate it
                 "note": "heta_sparse_adam on every learnable table (all rows), after the timed steps; not part of value"}
         del states
     res = {"ms_per_step": ms_per_step, "sparse_adam": adam, "fused_inference_forward": fused, "value": 2.0 * edge_features / (ms_per_step * 1e-3),
@@ -304,22 +429,13 @@ def measure_rgat(storage: str, args, heads: int = 4):
         torch.cuda.synchronize()
         stats = heta.heta_profile_read()
         heta.heta_profile_enable(False)
-        for name, st in stats.items():
-            k = {"launches_per_step": st["launches"] / args.steps, "ms_per_step": st["total_ms"] / args.steps,
-                 "GBps": st["algorithmic_bytes"] / st["total_ms"] / 1e6}
-            if st["flops"] > 0:
-                k["TFLOPs"] = st["flops"] / st["total_ms"] / 1e9
-            kernels[name] = k
-    agg = [v for n, v in kernels.items() if n.startswith("agg_")]
-    agg_ms = sum(v["ms_per_step"] for v in agg)
-    agg_mb = sum(v["GBps"] * v["ms_per_step"] for v in agg)
+        kernels = kernel_table(stats, args.steps)
     res = {"model": f"R-GAT layer on the config-3 graph, {heads} heads, 128->256, {storage} tables",
            "ms_per_step": ms_per_step, "fwd_ms": ev[0].elapsed_time(ev[1]), "bwd_ms": ev[1].elapsed_time(ev[2]),
            "value": 2.0 * edge_features / (ms_per_step * 1e-3), "unit": "edge-features/s at the output width (fwd+bwd)",
            "edges": n_edges,
-           "aggregation_all_kernels": {"bound": "hbm", "ms_per_step": agg_ms, "achieved": agg_mb / agg_ms if agg_ms else 0.0,
-                                       "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                       "frac": (agg_mb / agg_ms / PEAK_HBM_GBS) if agg_ms else 0.0},
+           "aggregation_all_kernels": aggregation_summary(kernels, None),
+           "roofline": roofline_of(kernels, None, None),
            "kernels": kernels}
     graph.destroy()
     del layer, G
@@ -420,13 +536,19 @@ def measure_minibatch(args, which: str = "config5"):
     torch.cuda.synchronize()
     stats = heta.heta_profile_read()
     heta.heta_profile_enable(False)
-    kernels = {n: {"launches_per_step": s["launches"] / args.steps, "ms_per_step": s["total_ms"] / args.steps,
-                   "GBps": s["algorithmic_bytes"] / s["total_ms"] / 1e6,
-                   **({"TFLOPs": s["flops"] / s["total_ms"] / 1e9} if s["flops"] > 0 else {})} for n, s in stats.items()}
+    kernels = kernel_table(stats, args.steps)
+    traffic, traffic_source = load_traffic(which, storage, args.scale)
+    roofline = roofline_of(kernels, traffic, traffic_source)
+    if roofline is not None:
+        roofline["aggregation_all_kernels"] = aggregation_summary(kernels, traffic)
+        n_launch = sum(k["launches_per_step"] for k in kernels.values())
+        roofline["regime"] = (f"launch-bound: {n_edges} sampled edges per mini-batch over {n_launch:.0f} kernel launches of "
+                              f"{1e3 * sum(k['ms_per_step'] for k in kernels.values()) / max(n_launch, 1):.1f} us on average; "
+                              "no kernel of a block this small can approach a bandwidth or MFMA roofline")
     # The step before the path: sampling the mini-batch's blocks on the device from the resident base graph
     # (heta_sample_neighbors per relation and hop, heta_unique_relabel per source type, block handles from
     # the device arrays).  Not part of `value`, whose blocks come from the host generator.
-    sampler = None
+    sampler, large_block = None, None
     if not args.no_device_sampler:
         for g in graphs:
             g.destroy()
@@ -477,7 +599,16 @@ def measure_minibatch(args, which: str = "config5"):
         except heta.HetaError as err:
             sampler["train_step_ms"] = None
             sampler["train_step_note"] = f"failed: {err.message}"
+        if which == "config5" and not args.no_large_block:
+            large_block = large_block_sweep(base, mb, tables, W, fanouts, args)
         base.destroy()
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle on the outer block (layer 1) of this same mini-batch: compact host tables of the sampled rows
+        lp = mb.layer_problem(0, None)
+        rels = [(r.name, *r.edge_list(), lp.graph.ntypes[r.src_type].num_nodes, lp.graph.ntypes[r.dst_type].num_nodes,
+                 lp.tables[r.src_type], lp.W[i]) for i, r in enumerate(lp.graph.relations) if r.num_edges > 0]
+        cpu = cpu_baseline_both(rels, mb.op, budget_s=4.0)
     ms = compute_ms + ingest_ms
     return {"metric": "aggregated edge-features/sec (fwd+bwd), 1 GPU", "value": 2.0 * edge_features / (ms * 1e-3),
             "unit": "edge-features/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
@@ -492,8 +623,76 @@ def measure_minibatch(args, which: str = "config5"):
                        "edges": n_edges, "edge_features_per_pass": edge_features,
                        "block_sizes": [[(t.name, t.num_nodes) for t in b.graph.ntypes] for b in mb.blocks]},
             "compute_ms": compute_ms, "ingest_ms_per_batch": ingest_ms, "ingest_ms_mean": ingest_mean_ms,
-            "ingest_ms_max": ingest_max_ms, "input_generation_s": gen_s, "kernels": kernels,
-            "device_sampler": sampler}
+            "ingest_ms_max": ingest_max_ms, "input_generation_s": gen_s, "roofline": roofline, "kernels": kernels,
+            "device_sampler": sampler, "large_block": large_block, "cpu_baseline": cpu}
+
+
+def large_block_sweep(base, mb, tables, W, fanouts, args):
+    """The aggregation kernels of config 5 on outer blocks of growing size.  With the degree law of the
+    generator a 4,096-seed mini-batch samples only ~4e4 edges, far below the 1-6 M edges at which a block is
+    bandwidth-bound; so the same layer-1 calls (tables read through the block's row map, 768 bf16 columns,
+    mean, forward and CSC backward) are timed on blocks sampled by the device sampler from more seeds of the
+    same partition, up to a few million sampled edges."""
+    import numpy as np
+    import torch
+    import paper_2408_09697_amd as heta
+    from gen import rng
+    T = len(mb.base.ntypes)
+    n_paper = mb.base.ntypes[mb.seed_type].num_nodes
+    rows = []
+    for n_seeds in (4096, 65536, 524288, 2097152):
+        n_seeds = min(n_seeds, n_paper // 2)
+        seeds = torch.from_numpy(np.sort(rng.stream("bench", f"large-block/{n_seeds}").choice(
+            n_paper, size=n_seeds, replace=False)).astype(np.int64)).cuda()
+        blocks = heta.sampler.sample_blocks(base, mb.seed_type, seeds, fanouts, 20240809)
+        b = blocks[0]
+        g = b.graph
+        rels = [i for i in range(len(g.rels)) if g.n_dst(i) > 0 and g.rels[i][2] > 0]
+        n_edges = sum(g.rels[i][2] for i in rels)
+        d = mb.base.ntypes[0].feat_dim
+        esz = tables[0].element_size()
+        outs = {i: torch.empty((g.n_dst(i), d), dtype=tables[0].dtype, device="cuda") for i in rels}
+        gins = {i: torch.zeros((g.n_dst(i), d), dtype=tables[0].dtype, device="cuda") for i in rels}
+        backs = {i: torch.empty((g.n_src(i), d), dtype=torch.float32, device="cuda") for i in rels}
+
+        def run():
+            for i in rels:
+                s_t = g.rels[i][0]
+                heta.heta_rel_aggregate_fwd(g, i, heta.HETA_MEAN, tables[s_t], outs[i], src_gid=b.src_ids[s_t])
+                heta.heta_rel_aggregate_bwd(g, i, heta.HETA_MEAN, gins[i], backs[i])
+
+        run()
+        torch.cuda.synchronize()
+        heta.heta_profile_enable(True)
+        heta.heta_profile_reset()
+        reps = max(3, args.steps // 2)
+        for _ in range(reps):
+            run()
+        torch.cuda.synchronize()
+        kern = kernel_table(heta.heta_profile_read(), reps)
+        heta.heta_profile_enable(False)
+        by_width = 0.0
+        for i in rels:
+            E, n_s, n_t = g.rels[i][2], g.n_src(i), g.n_dst(i)
+            by_width += E * d * esz + 4 * E + 8 * (n_t + 1) + n_t * d * esz + 8 * E   # forward, incl. the 8-byte row map entry per edge
+            by_width += E * d * esz + 4 * E + 8 * (n_s + 1) + n_s * d * 4            # backward
+        summ = aggregation_summary(kern, None, by_width)
+        rows.append({"seeds": int(n_seeds), "sampled_edges_outer_block": int(n_edges),
+                     "sampled_edges_seed_block": int(sum(r[2] for r in blocks[1].graph.rels)),
+                     "source_rows": int(sum(int(x.numel()) for x in b.src_ids)),
+                     "aggregation_ms": summ["ms_per_step"] if summ else None,
+                     "algorithmic_GBps": summ["achieved"] if summ else None,
+                     "algorithmic_rate_over_hbm_peak": summ["frac"] if summ else None,
+                     "edge_features_per_s": 2.0 * n_edges * d / (summ["ms_per_step"] * 1e-3) if summ else None})
+        for blk in blocks:
+            blk.graph.destroy()
+        del outs, gins, backs
+        torch.cuda.empty_cache()
+        if n_seeds >= n_paper // 2:
+            break
+    return {"what": "forward + backward aggregation of the outer block (layer 1 of config 5) per seed count; device-sampled blocks, "
+                    "fan-outs [25, 15], tables through the block's row map",
+            "rows": rows}
 
 
 def main() -> int:
@@ -516,6 +715,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel HIP-event pass")
     ap.add_argument("--no-device-sampler", action="store_true", help="config5: skip the device-sampler measurement")
+    ap.add_argument("--no-large-block", action="store_true", help="config5: skip the sweep over larger sampled blocks")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one GPU's share of the layer); "
@@ -547,64 +747,90 @@ def main() -> int:
     if args.workload in ("config2", "config5"):
         print(json.dumps(measure_minibatch(args, args.workload)))
         return 0
-    if args.workload == "config4":
-        args.dtype, args.single, args.no_cpu_baseline = "bf16", True, True
     want_cpu = not args.no_cpu_baseline
-    main_res, problem = measure(args.dtype, args, keep_problem=want_cpu and args.dtype == "f32")
     scale_note = "" if args.scale == 1.0 else f" (scale {args.scale})"
-    out = {
-        "metric": "aggregated edge-features/sec (fwd+bwd), 1 GPU",
-        "value": main_res["value"],
-        "unit": "edge-features/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if args.dtype == "f32" else "bf16 storage, f32 accumulate",
-        "data": "synthetic",
-        "config": {"workload": (f"config 3: full-graph single layer, academic-shaped graph, {main_res['edges']} edges, "
-                                f"7 relations, 128->256, mean, {args.dtype} tables{scale_note}") if args.workload == "config3"
-                   else (f"config 4: full-graph single layer, 7 node types of widths 7..789, {main_res['edges']} edges, "
-                         f"12 relations, d_src->256, sum, bf16 tables{scale_note}"),
-                   "edges": main_res["edges"], "edge_features_per_pass": main_res["edge_features_per_pass"],
-                   "relation_order": {"rule": args.project_first, "projected_first": main_res["projected_first"],
-                                      "note": "aggregation and projection commute (linearity of Eq. 1); per relation the "
-                                              "cheaper order is used, same result"}},
-        "edges_per_s": main_res["edges_per_s"],
-        "fwd_ms": main_res["fwd_ms"], "bwd_ms": main_res["bwd_ms"],
-        "step_time": main_res["step_time"],
-        "per_relation_aggregation": main_res["per_relation_aggregation"],
-        "per_relation_aggregation_note": "standalone heta_rel_aggregate_fwd / _bwd per relation; GB/s and fractions use the "
-                                         "algorithmic byte count, which charges one source row per edge: a fraction above 1 "
-                                         "means rows re-read from cache, not more than 8 TB/s from HBM",
-        "ingest": {"ms": main_res["ingest_ms"],
-                   "note": "heta_graph_create for every relation (host validation of the caller's arrays, upload, then "
-                           "device kernels: radix-sort transpose, scans, degree-sorted schedules); once per graph, "
-                           "outside the timed steps"},
-        "input_generation_s": main_res["input_generation_s"],
-        "roofline": main_res["roofline"],
-        "kernels": main_res["kernels"],
-        "sparse_adam": main_res["sparse_adam"],
-        "fused_inference_forward": main_res["fused_inference_forward"],
-    }
+
+    def full_graph_record(workload: str, dtype: str):
+        """One full-graph layer workload as a record of the bench line's shape (+ its oracle baseline)."""
+        res, problem = measure(dtype, workload, args, keep_problem=want_cpu)
+        rec = {
+            "metric": "aggregated edge-features/sec (fwd+bwd), 1 GPU",
+            "value": res["value"],
+            "unit": "edge-features/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32" if dtype == "f32" else "bf16 storage, f32 accumulate",
+            "data": "synthetic",
+            "config": {"workload": (f"config 3: full-graph single layer, academic-shaped graph, {res['edges']} edges, "
+                                    f"7 relations, 128->256, mean, {dtype} tables{scale_note}") if workload == "config3"
+                       else (f"config 4: full-graph single layer, 7 node types of widths 7..789, {res['edges']} edges, "
+                             f"12 relations, d_src->256, sum, bf16 tables{scale_note}"),
+                       "edges": res["edges"], "edge_features_per_pass": res["edge_features_per_pass"],
+                       "relation_order": {"rule": args.project_first, "projected_first": res["projected_first"],
+                                          "note": "aggregation and projection commute (linearity of Eq. 1); per relation the "
+                                                  "cheaper order is used, same result"}},
+            "edges_per_s": res["edges_per_s"],
+            "fwd_ms": res["fwd_ms"], "bwd_ms": res["bwd_ms"],
+            "step_time": res["step_time"],
+            "per_relation_aggregation": res["per_relation_aggregation"],
+            "per_relation_aggregation_note": "standalone heta_rel_aggregate_fwd / _bwd per relation; the algorithmic byte count "
+                                             "charges one source row per edge, so its rate is NOT HBM traffic: above 1.0 of the "
+                                             "HBM peak means rows served again from L2 / Infinity Cache",
+            "ingest": {"ms": res["ingest_ms"],
+                       "note": "heta_graph_create for every relation (host validation of the caller's arrays, upload, then "
+                               "device kernels: radix-sort transpose, scans, degree-sorted schedules); once per graph, "
+                               "outside the timed steps"},
+            "input_generation_s": res["input_generation_s"],
+            "roofline": res["roofline"],
+            "kernels": res["kernels"],
+            "sparse_adam": res["sparse_adam"],
+            "fused_inference_forward": res["fused_inference_forward"],
+        }
+        return rec, res, problem
+
+    def oracle_leg(problem, workload: str):
+        names = ("cites", "writes", "rev_writes", "has_topic") if workload == "config3" else None
+        return cpu_baseline_both(layer_problem_relations(problem, names), problem.op, budget_s=6.0 if workload == "config3" else 4.0)
+
+    if args.workload == "config4":
+        out, _, problem = full_graph_record("config4", "bf16")
+        if want_cpu:
+            out["cpu_baseline"] = oracle_leg(problem, "config4")
+        print(json.dumps(out))
+        return 0
+
+    out, _, problem = full_graph_record("config3", args.dtype)
     if not args.single:
         other = "bf16" if args.dtype == "f32" else "f32"
-        res, p2 = measure(other, args, keep_problem=want_cpu and other == "f32")
-        problem = problem or p2
+        res, p2 = measure(other, "config3", args, keep_problem=want_cpu and problem is None)
         out["bf16_storage" if other == "bf16" else "f32_storage"] = {
             k: res[k] for k in ("value", "ms_per_step", "edges_per_s", "fwd_ms", "bwd_ms", "roofline", "kernels", "sparse_adam",
                                 "fused_inference_forward", "projected_first", "step_time", "per_relation_aggregation")}
-    if not args.single and args.workload == "config3":
         # the paper's second model on the same graph: R-GAT layer, forward + backward (not part of `value`)
         out["rgat"] = {}
         for st_ in ("f32", "bf16"):
             r = measure_rgat(st_, args)
             out["rgat"][st_] = {k: r[k] for k in ("model", "ms_per_step", "fwd_ms", "bwd_ms", "value", "unit",
-                                                   "aggregation_all_kernels")}
-    if not args.single and args.workload == "config3":
+                                                   "aggregation_all_kernels", "roofline")}
         # the sampled 2-layer mini-batch on the same graph (1,024 seeds, fan-outs [25, 20], fp32): launch-bound
         # blocks of ~10^4-10^5 edges; with the device sampler and the whole device training iteration
         mbr = measure_minibatch(args, "config2")
         out["minibatch_config2"] = {k: mbr[k] for k in ("value", "unit", "ms_per_step", "compute_ms", "ingest_ms_per_batch",
-                                                        "dtype", "config", "device_sampler")}
+                                                        "dtype", "config", "roofline", "device_sampler", "cpu_baseline")}
+    if want_cpu:
+        out["cpu_baseline"] = oracle_leg(problem, "config3")
+    del problem
+    if not args.single:
+        # the other two large configurations, each with its own roofline and oracle leg
+        c4, _, p4 = full_graph_record("config4", "bf16")
+        if want_cpu:
+            c4["cpu_baseline"] = oracle_leg(p4, "config4")
+        del p4
+        out["config4"] = {k: c4[k] for k in ("value", "unit", "ms_per_step", "dtype", "config", "edges_per_s", "fwd_ms", "bwd_ms",
+                                             "step_time", "ingest", "roofline", "kernels", "cpu_baseline") if k in c4}
+        c5 = measure_minibatch(args, "config5")
+        out["config5"] = {k: c5[k] for k in ("value", "unit", "ms_per_step", "compute_ms", "ingest_ms_per_batch", "dtype", "config",
+                                             "roofline", "kernels", "device_sampler", "large_block", "cpu_baseline")}
     # The paper reports no per-layer or per-kernel figure; its end-to-end results are quoted as context only
     # (evaluation section: 2 machines x 8 NVIDIA T4 16 GB, 2-layer models, hidden 64, batch 1,024, fan-out {25, 20}).
     out["paper_context"] = {
@@ -614,11 +840,6 @@ def main() -> int:
         "average_speedup_per_model": {"R-GCN": 2.8, "R-GAT": 2.6, "HGT": 2.4},
         "learnable_feature_update_share_of_a_DGL_epoch": "24%-35%",
         "note": "end-to-end distributed training on other hardware: context, not a target for this one-GPU kernel metric"}
-    if want_cpu:
-        if problem is None:
-            from gen import workloads
-            problem = workloads.config3("f32", scale=args.scale, upstream=False)
-        out["cpu_baseline"] = cpu_baseline(problem)
     print(json.dumps(out))
     return 0
 
