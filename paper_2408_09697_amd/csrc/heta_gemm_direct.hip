@@ -12,8 +12,13 @@
 //       k-contiguous operand (element (r,k) at base[r*ld + k]): LDS row r holds the tile's k
 //         range of row r, its 16-byte chunks permuted by an XOR with a function of r so that the
 //         128-bit fragment reads of neighbouring rows fall on distinct banks (no padding);
-//       r-contiguous fp32 operand (element (r,k) at base[k*ld + r]): LDS row k, as in memory;
-//         fragments are 32-bit reads with lanes along r.
+//       r-contiguous operand (element (r,k) at base[k*ld + r]): LDS row k, as in memory; fp32 compute
+//         reads fragments with 32-bit loads, lanes along r; under bf16 compute (the weight gradient,
+//         whose two operands both lie with the contraction index outermost) a lane gathers its eight
+//         consecutive k-values with eight 16-bit loads (bf16 storage) or eight 32-bit loads and
+//         packed converts (fp32 storage).  That costs four times the LDS instructions of a
+//         k-contiguous fragment, which a product bound by HBM (two short operand rows per graph row
+//         against 2*d_in*d_out flops) can afford; in exchange no operand passes through registers.
 //     Rows / chunks beyond the matrix are clamped to the last valid one (the duplicated data
 //     only reaches outputs that are never stored); a ragged last k-tile is masked in registers.
 //   - an operand that must be converted (fp32 -> bf16) or pair-interleaved (r-contiguous bf16)
@@ -87,10 +92,12 @@ struct DirectLoader {
     static constexpr int CPR = RC ? ROWS / E : BK / E;   // chunks per LDS row
     static constexpr int NROW = RC ? BK : ROWS;          // LDS rows per tile
     static constexpr int CHUNKS = NROW * CPR;
-    static constexpr int NI = CHUNKS / (64 * NW);        // load instructions per wavefront and tile
+    // load instructions per wavefront and tile.  Every wavefront issues the same number (the kernel counts
+    // outstanding loads per wavefront); when the tile is not a whole number of workgroup-wide loads the
+    // surplus slots wrap around and fetch chunks a second time into the same LDS place (same bytes).
+    static constexpr int NI = (CHUNKS + 64 * NW - 1) / (64 * NW);
     static constexpr int STAGE_ELEMS = CHUNKS * E;
-    static_assert(CHUNKS % (64 * NW) == 0, "tile must be a whole number of wavefront loads");
-    static_assert(!RC || sizeof(T) == 4, "r-contiguous direct loads are fp32 only");
+    static_assert(CHUNKS % 64 == 0, "tile must be a whole number of wavefront loads");
 
     const char *tile;     // uniform: address of element (r0, k of the next tile)
     uint32_t off[NI];     // per lane: byte offset of its chunk from `tile`
@@ -98,10 +105,12 @@ struct DirectLoader {
     int64_t step;         // uniform: bytes from one k-tile to the next
     int r_room;           // KC: valid rows from r0 on, minus 1 ; RC: valid chunks along r from r0 on, minus 1
 
-    __device__ __forceinline__ static int row_of(int i, int wave, int lane) { return ((i * NW + wave) * 64 + lane) / CPR; }
+    // the 64-chunk slot that instruction i of this wavefront fills
+    __device__ __forceinline__ static int slot_of(int i, int wave) { return (i * NW + wave) % (CHUNKS / 64); }
+    __device__ __forceinline__ static int row_of(int i, int wave, int lane) { return (slot_of(i, wave) * 64 + lane) / CPR; }
     __device__ __forceinline__ static int pos_of(int i, int wave, int lane)
     {
-        const int q = (i * NW + wave) * 64 + lane;
+        const int q = slot_of(i, wave) * 64 + lane;
         return RC ? q % CPR : (q % CPR) ^ swz<CPR>(q / CPR);
     }
 
@@ -125,7 +134,7 @@ struct DirectLoader {
     __device__ __forceinline__ void issue(uint32_t lds, int wave)
     {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) load_chunk_to_lds(tile, off[i], lds + (i * NW + wave) * 1024);
+        for (int i = 0; i < NI; ++i) load_chunk_to_lds(tile, off[i], lds + slot_of(i, wave) * 1024);
         tile += step;
     }
 
@@ -142,7 +151,7 @@ struct DirectLoader {
             if (RC) o = static_cast<uint32_t>(min(lr, kv - 1)) * ld_bytes + static_cast<uint32_t>(min(pos, r_room)) * 16u;
             else o = static_cast<uint32_t>(min(lr, r_room)) * ld_bytes +
                      static_cast<uint32_t>(min(static_cast<int64_t>(pos), k_room / E - 1)) * 16u;
-            load_chunk_to_lds(tile, o, lds + (i * NW + wave) * 1024);
+            load_chunk_to_lds(tile, o, lds + slot_of(i, wave) * 1024);
         }
         tile += step;
     }
@@ -200,6 +209,42 @@ template <int BK> __device__ __forceinline__ uint4 dfrag_bf16_from_f32(const flo
     return make_uint4(pack_bf16(lo.x, lo.y), pack_bf16(lo.z, lo.w), pack_bf16(hi.x, hi.y), pack_bf16(hi.z, hi.w));
 }
 
+// bf16 fragment of an r-contiguous bf16 operand lying in LDS as in memory (row k holds ROWS elements):
+// the lane's eight k-values kk + 8*half + 0..7 of its row r, one 16-bit read each
+template <int ROWS> __device__ __forceinline__ uint4 dfrag_bf16_rc(const bf16_t *tile, int r, int kk, int half)
+{
+    const bf16_t *p = tile + (kk + 8 * half) * ROWS + r;
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        w[j] = static_cast<uint32_t>(p[(2 * j) * ROWS]) | (static_cast<uint32_t>(p[(2 * j + 1) * ROWS]) << 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// the same for an r-contiguous fp32 operand: eight 32-bit reads, rounded to bf16 in pairs.  With SPLIT
+// the fragment `lo` receives what the rounding left (x - bf16(x), itself rounded to bf16): fed as a
+// second MFMA term it restores 16 significant bits of the operand.
+template <int ROWS, bool SPLIT>
+__device__ __forceinline__ uint4 dfrag_bf16_rc_from_f32(const float *tile, int r, int kk, int half, uint4 *lo)
+{
+    const float *p = tile + (kk + 8 * half) * ROWS + r;
+    float x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = p[j * ROWS];
+    uint32_t w[4], wl[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        w[j] = pack_bf16(x[2 * j], x[2 * j + 1]);
+        if (SPLIT) {
+            const float ra = x[2 * j] - __uint_as_float(w[j] << 16);
+            const float rb = x[2 * j + 1] - __uint_as_float(w[j] & 0xffff0000u);
+            wl[j] = pack_bf16(ra, rb);
+        }
+    }
+    if (SPLIT) *lo = make_uint4(wl[0], wl[1], wl[2], wl[3]);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 // zeroes the k-values of a bf16 fragment (8 consecutive k from k_first) that are >= kv
 __device__ __forceinline__ uint4 mask_bf16(uint4 v, int k_first, int kv)
 {
@@ -239,11 +284,16 @@ template <int BK> struct TileSeq {
     }
 };
 
+// Shape of the output tile: WMW x WN wavefronts, each holding MI x NJ MFMA 32 x 32 accumulators; the
+// tile is (32 MI WMW) x (32 NJ WN).  The default 2 x 2 blocks per wavefront with 2 x WN wavefronts is the
+// 128 x (64 WN) tile; tall tiles (MI = 5, NJ = 1: 320 x 128) let a weight gradient whose input is wider than
+// 128 columns read its large gradient operand once, wide ones (MI = 1, NJ = 5: 128 x 320) do the same for a
+// product with more than 256 output columns and its input rows.
 template <typename CT, typename SA_T, bool A_RC, bool A_DIRECT, typename SB_T, bool B_RC, bool B_DIRECT, int WN, int BK,
-          int ST, int OCC>
-__global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p)
+          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2>
+__global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmParams p)
 {
-    constexpr int NT = 128 * WN, NW = 2 * WN, BN = 64 * WN;
+    constexpr int NW = WMW * WN, NT = 64 * NW, BN = 32 * NJ * WN, BM = 32 * MI * WMW; // BM shadows the default tile height
     // a direct operand lies in LDS in its storage type (fp32 storage under bf16 compute is converted
     // when fragments are read); a staged operand lies there in the compute type
     using DA = std::conditional_t<A_DIRECT, DirectLoader<SA_T, A_RC && A_DIRECT, BM, BK, NW>, NoLoader>;
@@ -257,13 +307,15 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
     constexpr int A_BYTES = (A_DIRECT ? ST : 2) * A_STRIDE, B_BYTES = (B_DIRECT ? ST : 2) * B_STRIDE;
     constexpr int LD_PER_TILE = (A_DIRECT ? DA::NI : 0) + (B_DIRECT ? DB::NI : 0);
     static_assert(A_DIRECT || B_DIRECT, "at least one operand is loaded directly");
+    static_assert(!B_SPLIT || (B_DIRECT && B_RC && sizeof(SB_T) == 4 && sizeof(CT) == 2), "two-term feeding: direct r-contiguous fp32 B");
     static_assert(ST >= 2 && (ST - 2) * LD_PER_TILE < 64, "vmcnt range");
-    __shared__ __attribute__((aligned(1024))) char As[A_BYTES];
-    __shared__ __attribute__((aligned(1024))) char Bs[B_BYTES];
+    static_assert(A_BYTES % 1024 == 0, "stage addresses stay 1 KB aligned");
+    __shared__ __attribute__((aligned(1024))) char ring[A_BYTES + B_BYTES];
+    char *const As = ring, *const Bs = ring + A_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = (wave / WN) * 64, wn = (wave % WN) * 64;
+    const int wm = (wave / WN) * (32 * MI), wn = (wave % WN) * (32 * NJ);
     const int half = lane >> 5, l32 = lane & 31;
 
     // workgroup id -> (XCD, position in that XCD's queue) -> (outer, inner).  Workgroups are dealt
@@ -288,11 +340,11 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
     const int rows_a = static_cast<int>(min(out_seg.M - m0, static_cast<int64_t>(BM)));
     const int rows_b = static_cast<int>(min(out_seg.N - n0, static_cast<int64_t>(BN)));
 
-    floatx16 acc[2][2];
+    floatx16 acc[MI][NJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
+        for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
 
@@ -383,14 +435,14 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
             if constexpr (sizeof(CT) == 4) {
 #pragma unroll
                 for (int kk = 0; kk < BK; kk += 8) {
-                    float a[2][4], b[2][4];
+                    float a[MI][4], b[NJ][4];
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
+                    for (int i = 0; i < MI; ++i) {
                         if constexpr (A_DIRECT) dfrag_f32<A_RC, BM, BK>(reinterpret_cast<const float *>(At), wm + i * 32 + l32, kk, half, a[i]);
                         else frag_f32<A_RC, BM, BK>(reinterpret_cast<const float *>(At), wm + i * 32 + l32, kk, half, a[i]);
                     }
 #pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) {
+                    for (int jj = 0; jj < NJ; ++jj) {
                         if constexpr (B_DIRECT) dfrag_f32<B_RC, BN, BK>(reinterpret_cast<const float *>(Bt), wn + jj * 32 + l32, kk, half, b[jj]);
                         else frag_f32<B_RC, BN, BK>(reinterpret_cast<const float *>(Bt), wn + jj * 32 + l32, kk, half, b[jj]);
                     }
@@ -398,48 +450,65 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
 #pragma unroll
                         for (int t = 0; t < 4; ++t)
                             if (kk + 4 * half + t >= kv) {
-                                a[0][t] = a[1][t] = 0.f;
-                                b[0][t] = b[1][t] = 0.f;
+#pragma unroll
+                                for (int i = 0; i < MI; ++i) a[i][t] = 0.f;
+#pragma unroll
+                                for (int jj = 0; jj < NJ; ++jj) b[jj][t] = 0.f;
                             }
                     }
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
 #pragma unroll
-                        for (int i = 0; i < 2; ++i)
+                        for (int i = 0; i < MI; ++i)
 #pragma unroll
-                            for (int jj = 0; jj < 2; ++jj)
+                            for (int jj = 0; jj < NJ; ++jj)
                                 acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[jj][t], acc[i][jj], 0, 0, 0);
                 }
             } else {
 #pragma unroll
                 for (int kk = 0; kk < BK; kk += 16) {
-                    union Frag { uint4 u; bf16x8 v; } a[2], b[2];
+                    union Frag { uint4 u; bf16x8 v; } a[MI], b[NJ], bl[NJ];
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        if constexpr (A_DIRECT && sizeof(SA_T) == 4)
+                    for (int i = 0; i < MI; ++i) {
+                        if constexpr (A_DIRECT && A_RC && sizeof(SA_T) == 2)
+                            a[i].u = dfrag_bf16_rc<BM>(reinterpret_cast<const bf16_t *>(At), wm + i * 32 + l32, kk, half);
+                        else if constexpr (A_DIRECT && sizeof(SA_T) == 4)
                             a[i].u = dfrag_bf16_from_f32<BK>(reinterpret_cast<const float *>(At), wm + i * 32 + l32, kk, half);
                         else if constexpr (A_DIRECT) a[i].u = dfrag_bf16<BK>(reinterpret_cast<const bf16_t *>(At), wm + i * 32 + l32, kk, half);
                         else a[i].u = frag_bf16<A_RC, BM, BK>(reinterpret_cast<const bf16_t *>(At), wm + i * 32 + l32, kk, half);
                     }
 #pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) {
-                        if constexpr (B_DIRECT && sizeof(SB_T) == 4)
+                    for (int jj = 0; jj < NJ; ++jj) {
+                        if constexpr (B_DIRECT && B_RC && sizeof(SB_T) == 4)
+                            b[jj].u = dfrag_bf16_rc_from_f32<BN, B_SPLIT>(reinterpret_cast<const float *>(Bt), wn + jj * 32 + l32, kk, half, &bl[jj].u);
+                        else if constexpr (B_DIRECT && B_RC)
+                            b[jj].u = dfrag_bf16_rc<BN>(reinterpret_cast<const bf16_t *>(Bt), wn + jj * 32 + l32, kk, half);
+                        else if constexpr (B_DIRECT && sizeof(SB_T) == 4)
                             b[jj].u = dfrag_bf16_from_f32<BK>(reinterpret_cast<const float *>(Bt), wn + jj * 32 + l32, kk, half);
                         else if constexpr (B_DIRECT) b[jj].u = dfrag_bf16<BK>(reinterpret_cast<const bf16_t *>(Bt), wn + jj * 32 + l32, kk, half);
                         else b[jj].u = frag_bf16<B_RC, BN, BK>(reinterpret_cast<const bf16_t *>(Bt), wn + jj * 32 + l32, kk, half);
                     }
                     if (ragged) {
 #pragma unroll
-                        for (int i = 0; i < 2; ++i) {
-                            a[i].u = mask_bf16(a[i].u, kk + 8 * half, kv);
-                            b[i].u = mask_bf16(b[i].u, kk + 8 * half, kv);
+                        for (int i = 0; i < MI; ++i) a[i].u = mask_bf16(a[i].u, kk + 8 * half, kv);
+#pragma unroll
+                        for (int jj = 0; jj < NJ; ++jj) {
+                            b[jj].u = mask_bf16(b[jj].u, kk + 8 * half, kv);
+                            if constexpr (B_SPLIT) bl[jj].u = mask_bf16(bl[jj].u, kk + 8 * half, kv);
                         }
                     }
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
+                    for (int i = 0; i < MI; ++i)
 #pragma unroll
-                        for (int jj = 0; jj < 2; ++jj)
+                        for (int jj = 0; jj < NJ; ++jj)
                             acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, b[jj].v, acc[i][jj], 0, 0, 0);
+                    if constexpr (B_SPLIT) {
+#pragma unroll
+                        for (int i = 0; i < MI; ++i)
+#pragma unroll
+                            for (int jj = 0; jj < NJ; ++jj)
+                                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i].v, bl[jj].v, acc[i][jj], 0, 0, 0);
+                    }
                 }
             }
             --ahead;
@@ -451,46 +520,96 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
         }
     }
 
-    // epilogue: accumulator register v of lane (half, l32) is C[8*(v/4) + 4*half + v%4][l32] of its 32x32 tile;
-    // a store instruction writes two 128-byte row segments (32-bit stores with lanes along the row:
-    // 128-bit stores of a transposed accumulator, 32 bytes in each of 32 rows, measured slower)
+    // Epilogue through LDS.  Accumulator register v of lane (half, l32) is C[8*(v/4) + 4*half + v%4][l32] of
+    // its 32 x 32 tile: written out as it lies, a store instruction would touch 32 x 4 (or 32 x 2) bytes in
+    // each of two rows.  Instead every wavefront passes its 64 x 64 block through a private LDS strip, 8 rows
+    // x 64 columns at a time (the ring stages are free once every wavefront has left the k loop), and reads
+    // it back with a lane owning 4 consecutive columns: a store instruction then writes whole 256-byte
+    // (fp32) or 128-byte (bf16) row segments of 4 rows, and the accumulate / scale / activation forms read
+    // and write the same 16-byte pieces.
+    constexpr int EW = 32 * NJ;    // columns of a wavefront's block
+    constexpr int EPP = EW + 4;    // strip pitch in floats (rows 4 apart fall on different banks)
+    constexpr int PIECES = 8 * NJ; // 16-byte pieces per strip row
+    static_assert(A_BYTES + B_BYTES >= NW * 8 * EPP * 4, "the epilogue strips overlay the ring");
+    barrier_no_drain();     // every wavefront's last fragment reads are done (they fed its last MFMAs)
+    float *ep = reinterpret_cast<float *>(ring) + wave * (8 * EPP);
     float *Cp = out_seg.C + (p.partial ? split * out_seg.M * out_seg.ldc : 0);
+    bf16_t *Hp = reinterpret_cast<bf16_t *>(out_seg.C);
     const bool direct = !p.partial;
-    const bool plain = !direct || (!p.row_scale && p.beta == 0.f && !p.relu);
-    const bool interior = rows_a == BM && rows_b == BN;
+    const bool fused = direct && (p.row_scale || p.beta != 0.f || p.relu);
+    // 16-byte pieces (4 fp32 or 8 bf16 columns) need rows that keep that alignment
+    const bool vec_out = p.out_bf16 ? ((out_seg.ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(Hp) & 15u) == 0)
+                                    : ((out_seg.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(Cp) & 15u) == 0);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int nl = wn + jj * 32 + l32;
-            float *col = Cp + (m0 + wm + i * 32 + 4 * half) * out_seg.ldc + n0 + nl;
-            if (p.out_bf16) { // bf16 output: same element mapping, 16-bit stores
-                if (nl >= rows_b) continue;
-                bf16_t *hcol = reinterpret_cast<bf16_t *>(out_seg.C) + (m0 + wm + i * 32 + 4 * half) * out_seg.ldc + n0 + nl;
+        for (int q = 0; q < 4; ++q) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (wm + i * 32 + 8 * (v / 4) + 4 * half + (v % 4) < rows_a)
-                        hcol[(8 * (v / 4) + (v % 4)) * out_seg.ldc] = to_bf16(acc[i][jj][v]);
-                continue;
-            }
-            if (interior && plain) {
+            for (int jj = 0; jj < NJ; ++jj)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) col[(8 * (v / 4) + (v % 4)) * out_seg.ldc] = acc[i][jj][v];
-                continue;
-            }
-            if (nl >= rows_b) continue;
+                for (int t = 0; t < 4; ++t) ep[(4 * half + t) * EPP + jj * 32 + l32] = acc[i][jj][4 * q + t];
+            if (p.out_bf16) { // 8 rows x 4 NJ pieces of 8 columns: 16-byte stores, 128-byte row segments for NJ = 2
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int ml = wm + i * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (ml >= rows_a) continue;
-                float val = acc[i][jj][v];
-                float *o = col + (8 * (v / 4) + (v % 4)) * out_seg.ldc;
-                if (direct) {
-                    if (p.row_scale) val *= p.row_scale[m0 + ml];
-                    if (p.beta != 0.f) val += p.beta * *o;
-                    if (p.relu) val = fmaxf(val, 0.f);
+                for (int h = 0; h < (NJ + 1) / 2; ++h) {
+                    const int piece = h * 64 + lane;
+                    if (piece >= 32 * NJ) continue;
+                    const int row_l = piece / (4 * NJ), c8 = (piece % (4 * NJ)) * 8;
+                    const float4 lo4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c8]);
+                    const float4 hi4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c8 + 4]);
+                    const int ml = wm + i * 32 + 8 * q + row_l, nl = wn + c8;
+                    if (ml >= rows_a || nl >= rows_b) continue;
+                    const int64_t off = (m0 + ml) * out_seg.ldc + n0 + nl;
+                    if (vec_out && nl + 8 <= rows_b) {
+                        *reinterpret_cast<uint4 *>(Hp + off) = make_uint4(pack_bf16(lo4.x, lo4.y), pack_bf16(lo4.z, lo4.w),
+                                                                          pack_bf16(hi4.x, hi4.y), pack_bf16(hi4.z, hi4.w));
+                    } else {
+                        const float v[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (nl + e < rows_b) Hp[off + e] = to_bf16(v[e]);
+                    }
                 }
-                *o = val;
+                continue;
+            }
+#pragma unroll
+            for (int h = 0; h < NJ; ++h) { // the strip's 8 x PIECES pieces, 64 per pass
+                const int piece = h * 64 + lane;
+                const int row_l = piece / PIECES, c4 = (piece % PIECES) * 4;
+                const float4 v4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c4]);
+                const int ml = wm + i * 32 + 8 * q + row_l, nl = wn + c4;
+                if (ml >= rows_a || nl >= rows_b) continue;
+                float v[4] = {v4.x, v4.y, v4.z, v4.w};
+                const int64_t off = (m0 + ml) * out_seg.ldc + n0 + nl;
+                float *o = Cp + off;
+                const bool whole = vec_out && nl + 4 <= rows_b;
+                if (fused) {
+                    const float sc = p.row_scale ? p.row_scale[m0 + ml] : 1.f;
+                    float old[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (p.beta != 0.f) {
+                        if (whole) {
+                            const float4 o4 = *reinterpret_cast<const float4 *>(o);
+                            old[0] = o4.x; old[1] = o4.y; old[2] = o4.z; old[3] = o4.w;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (nl + e < rows_b) old[e] = o[e];
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float x = v[e] * sc;
+                        if (p.beta != 0.f) x += p.beta * old[e];
+                        if (p.relu) x = fmaxf(x, 0.f);
+                        v[e] = x;
+                    }
+                }
+                if (whole) {
+                    *reinterpret_cast<float4 *>(o) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (nl + e < rows_b) o[e] = v[e];
+                }
             }
         }
 }
@@ -498,10 +617,10 @@ __global__ void __launch_bounds__(128 * WN, OCC) gemm_direct_kernel(GemmParams p
 // ---- host side -------------------------------------------------------------------------------------
 
 template <typename CT, typename SA_T, bool A_RC, bool A_DIRECT, typename SB_T, bool B_RC, bool B_DIRECT, int WN, int BK,
-          int ST, int OCC>
+          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2>
 static heta_status launch_direct(GemmParams &p, hipStream_t st, const char *name, double bytes, double flops)
 {
-    constexpr int BN = 64 * WN;
+    constexpr int BN = 32 * NJ * WN, BM = 32 * MI * WMW;
     int64_t mt = 0, nt = 0;
     for (int s = 0; s < p.n_seg; ++s) {
         mt = std::max(mt, (p.seg[s].M + BM - 1) / BM);
@@ -515,8 +634,8 @@ static heta_status launch_direct(GemmParams &p, hipStream_t st, const char *name
     if (blocks <= 0) return HETA_OK;
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
     ProfScope prof(name, st, bytes, flops);
-    hipLaunchKernelGGL((gemm_direct_kernel<CT, SA_T, A_RC, A_DIRECT, SB_T, B_RC, B_DIRECT, WN, BK, ST, OCC>),
-                       dim3((unsigned)blocks), dim3(128 * WN), 0, st, p);
+    hipLaunchKernelGGL((gemm_direct_kernel<CT, SA_T, A_RC, A_DIRECT, SB_T, B_RC, B_DIRECT, WN, BK, ST, OCC, B_SPLIT, MI, NJ, WMW>),
+                       dim3((unsigned)blocks), dim3(64 * WMW * WN), 0, st, p);
     HETA_LAUNCH_CHECK("gemm_direct_kernel");
     return HETA_OK;
 }
@@ -540,6 +659,23 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         n_max = std::max(n_max, g.N);
     }
     if (p.n_split > 1 && p.k_per_split * p.n_split >= (int64_t(1) << 31) - 256) return HETA_OK;
+    if (a_dt == HETA_BF16 && b_dt == HETA_F32 && a_rc && b_rc) {
+        // The weight gradient with bf16 inputs: both operands lie with the graph rows (the contraction index)
+        // outermost and stream into LDS as they are, 16 graph rows per stage, four stages; 128 x 128 output tiles
+        // (256 threads, three workgroups per CU); the fp32 gradient operand is rounded, or split into two bf16
+        // terms, when its fragments are read.
+        *handled = true;
+        int64_t m_max = 0;
+        for (int s = 0; s < p.n_seg; ++s) m_max = std::max(m_max, p.seg[s].M);
+        if (m_max > 128) {
+            // inputs wider than 128 columns: 320 x 128 tiles (8 wavefronts of 5 x 1 accumulators), so that up to 320
+            // input columns share one pass over the gradient operand, which is the larger of the two
+            return p.split_b ? launch_direct<bf16_t, bf16_t, true, true, float, true, true, 4, 16, 4, 2, true, 5, 1, 2>(p, st, name, bytes, flops)
+                             : launch_direct<bf16_t, bf16_t, true, true, float, true, true, 4, 16, 4, 2, false, 5, 1, 2>(p, st, name, bytes, flops);
+        }
+        return p.split_b ? launch_direct<bf16_t, bf16_t, true, true, float, true, true, 2, 16, 4, 3, true>(p, st, name, bytes, flops)
+                         : launch_direct<bf16_t, bf16_t, true, true, float, true, true, 2, 16, 4, 3, false>(p, st, name, bytes, flops);
+    }
     bool wide = n_max > 128;
     if (wide) {
         // A launch that gives a workgroup to half the CUs at most (the projections of a sampled mini-batch
@@ -564,14 +700,15 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         if (a_rc && b_rc) { HETA_D32(true, true); }
 #undef HETA_D32
     }
-    if (a_dt == HETA_BF16 && b_dt == HETA_BF16 && !a_rc && b_rc) { // forward: M_r (bf16) x W_r (bf16, n-contiguous)
-        return wide ? launch_direct<bf16_t, bf16_t, false, true, bf16_t, true, false, 4, 32, 3, 4>(p, st, name, bytes, flops)
-                    : launch_direct<bf16_t, bf16_t, false, true, bf16_t, true, false, 2, 32, 3, 2>(p, st, name, bytes, flops);
+    if (a_dt == HETA_BF16 && b_dt == HETA_BF16 && !a_rc && b_rc) { // forward: M_r (bf16) x W_r (bf16, n-contiguous, as it lies in memory)
+        return wide ? launch_direct<bf16_t, bf16_t, false, true, bf16_t, true, true, 4, 32, 3, 4>(p, st, name, bytes, flops)
+                    : launch_direct<bf16_t, bf16_t, false, true, bf16_t, true, true, 2, 32, 3, 3>(p, st, name, bytes, flops);
     }
     if (a_dt == HETA_F32 && b_dt == HETA_BF16 && !a_rc && !b_rc) { // backward: G (fp32, rounded at the MFMA) x W_r^T (bf16, k-contiguous)
-        // (256 output columns: the fp32 tiles of a direct A would leave LDS room for one workgroup per CU only,
-        // so A goes through the register stage there)
-        return wide ? launch_direct<bf16_t, float, false, false, bf16_t, false, true, 4, 32, 3, 4>(p, st, name, bytes, flops)
+        // (256 output columns: 16 k-values per stage keep the fp32 tiles of A small enough for two workgroups per CU)
+        if (n_max > 256 && n_max <= 320) // 128 x 320 tiles (8 wavefronts of 1 x 5 accumulators): the fp32 rows of A are read once
+            return launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 16, 4, 2, false, 1, 5, 4>(p, st, name, bytes, flops);
+        return wide ? launch_direct<bf16_t, float, false, true, bf16_t, false, true, 4, 16, 4, 4>(p, st, name, bytes, flops)
                     : launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 32, 3, 2>(p, st, name, bytes, flops);
     }
     if (a_dt == HETA_BF16 && b_dt == HETA_BF16 && !a_rc && !b_rc) { // both k-contiguous bf16 (forward with a packed W_r^T)

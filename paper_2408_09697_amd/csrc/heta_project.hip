@@ -460,7 +460,15 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     if (misaligned(gout, 4)) return fail(HETA_ERR_INVALID_ARG, "%s: gout not 4-byte aligned", who);
     GemmParams p{};
     int64_t out_elems = 0, tiles = 0;
-    const int BN = d_out > 128 ? 256 : 128;
+    // bf16 inputs with 16-byte rows take the all-direct kernel: 128 x 128 tiles, three workgroups per CU
+    bool bf16_direct = in_dt == HETA_BF16 && !g_force_staged;
+    for (int s = 0; s < n_seg && bf16_direct; ++s)
+        bf16_direct = ins[s] && vec_ok(ins[s], ld_in[s], in_dt) && vec_ok(gouts ? gouts[s] : gout, gouts ? ld_gos[s] : ld_go, HETA_F32);
+    const int BN = (d_out > 128 && !bf16_direct) ? 256 : 128;
+    int d_in_max = 0;
+    for (int s = 0; s < n_seg; ++s) d_in_max = std::max(d_in_max, d_in[s]);
+    const bool tall = bf16_direct && d_in_max > 128; // 320 x 128 tiles, one 512-thread workgroup per CU
+    const int BMt = tall ? 320 : BM;
     for (int s = 0; s < n_seg; ++s) {
         if (!ins[s] || !dW[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
         if (d_in[s] <= 0 || ld_in[s] < d_in[s] || ld_dw[s] < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
@@ -476,7 +484,7 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
         q.K = n_rows;
         q.ldc = d_out;
         out_elems += static_cast<int64_t>(d_in[s]) * d_out;
-        tiles += ((d_in[s] + BM - 1) / BM) * ((d_out + BN - 1) / BN);
+        tiles += ((d_in[s] + BMt - 1) / BMt) * ((d_out + BN - 1) / BN);
     }
     // Split the graph rows so that the workgroups fill the chip exactly once and never spill into a
     // second, nearly empty round.  Workgroups are dealt round-robin to the 8 XCDs (32 CUs each) and
@@ -486,10 +494,10 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     // workgroup's k-tiles are latency-bound when few workgroups run).
     const int64_t BK = in_dt == HETA_F32 ? 32 : 64;
     const int64_t k_tiles = (n_rows + BK - 1) / BK;
-    const int64_t slots_per_xcd = 32 * (d_out > 128 ? 2 : (in_dt == HETA_F32 ? 3 : 4));
+    const int64_t slots_per_xcd = 32 * (tall ? 1 : bf16_direct ? 3 : (d_out > 128 ? 2 : (in_dt == HETA_F32 ? 3 : 4)));
     // a split's workgroups are (largest segment's row tiles) x (column tiles) x (segments), all on one XCD
     int64_t mt_max = 1;
-    for (int s = 0; s < n_seg; ++s) mt_max = std::max<int64_t>(mt_max, (d_in[s] + BM - 1) / BM);
+    for (int s = 0; s < n_seg; ++s) mt_max = std::max<int64_t>(mt_max, (d_in[s] + BMt - 1) / BMt);
     const int64_t slots_per_split = std::max<int64_t>(tiles, mt_max * ((d_out + BN - 1) / BN) * n_seg);
     const int64_t splits_per_xcd = std::max<int64_t>(1, slots_per_xcd / std::max<int64_t>(1, slots_per_split));
     int64_t n_split = std::max<int64_t>(1, std::min<int64_t>((k_tiles + 3) / 4, 8 * splits_per_xcd));
