@@ -366,8 +366,9 @@ heta_status heta_unique_relabel_batch(int32_t n_groups, const int32_t *group_ptr
  *   table[r] -= lr * (m[r] / (1 - beta1^t)) / (sqrt(v[r] / (1 - beta2^t)) + eps).
  * table: device [n_table_rows, ld_table] of dt (a bf16 table is widened, updated in fp32 and rounded
  * back); m, v: device fp32 [n_table_rows, ld_state]; grad: device fp32 [n, ld_grad]; ids: device
- * [n] DISTINCT rows in [0, n_table_rows) (unchecked: heta_check_ids can verify the range; repeated
- * rows would race) or NULL for the first n rows.  Rows not listed are untouched, states included.
+ * [n] DISTINCT rows in [0, n_table_rows) or NULL for the first n rows.  An id outside that range is
+ * skipped by the kernel (nothing is read or written for it; heta_check_ids reports such ids); repeated
+ * rows would race.  Rows not listed are untouched, states included.
  * `step` is the global step counter t >= 1.  One pass, asynchronous on the stream. */
 heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_table, int32_t d, int64_t n_table_rows,
                              float *m, float *v, int64_t ld_state, const int64_t *ids, int64_t n,

@@ -25,7 +25,7 @@ struct AdamParams {
     float *m, *v;
     int64_t ld_state;
     const int64_t *ids; // nullable: identity
-    int64_t n;
+    int64_t n, n_table_rows;
     const float *grad;
     int64_t ld_grad;
     int d;
@@ -56,6 +56,7 @@ __global__ void __launch_bounds__(256) sparse_adam_kernel(AdamParams p)
     if (i >= p.n) return;
     const int c = static_cast<int>(t % per_row) * V;
     const int64_t r = p.ids ? p.ids[i] : i;
+    if (r < 0 || r >= p.n_table_rows) return; // a row id outside the table: nothing is read or written for it
     const float *gp = p.grad + i * p.ld_grad + c;
     float *mp = p.m + r * p.ld_state + c, *vp = p.v + r * p.ld_state + c;
     if (V == 4) {
@@ -127,6 +128,7 @@ extern "C" heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_t
     p.ld_state = ld_state;
     p.ids = ids;
     p.n = n;
+    p.n_table_rows = n_table_rows;
     p.grad = grad;
     p.ld_grad = ld_grad;
     p.d = d;
@@ -144,6 +146,7 @@ extern "C" heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_t
     ProfScope prof("sparse_adam_kernel", st, bytes, 0);
     if (vec) {
         const int64_t threads = n * (d / 4);
+        if ((threads + 255) / 256 > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "%s: too many elements for one launch", who);
         hipLaunchKernelGGL(sparse_adam_kernel<4>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, p);
     } else {
         const int64_t threads = n * d;

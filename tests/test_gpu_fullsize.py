@@ -251,3 +251,59 @@ def test_full_size_rgat_sampled_rows_and_invariants(full_graph):
             assert_rows_close(dh[v:v + 1], rder, 1e-4, f"{r.name} der[{v}]")
         del zd, god, out, out_pos, dz, ones, norm
     torch.cuda.empty_cache()
+
+
+def test_full_size_layer_integer_inputs_bit_exact_through_both_orders():
+    """The whole layer at full size with small-integer tables, weights in {-1, 0, 1} and an integer upstream
+    gradient, sum aggregation: every partial sum of a row whose degree keeps it below 2^24 is exact in fp32
+    whatever the order, so H_t and dH0_s of those rows must equal the oracle's bit for bit - through the
+    relations that are aggregated first and through those that are projected first alike (the projection,
+    the accumulation into H_t, the CSC gather at the output width and the summed input gradient included).
+    The few hub rows above the bound are compared at 1e-4."""
+    p = workloads.config3("f32", scale=1.0, exact=True)
+    p.op = "sum"
+    g = p.graph
+    layer = make_layer(p)
+    pf = {g.relations[i].name for i in layer.pf}
+    assert pf and len(pf) < len(g.relations), "the run is meant to cover both orders"
+    H = layer.forward()
+    G = {t: torch.from_numpy(x).cuda() for t, x in p.G.items()}
+    _, dH0, _ = layer.backward(G)
+    torch.cuda.synchronize()
+    max_x, max_w, max_g, d_in, d_out = 2.0, 1.0, 2.0, 128, 256
+    # forward: |any partial sum of H_t[v]| <= (total in-degree of v) * d_in * max|x| * max|w|
+    for t in sorted(H):
+        ref = np.zeros((g.ntypes[t].num_nodes, d_out))
+        indeg = np.zeros(g.ntypes[t].num_nodes, dtype=np.int64)
+        for i in g.rels_into(t):
+            r = g.relations[i]
+            src, dst = r.edge_list()
+            ref += oracle.project(oracle.aggregate_fwd(src, dst, ref.shape[0], p.tables[r.src_type], "sum"), p.W[i])
+            indeg += np.diff(r.rowptr)
+        got = H[t].cpu().numpy()
+        exact = indeg * (d_in * max_x * max_w) < 2 ** 24
+        assert exact.mean() > 0.999
+        assert np.array_equal(got[exact].astype(np.float64), ref[exact]), f"H[{g.ntypes[t].name}]"
+        if (~exact).any():
+            assert_rows_close(got[~exact], ref[~exact], 1e-4, f"H[{g.ntypes[t].name}] hub rows")
+        del ref, got
+    # backward: |any partial sum of dH0_s[u]| <= (total out-degree of u) * d_out * max|g| * max|w|
+    for s in sorted(dH0):
+        n_s = g.ntypes[s].num_nodes
+        ref = np.zeros((n_s, d_in))
+        outdeg = np.zeros(n_s, dtype=np.int64)
+        for i in g.rels_from(s):
+            r = g.relations[i]
+            src, dst = r.edge_list()
+            dM = p.G[r.dst_type].astype(np.float64) @ p.W[i].astype(np.float64).T
+            oracle.aggregate_bwd(src, dst, n_s, g.ntypes[r.dst_type].num_nodes, dM, "sum", out=ref)
+            outdeg += np.bincount(r.col, minlength=n_s)
+            del dM
+        got = dH0[s].cpu().numpy()
+        exact = outdeg * (d_out * max_g * max_w) < 2 ** 24
+        assert exact.mean() > 0.999
+        assert np.array_equal(got[exact].astype(np.float64), ref[exact]), f"dH0[{g.ntypes[s].name}]"
+        if (~exact).any():
+            assert_rows_close(got[~exact], ref[~exact], 1e-4, f"dH0[{g.ntypes[s].name}] hub rows")
+        del ref, got
+    layer.g.destroy()

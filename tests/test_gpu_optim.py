@@ -75,3 +75,25 @@ def test_sparse_adam_identity_ids_and_argument_checks():
         heta.heta_sparse_adam(table, m, v, dev_table(grad, "f32", 4), beta1=1.0)
     with pytest.raises(heta.HetaError):   # more gradient rows than table rows without ids
         heta.heta_sparse_adam(table, m, v, torch.zeros((n + 1, d), device="cuda"))
+
+
+def test_sparse_adam_skips_row_ids_outside_the_table():
+    """An id outside [0, n_table_rows) is ignored by the kernel: the listed valid rows are updated as if the
+    bad entries were absent, nothing else changes (heta_check_ids is the call that reports such ids)."""
+    n, d = 64, 16
+    theta0 = rng.normal_table(n, d, "tests", "adam-oob")
+    grad = rng.normal_table(6, d, "tests", "adam-oobg")
+    ids = np.array([3, -1, 10, n, 1 << 40, 20], dtype=np.int64)
+    table = dev_table(theta0, "f32", 4)
+    guard = torch.full((4 * n, d), 7.0, dtype=torch.float32, device="cuda")   # m lives in the middle of a guarded buffer
+    m, v = guard[n:2 * n], torch.zeros((n, d), dtype=torch.float32, device="cuda")
+    m.zero_()
+    heta.heta_sparse_adam(table, m, v, dev_table(grad, "f32", 4), ids=torch.from_numpy(ids).cuda(), lr=0.05, step=1)
+    torch.cuda.synchronize()
+    ok = np.array([0, 2, 5])
+    ref, ref_m, _ = oracle.sparse_adam_step(theta0, np.zeros((n, d)), np.zeros((n, d)), ids[ok], grad[ok], 0.05, 0.9, 0.999, 1e-8, 1)
+    close(table.cpu().numpy(), ref, 1e-5, "valid rows updated, others untouched")
+    close(m.cpu().numpy(), ref_m, 1e-5, "moments")
+    assert bool((guard[:n] == 7.0).all()) and bool((guard[2 * n:] == 7.0).all())
+    with pytest.raises(heta.HetaError):
+        heta.heta_check_ids(torch.from_numpy(ids).cuda(), n)

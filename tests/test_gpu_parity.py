@@ -643,3 +643,55 @@ def test_project_batch_sum_and_wgrad_batch(in_s, w_s, gemm_path):
             if two and in_s == "bf16":   # 16 significant bits of the gradient operand: far inside the storage tolerance
                 assert_rows_close(w.cpu().numpy(), refw, 2e-4, "wgrad batch, two-term gradient")
     hg.destroy()
+
+
+# ---- determinism of a whole layer step ---------------------------------------------------------------
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_whole_layer_is_bitwise_reproducible_run_to_run(storage):
+    """No floating-point atomics anywhere on the path: two forward + backward passes of the whole layer
+    over the same buffers give identical bits - embeddings (k-concatenated projection), every weight
+    gradient (row range split over workgroups, partials added in split order) and every input gradient -
+    with relations of both orders in the layer.  A second layer object on a second handle, fed the same
+    inputs, must agree with the first as well."""
+    p = workloads.config3(storage, scale=0.02)
+    G = {t: torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).cuda() for t, g in p.G.items()}
+    runs = []
+    layers = [make_layer(p, project_first=[p.graph.rel_index("rev_affiliated"), p.graph.rel_index("rev_has_topic")]) for _ in range(2)]
+    for layer in (layers[0], layers[0], layers[1]):
+        H = layer.forward()
+        dW, dH0, _ = layer.backward(G)
+        torch.cuda.synchronize()
+        runs.append(([H[t].clone() for t in sorted(H)], [dW[r].clone() for r in sorted(dW)], [dH0[s].clone() for s in sorted(dH0)]))
+    for other in runs[1:]:
+        for fam_a, fam_b in zip(runs[0], other):
+            for a, b in zip(fam_a, fam_b):
+                assert torch.equal(a, b)
+    for layer in layers:
+        layer.g.destroy()
+
+
+def test_one_full_size_relation_weight_gradient_and_projection_are_reproducible():
+    """The same at the size the benchmark runs: one relation of 700 k destination rows (the split weight
+    gradient with its ordered combine, the projection and its backward), twice."""
+    n, d_in, d_out = 700_000, 128, 256
+    hg = heta.heta_graph_create([(n, 8, 0)], [(0, 0, np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32))])
+    gen_dev = torch.Generator(device="cuda")
+    gen_dev.manual_seed(5)
+    for dt in (torch.float32, torch.bfloat16):
+        M = torch.randn((n, d_in), generator=gen_dev, device="cuda").to(dt)
+        W = (torch.randn((d_in, d_out), generator=gen_dev, device="cuda") / 11).to(dt)
+        Gd = torch.randn((n, d_out), generator=gen_dev, device="cuda")
+        outs = []
+        for _ in range(2):
+            Z = torch.empty((n, d_out), device="cuda")
+            dW = torch.empty((d_in, d_out), device="cuda")
+            dM = torch.empty((n, d_in), device="cuda")
+            heta.heta_rel_project(hg, 0, M, W, Z)
+            heta.heta_rel_project_wgrad(hg, 0, M, Gd, dW)
+            heta.heta_rel_project(hg, 0, Gd, W, dM, trans_w=True)
+            torch.cuda.synchronize()
+            outs.append((Z, dW, dM))
+        for a, b in zip(*outs):
+            assert torch.equal(a, b)
+    hg.destroy()
