@@ -229,6 +229,13 @@ def measure(storage: str, workload: str, args, keep_problem: bool = False):
     t0 = time.perf_counter()
     graph = make_graph(p)
     ingest_ms = (time.perf_counter() - t0) * 1e3
+    index_bytes = heta.heta_graph_index_bytes(graph)
+    n_reverse = sum(1 for r in p.graph.relations if getattr(r, "reverse_of", None))
+    index_bytes_undeclared = None
+    if n_reverse:   # the same graph without the reverse declarations: every relation holds its own arrays
+        plain = make_graph(p, declare_reverses=False)
+        index_bytes_undeclared = heta.heta_graph_index_bytes(plain)
+        plain.destroy()
     pf = {"auto": None, "none": False, "width": True}.get(args.project_first, args.project_first)
     layer = make_layer(p, graph, project_first=[int(x) for x in pf.split(",")] if isinstance(pf, str) else pf)
     gen_dev = torch.Generator(device="cuda")
@@ -368,7 +375,8 @@ def measure(storage: str, workload: str, args, keep_problem: bool = False):
         del states
     res = {"ms_per_step": ms_per_step, "sparse_adam": adam, "fused_inference_forward": fused, "value": 2.0 * edge_features / (ms_per_step * 1e-3),
            "edges_per_s": 2.0 * n_edges / (ms_per_step * 1e-3), "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
-           "ingest_ms": ingest_ms, "input_generation_s": gen_s, "roofline": roofline, "kernels": kernels,
+           "ingest_ms": ingest_ms, "index_bytes": index_bytes, "index_bytes_without_reverse_declarations": index_bytes_undeclared,
+           "declared_reverse_relations": n_reverse, "input_generation_s": gen_s, "roofline": roofline, "kernels": kernels,
            "edges": n_edges, "edge_features_per_pass": edge_features,
            "projected_first": sorted(p.graph.relations[r].name for r in layer.pf),
            "step_time": step_stats, "per_relation_aggregation": per_relation}
@@ -780,7 +788,9 @@ def main() -> int:
             "per_relation_aggregation_note": "standalone heta_rel_aggregate_fwd / _bwd per relation; the algorithmic byte count "
                                              "charges one source row per edge, so its rate is NOT HBM traffic: above 1.0 of the "
                                              "HBM peak means rows served again from L2 / Infinity Cache",
-            "ingest": {"ms": res["ingest_ms"],
+            "ingest": {"ms": res["ingest_ms"], "index_bytes": res["index_bytes"],
+                       "index_bytes_without_reverse_declarations": res["index_bytes_without_reverse_declarations"],
+                       "declared_reverse_relations": res["declared_reverse_relations"],
                        "note": "heta_graph_create for every relation (host validation of the caller's arrays, upload, then "
                                "device kernels: radix-sort transpose, scans, degree-sorted schedules); once per graph, "
                                "outside the timed steps"},

@@ -9,7 +9,7 @@ mono-relation subgraph).  Nothing here computes any part of the layer.
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import List, Tuple
+from typing import Optional, List, Tuple
 
 import numpy as np
 
@@ -33,6 +33,7 @@ class Relation:
     dst_type: int
     rowptr: np.ndarray  # int64 [n_dst + 1], CSR over destination rows
     col: np.ndarray     # int32 [E], source node ids (duplicates allowed, any order)
+    reverse_of: Optional[str] = None  # name of the relation this one is the exact transpose of, if it was built as one
 
     @property
     def num_edges(self) -> int:
@@ -122,4 +123,4 @@ def reverse_relation(name: str, base: Relation, n_src_of_base: int) -> Relation:
     sources, so here the *sources* carry the skew."""
     src, dst = base.edge_list()
     rowptr, col = csr_from_edges(dst, src, n_src_of_base)
-    return Relation(name, base.dst_type, base.src_type, rowptr, col)
+    return Relation(name, base.dst_type, base.src_type, rowptr, col, reverse_of=base.name)

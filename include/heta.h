@@ -66,12 +66,30 @@ typedef struct {
 } heta_ntype;
 
 /* A relation = one mono-relation subgraph (Section 2.1), a bipartite adjacency from
- * src_type to dst_type given as a CSR over DESTINATION rows. */
+ * src_type to dst_type given as a CSR over DESTINATION rows, optionally with its CSC.
+ *
+ * csc_colptr / csc_row (both or neither; NULL = the library derives them): the transposed adjacency,
+ * column u listing the destinations of u's out-edges in ascending original edge position, which for a
+ * CSR means in non-decreasing order.  That order makes the CSC unique; the library checks a supplied
+ * CSC against the one it derives from the CSR, element by element, and rejects any difference with
+ * HETA_ERR_BAD_CSR (a backward pass over a CSC that disagreed with the CSR would silently compute the
+ * gradient of another graph).  The check costs what deriving costs, so supplying a CSC saves nothing.
+ *
+ * reverse_of (-1 = none; else the index j < i of an earlier relation of the same array): declares this
+ * relation to be the exact transpose of relation j - source and destination types swapped, the same
+ * edges, its CSR equal to relation j's CSC element by element (checked: HETA_ERR_BAD_CSR otherwise).
+ * The graphs of the paper's evaluation list every relation with its reverse.  A declared reverse shares
+ * relation j's index arrays and row schedules (its CSR is j's CSC, its CSC is j's CSR) instead of
+ * holding copies: half the index memory of the pair.  Results are those of an undeclared reverse.
+ * Zero-initialise the struct and set reverse_of = -1 when the fields are not used. */
 typedef struct {
     int32_t src_type, dst_type;
     int64_t num_edges;
     const int64_t *csr_rowptr; /* [n_dst + 1], rowptr[0] = 0, non-decreasing, rowptr[n_dst] = num_edges */
     const int32_t *csr_col;    /* [num_edges] source node ids in [0, n_src); any order, duplicates allowed */
+    const int64_t *csc_colptr; /* [n_src + 1] or NULL */
+    const int32_t *csc_row;    /* [num_edges] destination node ids, or NULL */
+    int32_t reverse_of;        /* -1, or the index of the relation this one is the transpose of */
 } heta_relation;
 
 /* ---- graph ingest (HetG and its decomposition into mono-relation subgraphs, Section 2.1) ------
@@ -83,12 +101,13 @@ typedef struct {
 heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels,
                               int32_t n_rels, uint32_t flags, heta_graph **out);
 heta_status heta_graph_destroy(heta_graph *g); /* NULL is accepted; synchronises the device */
-/* Testing switch (process-wide): 0 = relations of at least 2^18 edges + rows are ingested by device
- * kernels and smaller ones on the host (the default), 1 = always on the host, 2 = always on the
- * device.  Both paths produce identical index arrays. */
-heta_status heta_ingest_force(int32_t mode);
+/* Device bytes the handle holds for index data (adjacency in both directions, schedules, 1/deg);
+ * arrays shared through reverse_of count once. */
+heta_status heta_graph_index_bytes(const heta_graph *g, int64_t *bytes);
 
-/* Read-back of the derived index data into HOST buffers (for bit-exact checks). Synchronous. */
+/* Read-back of the derived index data into HOST buffers (for bit-exact checks). Synchronous.  The CSC
+ * comes back in its unique order (rows of a column non-decreasing) also for a relation that shares
+ * another one's arrays. */
 heta_status heta_graph_get_csc(const heta_graph *g, int32_t rel, int64_t *colptr /* [n_src+1] */,
                                int32_t *row /* [num_edges] */);
 heta_status heta_graph_get_degrees(const heta_graph *g, int32_t rel, int64_t *in_deg /* [n_dst] */);
@@ -166,11 +185,6 @@ heta_status heta_rel_project(heta_graph *g, int32_t rel, const void *in, heta_dt
                              int64_t ld_in, int32_t d_in, const void *W, heta_dtype w_dt, int64_t ld_w,
                              int32_t d_out, int32_t transW, const float *row_scale, void *out,
                              heta_dtype out_dt, int64_t ld_out, float beta, void *hip_stream);
-
-/* Testing / measurement switch (process-wide, not thread-safe): when on, every projection runs the
- * register-staged kernel that otherwise only serves operands whose rows are not 16-byte aligned;
- * off (the default) prefers the direct-to-LDS pipeline.  Results agree to rounding order. */
-heta_status heta_projection_force_staged(int32_t on);
 
 /* Weight gradient dW[0:d_in, 0:d_out] = beta * dW + in^T . gout, the sum running over the n_dst
  * rows of the relation in a fixed order (split over workgroups, then combined in order).

@@ -28,11 +28,14 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
-           "heta_cross_rel_project_wgrad", "heta_projection_force_staged", "heta_ingest_force", "heta_sparse_adam", "heta_project_batch",
+           "heta_cross_rel_project_wgrad", "heta_sparse_adam", "heta_project_batch",
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
            "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel",
            "heta_cross_rel_aggregate_project", "heta_meta_partition", "heta_sample_neighbors_batch",
-           "heta_unique_relabel_batch", "heta_rel_aggregate_fwd_noalloc", "heta_attn_fold", "heta_attn_fold_bwd"]
+           "heta_unique_relabel_batch", "heta_rel_aggregate_fwd_noalloc", "heta_attn_fold", "heta_attn_fold_bwd",
+           "heta_graph_index_bytes"]
+# process-wide switches for tests and measurements, declared in csrc/heta_test_hooks.h (not in the public header)
+TEST_HOOKS = ["heta_projection_force_staged", "heta_ingest_force"]
 HETA_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
@@ -49,7 +52,8 @@ class _NType(ctypes.Structure):
 
 class _Relation(ctypes.Structure):
     _fields_ = [("src_type", ctypes.c_int32), ("dst_type", ctypes.c_int32), ("num_edges", ctypes.c_int64),
-                ("csr_rowptr", ctypes.c_void_p), ("csr_col", ctypes.c_void_p)]
+                ("csr_rowptr", ctypes.c_void_p), ("csr_col", ctypes.c_void_p),
+                ("csc_colptr", ctypes.c_void_p), ("csc_row", ctypes.c_void_p), ("reverse_of", ctypes.c_int32)]
 
 
 _lib = None
@@ -79,7 +83,7 @@ def load_library() -> ctypes.CDLL:
     L.heta_rel_project_wgrad.argtypes = [vp, i32, vp, i32, i64, i32, vp, i64, i32, vp, i64, f32, vp]
     L.heta_cross_rel_reduce.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, i64, vp]
     L.heta_act_bwd.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp]
-    for name in EXPORTS:
+    for name in EXPORTS + TEST_HOOKS:
         getattr(L, name).restype = ctypes.c_int
     L.heta_last_error.restype = ctypes.c_char_p
     L.heta_last_error.argtypes = []
@@ -171,8 +175,9 @@ def heta_last_error() -> str:
 
 def heta_graph_create(ntypes: Sequence[Sequence[int]], relations: Sequence[Sequence], flags: int = 0) -> Graph:
     """ntypes: (num_nodes, feat_dim, learnable) per node type.  relations: (src_type, dst_type,
-    rowptr, col) per relation, rowptr int64 [n_dst+1] and col int32 [E]; numpy arrays, or device
-    tensors when flags has HETA_PTRS_ON_DEVICE."""
+    rowptr, col[, extras]) per relation, rowptr int64 [n_dst+1] and col int32 [E]; numpy arrays, or device
+    tensors when flags has HETA_PTRS_ON_DEVICE.  extras: a dict with "csc": (colptr int64 [n_src+1], row int32 [E])
+    and / or "reverse_of": index of the earlier relation this one is the exact transpose of."""
     L = load_library()
     nt = (_NType * max(1, len(ntypes)))()
     for i, (n, d, l) in enumerate(ntypes):
@@ -180,17 +185,28 @@ def heta_graph_create(ntypes: Sequence[Sequence[int]], relations: Sequence[Seque
     rl = (_Relation * max(1, len(relations)))()
     keep = []
     meta = []
-    for i, (s, t, rowptr, col) in enumerate(relations):
+    for i, relation in enumerate(relations):
+        s, t, rowptr, col = relation[:4]
+        extras = relation[4] if len(relation) > 4 else {}
+        csc = extras.get("csc")
+        ccp = crp = None
         if flags & HETA_PTRS_ON_DEVICE:
             rp = _dev(rowptr, "rowptr", torch.int64)
             cp = _dev(col, "col", torch.int32)
             n_e = int(col.numel())
+            if csc is not None:
+                ccp, crp = _dev(csc[0], "csc colptr", torch.int64), _dev(csc[1], "csc row", torch.int32)
+                keep += list(csc)
         else:
             rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
             col = np.ascontiguousarray(col, dtype=np.int32)
             rp, cp, n_e = rowptr.ctypes.data, col.ctypes.data, int(col.size)
+            if csc is not None:
+                c0, c1 = np.ascontiguousarray(csc[0], dtype=np.int64), np.ascontiguousarray(csc[1], dtype=np.int32)
+                ccp, crp = c0.ctypes.data, c1.ctypes.data
+                keep += [c0, c1]
         keep += [rowptr, col]
-        rl[i] = _Relation(int(s), int(t), n_e, rp, cp)
+        rl[i] = _Relation(int(s), int(t), n_e, rp, cp, ccp, crp, int(extras.get("reverse_of", -1)))
         meta.append((int(s), int(t), n_e))
     out = ctypes.c_void_p()
     _check(L.heta_graph_create(ctypes.addressof(nt) if len(ntypes) else None, len(ntypes),
@@ -211,6 +227,15 @@ def heta_graph_get_csc(g: Graph, rel: int):
     row = np.zeros(n_e, dtype=np.int32)
     _check(load_library().heta_graph_get_csc(g.handle, rel, colptr.ctypes.data, row.ctypes.data))
     return colptr, row
+
+
+def heta_graph_index_bytes(g: Graph) -> int:
+    """Device bytes the handle holds for index data; arrays shared through reverse_of count once."""
+    L = load_library()
+    L.heta_graph_index_bytes.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64)]
+    out = ctypes.c_int64()
+    _check(L.heta_graph_index_bytes(g.handle, ctypes.byref(out)))
+    return int(out.value)
 
 
 def heta_graph_get_degrees(g: Graph, rel: int) -> np.ndarray:

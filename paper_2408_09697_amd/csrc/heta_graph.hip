@@ -19,6 +19,7 @@
 #include <utility>
 
 #include "heta_internal.h"
+#include "heta_test_hooks.h"
 
 namespace heta {
 
@@ -346,6 +347,10 @@ static void destroy(heta_graph *g)
         (void)hipFree(r.d_hub_slot);
         (void)hipFree(r.d_hub_rows);
         if (r.host_built) continue; // its arrays live in the graph's arena
+        if (r.shares >= 0) {        // a declared reverse: the schedules belong to the relation it names
+            (void)hipFree(r.d_inv_deg);
+            continue;
+        }
         free_schedule(r.csr);
         free_schedule(r.csc);
         (void)hipFree(r.d_inv_deg);
@@ -388,7 +393,77 @@ static heta_status check_relation_args(const std::vector<heta_ntype> &ntypes, co
         return fail(HETA_ERR_INVALID_ARG, "relation %d: negative num_edges", index);
     if (!in.csr_rowptr || (in.num_edges > 0 && !in.csr_col))
         return fail(HETA_ERR_INVALID_ARG, "relation %d: null CSR pointer", index);
+    if ((in.csc_colptr != nullptr) != (in.csc_row != nullptr) && in.num_edges > 0)
+        return fail(HETA_ERR_INVALID_ARG, "relation %d: csc_colptr and csc_row come together or not at all", index);
+    if (in.reverse_of < -1 || in.reverse_of >= index)
+        return fail(HETA_ERR_INVALID_ARG, "relation %d: reverse_of = %d must be -1 or the index of an earlier relation", index,
+                    in.reverse_of);
     return HETA_OK;
+}
+
+// reverse_of against the relation it names (both argument structs are already checked on their own)
+static heta_status check_reverse_args(const heta_relation *rels, int32_t index)
+{
+    const heta_relation &in = rels[index];
+    if (in.reverse_of < 0) return HETA_OK;
+    const heta_relation &base = rels[in.reverse_of];
+    if (base.reverse_of >= 0)
+        return fail(HETA_ERR_INVALID_ARG, "relation %d: reverse_of names relation %d, which is itself declared a reverse", index,
+                    in.reverse_of);
+    if (base.src_type != in.dst_type || base.dst_type != in.src_type || base.num_edges != in.num_edges)
+        return fail(HETA_ERR_BAD_CSR, "relation %d is not the transpose of relation %d: node types or edge counts differ", index,
+                    in.reverse_of);
+    return HETA_OK;
+}
+
+// ---- element-wise comparison of index arrays on the device -------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) arrays_differ_kernel(const T *a, const T *b, int64_t n, int *flag)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n && a[i] != b[i]) *flag = 1; // every writer stores the same value
+}
+
+__global__ void __launch_bounds__(256) inv_degree_kernel(const int64_t *ptr, int64_t n, float *inv)
+{
+    const int64_t v = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (v >= n) return;
+    const int64_t d = ptr[v + 1] - ptr[v];
+    inv[v] = d > 0 ? 1.0f / static_cast<float>(d) : 0.0f;
+}
+
+// *differ = whether caller[0..n) (host array, or device array with on_device) differs from dev[0..n).  Synchronous.
+template <typename T>
+static heta_status differs_from_device(const T *caller, bool on_device, const T *dev, int64_t n, bool *differ)
+{
+    *differ = false;
+    if (n <= 0) return HETA_OK;
+    T *tmp = nullptr;
+    int *flag = nullptr;
+    heta_status st = HETA_OK;
+    auto done = [&](heta_status s) {
+        (void)hipFree(tmp);
+        (void)hipFree(flag);
+        return s;
+    };
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&flag), sizeof(int));
+    if (e == hipSuccess) e = hipMemset(flag, 0, sizeof(int));
+    const T *a = caller;
+    if (e == hipSuccess && !on_device) {
+        e = hipMalloc(reinterpret_cast<void **>(&tmp), n * sizeof(T));
+        if (e == hipSuccess) e = hipMemcpy(tmp, caller, n * sizeof(T), hipMemcpyHostToDevice);
+        a = tmp;
+    }
+    if (e != hipSuccess) return done(fail(e == hipErrorOutOfMemory ? HETA_ERR_OOM : HETA_ERR_DEVICE, "heta_graph_create: %s", hipGetErrorString(e)));
+    const int64_t blocks = (n + 255) / 256;
+    if (blocks > 0x7fffffff) return done(fail(HETA_ERR_UNSUPPORTED, "heta_graph_create: index array too long to compare"));
+    hipLaunchKernelGGL(arrays_differ_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, nullptr, a, dev, n, flag);
+    int h = 0;
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpy(&h, flag, sizeof(int), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return done(fail(HETA_ERR_DEVICE, "heta_graph_create: %s", hipGetErrorString(e)));
+    *differ = h != 0;
+    return done(st);
 }
 
 // Relations below this many edges + rows are ingested on the host: a few microseconds of CPU work
@@ -430,6 +505,32 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
 
     device_path = takes_device_path(E, n_dst, n_src);
     if (!device_path) return HETA_OK;
+    if (in.reverse_of >= 0) {
+        // A declared reverse: its CSR must be the named relation's CSC; then it keeps no arrays of its own
+        // but 1/deg.  (The named relation has the same size, so it took the device path as well.)
+        const Relation &base = g->rels[in.reverse_of];
+        bool d1 = false, d2 = false;
+        heta_status vst = differs_from_device(in.csr_rowptr, on_device, base.csc.d_ptr, n_dst + 1, &d1);
+        if (vst == HETA_OK) vst = differs_from_device(in.csr_col, on_device, base.csc.d_idx, E, &d2);
+        if (vst != HETA_OK) return vst;
+        if (d1 || d2)
+            return fail(HETA_ERR_BAD_CSR, "relation %d: its CSR is not the transposed adjacency of relation %d", index, in.reverse_of);
+        if (in.csc_colptr) {
+            vst = differs_from_device(in.csc_colptr, on_device, base.csr.d_ptr, n_src + 1, &d1);
+            if (vst != HETA_OK) return vst;
+            if (d1) return fail(HETA_ERR_BAD_CSR, "relation %d: the supplied CSC does not match the CSR of relation %d", index, in.reverse_of);
+        }
+        rel.csr = base.csc;
+        rel.csc = base.csr;
+        rel.shares = in.reverse_of;
+        HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.d_inv_deg), std::max<int64_t>(n_dst, 1) * sizeof(float)));
+        if (n_dst > 0) {
+            hipLaunchKernelGGL(inv_degree_kernel, dim3((unsigned)((n_dst + 255) / 256)), dim3(256), 0, st, rel.csr.d_ptr, n_dst, rel.d_inv_deg);
+            HETA_LAUNCH_CHECK("inv_degree_kernel");
+            HETA_HIP(hipStreamSynchronize(st));
+        }
+        return HETA_OK;
+    }
     // the CSR itself: a device copy of the caller's arrays
     HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_ptr), (n_dst + 1) * sizeof(int64_t)));
     HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.csr.d_idx), std::max<int64_t>(E, 1) * sizeof(int32_t)));
@@ -443,6 +544,14 @@ static heta_status ingest_relation(heta_graph *g, const heta_relation &in, int32
     HETA_HIP(hipMalloc(reinterpret_cast<void **>(&rel.d_inv_deg), std::max<int64_t>(n_dst, 1) * sizeof(float)));
     heta_status e;
     if ((e = transpose_on_device(rel.csr, n_src, rel.csc, st)) != HETA_OK) return e;
+    if (in.csc_colptr) { // a supplied CSC must be the one just derived
+        bool d1 = false, d2 = false;
+        if ((e = differs_from_device(in.csc_colptr, on_device, rel.csc.d_ptr, n_src + 1, &d1)) != HETA_OK) return e;
+        if ((e = differs_from_device(in.csc_row, on_device, rel.csc.d_idx, E, &d2)) != HETA_OK) return e;
+        if (d1 || d2)
+            return fail(HETA_ERR_BAD_CSR, "relation %d: the supplied CSC is not the transposed adjacency of its CSR (columns in "
+                                          "ascending edge order)", index);
+    }
     if ((e = build_schedule_on_device(rel.csr, rel.d_inv_deg, st)) != HETA_OK) return e;
     return build_schedule_on_device(rel.csc, nullptr, st);
 }
@@ -550,8 +659,49 @@ static heta_status build_small_relations(heta_graph *g, const heta_relation *rel
     }
     run();
     for (std::thread &w : workers) w.join();
-    for (size_t k = 0; k < small.size(); ++k) {
+    for (size_t k = 0; k < small.size(); ++k)
         if (built[k].status != HETA_OK) return fail(built[k].status, "%s", built[k].message.c_str());
+    // Supplied CSCs and declared reverses of host-built relations are checked against what was just built
+    // (small relations keep arrays of their own either way: sharing pays for the large, device-built ones).
+    std::vector<char> fetched;
+    auto on_host = [&](const void *p, size_t bytes, const void **out) -> heta_status { // caller's array as host memory
+        *out = p;
+        if (!on_device || bytes == 0) return HETA_OK;
+        fetched.resize(bytes);
+        HETA_HIP(hipMemcpy(fetched.data(), p, bytes, hipMemcpyDeviceToHost));
+        *out = fetched.data();
+        return HETA_OK;
+    };
+    for (size_t k = 0; k < small.size(); ++k) {
+        const int32_t i = small[k];
+        const heta_relation &in = rels[i];
+        const Relation &rel = g->rels[i];
+        const void *q = nullptr;
+        if (in.csc_colptr) {
+            heta_status st = on_host(in.csc_colptr, (rel.n_src + 1) * sizeof(int64_t), &q);
+            if (st != HETA_OK) return st;
+            bool bad = std::memcmp(q, base + lay[k].csc.ptr, (rel.n_src + 1) * sizeof(int64_t)) != 0;
+            if (!bad && rel.n_edges) {
+                if ((st = on_host(in.csc_row, rel.n_edges * sizeof(int32_t), &q)) != HETA_OK) return st;
+                bad = std::memcmp(q, base + lay[k].csc.idx, rel.n_edges * sizeof(int32_t)) != 0;
+            }
+            if (bad)
+                return fail(HETA_ERR_BAD_CSR, "relation %d: the supplied CSC is not the transposed adjacency of its CSR (columns in "
+                                              "ascending edge order)", i);
+        }
+        if (in.reverse_of >= 0) {
+            size_t kj = small.size();
+            for (size_t t = 0; t < small.size(); ++t)
+                if (small[t] == in.reverse_of) kj = t;
+            if (kj == small.size()) return fail(HETA_ERR_BAD_CSR, "relation %d is not the transpose of relation %d", i, in.reverse_of);
+            const int64_t *ptr = on_device ? staged[i].ptr : in.csr_rowptr;
+            const int32_t *col = on_device ? staged[i].col : in.csr_col;
+            if (std::memcmp(ptr, base + lay[kj].csc.ptr, (rel.n_dst + 1) * sizeof(int64_t)) != 0 ||
+                (rel.n_edges && std::memcmp(col, base + lay[kj].csc.idx, rel.n_edges * sizeof(int32_t)) != 0))
+                return fail(HETA_ERR_BAD_CSR, "relation %d: its CSR is not the transposed adjacency of relation %d", i, in.reverse_of);
+        }
+    }
+    for (size_t k = 0; k < small.size(); ++k) {
         PendingRelation pr;
         pr.rel = static_cast<size_t>(small[k]);
         pr.csr = lay[k].csr;
@@ -613,6 +763,7 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
         std::vector<heta_ntype> nts(ntypes, ntypes + n_ntypes);
         for (int32_t i = 0; i < n_rels; ++i) {
             heta_status st = check_relation_args(nts, rels[i], i);
+            if (st == HETA_OK) st = check_reverse_args(rels, i);
             if (st == HETA_OK && !on_device)
                 st = validate_relation(nts, rels[i], i, rels[i].csr_rowptr, rels[i].csr_col);
             if (st != HETA_OK)
@@ -695,6 +846,27 @@ heta_status heta_graph_get_csc(const heta_graph *g, int32_t rel, int64_t *colptr
     HETA_HIP(hipMemcpy(colptr, r.csc.d_ptr, (r.n_src + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
     if (r.n_edges)
         HETA_HIP(hipMemcpy(row, r.csc.d_idx, r.n_edges * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (r.shares >= 0) {
+        // The shared array is the named relation's CSR, whose rows hold their neighbours in the caller's order;
+        // the transposed adjacency in ascending edge order lists each column's rows in non-decreasing order.
+        for (int64_t u = 0; u < r.n_src; ++u) std::sort(row + colptr[u], row + colptr[u + 1]);
+    }
+    return HETA_OK;
+}
+
+heta_status heta_graph_index_bytes(const heta_graph *g, int64_t *bytes)
+{
+    if (!g || !bytes) return fail(HETA_ERR_INVALID_ARG, "heta_graph_index_bytes: null argument");
+    auto schedule_bytes = [](const Schedule &s) {
+        return (s.n_rows + 1) * 8 * 2 + s.n_edges * 4 * 2 + s.n_rows * 4 + s.n_hub_chunks * static_cast<int64_t>(sizeof(HubChunk)) +
+               (s.n_hub_rows + 1) * 8;
+    };
+    int64_t total = 0;
+    for (const Relation &r : g->rels) {
+        total += r.n_dst * 4; // 1/deg
+        if (r.shares < 0) total += schedule_bytes(r.csr) + schedule_bytes(r.csc);
+    }
+    *bytes = total;
     return HETA_OK;
 }
 

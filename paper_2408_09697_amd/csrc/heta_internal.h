@@ -77,6 +77,7 @@ struct Relation {
     float *d_hub_rows = nullptr;   // aggregated hub rows of the fused forward, grown on demand
     size_t hub_rows_bytes = 0;
     bool host_built = false;      // its device arrays are slices of the graph's arena, not allocations of their own
+    int32_t shares = -1;          // >= 0: csr / csc are relation `shares`' csc / csr (a declared reverse); only d_inv_deg is its own
 };
 
 } // namespace heta

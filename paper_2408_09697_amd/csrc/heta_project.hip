@@ -29,6 +29,7 @@
 #include <algorithm>
 
 #include "heta_gemm.h"
+#include "heta_test_hooks.h"
 
 namespace heta {
 

@@ -28,10 +28,24 @@ def dev_table(x: np.ndarray, storage: str, pad_to: int = 1) -> torch.Tensor:
     return buf[:, :d]
 
 
-def make_graph(p) -> heta.Graph:
+def relation_tuples(graph, declare_reverses: bool = True):
+    """(src_type, dst_type, rowptr, col[, extras]) per relation for heta_graph_create; a relation the
+    generator built as the exact transpose of an earlier one is declared as its reverse, so that the
+    handle shares the index arrays of the pair."""
+    names = [r.name for r in graph.relations]
+    out = []
+    for i, r in enumerate(graph.relations):
+        base = getattr(r, "reverse_of", None)
+        if declare_reverses and base in names[:i]:
+            out.append((r.src_type, r.dst_type, r.rowptr, r.col, {"reverse_of": names.index(base)}))
+        else:
+            out.append((r.src_type, r.dst_type, r.rowptr, r.col))
+    return out
+
+
+def make_graph(p, declare_reverses: bool = True) -> heta.Graph:
     nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in p.graph.ntypes]
-    rels = [(r.src_type, r.dst_type, r.rowptr, r.col) for r in p.graph.relations]
-    return heta.heta_graph_create(nts, rels)
+    return heta.heta_graph_create(nts, relation_tuples(p.graph, declare_reverses))
 
 
 def make_layer(p, graph: Optional[heta.Graph] = None, rels=None, project_first=None) -> RafLayer:

@@ -12,8 +12,8 @@ from paper_2408_09697_amd import binding as hb
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "heta.h")).read()
+def declared_symbols(header=os.path.join("include", "heta.h")):
+    text = open(os.path.join(ROOT, header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(heta_[a-z_0-9]+)\s*\(", text)))
 
@@ -25,6 +25,11 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in heta.h but not exported"
     assert sorted(hb.EXPORTS) == names
+    # the process-wide test switches live in an internal header, outside the public ABI, and are exported too
+    hooks = declared_symbols(os.path.join("paper_2408_09697_amd", "csrc", "heta_test_hooks.h"))
+    assert sorted(hb.TEST_HOOKS) == hooks and not set(hooks) & set(names)
+    for n in hooks:
+        assert hasattr(lib, n), n
     assert heta.heta_version() == "0.1"
 
 
@@ -151,3 +156,34 @@ def test_relation_order_rule_on_the_shapes_it_was_measured_on():
     assert [i for i, (s, t, e) in enumerate(c3) if pays(s, t, e, 128, 256, 2)] == [6]
     assert pays(500_000, 1_500_000, 5_000_000, 300, 256, 2) and pays(100_000, 500_000, 2_000_000, 789, 256, 2)
     assert not pays(1_500_000, 500_000, 5_000_000, 7, 256, 2) and not pays(800_000, 500_000, 4_000_000, 64, 256, 2)
+
+
+def test_csc_and_reverse_arguments_are_checked_on_the_host():
+    rp = np.array([0, 1, 2, 2], dtype=np.int64)           # type 0 (4 nodes) -> type 1 (3 nodes), 2 edges
+    col = np.array([0, 3], dtype=np.int32)
+    trp = np.array([0, 1, 1, 1, 2], dtype=np.int64)        # its transpose: type 1 -> type 0
+    tcol = np.array([0, 1], dtype=np.int32)
+    L = hb.load_library()
+    import ctypes
+    nt = (hb._NType * 2)(hb._NType(4, 8, 0), hb._NType(3, 8, 1))
+
+    def create(structs):
+        arr = (hb._Relation * len(structs))(*structs)
+        out = ctypes.c_void_p()
+        st = L.heta_graph_create(ctypes.addressof(nt), 2, ctypes.addressof(arr), len(structs), 0, ctypes.byref(out))
+        return st, L.heta_last_error().decode(), out.value
+
+    base = hb._Relation(0, 1, 2, rp.ctypes.data, col.ctypes.data, None, None, -1)
+    # one CSC pointer without the other
+    st, msg, h = create([hb._Relation(0, 1, 2, rp.ctypes.data, col.ctypes.data, trp.ctypes.data, None, -1)])
+    assert st == hb.HETA_ERR_INVALID_ARG and "come together" in msg and h is None
+    # reverse_of must name an earlier relation
+    st, msg, h = create([hb._Relation(0, 1, 2, rp.ctypes.data, col.ctypes.data, None, None, 0)])
+    assert st == hb.HETA_ERR_INVALID_ARG and "earlier relation" in msg and h is None
+    # ... that is not itself a declared reverse
+    rev = hb._Relation(1, 0, 2, trp.ctypes.data, tcol.ctypes.data, None, None, 0)
+    st, msg, h = create([base, rev, hb._Relation(0, 1, 2, rp.ctypes.data, col.ctypes.data, None, None, 1)])
+    assert st == hb.HETA_ERR_INVALID_ARG and "itself declared a reverse" in msg and h is None
+    # node types that are not swapped
+    st, msg, h = create([base, hb._Relation(0, 1, 2, rp.ctypes.data, col.ctypes.data, None, None, 0)])
+    assert st == hb.HETA_ERR_BAD_CSR and "node types or edge counts" in msg and h is None

@@ -695,3 +695,110 @@ def test_one_full_size_relation_weight_gradient_and_projection_are_reproducible(
         for a, b in zip(*outs):
             assert torch.equal(a, b)
     hg.destroy()
+
+
+# ---- the boundary's CSC and reverse_of fields -----------------------------------------------------------
+
+def _reverse_pair_graph(mode):
+    """config 3 at a small scale with the three relations the generator built as exact transposes, ingested
+    by the host path or by the device kernels."""
+    from paper_2408_09697_amd.problems import relation_tuples
+    p = workloads.config3("f32", scale=0.02, exact=True)
+    nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in p.graph.ntypes]
+    heta.heta_ingest_force(mode)
+    try:
+        declared = heta.heta_graph_create(nts, relation_tuples(p.graph, True))
+        plain = heta.heta_graph_create(nts, relation_tuples(p.graph, False))
+    finally:
+        heta.heta_ingest_force(0)
+    return p, declared, plain
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["host_ingest", "device_ingest"])
+def test_declared_reverse_relations_share_arrays_and_give_the_same_results(mode):
+    """A relation declared as the reverse of an earlier one is checked against that relation's transposed
+    adjacency and (device-built) shares its arrays.  Index data read back is the oracle's for every relation;
+    with integer inputs forward and backward aggregations equal those of the undeclared graph bit for bit;
+    and for sum aggregation the backward of a relation is the forward of its reverse (both on the GPU)."""
+    p, declared, plain = _reverse_pair_graph(mode)
+    g = p.graph
+    pairs = [(g.rel_index(r.reverse_of), i) for i, r in enumerate(g.relations) if r.reverse_of]
+    assert len(pairs) == 3
+    if mode == 2:   # device-built: the reverses hold no adjacency of their own
+        assert heta.heta_graph_index_bytes(declared) < 0.75 * heta.heta_graph_index_bytes(plain)
+    else:
+        assert heta.heta_graph_index_bytes(declared) == heta.heta_graph_index_bytes(plain)
+    d = 24
+    for i, r in enumerate(g.relations):
+        src, dst = r.edge_list()
+        n_s, n_t = g.ntypes[r.src_type].num_nodes, g.ntypes[r.dst_type].num_nodes
+        colptr, row = heta.heta_graph_get_csc(declared, i)
+        rc, rr = oracle.csc(src, dst, n_s)
+        assert np.array_equal(colptr, rc) and np.array_equal(row, rr), r.name
+        assert np.array_equal(heta.heta_graph_get_degrees(declared, i), oracle.in_degree(src, dst, n_t)), r.name
+        x = rng.small_int_table(n_s, d, -2, 2, "tests", f"rev/x/{r.name}")
+        gx = rng.small_int_table(n_t, d, -2, 2, "tests", f"rev/g/{r.name}")
+        outs = []
+        for hg in (declared, plain):
+            f = torch.empty((n_t, d), device="cuda")
+            b = torch.empty((n_s, d), device="cuda")
+            heta.heta_rel_aggregate_fwd(hg, i, heta.HETA_MEAN, dev_table(x, "f32", 4), f)
+            heta.heta_rel_aggregate_bwd(hg, i, heta.HETA_SUM, dev_table(gx, "f32", 4), b)
+            outs.append((f, b))
+        assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1]), r.name
+        assert_rows_close(outs[0][0].cpu().numpy(), oracle.aggregate_fwd(src, dst, n_t, x, "mean"), 1e-4, r.name)
+        assert np.array_equal(outs[0][1].cpu().numpy().astype(np.float64), oracle.aggregate_bwd(src, dst, n_s, n_t, gx.astype(np.float64), "sum"))
+    for j, i in pairs:   # backward of the base (sum) == forward of its reverse (sum), floating-point inputs
+        n_s, n_t = g.ntypes[g.relations[j].src_type].num_nodes, g.ntypes[g.relations[j].dst_type].num_nodes
+        gm = dev_table(rng.normal_table(n_t, d, "tests", f"rev/p9/{j}"), "f32", 4)
+        b = torch.empty((n_s, d), device="cuda")
+        f = torch.empty((n_s, d), device="cuda")
+        heta.heta_rel_aggregate_bwd(declared, j, heta.HETA_SUM, gm, b)
+        heta.heta_rel_aggregate_fwd(declared, i, heta.HETA_SUM, gm, f)
+        assert_rows_close(f.cpu().numpy(), b.cpu().numpy().astype(np.float64), 1e-5, "bwd(base) vs fwd(reverse)")
+    declared.destroy()
+    plain.destroy()
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["host_ingest", "device_ingest"])
+def test_supplied_csc_and_reverse_declarations_are_validated(mode):
+    rel = skewed_relation()
+    src, dst = rel.edge_list()
+    colptr, row = oracle.csc(src, dst, 3000)
+    nts = [(3000, 8, 0), (2000, 8, 0)]
+    heta.heta_ingest_force(mode)
+    try:
+        hg = heta.heta_graph_create(nts, [(0, 1, rel.rowptr, rel.col, {"csc": (colptr, row)})])   # the right one is accepted
+        got = heta.heta_graph_get_csc(hg, 0)
+        assert np.array_equal(got[0], colptr) and np.array_equal(got[1], row)
+        hg.destroy()
+        # the same through device pointers
+        dev = lambda a: torch.from_numpy(a).cuda()
+        hg = heta.heta_graph_create(nts, [(0, 1, dev(rel.rowptr), dev(rel.col), {"csc": (dev(colptr), dev(row))})],
+                                    flags=heta.HETA_PTRS_ON_DEVICE)
+        hg.destroy()
+        u = int(np.argmax(np.diff(colptr) >= 2))            # a column with two edges
+        bad_row = row.copy()
+        a = int(colptr[u])
+        if bad_row[a] == bad_row[a + 1]:
+            bad_row[a + 1] = (bad_row[a + 1] + 1) % 2000     # another destination
+        else:
+            bad_row[a], bad_row[a + 1] = bad_row[a + 1], bad_row[a]   # same edges, wrong order within the column
+        bad_ptr = colptr.copy()
+        bad_ptr[5] += 1
+        for csc in ((colptr, bad_row), (bad_ptr, row)):
+            with pytest.raises(heta.HetaError) as ei:
+                heta.heta_graph_create(nts, [(0, 1, rel.rowptr, rel.col, {"csc": csc})])
+            assert ei.value.status == heta.HETA_ERR_BAD_CSR and "supplied CSC" in ei.value.message
+        # a declared reverse that is the transpose of something else
+        other = Relation("other", 0, 1, rel.rowptr, rng.stream("tests", "revbad").permutation(rel.col))   # same degrees, other sources
+        osrc, odst = other.edge_list()
+        ocp, orow = oracle.csc(osrc, odst, 3000)
+        with pytest.raises(heta.HetaError) as ei:
+            heta.heta_graph_create(nts, [(0, 1, rel.rowptr, rel.col), (1, 0, ocp, orow, {"reverse_of": 0})])
+        assert ei.value.status == heta.HETA_ERR_BAD_CSR and "transposed adjacency of relation 0" in ei.value.message
+        hg = heta.heta_graph_create(nts, [(0, 1, rel.rowptr, rel.col), (1, 0, colptr, row, {"reverse_of": 0})])
+        assert np.array_equal(heta.heta_graph_get_degrees(hg, 1), np.diff(colptr))
+        hg.destroy()
+    finally:
+        heta.heta_ingest_force(0)
