@@ -13,7 +13,7 @@ LIB_DIR = os.path.join(PKG, "lib")
 LIB = os.path.join(LIB_DIR, "libheta.so")
 OBJ_DIR = os.path.join(LIB_DIR, "obj")
 
-SOURCES = ["heta_graph.hip", "heta_ingest.hip", "heta_aggregate.hip", "heta_project.hip", "heta_gemm_direct.hip", "heta_reduce.hip", "heta_optim.hip", "heta_attention.hip", "heta_sample.hip", "heta_fused.hip", "heta_metapartition.hip", "heta_profile.hip"]
+SOURCES = ["heta_graph.hip", "heta_ingest.hip", "heta_block_ingest.hip", "heta_aggregate.hip", "heta_project.hip", "heta_gemm_direct.hip", "heta_reduce.hip", "heta_optim.hip", "heta_attention.hip", "heta_sample.hip", "heta_fused.hip", "heta_metapartition.hip", "heta_profile.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -356,6 +356,7 @@ static void destroy(heta_graph *g)
         (void)hipFree(r.d_inv_deg);
     }
     scratch_free(g->d_arena); // the device is idle here
+    scratch_free(g->d_block_arena);
     scratch_free(g->d_ws);
     scratch_free(g->d_pack);
     (void)hipFree(g->d_attn);
@@ -470,7 +471,10 @@ static heta_status differs_from_device(const T *caller, bool on_device, const T 
 // beat the launch latencies of the device pipeline (sampled mini-batch blocks); everything larger
 // is built by the kernels of heta_ingest.hip.  heta_ingest_force() overrides the choice.
 constexpr int64_t kDeviceIngestMin = 1 << 18;
-static int g_ingest_mode = 0; // 0 = by size, 1 = host, 2 = device
+// The small relations of one graph together (a sampled block) go through the whole-block device ingest when they
+// add up to this many edges + rows (and are at most 32); below it the host builds them faster than ~40 launches run.
+constexpr int64_t kBlockIngestMin = 1 << 16;
+static int g_ingest_mode = 0; // 0 = by size, 1 = host, 2 = per-relation device kernels, 3 = small relations by the whole-block device ingest
 
 // A host-built relation waits in the graph's host buffer until every relation is built; then one
 // allocation and one copy bring all of them to the device and the offsets become pointers.
@@ -482,7 +486,99 @@ struct PendingRelation {
 
 static bool takes_device_path(int64_t E, int64_t n_dst, int64_t n_src)
 {
-    return g_ingest_mode == 2 || (g_ingest_mode == 0 && E + n_dst + n_src >= kDeviceIngestMin);
+    return g_ingest_mode == 2 || ((g_ingest_mode == 0 || g_ingest_mode == 3) && E + n_dst + n_src >= kDeviceIngestMin);
+}
+
+// whether the small relations of a graph (those that do not take the per-relation device path) are built together on the device
+static bool takes_block_path(const std::vector<heta_ntype> &nts, const heta_relation *rels, int32_t n_rels)
+{
+    if (g_ingest_mode == 1 || g_ingest_mode == 2) return false;
+    int64_t work = 0;
+    int32_t n_small = 0;
+    for (int32_t i = 0; i < n_rels; ++i) {
+        const int64_t n_dst = nts[rels[i].dst_type].num_nodes, n_src = nts[rels[i].src_type].num_nodes, E = rels[i].num_edges;
+        if (takes_device_path(E, n_dst, n_src)) continue;
+        work += E + n_dst + n_src;
+        ++n_small;
+    }
+    if (n_small == 0 || n_small > block_ingest_max_relations()) return false;
+    return g_ingest_mode == 3 || work >= kBlockIngestMin;
+}
+
+// The small relations of g through the whole-block device ingest.  Host arrays are staged through the page-locked
+// buffer and one device block first; supplied CSCs and declared reverses are then checked against what was built.
+static heta_status build_small_relations_on_device(heta_graph *g, const heta_relation *rels, const std::vector<int32_t> &small,
+                                                   bool on_device)
+{
+    const size_t n = small.size();
+    std::vector<const int64_t *> ptrs(n);
+    std::vector<const int32_t *> cols(n);
+    void *staging = nullptr;
+    if (on_device) {
+        for (size_t k = 0; k < n; ++k) {
+            ptrs[k] = rels[small[k]].csr_rowptr;
+            cols[k] = rels[small[k]].csr_col;
+        }
+    } else {
+        HostPack pack;
+        std::vector<size_t> off_ptr(n), off_col(n);
+        size_t total = 0;
+        for (size_t k = 0; k < n; ++k) {
+            const Relation &r = g->rels[small[k]];
+            off_ptr[k] = take(total, (static_cast<size_t>(r.n_dst) + 1) * sizeof(int64_t));
+            off_col[k] = take(total, static_cast<size_t>(r.n_edges) * sizeof(int32_t));
+        }
+        if (!pack.reserve(total)) return fail(HETA_ERR_OOM, "heta_graph_create: page-locked host allocation of %zu bytes failed", total);
+        for (size_t k = 0; k < n; ++k) {
+            const Relation &r = g->rels[small[k]];
+            std::memcpy(t_pinned.p + off_ptr[k], rels[small[k]].csr_rowptr, (r.n_dst + 1) * sizeof(int64_t));
+            if (r.n_edges) std::memcpy(t_pinned.p + off_col[k], rels[small[k]].csr_col, r.n_edges * sizeof(int32_t));
+        }
+        HETA_HIP(scratch_alloc(&staging, total));
+        hipError_t e = hipMemcpyAsync(staging, t_pinned.p, total, hipMemcpyHostToDevice, nullptr);
+        if (e != hipSuccess) {
+            (void)hipStreamSynchronize(nullptr);
+            scratch_free(staging);
+            return fail(HETA_ERR_DEVICE, "heta_graph_create: %s", hipGetErrorString(e));
+        }
+        for (size_t k = 0; k < n; ++k) {
+            ptrs[k] = reinterpret_cast<const int64_t *>(static_cast<char *>(staging) + off_ptr[k]);
+            cols[k] = reinterpret_cast<const int32_t *>(static_cast<char *>(staging) + off_col[k]);
+        }
+    }
+    // The build runs on a stream of the library's own (per thread and device, default priority, non-blocking): its inputs
+    // are complete (host arrays; device arrays the caller has finished, as for every synchronous call) and it is complete
+    // when the call returns.  On the legacy default stream every one of its ~45 launches would first be ordered against
+    // all other streams of the process, which costs more than the kernels run.
+    static thread_local hipStream_t t_stream[64] = {};
+    int dev = 0;
+    HETA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return fail(HETA_ERR_UNSUPPORTED, "device index %d beyond 64", dev);
+    if (!t_stream[dev]) HETA_HIP(hipStreamCreateWithFlags(&t_stream[dev], hipStreamNonBlocking));
+    if (staging) HETA_HIP(hipStreamSynchronize(nullptr)); // the staged arrays have arrived
+    heta_status st = build_block_on_device(g, small, ptrs.data(), cols.data(), &g->d_block_arena, t_stream[dev]); // synchronous
+    scratch_free(staging);
+    if (st != HETA_OK) return st;
+    for (size_t k = 0; k < n; ++k) {
+        const int32_t i = small[k];
+        const heta_relation &in = rels[i];
+        const Relation &rel = g->rels[i];
+        bool d1 = false, d2 = false;
+        if (in.csc_colptr) {
+            if ((st = differs_from_device(in.csc_colptr, on_device, rel.csc.d_ptr, rel.n_src + 1, &d1)) != HETA_OK) return st;
+            if ((st = differs_from_device(in.csc_row, on_device, rel.csc.d_idx, rel.n_edges, &d2)) != HETA_OK) return st;
+            if (d1 || d2)
+                return fail(HETA_ERR_BAD_CSR, "relation %d: the supplied CSC is not the transposed adjacency of its CSR (columns in "
+                                              "ascending edge order)", i);
+        }
+        if (in.reverse_of >= 0) {
+            const Relation &base = g->rels[in.reverse_of];
+            if ((st = differs_from_device(in.csr_rowptr, on_device, base.csc.d_ptr, rel.n_dst + 1, &d1)) != HETA_OK) return st;
+            if ((st = differs_from_device(in.csr_col, on_device, base.csc.d_idx, rel.n_edges, &d2)) != HETA_OK) return st;
+            if (d1 || d2) return fail(HETA_ERR_BAD_CSR, "relation %d: its CSR is not the transposed adjacency of relation %d", i, in.reverse_of);
+        }
+    }
+    return HETA_OK;
 }
 
 // Registers relation `index` in g; a large relation is built on the device right away, a small one
@@ -792,7 +888,8 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
         HostPack pack;
         std::vector<PendingRelation> pending;
         std::vector<StagedCsr> staged(n_rels);
-        if (on_device) {
+        const bool block_path = takes_block_path(g->ntypes, rels, n_rels);
+        if (on_device && !block_path) {
             heta_status st = download_small_relations(g->ntypes, rels, n_rels, staged);
             if (st != HETA_OK) {
                 destroy(g);
@@ -809,8 +906,13 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
             }
             if (!device_path) small.push_back(i);
         }
-        heta_status st = build_small_relations(g, rels, small, on_device, staged, pack, pending);
-        if (st == HETA_OK) st = upload_host_built(g, pack, pending);
+        heta_status st;
+        if (block_path) {
+            st = build_small_relations_on_device(g, rels, small, on_device);
+        } else {
+            st = build_small_relations(g, rels, small, on_device, staged, pack, pending);
+            if (st == HETA_OK) st = upload_host_built(g, pack, pending);
+        }
         if (st != HETA_OK) {
             destroy(g);
             return st;
@@ -825,7 +927,7 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
 
 heta_status heta_ingest_force(int32_t mode)
 {
-    if (mode < 0 || mode > 2) return fail(HETA_ERR_INVALID_ARG, "heta_ingest_force: mode must be 0, 1 or 2");
+    if (mode < 0 || mode > 3) return fail(HETA_ERR_INVALID_ARG, "heta_ingest_force: mode must be 0, 1, 2 or 3");
     g_ingest_mode = mode;
     return HETA_OK;
 }

@@ -113,12 +113,59 @@ template <typename TO> __global__ void __launch_bounds__(256) scan_add_kernel(TO
     if (i < n) out[i] += tile_sums[i / kScanTile];
 }
 
+// The whole scan by one workgroup of 1024 threads, 8192 elements per round with a running carry: for the
+// short arrays of a sampled block (digit histograms of a sort pass, a few thousand rows) one launch instead
+// of three dependent ones.
+constexpr int kScanSingleMax = 4 * 8192;
+template <typename TI, typename TO>
+__global__ void __launch_bounds__(1024) scan_single_kernel(const TI *in, int64_t n_in, TO *out, int64_t n_out)
+{
+    __shared__ TO wave_tot[16];
+    __shared__ TO carry_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t round0 = 0; round0 < n_out; round0 += 1024 * kScanItems) {
+        const int64_t base = round0 + static_cast<int64_t>(tid) * kScanItems;
+        TO v[kScanItems];
+        TO sum = 0;
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            v[i] = (base + i < n_in) ? static_cast<TO>(in[base + i]) : TO(0);
+            sum += v[i];
+        }
+        TO incl = sum;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const TO up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        TO before = carry_s + incl - sum;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            if (base + i < n_out) out[base + i] = before;
+            before += v[i];
+        }
+        __syncthreads();
+        if (tid == 1023) carry_s = before;
+        __syncthreads();
+    }
+}
+
 // tile_sums: scratch of (n_out + kScanTile - 1) / kScanTile elements; asynchronous on st
 template <typename TI, typename TO>
 heta_status exclusive_scan_with(const TI *in, int64_t n_in, TO *out, int64_t n_out, TO *tile_sums, hipStream_t st)
 {
     if (n_out <= 0) return HETA_OK;
     const int64_t tiles = (n_out + kScanTile - 1) / kScanTile;
+    if (tiles > 1 && n_out <= kScanSingleMax) {
+        hipLaunchKernelGGL((scan_single_kernel<TI, TO>), dim3(1), dim3(1024), 0, st, in, n_in, out, n_out);
+        HETA_LAUNCH_CHECK("scan_single_kernel");
+        return HETA_OK;
+    }
     hipLaunchKernelGGL((scan_tile_kernel<TI, TO>), dim3((unsigned)tiles), dim3(256), 0, st, in, n_in, out, n_out, tile_sums);
     HETA_LAUNCH_CHECK("scan_tile_kernel");
     if (tiles > 1) {

@@ -87,6 +87,7 @@ struct heta_graph {
     std::vector<heta_ntype> ntypes;
     std::vector<heta::Relation> rels;
     void *d_arena = nullptr;      // every host-built relation's arrays: one allocation, one copy
+    void *d_block_arena = nullptr; // the arrays of the relations built by the whole-block device ingest
     // workspace for hub-row partials and split weight-gradient partials; grown on demand
     void *d_ws = nullptr;
     size_t ws_bytes = 0;
@@ -123,6 +124,12 @@ heta_status validate_csr_on_device(int32_t index, const int64_t *d_ptr, const in
 heta_status transpose_on_device(const Schedule &csr, int64_t n_src, Schedule &csc, hipStream_t st);
 // everything of s beyond d_ptr / d_idx (allocated here); inv_deg (optional, [n_rows]) = 1/degree
 heta_status build_schedule_on_device(Schedule &s, float *inv_deg, hipStream_t st);
+
+// Whole-block ingest (heta_block_ingest.hip): the index data of up to block_ingest_max_relations() relations of g
+// (listed in `which`, registered already) from their DEVICE CSR arrays, in one pass; *arena_out owns their arrays.
+int block_ingest_max_relations();
+heta_status build_block_on_device(heta_graph *g, const std::vector<int32_t> &which, const int64_t *const *rowptr,
+                                  const int32_t *const *col, void **arena_out, hipStream_t st);
 
 // out[i] = in[0] + ... + in[i-1] for i < n_out (in[j] = 0 for j >= n_in); synchronous on st.
 heta_status device_exclusive_scan_i64(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, hipStream_t st);

@@ -8,9 +8,11 @@
 extern "C" {
 #endif
 
-/* 0 = relations of at least 2^18 edges + rows are ingested by device kernels and smaller ones on the
- * host (the default), 1 = always on the host, 2 = always on the device.  Both paths produce identical
- * index arrays. */
+/* 0 = by size (the default): a relation of at least 2^18 edges + rows is ingested by the per-relation device
+ * kernels; the smaller relations of a graph together by the whole-block device ingest when they add up
+ * to 2^16 edges + rows, else on the host.  1 = everything on the host, 2 = everything by the
+ * per-relation device kernels, 3 = small relations always by the whole-block device ingest.  All paths
+ * produce identical index arrays. */
 heta_status heta_ingest_force(int32_t mode);
 
 /* When on, every projection runs the register-staged kernel that otherwise only serves operands whose

@@ -40,12 +40,16 @@ def one_relation_graph(rel, n_src, n_dst):
     return g, heta.heta_graph_create(nts, [(0, 1, rel.rowptr, rel.col)])
 
 
-@pytest.fixture(scope="module", params=["host_ingest", "device_ingest"])
+INGEST_MODE = {"host_ingest": 1, "device_ingest": 2, "block_ingest": 3}
+
+
+@pytest.fixture(scope="module", params=["host_ingest", "device_ingest", "block_ingest"])
 def skew(request):
-    """The skewed relation, ingested once by the host path (what a relation of this size gets by
-    default) and once by the device kernels (what relations of 2^18+ edges and rows get)."""
+    """The skewed relation, ingested by the host path (what a relation of this size gets by default), by the
+    per-relation device kernels (what relations of 2^18+ edges and rows get) and by the whole-block device
+    ingest (what the relations of a sampled block of 2^16+ edges and rows get together)."""
     rel = skewed_relation()
-    heta.heta_ingest_force(1 if request.param == "host_ingest" else 2)
+    heta.heta_ingest_force(INGEST_MODE[request.param])
     g, hg = one_relation_graph(rel, 3000, 2000)
     heta.heta_ingest_force(0)
     yield rel, hg
@@ -63,7 +67,7 @@ def test_ingest_csc_and_degrees_bit_exact(skew):
     assert np.array_equal(heta.heta_graph_get_degrees(hg, 0), oracle.in_degree(src, dst, 2000))
 
 
-@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("mode", [1, 2, 3])
 def test_ingest_config1_and_device_pointers(mode):
     p = workloads.config1()
     nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in p.graph.ntypes]
@@ -89,15 +93,21 @@ def test_ingest_config1_and_device_pointers(mode):
                                 ([0] * 2000 + [1], torch.full((1,), 2000, dtype=torch.int32).cuda(), "col[0]"),
                                 ([0] * 2000 + [1], torch.full((1,), -1, dtype=torch.int32).cuda(), "col[0]")]:
         bad = [(0, 0, torch.tensor(rowptr, dtype=torch.int64).cuda(), col)]
-        with pytest.raises(heta.HetaError) as ei:
-            heta.heta_graph_create(nts, bad, flags=heta.HETA_PTRS_ON_DEVICE)
-        assert ei.value.status == heta.HETA_ERR_BAD_CSR and needle in ei.value.message, ei.value.message
+        for bad_mode in (0, 3):   # by size (this one goes to the host), and through the whole-block device ingest
+            heta.heta_ingest_force(bad_mode)
+            try:
+                with pytest.raises(heta.HetaError) as ei:
+                    heta.heta_graph_create(nts, bad, flags=heta.HETA_PTRS_ON_DEVICE)
+            finally:
+                heta.heta_ingest_force(0)
+            assert ei.value.status == heta.HETA_ERR_BAD_CSR and needle in ei.value.message, ei.value.message
 
 
-def test_device_ingest_edge_cases():
+@pytest.mark.parametrize("mode", [2, 3], ids=["device_ingest", "block_ingest"])
+def test_device_ingest_edge_cases(mode):
     """Device-built index arrays on shapes that stress the sort and the scans: no edges, one row, one
     column holding every edge, a ragged last sort tile, more tiles than one scan tile of tile counts."""
-    heta.heta_ingest_force(2)
+    heta.heta_ingest_force(mode)
     try:
         g = rng.stream("tests", "ingest-edge")
         cases = [(5, 7, 0), (1, 1, 1), (1, 9, 4097), (3, 1, 5000), (40000, 70000, 300001)]
@@ -714,7 +724,7 @@ def _reverse_pair_graph(mode):
     return p, declared, plain
 
 
-@pytest.mark.parametrize("mode", [1, 2], ids=["host_ingest", "device_ingest"])
+@pytest.mark.parametrize("mode", [1, 2, 3], ids=["host_ingest", "device_ingest", "block_ingest"])
 def test_declared_reverse_relations_share_arrays_and_give_the_same_results(mode):
     """A relation declared as the reverse of an earlier one is checked against that relation's transposed
     adjacency and (device-built) shares its arrays.  Index data read back is the oracle's for every relation;
@@ -760,7 +770,7 @@ def test_declared_reverse_relations_share_arrays_and_give_the_same_results(mode)
     plain.destroy()
 
 
-@pytest.mark.parametrize("mode", [1, 2], ids=["host_ingest", "device_ingest"])
+@pytest.mark.parametrize("mode", [1, 2, 3], ids=["host_ingest", "device_ingest", "block_ingest"])
 def test_supplied_csc_and_reverse_declarations_are_validated(mode):
     rel = skewed_relation()
     src, dst = rel.edge_list()
@@ -802,3 +812,54 @@ def test_supplied_csc_and_reverse_declarations_are_validated(mode):
         hg.destroy()
     finally:
         heta.heta_ingest_force(0)
+
+
+def test_block_ingest_of_many_relations_matches_the_host_path_bit_for_bit():
+    """A block of 12 relations over 5 node types (empty relations, relations without rows, multi-edges, a hub
+    column of more than 512 edges, a hub row): every index array the whole-block device ingest produces is
+    the host path's, read back through the public calls and through exact integer aggregations."""
+    g = rng.stream("tests", "block-ingest")
+    n_nodes = [3000, 1, 0, 700, 5000]
+    nts = [(n, 8, 0) for n in n_nodes]
+    rels, lists = [], []
+    for k, (s, t, n_e) in enumerate([(0, 3, 9000), (3, 0, 20000), (0, 0, 0), (1, 0, 2500), (0, 1, 1200), (2, 0, 0), (0, 2, 0),
+                                     (4, 4, 30000), (4, 0, 7), (3, 4, 4000), (0, 4, 15000), (3, 3, 1)]):
+        n_s, n_t = n_nodes[s], n_nodes[t]
+        dst = np.sort(g.integers(0, max(n_t, 1), size=n_e)).astype(np.int64)
+        src = g.integers(0, max(n_s, 1), size=n_e, dtype=np.int32)
+        if n_e >= 9000:
+            src[: n_e // 10] = n_s // 2                       # a hub column
+            dst[: 600] = 0                                     # a hub row (stays sorted: the smallest id)
+        rowptr = np.zeros(n_t + 1, dtype=np.int64)
+        np.add.at(rowptr, dst + 1, 1)
+        rowptr = np.cumsum(rowptr)
+        rels.append((s, t, rowptr, src))
+        lists.append((src, dst.astype(np.int32), n_s, n_t))
+    graphs = []
+    for mode in (1, 3):
+        heta.heta_ingest_force(mode)
+        try:
+            graphs.append(heta.heta_graph_create(nts, rels))
+        finally:
+            heta.heta_ingest_force(0)
+    host, block = graphs
+    for i, (src, dst, n_s, n_t) in enumerate(lists):
+        a, b = heta.heta_graph_get_csc(host, i), heta.heta_graph_get_csc(block, i)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), i
+        rc, rr = oracle.csc(src, dst, n_s)
+        assert np.array_equal(b[0], rc) and np.array_equal(b[1], rr), i
+        assert np.array_equal(heta.heta_graph_get_degrees(block, i), oracle.in_degree(src, dst, n_t)), i
+        if n_s == 0 or n_t == 0:
+            continue
+        x = rng.small_int_table(n_s, 12, -2, 2, "tests", f"blk/x/{i}")
+        gx = rng.small_int_table(n_t, 12, -2, 2, "tests", f"blk/g/{i}")
+        for hg in (host, block):
+            f = torch.full((n_t, 12), float("nan"), device="cuda")
+            bk = torch.full((n_s, 12), float("nan"), device="cuda")
+            heta.heta_rel_aggregate_fwd(hg, i, heta.HETA_SUM, dev_table(x, "f32", 4), f)
+            heta.heta_rel_aggregate_bwd(hg, i, heta.HETA_MEAN, dev_table(gx, "f32", 4), bk)
+            assert np.array_equal(f.cpu().numpy().astype(np.float64), oracle.aggregate_fwd(src, dst, n_t, x, "sum")), i
+            assert_rows_close(bk.cpu().numpy(), oracle.aggregate_bwd(src, dst, n_s, n_t, gx.astype(np.float64), "mean"), 1e-4, f"bwd {i}")
+    assert heta.heta_graph_index_bytes(host) == heta.heta_graph_index_bytes(block)
+    host.destroy()
+    block.destroy()
