@@ -166,6 +166,37 @@ heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, c
                                    heta_dtype go_dt, int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs,
                                    float beta, void *hip_stream);
 
+/* ---- several relations per launch (Algorithm 1: a worker aggregates every relation of its partition;
+ * the relation-specific aggregations of one layer are independent of each other) ------------------
+ * One item is one heta_rel_aggregate_fwd / heta_rel_aggregate_bwd call; a call with n items computes
+ * exactly what the n single calls compute (same kernels, same summation order, bitwise the same
+ * results), but items that take the same kernel (same dtype, same d, same alignment class) share
+ * launches of up to four relations.  For the small relations of a sampled mini-batch block, where a
+ * launch costs more than its work, this is the difference between n launch latencies and n / 4.
+ * The items of one call run concurrently: no two may write overlapping outputs (checked; a type that
+ * is the source of two relations takes its two backward items in two calls, beta = 0 then beta = 1).
+ *   forward : in = src_table [n_table_rows, ld_in] of in_dt, src_gid as in heta_rel_aggregate_fwd,
+ *             out [n_dst, ld_out] of out_dt
+ *   backward: in = grad_out [n_dst, ld_in] of in_dt; out = grad_src, fp32 [n_src, ld_out];
+ *             n_table_rows and src_gid are ignored
+ * items: host array, read before the call returns.  n = 0 is a no-op.  Errors as the single calls,
+ * detected before anything is launched. */
+typedef struct heta_agg_item {
+    int32_t rel;
+    int32_t d;
+    const void *in;          /* device */
+    int64_t ld_in;
+    int64_t n_table_rows;
+    const int64_t *src_gid;  /* device or NULL */
+    void *out;               /* device */
+    int64_t ld_out;
+    float beta;              /* 0 or 1 */
+} heta_agg_item;
+heta_status heta_rel_aggregate_fwd_multi(heta_graph *g, int32_t n, const heta_agg_item *items, heta_reduce op,
+                                         heta_dtype in_dt, heta_dtype out_dt, void *hip_stream);
+heta_status heta_rel_aggregate_bwd_multi(heta_graph *g, int32_t n, const heta_agg_item *items, heta_reduce op,
+                                         heta_dtype in_dt, void *hip_stream);
+
 /* ---- per-relation projection (the per-relation weight matrices of R-GCN, Section 2.1) ---------
  * out[i, 0:d_out] = beta * out[i, 0:d_out] + s_i * sum_k in[i, k] * B[k, j],  i < n_rows,
  *   B = W          (W is [d_in, d_out], ld_w >= d_out)   when transW == 0     (forward,  Z = M W)

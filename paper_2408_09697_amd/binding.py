@@ -25,6 +25,7 @@ HETA_PTRS_ON_DEVICE = 1
 
 EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "heta_graph_get_degrees",
            "heta_feature_gather", "heta_check_ids", "heta_rel_aggregate_fwd", "heta_rel_aggregate_bwd",
+           "heta_rel_aggregate_fwd_multi", "heta_rel_aggregate_bwd_multi",
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
@@ -56,6 +57,12 @@ class _Relation(ctypes.Structure):
                 ("csc_colptr", ctypes.c_void_p), ("csc_row", ctypes.c_void_p), ("reverse_of", ctypes.c_int32)]
 
 
+class _AggItem(ctypes.Structure):
+    _fields_ = [("rel", ctypes.c_int32), ("d", ctypes.c_int32), ("inp", ctypes.c_void_p), ("ld_in", ctypes.c_int64),
+                ("n_table_rows", ctypes.c_int64), ("src_gid", ctypes.c_void_p), ("out", ctypes.c_void_p),
+                ("ld_out", ctypes.c_int64), ("beta", ctypes.c_float)]
+
+
 _lib = None
 
 
@@ -78,6 +85,8 @@ def load_library() -> ctypes.CDLL:
     L.heta_rel_aggregate_fwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, i64, vp, vp, i32, i64, f32, vp]
     L.heta_rel_aggregate_fwd_noalloc.argtypes = L.heta_rel_aggregate_fwd.argtypes
     L.heta_rel_aggregate_bwd.argtypes = [vp, i32, i32, vp, i32, i64, i32, vp, i64, f32, vp]
+    L.heta_rel_aggregate_fwd_multi.argtypes = [vp, i32, ctypes.POINTER(_AggItem), i32, i32, i32, vp]
+    L.heta_rel_aggregate_bwd_multi.argtypes = [vp, i32, ctypes.POINTER(_AggItem), i32, i32, vp]
     L.heta_project.argtypes = [i64, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i32, i64, f32, vp]
     L.heta_rel_project.argtypes = [vp, i32, vp, i32, i64, i32, vp, i32, i64, i32, i32, vp, vp, i32, i64, f32, vp]
     L.heta_rel_project_wgrad.argtypes = [vp, i32, vp, i32, i64, i32, vp, i64, i32, vp, i64, f32, vp]
@@ -297,6 +306,56 @@ def heta_rel_aggregate_bwd(g: Graph, rel: int, op: int, grad_out: torch.Tensor, 
         g.handle, rel, op, _dev(grad_out, "grad_out"), _dt(grad_out), _ld(grad_out), d,
         _dev(grad_src, "grad_src", torch.float32), _ld(grad_src), beta, _stream(stream)))
     return grad_src
+
+
+def heta_rel_aggregate_fwd_multi(g: Graph, rels: Sequence[int], op: int, src_tables: Sequence[torch.Tensor],
+                                 outs: Sequence[torch.Tensor], d: Optional[Sequence[int]] = None,
+                                 src_gids: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                                 betas: Optional[Sequence[float]] = None, stream=None) -> None:
+    """heta_rel_aggregate_fwd for several relations at once (relations of equal shape class share launches)."""
+    n = len(rels)
+    if n == 0:
+        return
+    items = (_AggItem * n)()
+    for i, r in enumerate(rels):
+        x, o = src_tables[i], outs[i]
+        gid = None if src_gids is None else src_gids[i]
+        if o.shape[0] < g.n_dst(r):
+            raise HetaError(HETA_ERR_SHAPE, "out has fewer rows than the relation has destinations")
+        if gid is not None and gid.numel() < g.n_src(r):
+            raise HetaError(HETA_ERR_SHAPE, "src_gid has fewer entries than the relation has sources")
+        if x.dtype != src_tables[0].dtype or o.dtype != outs[0].dtype:
+            raise HetaError(HETA_ERR_INVALID_ARG, "the items of one call share their element types")
+        it = items[i]
+        it.rel, it.d = r, (x.shape[1] if d is None else d[i])
+        it.inp, it.ld_in, it.n_table_rows = _dev(x, "src_table"), _ld(x), x.shape[0]
+        it.src_gid = _dev(gid, "src_gid", torch.int64)
+        it.out, it.ld_out = _dev(o, "out"), _ld(o)
+        it.beta = 0.0 if betas is None else betas[i]
+    _check(load_library().heta_rel_aggregate_fwd_multi(g.handle, n, items, op, _dt(src_tables[0]), _dt(outs[0]),
+                                                       _stream(stream)))
+
+
+def heta_rel_aggregate_bwd_multi(g: Graph, rels: Sequence[int], op: int, grad_outs: Sequence[torch.Tensor],
+                                 grad_srcs: Sequence[torch.Tensor], betas: Optional[Sequence[float]] = None,
+                                 d: Optional[Sequence[int]] = None, stream=None) -> None:
+    """heta_rel_aggregate_bwd for several relations at once; no two items may share a grad_src."""
+    n = len(rels)
+    if n == 0:
+        return
+    items = (_AggItem * n)()
+    for i, r in enumerate(rels):
+        x, o = grad_outs[i], grad_srcs[i]
+        if x.shape[0] < g.n_dst(r) or o.shape[0] < g.n_src(r):
+            raise HetaError(HETA_ERR_SHAPE, "gradient buffers have fewer rows than the relation needs")
+        if x.dtype != grad_outs[0].dtype:
+            raise HetaError(HETA_ERR_INVALID_ARG, "the items of one call share their element types")
+        it = items[i]
+        it.rel, it.d = r, (x.shape[1] if d is None else d[i])
+        it.inp, it.ld_in, it.n_table_rows, it.src_gid = _dev(x, "grad_out"), _ld(x), 0, None
+        it.out, it.ld_out = _dev(o, "grad_src", torch.float32), _ld(o)
+        it.beta = 0.0 if betas is None else betas[i]
+    _check(load_library().heta_rel_aggregate_bwd_multi(g.handle, n, items, op, _dt(grad_outs[0]), _stream(stream)))
 
 
 def _w_ld(W: torch.Tensor) -> int:

@@ -34,6 +34,8 @@
 //     broadcast with lane shuffles.
 #include <algorithm>
 #include <mutex>
+#include <utility>
+#include <vector>
 
 #include "heta_internal.h"
 
@@ -227,7 +229,7 @@ __host__ __device__ inline int batch_rows(int k, int G)
 }
 
 template <typename T, int EPC, int L, int CPL, bool DUAL>
-__global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
+__device__ __forceinline__ void agg_batch_body(const AggParams &p)
 {
     constexpr int G = 64 / L;          // lane groups = rows in progress per wavefront
     constexpr int U = CPL == 1 ? 8 : 4; // row loads in flight per lane group
@@ -370,7 +372,7 @@ __global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p)
 
 // ---- long rows and hub chunks: one wavefront per item ----------------------------------------------
 template <typename T, int EPC, int L, int CPL, bool DUAL>
-__global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
+__device__ __forceinline__ void agg_wave_body(const AggParams &p)
 {
     constexpr int G = 64 / L;            // lane groups per wavefront
     constexpr int U = CPL == 2 ? 4 : ((G >= 16) ? 1 : ((G >= 8) ? 2 : ((G >= 4) ? 4 : 8))); // edges in flight per group and step
@@ -492,11 +494,12 @@ __global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p)
 // w, w+16, w+32, ... (four loads in flight) and the sixteen sums are combined through LDS in
 // wavefront order, so the summation order is fixed.
 constexpr int kCombineWaves = 16;
-__global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_kernel(AggParams p)
+__device__ __forceinline__ void agg_hub_combine_body(const AggParams &p)
 {
     __shared__ float4 part[kCombineWaves][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t h = blockIdx.x;
+    if (h >= p.n_hub_rows) return; // whole workgroup (a launch over several relations is as wide as the widest)
     const int64_t row = p.hub_only ? h : p.perm[h];
     const int64_t s0 = p.hub_chunk_ptr[h], s1 = p.hub_chunk_ptr[h + 1];
     const int col0 = (blockIdx.y * 64 + lane) * 4;
@@ -527,6 +530,28 @@ __global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_kernel(Agg
     store_out<4>(p, row, col0, acc, scale);
 }
 
+// The kernels proper.  The single-relation forms take the parameters of their relation; the multi forms
+// take up to kAggMulti parameter blocks and blockIdx.z picks one, so that the small relations of a
+// sampled mini-batch block share one launch (and one launch latency) instead of queueing behind each
+// other.  Every body guards its own item count, so a grid as wide as the widest relation is safe.
+constexpr int kAggMulti = 4;
+struct AggMulti {
+    AggParams p[kAggMulti];
+};
+static_assert(sizeof(AggMulti) <= 3584, "kernel arguments are limited to 4 KB");
+
+template <typename T, int EPC, int L, int CPL, bool DUAL>
+__global__ void __launch_bounds__(256) agg_batch_kernel(AggParams p) { agg_batch_body<T, EPC, L, CPL, DUAL>(p); }
+template <typename T, int EPC, int L, int CPL, bool DUAL>
+__global__ void __launch_bounds__(256) agg_wave_kernel(AggParams p) { agg_wave_body<T, EPC, L, CPL, DUAL>(p); }
+__global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_kernel(AggParams p) { agg_hub_combine_body(p); }
+
+template <typename T, int EPC, int L, int CPL, bool DUAL>
+__global__ void __launch_bounds__(256) agg_batch_multi_kernel(AggMulti m) { agg_batch_body<T, EPC, L, CPL, DUAL>(m.p[blockIdx.z]); }
+template <typename T, int EPC, int L, int CPL, bool DUAL>
+__global__ void __launch_bounds__(256) agg_wave_multi_kernel(AggMulti m) { agg_wave_body<T, EPC, L, CPL, DUAL>(m.p[blockIdx.z]); }
+__global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_multi_kernel(AggMulti m) { agg_hub_combine_body(m.p[blockIdx.z]); }
+
 // ---- launch ---------------------------------------------------------------------------------------
 // algorithmic bytes of the two row classes of one call (for the optional profiler)
 struct AggCost {
@@ -535,67 +560,83 @@ struct AggCost {
 };
 
 template <typename T, int EPC, int L, int CPL, bool DUAL = false>
-static heta_status launch_pair(const AggParams &p, int n_super, hipStream_t st, const AggCost &cost)
+static heta_status launch_pair(const AggParams *ps, int n, int n_super, hipStream_t st, const AggCost &cost)
 {
     if constexpr (!DUAL && EPC > 1) { // the two-weight form exists for the 128-bit paths
-        if (p.slot_w2) return launch_pair<T, EPC, L, CPL, true>(p, n_super, st, cost);
+        if (ps[0].slot_w2) return launch_pair<T, EPC, L, CPL, true>(ps, n, n_super, st, cost);
     }
-    if (p.n_wave_items > 0) {
-        const int64_t blocks = (p.n_wave_items + 3) / 4;
-        if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many long rows");
+    int64_t wave_blocks = 0, batch_blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        wave_blocks = std::max<int64_t>(wave_blocks, (ps[i].n_wave_items + 3) / 4);
+        batch_blocks = std::max<int64_t>(batch_blocks, (ps[i].batch0[kShortDeg] + 3) / 4);
+    }
+    if (wave_blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many long rows");
+    AggMulti m{};
+    if (n > 1)
+        for (int i = 0; i < n; ++i) m.p[i] = ps[i];
+    if (wave_blocks > 0) {
         ProfScope prof(cost.timed ? "agg_wave_kernel" : nullptr, st, cost.wave_bytes, 0);
-        hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)blocks, n_super), dim3(256), 0, st, p);
+        if (n == 1)
+            hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)wave_blocks, n_super), dim3(256), 0, st, ps[0]);
+        else
+            hipLaunchKernelGGL((agg_wave_multi_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)wave_blocks, n_super, n), dim3(256), 0, st, m);
         HETA_LAUNCH_CHECK("agg_wave_kernel");
     }
-    const int n_batches = p.batch0[kShortDeg];
-    if (n_batches > 0) {
+    if (batch_blocks > 0) {
         ProfScope prof(cost.timed ? "agg_batch_kernel" : nullptr, st, cost.group_bytes, 0);
-        hipLaunchKernelGGL((agg_batch_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)((n_batches + 3) / 4), n_super), dim3(256), 0, st, p);
+        if (n == 1)
+            hipLaunchKernelGGL((agg_batch_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)batch_blocks, n_super), dim3(256), 0, st, ps[0]);
+        else
+            hipLaunchKernelGGL((agg_batch_multi_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)batch_blocks, n_super, n), dim3(256), 0, st, m);
         HETA_LAUNCH_CHECK("agg_batch_kernel");
     }
     return HETA_OK;
 }
 
 template <typename T, int EPC>
-static heta_status launch_vec(const AggParams &p, int n_chunks, hipStream_t st, const AggCost &c)
+static heta_status launch_vec(const AggParams *ps, int n, int n_chunks, hipStream_t st, const AggCost &c)
 {
-    if (n_chunks <= 1) return launch_pair<T, EPC, 1, 1>(p, 1, st, c);
-    if (n_chunks <= 2) return launch_pair<T, EPC, 2, 1>(p, 1, st, c);
-    if (n_chunks <= 4) return launch_pair<T, EPC, 4, 1>(p, 1, st, c);
-    if (n_chunks <= 8) return launch_pair<T, EPC, 8, 1>(p, 1, st, c);
-    if (n_chunks <= 16) return launch_pair<T, EPC, 16, 1>(p, 1, st, c);
-    if (n_chunks <= 32) return launch_pair<T, EPC, 32, 1>(p, 1, st, c);
-    if (n_chunks <= 64) return launch_pair<T, EPC, 64, 1>(p, 1, st, c);
-    return launch_pair<T, EPC, 64, 2>(p, (n_chunks + 127) / 128, st, c);
+    if (n_chunks <= 1) return launch_pair<T, EPC, 1, 1>(ps, n, 1, st, c);
+    if (n_chunks <= 2) return launch_pair<T, EPC, 2, 1>(ps, n, 1, st, c);
+    if (n_chunks <= 4) return launch_pair<T, EPC, 4, 1>(ps, n, 1, st, c);
+    if (n_chunks <= 8) return launch_pair<T, EPC, 8, 1>(ps, n, 1, st, c);
+    if (n_chunks <= 16) return launch_pair<T, EPC, 16, 1>(ps, n, 1, st, c);
+    if (n_chunks <= 32) return launch_pair<T, EPC, 32, 1>(ps, n, 1, st, c);
+    if (n_chunks <= 64) return launch_pair<T, EPC, 64, 1>(ps, n, 1, st, c);
+    return launch_pair<T, EPC, 64, 2>(ps, n, (n_chunks + 127) / 128, st, c);
 }
 
-// The shared entry of forward and backward.  With fixed_ws the hub partials go to that buffer of
-// fixed_ws_bytes instead of the handle's grow-on-demand workspace, and nothing is allocated: a shape
-// that does not fit is an error, and the launches are not bracketed by profiling events.
-static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, heta_dtype in_dt,
-                                 int64_t table_elems_ld, hipStream_t st, float *fixed_ws = nullptr,
-                                 size_t fixed_ws_bytes = 0)
+// Everything about one aggregation that the host decides before a launch: the filled-in kernel
+// parameters (all but the address of the hub partials), the kernel family it takes, the bytes of hub
+// partials it needs and its algorithmic bytes.
+struct AggPlan {
+    AggParams p;
+    heta_dtype in_dt = HETA_F32;
+    bool vec = false, dual = false;
+    int n_chunks = 0;
+    size_t ws_need = 0;
+    AggCost cost;
+    double hub_bytes = 0;
+    int64_t n_hub_rows = 0;
+    // relations with equal keys run the same kernel instantiation with the same grid.y
+    int key() const { return (in_dt == HETA_F32 ? 0 : 1) | (vec ? 2 : 0) | (dual ? 4 : 0) | (n_chunks << 3); }
+};
+
+static bool agg_vectorized(const AggParams &p, heta_dtype in_dt)
 {
-    (void)table_elems_ld;
-    if (s.n_rows == 0) return HETA_OK;
     const size_t esz = dtype_size(in_dt);
     // with per-head weights a lane's chunk must not straddle two heads
-    const bool vec = aligned16(p.table) && ((p.ld * esz) % 16 == 0) &&
-                     (!p.slot_w || p.head_dim % static_cast<int>(16 / esz) == 0);
-    if (p.slot_w2 && !vec) { // the two-weight kernels exist for the 128-bit paths only: two passes otherwise
-        AggParams a = p, b = p;
-        a.slot_w2 = nullptr;
-        b.slot_w = p.slot_w2;
-        b.slot_w2 = nullptr;
-        b.out = p.out2;
-        b.ld_out = p.ld_out2;
-        heta_status e1 = run_aggregate(g, s, a, in_dt, table_elems_ld, st);
-        return e1 != HETA_OK ? e1 : run_aggregate(g, s, b, in_dt, table_elems_ld, st);
-    }
+    return aligned16(p.table) && ((p.ld * esz) % 16 == 0) && (!p.slot_w || p.head_dim % static_cast<int>(16 / esz) == 0);
+}
+
+static heta_status plan_aggregate(const Schedule &s, AggParams p, heta_dtype in_dt, AggPlan *plan)
+{
+    const size_t esz = dtype_size(in_dt);
+    const bool vec = agg_vectorized(p, in_dt);
     const bool dual = p.slot_w2 != nullptr;
     const int epc = vec ? static_cast<int>(16 / esz) : 1;
     const int n_chunks = (p.d + epc - 1) / epc;
-    int L = 64; // lanes per row, as the dispatch below picks them
+    int L = 64; // lanes per row, as the dispatch picks them
     if (vec) {
         L = 1;
         while (L < n_chunks && L < 64) L <<= 1;
@@ -629,53 +670,142 @@ static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, 
     p.ws_ld = (static_cast<int64_t>(p.d) + 7) / 8 * 8;
     p.ws_stride = dual ? 2 * p.ws_ld : p.ws_ld;
     p.ws = nullptr;
-    if (s.n_hub_chunks > 0) {
-        const size_t need = static_cast<size_t>(s.n_hub_chunks) * p.ws_stride * sizeof(float);
-        if (fixed_ws) {
-            if (need > fixed_ws_bytes)
-                return fail(HETA_ERR_UNSUPPORTED,
-                            "aggregate: %lld hub chunks of %d columns need %zu bytes of partial sums, the fixed scratch "
-                            "holds %zu; use the allocating entry point",
-                            (long long)s.n_hub_chunks, p.d, need, fixed_ws_bytes);
-            p.ws = fixed_ws;
-        } else {
-            heta_status e = ensure_workspace(g, need);
-            if (e != HETA_OK) return e;
-            p.ws = static_cast<float *>(g->d_ws);
-        }
-    }
+    if (s.n_hub_rows > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many hub rows");
+    plan->ws_need = static_cast<size_t>(s.n_hub_chunks) * p.ws_stride * sizeof(float);
     // Algorithmic bytes per row class: one neighbour row and one 4-byte index per edge, one 8-byte
     // row pointer and one output row per row.  Hub rows' outputs are written by the combine kernel.
-    AggCost cost;
-    cost.timed = fixed_ws == nullptr;
     const double osz = p.out_bf16 ? 2.0 : 4.0;
     const double per_edge = static_cast<double>(p.d) * esz + 4.0 + (p.slot_w ? 4.0 * p.heads : 0.0) + (dual ? 4.0 * p.heads : 0.0);
     const double per_row = 8.0 + p.d * osz * (dual ? 2.0 : 1.0);
     const double e_wave = static_cast<double>(s.edges_with_deg_ge[wave_min]);
     const double r_long = static_cast<double>(n_long_or_hub - s.n_hub_rows);
-    cost.wave_bytes = e_wave * per_edge + r_long * per_row;
-    cost.group_bytes = (static_cast<double>(s.n_edges) - e_wave) * per_edge +
-                       static_cast<double>(s.n_rows - n_long_or_hub) * per_row;
+    plan->cost.wave_bytes = e_wave * per_edge + r_long * per_row;
+    plan->cost.group_bytes = (static_cast<double>(s.n_edges) - e_wave) * per_edge +
+                             static_cast<double>(s.n_rows - n_long_or_hub) * per_row;
+    plan->hub_bytes = static_cast<double>(s.n_hub_rows) * per_row;
+    plan->n_hub_rows = s.n_hub_rows;
+    plan->p = p;
+    plan->in_dt = in_dt;
+    plan->vec = vec;
+    plan->dual = dual;
+    plan->n_chunks = n_chunks;
+    return HETA_OK;
+}
+
+// Launches n planned aggregations of one key (n = 1: the single-relation kernels) whose hub partial
+// addresses are set.
+static heta_status launch_plans(const AggPlan *plans, int n, hipStream_t st, bool timed)
+{
+    AggParams ps[kAggMulti];
+    AggCost cost;
+    cost.timed = timed;
+    double hub_bytes = 0;
+    int64_t hub_rows = 0;
+    for (int i = 0; i < n; ++i) {
+        ps[i] = plans[i].p;
+        cost.wave_bytes += plans[i].cost.wave_bytes;
+        cost.group_bytes += plans[i].cost.group_bytes;
+        hub_bytes += plans[i].hub_bytes;
+        hub_rows = std::max(hub_rows, plans[i].n_hub_rows);
+    }
+    const AggPlan &f = plans[0];
     heta_status e;
-    if (in_dt == HETA_F32)
-        e = vec ? launch_vec<float, 4>(p, n_chunks, st, cost) : launch_pair<float, 1, 64, 2>(p, (n_chunks + 127) / 128, st, cost);
+    if (f.in_dt == HETA_F32)
+        e = f.vec ? launch_vec<float, 4>(ps, n, f.n_chunks, st, cost) : launch_pair<float, 1, 64, 2>(ps, n, (f.n_chunks + 127) / 128, st, cost);
     else
-        e = vec ? launch_vec<bf16_t, 8>(p, n_chunks, st, cost) : launch_pair<bf16_t, 1, 64, 2>(p, (n_chunks + 127) / 128, st, cost);
+        e = f.vec ? launch_vec<bf16_t, 8>(ps, n, f.n_chunks, st, cost) : launch_pair<bf16_t, 1, 64, 2>(ps, n, (f.n_chunks + 127) / 128, st, cost);
     if (e != HETA_OK) return e;
-    if (s.n_hub_rows > 0) {
-        if (s.n_hub_rows > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many hub rows");
-        const int tiles = static_cast<int>((p.ws_ld + 255) / 256);
-        ProfScope prof(cost.timed ? "agg_hub_combine_kernel" : nullptr, st, static_cast<double>(s.n_hub_rows) * per_row, 0);
-        hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, p);
-        HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
-        if (dual) {
-            AggParams p2 = p;
-            p2.ws = p.ws + p.ws_ld;
-            p2.out = p.out2;
-            p2.ld_out = p.ld_out2;
-            hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)s.n_hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, p2);
+    if (hub_rows > 0) {
+        const int tiles = static_cast<int>((f.p.ws_ld + 255) / 256);
+        ProfScope prof(timed ? "agg_hub_combine_kernel" : nullptr, st, hub_bytes, 0);
+        if (n == 1) {
+            hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, ps[0]);
+            HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
+            if (f.dual) {
+                AggParams p2 = ps[0];
+                p2.ws = ps[0].ws + ps[0].ws_ld;
+                p2.out = ps[0].out2;
+                p2.ld_out = ps[0].ld_out2;
+                hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, p2);
+                HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
+            }
+        } else {
+            AggMulti m{};
+            for (int i = 0; i < n; ++i) m.p[i] = ps[i];
+            hipLaunchKernelGGL(agg_hub_combine_multi_kernel, dim3((unsigned)hub_rows, tiles, n), dim3(64 * kCombineWaves), 0, st, m);
             HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
         }
+    }
+    return HETA_OK;
+}
+
+// The shared entry of forward and backward.  With fixed_ws the hub partials go to that buffer of
+// fixed_ws_bytes instead of the handle's grow-on-demand workspace, and nothing is allocated: a shape
+// that does not fit is an error, and the launches are not bracketed by profiling events.
+static heta_status run_aggregate(heta_graph *g, const Schedule &s, AggParams p, heta_dtype in_dt,
+                                 int64_t table_elems_ld, hipStream_t st, float *fixed_ws = nullptr,
+                                 size_t fixed_ws_bytes = 0)
+{
+    (void)table_elems_ld;
+    if (s.n_rows == 0) return HETA_OK;
+    if (p.slot_w2 && !agg_vectorized(p, in_dt)) { // the two-weight kernels exist for the 128-bit paths only: two passes otherwise
+        AggParams a = p, b = p;
+        a.slot_w2 = nullptr;
+        b.slot_w = p.slot_w2;
+        b.slot_w2 = nullptr;
+        b.out = p.out2;
+        b.ld_out = p.ld_out2;
+        heta_status e1 = run_aggregate(g, s, a, in_dt, table_elems_ld, st);
+        return e1 != HETA_OK ? e1 : run_aggregate(g, s, b, in_dt, table_elems_ld, st);
+    }
+    AggPlan plan;
+    heta_status e = plan_aggregate(s, p, in_dt, &plan);
+    if (e != HETA_OK) return e;
+    if (plan.ws_need > 0) {
+        if (fixed_ws) {
+            if (plan.ws_need > fixed_ws_bytes)
+                return fail(HETA_ERR_UNSUPPORTED,
+                            "aggregate: %lld hub chunks of %d columns need %zu bytes of partial sums, the fixed scratch "
+                            "holds %zu; use the allocating entry point",
+                            (long long)s.n_hub_chunks, p.d, plan.ws_need, fixed_ws_bytes);
+            plan.p.ws = fixed_ws;
+        } else {
+            e = ensure_workspace(g, plan.ws_need);
+            if (e != HETA_OK) return e;
+            plan.p.ws = static_cast<float *>(g->d_ws);
+        }
+    }
+    return launch_plans(&plan, 1, st, fixed_ws == nullptr);
+}
+
+// Several independent aggregations (no two write the same output) in as few launches as their kernel
+// families allow: plans of one key share launches of up to kAggMulti relations, each with a region of
+// its own in the hub-partial workspace.
+static heta_status run_aggregate_multi(heta_graph *g, std::vector<AggPlan> &plans, hipStream_t st)
+{
+    size_t total = 0;
+    for (const AggPlan &pl : plans) total += (pl.ws_need + 255) / 256 * 256;
+    if (total > 0) {
+        heta_status e = ensure_workspace(g, total);
+        if (e != HETA_OK) return e;
+        size_t off = 0;
+        for (AggPlan &pl : plans) {
+            if (pl.ws_need > 0) pl.p.ws = reinterpret_cast<float *>(static_cast<char *>(g->d_ws) + off);
+            off += (pl.ws_need + 255) / 256 * 256;
+        }
+    }
+    std::vector<char> done(plans.size(), 0);
+    for (size_t i = 0; i < plans.size(); ++i) {
+        if (done[i]) continue;
+        AggPlan group[kAggMulti];
+        int n = 0;
+        for (size_t j = i; j < plans.size() && n < kAggMulti; ++j)
+            if (!done[j] && plans[j].key() == plans[i].key()) {
+                group[n++] = plans[j];
+                done[j] = 1;
+            }
+        heta_status e = launch_plans(group, n, st, true);
+        if (e != HETA_OK) return e;
     }
     return HETA_OK;
 }
@@ -821,6 +951,39 @@ static AggParams fwd_params(heta_reduce op, const void *src_table, int64_t ld_sr
     return p;
 }
 
+static heta_status check_bwd_args(const char *fn, heta_graph *g, int32_t rel, heta_reduce op, const void *grad_out,
+                                  heta_dtype go_dt, int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs, float beta)
+{
+    if (!g || !grad_out || !grad_src) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", fn);
+    if (rel < 0 || rel >= (int32_t)g->rels.size()) return fail(HETA_ERR_INVALID_ARG, "%s: relation %d out of range", fn, rel);
+    if (op != HETA_SUM && op != HETA_MEAN) return fail(HETA_ERR_INVALID_ARG, "%s: bad reduce op", fn);
+    if (!valid_dtype(go_dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", fn);
+    if (d <= 0 || ld_go < d || ld_gs < d)
+        return fail(HETA_ERR_SHAPE, "%s: need 0 < d <= ld (d=%d ld_go=%lld ld_gs=%lld)", fn, d, (long long)ld_go,
+                    (long long)ld_gs);
+    if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "%s: beta must be 0 or 1", fn);
+    if ((reinterpret_cast<uintptr_t>(grad_out) % dtype_size(go_dt)) || (reinterpret_cast<uintptr_t>(grad_src) & 3u))
+        return fail(HETA_ERR_INVALID_ARG, "%s: pointer not aligned to its element size", fn);
+    return HETA_OK;
+}
+
+static AggParams bwd_params(const Relation &r, heta_reduce op, const void *grad_out, int64_t ld_go, int32_t d,
+                            float *grad_src, int64_t ld_gs, float beta)
+{
+    AggParams p{};
+    p.table = grad_out;
+    p.ld = ld_go;
+    p.gid = nullptr;
+    p.edge_w = (op == HETA_MEAN) ? r.d_inv_deg : nullptr;
+    p.mean = 0;
+    p.out = grad_src;
+    p.ld_out = ld_gs;
+    p.out_bf16 = 0;
+    p.beta = beta;
+    p.d = d;
+    return p;
+}
+
 extern "C" {
 
 heta_status heta_rel_aggregate_fwd(heta_graph *g, int32_t rel, heta_reduce op, const void *src_table,
@@ -856,30 +1019,93 @@ heta_status heta_rel_aggregate_bwd(heta_graph *g, int32_t rel, heta_reduce op, c
                                    heta_dtype go_dt, int64_t ld_go, int32_t d, float *grad_src, int64_t ld_gs,
                                    float beta, void *hip_stream)
 {
-    if (!g || !grad_out || !grad_src) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: null argument");
-    if (rel < 0 || rel >= (int32_t)g->rels.size())
-        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: relation %d out of range", rel);
-    if (op != HETA_SUM && op != HETA_MEAN) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: bad reduce op");
-    if (!valid_dtype(go_dt)) return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: bad dtype");
-    if (d <= 0 || ld_go < d || ld_gs < d)
-        return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_bwd: need 0 < d <= ld (d=%d ld_go=%lld ld_gs=%lld)", d,
-                    (long long)ld_go, (long long)ld_gs);
-    if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "heta_rel_aggregate_bwd: beta must be 0 or 1");
-    if ((reinterpret_cast<uintptr_t>(grad_out) % dtype_size(go_dt)) || (reinterpret_cast<uintptr_t>(grad_src) & 3u))
-        return fail(HETA_ERR_INVALID_ARG, "heta_rel_aggregate_bwd: pointer not aligned to its element size");
+    heta_status e = check_bwd_args("heta_rel_aggregate_bwd", g, rel, op, grad_out, go_dt, ld_go, d, grad_src, ld_gs, beta);
+    if (e != HETA_OK) return e;
     const Relation &r = g->rels[rel];
-    AggParams p{};
-    p.table = grad_out;
-    p.ld = ld_go;
-    p.gid = nullptr;
-    p.edge_w = (op == HETA_MEAN) ? r.d_inv_deg : nullptr;
-    p.mean = 0;
-    p.out = grad_src;
-    p.ld_out = ld_gs;
-    p.out_bf16 = 0;
-    p.beta = beta;
-    p.d = d;
-    return run_aggregate(g, r.csc, p, go_dt, ld_go, as_stream(hip_stream));
+    return run_aggregate(g, r.csc, bwd_params(r, op, grad_out, ld_go, d, grad_src, ld_gs, beta), go_dt, ld_go,
+                         as_stream(hip_stream));
+}
+
+// Byte ranges [lo, hi) of the outputs of the items of one multi call must not overlap.
+static heta_status check_disjoint(const char *fn, const std::vector<std::pair<uintptr_t, uintptr_t>> &ranges)
+{
+    for (size_t i = 0; i < ranges.size(); ++i)
+        for (size_t j = i + 1; j < ranges.size(); ++j)
+            if (ranges[i].first < ranges[j].second && ranges[j].first < ranges[i].second)
+                return fail(HETA_ERR_INVALID_ARG, "%s: the outputs of items %zu and %zu overlap", fn, i, j);
+    return HETA_OK;
+}
+
+static std::pair<uintptr_t, uintptr_t> out_range(const void *out, int64_t rows, int64_t ld, int32_t d, size_t esz)
+{
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(out);
+    return {lo, rows > 0 ? lo + static_cast<uintptr_t>(((rows - 1) * ld + d) * static_cast<int64_t>(esz)) : lo};
+}
+
+heta_status heta_rel_aggregate_fwd_multi(heta_graph *g, int32_t n, const heta_agg_item *items, heta_reduce op,
+                                         heta_dtype in_dt, heta_dtype out_dt, void *hip_stream)
+{
+    const char *fn = "heta_rel_aggregate_fwd_multi";
+    if (n < 0 || (n > 0 && !items)) return fail(HETA_ERR_INVALID_ARG, "%s: bad item array", fn);
+    if (n == 0) return HETA_OK;
+    try {
+        std::vector<AggPlan> plans;
+        std::vector<std::pair<uintptr_t, uintptr_t>> ranges;
+        for (int32_t i = 0; i < n; ++i) {
+            const heta_agg_item &it = items[i];
+            heta_status e = check_fwd_args(fn, g, it.rel, op, it.in, in_dt, it.ld_in, it.d, it.n_table_rows, it.src_gid,
+                                           it.out, out_dt, it.ld_out, it.beta);
+            if (e != HETA_OK) return e;
+            const Relation &r = g->rels[it.rel];
+            ranges.push_back(out_range(it.out, r.n_dst, it.ld_out, it.d, dtype_size(out_dt)));
+            if (r.csr.n_rows == 0) continue;
+            AggPlan pl;
+            e = plan_aggregate(r.csr, fwd_params(op, it.in, it.ld_in, it.d, it.src_gid, it.out, out_dt, it.ld_out, it.beta),
+                               in_dt, &pl);
+            if (e != HETA_OK) return e;
+            plans.push_back(pl);
+        }
+        heta_status e = check_disjoint(fn, ranges);
+        if (e != HETA_OK) return e;
+        return run_aggregate_multi(g, plans, as_stream(hip_stream));
+    } catch (const std::bad_alloc &) {
+        return fail(HETA_ERR_OOM, "%s: host allocation failed", fn);
+    } catch (...) {
+        return fail(HETA_ERR_DEVICE, "%s: unexpected exception", fn);
+    }
+}
+
+heta_status heta_rel_aggregate_bwd_multi(heta_graph *g, int32_t n, const heta_agg_item *items, heta_reduce op,
+                                         heta_dtype in_dt, void *hip_stream)
+{
+    const char *fn = "heta_rel_aggregate_bwd_multi";
+    if (n < 0 || (n > 0 && !items)) return fail(HETA_ERR_INVALID_ARG, "%s: bad item array", fn);
+    if (n == 0) return HETA_OK;
+    try {
+        std::vector<AggPlan> plans;
+        std::vector<std::pair<uintptr_t, uintptr_t>> ranges;
+        for (int32_t i = 0; i < n; ++i) {
+            const heta_agg_item &it = items[i];
+            heta_status e = check_bwd_args(fn, g, it.rel, op, it.in, in_dt, it.ld_in, it.d, static_cast<float *>(it.out),
+                                           it.ld_out, it.beta);
+            if (e != HETA_OK) return e;
+            const Relation &r = g->rels[it.rel];
+            ranges.push_back(out_range(it.out, r.n_src, it.ld_out, it.d, sizeof(float)));
+            if (r.csc.n_rows == 0) continue;
+            AggPlan pl;
+            e = plan_aggregate(r.csc, bwd_params(r, op, it.in, it.ld_in, it.d, static_cast<float *>(it.out), it.ld_out, it.beta),
+                               in_dt, &pl);
+            if (e != HETA_OK) return e;
+            plans.push_back(pl);
+        }
+        heta_status e = check_disjoint(fn, ranges);
+        if (e != HETA_OK) return e;
+        return run_aggregate_multi(g, plans, as_stream(hip_stream));
+    } catch (const std::bad_alloc &) {
+        return fail(HETA_ERR_OOM, "%s: host allocation failed", fn);
+    } catch (...) {
+        return fail(HETA_ERR_DEVICE, "%s: unexpected exception", fn);
+    }
 }
 
 heta_status heta_feature_gather(const void *table, heta_dtype dt, int64_t ld_table, int32_t d,

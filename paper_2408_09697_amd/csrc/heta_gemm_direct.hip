@@ -690,7 +690,28 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         const int64_t outer = p.partial ? std::max(1, p.n_split) : mt;
         if (outer * inner <= 128) wide = false;
     }
+    // Fewer than a hundred 128 x 128 tiles (the projections of a sampled mini-batch block: a few thousand rows):
+    // every tile is a serial chain of MFMAs on one CU while most CUs idle.  64 x 64 tiles (four wavefronts of one
+    // accumulator each) cut the chain to a quarter and put four times as many CUs to work.
+    bool small = false;
+    if (!p.partial) {
+        int64_t mt = 0, nt = 0;
+        for (int s = 0; s < p.n_seg; ++s) {
+            mt = std::max(mt, (p.seg[s].M + 127) / 128);
+            nt = std::max(nt, (p.seg[s].N + 127) / 128);
+        }
+        small = mt * nt * (p.batch ? p.n_seg : 1) <= 96;
+    }
     *handled = true;
+    if (small) {
+        if (a_dt == HETA_F32 && b_dt == HETA_F32 && !a_rc)
+            return b_rc ? launch_direct<float, float, false, true, float, true, true, 2, 16, 3, 4, false, 1, 1, 2>(p, st, name, bytes, flops)
+                        : launch_direct<float, float, false, true, float, false, true, 2, 16, 3, 4, false, 1, 1, 2>(p, st, name, bytes, flops);
+        if (a_dt == HETA_BF16 && b_dt == HETA_BF16 && !a_rc && b_rc)
+            return launch_direct<bf16_t, bf16_t, false, true, bf16_t, true, true, 2, 32, 3, 4, false, 1, 1, 2>(p, st, name, bytes, flops);
+        if (a_dt == HETA_F32 && b_dt == HETA_BF16 && !a_rc && !b_rc)
+            return launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 32, 3, 4, false, 1, 1, 2>(p, st, name, bytes, flops);
+    }
     if (a_dt == HETA_F32 && b_dt == HETA_F32) {
 #define HETA_D32(ARC, BRC)                                                                                          \
     return wide ? launch_direct<float, float, ARC, true, float, BRC, true, 4, 16, 3, 4>(p, st, name, bytes, flops)   \

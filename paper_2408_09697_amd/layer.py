@@ -166,6 +166,15 @@ class RafLayer:
         hb.heta_rel_aggregate_fwd(self.g, r, self.op, self.source(s), self.M[r], d=self.d_rel[r], src_gid=gid,
                                   stream=stream)
 
+    def _aggregate_all(self, rs: Sequence[int], stream):
+        if len(rs) == 1:
+            return self._aggregate(rs[0], stream)
+        srcs = [self.g.rels[r][0] for r in rs]
+        hb.heta_rel_aggregate_fwd_multi(self.g, rs, self.op, [self.source(s) for s in srcs], [self.M[r] for r in rs],
+                                        d=[self.d_rel[r] for r in rs],
+                                        src_gids=None if self.src_gid is None else [self.src_gid[s] for s in srcs],
+                                        stream=stream)
+
     # ---- forward ------------------------------------------------------------------------------------
     def forward(self, stream=None) -> Dict[int, torch.Tensor]:
         """aggregate every relation, then one fused projection + cross-relation sum per type."""
@@ -177,11 +186,12 @@ class RafLayer:
                 part = pfs[c:c + 8]
                 hb.heta_project_batch([self.source(s)] * len(part), [self.W[r] for r in part], [self.Zp[r] for r in part],
                                       n_rows=self.g.ntypes[s][0], stream=stream)
+        # the relation-specific aggregations of a layer do not depend on each other: one call for all of them
+        # (relations of one shape class share launches, which is what a sampled block's small relations need)
+        self._aggregate_all([r for r in self.rels if r not in self.pf], stream)
         for t, all_rs in self.rels_into.items():
             rs = [r for r in all_rs if r not in self.pf]
             pfs = [r for r in all_rs if r in self.pf]
-            for r in rs:
-                self._aggregate(r, stream)
             wrote = False
             for c in range(0, len(rs), 8):  # the library takes up to 8 relations per call
                 part = rs[c:c + 8]
@@ -247,6 +257,7 @@ class RafLayer:
     # ---- backward: dZ = G; dW = M^T dZ; dM = dZ W^T; dH0 += CSC gather of dM ---------------------------
     def backward(self, G: Dict[int, torch.Tensor], stream=None, per_relation: bool = False):
         first_for_src = {s: True for s in self.rels_from}
+        per_src: Dict[int, list] = {}  # source type -> [(relation, dM_r)] in the order of the sum
         for t, all_rs in self.rels_into.items():
             rs = [r for r in all_rs if r not in self._pf_active]
             pfs = [r for r in all_rs if r in self._pf_active]
@@ -270,12 +281,23 @@ class RafLayer:
                     hb.heta_cross_rel_project_bwd(self.g, t, g, [self.W[r] for r in part],
                                                   [self.dM[r] for r in part], stream=stream)
             for r in rs:
-                s = self.g.rels[r][0]
-                hb.heta_rel_aggregate_bwd(self.g, r, self.op, dM[r], self.dH0[s],
-                                          beta=0.0 if first_for_src[s] else 1.0, stream=stream)
-                first_for_src[s] = False
+                per_src.setdefault(self.g.rels[r][0], []).append((r, dM[r]))
             for r in pfs:  # dZ'_r = CSC gather of G_t over the source rows
                 hb.heta_rel_aggregate_bwd(self.g, r, self.op, g, self.Ghat[r], d=self.d_out, stream=stream)
+        # dH0_s = sum over the relations leaving s of the CSC gather of dM_r.  Round k takes the k-th relation
+        # of every source type (their outputs are distinct, so one call covers them); the rounds follow each
+        # other on the stream, which keeps the order of the sum over the relations of a type fixed.
+        for k in range(max((len(v) for v in per_src.values()), default=0)):
+            items = [(s, v[k]) for s, v in per_src.items() if k < len(v)]
+            if len(items) == 1:
+                s, (r, dm) = items[0]
+                hb.heta_rel_aggregate_bwd(self.g, r, self.op, dm, self.dH0[s], beta=0.0 if k == 0 else 1.0, stream=stream)
+            else:
+                hb.heta_rel_aggregate_bwd_multi(self.g, [r for _, (r, _) in items], self.op, [dm for _, (_, dm) in items],
+                                                [self.dH0[s] for s, _ in items], betas=[0.0 if k == 0 else 1.0] * len(items),
+                                                stream=stream)
+        for s in per_src:
+            first_for_src[s] = False
         for s, rs in self.rels_from.items():  # per source type: dW_r = H0_s^T dZ'_r ; dH0_s += sum_r dZ'_r W_r^T
             pfs = [r for r in rs if r in self._pf_active]
             for c in range(0, len(pfs), 8):

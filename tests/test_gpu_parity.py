@@ -385,7 +385,9 @@ def gemm_path(request):
 
 
 PROJ_SHAPES = [(1000, 32, 32), (777, 128, 256), (300, 7, 256), (513, 24, 256), (400, 300, 256),
-               (260, 789, 256), (129, 768, 1024), (64, 1024, 1024), (1, 5, 3), (2000, 64, 40)]
+               (260, 789, 256), (129, 768, 1024), (64, 1024, 1024), (1, 5, 3), (2000, 64, 40),
+               # more than 96 tiles of 128 x 128: the full-size tiles (the shapes above take the 64 x 64 ones)
+               (20000, 128, 256), (13001, 256, 100)]
 
 
 @pytest.mark.parametrize("n,d_in,d_out", PROJ_SHAPES)
@@ -863,3 +865,70 @@ def test_block_ingest_of_many_relations_matches_the_host_path_bit_for_bit():
     assert heta.heta_graph_index_bytes(host) == heta.heta_graph_index_bytes(block)
     host.destroy()
     block.destroy()
+
+
+# ---- several relations per launch ------------------------------------------------------------------
+def _multi_relation_graph():
+    """Seven relations over three node types: five of one shape class (so that one group spills into a second
+    launch), one with hub rows, one empty; sources shared between relations for the backward rounds."""
+    g = rng.stream("tests", "multi")
+    n = [1500, 900, 1100]
+    rels = []
+    for i, (s, t, e) in enumerate([(0, 1, 9000), (1, 0, 7000), (2, 1, 4000), (0, 2, 12000), (1, 2, 3000), (2, 0, 0)]):
+        deg = power_law_degrees(n[t], e, 1.5, g) if e else np.zeros(n[t], dtype=np.int64)
+        rowptr = np.zeros(n[t] + 1, dtype=np.int64)
+        np.cumsum(deg, out=rowptr[1:])
+        rels.append(Relation(f"m{i}", s, t, rowptr, g.integers(0, n[s], size=int(rowptr[-1]), dtype=np.int32)))
+    hub = skewed_relation(n_src=n[0], n_dst=n[1], n_edges=20000, name="multi_hub")
+    rels.append(Relation("hub", 0, 1, hub.rowptr, hub.col))
+    hg = heta.heta_graph_create([(k, 8, 0) for k in n], [(r.src_type, r.dst_type, r.rowptr, r.col) for r in rels])
+    return n, rels, hg
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+@pytest.mark.parametrize("op", ["sum", "mean"])
+def test_multi_relation_aggregation_equals_the_single_calls_bit_for_bit(storage, op):
+    n, rels, hg = _multi_relation_graph()
+    hop = heta.HETA_SUM if op == "sum" else heta.HETA_MEAN
+    dt = torch.float32 if storage == "f32" else torch.bfloat16
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    try:
+        for widths in ([128] * 7, [128, 64, 128, 300, 7, 128, 128]):
+            tabs = {(t, d): torch.randn((n[t], d), generator=gen).to(dt).cuda() for t in range(3) for d in set(widths)}
+            idx = list(range(len(rels)))
+            srcs = [tabs[(rels[i].src_type, widths[i])] for i in idx]
+            single = [torch.full((n[rels[i].dst_type], widths[i]), 7.0, dtype=dt, device="cuda") for i in idx]
+            multi = [t.clone() for t in single]
+            for i in idx:
+                heta.heta_rel_aggregate_fwd(hg, i, hop, srcs[i], single[i])
+            heta.heta_rel_aggregate_fwd_multi(hg, idx, hop, srcs, multi)
+            torch.cuda.synchronize()
+            for i in idx:
+                assert torch.equal(single[i].view(torch.int16 if storage == "bf16" else torch.int32),
+                                   multi[i].view(torch.int16 if storage == "bf16" else torch.int32)), (widths, i)
+            # forward against the oracle as well (one relation per shape class is enough: the rest are bitwise equal)
+            e_src, e_dst = rels[6].edge_list()
+            ref = oracle.aggregate_fwd(e_src, e_dst, n[1], srcs[6].float().cpu().numpy().astype(np.float64), op)
+            assert_rows_close(multi[6].float().cpu().numpy(), ref, TOL[storage])
+            # backward: relation i's gradient rows gathered into a buffer per relation, beta = 1 on top of ones
+            gouts = [tabs[(rels[i].dst_type, widths[i])] for i in idx]
+            gs_single = [torch.ones((n[rels[i].src_type], widths[i]), dtype=torch.float32, device="cuda") for i in idx]
+            gs_multi = [t.clone() for t in gs_single]
+            for i in idx:
+                heta.heta_rel_aggregate_bwd(hg, i, hop, gouts[i], gs_single[i], beta=1.0)
+            heta.heta_rel_aggregate_bwd_multi(hg, idx, hop, gouts, gs_multi, betas=[1.0] * len(idx))
+            torch.cuda.synchronize()
+            for i in idx:
+                assert torch.equal(gs_single[i].view(torch.int32), gs_multi[i].view(torch.int32)), (widths, i)
+        # items that write the same rows are refused before anything runs
+        shared = torch.zeros((n[1], 128), dtype=dt, device="cuda")
+        with pytest.raises(heta.HetaError) as ei:
+            heta.heta_rel_aggregate_fwd_multi(hg, [0, 6], hop, [srcs[0], srcs[6]], [shared, shared[:, :128]])
+        assert ei.value.status == heta.HETA_ERR_INVALID_ARG and "overlap" in str(ei.value)
+        torch.cuda.synchronize()
+        assert float(shared.float().abs().max()) == 0.0
+        with pytest.raises(heta.HetaError):
+            heta.heta_rel_aggregate_bwd_multi(hg, [0, 3], hop, [gouts[0], gouts[3]], [gs_multi[0], gs_multi[0]])
+        heta.heta_rel_aggregate_fwd_multi(hg, [], hop, [], [])
+    finally:
+        hg.destroy()
