@@ -88,6 +88,10 @@ def roofline_of(kernels, traffic, traffic_source):
         r["mfma_busy"] = rec["mfma_busy"]
     r["avg_launch_ms"] = k["avg_launch_ms"]
     r["timing"] = "HIP events on the launch stream around every launch, over the same K steps"
+    if r["bound"] == "mfma" and SUSTAINED_MFMA:
+        sus = SUSTAINED_MFMA["f32" if dom.endswith("f32") else "bf16"]["TFLOPs"]
+        # frac stays against the published peak; this is the same rate against what register-only MFMA loops reach
+        r["sustained_mfma"] = {"TFLOPs": sus, "achieved_over_sustained": k["TFLOPs"] / sus, "how": SUSTAINED_MFMA["note"]}
     return r
 
 
@@ -704,6 +708,33 @@ def large_block_sweep(base, mb, tables, W, fanouts, args):
             "rows": rows}
 
 
+SUSTAINED_MFMA = None
+
+
+def measure_sustained_mfma():
+    """TFLOP/s of register-only MFMA loops (no memory traffic) on every SIMD: the rate the matrix pipes hold
+    at the clock the chip sustains under that load, reported beside the published peaks."""
+    import torch
+    import paper_2408_09697_amd as heta
+    sink = torch.empty(4096, dtype=torch.float32, device="cuda")
+    out = {}
+    for name, dt, iters in (("f32", heta.HETA_F32, 6000), ("bf16", heta.HETA_BF16, 12000)):
+        heta.heta_calibration_mfma(dt, iters, sink)  # warm-up: clocks settle under the load
+        best, mean = 0.0, 0.0
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = heta.heta_calibration_mfma(dt, iters, sink)
+            e1.record()
+            e1.synchronize()
+            tf = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            best, mean = max(best, tf), mean + tf / 5
+        out[name] = {"TFLOPs": mean, "best_TFLOPs": best}
+    out["note"] = ("heta_calibration_mfma: 2 wavefronts per SIMD, 16 independent 32x32 MFMAs per loop trip, operands in "
+                   "registers; mean and best of 5 launches of a few ms after one warm-up launch")
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -749,6 +780,8 @@ def main() -> int:
     torch.cuda.synchronize()
     del calib_src, calib_dst
     torch.cuda.empty_cache()
+    global SUSTAINED_MFMA
+    SUSTAINED_MFMA = measure_sustained_mfma()
 
     if args.model == "rgat":
         out = {"f32": measure_rgat("f32", args)}

@@ -28,7 +28,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_rel_aggregate_fwd_multi", "heta_rel_aggregate_bwd_multi",
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
-           "heta_profile_read", "heta_calibration_copy", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
+           "heta_profile_read", "heta_calibration_copy", "heta_calibration_mfma", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
            "heta_cross_rel_project_wgrad", "heta_sparse_adam", "heta_project_batch",
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
            "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel",
@@ -940,6 +940,17 @@ def heta_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> 
     L = load_library()
     L.heta_calibration_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     _check(L.heta_calibration_copy(_dev(dst, "dst"), _dev(src, "src"), n_bytes, _stream(stream)))
+
+
+def heta_calibration_mfma(dtype: int, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Launches the register-only MFMA kernel; returns the flops of the launch."""
+    L = load_library()
+    L.heta_calibration_mfma.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                        ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    flops = ctypes.c_double(0.0)
+    _check(L.heta_calibration_mfma(dtype, iters, _dev(sink, "sink", torch.float32), sink.numel(), ctypes.byref(flops),
+                                   _stream(stream)))
+    return flops.value
 
 
 def heta_profile_reset() -> None:

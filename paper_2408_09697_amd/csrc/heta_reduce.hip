@@ -74,6 +74,43 @@ __global__ void __launch_bounds__(256) calibration_copy_kernel(const uint4 *src,
     if (i < n) dst[i] = src[i];
 }
 
+// Matrix instructions on registers only, no memory traffic: what the matrix pipes sustain at the clock the
+// chip holds under that load.  Each wavefront keeps four independent 32 x 32 accumulators busy (16 MFMAs
+// per loop trip, none waiting on another); the operands are zero on one side, so the sums stay zero.
+typedef float calib_f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 calib_bf16x8 __attribute__((ext_vector_type(8)));
+template <bool BF16>
+__global__ void __launch_bounds__(256) calibration_mfma_kernel(int64_t iters, float *sink)
+{
+    calib_f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+    const float a = static_cast<float>(threadIdx.x & 63) * 0.015625f;
+    calib_bf16x8 av, bv;
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        av[v] = static_cast<__bf16>(a);
+        bv[v] = static_cast<__bf16>(0.f);
+    }
+    for (int64_t i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (BF16) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[j], 0, 0, 0);
+                else acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, 0.f, acc[j], 0, 0, 0);
+            }
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t += acc[j][v];
+    if ((threadIdx.x & 63) == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = t;
+}
+
 } // namespace heta
 
 using namespace heta;
@@ -163,6 +200,25 @@ heta_status heta_calibration_copy(void *dst, const void *src, int64_t n_bytes, v
     hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(hip_stream),
                        static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n);
     HETA_LAUNCH_CHECK("calibration_copy_kernel");
+    return HETA_OK;
+}
+
+heta_status heta_calibration_mfma(heta_dtype dt, int64_t iters, float *sink, int64_t sink_elems, double *flops_out,
+                                  void *hip_stream)
+{
+    constexpr int kBlocks = 512; // two workgroups of four wavefronts per CU: two wavefronts per SIMD
+    if (!valid_dtype(dt)) return fail(HETA_ERR_INVALID_ARG, "heta_calibration_mfma: bad dtype");
+    if (!sink || sink_elems < kBlocks * 4 || iters < 1 || iters > (int64_t(1) << 24))
+        return fail(HETA_ERR_INVALID_ARG, "heta_calibration_mfma: need 1 <= iters <= 2^24 and a sink of %d floats", kBlocks * 4);
+    const double per_mfma = dt == HETA_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+    const double flops = per_mfma * 16.0 * static_cast<double>(iters) * 4.0 * kBlocks;
+    if (flops_out) *flops_out = flops;
+    ProfScope prof("calibration_mfma_kernel", as_stream(hip_stream), 0, flops);
+    if (dt == HETA_BF16)
+        hipLaunchKernelGGL(calibration_mfma_kernel<true>, dim3(kBlocks), dim3(256), 0, as_stream(hip_stream), iters, sink);
+    else
+        hipLaunchKernelGGL(calibration_mfma_kernel<false>, dim3(kBlocks), dim3(256), 0, as_stream(hip_stream), iters, sink);
+    HETA_LAUNCH_CHECK("calibration_mfma_kernel");
     return HETA_OK;
 }
 

@@ -932,3 +932,15 @@ def test_multi_relation_aggregation_equals_the_single_calls_bit_for_bit(storage,
         heta.heta_rel_aggregate_fwd_multi(hg, [], hop, [], [])
     finally:
         hg.destroy()
+
+
+def test_calibration_mfma_runs_and_reports_its_flops():
+    sink = torch.full((2048,), 3.0, dtype=torch.float32, device="cuda")
+    assert heta.heta_calibration_mfma(heta.HETA_F32, 10, sink) == 2.0 * 32 * 32 * 2 * 16 * 10 * 4 * 512
+    assert heta.heta_calibration_mfma(heta.HETA_BF16, 10, sink) == 2.0 * 32 * 32 * 16 * 16 * 10 * 4 * 512
+    torch.cuda.synchronize()
+    assert float(sink.abs().max()) == 0.0  # one operand is zero: the accumulators stay zero
+    with pytest.raises(heta.HetaError):
+        heta.heta_calibration_mfma(heta.HETA_F32, 10, sink[:100])
+    with pytest.raises(heta.HetaError):
+        heta.heta_calibration_mfma(heta.HETA_F32, 0, sink)
