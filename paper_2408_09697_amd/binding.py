@@ -36,7 +36,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_unique_relabel_batch", "heta_rel_aggregate_fwd_noalloc", "heta_attn_fold", "heta_attn_fold_bwd",
            "heta_graph_index_bytes"]
 # process-wide switches for tests and measurements, declared in csrc/heta_test_hooks.h (not in the public header)
-TEST_HOOKS = ["heta_projection_force_staged", "heta_ingest_force"]
+TEST_HOOKS = ["heta_projection_force_staged", "heta_ingest_force", "heta_projection_f32_native"]
 HETA_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
@@ -931,6 +931,12 @@ def heta_projection_force_staged(on: bool) -> None:
     L = load_library()
     L.heta_projection_force_staged.argtypes = [ctypes.c_int32]
     _check(L.heta_projection_force_staged(1 if on else 0))
+
+
+def heta_projection_f32_native(on: bool) -> None:
+    L = load_library()
+    L.heta_projection_f32_native.argtypes = [ctypes.c_int32]
+    _check(L.heta_projection_f32_native(1 if on else 0))
 
 
 def heta_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

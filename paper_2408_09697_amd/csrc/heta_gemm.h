@@ -248,6 +248,7 @@ struct TileLoader {
 
 // The direct-to-LDS pipeline (heta_gemm_direct.hip).  Sets *handled when it launched the product;
 // otherwise the caller falls back to the register-staged kernel.
+extern bool g_f32_native; // test switch, see heta_test_hooks.h
 heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, bool a_rc, bool b_rc, hipStream_t st,
                                const char *name, double bytes, double flops, bool *handled);
 

@@ -37,6 +37,7 @@
 
 #include "heta_gemm.h"
 
+
 namespace heta {
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
@@ -245,6 +246,58 @@ __device__ __forceinline__ uint4 dfrag_bf16_rc_from_f32(const float *tile, int r
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// fp32 products on the bf16 matrix pipe.  x = h + m + l with three bf16 terms (h = bf16(x), m = bf16(x - h),
+// l = bf16(x - h - m); both differences are exact in fp32), so |x - (h + m + l)| <= 2^-27 |x|.  A product a b
+// is fed as the six terms ah bh, ah bm, am bh, am bm, ah bl, al bh (each a product of two 8-bit significands,
+// exact in the fp32 accumulator's input); the three terms left out are below 2^-25 |a b|, less than the
+// rounding of one fp32 multiplication.  Six bf16 MFMAs of 16 k-values cost 6 x 8 passes where the fp32 MFMA
+// needs 8 x 16 for the same 16 k-values.
+__device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t &h, uint32_t &m, uint32_t &l)
+{
+    h = pack_bf16(x0, x1);
+    const float r0 = x0 - __uint_as_float(h << 16), r1 = x1 - __uint_as_float(h & 0xffff0000u);
+    m = pack_bf16(r0, r1);
+    const float s0 = r0 - __uint_as_float(m << 16), s1 = r1 - __uint_as_float(m & 0xffff0000u);
+    l = pack_bf16(s0, s1);
+}
+
+// The lane's eight k-values kk + 8*half + 0..7 of row r of an fp32 operand lying in LDS (k-contiguous with
+// swizzled chunks, or r-contiguous as in memory): the LDS reads only.
+template <bool RC, int ROWS, int BK>
+__device__ __forceinline__ void dfrag_load8(const float *tile, int r, int kk, int half, float x[8])
+{
+    if constexpr (RC) {
+        const float *p = tile + (kk + 8 * half) * ROWS + r;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = p[j * ROWS];
+    } else {
+        constexpr int CPR = BK / 4;
+        const int c0 = kk / 4 + 2 * half, sw = swz<CPR>(r);
+        const float4 lo = *reinterpret_cast<const float4 *>(&tile[(r * CPR + (c0 ^ sw)) * 4]);
+        const float4 hi = *reinterpret_cast<const float4 *>(&tile[(r * CPR + ((c0 + 1) ^ sw)) * 4]);
+        x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w; x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+    }
+}
+
+// Eight k-values (the first is k0 of its tile) as three bf16 fragments; with MASKED, k-values from kv on
+// count as zero (branch-free: the caller's code stays one scheduling region).
+template <bool MASKED> __device__ __forceinline__ void split3_frag(const float x[8], int k0, int kv, uint4 out[3])
+{
+    uint32_t h[4], m[4], l[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float x0 = x[2 * j], x1 = x[2 * j + 1];
+        if constexpr (MASKED) {
+            x0 = k0 + 2 * j < kv ? x0 : 0.f;
+            x1 = k0 + 2 * j + 1 < kv ? x1 : 0.f;
+        }
+        split3_pair(x0, x1, h[j], m[j], l[j]);
+    }
+    out[0] = make_uint4(h[0], h[1], h[2], h[3]);
+    out[1] = make_uint4(m[0], m[1], m[2], m[3]);
+    out[2] = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
 // zeroes the k-values of a bf16 fragment (8 consecutive k from k_first) that are >= kv
 __device__ __forceinline__ uint4 mask_bf16(uint4 v, int k_first, int kv)
 {
@@ -284,13 +337,112 @@ template <int BK> struct TileSeq {
     }
 };
 
+// ---- epilogue ---------------------------------------------------------------------------------------
+template <int MI, int NJ>
+__device__ __forceinline__ void store_tile(const GemmParams &p, const GemmSeg &out_seg, float *strips, floatx16 (&acc)[MI][NJ],
+                                           int wave, int lane, int wm, int wn, int64_t m0, int64_t n0, int rows_a, int rows_b,
+                                           int64_t split)
+{
+    // Epilogue through LDS.  Accumulator register v of lane (half, l32) is C[8*(v/4) + 4*half + v%4][l32] of
+    // its 32 x 32 tile: written out as it lies, a store instruction would touch 32 x 4 (or 32 x 2) bytes in
+    // each of two rows.  Instead every wavefront passes its 64 x 64 block through a private LDS strip, 8 rows
+    // x 64 columns at a time (the ring stages are free once every wavefront has left the k loop), and reads
+    // it back with a lane owning 4 consecutive columns: a store instruction then writes whole 256-byte
+    // (fp32) or 128-byte (bf16) row segments of 4 rows, and the accumulate / scale / activation forms read
+    // and write the same 16-byte pieces.
+    constexpr int EW = 32 * NJ;    // columns of a wavefront's block
+    constexpr int EPP = EW + 4;    // strip pitch in floats (rows 4 apart fall on different banks)
+    constexpr int PIECES = 8 * NJ; // 16-byte pieces per strip row
+    const int half = lane >> 5, l32 = lane & 31;
+    float *ep = strips + wave * (8 * EPP);
+    float *Cp = out_seg.C + (p.partial ? split * out_seg.M * out_seg.ldc : 0);
+    bf16_t *Hp = reinterpret_cast<bf16_t *>(out_seg.C);
+    const bool direct = !p.partial;
+    const bool fused = direct && (p.row_scale || p.beta != 0.f || p.relu);
+    // 16-byte pieces (4 fp32 or 8 bf16 columns) need rows that keep that alignment
+    const bool vec_out = p.out_bf16 ? ((out_seg.ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(Hp) & 15u) == 0)
+                                    : ((out_seg.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(Cp) & 15u) == 0);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int jj = 0; jj < NJ; ++jj)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) ep[(4 * half + t) * EPP + jj * 32 + l32] = acc[i][jj][4 * q + t];
+            if (p.out_bf16) { // 8 rows x 4 NJ pieces of 8 columns: 16-byte stores, 128-byte row segments for NJ = 2
+#pragma unroll
+                for (int h = 0; h < (NJ + 1) / 2; ++h) {
+                    const int piece = h * 64 + lane;
+                    if (piece >= 32 * NJ) continue;
+                    const int row_l = piece / (4 * NJ), c8 = (piece % (4 * NJ)) * 8;
+                    const float4 lo4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c8]);
+                    const float4 hi4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c8 + 4]);
+                    const int ml = wm + i * 32 + 8 * q + row_l, nl = wn + c8;
+                    if (ml >= rows_a || nl >= rows_b) continue;
+                    const int64_t off = (m0 + ml) * out_seg.ldc + n0 + nl;
+                    if (vec_out && nl + 8 <= rows_b) {
+                        *reinterpret_cast<uint4 *>(Hp + off) = make_uint4(pack_bf16(lo4.x, lo4.y), pack_bf16(lo4.z, lo4.w),
+                                                                          pack_bf16(hi4.x, hi4.y), pack_bf16(hi4.z, hi4.w));
+                    } else {
+                        const float v[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (nl + e < rows_b) Hp[off + e] = to_bf16(v[e]);
+                    }
+                }
+                continue;
+            }
+#pragma unroll
+            for (int h = 0; h < NJ; ++h) { // the strip's 8 x PIECES pieces, 64 per pass
+                const int piece = h * 64 + lane;
+                const int row_l = piece / PIECES, c4 = (piece % PIECES) * 4;
+                const float4 v4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c4]);
+                const int ml = wm + i * 32 + 8 * q + row_l, nl = wn + c4;
+                if (ml >= rows_a || nl >= rows_b) continue;
+                float v[4] = {v4.x, v4.y, v4.z, v4.w};
+                const int64_t off = (m0 + ml) * out_seg.ldc + n0 + nl;
+                float *o = Cp + off;
+                const bool whole = vec_out && nl + 4 <= rows_b;
+                if (fused) {
+                    const float sc = p.row_scale ? p.row_scale[m0 + ml] : 1.f;
+                    float old[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (p.beta != 0.f) {
+                        if (whole) {
+                            const float4 o4 = *reinterpret_cast<const float4 *>(o);
+                            old[0] = o4.x; old[1] = o4.y; old[2] = o4.z; old[3] = o4.w;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (nl + e < rows_b) old[e] = o[e];
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float x = v[e] * sc;
+                        if (p.beta != 0.f) x += p.beta * old[e];
+                        if (p.relu) x = fmaxf(x, 0.f);
+                        v[e] = x;
+                    }
+                }
+                if (whole) {
+                    *reinterpret_cast<float4 *>(o) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (nl + e < rows_b) o[e] = v[e];
+                }
+            }
+        }
+}
+
 // Shape of the output tile: WMW x WN wavefronts, each holding MI x NJ MFMA 32 x 32 accumulators; the
 // tile is (32 MI WMW) x (32 NJ WN).  The default 2 x 2 blocks per wavefront with 2 x WN wavefronts is the
 // 128 x (64 WN) tile; tall tiles (MI = 5, NJ = 1: 320 x 128) let a weight gradient whose input is wider than
 // 128 columns read its large gradient operand once, wide ones (MI = 1, NJ = 5: 128 x 320) do the same for a
 // product with more than 256 output columns and its input rows.
 template <typename CT, typename SA_T, bool A_RC, bool A_DIRECT, typename SB_T, bool B_RC, bool B_DIRECT, int WN, int BK,
-          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2>
+          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2, bool X3 = false>
 __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmParams p)
 {
     constexpr int NW = WMW * WN, NT = 64 * NW, BN = 32 * NJ * WN, BM = 32 * MI * WMW; // BM shadows the default tile height
@@ -309,6 +461,8 @@ __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmPar
     static_assert(A_DIRECT || B_DIRECT, "at least one operand is loaded directly");
     static_assert(!B_SPLIT || (B_DIRECT && B_RC && sizeof(SB_T) == 4 && sizeof(CT) == 2), "two-term feeding: direct r-contiguous fp32 B");
     static_assert(ST >= 2 && (ST - 2) * LD_PER_TILE < 64, "vmcnt range");
+    static_assert(!X3 || (A_DIRECT && B_DIRECT && sizeof(SA_T) == 4 && sizeof(SB_T) == 4 && sizeof(CT) == 2 && !B_SPLIT),
+                  "three-term feeding: both operands direct fp32, bf16 MFMA");
     static_assert(A_BYTES % 1024 == 0, "stage addresses stay 1 KB aligned");
     __shared__ __attribute__((aligned(1024))) char ring[A_BYTES + B_BYTES];
     char *const As = ring, *const Bs = ring + A_BYTES;
@@ -464,6 +618,39 @@ __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmPar
                             for (int jj = 0; jj < NJ; ++jj)
                                 acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[jj][t], acc[i][jj], 0, 0, 0);
                 }
+            } else if constexpr (X3) {
+                // fp32 operands, every product as six bf16 terms (split3_pair)
+#pragma unroll
+                for (int kk = 0; kk < BK; kk += 16) {
+                    union Frag { uint4 u; bf16x8 v; };
+                    uint4 a3[MI][3], b3[NJ][3];
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) {
+                        float x[8];
+                        dfrag_load8<A_RC, BM, BK>(reinterpret_cast<const float *>(At), wm + i * 32 + l32, kk, half, x);
+                        if (ragged) split3_frag<true>(x, kk + 8 * half, kv, a3[i]);
+                        else split3_frag<false>(x, kk + 8 * half, kv, a3[i]);
+                    }
+#pragma unroll
+                    for (int jj = 0; jj < NJ; ++jj) {
+                        float x[8];
+                        dfrag_load8<B_RC, BN, BK>(reinterpret_cast<const float *>(Bt), wn + jj * 32 + l32, kk, half, x);
+                        if (ragged) split3_frag<true>(x, kk + 8 * half, kv, b3[jj]);
+                        else split3_frag<false>(x, kk + 8 * half, kv, b3[jj]);
+                    }
+                    constexpr int TA[6] = {2, 0, 1, 1, 0, 0}, TB[6] = {0, 2, 1, 0, 1, 0}; // smallest products first
+#pragma unroll
+                    for (int q = 0; q < 6; ++q)
+#pragma unroll
+                        for (int i = 0; i < MI; ++i)
+#pragma unroll
+                            for (int jj = 0; jj < NJ; ++jj) {
+                                Frag fa, fb;
+                                fa.u = a3[i][TA[q]];
+                                fb.u = b3[jj][TB[q]];
+                                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb.v, acc[i][jj], 0, 0, 0);
+                            }
+                }
             } else {
 #pragma unroll
                 for (int kk = 0; kk < BK; kk += 16) {
@@ -520,104 +707,15 @@ __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmPar
         }
     }
 
-    // Epilogue through LDS.  Accumulator register v of lane (half, l32) is C[8*(v/4) + 4*half + v%4][l32] of
-    // its 32 x 32 tile: written out as it lies, a store instruction would touch 32 x 4 (or 32 x 2) bytes in
-    // each of two rows.  Instead every wavefront passes its 64 x 64 block through a private LDS strip, 8 rows
-    // x 64 columns at a time (the ring stages are free once every wavefront has left the k loop), and reads
-    // it back with a lane owning 4 consecutive columns: a store instruction then writes whole 256-byte
-    // (fp32) or 128-byte (bf16) row segments of 4 rows, and the accumulate / scale / activation forms read
-    // and write the same 16-byte pieces.
-    constexpr int EW = 32 * NJ;    // columns of a wavefront's block
-    constexpr int EPP = EW + 4;    // strip pitch in floats (rows 4 apart fall on different banks)
-    constexpr int PIECES = 8 * NJ; // 16-byte pieces per strip row
-    static_assert(A_BYTES + B_BYTES >= NW * 8 * EPP * 4, "the epilogue strips overlay the ring");
     barrier_no_drain();     // every wavefront's last fragment reads are done (they fed its last MFMAs)
-    float *ep = reinterpret_cast<float *>(ring) + wave * (8 * EPP);
-    float *Cp = out_seg.C + (p.partial ? split * out_seg.M * out_seg.ldc : 0);
-    bf16_t *Hp = reinterpret_cast<bf16_t *>(out_seg.C);
-    const bool direct = !p.partial;
-    const bool fused = direct && (p.row_scale || p.beta != 0.f || p.relu);
-    // 16-byte pieces (4 fp32 or 8 bf16 columns) need rows that keep that alignment
-    const bool vec_out = p.out_bf16 ? ((out_seg.ldc & 7) == 0 && (reinterpret_cast<uintptr_t>(Hp) & 15u) == 0)
-                                    : ((out_seg.ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(Cp) & 15u) == 0);
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-#pragma unroll
-            for (int jj = 0; jj < NJ; ++jj)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) ep[(4 * half + t) * EPP + jj * 32 + l32] = acc[i][jj][4 * q + t];
-            if (p.out_bf16) { // 8 rows x 4 NJ pieces of 8 columns: 16-byte stores, 128-byte row segments for NJ = 2
-#pragma unroll
-                for (int h = 0; h < (NJ + 1) / 2; ++h) {
-                    const int piece = h * 64 + lane;
-                    if (piece >= 32 * NJ) continue;
-                    const int row_l = piece / (4 * NJ), c8 = (piece % (4 * NJ)) * 8;
-                    const float4 lo4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c8]);
-                    const float4 hi4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c8 + 4]);
-                    const int ml = wm + i * 32 + 8 * q + row_l, nl = wn + c8;
-                    if (ml >= rows_a || nl >= rows_b) continue;
-                    const int64_t off = (m0 + ml) * out_seg.ldc + n0 + nl;
-                    if (vec_out && nl + 8 <= rows_b) {
-                        *reinterpret_cast<uint4 *>(Hp + off) = make_uint4(pack_bf16(lo4.x, lo4.y), pack_bf16(lo4.z, lo4.w),
-                                                                          pack_bf16(hi4.x, hi4.y), pack_bf16(hi4.z, hi4.w));
-                    } else {
-                        const float v[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (nl + e < rows_b) Hp[off + e] = to_bf16(v[e]);
-                    }
-                }
-                continue;
-            }
-#pragma unroll
-            for (int h = 0; h < NJ; ++h) { // the strip's 8 x PIECES pieces, 64 per pass
-                const int piece = h * 64 + lane;
-                const int row_l = piece / PIECES, c4 = (piece % PIECES) * 4;
-                const float4 v4 = *reinterpret_cast<const float4 *>(&ep[row_l * EPP + c4]);
-                const int ml = wm + i * 32 + 8 * q + row_l, nl = wn + c4;
-                if (ml >= rows_a || nl >= rows_b) continue;
-                float v[4] = {v4.x, v4.y, v4.z, v4.w};
-                const int64_t off = (m0 + ml) * out_seg.ldc + n0 + nl;
-                float *o = Cp + off;
-                const bool whole = vec_out && nl + 4 <= rows_b;
-                if (fused) {
-                    const float sc = p.row_scale ? p.row_scale[m0 + ml] : 1.f;
-                    float old[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (p.beta != 0.f) {
-                        if (whole) {
-                            const float4 o4 = *reinterpret_cast<const float4 *>(o);
-                            old[0] = o4.x; old[1] = o4.y; old[2] = o4.z; old[3] = o4.w;
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (nl + e < rows_b) old[e] = o[e];
-                        }
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float x = v[e] * sc;
-                        if (p.beta != 0.f) x += p.beta * old[e];
-                        if (p.relu) x = fmaxf(x, 0.f);
-                        v[e] = x;
-                    }
-                }
-                if (whole) {
-                    *reinterpret_cast<float4 *>(o) = make_float4(v[0], v[1], v[2], v[3]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (nl + e < rows_b) o[e] = v[e];
-                }
-            }
-        }
+    static_assert(A_BYTES + B_BYTES >= NW * 8 * (32 * NJ + 4) * 4, "the epilogue strips overlay the ring");
+    store_tile<MI, NJ>(p, out_seg, reinterpret_cast<float *>(ring), acc, wave, lane, wm, wn, m0, n0, rows_a, rows_b, split);
 }
 
 // ---- host side -------------------------------------------------------------------------------------
 
 template <typename CT, typename SA_T, bool A_RC, bool A_DIRECT, typename SB_T, bool B_RC, bool B_DIRECT, int WN, int BK,
-          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2>
+          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2, bool X3 = false>
 static heta_status launch_direct(GemmParams &p, hipStream_t st, const char *name, double bytes, double flops)
 {
     constexpr int BN = 32 * NJ * WN, BM = 32 * MI * WMW;
@@ -634,11 +732,14 @@ static heta_status launch_direct(GemmParams &p, hipStream_t st, const char *name
     if (blocks <= 0) return HETA_OK;
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "projection: matrix too large for one launch");
     ProfScope prof(name, st, bytes, flops);
-    hipLaunchKernelGGL((gemm_direct_kernel<CT, SA_T, A_RC, A_DIRECT, SB_T, B_RC, B_DIRECT, WN, BK, ST, OCC, B_SPLIT, MI, NJ, WMW>),
+    hipLaunchKernelGGL((gemm_direct_kernel<CT, SA_T, A_RC, A_DIRECT, SB_T, B_RC, B_DIRECT, WN, BK, ST, OCC, B_SPLIT, MI, NJ, WMW, X3>),
                        dim3((unsigned)blocks), dim3(64 * WMW * WN), 0, st, p);
     HETA_LAUNCH_CHECK("gemm_direct_kernel");
     return HETA_OK;
 }
+
+// test switch: fp32 products on the fp32 MFMA (32x32x2) instead of as six bf16 terms
+bool g_f32_native = false;
 
 heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, bool a_rc, bool b_rc, hipStream_t st,
                                const char *name, double bytes, double flops, bool *handled)
@@ -703,6 +804,17 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         small = mt * nt * (p.batch ? p.n_seg : 1) <= 96;
     }
     *handled = true;
+    if (a_dt == HETA_F32 && b_dt == HETA_F32 && !g_f32_native) {
+        // fp32 operands, fp32-exact products as six bf16 MFMA terms each (see split3_pair), fp32 accumulation
+#define HETA_X32(ARC, BRC)                                                                                                        \
+    return small ? launch_direct<bf16_t, float, ARC, true, float, BRC, true, 2, 16, 3, 4, false, 1, 1, 2, true>(p, st, name, bytes, flops) \
+         : wide  ? launch_direct<bf16_t, float, ARC, true, float, BRC, true, 4, 16, 3, 2, false, 2, 2, 2, true>(p, st, name, bytes, flops) \
+                 : launch_direct<bf16_t, float, ARC, true, float, BRC, true, 2, 16, 3, 3, false, 2, 2, 2, true>(p, st, name, bytes, flops)
+        if (!a_rc && b_rc) { HETA_X32(false, true); }
+        if (!a_rc && !b_rc) { HETA_X32(false, false); }
+        if (a_rc && b_rc) { HETA_X32(true, true); }
+#undef HETA_X32
+    }
     if (small) {
         if (a_dt == HETA_F32 && b_dt == HETA_F32 && !a_rc)
             return b_rc ? launch_direct<float, float, false, true, float, true, true, 2, 16, 3, 4, false, 1, 1, 2>(p, st, name, bytes, flops)

@@ -557,6 +557,12 @@ using namespace heta;
 
 extern "C" {
 
+heta_status heta_projection_f32_native(int32_t on)
+{
+    g_f32_native = on != 0;
+    return HETA_OK;
+}
+
 heta_status heta_projection_force_staged(int32_t on)
 {
     g_force_staged = on != 0;

@@ -20,6 +20,11 @@ heta_status heta_ingest_force(int32_t mode);
  * rounding order. */
 heta_status heta_projection_force_staged(int32_t on);
 
+/* fp32 x fp32 projections on the direct pipeline form every product from three bf16 terms per operand (six
+ * bf16 MFMAs, fp32 accumulation: products exact to 2^-25).  When on, they run on the fp32 MFMA (32x32x2)
+ * instead: the same results to rounding order at about 2.5 times the matrix-pipe time. */
+heta_status heta_projection_f32_native(int32_t on);
+
 #ifdef __cplusplus
 }
 #endif
