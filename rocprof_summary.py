@@ -44,9 +44,13 @@ def family(name: str) -> str:
     if base in ("gemm_kernel", "gemm_direct_kernel"):
         args = [a.strip() for a in name[name.index("<") + 1:name.rindex(">")].split(",")]
         ct = "f32" if args[0] == "float" else "bf16"
+        if base == "gemm_direct_kernel" and args[1] == "float" and args[4] == "float":
+            ct = "f32"  # fp32 operands on the bf16 MFMA as six terms per product: the library times it as an fp32 projection
         # both operands r-contiguous = the weight gradient (contraction over graph rows)
         wgrad = (args[2] == "true" and args[4] == "true") if base == "gemm_kernel" else (args[2] == "true" and args[5] == "true")
         return f"gemm_wgrad_{ct}" if wgrad else f"gemm_{ct}"
+    if base.endswith("_multi_kernel"):  # several relations per launch: timed under the single-relation kernel's name
+        return base[:-len("_multi_kernel")] + "_kernel"
     return base
 
 

@@ -944,3 +944,44 @@ def test_calibration_mfma_runs_and_reports_its_flops():
         heta.heta_calibration_mfma(heta.HETA_F32, 10, sink[:100])
     with pytest.raises(heta.HetaError):
         heta.heta_calibration_mfma(heta.HETA_F32, 0, sink)
+
+
+@pytest.mark.parametrize("n,d_in,d_out,trans", [(3000, 384, 256, False), (3000, 256, 128, True), (20000, 128, 256, False),
+                                                (777, 300, 40, False)])
+def test_f32_products_as_six_bf16_terms_are_as_accurate_as_the_fp32_mfma(n, d_in, d_out, trans):
+    """fp32 projections split every operand into three bf16 terms and feed six MFMA terms per product.  The
+    claim is fp32 accuracy, so the measure is the fp32 MFMA itself (the test switch): both paths against the
+    fp64 oracle on operands spread over twelve binades, entries of mixed sign."""
+    g = rng.stream("tests", f"x3_{n}_{d_in}")
+    x = (g.standard_normal((n, d_in)) * np.exp2(g.integers(-6, 6, size=(n, d_in)))).astype(np.float32)
+    w_shape = (d_out, d_in) if trans else (d_in, d_out)
+    w = (g.standard_normal(w_shape) * np.exp2(g.integers(-6, 6, size=w_shape)) / np.sqrt(d_in)).astype(np.float32)
+    ref = x.astype(np.float64) @ (w.astype(np.float64).T if trans else w.astype(np.float64))
+    scale = np.maximum(1.0, np.abs(ref).max(axis=1, keepdims=True))
+    err = {}
+    try:
+        for native in (False, True):
+            heta.heta_projection_f32_native(native)
+            out = torch.full((n, d_out), float("nan"), dtype=torch.float32, device="cuda")
+            heta.heta_project(dev_table(x, "f32", 4), dev_table(w, "f32", 4), out, trans_w=trans)
+            err[native] = float((np.abs(out.cpu().numpy().astype(np.float64) - ref) / scale).max())
+    finally:
+        heta.heta_projection_f32_native(False)
+    assert err[True] <= 1e-5 and err[False] <= 1e-5, err
+    # no worse than the fp32 MFMA beyond the noise of the summation order
+    assert err[False] <= 2.0 * err[True] + 1e-7, err
+    # the weight gradient takes the same path with both operands row-major over the contraction index
+    hg = heta.heta_graph_create([(n, 8, 0)], [])
+    try:
+        gout = (g.standard_normal((n, d_out)) * np.exp2(g.integers(-6, 6, size=(n, d_out)))).astype(np.float32)
+        ref_w = x.astype(np.float64).T @ gout.astype(np.float64)
+        errw = {}
+        for native in (False, True):
+            heta.heta_projection_f32_native(native)
+            dw = torch.full((d_in, d_out), float("nan"), dtype=torch.float32, device="cuda")
+            heta.heta_project_wgrad_batch(hg, [dev_table(x, "f32", 4)], [dev_table(gout, "f32", 4)], [dw], n_rows=n)
+            errw[native] = float(np.abs(dw.cpu().numpy().astype(np.float64) - ref_w).max() / np.abs(ref_w).max())
+    finally:
+        heta.heta_projection_f32_native(False)
+        hg.destroy()
+    assert errw[True] <= 1e-5 and errw[False] <= 2.0 * errw[True] + 1e-7, errw
