@@ -43,6 +43,7 @@ namespace heta {
 
 constexpr int kShortDeg = 32;      // rows of fewer edges are batched by degree
 constexpr int kBatchIds = 256;     // neighbour ids a batch wavefront parks in LDS
+constexpr int kWaveSplitMaxItems = 2048; // long rows + hub chunks up to which a relation's items get a workgroup each
 
 struct AggParams {
     const int64_t *sptr;   // schedule-ordered row offsets
@@ -62,6 +63,7 @@ struct AggParams {
     int64_t ld_out2;
     int mean;              // divide the row sum by the row's degree
     int hub_only;          // reduce the hub rows only, into out[h] for the h-th hub row of the schedule
+    int wave_split;        // few long rows / hub chunks: four wavefronts per item (agg_wave_split_kernel)
     void *out;
     int64_t ld_out;
     int out_bf16;
@@ -371,14 +373,21 @@ __device__ __forceinline__ void agg_batch_body(const AggParams &p)
 }
 
 // ---- long rows and hub chunks: one wavefront per item ----------------------------------------------
-template <typename T, int EPC, int L, int CPL, bool DUAL>
+// SPLIT: the four wavefronts of a workgroup share one item, wavefront s taking the 64-edge segments s, s + 4,
+// ...; their sums are added through LDS in wavefront order.  For launches of few items (the long rows of a
+// sampled block), where one wavefront per item leaves most of the chip idle behind a serial walk of up to 511
+// edges.
+template <typename T, int EPC, int L, int CPL, bool DUAL, bool SPLIT = false>
 __device__ __forceinline__ void agg_wave_body(const AggParams &p)
 {
     constexpr int G = 64 / L;            // lane groups per wavefront
     constexpr int U = CPL == 2 ? 4 : ((G >= 16) ? 1 : ((G >= 8) ? 2 : ((G >= 4) ? 4 : 8))); // edges in flight per group and step
+    constexpr int NACC = CPL * EPC * (DUAL ? 2 : 1);
+    __shared__ float part_s[SPLIT ? 3 : 1][SPLIT ? NACC : 1][SPLIT ? L : 1]; // wavefronts 1..3, one value per (sum element, lane of group 0)
     const int lane = threadIdx.x & 63;
-    const int64_t w = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (w >= p.n_wave_items) return;     // uniform per wavefront
+    const int ws = SPLIT ? static_cast<int>(threadIdx.x >> 6) : 0;
+    const int64_t w = SPLIT ? static_cast<int64_t>(blockIdx.x) : static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (w >= p.n_wave_items) return;     // uniform per wavefront (per workgroup with SPLIT)
     int64_t e0, e1, row = -1;
     int slot = -1;
     if (w < p.n_hub_chunks) {
@@ -409,7 +418,7 @@ __device__ __forceinline__ void agg_wave_body(const AggParams &p)
             if (DUAL) acc2[c][i] = 0.f;
         }
 
-    for (int64_t base = e0; base < e1; base += 64) {
+    for (int64_t base = e0 + 64 * ws; base < e1; base += SPLIT ? 256 : 64) {
         const int cnt = static_cast<int>(min(static_cast<int64_t>(64), e1 - base));
         int rid = 0;
         float wv = 1.f;
@@ -462,6 +471,30 @@ __device__ __forceinline__ void agg_wave_body(const AggParams &p)
                 acc[c][i] += __shfl_xor(acc[c][i], off, 64);
                 if (DUAL) acc2[c][i] += __shfl_xor(acc2[c][i], off, 64);
             }
+    if constexpr (SPLIT) {
+        if (ws > 0 && g == 0) {
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                for (int i = 0; i < EPC; ++i) {
+                    part_s[ws - 1][c * EPC + i][l] = acc[c][i];
+                    if (DUAL) part_s[ws - 1][CPL * EPC + c * EPC + i][l] = acc2[c][i];
+                }
+        }
+        __syncthreads();
+        if (ws > 0) return;
+        if (g == 0) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                    for (int i = 0; i < EPC; ++i) {
+                        acc[c][i] += part_s[q][c * EPC + i][l];
+                        if (DUAL) acc2[c][i] += part_s[q][CPL * EPC + c * EPC + i][l];
+                    }
+        }
+    }
     if (g != 0) return;
     if (slot >= 0) {
         float *o = p.ws + static_cast<int64_t>(slot) * p.ws_stride;
@@ -550,6 +583,10 @@ template <typename T, int EPC, int L, int CPL, bool DUAL>
 __global__ void __launch_bounds__(256) agg_batch_multi_kernel(AggMulti m) { agg_batch_body<T, EPC, L, CPL, DUAL>(m.p[blockIdx.z]); }
 template <typename T, int EPC, int L, int CPL, bool DUAL>
 __global__ void __launch_bounds__(256) agg_wave_multi_kernel(AggMulti m) { agg_wave_body<T, EPC, L, CPL, DUAL>(m.p[blockIdx.z]); }
+template <typename T, int EPC, int L, int CPL, bool DUAL>
+__global__ void __launch_bounds__(256) agg_wave_split_kernel(AggParams p) { agg_wave_body<T, EPC, L, CPL, DUAL, true>(p); }
+template <typename T, int EPC, int L, int CPL, bool DUAL>
+__global__ void __launch_bounds__(256) agg_wave_split_multi_kernel(AggMulti m) { agg_wave_body<T, EPC, L, CPL, DUAL, true>(m.p[blockIdx.z]); }
 __global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_multi_kernel(AggMulti m) { agg_hub_combine_body(m.p[blockIdx.z]); }
 
 // ---- launch ---------------------------------------------------------------------------------------
@@ -565,9 +602,10 @@ static heta_status launch_pair(const AggParams *ps, int n, int n_super, hipStrea
     if constexpr (!DUAL && EPC > 1) { // the two-weight form exists for the 128-bit paths
         if (ps[0].slot_w2) return launch_pair<T, EPC, L, CPL, true>(ps, n, n_super, st, cost);
     }
+    const bool split = ps[0].wave_split != 0; // the same for every item of a launch (part of the plan's key)
     int64_t wave_blocks = 0, batch_blocks = 0;
     for (int i = 0; i < n; ++i) {
-        wave_blocks = std::max<int64_t>(wave_blocks, (ps[i].n_wave_items + 3) / 4);
+        wave_blocks = std::max<int64_t>(wave_blocks, split ? ps[i].n_wave_items : (ps[i].n_wave_items + 3) / 4);
         batch_blocks = std::max<int64_t>(batch_blocks, (ps[i].batch0[kShortDeg] + 3) / 4);
     }
     if (wave_blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "aggregate: too many long rows");
@@ -576,7 +614,11 @@ static heta_status launch_pair(const AggParams *ps, int n, int n_super, hipStrea
         for (int i = 0; i < n; ++i) m.p[i] = ps[i];
     if (wave_blocks > 0) {
         ProfScope prof(cost.timed ? "agg_wave_kernel" : nullptr, st, cost.wave_bytes, 0);
-        if (n == 1)
+        if (split && n == 1)
+            hipLaunchKernelGGL((agg_wave_split_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)wave_blocks, n_super), dim3(256), 0, st, ps[0]);
+        else if (split)
+            hipLaunchKernelGGL((agg_wave_split_multi_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)wave_blocks, n_super, n), dim3(256), 0, st, m);
+        else if (n == 1)
             hipLaunchKernelGGL((agg_wave_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)wave_blocks, n_super), dim3(256), 0, st, ps[0]);
         else
             hipLaunchKernelGGL((agg_wave_multi_kernel<T, EPC, L, CPL, DUAL>), dim3((unsigned)wave_blocks, n_super, n), dim3(256), 0, st, m);
@@ -619,7 +661,7 @@ struct AggPlan {
     double hub_bytes = 0;
     int64_t n_hub_rows = 0;
     // relations with equal keys run the same kernel instantiation with the same grid.y
-    int key() const { return (in_dt == HETA_F32 ? 0 : 1) | (vec ? 2 : 0) | (dual ? 4 : 0) | (n_chunks << 3); }
+    int key() const { return (in_dt == HETA_F32 ? 0 : 1) | (vec ? 2 : 0) | (dual ? 4 : 0) | (p.wave_split ? 8 : 0) | (n_chunks << 4); }
 };
 
 static bool agg_vectorized(const AggParams &p, heta_dtype in_dt)
@@ -653,6 +695,9 @@ static heta_status plan_aggregate(const Schedule &s, AggParams p, heta_dtype in_
     p.n_hub_chunks = s.n_hub_chunks;
     p.n_hub_rows = s.n_hub_rows;
     p.n_wave_items = s.n_hub_chunks + (p.hub_only ? 0 : n_long_or_hub - s.n_hub_rows);
+    // at most two wavefronts per SIMD's worth of items: spread each over a workgroup (decided per relation, so
+    // that a relation is summed in the same order whatever shares its launch)
+    p.wave_split = p.n_wave_items <= kWaveSplitMaxItems;
     p.n_rows = s.n_rows;
     // short rows: bucket b = degree kShortDeg - 1 - b, in schedule order (descending degree)
     int64_t batches = 0;
