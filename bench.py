@@ -317,7 +317,28 @@ def measure(storage: str, workload: str, args, keep_problem: bool = False):
             d = p.W[r].shape[0]
             by_width += E * d * esz + 4 * E + 8 * (n_t + 1) + n_t * d * esz
             by_width += E * d * esz + 4 * E + 8 * (n_s + 1) + n_s * d * 4
-        roofline["aggregation_all_kernels"] = aggregation_summary(kernels, traffic, by_width)
+        agg_all = aggregation_summary(kernels, traffic, by_width)
+        roofline["aggregation_all_kernels"] = agg_all
+        if roofline["kernel"].startswith("agg_") and agg_all and "by_input_width" in agg_all:
+            # An aggregation kernel leads the step: the record's figure is the conservative one, every aggregation
+            # launch of the step priced at the relations' INPUT widths (a relation projected first is gathered at the
+            # wider output width, and its launches' own byte count would flatter the rate); the leading kernel's
+            # as-run figures stay beside it.
+            roofline["leading_kernel_as_run"] = {k: roofline[k] for k in ("kernel", "achieved", "frac", "traffic",
+                                                                          "moved_over_algorithmic", "avg_launch_ms")
+                                                 if k in roofline}
+            roofline["kernel"] = "aggregation kernels (" + ", ".join(sorted(n for n in kernels if n.startswith("agg_"))) + ")"
+            roofline["achieved"] = agg_all["by_input_width"]["GBps"]
+            roofline["frac"] = agg_all["by_input_width"]["over_hbm_peak"]
+            roofline["achieved_basis"] = ("algorithmic bytes of all aggregation launches of a step at the input widths "
+                                          "(E d_r b + 4 E + 8 (rows + 1) + rows d_r b per relation and direction) / their time")
+            if "counter" in agg_all:
+                roofline["traffic"] = agg_all["counter"]["MB_per_step"] * 1e6
+                roofline["moved_over_algorithmic"] = agg_all["counter"]["MB_per_step"] / agg_all["by_input_width"]["MB_per_step"]
+                roofline["traffic_note"] = ("per step, all aggregation launches: FETCH_SIZE x 2 + WRITE_SIZE (calibrated by a 1 GiB copy), "
+                                            "counted between L2 and the fabric")
+            roofline["avg_launch_ms"] = agg_all["ms_per_step"] / max(1.0, sum(v["launches_per_step"] for n, v in kernels.items()
+                                                                                if n.startswith("agg_")))
     # Each relation's aggregation on its own (standalone calls at the relation's input width, storage
     # type in, fp32 gradients in the backward): algorithmic bytes E*d*b_in + 4E + 8(rows+1) + rows*d*b_out.
     per_relation = []
