@@ -332,6 +332,19 @@ heta_status heta_attn_score(const void *x, heta_dtype dt, int64_t ld_x, int64_t 
 heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int64_t ld_x, int64_t n, int32_t d,
                                 const float *vec, int32_t heads, int32_t per_head, const float *dscore, float *dx,
                                 int64_t ld_dx, float beta, float *dvec, void *hip_stream);
+/* The same for several vector sets over ONE table in one pass (a node type is the source of some relations
+ * and the destination of others; each takes a score of the type's table with vectors of its own):
+ *   scores[s][i, k] = sum_j x[i, j] vecs[s][k][j]                              (per_head = 0 semantics)
+ *   dx[i, j] = beta dx[i, j] + sum_s sum_k dscores[s][i, k] vecs[s][k][j];  dvecs[s][k][j] = sum_i dscores[s][i, k] x[i, j]
+ * vecs / scores / dscores / dvecs: HOST arrays of n_sets device pointers (fp32; [K][d] and [n, K]); dvecs or
+ * single entries of it may be NULL, dx may be NULL.  Tables of at most 128 columns (a multiple of 4, rows
+ * 16-byte aligned for fp32, 8-byte for bf16) with n_sets <= 8 and n_sets * heads <= 32 are read once; other
+ * shapes are served set by set by the calls above, with the same results up to summation order. */
+heta_status heta_attn_score_multi(const void *x, heta_dtype dt, int64_t ld_x, int64_t n, int32_t d, int32_t n_sets,
+                                  const float *const *vecs, int32_t heads, float *const *scores, void *hip_stream);
+heta_status heta_attn_score_bwd_multi(heta_graph *g, const void *x, heta_dtype dt, int64_t ld_x, int64_t n, int32_t d,
+                                      int32_t n_sets, const float *const *vecs, int32_t heads, const float *const *dscores,
+                                      float *dx, int64_t ld_dx, float beta, float *const *dvecs, void *hip_stream);
 /* The source score taken off the input table: since z_u = W^T h_u, el[u, k] = <z_u[k,:], a[k,:]> equals
  * <h_u, wa[k,:]> with wa[k, j] = sum_f W[j, kF + f] a[k, f].  heta_attn_fold writes wa (device fp32
  * [K][d_in]); el is then heta_attn_score(H0_s, wa, per_head = 0) - read from the input table, so in the

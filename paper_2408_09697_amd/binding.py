@@ -30,7 +30,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "het
            "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_calibration_mfma", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
            "heta_cross_rel_project_wgrad", "heta_sparse_adam", "heta_project_batch",
-           "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd",
+           "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd", "heta_attn_score_multi", "heta_attn_score_bwd_multi",
            "heta_rel_attn_fwd", "heta_rel_attn_bwd", "heta_sample_neighbors", "heta_unique_relabel",
            "heta_cross_rel_aggregate_project", "heta_meta_partition", "heta_sample_neighbors_batch",
            "heta_unique_relabel_batch", "heta_rel_aggregate_fwd_noalloc", "heta_attn_fold", "heta_attn_fold_bwd",
@@ -692,6 +692,53 @@ def heta_attn_score_bwd(g: Graph, x: torch.Tensor, vec: torch.Tensor, per_head: 
                                  heads, int(bool(per_head)), _scores(dscore, "dscore", x.shape[0], heads),
                                  _dev(dx, "dx", torch.float32), _ld(dx) if dx is not None else 0, beta,
                                  _dev(dvec, "dvec", torch.float32), _stream(stream)))
+
+
+def heta_attn_score_multi(x: torch.Tensor, vecs: Sequence[torch.Tensor], scores: Sequence[torch.Tensor],
+                          d: Optional[int] = None, stream=None) -> None:
+    """scores[s] = x @ vecs[s]^T for every set s in one pass over x (vecs[s]: [heads, d] fp32)."""
+    if not vecs:
+        return
+    d = x.shape[1] if d is None else d
+    heads = vecs[0].shape[0]
+    for v in vecs:
+        if not v.is_contiguous() or tuple(v.shape) != (heads, d):
+            raise HetaError(HETA_ERR_SHAPE, "every vec must be contiguous [heads, d]")
+    L = load_library()
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.heta_attn_score_multi.argtypes = [vp, i32, i64, i64, i32, i32, vp, i32, vp, vp]
+    sc = (ctypes.c_void_p * len(vecs))(*[_scores(t, "score", x.shape[0], heads) for t in scores])
+    _check(L.heta_attn_score_multi(_dev(x, "x"), _dt(x), _ld(x), x.shape[0], d, len(vecs),
+                                   _ptr_array(vecs, "vec", torch.float32), heads, sc, _stream(stream)))
+
+
+def heta_attn_score_bwd_multi(g: Graph, x: torch.Tensor, vecs: Sequence[torch.Tensor], dscores: Sequence[torch.Tensor],
+                              dx: Optional[torch.Tensor] = None, beta: float = 0.0,
+                              dvecs: Optional[Sequence[Optional[torch.Tensor]]] = None, d: Optional[int] = None,
+                              stream=None) -> None:
+    """dx = beta dx + sum_s dscores[s] @ vecs[s];  dvecs[s] = dscores[s]^T @ x, all in one pass over x."""
+    if not vecs:
+        return
+    d = x.shape[1] if d is None else d
+    heads = vecs[0].shape[0]
+    for v in vecs:
+        if not v.is_contiguous() or tuple(v.shape) != (heads, d):
+            raise HetaError(HETA_ERR_SHAPE, "every vec must be contiguous [heads, d]")
+    if dvecs is not None:
+        for v, dv in zip(vecs, dvecs):
+            if dv is not None and (not dv.is_contiguous() or dv.shape != v.shape):
+                raise HetaError(HETA_ERR_SHAPE, "dvec must be contiguous and shaped like vec")
+    if dx is not None and (dx.shape[0] < x.shape[0] or dx.shape[1] < d):
+        raise HetaError(HETA_ERR_SHAPE, "dx is smaller than x")
+    L = load_library()
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.heta_attn_score_bwd_multi.argtypes = [vp, vp, i32, i64, i64, i32, i32, vp, i32, vp, vp, i64, f32, vp, vp]
+    ds = (ctypes.c_void_p * len(vecs))(*[_scores(t, "dscore", x.shape[0], heads) for t in dscores])
+    dv = None if dvecs is None else (ctypes.c_void_p * len(vecs))(*[_dev(t, "dvec", torch.float32) for t in dvecs])
+    _check(L.heta_attn_score_bwd_multi(g.handle, _dev(x, "x"), _dt(x), _ld(x), x.shape[0], d, len(vecs),
+                                       _ptr_array(vecs, "vec", torch.float32), heads, ds,
+                                       _dev(dx, "dx", torch.float32), _ld(dx) if dx is not None else 0, beta, dv,
+                                       _stream(stream)))
 
 
 def heta_rel_attn_fwd(g: Graph, rel: int, z: torch.Tensor, el: torch.Tensor, er: torch.Tensor, slope: float,

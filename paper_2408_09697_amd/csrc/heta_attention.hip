@@ -820,6 +820,198 @@ __global__ void __launch_bounds__(1024) attn_slab_sum_kernel(const float *part, 
 }
 
 
+// ---- scores of several vector sets in one pass over the table -------------------------------------------
+// A node type is the source of some relations and the destination of others, and every one of them takes
+// a row score <x_i, vec_k> of the same table with vectors of its own (el with W_r a_r, er with q_r).  One
+// pass serves them all: 32 lanes per row (two rows per wavefront), a lane owns four columns and keeps its
+// four columns of all (set, head) vectors in registers, so a row costs one 16-byte load per lane, 4 FMAs
+// per vector, and one reduce-scatter butterfly after which lane v holds score v.  Tables of at most 128
+// columns, at most 32 vectors.  The backward runs the same way: dx[i, :] = sum_v dscore_v[i] vec_v (the
+// 32 scalars of a row are broadcast by lane shuffles), dvec_v = sum_i dscore_v[i] x[i, :] through
+// per-slab partial sums added in slab order.
+constexpr int kMultiSets = 8, kMultiVecs = 32, kMultiCols = 128;
+struct ScoreMulti {
+    const float *vec[kMultiSets]; // [K][d] each
+    float *score[kMultiSets];     // [n][K] each: written by the forward, read (dscore) by the backward
+    float *dvec[kMultiSets];      // [K][d] each, or null
+    int n_sets, K, NV;            // NV = n_sets * K
+};
+
+// pointer j of a table of kMultiSets pointers for a lane-dependent j (a select chain: indexing the kernel
+// arguments by a vector register would move them to scratch memory)
+__device__ __forceinline__ float *pick(float *const (&tab)[kMultiSets], int j)
+{
+    float *p = tab[0];
+#pragma unroll
+    for (int q = 1; q < kMultiSets; ++q) p = j == q ? tab[q] : p;
+    return p;
+}
+
+template <typename T> __device__ __forceinline__ void load4(const T *p, float f[4]);
+template <> __device__ __forceinline__ void load4<float>(const float *p, float f[4])
+{
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+}
+template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t *p, float f[4])
+{
+    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+
+// this lane's four columns (4 l .. 4 l + 3) of the first NVC vectors; zero beyond d or beyond the NV vectors given
+template <int NVC> __device__ __forceinline__ void load_vectors(const ScoreMulti &m, int d, int l, float v[NVC][4])
+{
+#pragma unroll
+    for (int vi = 0; vi < NVC; ++vi) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[vi][c] = 0.f;
+        if (vi < m.NV && 4 * l < d) {
+            const float4 q = *reinterpret_cast<const float4 *>(m.vec[vi / m.K] + static_cast<int64_t>(vi % m.K) * d + 4 * l);
+            v[vi][0] = q.x; v[vi][1] = q.y; v[vi][2] = q.z; v[vi][3] = q.w;
+        }
+    }
+}
+
+// one step of the reduce-scatter over a row's 32 lanes: of its 2 CNT values a lane keeps the half its lane bit
+// CNT selects and adds the partner lane's copy of that half (register indices are compile-time constants)
+template <int CNT> __device__ __forceinline__ void reduce_scatter_step(float (&acc)[kMultiVecs], int l)
+{
+    const bool up = (l & CNT) != 0;
+#pragma unroll
+    for (int i = 0; i < CNT; ++i) {
+        const float send = up ? acc[i] : acc[i + CNT];
+        const float keep = up ? acc[i + CNT] : acc[i];
+        acc[i] = keep + __shfl_xor(send, CNT, 64);
+    }
+}
+
+template <typename T, int NVC>
+__global__ void __launch_bounds__(256) attn_score_multi_kernel(const T *x, int64_t ld_x, int64_t n, int d, ScoreMulti m)
+{
+    const int lane = threadIdx.x & 63, l = lane & 31, half = lane >> 5;
+    float v[NVC][4];
+    load_vectors<NVC>(m, d, l, v);
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6), n_waves = static_cast<int64_t>(gridDim.x) * 4;
+    for (int64_t r0 = wave * 2; r0 < n; r0 += n_waves * 2) { // uniform per wavefront
+        const int64_t r = r0 + half;
+        float xv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (r < n && 4 * l < d) load4<T>(x + r * ld_x + 4 * l, xv);
+        float acc[kMultiVecs];
+#pragma unroll
+        for (int vi = 0; vi < kMultiVecs; ++vi)
+            acc[vi] = vi < NVC ? (xv[0] * v[vi < NVC ? vi : 0][0] + xv[1] * v[vi < NVC ? vi : 0][1]) +
+                                     (xv[2] * v[vi < NVC ? vi : 0][2] + xv[3] * v[vi < NVC ? vi : 0][3])
+                               : 0.f;
+        // reduce-scatter over the 32 lanes of the row: each step halves the values a lane keeps (the half its
+        // lane bit selects) and adds the partner's; after five steps lane v holds the whole sum of value v
+        reduce_scatter_step<16>(acc, l);
+        reduce_scatter_step<8>(acc, l);
+        reduce_scatter_step<4>(acc, l);
+        reduce_scatter_step<2>(acc, l);
+        reduce_scatter_step<1>(acc, l);
+        if (r < n && l < m.NV) pick(m.score, l / m.K)[r * m.K + l % m.K] = acc[0];
+    }
+}
+
+template <int NVC>
+__global__ void __launch_bounds__(256) attn_score_bwd_multi_input_kernel(int64_t n, int d, ScoreMulti m, float *dx, int64_t ld_dx, float beta)
+{
+    const int lane = threadIdx.x & 63, l = lane & 31, half = lane >> 5;
+    float v[NVC][4];
+    load_vectors<NVC>(m, d, l, v);
+    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6), n_waves = static_cast<int64_t>(gridDim.x) * 4;
+    for (int64_t r0 = wave * 2; r0 < n; r0 += n_waves * 2) {
+        const int64_t r = r0 + half;
+        float ds = 0.f;
+        if (r < n && l < m.NV) ds = pick(m.score, l / m.K)[r * m.K + l % m.K];
+        float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int vi = 0; vi < NVC; ++vi) {
+            const float sv = __shfl(ds, (lane & 32) | vi, 64);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] = fmaf(sv, v[vi][c], o[c]);
+        }
+        if (r < n && 4 * l < d) {
+            float4 *dst = reinterpret_cast<float4 *>(dx + r * ld_dx + 4 * l);
+            float4 w4 = make_float4(o[0], o[1], o[2], o[3]);
+            if (beta != 0.f) {
+                const float4 old = *dst;
+                w4.x += old.x; w4.y += old.y; w4.z += old.z; w4.w += old.w;
+            }
+            *dst = w4;
+        }
+    }
+}
+
+// part[slab][v][128]: the slab's sum over its rows of dscore_v[i] x[i, :]; the two rows a wavefront has in
+// flight are added first (lane shuffle), then the four wavefronts in wavefront order through LDS
+template <typename T, int NVC>
+__global__ void __launch_bounds__(256) attn_score_bwd_multi_param_kernel(const T *x, int64_t ld_x, int64_t n, int d, ScoreMulti m, float *part)
+{
+    __shared__ float buf[NVC][kMultiCols];
+    const int lane = threadIdx.x & 63, l = lane & 31, half = lane >> 5, w = threadIdx.x >> 6;
+    const int64_t slab = blockIdx.x;
+    const int64_t i0 = slab * kSlabRows, i1 = min(n, i0 + kSlabRows);
+    float acc[NVC][4];
+#pragma unroll
+    for (int vi = 0; vi < NVC; ++vi)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[vi][c] = 0.f;
+    for (int64_t r0 = i0 + 2 * w; r0 < i1; r0 += 8) {
+        const int64_t r = r0 + half;
+        float xv[4] = {0.f, 0.f, 0.f, 0.f}, ds = 0.f;
+        if (r < i1 && 4 * l < d) load4<T>(x + r * ld_x + 4 * l, xv);
+        if (r < i1 && l < m.NV) ds = pick(m.score, l / m.K)[r * m.K + l % m.K];
+#pragma unroll
+        for (int vi = 0; vi < NVC; ++vi) {
+            const float sv = __shfl(ds, (lane & 32) | vi, 64);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[vi][c] = fmaf(sv, xv[c], acc[vi][c]);
+        }
+    }
+#pragma unroll
+    for (int vi = 0; vi < NVC; ++vi)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[vi][c] += __shfl_xor(acc[vi][c], 32, 64);
+    for (int q = 0; q < 4; ++q) { // wavefront q adds its sums to the buffer, in order
+        if (w == q && half == 0) {
+#pragma unroll
+            for (int vi = 0; vi < NVC; ++vi)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) buf[vi][4 * l + c] = (q == 0 ? 0.f : buf[vi][4 * l + c]) + acc[vi][c];
+        }
+        __syncthreads();
+    }
+    float *o = part + slab * (NVC * kMultiCols);
+    for (int t = threadIdx.x; t < NVC * kMultiCols; t += 256) o[t] = (&buf[0][0])[t];
+}
+
+// dvec_v[c] = sum over the slabs, in slab order per wavefront and wavefront order through LDS (as attn_slab_sum_kernel)
+__global__ void __launch_bounds__(1024) attn_multi_slab_sum_kernel(const float *part, int64_t n_slabs, int nvc, int d, ScoreMulti m)
+{
+    __shared__ float red[16][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t elems = static_cast<int64_t>(nvc) * kMultiCols;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 64 + lane;
+    float a = 0.f;
+    if (t < elems) {
+#pragma unroll 4
+        for (int64_t s = w; s < n_slabs; s += 16) a += part[s * elems + t];
+    }
+    red[w][lane] = a;
+    __syncthreads();
+    const int vi = static_cast<int>(t / kMultiCols), c = static_cast<int>(t % kMultiCols);
+    float *out = (t < elems && vi < m.NV) ? pick(m.dvec, vi / m.K) : nullptr;
+    if (w == 0 && out && c < d) {
+        float r = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) r += red[i][lane];
+        out[static_cast<int64_t>(vi % m.K) * d + c] = r;
+    }
+}
+
 // ---- the source score taken off the input table ------------------------------------------------------
 // el[u, k] = <z_u[k, :], a[k, :]> with z_u = W^T h_u equals <h_u, wa[k, :]> with wa[k, j] = sum_f W[j, kF + f] a[k, f]:
 // the scores then come from the (narrower, never rounded) input table instead of the stored projection.
@@ -987,6 +1179,127 @@ heta_status heta_attn_score_bwd(heta_graph *g, const void *x, heta_dtype dt, int
             hipLaunchKernelGGL(attn_slab_sum_kernel, dim3((unsigned)((elems + 63) / 64)), dim3(1024), 0, st, part, n_slabs, elems, dvec);
             HETA_LAUNCH_CHECK("attn_slab_sum_kernel");
         }
+    }
+    return HETA_OK;
+}
+
+// whether the one-pass kernels take this table and these vector sets
+static bool multi_ok(const void *x, heta_dtype dt, int64_t ld_x, int32_t d, int32_t n_sets, int32_t heads, const float *const *vecs)
+{
+    if (d > kMultiCols || d % 4 || n_sets > kMultiSets || n_sets * heads > kMultiVecs) return false;
+    if (reinterpret_cast<uintptr_t>(x) % (4 * dtype_size(dt)) || ld_x % 4) return false;
+    for (int j = 0; j < n_sets; ++j)
+        if (!aligned16(vecs[j])) return false;
+    return true;
+}
+
+heta_status heta_attn_score_multi(const void *x, heta_dtype dt, int64_t ld_x, int64_t n, int32_t d, int32_t n_sets,
+                                  const float *const *vecs, int32_t heads, float *const *scores, void *hip_stream)
+{
+    const char *who = "heta_attn_score_multi";
+    if (n_sets < 0 || (n_sets > 0 && (!vecs || !scores))) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n_sets == 0) return HETA_OK;
+    for (int j = 0; j < n_sets; ++j)
+        if (!vecs[j] || (n > 0 && !scores[j])) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n > 0 && !x) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (!valid_dtype(dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
+    if (n < 0 || d <= 0 || ld_x < d || heads <= 0 || heads > kMaxHeads)
+        return fail(HETA_ERR_SHAPE, "%s: bad shape (n=%lld d=%d ld=%lld heads=%d)", who, (long long)n, d, (long long)ld_x, heads);
+    hipStream_t st = as_stream(hip_stream);
+    if (!multi_ok(x, dt, ld_x, d, n_sets, heads, vecs)) { // shapes the one-pass kernel does not take: set by set
+        for (int j = 0; j < n_sets; ++j) {
+            heta_status e = heta_attn_score(x, dt, ld_x, n, d, vecs[j], heads, 0, scores[j], hip_stream);
+            if (e != HETA_OK) return e;
+        }
+        return HETA_OK;
+    }
+    if (n == 0) return HETA_OK;
+    ScoreMulti m{};
+    m.n_sets = n_sets;
+    m.K = heads;
+    m.NV = n_sets * heads;
+    for (int j = 0; j < n_sets; ++j) {
+        m.vec[j] = vecs[j];
+        m.score[j] = scores[j];
+    }
+    const int64_t blocks = std::min<int64_t>((n + 7) / 8, 256 * 8);
+    ProfScope prof("attn_score_multi_kernel", st, static_cast<double>(n) * (d * dtype_size(dt) + 4.0 * m.NV), 0);
+#define HETA_SM(TT, NVC) hipLaunchKernelGGL((attn_score_multi_kernel<TT, NVC>), dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const TT *>(x), ld_x, n, (int)d, m)
+#define HETA_SM_T(TT) do { if (m.NV <= 8) HETA_SM(TT, 8); else if (m.NV <= 16) HETA_SM(TT, 16); else if (m.NV <= 24) HETA_SM(TT, 24); else HETA_SM(TT, 32); } while (0)
+    if (dt == HETA_F32) HETA_SM_T(float);
+    else HETA_SM_T(bf16_t);
+#undef HETA_SM_T
+#undef HETA_SM
+    HETA_LAUNCH_CHECK("attn_score_multi_kernel");
+    return HETA_OK;
+}
+
+heta_status heta_attn_score_bwd_multi(heta_graph *g, const void *x, heta_dtype dt, int64_t ld_x, int64_t n, int32_t d,
+                                      int32_t n_sets, const float *const *vecs, int32_t heads, const float *const *dscores,
+                                      float *dx, int64_t ld_dx, float beta, float *const *dvecs, void *hip_stream)
+{
+    const char *who = "heta_attn_score_bwd_multi";
+    if (!g || n_sets < 0 || (n_sets > 0 && (!vecs || !dscores))) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n_sets == 0) return HETA_OK;
+    for (int j = 0; j < n_sets; ++j)
+        if (!vecs[j] || (n > 0 && !dscores[j])) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n > 0 && !x) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
+    if (!valid_dtype(dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
+    if (n < 0 || d <= 0 || ld_x < d || heads <= 0 || heads > kMaxHeads || (dx && ld_dx < d))
+        return fail(HETA_ERR_SHAPE, "%s: bad shape (n=%lld d=%d heads=%d)", who, (long long)n, d, heads);
+    if (beta != 0.f && beta != 1.f) return fail(HETA_ERR_SHAPE, "%s: beta must be 0 or 1", who);
+    hipStream_t st = as_stream(hip_stream);
+    const bool dx_ok = !dx || (aligned16(dx) && ld_dx % 4 == 0);
+    if (!multi_ok(x, dt, ld_x, d, n_sets, heads, vecs) || !dx_ok) { // set by set, accumulating into dx
+        for (int j = 0; j < n_sets; ++j) {
+            heta_status e = heta_attn_score_bwd(g, x, dt, ld_x, n, d, vecs[j], heads, 0, dscores[j], dx, ld_dx,
+                                                j == 0 ? beta : 1.f, dvecs ? dvecs[j] : nullptr, hip_stream);
+            if (e != HETA_OK) return e;
+        }
+        return HETA_OK;
+    }
+    ScoreMulti m{};
+    m.n_sets = n_sets;
+    m.K = heads;
+    m.NV = n_sets * heads;
+    bool any_dvec = false;
+    for (int j = 0; j < n_sets; ++j) {
+        m.vec[j] = vecs[j];
+        m.score[j] = const_cast<float *>(dscores[j]);
+        m.dvec[j] = dvecs ? dvecs[j] : nullptr;
+        any_dvec = any_dvec || m.dvec[j];
+    }
+    const int nvc = m.NV <= 8 ? 8 : m.NV <= 16 ? 16 : m.NV <= 24 ? 24 : 32;
+    if (dx && n > 0) {
+        const int64_t blocks = std::min<int64_t>((n + 7) / 8, 256 * 8);
+        ProfScope prof("attn_score_bwd_input_kernel", st, static_cast<double>(n) * (d * (beta != 0.f ? 8.0 : 4.0) + 4.0 * m.NV), 0);
+#define HETA_SI(NVC) hipLaunchKernelGGL((attn_score_bwd_multi_input_kernel<NVC>), dim3((unsigned)blocks), dim3(256), 0, st, n, (int)d, m, dx, ld_dx, beta)
+        if (nvc == 8) HETA_SI(8); else if (nvc == 16) HETA_SI(16); else if (nvc == 24) HETA_SI(24); else HETA_SI(32);
+#undef HETA_SI
+        HETA_LAUNCH_CHECK("attn_score_bwd_multi_input_kernel");
+    }
+    if (any_dvec) {
+        const int64_t n_slabs = (n + kSlabRows - 1) / kSlabRows;
+        if (n_slabs == 0) {
+            for (int j = 0; j < n_sets; ++j)
+                if (m.dvec[j]) HETA_HIP(hipMemsetAsync(m.dvec[j], 0, static_cast<size_t>(heads) * d * sizeof(float), st));
+            return HETA_OK;
+        }
+        if (n_slabs > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "%s: too many rows", who);
+        heta_status e = ensure_attn(g, static_cast<size_t>(n_slabs) * nvc * kMultiCols * sizeof(float));
+        if (e != HETA_OK) return e;
+        float *part = static_cast<float *>(g->d_attn);
+        ProfScope prof("attn_score_bwd_param_kernel", st, static_cast<double>(n) * (d * dtype_size(dt) + 4.0 * m.NV), 0);
+#define HETA_SP(TT, NVC) hipLaunchKernelGGL((attn_score_bwd_multi_param_kernel<TT, NVC>), dim3((unsigned)n_slabs), dim3(256), 0, st, static_cast<const TT *>(x), ld_x, n, (int)d, m, part)
+#define HETA_SP_T(TT) do { if (nvc == 8) HETA_SP(TT, 8); else if (nvc == 16) HETA_SP(TT, 16); else if (nvc == 24) HETA_SP(TT, 24); else HETA_SP(TT, 32); } while (0)
+        if (dt == HETA_F32) HETA_SP_T(float);
+        else HETA_SP_T(bf16_t);
+#undef HETA_SP_T
+#undef HETA_SP
+        HETA_LAUNCH_CHECK("attn_score_bwd_multi_param_kernel");
+        const int64_t elems = static_cast<int64_t>(nvc) * kMultiCols;
+        hipLaunchKernelGGL(attn_multi_slab_sum_kernel, dim3((unsigned)((elems + 63) / 64)), dim3(1024), 0, st, part, n_slabs, nvc, (int)d, m);
+        HETA_LAUNCH_CHECK("attn_multi_slab_sum_kernel");
     }
     return HETA_OK;
 }

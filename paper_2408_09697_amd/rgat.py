@@ -6,14 +6,15 @@ module allocates device buffers with torch and issues the C-ABI calls; it comput
 itself.  Per relation r from source type s to destination type t:
 
     Z_r  = H0_s W_r                         heta_project_batch (all relations leaving s in one launch)
-    el_r = <Z_r[u, head k], a_r[k]>         = <H0_s[u], (W_r a_r)[k]>: heta_attn_fold + heta_attn_score on the
-                                            input table (narrower than Z_r, and never rounded to the storage type)
-    er_r = <H0_t[v], q_r[k]>                heta_attn_score (whole row)
+    el_r = <Z_r[u, head k], a_r[k]>         = <H0_s[u], (W_r a_r)[k]>: heta_attn_fold, then a score of the input
+                                            table (narrower than Z_r, and never rounded to the storage type)
+    er_r = <H0_t[v], q_r[k]>                a score of the destination type's table; all scores of one table in
+                                            one pass (heta_attn_score_multi)
     O_r  = edge-softmax weighted sum of Z_r heta_rel_attn_fwd
     H_t  = ReLU(sum_r O_r)                  heta_cross_rel_reduce
 
 and the backward runs the same chain in reverse (heta_act_bwd, heta_rel_attn_bwd,
-heta_attn_score_bwd, heta_project_wgrad_batch, heta_attn_fold_bwd, heta_project_sum).
+heta_attn_score_bwd_multi, heta_project_wgrad_batch, heta_attn_fold_bwd, heta_project_sum).
 """
 from __future__ import annotations
 
@@ -24,6 +25,7 @@ import torch
 from . import binding as hb
 
 _MAX_BATCH = 8  # products per batched projection launch
+_MAX_SETS = 8   # score vector sets per one-pass score call
 
 
 class RgatLayer:
@@ -52,6 +54,12 @@ class RgatLayer:
             s, t, _ = graph.rels[r]
             self.rels_into.setdefault(t, []).append(r)
             self.rels_from.setdefault(s, []).append(r)
+        # (relation, is the source side) for every score taken off a node type's table
+        self._score_sets: Dict[int, List] = {}
+        for r in self.rels:
+            s, t, _ = graph.rels[r]
+            self._score_sets.setdefault(s, []).append((r, True))
+            self._score_sets.setdefault(t, []).append((r, False))
         store = self.W[self.rels[0]].dtype
         self.two_terms = store == torch.bfloat16
 
@@ -93,10 +101,16 @@ class RgatLayer:
                 hb.heta_project_batch([self.tables[s]] * len(part), [self.W[r] for r in part],
                                       [self.Z[r] for r in part], stream=stream)
         for r in self.rels:
-            s, t, _ = g.rels[r]
             hb.heta_attn_fold(self.W[r], self.a[r], self.wa[r], stream=stream)
-            hb.heta_attn_score(self.tables[s], self.wa[r], False, self.el[r], stream=stream)
-            hb.heta_attn_score(self.tables[t], self.q[r], False, self.er[r], stream=stream)
+        # every score of a node type's table in one pass over it: el of the relations leaving the type, er of
+        # those entering it
+        for t, sets in self._score_sets.items():
+            for i in range(0, len(sets), _MAX_SETS):
+                part = sets[i:i + _MAX_SETS]
+                hb.heta_attn_score_multi(self.tables[t], [self.wa[r] if src else self.q[r] for r, src in part],
+                                         [self.el[r] if src else self.er[r] for r, src in part], stream=stream)
+        for r in self.rels:
+            s, t, _ = g.rels[r]
             hb.heta_rel_attn_fwd(g, r, self.Z[r], self.el[r], self.er[r], self.slope, self.O[r], beta=0.0,
                                  smax=self.smax[r], sinv=self.sinv[r], out_pos=self.Opos[r], stream=stream)
         for t, rs in self.rels_into.items():
@@ -116,14 +130,16 @@ class RgatLayer:
             hb.heta_rel_attn_bwd(g, r, self.Z[r], self.el[r], self.er[r], self.slope, self.smax[r], self.sinv[r],
                                  self.O[r], grads[t], self.dZ[r], self.d_el[r], self.d_er[r], o_pos=self.Opos[r],
                                  stream=stream)
-            # el = <H0_s, wa>: its gradient reaches the source type's table and, through wa, W_r and a_r
-            hb.heta_attn_score_bwd(g, self.tables[s], self.wa[r], False, self.d_el[r], dx=self.dH0[s],
-                                   beta=1.0 if s in written else 0.0, dvec=self.dwa[r], stream=stream)
-            written.add(s)
-            # er = <H0_t, q>: its gradient reaches the destination type's table and gives dq
-            hb.heta_attn_score_bwd(g, self.tables[t], self.q[r], False, self.d_er[r], dx=self.dH0[t],
-                                   beta=1.0 if t in written else 0.0, dvec=self.dq[r], stream=stream)
-            written.add(t)
+        # el = <H0_s, wa> reaches the source type's table and, through wa, W_r and a_r; er = <H0_t, q> reaches the
+        # destination type's table and gives dq: per node type, all of them in one pass over its table
+        for t, sets in self._score_sets.items():
+            for i in range(0, len(sets), _MAX_SETS):
+                part = sets[i:i + _MAX_SETS]
+                hb.heta_attn_score_bwd_multi(g, self.tables[t], [self.wa[r] if src else self.q[r] for r, src in part],
+                                             [self.d_el[r] if src else self.d_er[r] for r, src in part], dx=self.dH0[t],
+                                             beta=1.0 if t in written else 0.0,
+                                             dvecs=[self.dwa[r] if src else self.dq[r] for r, src in part], stream=stream)
+                written.add(t)
         for s, rs in self.rels_from.items():
             for i in range(0, len(rs), _MAX_BATCH):
                 part = rs[i:i + _MAX_BATCH]

@@ -71,6 +71,47 @@ def test_attn_score_and_its_backward(n, d, heads, pad, per_head, storage):
     graph.destroy()
 
 
+@pytest.mark.parametrize("n,d,heads,n_sets,pad", [(3000, 128, 4, 6, 4), (1001, 128, 4, 8, 4), (700, 64, 1, 3, 4), (513, 100, 3, 5, 4),
+                                                  (40, 128, 16, 2, 4), (1, 8, 2, 1, 4),
+                                                  # shapes served set by set: wide table, unaligned rows, too many vectors
+                                                  (300, 256, 4, 3, 4), (200, 30, 3, 2, 1), (150, 128, 8, 6, 4)])
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_scores_of_several_vector_sets_in_one_pass(n, d, heads, n_sets, pad, storage):
+    g = rng.stream("tests", f"multi_score{n}x{d}x{heads}x{n_sets}")
+    x = g.standard_normal((n, d)).astype(np.float32)
+    if storage == "bf16":
+        x = rng.round_to_bf16(x)
+    x64 = x.astype(np.float64)
+    vecs = [g.standard_normal((heads, d)).astype(np.float32) for _ in range(n_sets)]
+    xd = dev_table(x, storage, (8 if storage == "bf16" else 4) if pad > 1 else 1)
+    scores = [torch.full((n, heads), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n_sets)]
+    heta.heta_attn_score_multi(xd, [up(v) for v in vecs], scores)
+    for v, sc in zip(vecs, scores):
+        assert_rows_close(host(sc), x64 @ v.astype(np.float64).T, 1e-4, "score")
+    ds = [g.standard_normal((n, heads)).astype(np.float32) for _ in range(n_sets)]
+    dx0 = g.standard_normal((n, d)).astype(np.float32)
+    graph = heta.heta_graph_create([(4, 4, 0)], [(0, 0, np.zeros(5, dtype=np.int64), np.zeros(0, dtype=np.int32))])
+    try:
+        rdx = sum(a.astype(np.float64) @ v.astype(np.float64) for a, v in zip(ds, vecs))
+        for beta in (0.0, 1.0):
+            dx = dev_table(dx0, "f32", 4 if pad > 1 else 1)
+            dvecs = [torch.full(v.shape, 7.0, dtype=torch.float32, device="cuda") for v in vecs]
+            dvecs[-1] = None if n_sets > 1 else dvecs[-1]  # a set whose vector gradient is not wanted
+            heta.heta_attn_score_bwd_multi(graph, xd, [up(v) for v in vecs], [up(a) for a in ds], dx=dx, beta=beta, dvecs=dvecs)
+            assert_rows_close(host(dx), rdx + beta * dx0, 1e-4, "dx")
+            for a, dv in zip(ds, dvecs):
+                if dv is not None:
+                    assert_rows_close(host(dv), a.astype(np.float64).T @ x64, 1e-4, "dvec")
+        # run to run the same bits (slab partials are added in a fixed order)
+        again = [torch.empty_like(v) if v is not None else None for v in dvecs]
+        heta.heta_attn_score_bwd_multi(graph, xd, [up(v) for v in vecs], [up(a) for a in ds], dvecs=again)
+        for u, w in zip(dvecs, again):
+            if u is not None:
+                assert torch.equal(u.view(torch.int32), w.view(torch.int32))
+    finally:
+        graph.destroy()
+
+
 # ---- one relation ---------------------------------------------------------------------------------------
 
 def _relation_case(kind, n_src, n_dst, n_edges):
