@@ -462,6 +462,10 @@ struct DotParams {
     float scale;          // out = scale * <x, y> - corr
     const float *corr;
     float *out;
+    // optional second operand with rows of its own (per_head only): out2 = scale2 * <x, y2>, in the same pass over x
+    const void *y2;
+    float scale2;
+    float *out2;
 };
 
 template <typename T> __device__ __forceinline__ float ld1(const T *p);
@@ -537,11 +541,16 @@ __global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int 
         }
     }
     if (p.per_head) {
+      for (int pass = 0; pass < (p.y2 ? 2 : 1); ++pass) { // uniform: the second operand's rows against the same x registers
+        const void *yp = pass ? p.y2 : p.y;
+        float *outp = pass ? p.out2 : p.out;
+        const float scl = pass ? p.scale2 : p.scale;
+        const float *corrp = pass ? nullptr : p.corr;
         float part[R][T];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int64_t i = first + static_cast<int64_t>(r) * G;
-            const TY *y = static_cast<const TY *>(p.y) + (live[r] ? i : 0) * p.ld_y;
+            const TY *y = static_cast<const TY *>(yp) + (live[r] ? i : 0) * p.ld_y;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const int c = l + L * t;
@@ -560,7 +569,7 @@ __global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int 
                     const int c = l + L * t;
                     if (live[r] && c < n_chunks && (l & (cph - 1)) == 0) {
                         const int k = c / cph;
-                        p.out[i * p.K + k] = p.scale * part[r][t] - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                        outp[i * p.K + k] = scl * part[r][t] - (corrp ? corrp[i * p.K + k] : 0.f);
                     }
                 }
             } else {
@@ -572,12 +581,13 @@ __global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int 
                     if ((t + 1) % m == 0) {
                         for (int off = L >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
                         const int k = t / m;
-                        if (live[r] && l == 0 && k < p.K) p.out[i * p.K + k] = p.scale * acc - (p.corr ? p.corr[i * p.K + k] : 0.f);
+                        if (live[r] && l == 0 && k < p.K) outp[i * p.K + k] = scl * acc - (corrp ? corrp[i * p.K + k] : 0.f);
                         acc = 0.f;
                     }
                 }
             }
         }
+      }
     } else {
         // y_k = p.y + k d is shared by every row (ld_y = 0): one load per k serves the R rows
         for (int k = 0; k < p.K; ++k) {
@@ -603,17 +613,45 @@ __global__ void __launch_bounds__(256) attn_rowdot_fast_kernel(DotParams p, int 
     }
 }
 
+// a[i] -= b[i]
+__global__ void __launch_bounds__(256) attn_sub_kernel(float *a, const float *b, int64_t n)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) a[i] -= b[i];
+}
+
 template <typename TX, typename TY>
 heta_status launch_rowdot_t(const DotParams &p, hipStream_t st)
 {
     if (p.n == 0) return HETA_OK;
     const size_t sx = sizeof(TX), sy = sizeof(TY);
+    if (p.y2) { // only the one-pass kernel takes a second operand: anything else runs as two launches
+        const int nc = p.d / 4, cph2 = p.F / 4;
+        int L2 = 1;
+        while (L2 < nc && L2 < 64) L2 <<= 1;
+        const int T2 = (nc + L2 - 1) / L2;
+        const bool one_pass = p.per_head && p.ld_y && (reinterpret_cast<uintptr_t>(p.x) % (4 * sx) == 0) && (p.ld_x % 4 == 0) &&
+                              (reinterpret_cast<uintptr_t>(p.y) % (4 * sy) == 0) && (reinterpret_cast<uintptr_t>(p.y2) % (4 * sy) == 0) &&
+                              (p.ld_y % 4 == 0) && (p.d % 4 == 0) && (p.F % 4 == 0) && T2 <= 4 && cph2 > 0 &&
+                              (cph2 & (cph2 - 1)) == 0 && (cph2 <= L2 || T2 % (cph2 / L2) == 0);
+        if (!one_pass) {
+            DotParams a = p, b = p;
+            a.y2 = nullptr;
+            b.y = p.y2;
+            b.y2 = nullptr;
+            b.scale = p.scale2;
+            b.corr = nullptr;
+            b.out = p.out2;
+            heta_status e = launch_rowdot_t<TX, TY>(a, st);
+            return e != HETA_OK ? e : launch_rowdot_t<TX, TY>(b, st);
+        }
+    }
     const bool vec = (reinterpret_cast<uintptr_t>(p.x) % (4 * sx) == 0) && (p.ld_x % 4 == 0) &&
                      (reinterpret_cast<uintptr_t>(p.y) % (4 * sy) == 0) && (p.ld_y % 4 == 0) && (p.d % 4 == 0) &&
                      (p.F % 4 == 0);
     const int64_t blocks = (p.n + 3) / 4;
     if (blocks > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "attention: too many rows");
-    const double bytes = static_cast<double>(p.n) * (p.d * (sx + (p.ld_y ? sy : 0)) + 4.0 * p.K * (p.corr ? 2 : 1));
+    const double bytes = static_cast<double>(p.n) * (p.d * (sx + (p.ld_y ? sy : 0) + (p.y2 ? sy : 0)) + 4.0 * p.K * ((p.corr ? 2 : 1) + (p.y2 ? 1 : 0)));
     ProfScope prof("attn_rowdot_kernel", st, bytes, 0);
     if (vec) {
         const int n_chunks = p.d / 4;
@@ -1454,8 +1492,14 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     dp.scale = 1.f;
     dp.corr = nullptr;
     dp.out = dot;
+    if (o_pos) { // <g, o_pos> in the same pass over g; der = (1 - slope) <g, o_pos> - corr_d is finished after the sweep
+        dp.y2 = o_pos;
+        dp.scale2 = 1.f - slope;
+        dp.out2 = der;
+    }
     e = launch_rowdot(dp, HETA_F32, o_dt, st);
     if (e != HETA_OK) return e;
+    dp.y2 = nullptr;
 
     // Destination side: der = sum_e gate_e <g, z[u_e]> - dot * sum_e gate_e, gate_e = alpha_e * LeakyReLU'.
     SweepParams sp{};
@@ -1475,13 +1519,11 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
         sp.dot_shift = slope;
         e = launch_sweeps<SWEEP_BWD_CSR>(r.csr, sp, hub_scratch, st, "attn_sweep_bwd_dst");
         if (e != HETA_OK) return e;
-        dp.y = o_pos;
-        dp.ld_y = ld_o;
-        dp.scale = 1.f - slope;
-        dp.corr = corr_d;
-        dp.out = der;
-        e = launch_rowdot(dp, HETA_F32, o_dt, st);
-        if (e != HETA_OK) return e;
+        const int64_t total = r.n_dst * K;
+        if (total > 0) {
+            hipLaunchKernelGGL(attn_sub_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, der, corr_d, total);
+            HETA_LAUNCH_CHECK("attn_sub_kernel");
+        }
     } else {
         // without it: R[v] = sum_e gate_e z[u_e] by one more weighted aggregation over the CSR
         sp.gate = w_gate;
