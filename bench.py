@@ -509,12 +509,10 @@ def measure_minibatch(args, which: str = "config5"):
                         for l, b in enumerate(mb.blocks) for i, r in enumerate(b.graph.relations))
     n_edges = sum(r.num_edges for b in mb.blocks for r in b.graph.relations)
 
-    def build():
-        graphs = []
-        for b in mb.blocks:
-            nts = [(t.num_nodes, t.feat_dim, int(t.learnable)) for t in b.graph.ntypes]
-            graphs.append(heta.heta_graph_create(nts, [(r.src_type, r.dst_type, r.rowptr, r.col) for r in b.graph.relations]))
-        return graphs
+    def build():  # the handles of both blocks of the mini-batch in one call
+        return heta.heta_graph_create_batch(
+            [([(t.num_nodes, t.feat_dim, int(t.learnable)) for t in b.graph.ntypes],
+              [(r.src_type, r.dst_type, r.rowptr, r.col) for r in b.graph.relations]) for b in mb.blocks])
 
     def make_layers(graphs):
         layers, prev = [], None

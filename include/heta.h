@@ -97,9 +97,24 @@ typedef struct {
  * transposed adjacency (CSC: for each source u the destinations of its out-edges in ascending
  * original edge position) and the degree-sorted row schedules both directions use (device
  * kernels: a stable radix sort of (source, destination) pairs, scans, binary searches).
- * Synchronous.  The caller's arrays may be freed on return.  `*out` is written only on success. */
+ * Synchronous.  The caller's arrays may be freed on return.  `*out` is written only on success.
+ * Where a CSR is checked: host arrays of a relation that is uploaded and built on its own are walked on
+ * the host first; device arrays (HETA_PTRS_ON_DEVICE), and the small relations of a graph that are built
+ * together on the device (a sampled block's), are checked by the build's own kernels - the same findings,
+ * HETA_ERR_BAD_CSR, and no handle, but only after those kernels ran. */
 heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels,
                               int32_t n_rels, uint32_t flags, heta_graph **out);
+/* Several graphs at once - the blocks of one sampled mini-batch (Algorithm 1 samples one block per layer
+ * and iteration): the same handles as n_graphs calls of heta_graph_create, array for array, but the small
+ * relations of all of them are built by one set of device kernels (one block-diagonal problem), so a
+ * mini-batch pays the launch chain of its block handles once instead of once per layer.  ntypes / n_ntypes /
+ * rels / n_rels: HOST arrays of n_graphs entries, each as for heta_graph_create; flags apply to all graphs;
+ * out: HOST array of n_graphs handles, all NULL on failure.  The handles are independent afterwards (each is
+ * destroyed on its own; memory the blocks share goes with the last).  Relations beyond what one build takes
+ * (32 small relations in all), or too few edges for the device to pay, are built graph by graph. */
+heta_status heta_graph_create_batch(int32_t n_graphs, const heta_ntype *const *ntypes, const int32_t *n_ntypes,
+                                    const heta_relation *const *rels, const int32_t *n_rels, uint32_t flags,
+                                    heta_graph **out);
 heta_status heta_graph_destroy(heta_graph *g); /* NULL is accepted; synchronises the device */
 /* Device bytes the handle holds for index data (adjacency in both directions, schedules, 1/deg);
  * arrays shared through reverse_of count once. */

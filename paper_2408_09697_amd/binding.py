@@ -23,7 +23,7 @@ HETA_SUM, HETA_MEAN = 0, 1
 HETA_ACT_NONE, HETA_ACT_RELU = 0, 1
 HETA_PTRS_ON_DEVICE = 1
 
-EXPORTS = ["heta_graph_create", "heta_graph_destroy", "heta_graph_get_csc", "heta_graph_get_degrees",
+EXPORTS = ["heta_graph_create", "heta_graph_create_batch", "heta_graph_destroy", "heta_graph_get_csc", "heta_graph_get_degrees",
            "heta_feature_gather", "heta_check_ids", "heta_rel_aggregate_fwd", "heta_rel_aggregate_bwd",
            "heta_rel_aggregate_fwd_multi", "heta_rel_aggregate_bwd_multi",
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
@@ -182,12 +182,8 @@ def heta_last_error() -> str:
     return load_library().heta_last_error().decode()
 
 
-def heta_graph_create(ntypes: Sequence[Sequence[int]], relations: Sequence[Sequence], flags: int = 0) -> Graph:
-    """ntypes: (num_nodes, feat_dim, learnable) per node type.  relations: (src_type, dst_type,
-    rowptr, col[, extras]) per relation, rowptr int64 [n_dst+1] and col int32 [E]; numpy arrays, or device
-    tensors when flags has HETA_PTRS_ON_DEVICE.  extras: a dict with "csc": (colptr int64 [n_src+1], row int32 [E])
-    and / or "reverse_of": index of the earlier relation this one is the exact transpose of."""
-    L = load_library()
+def _marshal_graph(ntypes: Sequence[Sequence[int]], relations: Sequence[Sequence], flags: int):
+    """The C arrays of one heta_graph_create call, what keeps their memory alive, and the relations' (s, t, E)."""
     nt = (_NType * max(1, len(ntypes)))()
     for i, (n, d, l) in enumerate(ntypes):
         nt[i] = _NType(int(n), int(d), int(l))
@@ -217,11 +213,41 @@ def heta_graph_create(ntypes: Sequence[Sequence[int]], relations: Sequence[Seque
         keep += [rowptr, col]
         rl[i] = _Relation(int(s), int(t), n_e, rp, cp, ccp, crp, int(extras.get("reverse_of", -1)))
         meta.append((int(s), int(t), n_e))
+    return nt, rl, keep, meta
+
+
+def heta_graph_create(ntypes: Sequence[Sequence[int]], relations: Sequence[Sequence], flags: int = 0) -> Graph:
+    """ntypes: (num_nodes, feat_dim, learnable) per node type.  relations: (src_type, dst_type,
+    rowptr, col[, extras]) per relation, rowptr int64 [n_dst+1] and col int32 [E]; numpy arrays, or device
+    tensors when flags has HETA_PTRS_ON_DEVICE.  extras: a dict with "csc": (colptr int64 [n_src+1], row int32 [E])
+    and / or "reverse_of": index of the earlier relation this one is the exact transpose of."""
+    L = load_library()
+    nt, rl, keep, meta = _marshal_graph(ntypes, relations, flags)
     out = ctypes.c_void_p()
     _check(L.heta_graph_create(ctypes.addressof(nt) if len(ntypes) else None, len(ntypes),
                                ctypes.addressof(rl) if len(relations) else None, len(relations),
                                flags, ctypes.byref(out)))
+    del keep
     return Graph(out.value, [tuple(int(x) for x in t) for t in ntypes], meta)
+
+
+def heta_graph_create_batch(graphs: Sequence[Sequence], flags: int = 0) -> List[Graph]:
+    """Several graphs (the blocks of one mini-batch) in one call: graphs[i] = (ntypes, relations) as for
+    heta_graph_create; their small relations are built together on the device."""
+    L = load_library()
+    n = len(graphs)
+    if n == 0:
+        return []
+    parts = [_marshal_graph(nts, rels, flags) for nts, rels in graphs]
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    L.heta_graph_create_batch.argtypes = [i32, vp, vp, vp, vp, ctypes.c_uint32, vp]
+    nt_ptrs = (vp * n)(*[ctypes.addressof(p[0]) for p in parts])
+    rl_ptrs = (vp * n)(*[ctypes.addressof(p[1]) for p in parts])
+    n_nt = (i32 * n)(*[len(g[0]) for g in graphs])
+    n_rl = (i32 * n)(*[len(g[1]) for g in graphs])
+    outs = (vp * n)()
+    _check(L.heta_graph_create_batch(n, nt_ptrs, n_nt, rl_ptrs, n_rl, flags, outs))
+    return [Graph(outs[i], [tuple(int(x) for x in t) for t in graphs[i][0]], parts[i][3]) for i in range(n)]
 
 
 def heta_graph_destroy(g: Graph) -> None:

@@ -297,15 +297,16 @@ template <typename T> size_t carve_size(size_t n) { return align_up(std::max<siz
 
 int block_ingest_max_relations() { return kMaxBlockRels; }
 
-// Builds the relations `which` of g (registered already: types, sizes; no arrays yet) from their CSRs.
+// Builds the listed relations (registered already in their graphs: types, sizes; no arrays yet) from their CSRs;
+// `names` says how an error message calls each.
 // rowptr / col: DEVICE arrays per listed relation.  On success the relations' schedules point into *arena_out
 // (one pool block, to be released with scratch_free when the graph goes) and carry their host-side histograms.
-// Synchronous.  The error of a malformed CSR names the relation by its index in g.
-heta_status build_block_on_device(heta_graph *g, const std::vector<int32_t> &which, const int64_t *const *rowptr,
-                                  const int32_t *const *col, void **arena_out, hipStream_t st)
+// Synchronous.
+heta_status build_block_on_device(const std::vector<Relation *> &rels, const std::vector<std::string> &names,
+                                  const int64_t *const *rowptr, const int32_t *const *col, void **arena_out, hipStream_t st)
 {
     *arena_out = nullptr;
-    const int n_rel = static_cast<int>(which.size());
+    const int n_rel = static_cast<int>(rels.size());
     if (n_rel == 0) return HETA_OK;
     if (n_rel > kMaxBlockRels) return fail(HETA_ERR_UNSUPPORTED, "block ingest takes at most %d relations at once", kMaxBlockRels);
     BlockTables t{};
@@ -313,7 +314,7 @@ heta_status build_block_on_device(heta_graph *g, const std::vector<int32_t> &whi
     t.n_rel = n_rel;
     size_t hub_total = 0, hubptr_total = 0;
     for (int i = 0; i < n_rel; ++i) {
-        const Relation &r = g->rels[which[i]];
+        const Relation &r = *rels[i];
         t.dst_off[i + 1] = t.dst_off[i] + r.n_dst;
         t.src_off[i + 1] = t.src_off[i] + r.n_src;
         t.edge_off[i + 1] = t.edge_off[i] + r.n_edges;
@@ -321,7 +322,7 @@ heta_status build_block_on_device(heta_graph *g, const std::vector<int32_t> &whi
         in.col[i] = col[i];
     }
     for (int s = 0; s < 2 * n_rel; ++s) { // chunk descriptors / chunk ranges per schedule: the same bounds as the host path's
-        const int64_t E = g->rels[which[s % n_rel]].n_edges;
+        const int64_t E = rels[s % n_rel]->n_edges;
         t.hub_off[s] = static_cast<int64_t>(hub_total);
         t.hubptr_off[s] = static_cast<int64_t>(hubptr_total);
         hub_total += static_cast<size_t>(E / kHubChunk + E / kHubMinDeg + 1);
@@ -330,10 +331,10 @@ heta_status build_block_on_device(heta_graph *g, const std::vector<int32_t> &whi
     t.hub_off[2 * n_rel] = static_cast<int64_t>(hub_total);
     t.hubptr_off[2 * n_rel] = static_cast<int64_t>(hubptr_total);
     for (int i = 0; i < n_rel; ++i) { // what needs no look at the arrays is rejected before anything is launched
-        const Relation &r = g->rels[which[i]];
+        const Relation &r = *rels[i];
         if (r.n_edges > 0 && r.n_dst == 0)
-            return fail(HETA_ERR_BAD_CSR, "relation %d: rowptr[n_dst] differs from num_edges = %lld", which[i], (long long)r.n_edges);
-        if (r.n_edges > 0 && r.n_src == 0) return fail(HETA_ERR_BAD_CSR, "relation %d: col[0] outside [0, 0)", which[i]);
+            return fail(HETA_ERR_BAD_CSR, "%s: rowptr[n_dst] differs from num_edges = %lld", names[i].c_str(), (long long)r.n_edges);
+        if (r.n_edges > 0 && r.n_src == 0) return fail(HETA_ERR_BAD_CSR, "%s: col[0] outside [0, 0)", names[i].c_str());
     }
     const int64_t nR = t.dst_off[n_rel], nS = t.src_off[n_rel], nE = t.edge_off[n_rel], nQ = nR + nS;
     if (nQ >= (int64_t(1) << 31) || nE >= (int64_t(1) << 31)) return fail(HETA_ERR_UNSUPPORTED, "block too large for the block ingest");
@@ -484,16 +485,17 @@ heta_status build_block_on_device(heta_graph *g, const std::vector<int32_t> &whi
     const unsigned long long bad = h[n_hist];
     if (bad != kNoError) {
         const unsigned long long kind = bad >> 56, at = bad & ((1ull << 48) - 1);
-        const int index = which[static_cast<int>((bad >> 48) & 0xff)];
-        const Relation &r = g->rels[index];
-        if (kind == kBadPtr0) e = fail(HETA_ERR_BAD_CSR, "relation %d: rowptr[0] is not 0", index);
-        else if (kind == kBadDecrease) e = fail(HETA_ERR_BAD_CSR, "relation %d: rowptr decreases at row %llu", index, at);
-        else if (kind == kBadTotal) e = fail(HETA_ERR_BAD_CSR, "relation %d: rowptr[n_dst] differs from num_edges = %lld", index, (long long)r.n_edges);
-        else e = fail(HETA_ERR_BAD_CSR, "relation %d: col[%llu] outside [0, %lld)", index, at, (long long)r.n_src);
+        const int which = static_cast<int>((bad >> 48) & 0xff);
+        const Relation &r = *rels[which];
+        const char *name = names[which].c_str();
+        if (kind == kBadPtr0) e = fail(HETA_ERR_BAD_CSR, "%s: rowptr[0] is not 0", name);
+        else if (kind == kBadDecrease) e = fail(HETA_ERR_BAD_CSR, "%s: rowptr decreases at row %llu", name, at);
+        else if (kind == kBadTotal) e = fail(HETA_ERR_BAD_CSR, "%s: rowptr[n_dst] differs from num_edges = %lld", name, (long long)r.n_edges);
+        else e = fail(HETA_ERR_BAD_CSR, "%s: col[%llu] outside [0, %lld)", name, at, (long long)r.n_src);
         return finish(e);
     }
     for (int i = 0; i < n_rel; ++i) {
-        Relation &r = g->rels[which[i]];
+        Relation &r = *rels[i];
         for (int side = 0; side < 2; ++side) {
             Schedule &s = side ? r.csc : r.csr;
             const int sched = side ? n_rel + i : i;

@@ -356,7 +356,7 @@ static void destroy(heta_graph *g)
         (void)hipFree(r.d_inv_deg);
     }
     scratch_free(g->d_arena); // the device is idle here
-    scratch_free(g->d_block_arena);
+    g->block_arena.reset(); // released with the last graph that shares it
     scratch_free(g->d_ws);
     scratch_free(g->d_pack);
     (void)hipFree(g->d_attn);
@@ -505,34 +505,52 @@ static bool takes_block_path(const std::vector<heta_ntype> &nts, const heta_rela
     return g_ingest_mode == 3 || work >= kBlockIngestMin;
 }
 
-// The small relations of g through the whole-block device ingest.  Host arrays are staged through the page-locked
-// buffer and one device block first; supplied CSCs and declared reverses are then checked against what was built.
-static heta_status build_small_relations_on_device(heta_graph *g, const heta_relation *rels, const std::vector<int32_t> &small,
-                                                   bool on_device)
+// One small relation of a graph about to be built: relation `index` of `rels`, registered in g; graph_no is the
+// graph's position in a batch (-1: a single heta_graph_create), used in error messages only.
+struct SmallRef {
+    heta_graph *g;
+    const heta_relation *rels;
+    int32_t index;
+    int graph_no;
+};
+
+// The listed small relations (of one graph, or of all graphs of a batch) through the whole-block device ingest.
+// Host arrays are staged through the page-locked buffer and one device block first; supplied CSCs and declared
+// reverses are then checked against what was built.  The graphs share the one arena that holds the arrays.
+static heta_status build_small_relations_on_device(const std::vector<SmallRef> &refs, bool on_device)
 {
-    const size_t n = small.size();
+    const size_t n = refs.size();
+    if (n == 0) return HETA_OK;
     std::vector<const int64_t *> ptrs(n);
     std::vector<const int32_t *> cols(n);
+    std::vector<Relation *> built(n);
+    std::vector<std::string> names(n);
+    for (size_t k = 0; k < n; ++k) {
+        built[k] = &refs[k].g->rels[refs[k].index];
+        names[k] = refs[k].graph_no < 0 ? "relation " + std::to_string(refs[k].index)
+                                        : "graph " + std::to_string(refs[k].graph_no) + " relation " + std::to_string(refs[k].index);
+    }
     void *staging = nullptr;
     if (on_device) {
         for (size_t k = 0; k < n; ++k) {
-            ptrs[k] = rels[small[k]].csr_rowptr;
-            cols[k] = rels[small[k]].csr_col;
+            ptrs[k] = refs[k].rels[refs[k].index].csr_rowptr;
+            cols[k] = refs[k].rels[refs[k].index].csr_col;
         }
     } else {
         HostPack pack;
         std::vector<size_t> off_ptr(n), off_col(n);
         size_t total = 0;
         for (size_t k = 0; k < n; ++k) {
-            const Relation &r = g->rels[small[k]];
+            const Relation &r = *built[k];
             off_ptr[k] = take(total, (static_cast<size_t>(r.n_dst) + 1) * sizeof(int64_t));
             off_col[k] = take(total, static_cast<size_t>(r.n_edges) * sizeof(int32_t));
         }
         if (!pack.reserve(total)) return fail(HETA_ERR_OOM, "heta_graph_create: page-locked host allocation of %zu bytes failed", total);
         for (size_t k = 0; k < n; ++k) {
-            const Relation &r = g->rels[small[k]];
-            std::memcpy(t_pinned.p + off_ptr[k], rels[small[k]].csr_rowptr, (r.n_dst + 1) * sizeof(int64_t));
-            if (r.n_edges) std::memcpy(t_pinned.p + off_col[k], rels[small[k]].csr_col, r.n_edges * sizeof(int32_t));
+            const Relation &r = *built[k];
+            const heta_relation &in = refs[k].rels[refs[k].index];
+            std::memcpy(t_pinned.p + off_ptr[k], in.csr_rowptr, (r.n_dst + 1) * sizeof(int64_t));
+            if (r.n_edges) std::memcpy(t_pinned.p + off_col[k], in.csr_col, r.n_edges * sizeof(int32_t));
         }
         HETA_HIP(scratch_alloc(&staging, total));
         hipError_t e = hipMemcpyAsync(staging, t_pinned.p, total, hipMemcpyHostToDevice, nullptr);
@@ -556,26 +574,31 @@ static heta_status build_small_relations_on_device(heta_graph *g, const heta_rel
     if (dev < 0 || dev >= 64) return fail(HETA_ERR_UNSUPPORTED, "device index %d beyond 64", dev);
     if (!t_stream[dev]) HETA_HIP(hipStreamCreateWithFlags(&t_stream[dev], hipStreamNonBlocking));
     if (staging) HETA_HIP(hipStreamSynchronize(nullptr)); // the staged arrays have arrived
-    heta_status st = build_block_on_device(g, small, ptrs.data(), cols.data(), &g->d_block_arena, t_stream[dev]); // synchronous
+    void *arena = nullptr;
+    heta_status st = build_block_on_device(built, names, ptrs.data(), cols.data(), &arena, t_stream[dev]); // synchronous
     scratch_free(staging);
     if (st != HETA_OK) return st;
+    {
+        std::shared_ptr<void> shared(arena, [](void *p) { scratch_free(p); });
+        for (const SmallRef &ref : refs) ref.g->block_arena = shared;
+    }
     for (size_t k = 0; k < n; ++k) {
-        const int32_t i = small[k];
-        const heta_relation &in = rels[i];
-        const Relation &rel = g->rels[i];
+        const heta_relation &in = refs[k].rels[refs[k].index];
+        const Relation &rel = *built[k];
+        const char *name = names[k].c_str();
         bool d1 = false, d2 = false;
         if (in.csc_colptr) {
             if ((st = differs_from_device(in.csc_colptr, on_device, rel.csc.d_ptr, rel.n_src + 1, &d1)) != HETA_OK) return st;
             if ((st = differs_from_device(in.csc_row, on_device, rel.csc.d_idx, rel.n_edges, &d2)) != HETA_OK) return st;
             if (d1 || d2)
-                return fail(HETA_ERR_BAD_CSR, "relation %d: the supplied CSC is not the transposed adjacency of its CSR (columns in "
-                                              "ascending edge order)", i);
+                return fail(HETA_ERR_BAD_CSR, "%s: the supplied CSC is not the transposed adjacency of its CSR (columns in "
+                                              "ascending edge order)", name);
         }
         if (in.reverse_of >= 0) {
-            const Relation &base = g->rels[in.reverse_of];
+            const Relation &base = refs[k].g->rels[in.reverse_of];
             if ((st = differs_from_device(in.csr_rowptr, on_device, base.csc.d_ptr, rel.n_dst + 1, &d1)) != HETA_OK) return st;
             if ((st = differs_from_device(in.csr_col, on_device, base.csc.d_idx, rel.n_edges, &d2)) != HETA_OK) return st;
-            if (d1 || d2) return fail(HETA_ERR_BAD_CSR, "relation %d: its CSR is not the transposed adjacency of relation %d", i, in.reverse_of);
+            if (d1 || d2) return fail(HETA_ERR_BAD_CSR, "%s: its CSR is not the transposed adjacency of relation %d", name, in.reverse_of);
         }
     }
     return HETA_OK;
@@ -835,11 +858,11 @@ extern "C" {
 const char *heta_last_error(void) { return g_last_error.c_str(); }
 const char *heta_version(void) { return "0.1"; }
 
-heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels,
-                              int32_t n_rels, uint32_t flags, heta_graph **out)
+// everything of a heta_graph_create call that can be rejected on the host, before the device is touched
+// everything of a heta_graph_create call that can be rejected without walking the relations' arrays
+static heta_status check_create_args(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels, int32_t n_rels,
+                                     uint32_t flags)
 {
-    if (!out)
-        return fail(HETA_ERR_INVALID_ARG, "heta_graph_create: out is NULL");
     if (!ntypes || n_ntypes <= 0)
         return fail(HETA_ERR_INVALID_ARG, "heta_graph_create: need at least one node type");
     if (n_rels < 0 || (n_rels > 0 && !rels))
@@ -853,19 +876,35 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
         if (ntypes[t].feat_dim < 0)
             return fail(HETA_ERR_INVALID_ARG, "node type %d: negative feat_dim", t);
     }
-    const bool on_device = (flags & HETA_PTRS_ON_DEVICE) != 0;
-    {
-        // everything that can be rejected on the host is rejected before the device is touched
-        std::vector<heta_ntype> nts(ntypes, ntypes + n_ntypes);
-        for (int32_t i = 0; i < n_rels; ++i) {
-            heta_status st = check_relation_args(nts, rels[i], i);
-            if (st == HETA_OK) st = check_reverse_args(rels, i);
-            if (st == HETA_OK && !on_device)
-                st = validate_relation(nts, rels[i], i, rels[i].csr_rowptr, rels[i].csr_col);
-            if (st != HETA_OK)
-                return st;
-        }
+    std::vector<heta_ntype> nts(ntypes, ntypes + n_ntypes);
+    for (int32_t i = 0; i < n_rels; ++i) {
+        heta_status st = check_relation_args(nts, rels[i], i);
+        if (st == HETA_OK) st = check_reverse_args(rels, i);
+        if (st != HETA_OK)
+            return st;
     }
+    return HETA_OK;
+}
+
+// The CSRs of host arrays, walked on the host before the device is touched.  small_on_device: the small relations go
+// through the whole-block device build, whose kernels check the same properties and fail the call the same way; only
+// the large relations (uploaded and built one by one) are walked here then.
+static heta_status validate_host_arrays(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels, int32_t n_rels,
+                                        bool small_on_device)
+{
+    std::vector<heta_ntype> nts(ntypes, ntypes + n_ntypes);
+    for (int32_t i = 0; i < n_rels; ++i) {
+        const bool large = takes_device_path(rels[i].num_edges, nts[rels[i].dst_type].num_nodes, nts[rels[i].src_type].num_nodes);
+        if (!large && small_on_device) continue;
+        heta_status st = validate_relation(nts, rels[i], i, rels[i].csr_rowptr, rels[i].csr_col);
+        if (st != HETA_OK) return st;
+    }
+    return HETA_OK;
+}
+
+// a new handle with its node types, on the current device
+static heta_status new_graph(const heta_ntype *ntypes, int32_t n_ntypes, heta_graph **out)
+{
     heta_graph *g = new (std::nothrow) heta_graph();
     if (!g)
         return fail(HETA_ERR_OOM, "heta_graph_create: host allocation failed");
@@ -875,14 +914,32 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
         delete g;
         return fail(HETA_ERR_DEVICE, "hipGetDevice failed: %s", hipGetErrorString(e));
     }
-    {
-        // set-up time: this device's address of the fixed scratch of heta_rel_aggregate_fwd_noalloc
-        heta_status st = noalloc_scratch_init();
-        if (st != HETA_OK) {
-            delete g;
-            return st;
-        }
+    // set-up time: this device's address of the fixed scratch of heta_rel_aggregate_fwd_noalloc
+    heta_status st = noalloc_scratch_init();
+    if (st != HETA_OK) {
+        delete g;
+        return st;
     }
+    *out = g;
+    return HETA_OK;
+}
+
+heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const heta_relation *rels,
+                              int32_t n_rels, uint32_t flags, heta_graph **out)
+{
+    if (!out)
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_create: out is NULL");
+    heta_status st0 = check_create_args(ntypes, n_ntypes, rels, n_rels, flags);
+    if (st0 != HETA_OK) return st0;
+    if (!(flags & HETA_PTRS_ON_DEVICE)) {
+        const std::vector<heta_ntype> nts(ntypes, ntypes + n_ntypes);
+        st0 = validate_host_arrays(ntypes, n_ntypes, rels, n_rels, takes_block_path(nts, rels, n_rels));
+        if (st0 != HETA_OK) return st0;
+    }
+    const bool on_device = (flags & HETA_PTRS_ON_DEVICE) != 0;
+    heta_graph *g = nullptr;
+    st0 = new_graph(ntypes, n_ntypes, &g);
+    if (st0 != HETA_OK) return st0;
     try {
         g->rels.reserve(n_rels);
         HostPack pack;
@@ -908,7 +965,9 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
         }
         heta_status st;
         if (block_path) {
-            st = build_small_relations_on_device(g, rels, small, on_device);
+            std::vector<SmallRef> refs;
+            for (int32_t i : small) refs.push_back(SmallRef{g, rels, i, -1});
+            st = build_small_relations_on_device(refs, on_device);
         } else {
             st = build_small_relations(g, rels, small, on_device, staged, pack, pending);
             if (st == HETA_OK) st = upload_host_built(g, pack, pending);
@@ -922,6 +981,80 @@ heta_status heta_graph_create(const heta_ntype *ntypes, int32_t n_ntypes, const 
         return fail(HETA_ERR_OOM, "heta_graph_create: host allocation failed");
     }
     *out = g;
+    return HETA_OK;
+}
+
+heta_status heta_graph_create_batch(int32_t n_graphs, const heta_ntype *const *ntypes, const int32_t *n_ntypes,
+                                    const heta_relation *const *rels, const int32_t *n_rels, uint32_t flags, heta_graph **out)
+{
+    if (n_graphs < 0 || (n_graphs > 0 && (!ntypes || !n_ntypes || !rels || !n_rels || !out)))
+        return fail(HETA_ERR_INVALID_ARG, "heta_graph_create_batch: null argument");
+    for (int32_t q = 0; q < n_graphs; ++q) out[q] = nullptr;
+    for (int32_t q = 0; q < n_graphs; ++q) {
+        heta_status st = check_create_args(ntypes[q], n_ntypes[q], rels[q], n_rels[q], flags);
+        if (st != HETA_OK) return st;
+    }
+    const bool on_device = (flags & HETA_PTRS_ON_DEVICE) != 0;
+    // The small relations of all graphs go through one whole-block build when together they qualify for it; otherwise
+    // (too few edges for the device to pay, too many relations for one build, or a forced path) graph by graph.
+    bool together = g_ingest_mode == 0 || g_ingest_mode == 3;
+    if (together) {
+        int64_t work = 0, n_small = 0;
+        for (int32_t q = 0; q < n_graphs; ++q)
+            for (int32_t i = 0; i < n_rels[q]; ++i) {
+                const heta_relation &r = rels[q][i];
+                const int64_t n_dst = ntypes[q][r.dst_type].num_nodes, n_src = ntypes[q][r.src_type].num_nodes;
+                if (takes_device_path(r.num_edges, n_dst, n_src)) continue;
+                work += r.num_edges + n_dst + n_src;
+                ++n_small;
+            }
+        together = n_small > 0 && n_small <= block_ingest_max_relations() && (g_ingest_mode == 3 || work >= kBlockIngestMin);
+    }
+    if (together && !on_device)
+        for (int32_t q = 0; q < n_graphs; ++q) {
+            heta_status st = validate_host_arrays(ntypes[q], n_ntypes[q], rels[q], n_rels[q], true);
+            if (st != HETA_OK) return st;
+        }
+    if (!together) {
+        for (int32_t q = 0; q < n_graphs; ++q) {
+            heta_status st = heta_graph_create(ntypes[q], n_ntypes[q], rels[q], n_rels[q], flags, &out[q]);
+            if (st != HETA_OK) {
+                for (int32_t p = 0; p < q; ++p) {
+                    destroy(out[p]);
+                    out[p] = nullptr;
+                }
+                return st;
+            }
+        }
+        return HETA_OK;
+    }
+    std::vector<heta_graph *> made;
+    auto undo = [&](heta_status st) {
+        for (heta_graph *g : made) destroy(g);
+        for (int32_t q = 0; q < n_graphs; ++q) out[q] = nullptr;
+        return st;
+    };
+    try {
+        std::vector<SmallRef> refs;
+        for (int32_t q = 0; q < n_graphs; ++q) {
+            heta_graph *g = nullptr;
+            heta_status st = new_graph(ntypes[q], n_ntypes[q], &g);
+            if (st != HETA_OK) return undo(st);
+            made.push_back(g);
+            g->rels.reserve(n_rels[q]);
+            for (int32_t i = 0; i < n_rels[q]; ++i) {
+                bool device_path = false;
+                st = ingest_relation(g, rels[q][i], i, on_device, device_path);
+                if (st != HETA_OK) return undo(st);
+                if (!device_path) refs.push_back(SmallRef{g, rels[q], i, q});
+            }
+        }
+        heta_status st = build_small_relations_on_device(refs, on_device);
+        if (st != HETA_OK) return undo(st);
+    } catch (const std::bad_alloc &) {
+        return undo(fail(HETA_ERR_OOM, "heta_graph_create_batch: host allocation failed"));
+    }
+    for (int32_t q = 0; q < n_graphs; ++q) out[q] = made[q];
     return HETA_OK;
 }
 

@@ -6,6 +6,8 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <memory>
+#include <string>
 #include <vector>
 
 #include "heta.h"
@@ -87,7 +89,9 @@ struct heta_graph {
     std::vector<heta_ntype> ntypes;
     std::vector<heta::Relation> rels;
     void *d_arena = nullptr;      // every host-built relation's arrays: one allocation, one copy
-    void *d_block_arena = nullptr; // the arrays of the relations built by the whole-block device ingest
+    // the arrays of the relations built by the whole-block device ingest; the blocks of one heta_graph_create_batch
+    // call share one allocation, released with the last of them
+    std::shared_ptr<void> block_arena;
     // workspace for hub-row partials and split weight-gradient partials; grown on demand
     void *d_ws = nullptr;
     size_t ws_bytes = 0;
@@ -128,8 +132,8 @@ heta_status build_schedule_on_device(Schedule &s, float *inv_deg, hipStream_t st
 // Whole-block ingest (heta_block_ingest.hip): the index data of up to block_ingest_max_relations() relations of g
 // (listed in `which`, registered already) from their DEVICE CSR arrays, in one pass; *arena_out owns their arrays.
 int block_ingest_max_relations();
-heta_status build_block_on_device(heta_graph *g, const std::vector<int32_t> &which, const int64_t *const *rowptr,
-                                  const int32_t *const *col, void **arena_out, hipStream_t st);
+heta_status build_block_on_device(const std::vector<Relation *> &rels, const std::vector<std::string> &names,
+                                  const int64_t *const *rowptr, const int32_t *const *col, void **arena_out, hipStream_t st);
 
 // out[i] = in[0] + ... + in[i-1] for i < n_out (in[j] = 0 for j >= n_in); synchronous on st.
 heta_status device_exclusive_scan_i64(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, hipStream_t st);

@@ -2,7 +2,8 @@
 Algorithm 1 of the paper): hop by hop from the seeds outwards, per relation a call of
 `heta_sample_neighbors` on the current frontier of its destination type, then per source type one
 `heta_unique_relabel` over the relations leaving it (each hop issues them as one batched call of each
-kind, synchronising twice), and one `heta_graph_create` on the device arrays of the hop.  No arithmetic here beyond the seed given to each (hop, relation) pair.
+kind, synchronising twice); the handles of all hops' blocks are then built by one `heta_graph_create_batch` on
+the hops' device arrays.  No arithmetic here beyond the seed given to each (hop, relation) pair.
 """
 from __future__ import annotations
 
@@ -39,7 +40,8 @@ def sample_blocks(base: hb.Graph, seed_type: int, seeds: torch.Tensor, fanouts: 
     frontier: List[Optional[torch.Tensor]] = [None] * T
     frontier[seed_type] = seeds
     empty = torch.zeros(0, dtype=torch.int64, device=seeds.device)
-    blocks: List[DeviceBlock] = []
+    specs = []
+    parts = []
     for hop, fanout in enumerate(reversed(list(fanouts))):
         n_rels = len(base.rels)
         sampled = hb.heta_sample_neighbors_batch(
@@ -59,8 +61,11 @@ def sample_blocks(base: hb.Graph, seed_type: int, seeds: torch.Tensor, fanouts: 
         nts = [(int(src_ids[k].numel()), base.ntypes[k][1], base.ntypes[k][2]) for k in range(T)]
         nts += [(0 if frontier[k] is None else int(frontier[k].numel()), base.ntypes[k][1], base.ntypes[k][2]) for k in range(T)]
         rels = [(s, T + t, rowptrs[i], cols[i]) for i, (s, t, _) in enumerate(base.rels)]
-        graph = hb.heta_graph_create(nts, rels, flags=hb.HETA_PTRS_ON_DEVICE)
-        blocks.append(DeviceBlock(graph, src_ids, list(frontier), rowptrs, cols))
+        specs.append((nts, rels))
+        parts.append((src_ids, list(frontier), rowptrs, cols))
         frontier = [u if u.numel() else None for u in src_ids]
+    # the blocks' handles (CSC, 1/deg, schedules of every relation of every hop) in one build
+    graphs = hb.heta_graph_create_batch(specs, flags=hb.HETA_PTRS_ON_DEVICE)
+    blocks = [DeviceBlock(g, *p) for g, p in zip(graphs, parts)]
     blocks.reverse()
     return blocks

@@ -985,3 +985,94 @@ def test_f32_products_as_six_bf16_terms_are_as_accurate_as_the_fp32_mfma(n, d_in
         heta.heta_projection_f32_native(False)
         hg.destroy()
     assert errw[True] <= 1e-5 and errw[False] <= 2.0 * errw[True] + 1e-7, errw
+
+
+@pytest.mark.parametrize("on_device", [False, True])
+@pytest.mark.parametrize("mode", [0, 1, 3], ids=["by_size", "host_ingest", "block_ingest"])
+def test_graphs_created_in_one_batch_equal_graphs_created_one_by_one(mode, on_device):
+    """heta_graph_create_batch: three graphs of different type counts and sizes (one with a declared reverse and a
+    supplied CSC, one with an empty relation), every derived array compared with the single creation bit for bit,
+    the handles destroyed in an order that releases the shared memory last from the middle one."""
+    g = rng.stream("tests", "create_batch")
+
+    def relation(n_src, n_dst, e):
+        deg = power_law_degrees(n_dst, e, 1.8, g) if e else np.zeros(n_dst, dtype=np.int64)
+        rowptr = np.zeros(n_dst + 1, dtype=np.int64)
+        np.cumsum(deg, out=rowptr[1:])
+        return rowptr, g.integers(0, max(n_src, 1), size=int(rowptr[-1]), dtype=np.int32)
+
+    sizes = [[900, 1400, 300], [5000, 2500], [64, 64, 64, 10]]
+    layouts = [[(0, 1, 20000), (1, 2, 6000), (2, 0, 900)], [(0, 1, 70000), (1, 0, 0)], [(0, 1, 200), (1, 2, 300), (3, 0, 50)]]
+    specs = []
+    for n, rels in zip(sizes, layouts):
+        specs.append(([(k, 8, 0) for k in n], [(s, t) + relation(n[s], n[t], e) for s, t, e in rels]))
+    # graph 0 gets the exact transpose of its first relation, declared and with its CSC supplied
+    nts0, rels0 = specs[0]
+    src0, dst0 = np.repeat(np.arange(sizes[0][1]), np.diff(rels0[0][2])), rels0[0][3].astype(np.int64)
+    order = np.lexsort((np.arange(len(dst0)), dst0))           # stable by source id = the unique CSC order
+    colptr = np.zeros(sizes[0][0] + 1, dtype=np.int64)
+    np.cumsum(np.bincount(dst0, minlength=sizes[0][0]), out=colptr[1:])
+    # its own CSC is relation 0's CSR with every row's sources in ascending order (the order is part of the contract)
+    row_sorted = rels0[0][3][np.lexsort((rels0[0][3], src0))]
+    rels0.append((1, 0, colptr, src0[order].astype(np.int32), {"reverse_of": 0, "csc": (rels0[0][2], row_sorted)}))
+
+    def up(spec):
+        if not on_device:
+            return spec, 0
+        nts, rels = spec
+        out = []
+        for r in rels:
+            ex = dict(r[4]) if len(r) > 4 else {}
+            if "csc" in ex:
+                ex["csc"] = (torch.from_numpy(ex["csc"][0]).cuda(), torch.from_numpy(ex["csc"][1]).cuda())
+            out.append((r[0], r[1], torch.from_numpy(r[2]).cuda(), torch.from_numpy(r[3]).cuda(), ex))
+        return (nts, out), heta.HETA_PTRS_ON_DEVICE
+
+    heta.heta_ingest_force(mode)
+    try:
+        flags = up(specs[0])[1]
+        together = heta.heta_graph_create_batch([up(s)[0] for s in specs], flags=flags)
+        singles = [heta.heta_graph_create(*up(s)[0], flags=flags) for s in specs]
+    finally:
+        heta.heta_ingest_force(0)
+    try:
+        for a, b, (nts, rels) in zip(together, singles, specs):
+            for i in range(len(rels)):
+                ca, cb = heta.heta_graph_get_csc(a, i), heta.heta_graph_get_csc(b, i)
+                assert np.array_equal(ca[0], cb[0]) and np.array_equal(ca[1], cb[1])
+                assert np.array_equal(heta.heta_graph_get_degrees(a, i), heta.heta_graph_get_degrees(b, i))
+                e_dst = np.repeat(np.arange(nts[rels[i][1]][0]), np.diff(rels[i][2]))
+                ref_ptr, ref_row = oracle.csc(rels[i][3], e_dst, nts[rels[i][0]][0])
+                assert np.array_equal(ca[0], ref_ptr) and np.array_equal(ca[1], ref_row)
+                # the schedules through an integer aggregation in both directions
+                d = 8
+                x = torch.from_numpy(g.integers(-3, 4, size=(nts[rels[i][0]][0], d)).astype(np.float32)).cuda()
+                go = torch.from_numpy(g.integers(-3, 4, size=(nts[rels[i][1]][0], d)).astype(np.float32)).cuda()
+                outs = []
+                for h in (a, b):
+                    o = torch.zeros((nts[rels[i][1]][0], d), device="cuda")
+                    gs = torch.zeros((nts[rels[i][0]][0], d), device="cuda")
+                    heta.heta_rel_aggregate_fwd(h, i, heta.HETA_SUM, x, o)
+                    heta.heta_rel_aggregate_bwd(h, i, heta.HETA_SUM, go, gs)
+                    outs.append((o, gs))
+                assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+        # the first and the last handle go; the middle one still works on the memory the three share
+        together[0].destroy()
+        together[2].destroy()
+        nts, rels = specs[1]
+        x = torch.ones((nts[0][0], 4), device="cuda")
+        o = torch.zeros((nts[1][0], 4), device="cuda")
+        heta.heta_rel_aggregate_fwd(together[1], 0, heta.HETA_SUM, x, o)
+        torch.cuda.synchronize()
+        assert np.array_equal(o[:, 0].cpu().numpy().astype(np.int64), np.diff(rels[0][2]))
+    finally:
+        for h in together + singles:
+            h.destroy()
+    # a bad relation anywhere fails the whole call and leaves no handle
+    bad_ptr = rels0[1][2].copy()
+    bad_ptr[3] = bad_ptr[4] + 1
+    bad = (specs[1][0], [(0, 1, specs[1][1][0][2], specs[1][1][0][3])]), (nts0, [(rels0[1][0], rels0[1][1], bad_ptr, rels0[1][3])])
+    with pytest.raises(heta.HetaError) as ei:
+        heta.heta_graph_create_batch(list(bad))
+    assert ei.value.status == heta.HETA_ERR_BAD_CSR
+    assert heta.heta_graph_create_batch([]) == []
