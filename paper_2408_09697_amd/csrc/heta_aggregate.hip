@@ -64,6 +64,14 @@ struct AggParams {
     int mean;              // divide the row sum by the row's degree
     int hub_only;          // reduce the hub rows only, into out[h] for the h-th hub row of the schedule
     int wave_split;        // few long rows / hub chunks: four wavefronts per item (agg_wave_split_kernel)
+    // With slot_w2, instead of storing the second sum: dot_out[row, k] = <second sum of head k, dot_z[row, head k]> -
+    // dot_corr[row, k] (the attention backward needs only this dot of the gate-weighted sum, not the sum itself).
+    const void *dot_z;     // nullable; rows indexed like out, ld_z elements apart, fp32 or bf16 (dot_z_bf16)
+    int64_t ld_z;
+    int dot_z_bf16;
+    const float *dot_corr; // nullable
+    float *dot_out;        // [n_rows][heads]
+    int combine_dot;       // set on the hub combine launch that finishes dot_out
     void *out;
     int64_t ld_out;
     int out_bf16;
@@ -218,6 +226,46 @@ __device__ __forceinline__ float row_scale(const AggParams &p, int64_t deg)
     return deg > 0 ? 1.f / static_cast<float>(deg) : 0.f;
 }
 
+// The dot form of the second sum's store: acc2 holds EPC consecutive columns (from col0) of the row's second
+// sum; the lanes of a head (head_dim / EPC of them, a power of two, consecutive) add their partial dots.  Every
+// lane of the row's lane group calls it (lanes beyond the row's width contribute 0).
+template <int EPC>
+__device__ __forceinline__ void dot_store(const AggParams &p, int64_t row, int col0, const float *acc2, float scale, int l)
+{
+    float part = 0.f;
+    const bool live = col0 < p.d;
+    if (live) { // the host has checked that z's chunks of EPC elements are aligned as vectors
+        if (p.dot_z_bf16) {
+            const uint16_t *z = static_cast<const uint16_t *>(p.dot_z) + row * p.ld_z + col0;
+#pragma unroll
+            for (int q = 0; q < EPC / 4; ++q) {
+                const uint2 raw = *reinterpret_cast<const uint2 *>(z + 4 * q);
+                part = fmaf(acc2[4 * q + 0], __uint_as_float(raw.x << 16), part);
+                part = fmaf(acc2[4 * q + 1], __uint_as_float(raw.x & 0xffff0000u), part);
+                part = fmaf(acc2[4 * q + 2], __uint_as_float(raw.y << 16), part);
+                part = fmaf(acc2[4 * q + 3], __uint_as_float(raw.y & 0xffff0000u), part);
+            }
+        } else {
+            const float *z = static_cast<const float *>(p.dot_z) + row * p.ld_z + col0;
+#pragma unroll
+            for (int q = 0; q < EPC / 4; ++q) {
+                const float4 v = *reinterpret_cast<const float4 *>(z + 4 * q);
+                part = fmaf(acc2[4 * q + 0], v.x, part);
+                part = fmaf(acc2[4 * q + 1], v.y, part);
+                part = fmaf(acc2[4 * q + 2], v.z, part);
+                part = fmaf(acc2[4 * q + 3], v.w, part);
+            }
+        }
+    }
+    part *= scale;
+    const int lph = p.head_dim / EPC;
+    for (int off = lph >> 1; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+    if (live && (l & (lph - 1)) == 0) {
+        const int64_t at = row * p.heads + col0 / p.head_dim;
+        p.dot_out[at] = part - (p.dot_corr ? p.dot_corr[at] : 0.f);
+    }
+}
+
 // ---- short rows: one wavefront per batch of equal-degree rows ---------------------------------------
 // Rows per batch for degree k and G lane groups: about 16 row loads per lane group (two fills of its
 // load pipeline), at most 64 rows and kBatchIds neighbour ids - small enough that a block of a sampled
@@ -282,9 +330,17 @@ __device__ __forceinline__ void agg_batch_body(const AggParams &p)
                     const int ch = ch0 + c * L;
                     if (ch < n_chunks) {
                         store_out<EPC>(p, row_s[wave][r], ch * EPC, zero, 0.f);
-                        if (DUAL) store_out<EPC>(p, p.out2, p.ld_out2, row_s[wave][r], ch * EPC, zero, 0.f);
+                        if (DUAL && !p.dot_out) store_out<EPC>(p, p.out2, p.ld_out2, row_s[wave][r], ch * EPC, zero, 0.f);
                     }
                 }
+        }
+        if constexpr (DUAL && CPL == 1) { // an empty row's second sum is zero: its dot is zero
+            if (p.dot_out) {
+                float zero[EPC];
+#pragma unroll
+                for (int i = 0; i < EPC; ++i) zero[i] = 0.f;
+                for (int r = g; r < nrows; r += G) dot_store<EPC>(p, row_s[wave][r], ch0 * EPC, zero, 0.f, l);
+            }
         }
         return;
     }
@@ -353,8 +409,11 @@ __device__ __forceinline__ void agg_batch_body(const AggParams &p)
                             const int ch = ch0 + c * L;
                             if (ch < n_chunks) {
                                 store_out<EPC>(p, row, ch * EPC, acc[c], scale);
-                                if (DUAL) store_out<EPC>(p, p.out2, p.ld_out2, row, ch * EPC, acc2[c], scale);
+                                if (DUAL && !p.dot_out) store_out<EPC>(p, p.out2, p.ld_out2, row, ch * EPC, acc2[c], scale);
                             }
+                        }
+                        if constexpr (DUAL && CPL == 1) {
+                            if (p.dot_out) dot_store<EPC>(p, row, ch0 * EPC, acc2[0], scale, l);
                         }
                     }
 #pragma unroll
@@ -516,8 +575,11 @@ __device__ __forceinline__ void agg_wave_body(const AggParams &p)
             const int ch = ch0 + c * L;
             if (ch < n_chunks) {
                 store_out<EPC>(p, row, ch * EPC, acc[c], scale);
-                if (DUAL) store_out<EPC>(p, p.out2, p.ld_out2, row, ch * EPC, acc2[c], scale);
+                if (DUAL && !p.dot_out) store_out<EPC>(p, p.out2, p.ld_out2, row, ch * EPC, acc2[c], scale);
             }
+        }
+        if constexpr (DUAL && CPL == 1) {
+            if (p.dot_out) dot_store<EPC>(p, row, ch0 * EPC, acc2[0], scale, l);
         }
     }
 }
@@ -552,7 +614,7 @@ __device__ __forceinline__ void agg_hub_combine_body(const AggParams &p)
     }
     part[wave][lane] = a;
     __syncthreads();
-    if (wave != 0 || col0 >= p.d) return;
+    if (wave != 0 || (col0 >= p.d && !p.combine_dot)) return;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int k = 0; k < kCombineWaves; ++k) {
@@ -560,7 +622,8 @@ __device__ __forceinline__ void agg_hub_combine_body(const AggParams &p)
         acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
     }
     const float scale = row_scale(p, p.sptr[h + 1] - p.sptr[h]);
-    store_out<4>(p, row, col0, acc, scale);
+    if (p.combine_dot) dot_store<4>(p, row, col0, acc, scale, lane); // all 64 lanes of wavefront 0 (one 256-column tile)
+    else store_out<4>(p, row, col0, acc, scale);
 }
 
 // The kernels proper.  The single-relation forms take the parameters of their relation; the multi forms
@@ -771,6 +834,7 @@ static heta_status launch_plans(const AggPlan *plans, int n, hipStream_t st, boo
                 p2.ws = ps[0].ws + ps[0].ws_ld;
                 p2.out = ps[0].out2;
                 p2.ld_out = ps[0].ld_out2;
+                p2.combine_dot = ps[0].dot_out ? 1 : 0;
                 hipLaunchKernelGGL(agg_hub_combine_kernel, dim3((unsigned)hub_rows, tiles), dim3(64 * kCombineWaves), 0, st, p2);
                 HETA_LAUNCH_CHECK("agg_hub_combine_kernel");
             }
@@ -860,7 +924,7 @@ static heta_status run_aggregate_multi(heta_graph *g, std::vector<AggPlan> &plan
 heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld,
                                     int d, const float *slot_w, int heads, void *out, heta_dtype out_dt,
                                     int64_t ld_out, float beta, hipStream_t st, const float *slot_w2, void *out2,
-                                    int64_t ld_out2)
+                                    int64_t ld_out2, const SecondSumDot *dot, bool *dot_done)
 {
     AggParams p{};
     p.table = table;
@@ -876,6 +940,26 @@ heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void
     p.out_bf16 = (out_dt == HETA_BF16);
     p.beta = beta;
     p.d = d;
+    if (dot_done) *dot_done = false;
+    if (dot && slot_w2 && dot->z && dot->out) {
+        // the dot form needs: the 128-bit path, one chunk per lane (a row inside one lane group), heads that are a
+        // power-of-two number of chunks wide for both the row kernels' chunk (16 bytes of the gathered type) and the
+        // hub combine's (4 columns), z rows whose chunks are aligned, a single 256-column tile in the combine
+        const int epc = static_cast<int>(16 / dtype_size(dt));
+        const int hd = p.head_dim, lph = hd / epc, lph4 = hd / 4;
+        const size_t zsz = dtype_size(dot->z_dt);
+        const bool ok = agg_vectorized(p, dt) && d % epc == 0 && d / epc <= 64 && d <= 256 && hd % epc == 0 && hd % 4 == 0 &&
+                        lph > 0 && (lph & (lph - 1)) == 0 && (lph4 & (lph4 - 1)) == 0 &&
+                        reinterpret_cast<uintptr_t>(dot->z) % (epc * zsz) == 0 && dot->ld_z % epc == 0;
+        if (ok) {
+            p.dot_z = dot->z;
+            p.ld_z = dot->ld_z;
+            p.dot_z_bf16 = dot->z_dt == HETA_BF16;
+            p.dot_corr = dot->corr;
+            p.dot_out = dot->out;
+            if (dot_done) *dot_done = true;
+        }
+    }
     return run_aggregate(g, s, p, dt, ld, st);
 }
 

@@ -1556,8 +1556,13 @@ heta_status heta_rel_attn_bwd(heta_graph *g, int32_t rel, const void *z, heta_dt
     sp.corr = corr_s;
     e = launch_sweeps<SWEEP_BWD_CSC>(r.csc, sp, hub_scratch, st, "attn_sweep_bwd_src");
     if (e != HETA_OK) return e;
-    e = aggregate_slot_weighted(g, r.csc, grad_out, HETA_F32, ld_go, d, w_alpha, K, dz, HETA_F32, ld_dz, 0.f, st, w_gate, R, ld_r);
+    // del = <z, R> - corr_s is taken inside the aggregation when the shapes allow it (R is then never written)
+    const SecondSumDot zr{z, z_dt, ld_z, corr_s, del};
+    bool dot_done = false;
+    e = aggregate_slot_weighted(g, r.csc, grad_out, HETA_F32, ld_go, d, w_alpha, K, dz, HETA_F32, ld_dz, 0.f, st, w_gate, R, ld_r,
+                                &zr, &dot_done);
     if (e != HETA_OK) return e;
+    if (dot_done) return HETA_OK;
     dp.x = z;
     dp.ld_x = ld_z;
     dp.y = R;

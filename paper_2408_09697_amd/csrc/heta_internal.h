@@ -162,10 +162,20 @@ heta_status ensure_workspace(heta_graph *g, size_t bytes);
 // out[r] = beta out[r] + sum_e slot_w[e][head of the column] table[idx[e]] over the rows of s; slot_w is
 // indexed by the edge's position in s.d_sidx.  With slot_w2 the same gathered rows are reduced a second
 // time, with those weights, into out2 (same element type as out).  Uses g's workspace for hub rows.
+// dot: instead of storing the second sum, dot->out[row, k] = <second sum of head k, dot->z[row, head k]> - dot->corr[row, k];
+// *dot_done tells whether the shapes allowed it (else out2 was written as usual and the caller takes the dot itself).
+struct SecondSumDot {
+    const void *z;
+    heta_dtype z_dt;
+    int64_t ld_z;
+    const float *corr; // nullable
+    float *out;
+};
 heta_status aggregate_slot_weighted(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld,
                                     int d, const float *slot_w, int heads, void *out, heta_dtype out_dt,
                                     int64_t ld_out, float beta, hipStream_t st, const float *slot_w2 = nullptr,
-                                    void *out2 = nullptr, int64_t ld_out2 = 0);
+                                    void *out2 = nullptr, int64_t ld_out2 = 0, const SecondSumDot *dot = nullptr,
+                                    bool *dot_done = nullptr);
 // out[h] (fp32, compact) = sum or mean of the h-th hub row of s (rows of >= kHubMinDeg edges lead the schedule)
 heta_status aggregate_hub_rows(heta_graph *g, const Schedule &s, const void *table, heta_dtype dt, int64_t ld, int d,
                                const int64_t *gid, int mean, float *out, int64_t ld_out, hipStream_t st);
