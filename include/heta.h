@@ -250,12 +250,15 @@ heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, h
  * heta_project_wgrad_batch: dW[p] = beta * dW[p] + ins[p]^T . gouts[p] over n_rows rows, every p with
  *   its own gradient operand; uses the handle's workspace; gout_two_terms as in
  *   heta_cross_rel_project_wgrad.
- * Pointer and size arrays are HOST arrays of n entries; shapes and dtypes as in heta_project. */
-heta_status heta_project_batch(int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+ * Pointer and size arrays are HOST arrays of n entries; shapes and dtypes as in heta_project.
+ * g (heta_project_batch, heta_project_sum): optional (NULL allowed) handle whose packing buffer the call may use
+ *   to rewrite the weights into the form its kernel reads fastest (fp32 weights as three bf16 terms), on the
+ *   same terms as heta_cross_rel_project; the result does not depend on it beyond rounding order. */
+heta_status heta_project_batch(heta_graph *g, int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
                                const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
                                int32_t d_out, int32_t transW, void *const *outs, heta_dtype out_dt,
                                const int64_t *ld_out, void *hip_stream);
-heta_status heta_project_sum(int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+heta_status heta_project_sum(heta_graph *g, int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
                              const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
                              int32_t d_out, int32_t transW, float *out, int64_t ld_out, float beta, void *hip_stream);
 heta_status heta_project_wgrad_batch(heta_graph *g, int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt,
@@ -271,8 +274,10 @@ heta_status heta_project_wgrad_batch(heta_graph *g, int64_t n_rows, int32_t n, c
  * in_dt; Ws[p] device [d_in[p], ld_w[p] >= d_out] of w_dt; out device fp32 [n_rows, ld_out].
  * On a subset of a type's relations with beta = 0 it yields the partial aggregation of that subset.
  * With bf16 inputs and weights the call first rewrites the weights k-contiguous into a buffer of the
- * handle (grown on demand: the first call for a larger shape synchronises); calls on one handle
- * that do so must be stream-ordered, like the calls that use its workspace. */
+ * handle (grown on demand: the first call for a larger shape synchronises); with fp32 inputs and weights
+ * and enough rows for full-size tiles it rewrites the weights there as the three bf16 terms the product is
+ * fed with (so does heta_cross_rel_project_bwd).  Calls on one handle that do so must be stream-ordered,
+ * like the calls that use its workspace. */
 heta_status heta_cross_rel_project(heta_graph *g, int32_t dst_type, int32_t n, const void *const *ins,
                                    heta_dtype in_dt, const int64_t *ld_in, const int32_t *d_in,
                                    const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,

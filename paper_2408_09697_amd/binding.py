@@ -477,8 +477,9 @@ def heta_cross_rel_project(g: Graph, dst_type: int, ins: List[torch.Tensor], Ws:
 
 
 def heta_project_batch(ins: List[torch.Tensor], Ws: List[torch.Tensor], outs: List[torch.Tensor], trans_w: bool = False,
-                       n_rows: Optional[int] = None, stream=None) -> List[torch.Tensor]:
-    """outs[p] = ins[p] @ (Ws[p]^T if trans_w else Ws[p]), independent products in one launch."""
+                       n_rows: Optional[int] = None, stream=None, graph: Optional["Graph"] = None) -> List[torch.Tensor]:
+    """outs[p] = ins[p] @ (Ws[p]^T if trans_w else Ws[p]), independent products in one launch; graph: optional
+    handle whose packing buffer the call may use."""
     n_rows = ins[0].shape[0] if n_rows is None else n_rows
     d_out = Ws[0].shape[0] if trans_w else Ws[0].shape[1]
     if not ins or len(ins) != len(Ws) or len(ins) != len(outs):
@@ -490,8 +491,8 @@ def heta_project_batch(ins: List[torch.Tensor], Ws: List[torch.Tensor], outs: Li
             raise HetaError(HETA_ERR_SHAPE, "inputs / weights / outputs do not match")
     L = load_library()
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
-    L.heta_project_batch.argtypes = [i64, i32, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, i32, vp, vp]
-    _check(L.heta_project_batch(n_rows, len(ins), _ptr_array(ins, "in"), _dt(ins[0]), _i64_array([_ld(x) for x in ins]),
+    L.heta_project_batch.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, i32, vp, vp]
+    _check(L.heta_project_batch(graph.handle if graph is not None else None, n_rows, len(ins), _ptr_array(ins, "in"), _dt(ins[0]), _i64_array([_ld(x) for x in ins]),
                                 _i32_array([x.shape[1] for x in ins]), _ptr_array(Ws, "W"), _dt(Ws[0]),
                                 _i64_array([w.stride(0) for w in Ws]), d_out, int(trans_w), _ptr_array(outs, "out"),
                                 _dt(outs[0]), _i64_array([_ld(o) for o in outs]), _stream(stream)))
@@ -499,8 +500,9 @@ def heta_project_batch(ins: List[torch.Tensor], Ws: List[torch.Tensor], outs: Li
 
 
 def heta_project_sum(ins: List[torch.Tensor], Ws: List[torch.Tensor], out: torch.Tensor, trans_w: bool = False,
-                     beta: float = 0.0, n_rows: Optional[int] = None, stream=None) -> torch.Tensor:
-    """out = beta*out + sum_p ins[p] @ (Ws[p]^T if trans_w else Ws[p]), one contraction."""
+                     beta: float = 0.0, n_rows: Optional[int] = None, stream=None, graph: Optional["Graph"] = None) -> torch.Tensor:
+    """out = beta*out + sum_p ins[p] @ (Ws[p]^T if trans_w else Ws[p]), one contraction; graph: optional handle whose
+    packing buffer the call may use."""
     n_rows = ins[0].shape[0] if n_rows is None else n_rows
     d_out = Ws[0].shape[0] if trans_w else Ws[0].shape[1]
     if not ins or len(ins) != len(Ws) or out.shape[0] < n_rows or out.shape[1] < d_out:
@@ -511,8 +513,8 @@ def heta_project_sum(ins: List[torch.Tensor], Ws: List[torch.Tensor], out: torch
             raise HetaError(HETA_ERR_SHAPE, "inputs / weights do not match")
     L = load_library()
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
-    L.heta_project_sum.argtypes = [i64, i32, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, i64, ctypes.c_float, vp]
-    _check(L.heta_project_sum(n_rows, len(ins), _ptr_array(ins, "in"), _dt(ins[0]), _i64_array([_ld(x) for x in ins]),
+    L.heta_project_sum.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, i64, ctypes.c_float, vp]
+    _check(L.heta_project_sum(graph.handle if graph is not None else None, n_rows, len(ins), _ptr_array(ins, "in"), _dt(ins[0]), _i64_array([_ld(x) for x in ins]),
                               _i32_array([x.shape[1] for x in ins]), _ptr_array(Ws, "W"), _dt(Ws[0]),
                               _i64_array([w.stride(0) for w in Ws]), d_out, int(trans_w), _dev(out, "out", torch.float32),
                               _ld(out), beta, _stream(stream)))

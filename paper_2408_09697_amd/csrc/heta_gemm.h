@@ -24,6 +24,9 @@ struct GemmSeg {
     float *C;           // output of this segment (batch mode) - segment 0's is used in sum mode
     int64_t ldc;
     int64_t M, N, K;
+    // optional: B rewritten as three bf16 terms (pack_split3_weights), [term][k / 8][n_pad][8 k-values]
+    const void *B3;
+    int32_t ko, n_pad;  // k-octets (K rounded up to 16, over 8) and columns (N rounded up to 128) of B3
 };
 
 struct GemmParams {
@@ -249,6 +252,13 @@ struct TileLoader {
 // The direct-to-LDS pipeline (heta_gemm_direct.hip).  Sets *handled when it launched the product;
 // otherwise the caller falls back to the register-staged kernel.
 extern bool g_f32_native; // test switch, see heta_test_hooks.h
+// Bytes of the three-term form of a K x N fp32 operand, and the kernel that writes it: B(k, n) = W[k*ldw + n]
+// (trans = 0) or W[n*ldw + k] (trans = 1); x = h + m + l in bf16, zero beyond K and N.  out must be 16-byte aligned.
+size_t split3_weight_bytes(int64_t K, int64_t N);
+heta_status pack_split3_weights(const float *W, int64_t ldw, int64_t K, int64_t N, int trans, void *out, GemmSeg *seg,
+                                hipStream_t st);
+// whether the direct pipeline would give this launch its 64 x 64 tiles (too few 128 x 128 tiles to fill the chip)
+bool gemm_direct_small(const GemmParams &p);
 heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, bool a_rc, bool b_rc, hipStream_t st,
                                const char *name, double bytes, double flops, bool *handled);
 

@@ -311,6 +311,136 @@ __device__ __forceinline__ uint4 mask_bf16(uint4 v, int k_first, int kv)
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// The splitting of one fragment (8 k-values of a lane) in pieces, so that a k-step can place them between its
+// MFMAs: hp / mp / lp pack the leading, middle and last term of a pair of values, r1 / r2 leave the residuals.
+struct X3Frag {
+    float x[8];      // the values, then their residuals
+    uint32_t h[4], m[4], l[4];
+    __device__ __forceinline__ void hp(int j) { h[j] = pack_bf16(x[2 * j], x[2 * j + 1]); }
+    __device__ __forceinline__ void r1(int j)
+    {
+        x[2 * j] -= __uint_as_float(h[j] << 16);
+        x[2 * j + 1] -= __uint_as_float(h[j] & 0xffff0000u);
+    }
+    __device__ __forceinline__ void mp(int j) { m[j] = pack_bf16(x[2 * j], x[2 * j + 1]); }
+    __device__ __forceinline__ void r2(int j)
+    {
+        x[2 * j] -= __uint_as_float(m[j] << 16);
+        x[2 * j + 1] -= __uint_as_float(m[j] & 0xffff0000u);
+    }
+    __device__ __forceinline__ void lp(int j) { l[j] = pack_bf16(x[2 * j], x[2 * j + 1]); }
+    __device__ __forceinline__ bf16x8 term(int t) const
+    {
+        union { uint4 u; bf16x8 v; } f;
+        const uint32_t *w = t == 0 ? h : (t == 1 ? m : l);
+        f.u = make_uint4(w[0], w[1], w[2], w[3]);
+        return f.v;
+    }
+};
+
+// Loader of an operand that lies in memory as three bf16 terms (pack_split3_weights): a stage holds, for each
+// term and each of the tile's two k-octets, the BN columns' 16-byte chunks (8 k-values) side by side, so a
+// fragment read (lane = column, half = octet) is one conflict-free 128-bit load per term and a wavefront load
+// instruction copies 64 neighbouring columns' chunks, 1 KB that is contiguous in memory too.  The packed
+// operand is zero beyond K and N, so no tile needs clamping or masking on this side.
+template <int BN, int NW> struct Split3Loader {
+    static constexpr int SLOTS = 3 * 2 * (BN / 64);
+    static constexpr int NI = (SLOTS + NW - 1) / NW;
+    static constexpr int STAGE_BYTES = SLOTS * 1024;
+    const char *tile;    // uniform: the chunk of term 0, the next tile's first octet, column n0
+    uint32_t off;        // per lane
+    int64_t plane, oct;  // uniform: bytes from term to term, from octet to octet
+    __device__ __forceinline__ void init(const void *b3, int ko, int n_pad, int64_t n0, int64_t k0, int lane)
+    {
+        oct = static_cast<int64_t>(n_pad) * 16;
+        plane = ko * oct;
+        tile = static_cast<const char *>(b3) + (k0 / 8) * oct + n0 * 16;
+        off = static_cast<uint32_t>(lane) * 16u;
+    }
+    __device__ __forceinline__ void issue(uint32_t lds, int wave)
+    {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int slot = (i * NW + wave) % SLOTS; // surplus slots repeat earlier ones (same bytes, same place)
+            const int t = slot / (2 * (BN / 64)), o = (slot / (BN / 64)) % 2, hn = slot % (BN / 64);
+            load_chunk_to_lds(tile + t * plane + o * oct + hn * 1024, off, lds + slot * 1024);
+        }
+        tile += 2 * oct;
+    }
+    // term t of the 8 k-values of octet `half` of column c, of the stage at `stage`
+    __device__ __forceinline__ static uint4 frag(const char *stage, int t, int half, int c)
+    {
+        return *reinterpret_cast<const uint4 *>(stage + ((t * 2 + half) * BN + c) * 16);
+    }
+};
+
+// One whole k-step (16 k-values, none masked) of a wavefront's 2 x 2 accumulators with B already in three
+// terms: only A's two fragments are split (88 vector instructions), and the order is pinned with scheduling
+// barriers so that the splitting runs between the twelve MFMAs that need A's leading term alone; the twelve
+// that need its m and l terms follow.  Terms of one accumulator are added leading term first.
+template <bool A_RC, int BM, int BN, int BK>
+__device__ __forceinline__ void x3_step_2x2_presplit(const float *At, const char *Bt, int ra, int cb, int half, floatx16 (&acc)[2][2])
+{
+    X3Frag a[2];
+    dfrag_load8<A_RC, BM, BK>(At, ra, 0, half, a[0].x);
+    dfrag_load8<A_RC, BM, BK>(At, ra + 32, 0, half, a[1].x);
+    union BF { uint4 u; bf16x8 v; } b[2][3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j][t].u = Split3Loader<BN, 4>::frag(Bt, t, half, cb + 32 * j);
+#define X3_PIN __builtin_amdgcn_sched_barrier(0)
+#define X3_MM(TA_, I_, TB_, J_)                                                                                        \
+    X3_PIN;                                                                                                            \
+    acc[I_][J_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[I_].term(TA_), b[J_][TB_].v, acc[I_][J_], 0, 0, 0);       \
+    X3_PIN
+#define X3_ALL(F_, OP_) F_.OP_(0); F_.OP_(1); F_.OP_(2); F_.OP_(3)
+#define X3_LO(F_, OP_) F_.OP_(0); F_.OP_(1)
+#define X3_HI(F_, OP_) F_.OP_(2); F_.OP_(3)
+    X3_ALL(a[0], hp); X3_ALL(a[1], hp);
+    X3_MM(0, 0, 0, 0); X3_LO(a[0], r1);
+    X3_MM(0, 0, 0, 1); X3_HI(a[0], r1);
+    X3_MM(0, 1, 0, 0); X3_ALL(a[0], mp); X3_LO(a[1], r1);
+    X3_MM(0, 1, 0, 1); X3_HI(a[1], r1);
+    X3_MM(0, 0, 1, 0); X3_ALL(a[1], mp); X3_LO(a[0], r2);
+    X3_MM(0, 0, 1, 1); X3_HI(a[0], r2);
+    X3_MM(0, 1, 1, 0); X3_ALL(a[0], lp); X3_LO(a[1], r2);
+    X3_MM(0, 1, 1, 1); X3_HI(a[1], r2);
+    X3_MM(0, 0, 2, 0); X3_ALL(a[1], lp);
+    X3_MM(0, 0, 2, 1); X3_MM(0, 1, 2, 0); X3_MM(0, 1, 2, 1);
+    X3_MM(1, 0, 0, 0); X3_MM(1, 0, 0, 1); X3_MM(1, 1, 0, 0); X3_MM(1, 1, 0, 1);
+    X3_MM(1, 0, 1, 0); X3_MM(1, 0, 1, 1); X3_MM(1, 1, 1, 0); X3_MM(1, 1, 1, 1);
+    X3_MM(2, 0, 0, 0); X3_MM(2, 0, 0, 1); X3_MM(2, 1, 0, 0); X3_MM(2, 1, 0, 1);
+#undef X3_PIN
+#undef X3_MM
+#undef X3_ALL
+#undef X3_LO
+#undef X3_HI
+}
+
+// Writes the three-term form of one B operand: one thread per (k-octet, column).
+__global__ void __launch_bounds__(256) pack_split3_kernel(const float *W, int64_t ldw, int K, int N, int trans, uint4 *out, int ko, int n_pad)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int n = static_cast<int>(idx % n_pad), o = static_cast<int>(idx / n_pad);
+    if (o >= ko) return;
+    uint32_t h[4], m[4], l[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float x[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int k = o * 8 + 2 * j + e;
+            x[e] = (k < K && n < N) ? (trans ? W[static_cast<int64_t>(n) * ldw + k] : W[static_cast<int64_t>(k) * ldw + n]) : 0.f;
+        }
+        split3_pair(x[0], x[1], h[j], m[j], l[j]);
+    }
+    const int64_t plane = static_cast<int64_t>(ko) * n_pad, at = static_cast<int64_t>(o) * n_pad + n;
+    out[at] = make_uint4(h[0], h[1], h[2], h[3]);
+    out[plane + at] = make_uint4(m[0], m[1], m[2], m[3]);
+    out[2 * plane + at] = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
 // The sequence of k-tiles a workgroup walks: the k range of its split in every segment it owns.
 // All of it is wavefront-uniform 32-bit arithmetic (k extents are below 2^31).
 template <int BK> struct TileSeq {
@@ -436,26 +566,35 @@ __device__ __forceinline__ void store_tile(const GemmParams &p, const GemmSeg &o
         }
 }
 
+template <bool W3, bool B_DIRECT, typename DB, typename SB_T, typename Staged, typename CT> constexpr int b_stage_bytes()
+{
+    if constexpr (W3) return DB::STAGE_BYTES;
+    else if constexpr (B_DIRECT) return DB::STAGE_ELEMS * (int)sizeof(SB_T);
+    else return Staged::elems * (int)sizeof(CT);
+}
+
 // Shape of the output tile: WMW x WN wavefronts, each holding MI x NJ MFMA 32 x 32 accumulators; the
 // tile is (32 MI WMW) x (32 NJ WN).  The default 2 x 2 blocks per wavefront with 2 x WN wavefronts is the
 // 128 x (64 WN) tile; tall tiles (MI = 5, NJ = 1: 320 x 128) let a weight gradient whose input is wider than
 // 128 columns read its large gradient operand once, wide ones (MI = 1, NJ = 5: 128 x 320) do the same for a
 // product with more than 256 output columns and its input rows.
 template <typename CT, typename SA_T, bool A_RC, bool A_DIRECT, typename SB_T, bool B_RC, bool B_DIRECT, int WN, int BK,
-          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2, bool X3 = false>
+          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2, int X3 = 0>
 __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmParams p)
 {
     constexpr int NW = WMW * WN, NT = 64 * NW, BN = 32 * NJ * WN, BM = 32 * MI * WMW; // BM shadows the default tile height
     // a direct operand lies in LDS in its storage type (fp32 storage under bf16 compute is converted
     // when fragments are read); a staged operand lies there in the compute type
     using DA = std::conditional_t<A_DIRECT, DirectLoader<SA_T, A_RC && A_DIRECT, BM, BK, NW>, NoLoader>;
-    using DB = std::conditional_t<B_DIRECT, DirectLoader<SB_T, B_RC && B_DIRECT, BN, BK, NW>, NoLoader>;
+    // X3: fp32 operands as three bf16 terms each - 1: both split when their fragments are read, 2: B comes pre-split
+    constexpr bool W3 = X3 == 2;
+    using DB = std::conditional_t<W3, Split3Loader<BN, NW>, std::conditional_t<B_DIRECT, DirectLoader<SB_T, B_RC && B_DIRECT, BN, BK, NW>, NoLoader>>;
     using SA = std::conditional_t<A_DIRECT, NoLoader, TileLoader<SA_T, CT, A_RC, BM, NT, true, BK>>;
     using SB = std::conditional_t<B_DIRECT, NoLoader, TileLoader<SB_T, CT, B_RC, BN, NT, true, BK>>;
     constexpr bool ANY_STAGED = !A_DIRECT || !B_DIRECT;
     // bytes of one LDS stage / buffer of each operand
     constexpr int A_STRIDE = A_DIRECT ? DA::STAGE_ELEMS * (int)sizeof(SA_T) : LdsTile<CT, A_RC, BM, BK>::elems * (int)sizeof(CT);
-    constexpr int B_STRIDE = B_DIRECT ? DB::STAGE_ELEMS * (int)sizeof(SB_T) : LdsTile<CT, B_RC, BN, BK>::elems * (int)sizeof(CT);
+    constexpr int B_STRIDE = b_stage_bytes<W3, B_DIRECT, DB, SB_T, LdsTile<CT, B_RC, BN, BK>, CT>();
     constexpr int A_BYTES = (A_DIRECT ? ST : 2) * A_STRIDE, B_BYTES = (B_DIRECT ? ST : 2) * B_STRIDE;
     constexpr int LD_PER_TILE = (A_DIRECT ? DA::NI : 0) + (B_DIRECT ? DB::NI : 0);
     static_assert(A_DIRECT || B_DIRECT, "at least one operand is loaded directly");
@@ -463,6 +602,7 @@ __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmPar
     static_assert(ST >= 2 && (ST - 2) * LD_PER_TILE < 64, "vmcnt range");
     static_assert(!X3 || (A_DIRECT && B_DIRECT && sizeof(SA_T) == 4 && sizeof(SB_T) == 4 && sizeof(CT) == 2 && !B_SPLIT),
                   "three-term feeding: both operands direct fp32, bf16 MFMA");
+    static_assert(!W3 || (BK == 16 && MI == 2 && NJ == 2 && NW == 4 && !A_RC), "pre-split B: 128 x 128 tiles of 16 k-values");
     static_assert(A_BYTES % 1024 == 0, "stage addresses stay 1 KB aligned");
     __shared__ __attribute__((aligned(1024))) char ring[A_BYTES + B_BYTES];
     char *const As = ring, *const Bs = ring + A_BYTES;
@@ -514,7 +654,8 @@ __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmPar
     auto init_direct = [&]() {
         const GemmSeg &g = p.seg[I.s];
         if constexpr (A_DIRECT) da.init(static_cast<const SA_T *>(g.A), g.lda, m0, g.M, I.k, wave, lane);
-        if constexpr (B_DIRECT) db.init(static_cast<const SB_T *>(g.B), g.ldb, n0, g.N, I.k, wave, lane);
+        if constexpr (W3) db.init(g.B3, g.ko, g.n_pad, n0, I.k, lane);
+        else if constexpr (B_DIRECT) db.init(static_cast<const SB_T *>(g.B), g.ldb, n0, g.N, I.k, wave, lane);
     };
     auto init_staged = [&]() {
         const GemmSeg &g = p.seg[L.s];
@@ -537,7 +678,8 @@ __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmPar
         } else {
             const GemmSeg &g = p.seg[I.s];
             if constexpr (A_DIRECT) da.issue_ragged(a_lds + st * A_STRIDE, wave, lane, kv, g.lda - I.k);
-            if constexpr (B_DIRECT) db.issue_ragged(b_lds + st * B_STRIDE, wave, lane, kv, g.ldb - I.k);
+            if constexpr (W3) db.issue(b_lds + st * B_STRIDE, wave);
+            else if constexpr (B_DIRECT) db.issue_ragged(b_lds + st * B_STRIDE, wave, lane, kv, g.ldb - I.k);
         }
         ++ahead;
         if (I.advance()) {
@@ -618,7 +760,33 @@ __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmPar
                             for (int jj = 0; jj < NJ; ++jj)
                                 acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t], b[jj][t], acc[i][jj], 0, 0, 0);
                 }
-            } else if constexpr (X3) {
+            } else if constexpr (W3) {
+                // fp32 A split as its fragments are read, B read as the three terms it was packed into
+                if (!ragged) {
+                    x3_step_2x2_presplit<A_RC, BM, BN, BK>(reinterpret_cast<const float *>(At), Bt, wm + l32, wn + l32, half, acc);
+                } else {
+                    union Frag { uint4 u; bf16x8 v; };
+                    uint4 a3[2][3];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        float x[8];
+                        dfrag_load8<A_RC, BM, BK>(reinterpret_cast<const float *>(At), wm + i * 32 + l32, 0, half, x);
+                        split3_frag<true>(x, 8 * half, kv, a3[i]);
+                    }
+                    constexpr int TA[6] = {0, 0, 0, 1, 1, 2}, TB[6] = {0, 1, 2, 0, 1, 0}; // the order of x3_step_2x2_presplit
+#pragma unroll
+                    for (int q = 0; q < 6; ++q)
+#pragma unroll
+                        for (int i = 0; i < 2; ++i)
+#pragma unroll
+                            for (int jj = 0; jj < 2; ++jj) {
+                                Frag fa, fb;
+                                fa.u = a3[i][TA[q]];
+                                fb.u = DB::frag(Bt, TB[q], half, wn + jj * 32 + l32);
+                                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb.v, acc[i][jj], 0, 0, 0);
+                            }
+                }
+            } else if constexpr (X3 != 0) {
                 // fp32 operands, every product as six bf16 terms (split3_pair)
 #pragma unroll
                 for (int kk = 0; kk < BK; kk += 16) {
@@ -715,7 +883,7 @@ __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmPar
 // ---- host side -------------------------------------------------------------------------------------
 
 template <typename CT, typename SA_T, bool A_RC, bool A_DIRECT, typename SB_T, bool B_RC, bool B_DIRECT, int WN, int BK,
-          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2, bool X3 = false>
+          int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2, int X3 = 0>
 static heta_status launch_direct(GemmParams &p, hipStream_t st, const char *name, double bytes, double flops)
 {
     constexpr int BN = 32 * NJ * WN, BM = 32 * MI * WMW;
@@ -740,6 +908,35 @@ static heta_status launch_direct(GemmParams &p, hipStream_t st, const char *name
 
 // test switch: fp32 products on the fp32 MFMA (32x32x2) instead of as six bf16 terms
 bool g_f32_native = false;
+
+bool gemm_direct_small(const GemmParams &p)
+{
+    if (p.partial) return false;
+    int64_t mt = 0, nt = 0;
+    for (int s = 0; s < p.n_seg; ++s) {
+        mt = std::max(mt, (p.seg[s].M + 127) / 128);
+        nt = std::max(nt, (p.seg[s].N + 127) / 128);
+    }
+    return mt * nt * (p.batch ? p.n_seg : 1) <= 96;
+}
+
+static int64_t split3_octets(int64_t K) { return (K + 15) / 16 * 2; }
+static int64_t split3_columns(int64_t N) { return (N + 127) / 128 * 128; }
+size_t split3_weight_bytes(int64_t K, int64_t N) { return static_cast<size_t>(3 * split3_octets(K) * split3_columns(N) * 16); }
+
+heta_status pack_split3_weights(const float *W, int64_t ldw, int64_t K, int64_t N, int trans, void *out, GemmSeg *seg, hipStream_t st)
+{
+    const int64_t ko = split3_octets(K), n_pad = split3_columns(N);
+    if (K >= (int64_t(1) << 30) || N >= (int64_t(1) << 30) || ko * n_pad >= (int64_t(1) << 31))
+        return fail(HETA_ERR_UNSUPPORTED, "projection: weight matrix too large to pack");
+    hipLaunchKernelGGL(pack_split3_kernel, dim3((unsigned)((ko * n_pad + 255) / 256)), dim3(256), 0, st, W, ldw, static_cast<int>(K),
+                       static_cast<int>(N), trans, static_cast<uint4 *>(out), static_cast<int>(ko), static_cast<int>(n_pad));
+    HETA_LAUNCH_CHECK("pack_split3_kernel");
+    seg->B3 = out;
+    seg->ko = static_cast<int32_t>(ko);
+    seg->n_pad = static_cast<int32_t>(n_pad);
+    return HETA_OK;
+}
 
 heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, bool a_rc, bool b_rc, hipStream_t st,
                                const char *name, double bytes, double flops, bool *handled)
@@ -794,24 +991,23 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
     // Fewer than a hundred 128 x 128 tiles (the projections of a sampled mini-batch block: a few thousand rows):
     // every tile is a serial chain of MFMAs on one CU while most CUs idle.  64 x 64 tiles (four wavefronts of one
     // accumulator each) cut the chain to a quarter and put four times as many CUs to work.
-    bool small = false;
-    if (!p.partial) {
-        int64_t mt = 0, nt = 0;
-        for (int s = 0; s < p.n_seg; ++s) {
-            mt = std::max(mt, (p.seg[s].M + 127) / 128);
-            nt = std::max(nt, (p.seg[s].N + 127) / 128);
-        }
-        small = mt * nt * (p.batch ? p.n_seg : 1) <= 96;
-    }
+    const bool small = gemm_direct_small(p);
     *handled = true;
+    if (a_dt == HETA_F32 && b_dt == HETA_F32 && !g_f32_native && !a_rc && !small && !p.partial) {
+        // B already packed as three bf16 terms by the caller (the weights of a forward or input-gradient product):
+        // half the splitting arithmetic leaves the k loop.  12 KB of B per stage: two workgroups per CU.
+        bool packed = true;
+        for (int s = 0; s < p.n_seg; ++s) packed = packed && p.seg[s].B3 != nullptr;
+        if (packed) return launch_direct<bf16_t, float, false, true, float, false, true, 2, 16, 3, 2, false, 2, 2, 2, 2>(p, st, name, bytes, flops);
+    }
     if (a_dt == HETA_F32 && b_dt == HETA_F32 && !g_f32_native) {
         // fp32 operands, fp32-exact products as six bf16 MFMA terms each (see split3_pair), fp32 accumulation
         // 128 x 128 tiles (four wavefronts, three workgroups per CU) also where the output is wider: the
         // 128 x 256 tile's eight wavefronts need more than the 128 registers that two workgroups per CU allow,
         // and with one workgroup per CU nothing runs under its barriers (measured: 0.93 against 1.05 ms)
 #define HETA_X32(ARC, BRC)                                                                                                        \
-    return small ? launch_direct<bf16_t, float, ARC, true, float, BRC, true, 2, 16, 3, 4, false, 1, 1, 2, true>(p, st, name, bytes, flops) \
-                 : launch_direct<bf16_t, float, ARC, true, float, BRC, true, 2, 16, 3, 3, false, 2, 2, 2, true>(p, st, name, bytes, flops)
+    return small ? launch_direct<bf16_t, float, ARC, true, float, BRC, true, 2, 16, 3, 4, false, 1, 1, 2, 1>(p, st, name, bytes, flops) \
+                 : launch_direct<bf16_t, float, ARC, true, float, BRC, true, 2, 16, 3, 3, false, 2, 2, 2, 1>(p, st, name, bytes, flops)
         if (!a_rc && b_rc) { HETA_X32(false, true); }
         if (!a_rc && !b_rc) { HETA_X32(false, false); }
         if (a_rc && b_rc) { HETA_X32(true, true); }

@@ -343,6 +343,46 @@ static heta_status dispatch_gemm(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt
 
 static bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
+// the handle's buffer for rewritten weight matrices holds at least `bytes`
+static heta_status ensure_pack(heta_graph *owner, size_t bytes)
+{
+    if (bytes <= owner->pack_bytes) return HETA_OK;
+    if (owner->d_pack) {
+        HETA_HIP(hipDeviceSynchronize()); // earlier readers
+        scratch_free(owner->d_pack);
+    }
+    owner->d_pack = nullptr;
+    owner->pack_bytes = 0;
+    HETA_HIP(scratch_alloc(&owner->d_pack, bytes * 2));
+    owner->pack_bytes = bytes * 2;
+    return HETA_OK;
+}
+
+// fp32 x fp32 products through a graph handle whose B operands are weight matrices (forward, input gradient):
+// the weights are rewritten once per launch as the three bf16 terms the product is fed with, into the handle's
+// packing buffer, and the k loop splits only A.  Launches the direct pipeline would not take, or would give its
+// small tiles, are left as they are.  trans: B(k, n) = W[n*ldb + k].
+static heta_status pack_f32_weights(heta_graph *owner, GemmParams &p, int trans, hipStream_t st)
+{
+    if (!owner || g_force_staged || g_f32_native || p.partial || gemm_direct_small(p)) return HETA_OK;
+    size_t bytes = 0;
+    for (int s = 0; s < p.n_seg; ++s) {
+        const GemmSeg &g = p.seg[s];
+        if (!aligned16(g.A) || (g.lda * 4) % 16 || !aligned16(g.B) || (g.ldb * 4) % 16) return HETA_OK;
+        bytes += (split3_weight_bytes(g.K, g.N) + 255) / 256 * 256;
+    }
+    heta_status e = ensure_pack(owner, bytes);
+    if (e != HETA_OK) return e;
+    char *dst = static_cast<char *>(owner->d_pack);
+    for (int s = 0; s < p.n_seg; ++s) {
+        GemmSeg &g = p.seg[s];
+        e = pack_split3_weights(static_cast<const float *>(g.B), g.ldb, g.K, g.N, trans, dst, &g, st);
+        if (e != HETA_OK) return e;
+        dst += (split3_weight_bytes(g.K, g.N) + 255) / 256 * 256;
+    }
+    return HETA_OK;
+}
+
 // out = beta*out + row_scale * sum_s in_s . (W_s or W_s^T)
 static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
                                 const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w,
@@ -399,6 +439,10 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
     p.k_per_split = int64_t(1) << 40;
     p.n_split = 1;
     p.partial = 0;
+    if (in_dt == HETA_F32 && w_dt == HETA_F32) {
+        heta_status pe = pack_f32_weights(pack_owner, p, transW, st);
+        if (pe != HETA_OK) return pe;
+    }
     // B[k][n] = W[k][n] is n-contiguous (r-contiguous in the loader's terms); W^T is k-contiguous
     if (transW) return dispatch_gemm<false, false>(p, in_dt, w_dt, st);
     if (pack_owner && !g_force_staged && in_dt == HETA_BF16 && w_dt == HETA_BF16) {
@@ -411,16 +455,8 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
             bytes += static_cast<size_t>(d_out) * ((d_in[s] + 7) / 8 * 8) * 2 + 256;
         }
         if (ok) {
-            if (bytes > pack_owner->pack_bytes) {
-                if (pack_owner->d_pack) {
-                    HETA_HIP(hipDeviceSynchronize()); // earlier readers
-                    scratch_free(pack_owner->d_pack);
-                }
-                pack_owner->d_pack = nullptr;
-                pack_owner->pack_bytes = 0;
-                HETA_HIP(scratch_alloc(&pack_owner->d_pack, bytes * 2));
-                pack_owner->pack_bytes = bytes * 2;
-            }
+            heta_status pe = ensure_pack(pack_owner, bytes);
+            if (pe != HETA_OK) return pe;
             char *dst = static_cast<char *>(pack_owner->d_pack);
             for (int s = 0; s < n_seg; ++s) {
                 const int ldp = (d_in[s] + 7) / 8 * 8;
@@ -605,21 +641,21 @@ heta_status heta_rel_project_wgrad(heta_graph *g, int32_t rel, const void *in, h
                       as_stream(hip_stream), "heta_rel_project_wgrad");
 }
 
-heta_status heta_project_batch(int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+heta_status heta_project_batch(heta_graph *g, int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
                                const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,
                                int32_t transW, void *const *outs, heta_dtype out_dt, const int64_t *ld_out, void *hip_stream)
 {
     if (!outs || !ld_out) return fail(HETA_ERR_INVALID_ARG, "heta_project_batch: null argument");
     return project_impl(n_rows, n, ins, in_dt, ld_in, d_in, Ws, w_dt, ld_w, d_out, transW, nullptr, 0, nullptr, 0, 0.f,
-                        as_stream(hip_stream), "heta_project_batch", nullptr, out_dt, outs, ld_out);
+                        as_stream(hip_stream), "heta_project_batch", g, out_dt, outs, ld_out);
 }
 
-heta_status heta_project_sum(int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
+heta_status heta_project_sum(heta_graph *g, int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt, const int64_t *ld_in,
                              const int32_t *d_in, const void *const *Ws, heta_dtype w_dt, const int64_t *ld_w, int32_t d_out,
                              int32_t transW, float *out, int64_t ld_out, float beta, void *hip_stream)
 {
     return project_impl(n_rows, n, ins, in_dt, ld_in, d_in, Ws, w_dt, ld_w, d_out, transW, nullptr, 0, out, ld_out, beta,
-                        as_stream(hip_stream), "heta_project_sum");
+                        as_stream(hip_stream), "heta_project_sum", g);
 }
 
 heta_status heta_project_wgrad_batch(heta_graph *g, int64_t n_rows, int32_t n, const void *const *ins, heta_dtype in_dt,
@@ -686,6 +722,10 @@ heta_status heta_cross_rel_project_bwd(const heta_graph *g, int32_t dst_type, in
     p.n_split = 1;
     p.partial = 0;
     p.out_bf16 = dm_dt == HETA_BF16;
+    if (w_dt == HETA_F32) { // the handle's packing buffer is scratch memory, not part of the graph it describes
+        e = pack_f32_weights(const_cast<heta_graph *>(g), p, 1, as_stream(hip_stream));
+        if (e != HETA_OK) return e;
+    }
     return dispatch_gemm<false, false>(p, HETA_F32, w_dt, as_stream(hip_stream));
 }
 

@@ -185,7 +185,7 @@ class RafLayer:
             for c in range(0, len(pfs), 8):
                 part = pfs[c:c + 8]
                 hb.heta_project_batch([self.source(s)] * len(part), [self.W[r] for r in part], [self.Zp[r] for r in part],
-                                      n_rows=self.g.ntypes[s][0], stream=stream)
+                                      n_rows=self.g.ntypes[s][0], stream=stream, graph=self.g)
         # the relation-specific aggregations of a layer do not depend on each other: one call for all of them
         # (relations of one shape class share launches, which is what a sampled block's small relations need)
         self._aggregate_all([r for r in self.rels if r not in self.pf], stream)
@@ -307,7 +307,8 @@ class RafLayer:
                                             [self.dW[r] for r in part], gout_two_terms=True, n_rows=self.g.ntypes[s][0],
                                             stream=stream)
                 hb.heta_project_sum([self.Ghat[r] for r in part], [self.W[r] for r in part], self.dH0[s], trans_w=True,
-                                    beta=0.0 if first_for_src[s] else 1.0, n_rows=self.g.ntypes[s][0], stream=stream)
+                                    beta=0.0 if first_for_src[s] else 1.0, n_rows=self.g.ntypes[s][0], stream=stream,
+                                    graph=self.g)
                 first_for_src[s] = False
         if self.pre_proj is not None:
             for s, gh in self.dH0.items():

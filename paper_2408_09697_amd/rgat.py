@@ -99,7 +99,7 @@ class RgatLayer:
             for i in range(0, len(rs), _MAX_BATCH):
                 part = rs[i:i + _MAX_BATCH]
                 hb.heta_project_batch([self.tables[s]] * len(part), [self.W[r] for r in part],
-                                      [self.Z[r] for r in part], stream=stream)
+                                      [self.Z[r] for r in part], stream=stream, graph=self.g)
         for r in self.rels:
             hb.heta_attn_fold(self.W[r], self.a[r], self.wa[r], stream=stream)
         # every score of a node type's table in one pass over it: el of the relations leaving the type, er of
@@ -149,6 +149,6 @@ class RgatLayer:
                     hb.heta_attn_fold_bwd(self.W[r], self.a[r], self.dwa[r], dW=self.dW[r], beta=1.0, da=self.da[r],
                                           stream=stream)
                 hb.heta_project_sum([self.dZ[r] for r in part], [self.W[r] for r in part], self.dH0[s], trans_w=True,
-                                    beta=1.0 if s in written else 0.0, stream=stream)
+                                    beta=1.0 if s in written else 0.0, stream=stream, graph=self.g)
                 written.add(s)
         return self.dW, self.da, self.dq, self.dH0

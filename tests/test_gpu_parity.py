@@ -582,9 +582,9 @@ def test_layer_with_relu_and_gid():
 
 @pytest.mark.parametrize("in_s,w_s", [("f32", "f32"), ("bf16", "bf16")])
 @pytest.mark.parametrize("d_out,relu", [(256, False), (40, True)])
-def test_cross_rel_project_family(in_s, w_s, d_out, relu, gemm_path):
+@pytest.mark.parametrize("n", [1500, 7000])   # 7000 rows: enough 128 x 128 tiles for the full-size kernels (fp32: packed weights)
+def test_cross_rel_project_family(n, in_s, w_s, d_out, relu, gemm_path):
     """Fused projection + cross-relation sum over relations of different widths, and its backward."""
-    n = 1500
     widths = [7, 24, 64, 128, 300, 37]
     hg = heta.heta_graph_create([(n, 8, 0)], [])
     tol = 1e-4 if in_s == "f32" else 2e-2
@@ -622,13 +622,15 @@ def test_cross_rel_project_family(in_s, w_s, d_out, relu, gemm_path):
 
 
 @pytest.mark.parametrize("in_s,w_s", [("f32", "f32"), ("bf16", "bf16")])
-def test_project_batch_sum_and_wgrad_batch(in_s, w_s, gemm_path):
+@pytest.mark.parametrize("n,with_handle", [(1100, False), (5000, True), (5000, False)])   # 5000 rows: full-size tiles
+def test_project_batch_sum_and_wgrad_batch(n, with_handle, in_s, w_s, gemm_path):
     """The batched projection calls used when relations are projected before they are aggregated:
     independent products sharing an input, a k-concatenated sum with transposed weights, and weight
     gradients with one gradient operand each (also fed as two bf16 terms)."""
-    n, d_in, d_out = 1100, 300, 256
+    d_in, d_out = 300, 256
     tol = 1e-4 if in_s == "f32" else 2e-2
     hg = heta.heta_graph_create([(n, 8, 0)], [])
+    owner = hg if with_handle else None   # a handle lends the two handle-less calls its packing buffer
     x = rng.normal_table(n, d_in, "tests", "pbx")
     ws = [rng.normal_table(d_in, d_out, "tests", f"pbw{i}") * np.float32(1 / np.sqrt(d_in)) for i in range(3)]
     xr = rng.round_to_bf16(x) if in_s == "bf16" else x
@@ -636,14 +638,14 @@ def test_project_batch_sum_and_wgrad_batch(in_s, w_s, gemm_path):
     dx, dw = dev_table(x, in_s, 8), [dev_table(w, w_s, 8) for w in ws]
     for out_s in (["f32", "bf16"] if in_s == "bf16" else ["f32"]):
         outs = [dev_table(np.full((n, d_out), np.nan, dtype=np.float32), out_s, 8) for _ in ws]
-        heta.heta_project_batch([dx] * 3, dw, outs)
+        heta.heta_project_batch([dx] * 3, dw, outs, graph=owner)
         for o, w in zip(outs, wr):
             assert_rows_close(o.float().cpu().numpy(), xr.astype(np.float64) @ w.astype(np.float64), tol, f"batch -> {out_s}")
     gs = [rng.normal_table(n, d_out, "tests", f"pbg{i}") * np.float32(30.0) for i in range(3)]   # "summed over edges": large
     dg = [dev_table(g, "f32", 4) for g in gs]
     prev = rng.normal_table(n, d_in, "tests", "pbprev")
     acc = dev_table(prev, "f32", 4)
-    heta.heta_project_sum(dg, dw, acc, trans_w=True, beta=1.0)
+    heta.heta_project_sum(dg, dw, acc, trans_w=True, beta=1.0, graph=owner)
     ref = prev.astype(np.float64) + sum(g.astype(np.float64) @ w.astype(np.float64).T for g, w in zip(gs, wr))
     assert_rows_close(acc.cpu().numpy(), ref, tol, "k-concatenated sum with W^T")
     for two in (False, True):
