@@ -497,7 +497,8 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     if (misaligned(gout, 4)) return fail(HETA_ERR_INVALID_ARG, "%s: gout not 4-byte aligned", who);
     GemmParams p{};
     int64_t out_elems = 0, tiles = 0;
-    // bf16 inputs with 16-byte rows take the all-direct kernel: 128 x 128 tiles, three workgroups per CU
+    // bf16 inputs with 16-byte rows take the all-direct kernel: 128 x 128 tiles, three workgroups per CU (wider and
+    // taller tiles below)
     bool bf16_direct = in_dt == HETA_BF16 && !g_force_staged;
     for (int s = 0; s < n_seg && bf16_direct; ++s)
         bf16_direct = ins[s] && vec_ok(ins[s], ld_in[s], in_dt) && vec_ok(gouts ? gouts[s] : gout, gouts ? ld_gos[s] : ld_go, HETA_F32);
@@ -505,10 +506,11 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     bool f32_terms = in_dt == HETA_F32 && !g_force_staged && !g_f32_native;
     for (int s = 0; s < n_seg && f32_terms; ++s)
         f32_terms = ins[s] && vec_ok(ins[s], ld_in[s], in_dt) && vec_ok(gouts ? gouts[s] : gout, gouts ? ld_gos[s] : ld_go, HETA_F32);
-    const int BN = (d_out > 128 && !bf16_direct && !f32_terms) ? 256 : 128;
     int d_in_max = 0;
     for (int s = 0; s < n_seg; ++s) d_in_max = std::max(d_in_max, d_in[s]);
     const bool tall = bf16_direct && d_in_max > 128; // 320 x 128 tiles, one 512-thread workgroup per CU
+    const bool wide_direct = bf16_direct && !tall && d_out > 128; // 128 x 256 tiles, two 512-thread workgroups per CU
+    const int BN = (d_out > 128 && (!bf16_direct || wide_direct) && !f32_terms) ? 256 : 128;
     const int BMt = tall ? 320 : BM;
     for (int s = 0; s < n_seg; ++s) {
         if (!ins[s] || !dW[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
@@ -535,7 +537,7 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     // workgroup's k-tiles are latency-bound when few workgroups run).
     const int64_t BK = in_dt == HETA_F32 ? 32 : 64;
     const int64_t k_tiles = (n_rows + BK - 1) / BK;
-    const int64_t slots_per_xcd = 32 * (tall ? 1 : (bf16_direct || f32_terms) ? 3 : (d_out > 128 ? 2 : (in_dt == HETA_F32 ? 3 : 4)));
+    const int64_t slots_per_xcd = 32 * (tall ? 1 : wide_direct ? 2 : (bf16_direct || f32_terms) ? 3 : (d_out > 128 ? 2 : (in_dt == HETA_F32 ? 3 : 4)));
     // a split's workgroups are (largest segment's row tiles) x (column tiles) x (segments), all on one XCD
     int64_t mt_max = 1;
     for (int s = 0; s < n_seg; ++s) mt_max = std::max<int64_t>(mt_max, (d_in[s] + BMt - 1) / BMt);
