@@ -357,7 +357,8 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
 
     // ---- scratch: one pool block ---------------------------------------------------------------------------
     const int64_t n_sort = std::max(nE, nQ);
-    const int64_t hist_elems = sort_hist_elems(std::max<int64_t>(n_sort, 1));
+    // (the tile size of a sort depends on its length, so the longer sort need not be the one with more tiles)
+    const int64_t hist_elems = std::max(sort_hist_elems(std::max<int64_t>(nE, 1)), sort_hist_elems(std::max<int64_t>(nQ, 1)));
     const size_t n_hist = static_cast<size_t>(2 * n_rel) * 2 * kDegHist;
     const size_t scratch_bytes = carve_size<int64_t>(nR + 1) + carve_size<int64_t>(nS + 1) + 2 * carve_size<int64_t>(nQ) +
                                  2 * carve_size<int64_t>(nQ + 1) + carve_size<int64_t>(scan_scratch_elems(nQ + 1)) +
