@@ -71,11 +71,13 @@ __device__ __forceinline__ int64_t last_le64(const int64_t *a, int64_t n, int64_
     return lo;
 }
 
-enum : unsigned long long { kBadPtr0 = 1, kBadDecrease = 2, kBadTotal = 3, kBadCol = 4, kNoError = ~0ull };
+enum : unsigned long long { kBadPtr0 = 1, kBadDecrease = 2, kBadTotal = 3, kBadCol = 4 };
 
+// The error word holds the complement of the smallest (kind, relation, position) reported, 0 while nothing is:
+// it is cleared by the same fill as the counters beside it.
 __device__ __forceinline__ void report(unsigned long long *err, unsigned long long kind, int rel, int64_t at)
 {
-    atomicMin(err, (kind << 56) | (static_cast<unsigned long long>(rel) << 48) | static_cast<unsigned long long>(at));
+    atomicMax(err, ~((kind << 56) | (static_cast<unsigned long long>(rel) << 48) | static_cast<unsigned long long>(at)));
 }
 
 __device__ __forceinline__ int64_t clamp64(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
@@ -357,8 +359,7 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
 
     // ---- scratch: one pool block ---------------------------------------------------------------------------
     const int64_t n_sort = std::max(nE, nQ);
-    // (the tile size of a sort depends on its length, so the longer sort need not be the one with more tiles)
-    const int64_t hist_elems = std::max(sort_hist_elems(std::max<int64_t>(nE, 1)), sort_hist_elems(std::max<int64_t>(nQ, 1)));
+    const int64_t hist_elems = sort_hist_elems(std::max<int64_t>(n_sort, 1));
     const size_t n_hist = static_cast<size_t>(2 * n_rel) * 2 * kDegHist;
     const size_t scratch_bytes = carve_size<int64_t>(nR + 1) + carve_size<int64_t>(nS + 1) + 2 * carve_size<int64_t>(nQ) +
                                  2 * carve_size<int64_t>(nQ + 1) + carve_size<int64_t>(scan_scratch_elems(nQ + 1)) +
@@ -405,9 +406,8 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
 
     // offsets of relations without rows, chunk ranges of schedules without hub rows: zero unless written
     HETA_BLK(hipMemsetAsync(arena, 0, reinterpret_cast<char *>(hub_chunks) - static_cast<char *>(arena), st));
-    HETA_BLK(hipMemsetAsync(hist, 0, n_hist * sizeof(unsigned long long), st));
-    HETA_BLK(hipMemsetAsync(err, 0xff, sizeof(unsigned long long), st));
-    HETA_BLK(hipMemsetAsync(n_chunks_dev, 0, 2 * n_rel * sizeof(int64_t), st));
+    // one fill for the histograms, the error word and the chunk counts (consecutive pieces)
+    HETA_BLK(hipMemsetAsync(hist, 0, reinterpret_cast<char *>(n_chunks_dev + 2 * n_rel) - reinterpret_cast<char *>(hist), st));
     // the schedule sort's pairs: CSR rows at [0, nR), CSC rows at [nR, nQ) of keyB / valB (keyA / valA serve the transpose first)
     if (nR > 0) {
         hipLaunchKernelGGL(blk_rows_kernel<0>, blocks_for(nR), dim3(256), 0, st, t, in, nR, (int64_t)0, csr_ptr, ptrG_csr, inv_deg, keyB,
@@ -483,8 +483,8 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
     HETA_BLK(hipStreamSynchronize(st));
 #undef HETA_BLK
 #undef HETA_BLK_LAUNCHED
-    const unsigned long long bad = h[n_hist];
-    if (bad != kNoError) {
+    if (h[n_hist] != 0) {
+        const unsigned long long bad = ~h[n_hist];
         const unsigned long long kind = bad >> 56, at = bad & ((1ull << 48) - 1);
         const int which = static_cast<int>((bad >> 48) & 0xff);
         const Relation &r = *rels[which];

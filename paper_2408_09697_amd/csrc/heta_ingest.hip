@@ -23,17 +23,8 @@ namespace {
 
 constexpr int kScanItems = 8;                 // per thread
 constexpr int kScanTile = 256 * kScanItems;   // per workgroup
-// Keys per thread of a sort pass (a workgroup's tile is 256 times that): 16 where there are keys enough for
-// every CU to get a tile that way, fewer for the short arrays of a sampled block, whose few large tiles would
-// leave most of the chip idle behind sixteen barrier-separated rounds each (a pass's scatter then takes 18 us
-// whatever the size).
-inline int sort_rounds_for(int64_t n)
-{
-    int r = 16;
-    while (r > 2 && (n + 256 * r - 1) / (256 * r) < 384) r >>= 1;
-    return r;
-}
-inline int64_t sort_tiles_for(int64_t n) { return (n + 256 * sort_rounds_for(n) - 1) / (256 * sort_rounds_for(n)); }
+constexpr int kSortRounds = 16;               // keys per thread
+constexpr int kSortTile = 256 * kSortRounds;  // keys per workgroup
 
 // Releases its device blocks when it goes out of scope (scratch of one ingest).  The blocks come from the
 // recycling pool, which needs them idle on release: the destructor waits for the device first.
@@ -198,15 +189,14 @@ heta_status exclusive_scan(const TI *in, int64_t n_in, TO *out, int64_t n_out, S
 
 // ---- stable LSD radix sort of (key, value) pairs ------------------------------------------------------
 // hist[digit * n_tiles + tile] = number of keys of the tile with that digit
-template <int ROUNDS>
 __global__ void __launch_bounds__(256) sort_hist_kernel(const uint32_t *keys, int64_t n, int shift, uint32_t *hist, int64_t n_tiles)
 {
     __shared__ uint32_t cnt[256];
     cnt[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t base = static_cast<int64_t>(blockIdx.x) * (256 * ROUNDS);
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kSortTile;
 #pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
+    for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = base + r * 256 + threadIdx.x;
         if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & 255u], 1u); // LDS integer counter: order-independent
     }
@@ -216,7 +206,6 @@ __global__ void __launch_bounds__(256) sort_hist_kernel(const uint32_t *keys, in
 
 // offs = exclusive scan of hist over (digit, tile); every key goes to offs[digit][tile] + its rank
 // among the tile's keys of the same digit, ranks taken in index order (stable).
-template <int ROUNDS>
 __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys, const uint32_t *vals, int64_t n, int shift,
                                                             const uint32_t *offs, int64_t n_tiles, uint32_t *keys_out,
                                                             uint32_t *vals_out)
@@ -228,8 +217,8 @@ __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys,
 #pragma unroll
     for (int w = 0; w < 4; ++w) wave_cnt[w][tid] = 0;
     __syncthreads();
-    const int64_t base = static_cast<int64_t>(blockIdx.x) * (256 * ROUNDS);
-    for (int r = 0; r < ROUNDS; ++r) {
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kSortTile;
+    for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = base + r * 256 + tid;
         const bool valid = i < n;
         const uint32_t key = valid ? keys[i] : 0u;
@@ -266,7 +255,7 @@ __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys,
 
 // Sorts n pairs by the low `bits` bits of the key.  (keys, vals) and (keys_tmp, vals_tmp) are
 // ping-pong buffers; *keys_res / *vals_res point at whichever holds the result.
-// hist, offs: scratch of sort_hist_elems(n) = 256 * sort_tiles_for(n) elements each; tile_sums: scratch
+// hist, offs: scratch of 256 * n_tiles elements each (n_tiles = (n + kSortTile - 1) / kSortTile); tile_sums: scratch
 // for a scan over 256 * n_tiles elements; asynchronous on st
 heta_status radix_sort_pairs_with(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n, int bits,
                                   uint32_t **keys_res, uint32_t **vals_res, uint32_t *hist, uint32_t *offs, uint32_t *tile_sums,
@@ -275,26 +264,14 @@ heta_status radix_sort_pairs_with(uint32_t *keys, uint32_t *vals, uint32_t *keys
     *keys_res = keys;
     *vals_res = vals;
     if (n <= 1 || bits <= 0) return HETA_OK;
-    const int rounds = sort_rounds_for(n);
-    const int64_t n_tiles = sort_tiles_for(n);
+    const int64_t n_tiles = (n + kSortTile - 1) / kSortTile;
     heta_status e;
     uint32_t *ki = keys, *vi = vals, *ko = keys_tmp, *vo = vals_tmp;
     for (int shift = 0; shift < bits; shift += 8) {
-        const dim3 grid((unsigned)n_tiles), block(256);
-        switch (rounds) {
-        case 2: hipLaunchKernelGGL(sort_hist_kernel<2>, grid, block, 0, st, ki, n, shift, hist, n_tiles); break;
-        case 4: hipLaunchKernelGGL(sort_hist_kernel<4>, grid, block, 0, st, ki, n, shift, hist, n_tiles); break;
-        case 8: hipLaunchKernelGGL(sort_hist_kernel<8>, grid, block, 0, st, ki, n, shift, hist, n_tiles); break;
-        default: hipLaunchKernelGGL(sort_hist_kernel<16>, grid, block, 0, st, ki, n, shift, hist, n_tiles); break;
-        }
+        hipLaunchKernelGGL(sort_hist_kernel, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, n, shift, hist, n_tiles);
         HETA_LAUNCH_CHECK("sort_hist_kernel");
         if ((e = exclusive_scan_with<uint32_t, uint32_t>(hist, 256 * n_tiles, offs, 256 * n_tiles, tile_sums, st)) != HETA_OK) return e;
-        switch (rounds) {
-        case 2: hipLaunchKernelGGL(sort_scatter_kernel<2>, grid, block, 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo); break;
-        case 4: hipLaunchKernelGGL(sort_scatter_kernel<4>, grid, block, 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo); break;
-        case 8: hipLaunchKernelGGL(sort_scatter_kernel<8>, grid, block, 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo); break;
-        default: hipLaunchKernelGGL(sort_scatter_kernel<16>, grid, block, 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo); break;
-        }
+        hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo);
         HETA_LAUNCH_CHECK("sort_scatter_kernel");
         std::swap(ki, ko);
         std::swap(vi, vo);
@@ -310,7 +287,7 @@ heta_status radix_sort_pairs(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp,
     *keys_res = keys;
     *vals_res = vals;
     if (n <= 1 || bits <= 0) return HETA_OK;
-    const int64_t n_tiles = sort_tiles_for(n);
+    const int64_t n_tiles = (n + kSortTile - 1) / kSortTile;
     uint32_t *hist = nullptr, *offs = nullptr, *tile_sums = nullptr;
     heta_status e;
     if ((e = scr.get(&hist, static_cast<size_t>(256 * n_tiles))) != HETA_OK) return e;
@@ -588,7 +565,7 @@ heta_status transpose_on_device(const Schedule &csr, int64_t n_src, Schedule &cs
 // ---- the scan and the sort for other translation units (the neighbour sampler) ---------------------------
 // Asynchronous forms with caller-provided scratch (sizes from the two helpers, in elements):
 int64_t scan_scratch_elems(int64_t n_out) { return (n_out + kScanTile - 1) / kScanTile; }
-int64_t sort_hist_elems(int64_t n) { return 256 * sort_tiles_for(n); }
+int64_t sort_hist_elems(int64_t n) { return 256 * ((n + kSortTile - 1) / kSortTile); }
 
 heta_status device_exclusive_scan_i64_async(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, int64_t *tile_sums,
                                             hipStream_t st)
