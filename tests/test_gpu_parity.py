@@ -948,7 +948,7 @@ def test_calibration_mfma_runs_and_reports_its_flops():
         heta.heta_calibration_mfma(heta.HETA_F32, 0, sink)
 
 
-@pytest.mark.parametrize("n,d_in,d_out,trans", [(3000, 384, 256, False), (3000, 256, 128, True), (20000, 128, 256, False),
+@pytest.mark.parametrize("n,d_in,d_out,trans", [(7000, 384, 256, False), (13000, 256, 128, True), (20000, 128, 256, False),
                                                 (777, 300, 40, False)])
 def test_f32_products_as_six_bf16_terms_are_as_accurate_as_the_fp32_mfma(n, d_in, d_out, trans):
     """fp32 projections split every operand into three bf16 terms and feed six MFMA terms per product.  The
@@ -972,8 +972,15 @@ def test_f32_products_as_six_bf16_terms_are_as_accurate_as_the_fp32_mfma(n, d_in
     assert err[True] <= 1e-5 and err[False] <= 1e-5, err
     # no worse than the fp32 MFMA beyond the noise of the summation order
     assert err[False] <= 2.0 * err[True] + 1e-7, err
-    # the weight gradient takes the same path with both operands row-major over the contraction index
     hg = heta.heta_graph_create([(n, 8, 0)], [])
+    # with a graph handle and enough rows for full-size tiles the weights are split once into a packing buffer and
+    # the kernel splits only the features: the same bound
+    if n * ((d_out + 127) // 128) > 96 * 128:
+        out = torch.full((n, d_out), float("nan"), dtype=torch.float32, device="cuda")
+        heta.heta_project_sum([dev_table(x, "f32", 4)], [dev_table(w, "f32", 4)], out, trans_w=trans, graph=hg)
+        err_packed = float((np.abs(out.cpu().numpy().astype(np.float64) - ref) / scale).max())
+        assert err_packed <= 1e-5 and err_packed <= 2.0 * err[True] + 1e-7, (err_packed, err)
+    # the weight gradient takes the same path with both operands row-major over the contraction index
     try:
         gout = (g.standard_normal((n, d_out)) * np.exp2(g.integers(-6, 6, size=(n, d_out)))).astype(np.float32)
         ref_w = x.astype(np.float64).T @ gout.astype(np.float64)
