@@ -506,11 +506,13 @@ heta_status heta_calibration_copy(void *dst, const void *src, int64_t n_bytes, v
 /* Matrix instructions on registers only (no memory traffic): 512 workgroups of four wavefronts, each
  * issuing 16 * iters independent 32 x 32 MFMAs of dt's kind (fp32: 32x32x2, bf16: 32x32x16).  Timing it
  * gives the rate the matrix pipes sustain at the clock the chip holds under that load, the reference
- * point beside the published peak when a projection kernel's MFMA rate is judged.  sink: device,
- * sink_elems >= 2048 floats (overwritten with zeros); flops_out (host, nullable) receives the launch's
- * flop count.  1 <= iters <= 2^24. */
-heta_status heta_calibration_mfma(heta_dtype dt, int64_t iters, float *sink, int64_t sink_elems, double *flops_out,
-                                  void *hip_stream);
+ * point beside the published peak when a projection kernel's MFMA rate is judged.  varying = 0: one
+ * operand pair with zeros on one side; varying != 0: four operand pairs of mixed signs and significands taken
+ * in turn, so that multipliers and accumulators see new bits with every instruction, as they do on real data
+ * (the chip's power management then holds a lower clock).  sink: device, sink_elems >= 2048 floats
+ * (overwritten); flops_out (host, nullable) receives the launch's flop count.  1 <= iters <= 2^24. */
+heta_status heta_calibration_mfma(heta_dtype dt, int32_t varying, int64_t iters, float *sink, int64_t sink_elems,
+                                  double *flops_out, void *hip_stream);
 
 /* Message of the last failure on the calling thread (valid until that thread's next call). */
 const char *heta_last_error(void);

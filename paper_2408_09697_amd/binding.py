@@ -1023,14 +1023,15 @@ def heta_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> 
     _check(L.heta_calibration_copy(_dev(dst, "dst"), _dev(src, "src"), n_bytes, _stream(stream)))
 
 
-def heta_calibration_mfma(dtype: int, iters: int, sink: torch.Tensor, stream=None) -> float:
-    """Launches the register-only MFMA kernel; returns the flops of the launch."""
+def heta_calibration_mfma(dtype: int, iters: int, sink: torch.Tensor, stream=None, varying: bool = False) -> float:
+    """Launches the register-only MFMA kernel (varying: operands that change from instruction to instruction); returns
+    the flops of the launch."""
     L = load_library()
-    L.heta_calibration_mfma.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+    L.heta_calibration_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
                                         ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     flops = ctypes.c_double(0.0)
-    _check(L.heta_calibration_mfma(dtype, iters, _dev(sink, "sink", torch.float32), sink.numel(), ctypes.byref(flops),
-                                   _stream(stream)))
+    _check(L.heta_calibration_mfma(dtype, int(varying), iters, _dev(sink, "sink", torch.float32), sink.numel(),
+                                   ctypes.byref(flops), _stream(stream)))
     return flops.value
 
 

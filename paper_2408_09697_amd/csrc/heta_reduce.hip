@@ -79,7 +79,7 @@ __global__ void __launch_bounds__(256) calibration_copy_kernel(const uint4 *src,
 // per loop trip, none waiting on another); the operands are zero on one side, so the sums stay zero.
 typedef float calib_f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 calib_bf16x8 __attribute__((ext_vector_type(8)));
-template <bool BF16>
+template <bool BF16, bool VARYING>
 __global__ void __launch_bounds__(256) calibration_mfma_kernel(int64_t iters, float *sink)
 {
     calib_f32x16 acc[4];
@@ -87,20 +87,29 @@ __global__ void __launch_bounds__(256) calibration_mfma_kernel(int64_t iters, fl
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-    const float a = static_cast<float>(threadIdx.x & 63) * 0.015625f;
-    calib_bf16x8 av, bv;
+    // VARYING: four operand pairs of mixed signs and significands, taken in turn, so that the multipliers and
+    // the accumulators see new bits with every instruction (what a kernel on real data makes them do); else one
+    // pair with zeros on one side (the sums stay zero)
+    float a[4], b[4];
+    calib_bf16x8 av[4], bv[4];
 #pragma unroll
-    for (int v = 0; v < 8; ++v) {
-        av[v] = static_cast<__bf16>(a);
-        bv[v] = static_cast<__bf16>(0.f);
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t h = (threadIdx.x * 2654435761u + q * 40503u) ^ (threadIdx.x >> 3);
+        a[q] = VARYING ? (static_cast<float>(h & 0xffffu) - 32768.f) * (1.f / 32768.f) : static_cast<float>(threadIdx.x & 63) * 0.015625f;
+        b[q] = VARYING ? (static_cast<float>((h >> 16) & 0xffffu) - 32768.f) * (1.f / 32768.f) : 0.f;
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            av[q][v] = static_cast<__bf16>(VARYING ? a[q] * (0.25f + 0.09375f * v) : a[q]);
+            bv[q][v] = static_cast<__bf16>(VARYING ? b[q] * (1.f - 0.109375f * v) : 0.f);
+        }
     }
     for (int64_t i = 0; i < iters; ++i) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if constexpr (BF16) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[j], 0, 0, 0);
-                else acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, 0.f, acc[j], 0, 0, 0);
+                if constexpr (BF16) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[VARYING ? u : 0], bv[VARYING ? u : 0], acc[j], 0, 0, 0);
+                else acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[VARYING ? u : 0], b[VARYING ? u : 0], acc[j], 0, 0, 0);
             }
     }
     float t = 0.f;
@@ -203,7 +212,7 @@ heta_status heta_calibration_copy(void *dst, const void *src, int64_t n_bytes, v
     return HETA_OK;
 }
 
-heta_status heta_calibration_mfma(heta_dtype dt, int64_t iters, float *sink, int64_t sink_elems, double *flops_out,
+heta_status heta_calibration_mfma(heta_dtype dt, int32_t varying, int64_t iters, float *sink, int64_t sink_elems, double *flops_out,
                                   void *hip_stream)
 {
     constexpr int kBlocks = 512; // two workgroups of four wavefronts per CU: two wavefronts per SIMD
@@ -214,10 +223,11 @@ heta_status heta_calibration_mfma(heta_dtype dt, int64_t iters, float *sink, int
     const double flops = per_mfma * 16.0 * static_cast<double>(iters) * 4.0 * kBlocks;
     if (flops_out) *flops_out = flops;
     ProfScope prof("calibration_mfma_kernel", as_stream(hip_stream), 0, flops);
-    if (dt == HETA_BF16)
-        hipLaunchKernelGGL(calibration_mfma_kernel<true>, dim3(kBlocks), dim3(256), 0, as_stream(hip_stream), iters, sink);
-    else
-        hipLaunchKernelGGL(calibration_mfma_kernel<false>, dim3(kBlocks), dim3(256), 0, as_stream(hip_stream), iters, sink);
+    const dim3 grid(kBlocks), block(256);
+    if (dt == HETA_BF16 && varying) hipLaunchKernelGGL((calibration_mfma_kernel<true, true>), grid, block, 0, as_stream(hip_stream), iters, sink);
+    else if (dt == HETA_BF16) hipLaunchKernelGGL((calibration_mfma_kernel<true, false>), grid, block, 0, as_stream(hip_stream), iters, sink);
+    else if (varying) hipLaunchKernelGGL((calibration_mfma_kernel<false, true>), grid, block, 0, as_stream(hip_stream), iters, sink);
+    else hipLaunchKernelGGL((calibration_mfma_kernel<false, false>), grid, block, 0, as_stream(hip_stream), iters, sink);
     HETA_LAUNCH_CHECK("calibration_mfma_kernel");
     return HETA_OK;
 }

@@ -942,6 +942,12 @@ def test_calibration_mfma_runs_and_reports_its_flops():
     assert heta.heta_calibration_mfma(heta.HETA_BF16, 10, sink) == 2.0 * 32 * 32 * 16 * 16 * 10 * 4 * 512
     torch.cuda.synchronize()
     assert float(sink.abs().max()) == 0.0  # one operand is zero: the accumulators stay zero
+    for dt in (heta.HETA_F32, heta.HETA_BF16):   # varying operands: the same work, finite non-zero sums
+        sink.zero_()
+        assert heta.heta_calibration_mfma(dt, 10, sink, varying=True) == heta.heta_calibration_mfma(dt, 10, sink)
+        heta.heta_calibration_mfma(dt, 10, sink, varying=True)
+        torch.cuda.synchronize()
+        assert torch.isfinite(sink[:2048]).all() and (sink[:2048] != 0).any()
     with pytest.raises(heta.HetaError):
         heta.heta_calibration_mfma(heta.HETA_F32, 10, sink[:100])
     with pytest.raises(heta.HetaError):
