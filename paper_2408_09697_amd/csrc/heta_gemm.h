@@ -259,6 +259,7 @@ heta_status pack_split3_weights(const float *W, int64_t ldw, int64_t K, int64_t 
                                 hipStream_t st);
 // whether the direct pipeline would give this launch its 64 x 64 tiles (too few 128 x 128 tiles to fill the chip)
 bool gemm_direct_small(const GemmParams &p);
+int wgrad_tile_rows(const GemmParams &p);
 heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, bool a_rc, bool b_rc, hipStream_t st,
                                const char *name, double bytes, double flops, bool *handled);
 

@@ -938,6 +938,18 @@ heta_status pack_split3_weights(const float *W, int64_t ldw, int64_t K, int64_t 
     return HETA_OK;
 }
 
+// rows of the output tile a weight gradient with more than 128 input and output columns takes: 320 or 256,
+// whichever pads the input columns (the tile rows) less over all segments
+int wgrad_tile_rows(const GemmParams &p)
+{
+    int64_t pad320 = 0, pad256 = 0;
+    for (int s = 0; s < p.n_seg; ++s) {
+        pad320 += (p.seg[s].M + 319) / 320 * 320;
+        pad256 += (p.seg[s].M + 255) / 256 * 256;
+    }
+    return pad256 < pad320 ? 256 : 320;
+}
+
 heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, bool a_rc, bool b_rc, hipStream_t st,
                                const char *name, double bytes, double flops, bool *handled)
 {
@@ -965,6 +977,17 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         *handled = true;
         int64_t m_max = 0;
         for (int s = 0; s < p.n_seg; ++s) m_max = std::max(m_max, p.seg[s].M);
+        if (m_max > 128 && n_max > 128) {
+            // inputs wider than 128 columns and more than 128 output columns: 320 x 256 tiles (8 wavefronts of 5 x 2
+            // accumulators, one workgroup per CU), or 256 x 256 (4 x 2) when that covers the input columns with less
+            // padding.  Per MFMA the workgroup loads two thirds of what a 320 x 128 tile loads, and these launches are
+            // bound by the loads a CU can keep in flight: 1.52 -> 0.93 ms on 6 x (500 k x 300)^T (500 k x 256).
+            if (wgrad_tile_rows(p) == 256)
+                return p.split_b ? launch_direct<bf16_t, bf16_t, true, true, float, true, true, 4, 16, 4, 1, true, 4, 2, 2>(p, st, name, bytes, flops)
+                                 : launch_direct<bf16_t, bf16_t, true, true, float, true, true, 4, 16, 4, 1, false, 4, 2, 2>(p, st, name, bytes, flops);
+            return p.split_b ? launch_direct<bf16_t, bf16_t, true, true, float, true, true, 4, 16, 4, 1, true, 5, 2, 2>(p, st, name, bytes, flops)
+                             : launch_direct<bf16_t, bf16_t, true, true, float, true, true, 4, 16, 4, 1, false, 5, 2, 2>(p, st, name, bytes, flops);
+        }
         if (m_max > 128) {
             // inputs wider than 128 columns: 320 x 128 tiles (8 wavefronts of 5 x 1 accumulators), so that up to 320
             // input columns share one pass over the gradient operand, which is the larger of the two
@@ -982,9 +1005,9 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
     }
     bool wide = n_max > 128;
     if (wide) {
-        // A launch that gives a workgroup to half the CUs at most (the projections of a sampled mini-batch
-        // block) is bound by the matrix pipe of the few CUs it runs on: a 128 x 256 tile keeps two wavefronts
-        // per SIMD busy for 32 MFMAs each per k-step.  128 x 128 tiles put the same work on twice the CUs.
+        // A launch of at most one and a half 128 x 256 tiles per CU (the projections of a sampled mini-batch
+        // block) runs as one uneven round of workgroups, each a serial chain of k-steps with nothing beside it
+        // on its CU: 128 x 128 tiles put the same work on twice the workgroups, two or three to a CU.
         int64_t mt = 0, nt = 0;
         for (int s = 0; s < p.n_seg; ++s) {
             mt = std::max(mt, (p.seg[s].M + BM - 1) / BM);
@@ -992,7 +1015,7 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
         }
         const int64_t inner = nt * (p.batch ? p.n_seg : 1) * (p.partial ? mt : 1);
         const int64_t outer = p.partial ? std::max(1, p.n_split) : mt;
-        if (outer * inner <= 128) wide = false;
+        if (outer * inner <= 384) wide = false;
     }
     // Fewer than a hundred 128 x 128 tiles (the projections of a sampled mini-batch block: a few thousand rows):
     // every tile is a serial chain of MFMAs on one CU while most CUs idle.  64 x 64 tiles (four wavefronts of one
@@ -1043,8 +1066,16 @@ heta_status launch_gemm_direct(GemmParams &p, heta_dtype a_dt, heta_dtype b_dt, 
     }
     if (a_dt == HETA_F32 && b_dt == HETA_BF16 && !a_rc && !b_rc) { // backward: G (fp32, rounded at the MFMA) x W_r^T (bf16, k-contiguous)
         // (256 output columns: 16 k-values per stage keep the fp32 tiles of A small enough for two workgroups per CU)
-        if (n_max > 256 && n_max <= 320) // 128 x 320 tiles (8 wavefronts of 1 x 5 accumulators): the fp32 rows of A are read once
+        if (n_max > 256 && n_max <= 320) {
+            // 320 output columns in one tile (wavefronts of MI x 5 accumulators): the fp32 rows of A are read once.  256 rows
+            // per tile (one workgroup per CU) where the launch still fills the chip several times: W_r^T, re-read by every
+            // workgroup, is then loaded once per 256 rows (1.25 -> 0.92 ms on 6 x (500 k x 256)(256 x 300)); else 128 rows.
+            int64_t m_all = 0;
+            for (int s = 0; s < p.n_seg; ++s) m_all = std::max(m_all, p.seg[s].M);
+            if (m_all >= 256 * 1024)
+                return launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 16, 4, 1, false, 2, 5, 4>(p, st, name, bytes, flops);
             return launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 16, 4, 2, false, 1, 5, 4>(p, st, name, bytes, flops);
+        }
         return wide ? launch_direct<bf16_t, float, false, true, bf16_t, false, true, 4, 16, 4, 4>(p, st, name, bytes, flops)
                     : launch_direct<bf16_t, float, false, true, bf16_t, false, true, 2, 32, 3, 2>(p, st, name, bytes, flops);
     }

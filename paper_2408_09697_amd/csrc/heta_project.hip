@@ -510,8 +510,17 @@ static heta_status wgrad_impl(heta_graph *g, int64_t n_rows, int n_seg, const vo
     for (int s = 0; s < n_seg; ++s) d_in_max = std::max(d_in_max, d_in[s]);
     const bool tall = bf16_direct && d_in_max > 128; // 320 x 128 tiles, one 512-thread workgroup per CU
     const bool wide_direct = bf16_direct && !tall && d_out > 128; // 128 x 256 tiles, two 512-thread workgroups per CU
-    const int BN = (d_out > 128 && (!bf16_direct || wide_direct) && !f32_terms) ? 256 : 128;
-    const int BMt = tall ? 320 : BM;
+    const bool tall_wide = tall && d_out > 128;                   // 320 x 256 or 256 x 256 tiles, one workgroup per CU
+    const int BN = (d_out > 128 && (!bf16_direct || wide_direct || tall_wide) && !f32_terms) ? 256 : 128;
+    int BMt = tall ? 320 : BM;
+    if (tall_wide) { // the tile height the launch will choose (wgrad_tile_rows): the one that pads the input columns less
+        int64_t pad320 = 0, pad256 = 0;
+        for (int s = 0; s < n_seg; ++s) {
+            pad320 += (static_cast<int64_t>(d_in[s]) + 319) / 320 * 320;
+            pad256 += (static_cast<int64_t>(d_in[s]) + 255) / 256 * 256;
+        }
+        if (pad256 < pad320) BMt = 256;
+    }
     for (int s = 0; s < n_seg; ++s) {
         if (!ins[s] || !dW[s]) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
         if (d_in[s] <= 0 || ld_in[s] < d_in[s] || ld_dw[s] < d_out) return fail(HETA_ERR_SHAPE, "%s: bad sizes", who);
