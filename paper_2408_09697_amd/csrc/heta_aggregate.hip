@@ -279,7 +279,7 @@ __host__ __device__ inline int batch_rows(int k, int G)
 }
 
 template <typename T, int EPC, int L, int CPL, bool DUAL>
-__device__ __forceinline__ void agg_batch_body(const AggParams &p)
+__device__ __forceinline__ void agg_batch_body(const AggParams &p, const unsigned bx = blockIdx.x)
 {
     constexpr int G = 64 / L;          // lane groups = rows in progress per wavefront
     constexpr int U = CPL == 1 ? 8 : 4; // row loads in flight per lane group
@@ -287,7 +287,7 @@ __device__ __forceinline__ void agg_batch_body(const AggParams &p)
     __shared__ float w_s[4][kBatchIds];
     __shared__ int32_t row_s[4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int w = blockIdx.x * 4 + wave;
+    const int w = bx * 4 + wave;
     const bool active = w < p.batch0[kShortDeg]; // uniform per wavefront; idle wavefronts still reach the barrier
     int k = 0, nrows = 0;
     int64_t e0 = 0;
@@ -437,7 +437,7 @@ __device__ __forceinline__ void agg_batch_body(const AggParams &p)
 // sampled block), where one wavefront per item leaves most of the chip idle behind a serial walk of up to 511
 // edges.
 template <typename T, int EPC, int L, int CPL, bool DUAL, bool SPLIT = false>
-__device__ __forceinline__ void agg_wave_body(const AggParams &p)
+__device__ __forceinline__ void agg_wave_body(const AggParams &p, const unsigned bx = blockIdx.x)
 {
     constexpr int G = 64 / L;            // lane groups per wavefront
     constexpr int U = CPL == 2 ? 4 : ((G >= 16) ? 1 : ((G >= 8) ? 2 : ((G >= 4) ? 4 : 8))); // edges in flight per group and step
@@ -445,7 +445,7 @@ __device__ __forceinline__ void agg_wave_body(const AggParams &p)
     __shared__ float part_s[SPLIT ? 3 : 1][SPLIT ? NACC : 1][SPLIT ? L : 1]; // wavefronts 1..3, one value per (sum element, lane of group 0)
     const int lane = threadIdx.x & 63;
     const int ws = SPLIT ? static_cast<int>(threadIdx.x >> 6) : 0;
-    const int64_t w = SPLIT ? static_cast<int64_t>(blockIdx.x) : static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t w = SPLIT ? static_cast<int64_t>(bx) : static_cast<int64_t>(bx) * 4 + (threadIdx.x >> 6);
     if (w >= p.n_wave_items) return;     // uniform per wavefront (per workgroup with SPLIT)
     int64_t e0, e1, row = -1;
     int slot = -1;
@@ -651,8 +651,24 @@ __global__ void __launch_bounds__(256) agg_wave_split_kernel(AggParams p) { agg_
 template <typename T, int EPC, int L, int CPL, bool DUAL>
 __global__ void __launch_bounds__(256) agg_wave_split_multi_kernel(AggMulti m) { agg_wave_body<T, EPC, L, CPL, DUAL, true>(m.p[blockIdx.z]); }
 __global__ void __launch_bounds__(64 * kCombineWaves) agg_hub_combine_multi_kernel(AggMulti m) { agg_hub_combine_body(m.p[blockIdx.z]); }
+// Both row classes of a small launch in one grid: the first `wave_blocks` workgroups along x walk the split long rows,
+// the rest the batches of short rows.  A sampled block has a handful of long rows; as a launch of their own they
+// keep a few CUs busy for a serial walk of several hundred edges while the rest of the chip waits for the next kernel.
+template <typename T, int EPC, int L, int CPL, bool DUAL>
+__global__ void __launch_bounds__(256) agg_pair_kernel(AggParams p, unsigned wave_blocks)
+{
+    if (blockIdx.x < wave_blocks) agg_wave_body<T, EPC, L, CPL, DUAL, true>(p, blockIdx.x);
+    else agg_batch_body<T, EPC, L, CPL, DUAL>(p, blockIdx.x - wave_blocks);
+}
+template <typename T, int EPC, int L, int CPL, bool DUAL>
+__global__ void __launch_bounds__(256) agg_pair_multi_kernel(AggMulti m, unsigned wave_blocks)
+{
+    if (blockIdx.x < wave_blocks) agg_wave_body<T, EPC, L, CPL, DUAL, true>(m.p[blockIdx.z], blockIdx.x);
+    else agg_batch_body<T, EPC, L, CPL, DUAL>(m.p[blockIdx.z], blockIdx.x - wave_blocks);
+}
 
 // ---- launch ---------------------------------------------------------------------------------------
+constexpr int64_t kPairWaveBlocks = 256; // split long rows up to which both row classes share a launch
 // algorithmic bytes of the two row classes of one call (for the optional profiler)
 struct AggCost {
     double wave_bytes = 0, group_bytes = 0;
@@ -675,6 +691,16 @@ static heta_status launch_pair(const AggParams *ps, int n, int n_super, hipStrea
     AggMulti m{};
     if (n > 1)
         for (int i = 0; i < n; ++i) m.p[i] = ps[i];
+    if (split && wave_blocks > 0 && wave_blocks <= kPairWaveBlocks && batch_blocks > 0) {
+        ProfScope prof(cost.timed ? "agg_batch_kernel" : nullptr, st, cost.wave_bytes + cost.group_bytes, 0);
+        const unsigned blocks = static_cast<unsigned>(wave_blocks + batch_blocks);
+        if (n == 1)
+            hipLaunchKernelGGL((agg_pair_kernel<T, EPC, L, CPL, DUAL>), dim3(blocks, n_super), dim3(256), 0, st, ps[0], (unsigned)wave_blocks);
+        else
+            hipLaunchKernelGGL((agg_pair_multi_kernel<T, EPC, L, CPL, DUAL>), dim3(blocks, n_super, n), dim3(256), 0, st, m, (unsigned)wave_blocks);
+        HETA_LAUNCH_CHECK("agg_pair_kernel");
+        return HETA_OK;
+    }
     if (wave_blocks > 0) {
         ProfScope prof(cost.timed ? "agg_wave_kernel" : nullptr, st, cost.wave_bytes, 0);
         if (split && n == 1)

@@ -445,13 +445,15 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
     }
     // B[k][n] = W[k][n] is n-contiguous (r-contiguous in the loader's terms); W^T is k-contiguous
     if (transW) return dispatch_gemm<false, false>(p, in_dt, w_dt, st);
-    if (pack_owner && !g_force_staged && in_dt == HETA_BF16 && w_dt == HETA_BF16) {
-        // bf16 forward with a graph handle: the small W_r are first rewritten k-contiguous into the
-        // handle's packing buffer, so that both operands can stream into LDS without a register stage
+    if (pack_owner && !g_force_staged && w_dt == HETA_BF16) {
+        // forward with bf16 weights and a graph handle: the small W_r are first rewritten k-contiguous into the
+        // handle's packing buffer, so that both operands can stream into LDS without a register stage (fp32
+        // inputs, an inner layer's embeddings, are rounded to bf16 when their fragments are read, as the
+        // register-staged kernel rounds them when it stages them)
         bool ok = true;
         size_t bytes = 0;
         for (int s = 0; s < n_seg; ++s) {
-            ok = ok && aligned16(ins[s]) && (ld_in[s] * 2) % 16 == 0;
+            ok = ok && aligned16(ins[s]) && (ld_in[s] * static_cast<int64_t>(dtype_size(in_dt))) % 16 == 0;
             bytes += static_cast<size_t>(d_out) * ((d_in[s] + 7) / 8 * 8) * 2 + 256;
         }
         if (ok) {
