@@ -227,13 +227,26 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(SplitSegs g, int n_s
     *o = (beta != 0.f) ? beta * *o + a : a;
 }
 
-// out[n][k] = W[k][n]: a bf16 weight matrix laid out k-contiguous, the form the direct-to-LDS
-// pipeline can copy into LDS as is (an n-contiguous bf16 operand would need pair interleaving)
-__global__ void __launch_bounds__(256) pack_weight_kernel(const bf16_t *W, int64_t ldw, int K, int N, bf16_t *out, int ld_out)
+// out[n][k] = W[k][n]: bf16 weight matrices laid out k-contiguous, the form the direct-to-LDS
+// pipeline can copy into LDS as is (an n-contiguous bf16 operand would need pair interleaving).
+// blockIdx.z picks the matrix: the weights of every segment of a product in one launch.
+struct PackSegs {
+    const bf16_t *W[kMaxSeg];
+    bf16_t *out[kMaxSeg];
+    int64_t ldw[kMaxSeg];
+    int K[kMaxSeg], ld_out[kMaxSeg];
+};
+__global__ void __launch_bounds__(256) pack_weight_kernel(PackSegs q, int N)
 {
     __shared__ bf16_t tile[32][33];
+    const int s = blockIdx.z;
+    const bf16_t *W = q.W[s];
+    bf16_t *out = q.out[s];
+    const int64_t ldw = q.ldw[s];
+    const int K = q.K[s], ld_out = q.ld_out[s];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5; // 32 x 8
     const int k0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    if (k0 >= ld_out) return; // uniform per workgroup: a narrower matrix of the launch
     for (int r = ty; r < 32; r += 8)
         tile[r][tx] = (k0 + r < K && n0 + tx < N) ? W[static_cast<int64_t>(k0 + r) * ldw + n0 + tx] : bf16_t(0);
     __syncthreads();
@@ -460,15 +473,22 @@ static heta_status project_impl(int64_t n_rows, int n_seg, const void *const *in
             heta_status pe = ensure_pack(pack_owner, bytes);
             if (pe != HETA_OK) return pe;
             char *dst = static_cast<char *>(pack_owner->d_pack);
+            PackSegs q{};
+            int ldp_max = 0;
             for (int s = 0; s < n_seg; ++s) {
                 const int ldp = (d_in[s] + 7) / 8 * 8;
-                hipLaunchKernelGGL(pack_weight_kernel, dim3((d_out + 31) / 32, (ldp + 31) / 32), dim3(256), 0, st,
-                                   static_cast<const bf16_t *>(Ws[s]), ld_w[s], d_in[s], d_out, reinterpret_cast<bf16_t *>(dst), ldp);
-                HETA_LAUNCH_CHECK("pack_weight_kernel");
+                q.W[s] = static_cast<const bf16_t *>(Ws[s]);
+                q.out[s] = reinterpret_cast<bf16_t *>(dst);
+                q.ldw[s] = ld_w[s];
+                q.K[s] = d_in[s];
+                q.ld_out[s] = ldp;
+                ldp_max = std::max(ldp_max, ldp);
                 p.seg[s].B = dst;
                 p.seg[s].ldb = ldp;
                 dst += (static_cast<size_t>(d_out) * ldp * 2 + 255) / 256 * 256;
             }
+            hipLaunchKernelGGL(pack_weight_kernel, dim3((d_out + 31) / 32, (ldp_max + 31) / 32, n_seg), dim3(256), 0, st, q, d_out);
+            HETA_LAUNCH_CHECK("pack_weight_kernel");
             return dispatch_gemm<false, false>(p, in_dt, w_dt, st);
         }
     }
