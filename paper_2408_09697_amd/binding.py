@@ -6,6 +6,7 @@ inside the library's HIP kernels; there is no fallback: a missing library is an 
 from __future__ import annotations
 
 import ctypes
+import struct
 import os
 from typing import List, Optional, Sequence
 
@@ -182,20 +183,27 @@ def heta_last_error() -> str:
     return load_library().heta_last_error().decode()
 
 
+_NT_PACK = struct.Struct("=qii")            # heta_ntype
+_REL_PACK = struct.Struct("=iiqQQQQi4x")     # heta_relation
+assert _NT_PACK.size == ctypes.sizeof(_NType) and _REL_PACK.size == ctypes.sizeof(_Relation)
+
+
 def _marshal_graph(ntypes: Sequence[Sequence[int]], relations: Sequence[Sequence], flags: int):
-    """The C arrays of one heta_graph_create call, what keeps their memory alive, and the relations' (s, t, E)."""
-    nt = (_NType * max(1, len(ntypes)))()
+    """The C arrays of one heta_graph_create call (packed byte buffers laid out as heta_ntype[] and
+    heta_relation[]), what keeps their memory alive, and the relations' (s, t, E)."""
+    nt = ctypes.create_string_buffer(_NT_PACK.size * max(1, len(ntypes)))
     for i, (n, d, l) in enumerate(ntypes):
-        nt[i] = _NType(int(n), int(d), int(l))
-    rl = (_Relation * max(1, len(relations)))()
+        _NT_PACK.pack_into(nt, i * _NT_PACK.size, int(n), int(d), int(l))
+    rl = ctypes.create_string_buffer(_REL_PACK.size * max(1, len(relations)))
     keep = []
     meta = []
+    on_device = bool(flags & HETA_PTRS_ON_DEVICE)
     for i, relation in enumerate(relations):
         s, t, rowptr, col = relation[:4]
-        extras = relation[4] if len(relation) > 4 else {}
-        csc = extras.get("csc")
-        ccp = crp = None
-        if flags & HETA_PTRS_ON_DEVICE:
+        extras = relation[4] if len(relation) > 4 else None
+        csc = extras.get("csc") if extras else None
+        ccp = crp = 0
+        if on_device:
             rp = _dev(rowptr, "rowptr", torch.int64)
             cp = _dev(col, "col", torch.int32)
             n_e = int(col.numel())
@@ -205,14 +213,16 @@ def _marshal_graph(ntypes: Sequence[Sequence[int]], relations: Sequence[Sequence
         else:
             rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
             col = np.ascontiguousarray(col, dtype=np.int32)
-            rp, cp, n_e = rowptr.ctypes.data, col.ctypes.data, int(col.size)
+            rp, cp, n_e = rowptr.__array_interface__["data"][0], col.__array_interface__["data"][0], int(col.size)
             if csc is not None:
                 c0, c1 = np.ascontiguousarray(csc[0], dtype=np.int64), np.ascontiguousarray(csc[1], dtype=np.int32)
-                ccp, crp = c0.ctypes.data, c1.ctypes.data
+                ccp, crp = c0.__array_interface__["data"][0], c1.__array_interface__["data"][0]
                 keep += [c0, c1]
         keep += [rowptr, col]
-        rl[i] = _Relation(int(s), int(t), n_e, rp, cp, ccp, crp, int(extras.get("reverse_of", -1)))
-        meta.append((int(s), int(t), n_e))
+        s, t = int(s), int(t)
+        _REL_PACK.pack_into(rl, i * _REL_PACK.size, s, t, n_e, rp or 0, cp or 0, ccp or 0, crp or 0,
+                            int(extras.get("reverse_of", -1)) if extras else -1)
+        meta.append((s, t, n_e))
     return nt, rl, keep, meta
 
 

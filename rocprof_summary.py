@@ -50,7 +50,11 @@ def family(name: str) -> str:
         wgrad = (args[2] == "true" and args[4] == "true") if base == "gemm_kernel" else (args[2] == "true" and args[5] == "true")
         return f"gemm_wgrad_{ct}" if wgrad else f"gemm_{ct}"
     if base.endswith("_multi_kernel"):  # several relations per launch: timed under the single-relation kernel's name
-        return base[:-len("_multi_kernel")] + "_kernel"
+        base = base[:-len("_multi_kernel")] + "_kernel"
+    if base == "agg_wave_split_kernel":  # the long rows of a small launch, four wavefronts per row
+        return "agg_wave_kernel"
+    if base == "agg_pair_kernel":  # both row classes of a small launch in one grid: timed as its short-row part
+        return "agg_batch_kernel"
     return base
 
 
