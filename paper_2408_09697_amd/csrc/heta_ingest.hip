@@ -210,44 +210,71 @@ __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys,
                                                             const uint32_t *offs, int64_t n_tiles, uint32_t *keys_out,
                                                             uint32_t *vals_out)
 {
-    __shared__ uint32_t bin_base[256];    // next free output slot of each digit for this tile
-    __shared__ uint32_t wave_cnt[4][256]; // keys of each digit per wavefront in the current round
+    // A step places kSortStep x 256 consecutive keys: sub-round q holds the keys base + (step * kSortStep + q) * 256 + tid,
+    // so index order is (q, wavefront, lane).  Three barriers per step instead of per 256 keys.
+    constexpr int kSortStep = 4;
+    static_assert(kSortRounds % kSortStep == 0, "a tile is a whole number of steps");
+    __shared__ uint32_t bin_base[256];               // next free output slot of each digit for this tile
+    __shared__ uint32_t wave_cnt[kSortStep][4][256]; // keys of each digit per (sub-round, wavefront) in the current step
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     bin_base[tid] = offs[static_cast<int64_t>(tid) * n_tiles + blockIdx.x];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) wave_cnt[w][tid] = 0;
-    __syncthreads();
+    for (int q = 0; q < kSortStep; ++q)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) wave_cnt[q][w][tid] = 0;
     const int64_t base = static_cast<int64_t>(blockIdx.x) * kSortTile;
+    // every round's key and value are loaded before the first step: one memory latency per tile instead of one
+    // per step (the steps are chained through barriers, so a load inside a step is never in flight with the next)
+    uint32_t key_r[kSortRounds], val_r[kSortRounds];
+#pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = base + r * 256 + tid;
-        const bool valid = i < n;
-        const uint32_t key = valid ? keys[i] : 0u;
-        const uint32_t val = valid ? vals[i] : 0u;
-        const uint32_t d = (key >> shift) & 255u;
-        // lanes of this wavefront holding the same digit
-        uint64_t peers = __ballot(valid);
+        key_r[r] = i < n ? keys[i] : 0u;
+        val_r[r] = i < n ? vals[i] : 0u;
+    }
+    __syncthreads();
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const uint64_t bal = __ballot(bit);
-            peers &= bit ? bal : ~bal;
+    for (int r0 = 0; r0 < kSortRounds; r0 += kSortStep) {
+        uint32_t rank[kSortStep];
+#pragma unroll
+        for (int q = 0; q < kSortStep; ++q) {
+            const bool valid = base + (r0 + q) * 256 + tid < n;
+            const uint32_t d = (key_r[r0 + q] >> shift) & 255u;
+            // lanes of this wavefront holding the same digit in this sub-round
+            uint64_t peers = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const bool bit = (d >> b) & 1u;
+                const uint64_t bal = __ballot(bit);
+                peers &= bit ? bal : ~bal;
+            }
+            rank[q] = __popcll(peers & ((uint64_t(1) << lane) - 1));
+            if (valid && rank[q] == 0) wave_cnt[q][wave][d] = __popcll(peers);
         }
-        const uint32_t rank = __popcll(peers & ((uint64_t(1) << lane) - 1));
-        if (valid && rank == 0) wave_cnt[wave][d] = __popcll(peers);
         __syncthreads();
-        if (valid) {
-            uint32_t pos = bin_base[d] + rank;
-            for (int w = 0; w < wave; ++w) pos += wave_cnt[w][d];
-            keys_out[pos] = key;
-            vals_out[pos] = val;
+#pragma unroll
+        for (int q = 0; q < kSortStep; ++q) {
+            if (base + (r0 + q) * 256 + tid < n) {
+                const uint32_t key = key_r[r0 + q], d = (key >> shift) & 255u;
+                uint32_t pos = bin_base[d] + rank[q];
+#pragma unroll
+                for (int qq = 0; qq < q; ++qq)
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) pos += wave_cnt[qq][w][d];
+                for (int w = 0; w < wave; ++w) pos += wave_cnt[q][w][d];
+                keys_out[pos] = key;
+                vals_out[pos] = val_r[r0 + q];
+            }
         }
         __syncthreads();
         uint32_t add = 0;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            add += wave_cnt[w][tid];
-            wave_cnt[w][tid] = 0;
-        }
+        for (int q = 0; q < kSortStep; ++q)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                add += wave_cnt[q][w][tid];
+                wave_cnt[q][w][tid] = 0;
+            }
         bin_base[tid] += add;
         __syncthreads();
     }
