@@ -86,12 +86,31 @@ __device__ __forceinline__ int64_t clamp64(int64_t x, int64_t lo, int64_t hi) { 
 // CSC (CSC = 1): from the global column offsets found in the sorted keys.  Writes the relation-local offsets,
 // the global offsets (CSR only; the CSC's are an input), 1/deg (CSR only), the schedule sort pair and the
 // degree histograms of the row's schedule.
+constexpr int kBlkRowsThreads = 1024; // rows per workgroup of blk_rows_kernel
+constexpr int kBlkLocalSched = 4;     // schedules whose histograms a workgroup keeps in LDS
 template <int CSC>
-__global__ void __launch_bounds__(256) blk_rows_kernel(BlockTables t, BlockInputs in, int64_t n_rows_total, int64_t sched_pos0,
-                                                       int64_t *ptr_local, int64_t *ptr_global, float *inv_deg, uint32_t *key,
-                                                       uint32_t *val, unsigned long long *hist, unsigned long long *err)
+__global__ void __launch_bounds__(kBlkRowsThreads) blk_rows_kernel(BlockTables t, BlockInputs in, int64_t n_rows_total, int64_t sched_pos0,
+                                                                   int64_t *ptr_local, int64_t *ptr_global, float *inv_deg, uint32_t *key,
+                                                                   uint32_t *val, unsigned long long *hist, unsigned long long *err)
 {
-    const int64_t R = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    // degree histograms of the workgroup's rows: the schedule of its first row and the three after it (a workgroup's
+    // 1,024 consecutive rows rarely span more) are counted in LDS and reach the global counters once per workgroup and
+    // bin; counted per wavefront, the few thousand wavefronts of a block queued up on the counters of degrees 1 and 2
+    __shared__ unsigned int rows_s[kBlkLocalSched][kDegHist];
+    __shared__ unsigned long long edges_s[kBlkLocalSched][kDegHist];
+    __shared__ int sched0_s;
+    for (int k = threadIdx.x; k < kBlkLocalSched * kDegHist; k += kBlkRowsThreads) {
+        (&rows_s[0][0])[k] = 0;
+        (&edges_s[0][0])[k] = 0;
+    }
+    if (threadIdx.x == 0) {
+        const int64_t R0 = static_cast<int64_t>(blockIdx.x) * kBlkRowsThreads;
+        const int rel0 = R0 < n_rows_total ? seg_of(CSC ? t.src_off : t.dst_off, t.n_rel, R0) : 0;
+        sched0_s = CSC ? t.n_rel + rel0 : rel0;
+    }
+    __syncthreads();
+    const int sched0 = sched0_s;
+    const int64_t R = static_cast<int64_t>(blockIdx.x) * kBlkRowsThreads + threadIdx.x;
     const bool live = R < n_rows_total;
     uint32_t hkey = 0xffffffffu; // (schedule, capped degree) of this lane's row, for the histogram at the end
     int64_t hdeg = 0;
@@ -127,23 +146,26 @@ __global__ void __launch_bounds__(256) blk_rows_kernel(BlockTables t, BlockInput
     hkey = (static_cast<uint32_t>(sched) << 10) | static_cast<uint32_t>(capped);
     hdeg = deg;
     }
-    // Degree histograms: the rows of a wavefront that share (schedule, capped degree) are counted by one lane, so a
-    // relation whose rows nearly all have the same degree does not queue its rows up on one counter.
-    unsigned long long todo = __ballot(live);
-    const int lane = threadIdx.x & 63;
-    while (todo) {
-        const int leader = __ffsll(static_cast<long long>(todo)) - 1;
-        const uint32_t lk = __shfl(hkey, leader, 64);
-        const unsigned long long same = __ballot(live && hkey == lk);
-        const int capped = static_cast<int>(lk & 1023u);
-        unsigned long long *h = hist + static_cast<int64_t>(lk >> 10) * 2 * kDegHist;
-        if (lane == leader) {
-            const unsigned long long n = static_cast<unsigned long long>(__popcll(same));
-            atomicAdd(&h[capped], n);
-            if (capped < kHubMinDeg) atomicAdd(&h[kDegHist + capped], n * static_cast<unsigned long long>(capped));
+    if (live) {
+        const int sched = static_cast<int>(hkey >> 10), capped = static_cast<int>(hkey & 1023u);
+        const int ls = sched - sched0;
+        if (ls >= 0 && ls < kBlkLocalSched) {
+            atomicAdd(&rows_s[ls][capped], 1u);
+            atomicAdd(&edges_s[ls][capped], static_cast<unsigned long long>(hdeg));
+        } else { // a workgroup that spans more than four schedules: straight to the global counters
+            unsigned long long *h = hist + static_cast<int64_t>(sched) * 2 * kDegHist;
+            atomicAdd(&h[capped], 1ull);
+            atomicAdd(&h[kDegHist + capped], static_cast<unsigned long long>(hdeg));
         }
-        if (capped == kHubMinDeg && live && hkey == lk) atomicAdd(&h[kDegHist + capped], static_cast<unsigned long long>(hdeg)); // hub rows: few
-        todo &= ~same;
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < kBlkLocalSched * kDegHist; k += kBlkRowsThreads) {
+        const unsigned int n = (&rows_s[0][0])[k];
+        if (n) {
+            unsigned long long *h = hist + static_cast<int64_t>(sched0 + k / kDegHist) * 2 * kDegHist;
+            atomicAdd(&h[k % kDegHist], static_cast<unsigned long long>(n));
+            atomicAdd(&h[kDegHist + k % kDegHist], (&edges_s[0][0])[k]);
+        }
     }
 }
 
@@ -410,7 +432,7 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
     HETA_BLK(hipMemsetAsync(hist, 0, reinterpret_cast<char *>(n_chunks_dev + 2 * n_rel) - reinterpret_cast<char *>(hist), st));
     // the schedule sort's pairs: CSR rows at [0, nR), CSC rows at [nR, nQ) of keyB / valB (keyA / valA serve the transpose first)
     if (nR > 0) {
-        hipLaunchKernelGGL(blk_rows_kernel<0>, blocks_for(nR), dim3(256), 0, st, t, in, nR, (int64_t)0, csr_ptr, ptrG_csr, inv_deg, keyB,
+        hipLaunchKernelGGL(blk_rows_kernel<0>, dim3(static_cast<unsigned>((nR + kBlkRowsThreads - 1) / kBlkRowsThreads)), dim3(kBlkRowsThreads), 0, st, t, in, nR, (int64_t)0, csr_ptr, ptrG_csr, inv_deg, keyB,
                            valB, hist, err);
         HETA_BLK_LAUNCHED("blk_rows_kernel");
     } else {
@@ -437,7 +459,7 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
         HETA_BLK_LAUNCHED("blk_csc_idx_kernel");
     }
     if (nS > 0) {
-        hipLaunchKernelGGL(blk_rows_kernel<1>, blocks_for(nS), dim3(256), 0, st, t, in, nS, nR, csc_ptr, ptrG_csc, (float *)nullptr, keyB,
+        hipLaunchKernelGGL(blk_rows_kernel<1>, dim3(static_cast<unsigned>((nS + kBlkRowsThreads - 1) / kBlkRowsThreads)), dim3(kBlkRowsThreads), 0, st, t, in, nS, nR, csc_ptr, ptrG_csc, (float *)nullptr, keyB,
                            valB, hist, err);
         HETA_BLK_LAUNCHED("blk_rows_kernel");
     }
