@@ -384,7 +384,7 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
     const int64_t hist_elems = sort_hist_elems(std::max<int64_t>(n_sort, 1));
     const size_t n_hist = static_cast<size_t>(2 * n_rel) * 2 * kDegHist;
     const size_t scratch_bytes = carve_size<int64_t>(nR + 1) + carve_size<int64_t>(nS + 1) + 2 * carve_size<int64_t>(nQ) +
-                                 2 * carve_size<int64_t>(nQ + 1) + carve_size<int64_t>(scan_scratch_elems(nQ + 1)) +
+                                 2 * carve_size<int64_t>(nQ + 1) + carve_size<int64_t>(2 * scan_scratch_elems(nQ + 1)) +
                                  4 * carve_size<uint32_t>(n_sort) + 2 * carve_size<uint32_t>(hist_elems) +
                                  carve_size<uint32_t>(scan_scratch_elems(hist_elems)) + carve_size<unsigned long long>(n_hist + 1) +
                                  carve_size<int64_t>(2 * n_rel);
@@ -398,7 +398,7 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
     int64_t *ptrG_csr = carve<int64_t>(cur, nR + 1), *ptrG_csc = carve<int64_t>(cur, nS + 1);
     int64_t *sdeg = carve<int64_t>(cur, nQ), *cnt = carve<int64_t>(cur, nQ);
     int64_t *sptrG = carve<int64_t>(cur, nQ + 1), *chunkG = carve<int64_t>(cur, nQ + 1);
-    int64_t *tile_sums = carve<int64_t>(cur, scan_scratch_elems(nQ + 1));
+    int64_t *tile_sums = carve<int64_t>(cur, 2 * scan_scratch_elems(nQ + 1)); // two scans share a launch set
     uint32_t *keyA = carve<uint32_t>(cur, n_sort), *valA = carve<uint32_t>(cur, n_sort);
     uint32_t *keyB = carve<uint32_t>(cur, n_sort), *valB = carve<uint32_t>(cur, n_sort);
     uint32_t *shist = carve<uint32_t>(cur, hist_elems), *soffs = carve<uint32_t>(cur, hist_elems);
@@ -473,8 +473,7 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
         hipLaunchKernelGGL(blk_perm_kernel, blocks_for(nQ), dim3(256), 0, st, t, vs2, nR, nQ, ptrG_csr, ptrG_csc, csr_perm, csc_perm, sdeg, cnt);
         HETA_BLK_LAUNCHED("blk_perm_kernel");
     }
-    if ((e = device_exclusive_scan_i64_async(sdeg, nQ, sptrG, nQ + 1, tile_sums, st)) != HETA_OK) return finish(e);
-    if ((e = device_exclusive_scan_i64_async(cnt, nQ, chunkG, nQ + 1, tile_sums, st)) != HETA_OK) return finish(e);
+    if ((e = device_exclusive_scan2_i64_async(sdeg, cnt, nQ, sptrG, chunkG, nQ + 1, tile_sums, st)) != HETA_OK) return finish(e);
     if (nQ > 0) {
         hipLaunchKernelGGL(blk_sptr_kernel, blocks_for(nQ), dim3(256), 0, st, t, nR, nQ, sptrG, chunkG, sdeg, csr_sptr, csc_sptr,
                            hub_chunk_ptr, hub_chunks, n_chunks_dev);
@@ -489,19 +488,20 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
     // (hist, err and n_chunks_dev are consecutive in the scratch block: 256-byte aligned pieces)
     static thread_local void *t_back = nullptr;
     static thread_local size_t t_back_cap = 0;
-    const size_t back_hist = (n_hist + 1) * sizeof(unsigned long long), back_total = back_hist + 2 * n_rel * sizeof(int64_t);
+    // one copy: the host buffer mirrors the device layout from hist to the end of the chunk counts
+    const size_t back_hist = reinterpret_cast<char *>(n_chunks_dev) - reinterpret_cast<char *>(hist);
+    const size_t back_total = back_hist + 2 * n_rel * sizeof(int64_t);
     if (back_total > t_back_cap) {
         if (t_back) (void)hipHostFree(t_back);
         t_back = nullptr;
         t_back_cap = 0;
-        const size_t cap = std::max<size_t>(back_total, (size_t(2) * kMaxBlockRels * 2 * kDegHist + 1) * 8 + 2 * kMaxBlockRels * 8);
+        const size_t cap = std::max<size_t>(back_total, (size_t(2) * kMaxBlockRels * 2 * kDegHist + 1) * 8 + 2 * kMaxBlockRels * 8 + 512);
         HETA_BLK(hipHostMalloc(&t_back, cap, hipHostMallocDefault));
         t_back_cap = cap;
     }
     unsigned long long *h = static_cast<unsigned long long *>(t_back);
     int64_t *n_chunks = reinterpret_cast<int64_t *>(static_cast<char *>(t_back) + back_hist);
-    HETA_BLK(hipMemcpyAsync(h, hist, back_hist, hipMemcpyDeviceToHost, st));
-    HETA_BLK(hipMemcpyAsync(n_chunks, n_chunks_dev, 2 * n_rel * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    HETA_BLK(hipMemcpyAsync(h, hist, back_total, hipMemcpyDeviceToHost, st));
     HETA_BLK(hipStreamSynchronize(st));
 #undef HETA_BLK
 #undef HETA_BLK_LAUNCHED

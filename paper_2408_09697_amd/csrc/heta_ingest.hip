@@ -51,7 +51,7 @@ struct Scratch {
 
 // ---- exclusive scan: out[i] = in[0] + ... + in[i-1] for i in [0, n_out), in[j] = 0 for j >= n_in ------
 template <typename TI, typename TO>
-__global__ void __launch_bounds__(256) scan_tile_kernel(const TI *in, int64_t n_in, TO *out, int64_t n_out, TO *tile_sums)
+__device__ __forceinline__ void scan_tile_body(const TI *in, int64_t n_in, TO *out, int64_t n_out, TO *tile_sums)
 {
     __shared__ TO wave_tot[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -80,8 +80,23 @@ __global__ void __launch_bounds__(256) scan_tile_kernel(const TI *in, int64_t n_
     }
     if (tid == 255) tile_sums[blockIdx.x] = before;
 }
+template <typename TI, typename TO>
+__global__ void __launch_bounds__(256) scan_tile_kernel(const TI *in, int64_t n_in, TO *out, int64_t n_out, TO *tile_sums)
+{
+    scan_tile_body<TI, TO>(in, n_in, out, n_out, tile_sums);
+}
+// two scans of equal length in one launch set: blockIdx.y picks the array (tile sums of the second after the first's)
+template <typename T> struct ScanPair {
+    const T *in[2];
+    T *out[2];
+};
+template <typename T>
+__global__ void __launch_bounds__(256) scan_tile_pair_kernel(ScanPair<T> a, int64_t n_in, int64_t n_out, T *tile_sums, int64_t tiles)
+{
+    scan_tile_body<T, T>(a.in[blockIdx.y], n_in, a.out[blockIdx.y], n_out, tile_sums + blockIdx.y * tiles);
+}
 
-template <typename TO> __global__ void __launch_bounds__(256) scan_sums_kernel(TO *sums, int64_t n)
+template <typename TO> __device__ __forceinline__ void scan_sums_body(TO *sums, int64_t n)
 {
     __shared__ TO wave_tot[4];
     __shared__ TO carry_s;
@@ -107,10 +122,18 @@ template <typename TO> __global__ void __launch_bounds__(256) scan_sums_kernel(T
     }
 }
 
+template <typename TO> __global__ void __launch_bounds__(256) scan_sums_kernel(TO *sums, int64_t n) { scan_sums_body<TO>(sums, n); }
+template <typename T> __global__ void __launch_bounds__(256) scan_sums_pair_kernel(T *sums, int64_t n) { scan_sums_body<T>(sums + blockIdx.x * n, n); }
+
 template <typename TO> __global__ void __launch_bounds__(256) scan_add_kernel(TO *out, int64_t n, const TO *tile_sums)
 {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (i < n) out[i] += tile_sums[i / kScanTile];
+}
+template <typename T> __global__ void __launch_bounds__(256) scan_add_pair_kernel(ScanPair<T> a, int64_t n, const T *tile_sums, int64_t tiles)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) a.out[blockIdx.y][i] += tile_sums[blockIdx.y * tiles + i / kScanTile];
 }
 
 // The whole scan by one workgroup of 1024 threads, 8192 elements per round with a running carry: for the
@@ -118,7 +141,7 @@ template <typename TO> __global__ void __launch_bounds__(256) scan_add_kernel(TO
 // of three dependent ones.
 constexpr int kScanSingleMax = 4 * 8192;
 template <typename TI, typename TO>
-__global__ void __launch_bounds__(1024) scan_single_kernel(const TI *in, int64_t n_in, TO *out, int64_t n_out)
+__device__ __forceinline__ void scan_single_body(const TI *in, int64_t n_in, TO *out, int64_t n_out)
 {
     __shared__ TO wave_tot[16];
     __shared__ TO carry_s;
@@ -153,6 +176,16 @@ __global__ void __launch_bounds__(1024) scan_single_kernel(const TI *in, int64_t
         if (tid == 1023) carry_s = before;
         __syncthreads();
     }
+}
+
+template <typename TI, typename TO>
+__global__ void __launch_bounds__(1024) scan_single_kernel(const TI *in, int64_t n_in, TO *out, int64_t n_out)
+{
+    scan_single_body<TI, TO>(in, n_in, out, n_out);
+}
+template <typename T> __global__ void __launch_bounds__(1024) scan_single_pair_kernel(ScanPair<T> a, int64_t n_in, int64_t n_out)
+{
+    scan_single_body<T, T>(a.in[blockIdx.x], n_in, a.out[blockIdx.x], n_out);
 }
 
 // tile_sums: scratch of (n_out + kScanTile - 1) / kScanTile elements; asynchronous on st
@@ -598,6 +631,28 @@ heta_status device_exclusive_scan_i64_async(const int64_t *in, int64_t n_in, int
                                             hipStream_t st)
 {
     return exclusive_scan_with<int64_t, int64_t>(in, n_in, out, n_out, tile_sums, st);
+}
+
+// outA / outB = exclusive scans of inA / inB (n_in inputs, n_out outputs each) in one launch set;
+// tile_sums: 2 x scan_scratch_elems(n_out) elements
+heta_status device_exclusive_scan2_i64_async(const int64_t *inA, const int64_t *inB, int64_t n_in, int64_t *outA, int64_t *outB,
+                                             int64_t n_out, int64_t *tile_sums, hipStream_t st)
+{
+    if (n_out <= 0) return HETA_OK;
+    const int64_t tiles = (n_out + kScanTile - 1) / kScanTile;
+    ScanPair<int64_t> a{{inA, inB}, {outA, outB}};
+    if (tiles == 1 || n_out <= kScanSingleMax) {
+        hipLaunchKernelGGL((scan_single_pair_kernel<int64_t>), dim3(2), dim3(1024), 0, st, a, n_in, n_out);
+        HETA_LAUNCH_CHECK("scan_single_kernel");
+        return HETA_OK;
+    }
+    hipLaunchKernelGGL((scan_tile_pair_kernel<int64_t>), dim3((unsigned)tiles, 2), dim3(256), 0, st, a, n_in, n_out, tile_sums, tiles);
+    HETA_LAUNCH_CHECK("scan_tile_kernel");
+    hipLaunchKernelGGL((scan_sums_pair_kernel<int64_t>), dim3(2), dim3(256), 0, st, tile_sums, tiles);
+    HETA_LAUNCH_CHECK("scan_sums_kernel");
+    hipLaunchKernelGGL((scan_add_pair_kernel<int64_t>), dim3((unsigned)((n_out + 255) / 256), 2), dim3(256), 0, st, a, n_out, tile_sums, tiles);
+    HETA_LAUNCH_CHECK("scan_add_kernel");
+    return HETA_OK;
 }
 
 heta_status device_sort_pairs_u32_async(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n,

@@ -146,6 +146,8 @@ heta_status device_sort_pairs_u32(uint32_t *keys, uint32_t *vals, uint32_t *keys
 // sort_hist_elems(n) elements each and tile_sums of scan_scratch_elems(sort_hist_elems(n)) elements.
 int64_t scan_scratch_elems(int64_t n_out);
 int64_t sort_hist_elems(int64_t n);
+heta_status device_exclusive_scan2_i64_async(const int64_t *inA, const int64_t *inB, int64_t n_in, int64_t *outA, int64_t *outB,
+                                             int64_t n_out, int64_t *tile_sums, hipStream_t st);
 heta_status device_exclusive_scan_i64_async(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, int64_t *tile_sums,
                                             hipStream_t st);
 heta_status device_sort_pairs_u32_async(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n,
