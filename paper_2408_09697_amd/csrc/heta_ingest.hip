@@ -221,40 +221,48 @@ heta_status exclusive_scan(const TI *in, int64_t n_in, TO *out, int64_t n_out, S
 }
 
 // ---- stable LSD radix sort of (key, value) pairs ------------------------------------------------------
-// hist[digit * n_tiles + tile] = number of keys of the tile with that digit
+// RB = bits per pass (8 or 9); hist[digit * n_tiles + tile] = number of keys of the tile with that digit
+template <int RB>
 __global__ void __launch_bounds__(256) sort_hist_kernel(const uint32_t *keys, int64_t n, int shift, uint32_t *hist, int64_t n_tiles)
 {
-    __shared__ uint32_t cnt[256];
-    cnt[threadIdx.x] = 0;
+    constexpr int BINS = 1 << RB;
+    __shared__ uint32_t cnt[BINS];
+#pragma unroll
+    for (int b = threadIdx.x; b < BINS; b += 256) cnt[b] = 0;
     __syncthreads();
     const int64_t base = static_cast<int64_t>(blockIdx.x) * kSortTile;
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = base + r * 256 + threadIdx.x;
-        if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & 255u], 1u); // LDS integer counter: order-independent
+        if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & (BINS - 1)], 1u); // LDS integer counter: order-independent
     }
     __syncthreads();
-    hist[static_cast<int64_t>(threadIdx.x) * n_tiles + blockIdx.x] = cnt[threadIdx.x];
+#pragma unroll
+    for (int b = threadIdx.x; b < BINS; b += 256) hist[static_cast<int64_t>(b) * n_tiles + blockIdx.x] = cnt[b];
 }
 
 // offs = exclusive scan of hist over (digit, tile); every key goes to offs[digit][tile] + its rank
 // among the tile's keys of the same digit, ranks taken in index order (stable).
+template <int RB>
 __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys, const uint32_t *vals, int64_t n, int shift,
                                                             const uint32_t *offs, int64_t n_tiles, uint32_t *keys_out,
                                                             uint32_t *vals_out)
 {
     // A step places kSortStep x 256 consecutive keys: sub-round q holds the keys base + (step * kSortStep + q) * 256 + tid,
     // so index order is (q, wavefront, lane).  Three barriers per step instead of per 256 keys.
-    constexpr int kSortStep = 4;
+    constexpr int kSortStep = 4, BINS = 1 << RB;
     static_assert(kSortRounds % kSortStep == 0, "a tile is a whole number of steps");
-    __shared__ uint32_t bin_base[256];               // next free output slot of each digit for this tile
-    __shared__ uint32_t wave_cnt[kSortStep][4][256]; // keys of each digit per (sub-round, wavefront) in the current step
+    __shared__ uint32_t bin_base[BINS];               // next free output slot of each digit for this tile
+    __shared__ uint32_t wave_cnt[kSortStep][4][BINS]; // keys of each digit per (sub-round, wavefront) in the current step
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    bin_base[tid] = offs[static_cast<int64_t>(tid) * n_tiles + blockIdx.x];
 #pragma unroll
-    for (int q = 0; q < kSortStep; ++q)
+    for (int b = tid; b < BINS; b += 256) {
+        bin_base[b] = offs[static_cast<int64_t>(b) * n_tiles + blockIdx.x];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) wave_cnt[q][w][tid] = 0;
+        for (int q = 0; q < kSortStep; ++q)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) wave_cnt[q][w][b] = 0;
+    }
     const int64_t base = static_cast<int64_t>(blockIdx.x) * kSortTile;
     // every round's key and value are loaded before the first step: one memory latency per tile instead of one
     // per step (the steps are chained through barriers, so a load inside a step is never in flight with the next)
@@ -272,11 +280,11 @@ __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys,
 #pragma unroll
         for (int q = 0; q < kSortStep; ++q) {
             const bool valid = base + (r0 + q) * 256 + tid < n;
-            const uint32_t d = (key_r[r0 + q] >> shift) & 255u;
+            const uint32_t d = (key_r[r0 + q] >> shift) & (BINS - 1);
             // lanes of this wavefront holding the same digit in this sub-round
             uint64_t peers = __ballot(valid);
 #pragma unroll
-            for (int b = 0; b < 8; ++b) {
+            for (int b = 0; b < RB; ++b) {
                 const bool bit = (d >> b) & 1u;
                 const uint64_t bal = __ballot(bit);
                 peers &= bit ? bal : ~bal;
@@ -288,7 +296,7 @@ __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys,
 #pragma unroll
         for (int q = 0; q < kSortStep; ++q) {
             if (base + (r0 + q) * 256 + tid < n) {
-                const uint32_t key = key_r[r0 + q], d = (key >> shift) & 255u;
+                const uint32_t key = key_r[r0 + q], d = (key >> shift) & (BINS - 1);
                 uint32_t pos = bin_base[d] + rank[q];
 #pragma unroll
                 for (int qq = 0; qq < q; ++qq)
@@ -300,23 +308,26 @@ __global__ void __launch_bounds__(256) sort_scatter_kernel(const uint32_t *keys,
             }
         }
         __syncthreads();
-        uint32_t add = 0;
 #pragma unroll
-        for (int q = 0; q < kSortStep; ++q)
+        for (int b = tid; b < BINS; b += 256) {
+            uint32_t add = 0;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                add += wave_cnt[q][w][tid];
-                wave_cnt[q][w][tid] = 0;
-            }
-        bin_base[tid] += add;
+            for (int q = 0; q < kSortStep; ++q)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    add += wave_cnt[q][w][b];
+                    wave_cnt[q][w][b] = 0;
+                }
+            bin_base[b] += add;
+        }
         __syncthreads();
     }
 }
 
 // Sorts n pairs by the low `bits` bits of the key.  (keys, vals) and (keys_tmp, vals_tmp) are
 // ping-pong buffers; *keys_res / *vals_res point at whichever holds the result.
-// hist, offs: scratch of 256 * n_tiles elements each (n_tiles = (n + kSortTile - 1) / kSortTile); tile_sums: scratch
-// for a scan over 256 * n_tiles elements; asynchronous on st
+// hist, offs: scratch of 512 * n_tiles elements each (n_tiles = (n + kSortTile - 1) / kSortTile); tile_sums: scratch
+// for a scan over 512 * n_tiles elements; asynchronous on st
 heta_status radix_sort_pairs_with(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp, uint32_t *vals_tmp, int64_t n, int bits,
                                   uint32_t **keys_res, uint32_t **vals_res, uint32_t *hist, uint32_t *offs, uint32_t *tile_sums,
                                   hipStream_t st)
@@ -327,11 +338,16 @@ heta_status radix_sort_pairs_with(uint32_t *keys, uint32_t *vals, uint32_t *keys
     const int64_t n_tiles = (n + kSortTile - 1) / kSortTile;
     heta_status e;
     uint32_t *ki = keys, *vi = vals, *ko = keys_tmp, *vo = vals_tmp;
-    for (int shift = 0; shift < bits; shift += 8) {
-        hipLaunchKernelGGL(sort_hist_kernel, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, n, shift, hist, n_tiles);
+    // 9 bits per pass where that saves a pass (17-18 or 25-27 key bits): a pass is three dependent launches
+    const int rb = (bits + 8) / 9 < (bits + 7) / 8 ? 9 : 8;
+    const int64_t bins = int64_t(1) << rb;
+    for (int shift = 0; shift < bits; shift += rb) {
+        if (rb == 9) hipLaunchKernelGGL(sort_hist_kernel<9>, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, n, shift, hist, n_tiles);
+        else hipLaunchKernelGGL(sort_hist_kernel<8>, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, n, shift, hist, n_tiles);
         HETA_LAUNCH_CHECK("sort_hist_kernel");
-        if ((e = exclusive_scan_with<uint32_t, uint32_t>(hist, 256 * n_tiles, offs, 256 * n_tiles, tile_sums, st)) != HETA_OK) return e;
-        hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo);
+        if ((e = exclusive_scan_with<uint32_t, uint32_t>(hist, bins * n_tiles, offs, bins * n_tiles, tile_sums, st)) != HETA_OK) return e;
+        if (rb == 9) hipLaunchKernelGGL(sort_scatter_kernel<9>, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo);
+        else hipLaunchKernelGGL(sort_scatter_kernel<8>, dim3((unsigned)n_tiles), dim3(256), 0, st, ki, vi, n, shift, offs, n_tiles, ko, vo);
         HETA_LAUNCH_CHECK("sort_scatter_kernel");
         std::swap(ki, ko);
         std::swap(vi, vo);
@@ -350,9 +366,9 @@ heta_status radix_sort_pairs(uint32_t *keys, uint32_t *vals, uint32_t *keys_tmp,
     const int64_t n_tiles = (n + kSortTile - 1) / kSortTile;
     uint32_t *hist = nullptr, *offs = nullptr, *tile_sums = nullptr;
     heta_status e;
-    if ((e = scr.get(&hist, static_cast<size_t>(256 * n_tiles))) != HETA_OK) return e;
-    if ((e = scr.get(&offs, static_cast<size_t>(256 * n_tiles))) != HETA_OK) return e;
-    if ((e = scr.get(&tile_sums, static_cast<size_t>((256 * n_tiles + kScanTile - 1) / kScanTile))) != HETA_OK) return e;
+    if ((e = scr.get(&hist, static_cast<size_t>(512 * n_tiles))) != HETA_OK) return e;
+    if ((e = scr.get(&offs, static_cast<size_t>(512 * n_tiles))) != HETA_OK) return e;
+    if ((e = scr.get(&tile_sums, static_cast<size_t>((512 * n_tiles + kScanTile - 1) / kScanTile))) != HETA_OK) return e;
     return radix_sort_pairs_with(keys, vals, keys_tmp, vals_tmp, n, bits, keys_res, vals_res, hist, offs, tile_sums, st);
 }
 
@@ -625,7 +641,7 @@ heta_status transpose_on_device(const Schedule &csr, int64_t n_src, Schedule &cs
 // ---- the scan and the sort for other translation units (the neighbour sampler) ---------------------------
 // Asynchronous forms with caller-provided scratch (sizes from the two helpers, in elements):
 int64_t scan_scratch_elems(int64_t n_out) { return (n_out + kScanTile - 1) / kScanTile; }
-int64_t sort_hist_elems(int64_t n) { return 256 * ((n + kSortTile - 1) / kSortTile); }
+int64_t sort_hist_elems(int64_t n) { return 512 * ((n + kSortTile - 1) / kSortTile); }
 
 heta_status device_exclusive_scan_i64_async(const int64_t *in, int64_t n_in, int64_t *out, int64_t n_out, int64_t *tile_sums,
                                             hipStream_t st)
