@@ -89,9 +89,9 @@ __device__ __forceinline__ int64_t clamp64(int64_t x, int64_t lo, int64_t hi) { 
 constexpr int kBlkRowsThreads = 1024; // rows per workgroup of blk_rows_kernel
 constexpr int kBlkLocalSched = 4;     // schedules whose histograms a workgroup keeps in LDS
 template <int CSC>
-__global__ void __launch_bounds__(kBlkRowsThreads) blk_rows_kernel(BlockTables t, BlockInputs in, int64_t n_rows_total, int64_t sched_pos0,
-                                                                   int64_t *ptr_local, int64_t *ptr_global, float *inv_deg, uint32_t *key,
-                                                                   uint32_t *val, unsigned long long *hist, unsigned long long *err)
+__device__ __forceinline__ void blk_rows_body(const unsigned bx, const BlockTables &t, const BlockInputs &in, int64_t n_rows_total,
+                                              int64_t sched_pos0, int64_t *ptr_local, int64_t *ptr_global, float *inv_deg, uint32_t *key,
+                                              uint32_t *val, unsigned long long *hist, unsigned long long *err)
 {
     // degree histograms of the workgroup's rows: the schedule of its first row and the three after it (a workgroup's
     // 1,024 consecutive rows rarely span more) are counted in LDS and reach the global counters once per workgroup and
@@ -104,13 +104,13 @@ __global__ void __launch_bounds__(kBlkRowsThreads) blk_rows_kernel(BlockTables t
         (&edges_s[0][0])[k] = 0;
     }
     if (threadIdx.x == 0) {
-        const int64_t R0 = static_cast<int64_t>(blockIdx.x) * kBlkRowsThreads;
+        const int64_t R0 = static_cast<int64_t>(bx) * kBlkRowsThreads;
         const int rel0 = R0 < n_rows_total ? seg_of(CSC ? t.src_off : t.dst_off, t.n_rel, R0) : 0;
         sched0_s = CSC ? t.n_rel + rel0 : rel0;
     }
     __syncthreads();
     const int sched0 = sched0_s;
-    const int64_t R = static_cast<int64_t>(blockIdx.x) * kBlkRowsThreads + threadIdx.x;
+    const int64_t R = static_cast<int64_t>(bx) * kBlkRowsThreads + threadIdx.x;
     const bool live = R < n_rows_total;
     uint32_t hkey = 0xffffffffu; // (schedule, capped degree) of this lane's row, for the histogram at the end
     int64_t hdeg = 0;
@@ -171,10 +171,9 @@ __global__ void __launch_bounds__(kBlkRowsThreads) blk_rows_kernel(BlockTables t
 
 // One thread per global edge: the caller's neighbour id, checked and sanitised, goes to the CSR's own copy and,
 // as a global source id, into the transpose's sort key; the value is the global edge id.
-__global__ void __launch_bounds__(256) blk_edges_kernel(BlockTables t, BlockInputs in, int64_t n_edges_total, int32_t *csr_idx,
-                                                        uint32_t *key, uint32_t *val, unsigned long long *err)
+__device__ __forceinline__ void blk_edges_body(const int64_t e, const BlockTables &t, const BlockInputs &in, int64_t n_edges_total,
+                                               int32_t *csr_idx, uint32_t *key, uint32_t *val, unsigned long long *err)
 {
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (e >= n_edges_total) return;
     const int rel = seg_of(t.edge_off, t.n_rel, e);
     const int64_t le = e - t.edge_off[rel], n_src = t.src_off[rel + 1] - t.src_off[rel];
@@ -188,10 +187,31 @@ __global__ void __launch_bounds__(256) blk_edges_kernel(BlockTables t, BlockInpu
     val[e] = static_cast<uint32_t>(e);
 }
 
-// global column offsets: colG[U] = number of sorted keys below U, U in [0, n_src_total]
-__global__ void __launch_bounds__(256) blk_colptr_kernel(const uint32_t *sorted_keys, int64_t n_edges, int64_t n_src_total, int64_t *colG)
+template <int CSC>
+__global__ void __launch_bounds__(kBlkRowsThreads) blk_rows_kernel(BlockTables t, BlockInputs in, int64_t n_rows_total, int64_t sched_pos0,
+                                                                   int64_t *ptr_local, int64_t *ptr_global, float *inv_deg, uint32_t *key,
+                                                                   uint32_t *val, unsigned long long *hist, unsigned long long *err)
 {
-    const int64_t U = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    blk_rows_body<CSC>(blockIdx.x, t, in, n_rows_total, sched_pos0, ptr_local, ptr_global, inv_deg, key, val, hist, err);
+}
+// The two kernels that read the caller's arrays in one grid (they depend on nothing and on each other not at all):
+// the first row_blocks workgroups take the CSR rows, the rest 1,024 edges each.
+__global__ void __launch_bounds__(kBlkRowsThreads) blk_rows_edges_kernel(BlockTables t, BlockInputs in, unsigned row_blocks, int64_t n_rows_total,
+                                                                         int64_t *ptr_local, int64_t *ptr_global, float *inv_deg, uint32_t *row_key,
+                                                                         uint32_t *row_val, unsigned long long *hist, int64_t n_edges_total,
+                                                                         int32_t *csr_idx, uint32_t *edge_key, uint32_t *edge_val,
+                                                                         unsigned long long *err)
+{
+    if (blockIdx.x < row_blocks)
+        blk_rows_body<0>(blockIdx.x, t, in, n_rows_total, 0, ptr_local, ptr_global, inv_deg, row_key, row_val, hist, err);
+    else
+        blk_edges_body(static_cast<int64_t>(blockIdx.x - row_blocks) * kBlkRowsThreads + threadIdx.x, t, in, n_edges_total, csr_idx, edge_key,
+                       edge_val, err);
+}
+
+// global column offsets: colG[U] = number of sorted keys below U, U in [0, n_src_total]
+__device__ __forceinline__ void blk_colptr_body(const int64_t U, const uint32_t *sorted_keys, int64_t n_edges, int64_t n_src_total, int64_t *colG)
+{
     if (U > n_src_total) return;
     int64_t lo = 0, hi = n_edges;
     while (lo < hi) {
@@ -204,15 +224,26 @@ __global__ void __launch_bounds__(256) blk_colptr_kernel(const uint32_t *sorted_
 
 // csc_idx[p] = relation-local destination row of the edge at sorted position p (the block-diagonal structure
 // keeps a relation's columns, and so its CSC slots, contiguous: p is already the slot's global position)
-__global__ void __launch_bounds__(256) blk_csc_idx_kernel(BlockTables t, const uint32_t *sorted_edge, int64_t n_edges_total,
-                                                          const int64_t *ptrG_csr, int64_t n_dst_total, int32_t *csc_idx)
+__device__ __forceinline__ void blk_csc_idx_body(const int64_t p, const BlockTables &t, const uint32_t *sorted_edge, int64_t n_edges_total,
+                                                 const int64_t *ptrG_csr, int64_t n_dst_total, int32_t *csc_idx)
 {
-    const int64_t p = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (p >= n_edges_total) return;
     const int64_t e = sorted_edge[p];
     const int64_t R = last_le64(ptrG_csr, n_dst_total, e); // the last row starting at or before e owns it (empty rows share offsets)
     const int rel = seg_of(t.edge_off, t.n_rel, e);
     csc_idx[p] = static_cast<int32_t>(R - t.dst_off[rel]);
+}
+
+// both readers of the transpose sort's result in one grid: the first col_blocks workgroups the column offsets
+__global__ void __launch_bounds__(256) blk_colptr_csc_idx_kernel(BlockTables t, unsigned col_blocks, const uint32_t *sorted_keys,
+                                                                 const uint32_t *sorted_edge, int64_t n_edges_total, int64_t n_src_total,
+                                                                 int64_t *colG, const int64_t *ptrG_csr, int64_t n_dst_total, int32_t *csc_idx)
+{
+    if (blockIdx.x < col_blocks)
+        blk_colptr_body(static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x, sorted_keys, n_edges_total, n_src_total, colG);
+    else
+        blk_csc_idx_body(static_cast<int64_t>(blockIdx.x - col_blocks) * 256 + threadIdx.x, t, sorted_edge, n_edges_total, ptrG_csr, n_dst_total,
+                         csc_idx);
 }
 
 // Sorted position Q of the schedule sort -> that row's place in its schedule: the row order (relation-local
@@ -242,11 +273,10 @@ __global__ void __launch_bounds__(256) blk_perm_kernel(BlockTables t, const uint
 // Relation-local schedule offsets, hub chunk ranges and hub chunk descriptors from the two global scans.
 // sptrG: exclusive scan of sdeg over all Q (CSR side counts from 0, CSC side continues from the edge total);
 // chunkG: exclusive scan of cnt.
-__global__ void __launch_bounds__(256) blk_sptr_kernel(BlockTables t, int64_t n_dst_total, int64_t n_total, const int64_t *sptrG,
-                                                       const int64_t *chunkG, const int64_t *sdeg, int64_t *csr_sptr, int64_t *csc_sptr,
-                                                       int64_t *hub_chunk_ptr, HubChunk *hub_chunks, int64_t *n_chunks_out)
+__device__ __forceinline__ void blk_sptr_body(const int64_t Q, const BlockTables &t, int64_t n_dst_total, int64_t n_total, const int64_t *sptrG,
+                                              const int64_t *chunkG, const int64_t *sdeg, int64_t *csr_sptr, int64_t *csc_sptr,
+                                              int64_t *hub_chunk_ptr, HubChunk *hub_chunks, int64_t *n_chunks_out)
 {
-    const int64_t Q = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (Q >= n_total) return;
     const bool csc = Q >= n_dst_total;
     const int64_t *off = csc ? t.src_off : t.dst_off;
@@ -287,12 +317,11 @@ __global__ void __launch_bounds__(256) blk_sptr_kernel(BlockTables t, int64_t n_
 
 // sidx of both directions: slot e' of the concatenated schedule-ordered adjacency (CSR slots first, then CSC
 // slots) takes the neighbour id of its row's (e' - row start)-th edge
-__global__ void __launch_bounds__(256) blk_sidx_kernel(int64_t n_edges_total, int64_t n_dst_total, int64_t n_src_total,
-                                                       const int64_t *sptrG, const uint32_t *sorted_row, const int64_t *ptrG_csr,
-                                                       const int64_t *ptrG_csc, const int32_t *csr_idx, const int32_t *csc_idx,
-                                                       int32_t *csr_sidx, int32_t *csc_sidx)
+__device__ __forceinline__ void blk_sidx_body(const int64_t x, int64_t n_edges_total, int64_t n_dst_total, int64_t n_src_total,
+                                              const int64_t *sptrG, const uint32_t *sorted_row, const int64_t *ptrG_csr,
+                                              const int64_t *ptrG_csc, const int32_t *csr_idx, const int32_t *csc_idx,
+                                              int32_t *csr_sidx, int32_t *csc_sidx)
 {
-    const int64_t x = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (x >= 2 * n_edges_total) return;
     if (x < n_edges_total) {
         const int64_t Q = last_le64(sptrG, n_dst_total, x);
@@ -304,6 +333,22 @@ __global__ void __launch_bounds__(256) blk_sidx_kernel(int64_t n_edges_total, in
         const int64_t U = static_cast<int64_t>(sorted_row[Q]) - n_dst_total;
         csc_sidx[x - n_edges_total] = csc_idx[clamp64(ptrG_csc[U] + (x - sptrG[Q]), 0, n_edges_total - 1)];
     }
+}
+
+// both consumers of the two row scans in one grid: the first sptr_blocks workgroups the schedule offsets and hub chunks
+__global__ void __launch_bounds__(256) blk_sptr_sidx_kernel(BlockTables t, unsigned sptr_blocks, int64_t n_dst_total, int64_t n_src_total,
+                                                            int64_t n_total, int64_t n_edges_total, const int64_t *sptrG, const int64_t *chunkG,
+                                                            const int64_t *sdeg, int64_t *csr_sptr, int64_t *csc_sptr, int64_t *hub_chunk_ptr,
+                                                            HubChunk *hub_chunks, int64_t *n_chunks_out, const uint32_t *sorted_row,
+                                                            const int64_t *ptrG_csr, const int64_t *ptrG_csc, const int32_t *csr_idx,
+                                                            const int32_t *csc_idx, int32_t *csr_sidx, int32_t *csc_sidx)
+{
+    if (blockIdx.x < sptr_blocks)
+        blk_sptr_body(static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x, t, n_dst_total, n_total, sptrG, chunkG, sdeg, csr_sptr, csc_sptr,
+                      hub_chunk_ptr, hub_chunks, n_chunks_out);
+    else
+        blk_sidx_body(static_cast<int64_t>(blockIdx.x - sptr_blocks) * 256 + threadIdx.x, n_edges_total, n_dst_total, n_src_total, sptrG,
+                      sorted_row, ptrG_csr, ptrG_csc, csr_idx, csc_idx, csr_sidx, csc_sidx);
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -431,17 +476,14 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
     // one fill for the histograms, the error word and the chunk counts (consecutive pieces)
     HETA_BLK(hipMemsetAsync(hist, 0, reinterpret_cast<char *>(n_chunks_dev + 2 * n_rel) - reinterpret_cast<char *>(hist), st));
     // the schedule sort's pairs: CSR rows at [0, nR), CSC rows at [nR, nQ) of keyB / valB (keyA / valA serve the transpose first)
-    if (nR > 0) {
-        hipLaunchKernelGGL(blk_rows_kernel<0>, dim3(static_cast<unsigned>((nR + kBlkRowsThreads - 1) / kBlkRowsThreads)), dim3(kBlkRowsThreads), 0, st, t, in, nR, (int64_t)0, csr_ptr, ptrG_csr, inv_deg, keyB,
-                           valB, hist, err);
-        HETA_BLK_LAUNCHED("blk_rows_kernel");
-    } else {
-        HETA_BLK(hipMemsetAsync(ptrG_csr, 0, sizeof(int64_t), st));
-    }
+    auto blocks_of = [](int64_t n, int64_t per) { return static_cast<unsigned>((n + per - 1) / per); };
+    if (nR == 0) HETA_BLK(hipMemsetAsync(ptrG_csr, 0, sizeof(int64_t), st));
     uint32_t *ks = keyA, *vs = valA;
-    if (nE > 0) {
-        hipLaunchKernelGGL(blk_edges_kernel, blocks_for(nE), dim3(256), 0, st, t, in, nE, csr_idx, keyA, valA, err);
-        HETA_BLK_LAUNCHED("blk_edges_kernel");
+    if (nR > 0 || nE > 0) { // CSR rows and edges, both straight from the caller's arrays, in one launch
+        const unsigned rb = blocks_of(nR, kBlkRowsThreads), eb = blocks_of(nE, kBlkRowsThreads);
+        hipLaunchKernelGGL(blk_rows_edges_kernel, dim3(rb + eb), dim3(kBlkRowsThreads), 0, st, t, in, rb, nR, csr_ptr, ptrG_csr, inv_deg, keyB,
+                           valB, hist, nE, csr_idx, keyA, valA, err);
+        HETA_BLK_LAUNCHED("blk_rows_edges_kernel");
     }
     // The transpose sort's ping-pong partner: keyB / valB already hold the CSR rows' schedule pairs, so the partner is the
     // arena's two sidx arrays (nE 32-bit words each), which nothing touches before the final fill.
@@ -452,11 +494,10 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
         if ((e = device_sort_pairs_u32_async(keyA, valA, keyT, valT, nE, int64_t(1) << bits, &ks, &vs, shist, soffs, stile, st)) != HETA_OK)
             return finish(e);
     }
-    hipLaunchKernelGGL(blk_colptr_kernel, blocks_for(nS + 1), dim3(256), 0, st, ks, nE, nS, ptrG_csc);
-    HETA_BLK_LAUNCHED("blk_colptr_kernel");
-    if (nE > 0) {
-        hipLaunchKernelGGL(blk_csc_idx_kernel, blocks_for(nE), dim3(256), 0, st, t, vs, nE, ptrG_csr, nR, csc_idx);
-        HETA_BLK_LAUNCHED("blk_csc_idx_kernel");
+    {
+        const unsigned cb = blocks_of(nS + 1, 256), ib = blocks_of(nE, 256);
+        hipLaunchKernelGGL(blk_colptr_csc_idx_kernel, dim3(cb + ib), dim3(256), 0, st, t, cb, ks, vs, nE, nS, ptrG_csc, ptrG_csr, nR, csc_idx);
+        HETA_BLK_LAUNCHED("blk_colptr_csc_idx_kernel");
     }
     if (nS > 0) {
         hipLaunchKernelGGL(blk_rows_kernel<1>, dim3(static_cast<unsigned>((nS + kBlkRowsThreads - 1) / kBlkRowsThreads)), dim3(kBlkRowsThreads), 0, st, t, in, nS, nR, csc_ptr, ptrG_csc, (float *)nullptr, keyB,
@@ -474,15 +515,11 @@ heta_status build_block_on_device(const std::vector<Relation *> &rels, const std
         HETA_BLK_LAUNCHED("blk_perm_kernel");
     }
     if ((e = device_exclusive_scan2_i64_async(sdeg, cnt, nQ, sptrG, chunkG, nQ + 1, tile_sums, st)) != HETA_OK) return finish(e);
-    if (nQ > 0) {
-        hipLaunchKernelGGL(blk_sptr_kernel, blocks_for(nQ), dim3(256), 0, st, t, nR, nQ, sptrG, chunkG, sdeg, csr_sptr, csc_sptr,
-                           hub_chunk_ptr, hub_chunks, n_chunks_dev);
-        HETA_BLK_LAUNCHED("blk_sptr_kernel");
-    }
-    if (nE > 0) {
-        hipLaunchKernelGGL(blk_sidx_kernel, blocks_for(2 * nE), dim3(256), 0, st, nE, nR, nS, sptrG, vs2, ptrG_csr, ptrG_csc, csr_idx,
-                           csc_idx, csr_sidx, csc_sidx);
-        HETA_BLK_LAUNCHED("blk_sidx_kernel");
+    if (nQ > 0 || nE > 0) {
+        const unsigned sb = blocks_of(nQ, 256), xb = blocks_of(2 * nE, 256);
+        hipLaunchKernelGGL(blk_sptr_sidx_kernel, dim3(sb + xb), dim3(256), 0, st, t, sb, nR, nS, nQ, nE, sptrG, chunkG, sdeg, csr_sptr, csc_sptr,
+                           hub_chunk_ptr, hub_chunks, n_chunks_dev, vs2, ptrG_csr, ptrG_csc, csr_idx, csc_idx, csr_sidx, csc_sidx);
+        HETA_BLK_LAUNCHED("blk_sptr_sidx_kernel");
     }
     // histograms, the error word and the chunk counts come back through a page-locked buffer of the thread's own
     // (hist, err and n_chunks_dev are consecutive in the scratch block: 256-byte aligned pieces)
