@@ -452,6 +452,26 @@ heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_table, int32
                              float *m, float *v, int64_t ld_state, const int64_t *ids, int64_t n,
                              const float *grad, int64_t ld_grad, float lr, float beta1, float beta2, float eps,
                              int64_t step, void *hip_stream);
+/* The same update for several tables in one call with one set of hyper-parameters and one step counter (the weight
+ * matrices of a model, ids = NULL, and its learnable tables after one backward pass): item i is what
+ * heta_sparse_adam(items[i]...) would do, bit for bit; tables of different items must not overlap.  All items are
+ * checked before anything is launched.  items: HOST array of n_items entries (device pointers inside).  Up to
+ * 16 items share a launch.  Asynchronous on the stream. */
+typedef struct heta_adam_item {
+    void *table;             /* device [n_table_rows, ld_table] of dt */
+    heta_dtype dt;
+    int64_t ld_table;
+    int32_t d;
+    int64_t n_table_rows;
+    float *m, *v;            /* device fp32 [n_table_rows, ld_state] */
+    int64_t ld_state;
+    const int64_t *ids;      /* device [n] distinct rows, or NULL for the first n rows */
+    int64_t n;
+    const float *grad;       /* device fp32 [n, ld_grad] */
+    int64_t ld_grad;
+} heta_adam_item;
+heta_status heta_sparse_adam_multi(int32_t n_items, const heta_adam_item *items, float lr, float beta1, float beta2, float eps,
+                                   int64_t step, void *hip_stream);
 
 /* ---- meta-partitioning (Section 5, Algorithm 2): which relations a GPU (or machine) holds ---------
  * Host-only: works on the weighted metagraph, touches no device.  All pointers are HOST arrays.

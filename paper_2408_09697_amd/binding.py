@@ -28,7 +28,7 @@ EXPORTS = ["heta_graph_create", "heta_graph_create_batch", "heta_graph_destroy",
            "heta_feature_gather", "heta_check_ids", "heta_rel_aggregate_fwd", "heta_rel_aggregate_bwd",
            "heta_rel_aggregate_fwd_multi", "heta_rel_aggregate_bwd_multi",
            "heta_project", "heta_rel_project", "heta_rel_project_wgrad", "heta_cross_rel_reduce",
-           "heta_act_bwd", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
+           "heta_act_bwd", "heta_sparse_adam_multi", "heta_last_error", "heta_version", "heta_profile_enable", "heta_profile_reset",
            "heta_profile_read", "heta_calibration_copy", "heta_calibration_mfma", "heta_cross_rel_project", "heta_cross_rel_project_bwd",
            "heta_cross_rel_project_wgrad", "heta_sparse_adam", "heta_project_batch",
            "heta_project_sum", "heta_project_wgrad_batch", "heta_attn_score", "heta_attn_score_bwd", "heta_attn_score_multi", "heta_attn_score_bwd_multi",
@@ -56,6 +56,12 @@ class _Relation(ctypes.Structure):
     _fields_ = [("src_type", ctypes.c_int32), ("dst_type", ctypes.c_int32), ("num_edges", ctypes.c_int64),
                 ("csr_rowptr", ctypes.c_void_p), ("csr_col", ctypes.c_void_p),
                 ("csc_colptr", ctypes.c_void_p), ("csc_row", ctypes.c_void_p), ("reverse_of", ctypes.c_int32)]
+
+
+class _AdamItem(ctypes.Structure):
+    _fields_ = [("table", ctypes.c_void_p), ("dt", ctypes.c_int32), ("ld_table", ctypes.c_int64), ("d", ctypes.c_int32),
+                ("n_table_rows", ctypes.c_int64), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("ld_state", ctypes.c_int64),
+                ("ids", ctypes.c_void_p), ("n", ctypes.c_int64), ("grad", ctypes.c_void_p), ("ld_grad", ctypes.c_int64)]
 
 
 class _AggItem(ctypes.Structure):
@@ -656,6 +662,29 @@ def heta_sparse_adam(table: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grad
                               _dev(ids, "ids", torch.int64), n, _dev(grad, "grad", torch.float32), _ld(grad),
                               lr, beta1, beta2, eps, int(step), _stream(stream)))
     return table
+
+
+def heta_sparse_adam_multi(items: Sequence[Sequence], lr: float = 1e-3, beta1: float = 0.9, beta2: float = 0.999,
+                           eps: float = 1e-8, step: int = 1, stream=None) -> None:
+    """One Adam step on several tables in one call: items[i] = (table, m, v, grad, ids or None), each as for
+    heta_sparse_adam (whole rows: d = table.shape[1])."""
+    n = len(items)
+    if n == 0:
+        return
+    arr = (_AdamItem * n)()
+    for i, (table, m, v, grad, ids) in enumerate(items):
+        rows = grad.shape[0]
+        if ids is not None and ids.numel() < rows:
+            raise HetaError(HETA_ERR_SHAPE, "fewer ids than gradient rows")
+        if m.shape[0] < table.shape[0] or v.shape[0] < table.shape[0]:
+            raise HetaError(HETA_ERR_SHAPE, "optimizer states have fewer rows than the table")
+        arr[i] = _AdamItem(_dev(table, "table"), _dt(table), _ld(table), table.shape[1], table.shape[0],
+                           _dev(m, "m", torch.float32), _dev(v, "v", torch.float32), _ld(m), _dev(ids, "ids", torch.int64),
+                           rows, _dev(grad, "grad", torch.float32), _ld(grad))
+    L = load_library()
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.heta_sparse_adam_multi.argtypes = [i32, vp, f32, f32, f32, f32, i64, vp]
+    _check(L.heta_sparse_adam_multi(n, ctypes.addressof(arr), lr, beta1, beta2, eps, int(step), _stream(stream)))
 
 
 def _scores(t: torch.Tensor, name: str, rows: int, heads: int) -> int:

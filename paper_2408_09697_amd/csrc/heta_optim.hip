@@ -35,6 +35,9 @@ struct AdamParams {
 
 __device__ __forceinline__ float adam_element(const AdamParams &p, float g, float &m, float &v, float theta)
 {
+    // every product and sum rounded on its own: which pairs the compiler fuses into an FMA differs from one kernel
+    // this function is inlined into to the next, and the single and the multi-table kernel must agree bit for bit
+#pragma clang fp contract(off)
     m = p.beta1 * m + (1.f - p.beta1) * g;
     v = p.beta2 * v + (1.f - p.beta2) * g * g;
     return theta - p.lr * (m * p.c1) / (sqrtf(v * p.c2) + p.eps);
@@ -48,7 +51,7 @@ __device__ __forceinline__ bf16_t adam_to_bf16(float f)
 }
 
 template <int V> // V = 4: 128-bit accesses on whole, aligned chunks; V = 1: element-wise
-__global__ void __launch_bounds__(256) sparse_adam_kernel(AdamParams p)
+__device__ __forceinline__ void sparse_adam_body(const AdamParams &p)
 {
     const int per_row = (p.d + V - 1) / V;
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
@@ -96,16 +99,22 @@ __global__ void __launch_bounds__(256) sparse_adam_kernel(AdamParams p)
     }
 }
 
-} // namespace heta
+template <int V> __global__ void __launch_bounds__(256) sparse_adam_kernel(AdamParams p) { sparse_adam_body<V>(p); }
 
-using namespace heta;
+// several tables in one launch (the weight matrices of a model and its learnable tables after one backward pass):
+// blockIdx.y picks the table
+constexpr int kAdamMulti = 16;
+struct AdamMulti {
+    AdamParams p[kAdamMulti];
+};
+static_assert(sizeof(AdamMulti) <= 3584, "kernel arguments are limited to 4 KB");
+template <int V> __global__ void __launch_bounds__(256) sparse_adam_multi_kernel(AdamMulti m) { sparse_adam_body<V>(m.p[blockIdx.y]); }
 
-extern "C" heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_table, int32_t d, int64_t n_table_rows,
-                                        float *m, float *v, int64_t ld_state, const int64_t *ids, int64_t n,
-                                        const float *grad, int64_t ld_grad, float lr, float beta1, float beta2, float eps,
-                                        int64_t step, void *hip_stream)
+// checks one update's arguments and fills its parameter block; *vec: 128-bit accesses are possible
+static heta_status adam_params(const char *who, void *table, heta_dtype dt, int64_t ld_table, int32_t d, int64_t n_table_rows, float *m,
+                               float *v, int64_t ld_state, const int64_t *ids, int64_t n, const float *grad, int64_t ld_grad, float lr,
+                               float beta1, float beta2, float eps, int64_t step, AdamParams *out, bool *vec, double *bytes)
 {
-    const char *who = "heta_sparse_adam";
     if (!table || !m || !v || (n > 0 && !grad)) return fail(HETA_ERR_INVALID_ARG, "%s: null argument", who);
     if (!valid_dtype(dt)) return fail(HETA_ERR_INVALID_ARG, "%s: bad dtype", who);
     if (d <= 0 || ld_table < d || ld_state < d || ld_grad < d || n < 0 || n_table_rows < 0)
@@ -118,7 +127,6 @@ extern "C" heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_t
     if ((reinterpret_cast<uintptr_t>(table) % esz) || (reinterpret_cast<uintptr_t>(m) & 3u) || (reinterpret_cast<uintptr_t>(v) & 3u) ||
         (reinterpret_cast<uintptr_t>(grad) & 3u))
         return fail(HETA_ERR_INVALID_ARG, "%s: pointer not aligned to its element size", who);
-    if (n == 0) return HETA_OK;
     AdamParams p{};
     p.table = table;
     p.table_bf16 = dt == HETA_BF16;
@@ -138,11 +146,81 @@ extern "C" heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_t
     p.eps = eps;
     p.c1 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(step))));
     p.c2 = static_cast<float>(1.0 / (1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(step))));
-    const bool vec = d % 4 == 0 && ld_state % 4 == 0 && ld_grad % 4 == 0 && aligned16(m) && aligned16(v) && aligned16(grad) &&
-                     (ld_table * esz) % (4 * esz) == 0 && (reinterpret_cast<uintptr_t>(table) % (4 * esz)) == 0;
-    hipStream_t st = as_stream(hip_stream);
+    *out = p;
+    *vec = d % 4 == 0 && ld_state % 4 == 0 && ld_grad % 4 == 0 && aligned16(m) && aligned16(v) && (n == 0 || aligned16(grad)) &&
+           (ld_table * esz) % (4 * esz) == 0 && (reinterpret_cast<uintptr_t>(table) % (4 * esz)) == 0;
     // algorithmic traffic: gradient, both states twice, the parameter twice, one id per row
-    const double bytes = static_cast<double>(n) * (d * (4.0 + 16.0 + 2.0 * esz) + (ids ? 8.0 : 0.0));
+    *bytes = static_cast<double>(n) * (d * (4.0 + 16.0 + 2.0 * esz) + (ids ? 8.0 : 0.0));
+    return HETA_OK;
+}
+
+} // namespace heta
+
+using namespace heta;
+
+extern "C" heta_status heta_sparse_adam_multi(int32_t n_items, const heta_adam_item *items, float lr, float beta1, float beta2, float eps,
+                                              int64_t step, void *hip_stream)
+{
+    const char *who = "heta_sparse_adam_multi";
+    if (n_items < 0 || (n_items > 0 && !items)) return fail(HETA_ERR_INVALID_ARG, "%s: bad item list", who);
+    hipStream_t st = as_stream(hip_stream);
+    for (int32_t i0 = 0; i0 < n_items; i0 += kAdamMulti) {
+        // every item is checked before anything is launched for this group of up to kAdamMulti
+        AdamMulti m{};
+        bool vec[kAdamMulti];
+        int n_live = 0;
+        double bytes = 0;
+        for (int32_t i = i0; i < n_items && i < i0 + kAdamMulti; ++i) {
+            const heta_adam_item &it = items[i];
+            AdamParams p{};
+            bool vq = false;
+            double b = 0;
+            heta_status e = adam_params(who, it.table, it.dt, it.ld_table, it.d, it.n_table_rows, it.m, it.v, it.ld_state, it.ids, it.n,
+                                        it.grad, it.ld_grad, lr, beta1, beta2, eps, step, &p, &vq, &b);
+            if (e != HETA_OK) return e;
+            if (it.n == 0) continue;
+            m.p[n_live] = p;
+            vec[n_live++] = vq;
+            bytes += b;
+        }
+        if (n_live == 0) continue;
+        // one launch for the items that take 128-bit accesses, one for the rest (blockIdx.y = position in the launch)
+        for (int pass = 0; pass < 2; ++pass) {
+            AdamMulti q{};
+            int k = 0;
+            int64_t threads_max = 0;
+            for (int i = 0; i < n_live; ++i)
+                if (vec[i] == (pass == 0)) {
+                    q.p[k++] = m.p[i];
+                    threads_max = std::max<int64_t>(threads_max, m.p[i].n * (pass == 0 ? m.p[i].d / 4 : m.p[i].d));
+                }
+            if (k == 0) continue;
+            if ((threads_max + 255) / 256 > 0x7fffffff) return fail(HETA_ERR_UNSUPPORTED, "%s: too many elements for one launch", who);
+            ProfScope prof("sparse_adam_kernel", st, bytes, 0);
+            bytes = 0; // counted once
+            const dim3 grid((unsigned)((threads_max + 255) / 256), (unsigned)k);
+            if (pass == 0) hipLaunchKernelGGL(sparse_adam_multi_kernel<4>, grid, dim3(256), 0, st, q);
+            else hipLaunchKernelGGL(sparse_adam_multi_kernel<1>, grid, dim3(256), 0, st, q);
+            HETA_LAUNCH_CHECK("sparse_adam_multi_kernel");
+        }
+    }
+    return HETA_OK;
+}
+
+extern "C" heta_status heta_sparse_adam(void *table, heta_dtype dt, int64_t ld_table, int32_t d, int64_t n_table_rows,
+                                        float *m, float *v, int64_t ld_state, const int64_t *ids, int64_t n,
+                                        const float *grad, int64_t ld_grad, float lr, float beta1, float beta2, float eps,
+                                        int64_t step, void *hip_stream)
+{
+    const char *who = "heta_sparse_adam";
+    AdamParams p{};
+    bool vec = false;
+    double bytes = 0;
+    heta_status e = adam_params(who, table, dt, ld_table, d, n_table_rows, m, v, ld_state, ids, n, grad, ld_grad, lr, beta1, beta2, eps, step,
+                                &p, &vec, &bytes);
+    if (e != HETA_OK) return e;
+    if (n == 0) return HETA_OK;
+    hipStream_t st = as_stream(hip_stream);
     ProfScope prof("sparse_adam_kernel", st, bytes, 0);
     if (vec) {
         const int64_t threads = n * (d / 4);

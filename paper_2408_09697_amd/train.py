@@ -101,15 +101,13 @@ class MiniBatchTrainer:
                     if t not in G:
                         G[t] = torch.zeros_like(h)
         # parameter update: dense Adam on the weights, sparse Adam on the touched rows of learnable tables
-        for l, layer in enumerate(layers):
-            for r in layer.rels:
-                hb.heta_sparse_adam(self.W[l][r], self.mW[l][r], self.vW[l][r], layer.dW[r], ids=None, lr=self.lr,
-                                    beta1=self.beta1, beta2=self.beta2, eps=self.eps, step=self.t, stream=stream)
+        # (every update of the iteration in one call: up to 16 tables share a launch)
+        updates = [(self.W[l][r], self.mW[l][r], self.vW[l][r], layer.dW[r], None) for l, layer in enumerate(layers) for r in layer.rels]
         first = layers[0]
         for t in self.learnable:
             if t in first.dH0 and blocks[0].src_ids[t].numel() > 0:
-                hb.heta_sparse_adam(self.tables[t], self.mT[t], self.vT[t], first.dH0[t], ids=blocks[0].src_ids[t],
-                                    lr=self.lr, beta1=self.beta1, beta2=self.beta2, eps=self.eps, step=self.t, stream=stream)
+                updates.append((self.tables[t], self.mT[t], self.vT[t], first.dH0[t], blocks[0].src_ids[t]))
+        hb.heta_sparse_adam_multi(updates, lr=self.lr, beta1=self.beta1, beta2=self.beta2, eps=self.eps, step=self.t, stream=stream)
         if keep_blocks:
             self.last_blocks, self.last_layers = blocks, layers
         else:

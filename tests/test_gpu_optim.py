@@ -97,3 +97,45 @@ def test_sparse_adam_skips_row_ids_outside_the_table():
     assert bool((guard[:n] == 7.0).all()) and bool((guard[2 * n:] == 7.0).all())
     with pytest.raises(heta.HetaError):
         heta.heta_check_ids(torch.from_numpy(ids).cuda(), n)
+
+
+def test_sparse_adam_multi_equals_the_single_calls_bit_for_bit():
+    """Twenty updates in one call (two launches' worth: fp32 and bf16 tables, with and without ids, widths that take the
+    128-bit path and widths that do not, an empty one) against the same updates one by one, over three steps."""
+    g = rng.stream("tests", "adam-multi")
+    shapes = [(256, 128, None), (300, 768, 120), (128, 7, 50), (64, 300, None), (1000, 64, 0), (512, 256, 512)] * 3 + \
+             [(1024, 1024, None), (77, 33, 20)]
+    assert len(shapes) > 16
+
+    def fresh():
+        out = []
+        for k, (n_rows, d, n_ids) in enumerate(shapes):
+            storage = "bf16" if k % 2 else "f32"
+            theta = rng.uniform_table(n_rows, d, -0.1, 0.1, "tests", f"adam-multi-theta{k}")
+            table = dev_table(rng.round_to_bf16(theta) if storage == "bf16" else theta, storage, 8 if d % 8 == 0 else 1)
+            pad = 4 if d % 4 == 0 else 1
+            m = torch.zeros((n_rows, (d + pad - 1) // pad * pad), dtype=torch.float32, device="cuda")[:, :d]
+            out.append((table, m, torch.zeros_like(m)))
+        return out
+
+    one, multi = fresh(), fresh()
+    for step in range(1, 4):
+        updates_one, updates_multi = [], []
+        for k, (n_rows, d, n_ids) in enumerate(shapes):
+            n = n_rows if n_ids is None else n_ids
+            ids = None if n_ids is None else torch.from_numpy(g.permutation(n_rows)[:n_ids].astype(np.int64)).cuda()
+            grad = dev_table(rng.normal_table(n, d, "tests", f"adam-multi-g{k}-{step}"), "f32", 4 if d % 4 == 0 else 1)
+            updates_one.append((*one[k], grad, ids))
+            updates_multi.append((*multi[k], grad, ids))
+        for table, m, v, grad, ids in updates_one:
+            heta.heta_sparse_adam(table, m, v, grad, ids=ids, lr=0.01, step=step)
+        heta.heta_sparse_adam_multi(updates_multi, lr=0.01, step=step)
+    torch.cuda.synchronize()
+    for k in range(len(shapes)):
+        for a, b, what in zip(one[k], multi[k], ("table", "m", "v")):
+            assert torch.equal(a, b), f"item {k} {shapes[k]}: {what} differs"
+    with pytest.raises(heta.HetaError):   # a bad item anywhere: nothing is launched, the call fails
+        bad = list(updates_multi)
+        t, m, v, grad, ids = bad[3]
+        bad[3] = (t, m[: t.shape[0] // 2], v, grad, ids)
+        heta.heta_sparse_adam_multi(bad, lr=0.01, step=1)
