@@ -818,16 +818,29 @@ def test_supplied_csc_and_reverse_declarations_are_validated(mode):
         heta.heta_ingest_force(0)
 
 
-def test_block_ingest_of_many_relations_matches_the_host_path_bit_for_bit():
-    """A block of 12 relations over 5 node types (empty relations, relations without rows, multi-edges, a hub
-    column of more than 512 edges, a hub row): every index array the whole-block device ingest produces is
+BLOCK_SHAPES = {
+    # 12 relations over 5 node types: empty relations, relations without rows, multi-edges, a hub column of more
+    # than 512 edges, a hub row
+    "mixed": ([3000, 1, 0, 700, 5000],
+              [(0, 3, 9000), (3, 0, 20000), (0, 0, 0), (1, 0, 2500), (0, 1, 1200), (2, 0, 0), (0, 2, 0), (4, 4, 30000), (4, 0, 7),
+               (3, 4, 4000), (0, 4, 15000), (3, 3, 1)]),
+    # 14 relations of 40 ... 180 rows: 1,024 consecutive rows of the block span up to ten schedules (the row kernel
+    # keeps four per workgroup in LDS and sends the rest straight to the global counters); one hub row and column
+    "narrow": ([90, 40, 180, 120, 60, 150],
+               [(0, 1, 700), (1, 2, 9000), (2, 3, 1500), (3, 4, 400), (4, 5, 2500), (5, 0, 900), (0, 2, 1300), (2, 0, 60), (1, 1, 300),
+                (3, 3, 800), (4, 0, 0), (5, 5, 2000), (0, 4, 450), (2, 5, 1100)]),
+}
+
+
+@pytest.mark.parametrize("shape", sorted(BLOCK_SHAPES))
+def test_block_ingest_of_many_relations_matches_the_host_path_bit_for_bit(shape):
+    """Blocks of 12 to 14 relations: every index array the whole-block device ingest produces is
     the host path's, read back through the public calls and through exact integer aggregations."""
-    g = rng.stream("tests", "block-ingest")
-    n_nodes = [3000, 1, 0, 700, 5000]
+    g = rng.stream("tests", "block-ingest" if shape == "mixed" else f"block-ingest/{shape}")
+    n_nodes, specs = BLOCK_SHAPES[shape]
     nts = [(n, 8, 0) for n in n_nodes]
     rels, lists = [], []
-    for k, (s, t, n_e) in enumerate([(0, 3, 9000), (3, 0, 20000), (0, 0, 0), (1, 0, 2500), (0, 1, 1200), (2, 0, 0), (0, 2, 0),
-                                     (4, 4, 30000), (4, 0, 7), (3, 4, 4000), (0, 4, 15000), (3, 3, 1)]):
+    for k, (s, t, n_e) in enumerate(specs):
         n_s, n_t = n_nodes[s], n_nodes[t]
         dst = np.sort(g.integers(0, max(n_t, 1), size=n_e)).astype(np.int64)
         src = g.integers(0, max(n_s, 1), size=n_e, dtype=np.int32)
