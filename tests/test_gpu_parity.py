@@ -67,6 +67,30 @@ def test_ingest_csc_and_degrees_bit_exact(skew):
     assert np.array_equal(heta.heta_graph_get_degrees(hg, 0), oracle.in_degree(src, dst, 2000))
 
 
+@pytest.mark.parametrize("n_src,mode", [(100_000, 2), (100_000, 3), (200_000, 3), (40_000_000, 2)])
+def test_ingest_transpose_at_key_widths_that_take_nine_bit_passes(n_src, mode):
+    """Source counts of 17, 18 and 26 bits: the radix sort behind the transpose takes 9 bits per pass there (two
+    passes instead of three, three instead of four).  CSC and degrees against the definition, bit for bit."""
+    g = rng.stream("tests", f"ingest-bits/{n_src}")
+    n_dst, n_e = 5000, 60_000
+    dst = np.sort(g.integers(0, n_dst, size=n_e)).astype(np.int64)
+    src = g.integers(0, n_src, size=n_e, dtype=np.int64).astype(np.int32)
+    src[:2000] = n_src - 1                                   # a column of many edges at the top of the key range
+    rowptr = np.zeros(n_dst + 1, dtype=np.int64)
+    np.add.at(rowptr, dst + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    heta.heta_ingest_force(mode)
+    try:
+        hg = heta.heta_graph_create([(n_src, 8, 0), (n_dst, 8, 0)], [(0, 1, rowptr, src)])
+    finally:
+        heta.heta_ingest_force(0)
+    colptr, row = heta.heta_graph_get_csc(hg, 0)
+    ref_colptr, ref_row = oracle.csc(src, dst.astype(np.int32), n_src)
+    assert np.array_equal(colptr, ref_colptr) and np.array_equal(row, ref_row)
+    assert np.array_equal(heta.heta_graph_get_degrees(hg, 0), np.diff(rowptr))
+    hg.destroy()
+
+
 @pytest.mark.parametrize("mode", [1, 2, 3])
 def test_ingest_config1_and_device_pointers(mode):
     p = workloads.config1()
