@@ -99,7 +99,7 @@ class RafLayer:
         # rows of every intermediate start on 16-byte boundaries (padded leading dimension), which
         # keeps awkward widths (7, 300, 789, ...) on the library's 128-bit paths
         def padded(n, d, dtype):
-            q = 16 // torch.empty((), dtype=dtype).element_size()
+            q = 16 // dtype.itemsize
             return torch.empty((n, (d + q - 1) // q * q), dtype=dtype, device=dev)[:, :d]
 
         # Aggregation and projection commute (Eq. 1 is linear in H0).  A relation can be projected

@@ -64,7 +64,7 @@ class RgatLayer:
         self.two_terms = store == torch.bfloat16
 
         def padded(n, d, dtype):
-            qd = 16 // torch.empty((), dtype=dtype).element_size()
+            qd = 16 // dtype.itemsize
             return torch.empty((n, (d + qd - 1) // qd * qd), dtype=dtype, device=dev)[:, :d]
 
         f32 = torch.float32
