@@ -577,7 +577,9 @@ template <bool W3, bool B_DIRECT, typename DB, typename SB_T, typename Staged, t
 // tile is (32 MI WMW) x (32 NJ WN).  The default 2 x 2 blocks per wavefront with 2 x WN wavefronts is the
 // 128 x (64 WN) tile; tall tiles (MI = 5, NJ = 1: 320 x 128) let a weight gradient whose input is wider than
 // 128 columns read its large gradient operand once, wide ones (MI = 1, NJ = 5: 128 x 320) do the same for a
-// product with more than 256 output columns and its input rows.
+// product with more than 256 output columns and its input rows.  Where the k loop is long, both grow along their
+// second side too (MI x NJ = 5 x 2 or 4 x 2: 320 x 256 / 256 x 256; 2 x 5: 256 x 320), one workgroup per CU: fewer
+// operand bytes loaded per MFMA.
 template <typename CT, typename SA_T, bool A_RC, bool A_DIRECT, typename SB_T, bool B_RC, bool B_DIRECT, int WN, int BK,
           int ST, int OCC, bool B_SPLIT = false, int MI = 2, int NJ = 2, int WMW = 2, int X3 = 0>
 __global__ void __launch_bounds__(64 * WMW * WN, OCC) gemm_direct_kernel(GemmParams p)
